@@ -1,0 +1,222 @@
+"""numpy front end of the CPU oracle (``dfq_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py``.  The GPU package never imports it and it never
+imports the GPU package.  All arithmetic lives in the C file; this module only
+marshals numpy arrays (NHWC activations, [K][R][S][C/groups] weights).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dfq_oracle.c")
+_LIB = os.path.join(_HERE, "libdfq_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc -O2 and OpenMP (across output elements only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c99",
+                               "-Wall", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+_i8p = C.POINTER(C.c_int8)
+_i32p = C.POINTER(C.c_int32)
+_f32p = C.POINTER(C.c_float)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        L.orc_beta_max.restype = C.c_int64
+        L.orc_beta_max.argtypes = [C.c_int, C.c_int]
+        L.orc_mac_acc_bits.restype = C.c_int
+        L.orc_mac_acc_bits.argtypes = [C.c_int64] * 5
+        L.orc_mac_max_len.restype = C.c_int64
+        L.orc_mac_max_len.argtypes = [C.c_int] + [C.c_int64] * 4
+        L.orc_add_acc_bits.restype = C.c_int
+        L.orc_add_acc_bits.argtypes = [C.c_int64] * 3
+        L.orc_add_max_len.restype = C.c_int64
+        L.orc_add_max_len.argtypes = [C.c_int, C.c_int64, C.c_int64]
+        L.orc_rne_shift.restype = C.c_int64
+        L.orc_rne_shift.argtypes = [C.c_int64, C.c_int]
+        L.orc_requant8.restype = C.c_int
+        L.orc_requant8.argtypes = [C.c_int64, C.c_int]
+        L.orc_quantize.restype = None
+        L.orc_quantize.argtypes = [_f32p, _i8p, C.c_size_t, C.c_int]
+        L.orc_quantize_i32.restype = None
+        L.orc_quantize_i32.argtypes = [_f32p, _i32p, C.c_size_t, C.c_int]
+        L.orc_dequantize.restype = None
+        L.orc_dequantize.argtypes = [_i8p, _f32p, C.c_size_t, C.c_int]
+        L.orc_conv_acc_at.restype = C.c_int64
+        L.orc_conv_acc_at.argtypes = [_i8p, _i8p, _i32p] + [C.c_int] * 14
+        L.orc_conv_q.restype = C.c_int
+        L.orc_conv_q.argtypes = [_i8p, _i8p, _i32p, _i8p, _i32p] + [C.c_int] * 15
+        L.orc_eltwise_q.restype = C.c_int
+        L.orc_eltwise_q.argtypes = [_i8p, C.c_int, _i8p, C.c_int, _i8p, C.c_int, _i32p, C.c_size_t, C.c_int]
+        L.orc_concat_q.restype = C.c_int
+        L.orc_concat_q.argtypes = [C.c_int, C.POINTER(_i8p), C.POINTER(C.c_int), C.POINTER(C.c_int),
+                                   _i8p, C.c_int, C.c_size_t]
+        L.orc_pool_q.restype = C.c_int
+        L.orc_pool_q.argtypes = [_i8p, _i8p] + [C.c_int] * 10
+        L.orc_absmax_f32.restype = C.c_float
+        L.orc_absmax_f32.argtypes = [_f32p, C.c_size_t]
+        L.orc_absmax_i32.restype = C.c_int64
+        L.orc_absmax_i32.argtypes = [_i32p, C.c_size_t, C.c_int]
+        L.orc_frac_from_absmax_f32.restype = C.c_int
+        L.orc_frac_from_absmax_f32.argtypes = [C.c_float]
+        L.orc_frac_from_absmax_i32.restype = C.c_int
+        L.orc_frac_from_absmax_i32.argtypes = [C.c_int64, C.c_int]
+        _lib = L
+    return _lib
+
+
+def _c(a: np.ndarray, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _p(a, ptype):
+    return None if a is None else a.ctypes.data_as(ptype)
+
+
+# ---- closed forms ---------------------------------------------------------- #
+def beta_max(n, p): return int(lib().orc_beta_max(n, p))
+def mac_acc_bits(N, bx, ex=0, by=None, ey=0): return int(lib().orc_mac_acc_bits(N, bx, ex, bx if by is None else by, ey))
+def mac_max_len(q, bx, ex=0, by=None, ey=0): return int(lib().orc_mac_max_len(q, bx, ex, bx if by is None else by, ey))
+def add_acc_bits(N, bx, ex=0): return int(lib().orc_add_acc_bits(N, bx, ex))
+def add_max_len(q, bx, ex=0): return int(lib().orc_add_max_len(q, bx, ex))
+def rne_shift(v, s): return int(lib().orc_rne_shift(int(v), int(s)))
+def requant8(v, s): return int(lib().orc_requant8(int(v), int(s)))
+
+
+# ---- conversions ------------------------------------------------------------ #
+def quantize(x: np.ndarray, f: int) -> np.ndarray:
+    x = _c(x, np.float32)
+    q = np.empty(x.shape, np.int8)
+    lib().orc_quantize(_p(x, _f32p), _p(q, _i8p), x.size, int(f))
+    return q
+
+
+def quantize_i32(x: np.ndarray, f: int) -> np.ndarray:
+    x = _c(x, np.float32)
+    q = np.empty(x.shape, np.int32)
+    lib().orc_quantize_i32(_p(x, _f32p), _p(q, _i32p), x.size, int(f))
+    return q
+
+
+def dequantize(q: np.ndarray, f: int) -> np.ndarray:
+    q = _c(q, np.int8)
+    x = np.empty(q.shape, np.float32)
+    lib().orc_dequantize(_p(q, _i8p), _p(x, _f32p), q.size, int(f))
+    return x
+
+
+# ---- layers ------------------------------------------------------------------ #
+def conv_out_hw(H, W, R, S, stride, pad):
+    return (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+
+
+def conv_q(x, w, b, f_in, f_w, f_out, stride=1, pad=0, groups=1, relu=False,
+           want_y=True, want_acc=False):
+    """Returns (y, acc): y int8 [N,P,Q,K] at f_out (or None), acc int32 [N,P,Q,K]
+    including bias, before ReLU (or None).  Raises if an accumulator overflowed int32."""
+    x = _c(x, np.int8); w = _c(w, np.int8)
+    b = None if b is None else _c(b, np.int32)
+    N, H, W, Cc = x.shape
+    K, R, S, Cg = w.shape
+    assert Cg * groups == Cc, "weight shape does not match C/groups"
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    y = np.empty((N, P, Q, K), np.int8) if want_y else None
+    acc = np.empty((N, P, Q, K), np.int32) if want_acc else None
+    rc = lib().orc_conv_q(_p(x, _i8p), _p(w, _i8p), _p(b, _i32p), _p(y, _i8p), _p(acc, _i32p),
+                          N, H, W, Cc, K, R, S, stride, pad, groups, K,
+                          int(f_in), int(f_w), int(f_out), int(bool(relu)))
+    if rc < 0:
+        raise ValueError("oracle conv_q: bad shape")
+    if rc > 0:
+        raise OverflowError("oracle conv_q: accumulator exceeds int32 (Eq. 8/9 precondition)")
+    return y, acc
+
+
+def conv_acc_at(x, w, b, stride, pad, groups, n, p, q, k) -> int:
+    x = _c(x, np.int8); w = _c(w, np.int8)
+    b = None if b is None else _c(b, np.int32)
+    N, H, W, Cc = x.shape
+    K, R, S, Cg = w.shape
+    return int(lib().orc_conv_acc_at(_p(x, _i8p), _p(w, _i8p), _p(b, _i32p), N, H, W, Cc, K, R, S,
+                                     stride, pad, groups, n, p, q, k))
+
+
+def eltwise_q(a, f_a, b, f_b, f_y, relu=False, want_y=True, want_acc=False):
+    a = _c(a, np.int8); b = _c(b, np.int8)
+    assert a.shape == b.shape
+    y = np.empty(a.shape, np.int8) if want_y else None
+    acc = np.empty(a.shape, np.int32) if want_acc else None
+    rc = lib().orc_eltwise_q(_p(a, _i8p), int(f_a), _p(b, _i8p), int(f_b), _p(y, _i8p), int(f_y),
+                             _p(acc, _i32p), a.size, int(bool(relu)))
+    if rc:
+        raise ValueError("oracle eltwise_q: formats too far apart")
+    return y, acc
+
+
+def concat_q(xs, fs, f_y):
+    xs = [_c(x, np.int8) for x in xs]
+    lead = xs[0].shape[:-1]
+    assert all(x.shape[:-1] == lead for x in xs)
+    Cs = [x.shape[-1] for x in xs]
+    pixels = int(np.prod(lead))
+    y = np.empty(lead + (sum(Cs),), np.int8)
+    ptrs = (_i8p * len(xs))(*[_p(x, _i8p) for x in xs])
+    rc = lib().orc_concat_q(len(xs), ptrs, (C.c_int * len(xs))(*Cs), (C.c_int * len(xs))(*[int(f) for f in fs]),
+                            _p(y, _i8p), int(f_y), pixels)
+    if rc:
+        raise ValueError("oracle concat_q: bad arguments")
+    return y
+
+
+def pool_q(x, mode, k, stride, pad, f_in, f_out):
+    """mode: 'max' or 'avg'."""
+    x = _c(x, np.int8)
+    N, H, W, Cc = x.shape
+    P, Q = conv_out_hw(H, W, k, k, stride, pad)
+    y = np.empty((N, P, Q, Cc), np.int8)
+    rc = lib().orc_pool_q(_p(x, _i8p), _p(y, _i8p), {"max": 0, "avg": 1}[mode], N, H, W, Cc,
+                          k, stride, pad, int(f_in), int(f_out))
+    if rc:
+        raise ValueError("oracle pool_q: bad arguments")
+    return y
+
+
+# ---- calibration building blocks ---------------------------------------------- #
+def absmax_f32(x) -> float:
+    x = _c(x, np.float32)
+    return float(lib().orc_absmax_f32(_p(x, _f32p), x.size))
+
+
+def absmax_i32(x, relu=False) -> int:
+    x = _c(x, np.int32)
+    return int(lib().orc_absmax_i32(_p(x, _i32p), x.size, int(bool(relu))))
+
+
+def frac_from_absmax_f32(gamma: float) -> int:
+    f = int(lib().orc_frac_from_absmax_f32(float(gamma)))
+    if f == -1000:
+        raise ValueError("threshold must be finite and non-negative")
+    return f
+
+
+def frac_from_absmax_i32(m: int, acc_frac: int) -> int:
+    f = int(lib().orc_frac_from_absmax_i32(int(m), int(acc_frac)))
+    if f == -1000:
+        raise ValueError("threshold must be non-negative")
+    return f

@@ -1,0 +1,117 @@
+"""Network-level oracle: single-batch calibration and inference over a layer graph.
+
+TEST INFRASTRUCTURE ONLY (see ``oracle/__init__.py``).  Follows the quantization
+procedure of Sec. 3 in the paper's order, one layer at a time:
+
+* weights: threshold = max |w| over the layer (the paper uses the maximum per
+  output channel; this build fixes one format per layer), smallest power-of-two
+  scale that holds it;
+* bias: an integer at the product scale of input and weights;
+* activations: "bootstrap" order - each layer's threshold is measured on the
+  output it produces from its already-quantized upstream tensors;
+* "lazy" thresholds - measured on the wide accumulator after the ReLU, only then
+  is the accumulator rescaled (by a factor in (0, 1]) into the int8 output format;
+* joins: element-wise add aligns both inputs exactly and rescales the sum once
+  (Eq. 10); concat rescales every branch into the coarsest branch format;
+  max / average pooling keep their input format.
+
+End-to-end results have no pin outside this file ("parity unpinned"); each
+ingredient it calls is pinned separately.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, Optional
+
+import numpy as np
+
+import oracle as orc
+
+
+@dataclass
+class Quantized:
+    """What calibration fixes for a network: per-tensor fractional lengths and the
+    integer weights / biases of every conv node."""
+    frac: Dict[str, int] = field(default_factory=dict)          # tensor name -> f
+    w_frac: Dict[str, int] = field(default_factory=dict)        # conv node name -> f_w
+    w: Dict[str, np.ndarray] = field(default_factory=dict)      # int8 [K,R,S,Cg]
+    b: Dict[str, np.ndarray] = field(default_factory=dict)      # int32 [K] at f_in + f_w
+
+
+def _input_codes(net, x, qz: Quantized, calibrating: bool):
+    if net.input_is_int8:
+        if calibrating:
+            qz.frac[net.input_name] = net.f_input_codes
+        return np.ascontiguousarray(x, np.int8)
+    if calibrating:
+        if net.fixed_f_input is not None:
+            qz.frac[net.input_name] = net.fixed_f_input
+        else:
+            qz.frac[net.input_name] = orc.frac_from_absmax_f32(orc.absmax_f32(x))
+    return orc.quantize(x, qz.frac[net.input_name])
+
+
+def _forward(net, x, qz: Quantized, calibrating: bool):
+    t = {net.input_name: _input_codes(net, x, qz, calibrating)}
+    for nd in net.nodes:
+        if nd.op == "conv":
+            src = nd.srcs[0]
+            f_in = qz.frac[src]
+            if calibrating:
+                wf, bf = net.weights(nd)
+                f_w = orc.frac_from_absmax_f32(orc.absmax_f32(wf))
+                qz.w_frac[nd.name] = f_w
+                qz.w[nd.name] = orc.quantize(wf, f_w)
+                qz.b[nd.name] = orc.quantize_i32(bf, f_in + f_w)
+            f_w = qz.w_frac[nd.name]
+            w, b = qz.w[nd.name], qz.b[nd.name]
+            if calibrating:
+                if nd.fixed_f_out is not None:
+                    qz.frac[nd.dst] = nd.fixed_f_out
+                else:
+                    _, acc = orc.conv_q(t[src], w, b, f_in, f_w, 0, nd.stride, nd.pad, nd.groups,
+                                        nd.relu, want_y=False, want_acc=True)
+                    m = orc.absmax_i32(acc, relu=nd.relu)
+                    del acc
+                    qz.frac[nd.dst] = orc.frac_from_absmax_i32(m, f_in + f_w)
+            y, _ = orc.conv_q(t[src], w, b, f_in, f_w, qz.frac[nd.dst], nd.stride, nd.pad, nd.groups, nd.relu)
+            t[nd.dst] = y
+        elif nd.op == "eltwise":
+            a, b = nd.srcs
+            fa, fb = qz.frac[a], qz.frac[b]
+            if calibrating:
+                _, acc = orc.eltwise_q(t[a], fa, t[b], fb, 0, nd.relu, want_y=False, want_acc=True)
+                m = orc.absmax_i32(acc, relu=nd.relu)
+                qz.frac[nd.dst] = orc.frac_from_absmax_i32(m, max(fa, fb))
+            t[nd.dst], _ = orc.eltwise_q(t[a], fa, t[b], fb, qz.frac[nd.dst], nd.relu)
+        elif nd.op == "concat":
+            fs = [qz.frac[s] for s in nd.srcs]
+            if calibrating:
+                qz.frac[nd.dst] = nd.fixed_f_out if nd.fixed_f_out is not None else min(fs)
+            t[nd.dst] = orc.concat_q([t[s] for s in nd.srcs], fs, qz.frac[nd.dst])
+        elif nd.op in ("maxpool", "avgpool"):
+            src = nd.srcs[0]
+            if calibrating:
+                qz.frac[nd.dst] = qz.frac[src]
+            t[nd.dst] = orc.pool_q(t[src], "max" if nd.op == "maxpool" else "avg", nd.R, nd.stride, nd.pad,
+                                   qz.frac[src], qz.frac[nd.dst])
+        else:
+            raise ValueError(nd.op)
+    return t
+
+
+def calibrate(net, x_calib):
+    """Chooses every format from ONE batch.  Returns (Quantized, tensors of that batch)."""
+    qz = Quantized()
+    t = _forward(net, x_calib, qz, calibrating=True)
+    return qz, t
+
+
+def infer(net, qz: Quantized, x):
+    """Runs the calibrated network; returns the dict of int8 tensors."""
+    return _forward(net, x, qz, calibrating=False)
+
+
+def logits(net, qz: Quantized, tensors) -> np.ndarray:
+    out = tensors[net.output_name]
+    return orc.dequantize(out, qz.frac[net.output_name]).reshape(out.shape[0], -1)

@@ -1,0 +1,82 @@
+"""Sanity of the network-level oracle (single-batch calibration, Sec. 3).
+
+End-to-end logits have no external pin ("parity unpinned"); what the max-abs
+rule implies can be checked: on the calibration batch nothing saturates, no
+bit of range is wasted unless the rescale factor is capped at 1, and the
+formats found are what an exact-rational evaluation of the thresholds gives.
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle as orc
+import oracle.net as onet
+import workloads as wl
+
+
+def _small_nets():
+    return [wl.resnet50(batch=2, hw=32, classes=10), wl.mobilenet_v1(batch=2, hw=32, classes=10),
+            wl.inception_block(batch=2, hw=8)]
+
+
+@pytest.mark.parametrize("net", _small_nets(), ids=lambda n: n.name)
+def test_calibration_uses_the_range_without_clipping(net):
+    x = net.input_int8() if net.input_is_int8 else net.input_float()
+    qz, t = onet.calibrate(net, x)
+    for nd in net.nodes:
+        y = t[nd.dst].astype(np.int32)
+        assert y.min() >= -127
+        if nd.fixed_f_out is not None or nd.op in ("maxpool", "avgpool", "concat"):
+            continue
+        acc_frac = (qz.frac[nd.srcs[0]] + qz.w_frac[nd.name]) if nd.op == "conv" else max(qz.frac[s] for s in nd.srcs)
+        f = qz.frac[nd.dst]
+        assert f <= acc_frac
+        # independent check of the threshold -> format rule from the real-valued threshold
+        if nd.op == "conv":
+            _, acc = orc.conv_q(t[nd.srcs[0]], qz.w[nd.name], qz.b[nd.name], 0, 0, 0, nd.stride, nd.pad,
+                                nd.groups, want_y=False, want_acc=True)
+        else:
+            a, b = nd.srcs
+            F = max(qz.frac[a], qz.frac[b])
+            acc = (t[a].astype(np.int64) << (F - qz.frac[a])) + (t[b].astype(np.int64) << (F - qz.frac[b]))
+        acc = acc.astype(np.int64)
+        if nd.relu:
+            acc = np.maximum(acc, 0)
+        gamma = Fraction(int(np.abs(acc).max())) / Fraction(2) ** acc_frac
+        assert gamma * Fraction(2) ** f <= 127
+        if f < acc_frac:
+            assert gamma * Fraction(2) ** (f + 1) > 127
+            assert np.abs(y).max() >= 64
+    # inference on the calibration batch reproduces the calibration tensors
+    t2 = onet.infer(net, qz, x)
+    for k in t:
+        assert np.array_equal(t[k], t2[k])
+    lg = onet.logits(net, qz, t)
+    assert lg.shape[0] == 2 and np.isfinite(lg).all()
+
+
+def test_images_are_independent():
+    net = wl.resnet50(batch=3, hw=32, classes=10)
+    x = net.input_float()
+    qz, _ = onet.calibrate(net, x[:2])
+    full = onet.infer(net, qz, x)
+    one = onet.infer(net, qz, x[2:3])
+    assert np.array_equal(full[net.output_name][2:3], one[net.output_name])
+
+
+def test_workload_shapes():
+    r = wl.resnet50()
+    assert sum(1 for n in r.nodes if n.op == "conv") == 54            # 53 convolutions + the FC layer
+    assert sum(1 for n in r.nodes if n.op == "eltwise") == 16
+    assert abs(r.macs_per_image() / 1e9 - 4.09) < 0.02
+    m = wl.mobilenet_v1()
+    assert sum(1 for n in m.nodes if n.op == "conv") == 28
+    assert abs(m.macs_per_image() / 1e9 - 0.569) < 0.005
+    i = wl.inception_block()
+    assert i.shapes[i.output_name] == (28, 28, 256)
+    assert abs(i.macs_per_image() * 64 / 1e9 - 8.86) < 0.05
+    c0 = wl.config0()
+    assert c0["x"].shape == (1, 32, 32, 16) and c0["w"].shape == (16, 3, 3, 16)
+    l = wl.config1_layer(4, batch=1)
+    assert l["x"].shape == (1, 7, 7, 512) and l["w_float"].shape == (2048, 1, 1, 512)

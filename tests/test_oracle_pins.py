@@ -1,0 +1,481 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Nothing here re-types the oracle's formulas: expected values are hand-worked
+closed-form numbers (tests/golden/closed_forms.txt), exact rational arithmetic
+with ``fractions.Fraction`` / Python big integers, brute-force enumeration, or
+library routines (numpy int64 matmul, scipy correlate2d) for special cases.
+"""
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+from scipy.signal import correlate2d
+
+import oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "closed_forms.txt")
+
+
+def _golden():
+    rows = []
+    for line in open(GOLDEN):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            parts = line.split()
+            rows.append((parts[0], [int(v) for v in parts[1:]]))
+    return rows
+
+
+# --------------------------------------------------------------------------- #
+# Sec. 2.1 / 2.2 closed forms                                                   #
+# --------------------------------------------------------------------------- #
+
+@pytest.mark.parametrize("kind,vals", _golden())
+def test_closed_forms_golden(kind, vals):
+    *args, want = vals
+    fn = {"beta_max": orc.beta_max, "mac_bits": orc.mac_acc_bits, "mac_len": orc.mac_max_len,
+          "add_bits": orc.add_acc_bits, "add_len": orc.add_max_len}[kind]
+    assert fn(*args) == want
+
+
+def _decode_sign_magnitude(bits, n, p):
+    """Eq. 2 with Eq. 4, by enumeration of the bit pattern."""
+    b = [(bits >> i) & 1 for i in range(n)]
+    e_hat = 0 if p == n - 1 else sum(b[i] << (i - p) for i in range(p, n - 1))
+    m = sum(b[i] << i for i in range(p))
+    sign = -1 if b[n - 1] else 1
+    if e_hat == 0:
+        return sign * m
+    return sign * (2 ** (e_hat - 1)) * (2 ** p + m)
+
+
+@pytest.mark.parametrize("n,p", [(8, 7), (8, 6), (8, 5), (8, 4), (8, 3), (7, 3), (6, 3), (6, 2), (5, 1), (4, 0)])
+def test_beta_max_is_largest_decoded_code(n, p):
+    codes = [_decode_sign_magnitude(v, n, p) for v in range(2 ** n)]
+    assert max(codes) == orc.beta_max(n, p)
+    assert min(codes) == -orc.beta_max(n, p)          # sign-magnitude range is symmetric
+
+
+def test_int8_member_of_family_has_every_integer_code():
+    # p = n-1 = 7 and p = 6 both give exactly the integers -127..127
+    for p in (7, 6):
+        assert sorted(set(_decode_sign_magnitude(v, 8, p) for v in range(256))) == list(range(-127, 128))
+
+
+def _smallest_q(lo, hi):
+    q = 1
+    while not (-(2 ** (q - 1)) <= lo and hi <= 2 ** (q - 1) - 1):
+        q += 1
+    return q
+
+
+def test_mac_width_is_smallest_accumulator_that_holds_eq7_range():
+    for N, bx, ex, by, ey in itertools.product([1, 2, 3, 7, 64, 576, 4608], [1, 7, 127], [0, 1, 3], [1, 15, 127], [0, 1]):
+        ax, ay = -bx - ex, -by - ey
+        lo = N * min(ay * bx, ax * by)
+        hi = N * ax * ay
+        assert orc.mac_acc_bits(N, bx, ex, by, ey) == _smallest_q(lo, hi), (N, bx, ex, by, ey)
+
+
+def test_mac_len_is_largest_n_for_width():
+    for q, bx, ex, by, ey in itertools.product([9, 16, 24, 32], [7, 127], [0, 1], [15, 127], [0, 1]):
+        N = orc.mac_max_len(q, bx, ex, by, ey)
+        hi = lambda n: n * (bx + ex) * (by + ey)
+        assert hi(N) <= 2 ** (q - 1) - 1 < hi(N + 1)
+
+
+def test_add_width_and_length():
+    for N, bx, ex in itertools.product([1, 2, 3, 49, 1000], [1, 7, 127], [0, 1, 2]):
+        assert orc.add_acc_bits(N, bx, ex) == _smallest_q(N * (-bx - ex), N * bx), (N, bx, ex)
+    for q, bx, ex in itertools.product([8, 9, 14, 16, 32], [7, 127], [0, 1, 2]):
+        N = orc.add_max_len(q, bx, ex)
+        fits = lambda n: -(2 ** (q - 1)) <= n * (-bx - ex) and n * bx <= 2 ** (q - 1) - 1
+        assert fits(N) and not fits(N + 1)
+
+
+def test_int32_accumulator_suffices_for_every_layer_of_the_configs():
+    # deepest reduction in the five configs is 3x3x512 = 4608 products of codes that may reach -128
+    assert orc.mac_acc_bits(4608, 127, 1, 127, 1) <= 32
+    assert orc.mac_max_len(32, 127, 1, 127, 1) >= 4608
+
+
+# --------------------------------------------------------------------------- #
+# rounding                                                                      #
+# --------------------------------------------------------------------------- #
+
+def _round_even(fr: Fraction) -> int:
+    return round(fr)  # Python rounds a Fraction to the nearest integer, ties to even
+
+
+def _sat(v):
+    return max(-127, min(127, v))
+
+
+def test_rne_shift_matches_exact_rational_rounding():
+    rng = np.random.default_rng(1)
+    vals = list(range(-70, 71)) + [int(v) for v in rng.integers(-2 ** 31, 2 ** 31, 4000)]
+    for v in vals:
+        for s in (0, 1, 2, 3, 5, 7, 8, 13, 20, 31, 32, 40):
+            assert orc.rne_shift(v, s) == _round_even(Fraction(v, 2 ** s)), (v, s)
+        for s in (-1, -3, -8):
+            assert orc.rne_shift(v, s) == v * 2 ** (-s)
+
+
+def test_rne_ties_by_hand():
+    # value/2: 1/2 -> 0, 3/2 -> 2, 5/2 -> 2, -1/2 -> 0, -3/2 -> -2, -5/2 -> -2
+    assert [orc.rne_shift(v, 1) for v in (1, 3, 5, -1, -3, -5)] == [0, 2, 2, 0, -2, -2]
+    # value/4: 2/4 -> 0, 6/4 -> 2, 10/4 -> 2, 5/4 -> 1, 7/4 -> 2
+    assert [orc.rne_shift(v, 2) for v in (2, 6, 10, 5, 7)] == [0, 2, 2, 1, 2]
+
+
+def test_requant8_any_shift():
+    rng = np.random.default_rng(2)
+    for v in [0, 1, -1, 127, -128, 2 ** 31 - 1, -2 ** 31] + [int(t) for t in rng.integers(-2 ** 31, 2 ** 31, 500)]:
+        for s in range(-100, 101):
+            want = _sat(_round_even(Fraction(v) / Fraction(2) ** s))
+            assert orc.requant8(v, s) == want, (v, s)
+
+
+# --------------------------------------------------------------------------- #
+# float <-> code                                                                #
+# --------------------------------------------------------------------------- #
+
+def test_quantize_hand_values():
+    x = np.array([0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 0.49999997, 126.5, 127.5, 300.0, -300.0,
+                  np.inf, -np.inf, np.nan, -128.0, 127.49], np.float32)
+    want = [0, 2, 2, 0, -2, -2, 0, 126, 127, 127, -127, 127, -127, 0, -127, 127]
+    assert orc.quantize(x, 0).tolist() == want
+    assert orc.quantize(np.array([0.03125, 0.09375, 1.0, -1.0, 7.9375, 8.0], np.float32), 4).tolist() == \
+        [0, 2, 16, -16, 127, 127]
+    assert orc.quantize(np.array([96.0, 160.0, 1000.0, 1e9], np.float32), -6).tolist() == [2, 2, 16, 127]
+
+
+def test_quantize_matches_exact_rational_rounding_and_properties():
+    rng = np.random.default_rng(3)
+    for f in (-6, -1, 0, 3, 4, 7, 12):
+        x = (rng.standard_normal(3000) * 2.0 ** (-f + 5)).astype(np.float32)
+        ties = ((rng.integers(-300, 300, 400) + 0.5) * 2.0 ** -f).astype(np.float32)
+        x = np.concatenate([x, ties])
+        q = orc.quantize(x, f)
+        want = [_sat(_round_even(Fraction(float(v)) * Fraction(2) ** f)) for v in x]
+        assert q.tolist() == want
+        # odd symmetry: fails for an asymmetric clamp or for round-half-up
+        assert np.array_equal(orc.quantize(-x, f), -q)
+        # monotone
+        order = np.argsort(x, kind="stable")
+        assert np.all(np.diff(q[order].astype(np.int32)) >= 0)
+        # round trip: |x - dq(q(x))| <= half a step inside the range
+        inside = np.abs(x) <= 127 * 2.0 ** -f
+        err = np.abs(x.astype(np.float64) - orc.dequantize(q, f).astype(np.float64))
+        assert np.all(err[inside] <= 2.0 ** -(f + 1))
+        # idempotent on codes; -128 is never produced
+        codes = np.arange(-127, 128).astype(np.int8)
+        assert np.array_equal(orc.quantize(orc.dequantize(codes, f), f), codes)
+        assert q.min() >= -127
+
+
+def test_dequantize_is_exact_scaling():
+    codes = np.arange(-128, 128).astype(np.int8)
+    for f in (-32, -3, 0, 4, 7, 32):
+        got = orc.dequantize(codes, f)
+        want = np.array([float(Fraction(int(c)) / Fraction(2) ** f) for c in codes], np.float32)
+        assert np.array_equal(got, want)
+
+
+def test_quantize_i32_saturates_and_rounds():
+    x = np.array([0.5, 1.5, -2.5, 3e9, -3e9, 2147483520.0, np.nan, 0.1], np.float32)
+    assert orc.quantize_i32(x, 0).tolist() == [0, 2, -2, 2 ** 31 - 1, -(2 ** 31 - 1), 2147483520, 0, 0]
+    assert orc.quantize_i32(np.array([0.1], np.float32), 11).tolist() == \
+        [_round_even(Fraction(float(np.float32(0.1))) * 2 ** 11)]
+
+
+# --------------------------------------------------------------------------- #
+# convolution                                                                   #
+# --------------------------------------------------------------------------- #
+
+def _brute_conv(x, w, b, stride, pad, groups):
+    """Independent big-int statement of the convolution sum over *padded* input."""
+    N, H, W, C = x.shape
+    K, R, S, Cg = w.shape
+    xp = np.zeros((N, H + 2 * pad, W + 2 * pad, C), dtype=object)
+    xp[:, pad:pad + H, pad:pad + W, :] = x.astype(object)
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    Kg = K // groups
+    out = np.zeros((N, P, Q, K), dtype=object)
+    for n, p, q, k in itertools.product(range(N), range(P), range(Q), range(K)):
+        g = k // Kg
+        patch = xp[n, p * stride:p * stride + R, q * stride:q * stride + S, g * Cg:(g + 1) * Cg]
+        out[n, p, q, k] = int((patch * w[k].astype(object)).sum()) + (0 if b is None else int(b[k]))
+    return out
+
+
+CONV_CASES = [
+    # N  H  W  C  K  R  S  st pad groups
+    (1, 5, 5, 3, 4, 3, 3, 1, 1, 1),
+    (2, 6, 5, 4, 6, 3, 3, 2, 1, 2),
+    (1, 7, 7, 2, 2, 5, 5, 1, 2, 1),
+    (1, 8, 6, 6, 6, 3, 3, 2, 0, 6),
+    (2, 4, 4, 8, 3, 1, 1, 1, 0, 1),
+    (1, 9, 9, 3, 5, 7, 7, 2, 3, 1),
+    (1, 3, 4, 4, 8, 2, 3, 1, 1, 4),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_matches_bigint_brute_force(case):
+    N, H, W, C, K, R, S, st, pad, g = case
+    rng = np.random.default_rng(sum(case))
+    x = rng.integers(-128, 128, (N, H, W, C)).astype(np.int8)
+    w = rng.integers(-128, 128, (K, R, S, C // g)).astype(np.int8)
+    b = rng.integers(-2 ** 20, 2 ** 20, (K,)).astype(np.int32)
+    want = _brute_conv(x, w, b, st, pad, g)
+    for f_in, f_w, f_out, relu in [(4, 7, 4, 0), (4, 7, 4, 1), (3, 5, 8, 0), (2, 2, 9, 1), (5, 6, -2, 0)]:
+        y, acc = orc.conv_q(x, w, b, f_in, f_w, f_out, st, pad, g, relu, want_acc=True)
+        assert np.array_equal(acc.astype(object), want)
+        ref = np.vectorize(lambda a: _sat(_round_even(Fraction(max(a, 0) if relu else a) /
+                                                      Fraction(2) ** (f_in + f_w - f_out))))(want)
+        assert np.array_equal(y.astype(np.int64), ref.astype(np.int64))
+    # no bias
+    _, acc = orc.conv_q(x, w, None, 0, 0, 0, st, pad, g, 0, want_acc=True)
+    assert np.array_equal(acc.astype(object), _brute_conv(x, w, None, st, pad, g))
+    # single-element entry point agrees
+    P, Q = acc.shape[1:3]
+    for n, p, q, k in [(0, 0, 0, 0), (N - 1, P - 1, Q - 1, K - 1), (0, P // 2, Q // 2, K // 2)]:
+        assert orc.conv_acc_at(x, w, b, st, pad, g, n, p, q, k) == want[n, p, q, k]
+
+
+def test_conv_1x1_is_an_integer_matrix_product():
+    rng = np.random.default_rng(5)
+    x = rng.integers(-128, 128, (2, 5, 7, 40)).astype(np.int8)
+    w = rng.integers(-128, 128, (24, 1, 1, 40)).astype(np.int8)
+    b = rng.integers(-1000, 1000, 24).astype(np.int32)
+    _, acc = orc.conv_q(x, w, b, 0, 0, 0, want_acc=True)
+    want = x.reshape(-1, 40).astype(np.int64) @ w.reshape(24, 40).astype(np.int64).T + b
+    assert np.array_equal(acc.reshape(-1, 24), want)
+    # stride 2 on a 1x1 kernel just subsamples the pixels
+    _, acc2 = orc.conv_q(x, w, b, 0, 0, 0, stride=2, want_acc=True)
+    assert np.array_equal(acc2, acc[:, ::2, ::2, :])
+
+
+def test_depthwise_is_per_channel_2d_correlation():
+    rng = np.random.default_rng(6)
+    C = 5
+    x = rng.integers(-128, 128, (1, 9, 8, C)).astype(np.int8)
+    w = rng.integers(-128, 128, (C, 3, 3, 1)).astype(np.int8)
+    _, acc = orc.conv_q(x, w, None, 0, 0, 0, stride=1, pad=1, groups=C, want_acc=True)
+    for c in range(C):
+        want = correlate2d(x[0, :, :, c].astype(np.int64), w[c, :, :, 0].astype(np.int64), mode="same")
+        assert np.array_equal(acc[0, :, :, c], want)
+
+
+def test_grouped_equals_dense_with_block_diagonal_weights():
+    rng = np.random.default_rng(7)
+    g, Cg, Kg = 3, 4, 2
+    x = rng.integers(-128, 128, (2, 6, 6, g * Cg)).astype(np.int8)
+    w = rng.integers(-128, 128, (g * Kg, 3, 3, Cg)).astype(np.int8)
+    dense = np.zeros((g * Kg, 3, 3, g * Cg), np.int8)
+    for k in range(g * Kg):
+        gi = k // Kg
+        dense[k, :, :, gi * Cg:(gi + 1) * Cg] = w[k]
+    ya, acca = orc.conv_q(x, w, None, 3, 6, 2, 2, 1, g, 1, want_acc=True)
+    yb, accb = orc.conv_q(x, dense, None, 3, 6, 2, 2, 1, 1, 1, want_acc=True)
+    assert np.array_equal(acca, accb) and np.array_equal(ya, yb)
+
+
+def test_extreme_codes_reach_the_eq8_bound_exactly():
+    x = np.full((1, 3, 3, 512), -128, np.int8)
+    w = np.full((1, 3, 3, 512), -128, np.int8)
+    _, acc = orc.conv_q(x, w, None, 0, 0, 0, want_acc=True)
+    assert acc.shape == (1, 1, 1, 1) and int(acc[0, 0, 0, 0]) == 4608 * 16384 == 75497472
+    assert 75497472 < 2 ** (orc.mac_acc_bits(4608, 127, 1, 127, 1) - 1)
+
+
+def test_conv_reports_int32_overflow():
+    x = np.full((1, 1, 1, 8), -128, np.int8)
+    w = np.full((1, 1, 1, 8), -128, np.int8)
+    b = np.array([2 ** 31 - 1], np.int32)
+    with pytest.raises(OverflowError):
+        orc.conv_q(x, w, b, 0, 0, 0)
+
+
+def test_relu_commutes_with_requantize():
+    rng = np.random.default_rng(8)
+    x = rng.integers(-128, 128, (1, 6, 6, 8)).astype(np.int8)
+    w = rng.integers(-128, 128, (8, 3, 3, 8)).astype(np.int8)
+    for s_out in (0, 3, 9, 12):
+        y_relu, _ = orc.conv_q(x, w, None, 4, 7, s_out, 1, 1, 1, relu=True)
+        y_lin, _ = orc.conv_q(x, w, None, 4, 7, s_out, 1, 1, 1, relu=False)
+        assert np.array_equal(y_relu, np.maximum(y_lin, 0))
+
+
+def test_identity_convolution_is_the_explicit_downscale():
+    rng = np.random.default_rng(9)
+    C = 6
+    x = rng.integers(-127, 128, (2, 4, 5, C)).astype(np.int8)
+    for f_w in (0, 3, 6):
+        w = (np.eye(C, dtype=np.int64) * 2 ** f_w).astype(np.int8).reshape(C, 1, 1, C)
+        y, _ = orc.conv_q(x, w, None, 4, f_w, 4)
+        assert np.array_equal(y, x)                       # factor 1: the layer could be spliced out
+        for f_out in (3, 1, -2):
+            y, _ = orc.conv_q(x, w, None, 4, f_w, f_out)
+            assert np.array_equal(y, orc.concat_q([x], [4], f_out))
+            z, _ = orc.eltwise_q(x, 4, np.zeros_like(x), 4, f_out)
+            assert np.array_equal(y, z)
+            want = np.vectorize(lambda c: _sat(_round_even(Fraction(int(c), 2 ** (4 - f_out)))))(x)
+            assert np.array_equal(y.astype(np.int64), want)
+
+
+# --------------------------------------------------------------------------- #
+# joins and pooling                                                             #
+# --------------------------------------------------------------------------- #
+
+def test_eltwise_is_one_rounding_of_the_exact_sum():
+    codes = np.arange(-128, 128).astype(np.int8)
+    a, b = np.meshgrid(codes, codes, indexing="ij")
+    a, b = a.ravel(), b.ravel()
+    for fa, fb, fy, relu in [(4, 4, 4, 0), (4, 4, 3, 1), (5, 2, 3, 0), (2, 6, 1, 1), (3, 4, 5, 0), (0, 7, -1, 0), (-3, -1, -4, 1)]:
+        y, acc = orc.eltwise_q(a, fa, b, fb, fy, relu, want_acc=True)
+        exact = [Fraction(int(u), 1) / Fraction(2) ** fa + Fraction(int(v), 1) / Fraction(2) ** fb for u, v in zip(a, b)]
+        F = max(fa, fb)
+        assert acc.tolist() == [int(e * Fraction(2) ** F) for e in exact]
+        want = [_sat(_round_even((max(e, 0) if relu else e) * Fraction(2) ** fy)) for e in exact]
+        assert y.tolist() == want
+        y2, _ = orc.eltwise_q(b, fb, a, fa, fy, relu)
+        assert np.array_equal(y, y2)                      # commutative
+    y, _ = orc.eltwise_q(a, 4, b, 4, 4)
+    assert np.array_equal(y, np.clip(a.astype(np.int32) + b, -127, 127))
+    with pytest.raises(ValueError):
+        orc.eltwise_q(a, 30, b, 0, 0)
+
+
+def test_eltwise_is_a_special_mac():
+    # add = 1x1 convolution over channel-stacked inputs with power-of-two "weights" (Sec. 2.2, first paragraph)
+    rng = np.random.default_rng(10)
+    C = 5
+    a = rng.integers(-128, 128, (1, 4, 4, C)).astype(np.int8)
+    b = rng.integers(-128, 128, (1, 4, 4, C)).astype(np.int8)
+    fa, fb, fy = 3, 5, 2
+    F = max(fa, fb)
+    w = np.concatenate([np.eye(C, dtype=np.int64) * 2 ** (F - fa), np.eye(C, dtype=np.int64) * 2 ** (F - fb)], axis=1)
+    w = w.astype(np.int8).reshape(C, 1, 1, 2 * C)
+    # inputs at a common nominal f_in = 0 with weights at f_w = F  ->  accumulator is the sum at F
+    y_conv, _ = orc.conv_q(np.concatenate([a, b], axis=3), w, None, 0, F, fy, relu=True)
+    y_add, _ = orc.eltwise_q(a, fa, b, fb, fy, relu=True)
+    assert np.array_equal(y_conv, y_add)
+
+
+def test_concat_rescales_each_branch_on_its_own():
+    rng = np.random.default_rng(11)
+    xs = [rng.integers(-128, 128, (2, 3, 3, c)).astype(np.int8) for c in (3, 1, 4)]
+    fs = [5, 2, 3]
+    y = orc.concat_q(xs, fs, 2)
+    assert y.shape == (2, 3, 3, 8)
+    off = 0
+    for x, f in zip(xs, fs):
+        want = np.vectorize(lambda c: _sat(_round_even(Fraction(int(c), 2 ** (f - 2)))))(x)
+        assert np.array_equal(y[..., off:off + x.shape[-1]].astype(np.int64), want)
+        off += x.shape[-1]
+    # equal formats: a byte copy, except that -128 is clamped into the symmetric range
+    y = orc.concat_q(xs, [3, 3, 3], 3)
+    assert np.array_equal(y, np.maximum(np.concatenate(xs, axis=3), -127))
+    # finer output format: exact multiplication then clamp
+    y = orc.concat_q([xs[0]], [2], 4)
+    assert np.array_equal(y, np.clip(xs[0].astype(np.int32) * 4, -127, 127))
+
+
+def _pool_ref(x, mode, k, st, pad, d):
+    N, H, W, C = x.shape
+    P, Q = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+    out = np.zeros((N, P, Q, C), np.int64)
+    for n, p, q, c in itertools.product(range(N), range(P), range(Q), range(C)):
+        vals = [int(x[n, ih, iw, c]) for ih in range(p * st - pad, p * st - pad + k)
+                for iw in range(q * st - pad, q * st - pad + k) if 0 <= ih < H and 0 <= iw < W]
+        if mode == "max":
+            out[n, p, q, c] = _sat(_round_even(Fraction(max(vals)) * Fraction(2) ** d))
+        else:
+            out[n, p, q, c] = _sat(_round_even(Fraction(sum(vals), k * k) * Fraction(2) ** d))
+    return out
+
+
+@pytest.mark.parametrize("mode", ["max", "avg"])
+def test_pool_matches_exact_rational_reference(mode):
+    rng = np.random.default_rng(12)
+    x = rng.integers(-128, 128, (2, 7, 6, 3)).astype(np.int8)
+    for k, st, pad in [(3, 2, 1), (3, 1, 1), (2, 2, 0), (7, 1, 3), (1, 1, 0), (6, 1, 0)]:
+        if k > 6 and pad == 0:
+            continue
+        for f_in, f_out in [(4, 4), (4, 2), (3, 5), (0, -3)]:
+            got = orc.pool_q(x, mode, k, st, pad, f_in, f_out)
+            assert np.array_equal(got.astype(np.int64), _pool_ref(x, mode, k, st, pad, f_out - f_in)), (k, st, pad, f_in, f_out)
+
+
+def test_pool_special_cases():
+    rng = np.random.default_rng(13)
+    x = rng.integers(-127, 128, (1, 6, 6, 4)).astype(np.int8)
+    for mode in ("max", "avg"):
+        assert np.array_equal(orc.pool_q(x, mode, 1, 1, 0, 3, 3), x)                 # k = 1 is the identity
+        const = np.full((1, 6, 6, 4), -37, np.int8)
+        assert np.all(orc.pool_q(const, mode, 3, 3, 0, 3, 3) == -37)                  # constant stays constant
+    # max commutes with the (monotone) rescale
+    a = orc.pool_q(orc.concat_q([x], [5], 2), "max", 3, 2, 1, 2, 2)
+    b = orc.pool_q(x, "max", 3, 2, 1, 5, 2)
+    assert np.array_equal(a, b)
+    # global average equals numpy's mean rounded half-even (exact rational compare)
+    g = orc.pool_q(x, "avg", 6, 1, 0, 3, 3)
+    want = [_sat(_round_even(Fraction(int(x[0, :, :, c].astype(np.int64).sum()), 36))) for c in range(4)]
+    assert g.reshape(-1).tolist() == want
+    # a 7x7 window of symmetric codes fits Eq. 12's 14-bit accumulator
+    assert 49 * 127 <= 2 ** (orc.add_acc_bits(49, 127) - 1) - 1
+
+
+# --------------------------------------------------------------------------- #
+# calibration building blocks                                                   #
+# --------------------------------------------------------------------------- #
+
+def test_format_from_float_threshold():
+    f = orc.frac_from_absmax_f32
+    assert f(1.0) == 6            # 127/64 = 1.98 >= 1 but 127/128 < 1
+    assert f(1.99) == 5
+    assert f(0.0) == 32
+    for k in range(-10, 11):
+        assert f(127.0 * 2.0 ** -k) == k
+        assert f(float(np.nextafter(np.float32(127.0 * 2.0 ** -k), np.float32(np.inf)))) == k - 1
+    assert f(1e30) == -32
+    with pytest.raises(ValueError):
+        f(float("nan"))
+    # gamma = alpha * beta_max: the chosen scale is the smallest power of two that still holds gamma
+    rng = np.random.default_rng(14)
+    for g in np.abs(rng.standard_normal(200)).astype(np.float32) * 50:
+        k = f(float(g))
+        assert Fraction(float(g)) * Fraction(2) ** k <= 127 < Fraction(float(g)) * Fraction(2) ** (k + 1)
+
+
+def test_format_from_integer_threshold():
+    f = orc.frac_from_absmax_i32
+    assert f(0, 11) == 11
+    assert f(127, 11) == 11
+    assert f(128, 11) == 10
+    assert f(254, 11) == 10
+    assert f(255, 11) == 9
+    assert f(127 * 2 ** 7, 11) == 4
+    assert f(127 * 2 ** 7 + 1, 11) == 3
+    assert f(1, 40) == 32
+    rng = np.random.default_rng(15)
+    for m in [int(v) for v in rng.integers(1, 2 ** 31, 300)]:
+        for af in (-5, 0, 9, 13):
+            k = f(m, af)
+            assert k <= af
+            assert Fraction(m) / Fraction(2) ** (af - k) <= 127                     # nothing is clipped
+            if k < af:
+                assert Fraction(m) / Fraction(2) ** (af - k - 1) > 127              # and no bit is wasted
+
+
+def test_absmax():
+    assert orc.absmax_f32(np.array([0.5, -3.25, np.nan, 2.0], np.float32)) == 3.25
+    a = np.array([5, -9, 3, -(2 ** 31)], np.int32)
+    assert orc.absmax_i32(a) == 2 ** 31
+    assert orc.absmax_i32(a, relu=True) == 5
+    assert orc.absmax_i32(np.zeros(4, np.int32)) == 0
