@@ -1,0 +1,165 @@
+/*
+ * dfq - quantized CNN inference primitives for AMD MI355X (gfx950), after
+ * Settle et al., "Quantizing Convolutional Neural Networks for Low-Power
+ * High-Throughput Inference Engines" (arXiv 1805.07941).
+ *
+ * The library implements the int8 member of the paper's dynamic floating-point
+ * family (Sec. 2.1, Eq. 1 with n = 8, p = n-1 and a power-of-two scale
+ * alpha = 2^-frac): a tensor element is an int8 code c whose value is
+ * c * 2^-frac, with frac ("fractional length") a per-tensor integer.  Every code
+ * the library WRITES lies in the symmetric range [-127, 127] (= +-beta_max of
+ * Eq. 5; the clamp rule that closes the multiply-accumulate analysis of
+ * Sec. 2.2).  Code -128 is accepted in inputs and weights.
+ *
+ * Rounding is to nearest, ties to even, everywhere (the paper leaves the mode
+ * open; the format is described as an extension of IEEE 754, whose default this
+ * is).  rne(v, s) below means v * 2^-s rounded that way (exact multiplication
+ * when s < 0) and sat8 the clamp to [-127, 127].
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library
+ *     allocates nothing, keeps no pointer and holds no state between calls.
+ *     Arrays described as "host" (branch tables of dfq_concat_q, dfq_fmt* outputs)
+ *     are ordinary host memory read or written before the call returns.
+ *   - Activations are NHWC int8, densely packed unless a channel stride is given.
+ *     Weights are [K][R][S][C/groups] int8.  Bias is [K] int32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue work and return without synchronizing; results that live on the
+ *     device (including the *_dev scalars) are ready when the stream reaches them.
+ *   - Errors are return codes only.  Arguments are validated before anything is
+ *     launched; on a non-zero status no work was enqueued.
+ *   - Input and output buffers of one call must not overlap.
+ */
+#ifndef DFQ_H
+#define DFQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* A tensor format: bits must be 8; value = code * 2^-frac; frac in [-32, 32]. */
+typedef struct { int32_t bits; int32_t frac; } dfq_fmt;
+
+typedef enum {
+    DFQ_OK = 0,
+    DFQ_EINVAL = 1,        /* null pointer, negative size, bad enum value */
+    DFQ_ESHAPE = 2,        /* inconsistent or empty geometry */
+    DFQ_EFMT = 3,          /* bits != 8, frac out of range, formats too far apart */
+    DFQ_EUNSUPPORTED = 4,  /* valid request this build has no kernel for */
+    DFQ_EDEVICE = 5        /* the HIP runtime refused a launch */
+} dfq_status;
+
+typedef enum { DFQ_POOL_MAX = 0, DFQ_POOL_AVG = 1 } dfq_pool_mode;
+
+/* Which convolution kernel dfq_conv_q_variant runs. */
+typedef enum {
+    DFQ_CONV_AUTO = 0,     /* what dfq_conv_q picks */
+    DFQ_CONV_DIRECT = 1,   /* one output element per lane; any shape */
+    DFQ_CONV_MFMA = 2,     /* implicit GEMM on int8 MFMA; groups == 1, C % 16 == 0 */
+    DFQ_CONV_DEPTHWISE = 3,/* groups == C == K, channel-vectorized VALU kernel; C % 4 == 0 */
+    DFQ_CONV_SMALLC = 4    /* implicit GEMM for few input channels (first layers); groups == 1, S*C <= 32 */
+} dfq_conv_variant;
+
+typedef void *dfq_stream;
+
+const char *dfq_status_string(dfq_status s);
+
+/* ---- float <-> code (Sec. 3, the conversion paragraph before Algorithm 1) ------------
+ * q[i] = sat8(round_ties_even(x[i] * 2^frac)); NaN -> 0, +-Inf -> +-127.
+ * x: n floats, q: n bytes.  n == 0 is a no-op. */
+dfq_status dfq_quantize(const float *x, int8_t *q, size_t n, dfq_fmt fmt, dfq_stream stream);
+
+/* Same conversion into 32-bit codes saturating at +-(2^31 - 1); frac in [-64, 64].  Used
+ * for the bias of a convolution, held at frac_in + frac_w (Sec. 3: bias thresholds as a
+ * function of input and weight thresholds). */
+dfq_status dfq_quantize_i32(const float *x, int32_t *q, size_t n, int32_t frac, dfq_stream stream);
+
+/* x[i] = q[i] * 2^-frac, exact in float. */
+dfq_status dfq_dequantize(const int8_t *q, float *x, size_t n, dfq_fmt fmt, dfq_stream stream);
+
+/* ---- convolution / inner product (Sec. 2.2, Eq. 6) -------------------------------------
+ * acc[n,p,q,k] = sum_{r,s,c} x[n, p*stride-pad+r, q*stride-pad+s, g*Cg+c] * w[k,r,s,c] + b[k]
+ * with Cg = C/groups, g = k / (K/groups); taps outside the image contribute 0.
+ * y[n,p,q,k]   = sat8(rne(relu ? max(acc,0) : acc, fmt_in.frac + fmt_w.frac - fmt_out.frac)).
+ * P = floor((H + 2*pad - R)/stride) + 1, Q likewise with W and S.
+ *
+ * x   [N][H][W][C] int8 at fmt_in          w  [K][R][S][Cg] int8 at fmt_w
+ * b   [K] int32 at fmt_in.frac+fmt_w.frac, or NULL (no bias)
+ * y   [N*P*Q] pixels of ldy bytes each, the first K written; ldy >= K lets a layer write
+ *     straight into a channel slice of a wider tensor.  May be NULL if acc_out is given.
+ * acc_out  NULL, or [N][P][Q][K] int32 receiving acc (bias included, before ReLU): the
+ *     calibration / debugging view of the wide accumulator.
+ * The 32-bit accumulator is exact as long as R*S*Cg <= 131071 (Eq. 9 with q = 32 and
+ * codes down to -128) and |b[k]| + R*S*Cg*2^14 < 2^31; the first is checked
+ * (DFQ_EUNSUPPORTED), the second is the caller's precondition.
+ * A fully connected layer is the case H = W = R = S = 1.  N == 0 is a no-op. */
+dfq_status dfq_conv_q(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int32_t *acc_out,
+                      int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                      int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu, dfq_stream stream);
+
+/* Same operation with the kernel chosen by the caller (tests, benchmarks).  Returns
+ * DFQ_EUNSUPPORTED if that kernel cannot run the shape. */
+dfq_status dfq_conv_q_variant(dfq_conv_variant variant,
+                              const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int32_t *acc_out,
+                              int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                              int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu, dfq_stream stream);
+
+/* The variant dfq_conv_q would run for this geometry (host, pure); DFQ_CONV_AUTO if the
+ * geometry is invalid. */
+dfq_conv_variant dfq_conv_q_select(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups);
+
+/* ---- scaled addition (Sec. 2.2, Eq. 10) -------------------------------------------------
+ * F = max(fa.frac, fb.frac); sum = a*2^(F-fa.frac) + b*2^(F-fb.frac)  (exact);
+ * y = sat8(rne(relu ? max(sum,0) : sum, F - fy.frac)): the exact sum rounded once.
+ * a, b, y: n bytes.  acc_out: NULL or n int32 receiving sum (before ReLU).  y may be NULL
+ * if acc_out is given.  Both alignment shifts must be <= 22 (DFQ_EFMT otherwise). */
+dfq_status dfq_eltwise_q(const int8_t *a, dfq_fmt fa, const int8_t *b, dfq_fmt fb, int8_t *y, dfq_fmt fy,
+                         int32_t *acc_out, size_t n, int relu, dfq_stream stream);
+
+/* ---- concat with per-branch rescale (Sec. 3: matching the scales of the inputs of a join;
+ * the N = 1 case of Eq. 10) -----------------------------------------------------------------
+ * y[px][off_i + c] = sat8(rne(xs[i][px][c], fs[i].frac - fy.frac)), off_i = Cs[0]+...+Cs[i-1].
+ * xs: HOST array of nbranch device pointers, branch i is [pixels][Cs[i]] int8;
+ * Cs, fs: HOST arrays.  y: [pixels][sum Cs].  1 <= nbranch <= 8. */
+dfq_status dfq_concat_q(int nbranch, const int8_t *const *xs, const int *Cs, const dfq_fmt *fs,
+                        int8_t *y, dfq_fmt fy, size_t pixels, dfq_stream stream);
+
+/* ---- pooling (the paper names max-pool among the layers that may need an explicit
+ * downscale, Sec. 3, and gives no arithmetic; average follows Eq. 10) -------------------
+ * k x k windows, floor-mode output size, NHWC.
+ * MAX: maximum over the window positions inside the image, then sat8(rne(., fin.frac-fout.frac)).
+ * AVG: sat8 of the exact rational  (sum of in-image codes) * 2^(fout.frac-fin.frac) / (k*k)
+ *      rounded once, ties to even (padded positions count as zeros in the divisor).
+ * 1 <= k <= 64, 0 <= pad < k. */
+dfq_status dfq_pool_q(const int8_t *x, int8_t *y, dfq_pool_mode mode, int N, int H, int W, int C,
+                      int k, int stride, int pad, dfq_fmt fin, dfq_fmt fout, dfq_stream stream);
+
+/* ---- calibration building blocks (Sec. 3: thresholds gamma = max |value| measured on one
+ * batch, after the ReLU, on the wide accumulator) ----------------------------------------
+ * out_dev: one DEVICE scalar, overwritten.  NaN elements are ignored.  n == 0 gives 0. */
+dfq_status dfq_absmax_f32(const float *x, size_t n, float *out_dev, dfq_stream stream);
+/* max |x[i]| (as uint32; relu != 0: negative entries count as 0). */
+dfq_status dfq_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out_dev, dfq_stream stream);
+
+/* gamma = alpha * beta_max (Sec. 2.1) solved for a power-of-two alpha: the largest frac in
+ * [-32, 32] with gamma * 2^frac <= 127; gamma = 0 gives 32.  Host, pure.  DFQ_EINVAL for a
+ * negative, infinite or NaN gamma. */
+dfq_status dfq_fmt_from_absmax_f32(float gamma, dfq_fmt *out);
+/* Integer form for accumulators held at acc_frac: the largest frac <= acc_frac (rescale factor
+ * in (0, 1], Sec. 3) with m * 2^(frac - acc_frac) <= 127, floored at -32.  Host, pure. */
+dfq_status dfq_fmt_from_absmax_i32(int64_t m, int32_t acc_frac, dfq_fmt *out);
+
+/* ---- closed forms of Sec. 2 (host, pure; return -1 on invalid arguments) ----------------- */
+int64_t dfq_beta_max(int n, int p);                                        /* Eq. 5, equality case */
+int     dfq_mac_acc_bits(int64_t N, int64_t bx, int64_t ex, int64_t by, int64_t ey);   /* Eq. 8 */
+int64_t dfq_mac_max_len(int q, int64_t bx, int64_t ex, int64_t by, int64_t ey);        /* Eq. 9 */
+int     dfq_add_acc_bits(int64_t N, int64_t bx, int64_t ex);                            /* Eq. 12 */
+int64_t dfq_add_max_len(int q, int64_t bx, int64_t ex);                                 /* Eq. 13 */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DFQ_H */

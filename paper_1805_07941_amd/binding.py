@@ -1,0 +1,264 @@
+"""ctypes binding of libdfq.so: one Python function per C entry point of include/dfq.h.
+
+Argument marshalling only.  Tensors are torch CUDA tensors (PyTorch supplies device
+memory and the current HIP stream); every arithmetic step runs inside the library's
+kernels.  There is no fallback: if the shared library is missing the import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdfq.so")
+
+OK, EINVAL, ESHAPE, EFMT, EUNSUPPORTED, EDEVICE = range(6)
+POOL_MAX, POOL_AVG = 0, 1
+CONV_AUTO, CONV_DIRECT, CONV_MFMA, CONV_DEPTHWISE, CONV_SMALLC = range(5)
+CONV_VARIANT_NAMES = {CONV_AUTO: "auto", CONV_DIRECT: "direct", CONV_MFMA: "mfma",
+                      CONV_DEPTHWISE: "depthwise", CONV_SMALLC: "smallc"}
+
+EXPORTS = [
+    "dfq_status_string", "dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q",
+    "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
+    "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32",
+    "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
+]
+
+
+class Fmt(C.Structure):
+    """dfq_fmt: value = code * 2^-frac, bits must be 8."""
+    _fields_ = [("bits", C.c_int32), ("frac", C.c_int32)]
+
+
+def fmt(frac: int) -> Fmt:
+    return Fmt(8, int(frac))
+
+
+class DfqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib():
+    """Loads libdfq.so (built by paper_1805_07941_amd.build); raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_1805_07941_amd.build` "
+                           "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+    L.dfq_status_string.restype = C.c_char_p
+    L.dfq_status_string.argtypes = [i32]
+    L.dfq_quantize.argtypes = [vp, vp, sz, Fmt, vp]
+    L.dfq_quantize_i32.argtypes = [vp, vp, sz, C.c_int32, vp]
+    L.dfq_dequantize.argtypes = [vp, vp, sz, Fmt, vp]
+    conv_args = [vp, vp, vp, vp, vp] + [i32] * 11 + [Fmt, Fmt, Fmt, i32, vp]
+    L.dfq_conv_q.argtypes = conv_args
+    L.dfq_conv_q_variant.argtypes = [i32] + conv_args
+    L.dfq_conv_q_select.argtypes = [i32] * 10
+    L.dfq_eltwise_q.argtypes = [vp, Fmt, vp, Fmt, vp, Fmt, vp, sz, i32, vp]
+    L.dfq_concat_q.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, Fmt, sz, vp]
+    L.dfq_pool_q.argtypes = [vp, vp, i32] + [i32] * 7 + [Fmt, Fmt, vp]
+    L.dfq_absmax_f32.argtypes = [vp, sz, vp, vp]
+    L.dfq_absmax_i32.argtypes = [vp, sz, i32, vp, vp]
+    L.dfq_fmt_from_absmax_f32.argtypes = [C.c_float, C.POINTER(Fmt)]
+    L.dfq_fmt_from_absmax_i32.argtypes = [i64, C.c_int32, C.POINTER(Fmt)]
+    for name in ("dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q", "dfq_conv_q_variant",
+                 "dfq_conv_q_select", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q", "dfq_absmax_f32",
+                 "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32"):
+        getattr(L, name).restype = i32
+    L.dfq_beta_max.restype = i64
+    L.dfq_beta_max.argtypes = [i32, i32]
+    L.dfq_mac_acc_bits.restype = i32
+    L.dfq_mac_acc_bits.argtypes = [i64] * 5
+    L.dfq_mac_max_len.restype = i64
+    L.dfq_mac_max_len.argtypes = [i32] + [i64] * 4
+    L.dfq_add_acc_bits.restype = i32
+    L.dfq_add_acc_bits.argtypes = [i64] * 3
+    L.dfq_add_max_len.restype = i64
+    L.dfq_add_max_len.argtypes = [i32, i64, i64]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().dfq_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise DfqError(status, where)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous CUDA tensor of {dtype}")
+    return t
+
+
+# ---- conversions ------------------------------------------------------------------ #
+def quantize(x: torch.Tensor, frac: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    _dev(x, torch.float32, "x")
+    q = out if out is not None else torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    _check(lib().dfq_quantize(_ptr(x), _ptr(q), x.numel(), fmt(frac), _stream(stream)), "dfq_quantize")
+    return q
+
+
+def quantize_i32(x: torch.Tensor, frac: int, stream=None) -> torch.Tensor:
+    _dev(x, torch.float32, "x")
+    q = torch.empty(x.shape, dtype=torch.int32, device=x.device)
+    _check(lib().dfq_quantize_i32(_ptr(x), _ptr(q), x.numel(), int(frac), _stream(stream)), "dfq_quantize_i32")
+    return q
+
+
+def dequantize(q: torch.Tensor, frac: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    _dev(q, torch.int8, "q")
+    x = out if out is not None else torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    _check(lib().dfq_dequantize(_ptr(q), _ptr(x), q.numel(), fmt(frac), _stream(stream)), "dfq_dequantize")
+    return x
+
+
+# ---- layers ---------------------------------------------------------------------- #
+def conv_out_hw(H, W, R, S, stride, pad):
+    return (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+
+
+def conv_q(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], f_in: int, f_w: int, f_out: int,
+           stride: int = 1, pad: int = 0, groups: int = 1, relu: bool = False,
+           out: Optional[torch.Tensor] = None, ldy: Optional[int] = None,
+           want_y: bool = True, want_acc: bool = False, acc_out: Optional[torch.Tensor] = None,
+           variant: int = CONV_AUTO, stream=None):
+    """x [N,H,W,C] int8, w [K,R,S,C/groups] int8, b [K] int32 or None.  Returns (y, acc).
+    `out` may be a preallocated destination (with `ldy` bytes per pixel when it is a channel
+    slice of a wider tensor)."""
+    _dev(x, torch.int8, "x"); _dev(w, torch.int8, "w")
+    if b is not None:
+        _dev(b, torch.int32, "b")
+    N, H, W, Cc = x.shape
+    K, R, S, Cg = w.shape
+    if Cg * groups != Cc:
+        raise DfqError(ESHAPE, "conv_q (weight shape does not match C/groups)")
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    y = out
+    if y is None and want_y:
+        y = torch.empty((N, max(P, 0), max(Q, 0), K), dtype=torch.int8, device=x.device)
+    acc = acc_out
+    if acc is None and want_acc:
+        acc = torch.empty((N, max(P, 0), max(Q, 0), K), dtype=torch.int32, device=x.device)
+    st = lib().dfq_conv_q_variant(int(variant), _ptr(x), _ptr(w), _ptr(b), _ptr(y), _ptr(acc),
+                                  N, H, W, Cc, K, R, S, stride, pad, groups, K if ldy is None else int(ldy),
+                                  fmt(f_in), fmt(f_w), fmt(f_out), int(bool(relu)), _stream(stream))
+    _check(st, "dfq_conv_q")
+    return y, acc
+
+
+def conv_q_select(N, H, W, Cc, K, R, S, stride, pad, groups) -> int:
+    return int(lib().dfq_conv_q_select(N, H, W, Cc, K, R, S, stride, pad, groups))
+
+
+def eltwise_q(a: torch.Tensor, f_a: int, b: torch.Tensor, f_b: int, f_y: int, relu: bool = False,
+              out: Optional[torch.Tensor] = None, want_y: bool = True, want_acc: bool = False, stream=None):
+    _dev(a, torch.int8, "a"); _dev(b, torch.int8, "b")
+    if a.shape != b.shape:
+        raise DfqError(ESHAPE, "eltwise_q (shapes differ)")
+    y = out if out is not None else (torch.empty_like(a) if want_y else None)
+    acc = torch.empty(a.shape, dtype=torch.int32, device=a.device) if want_acc else None
+    st = lib().dfq_eltwise_q(_ptr(a), fmt(f_a), _ptr(b), fmt(f_b), _ptr(y), fmt(f_y), _ptr(acc), a.numel(),
+                             int(bool(relu)), _stream(stream))
+    _check(st, "dfq_eltwise_q")
+    return y, acc
+
+
+def concat_q(xs: Sequence[torch.Tensor], fs: Sequence[int], f_y: int, out: Optional[torch.Tensor] = None,
+             stream=None) -> torch.Tensor:
+    for i, x in enumerate(xs):
+        _dev(x, torch.int8, f"xs[{i}]")
+    lead = tuple(xs[0].shape[:-1])
+    if any(tuple(x.shape[:-1]) != lead for x in xs):
+        raise DfqError(ESHAPE, "concat_q (pixel grids differ)")
+    Cs = [int(x.shape[-1]) for x in xs]
+    pixels = 1
+    for d in lead:
+        pixels *= int(d)
+    y = out if out is not None else torch.empty(lead + (sum(Cs),), dtype=torch.int8, device=xs[0].device)
+    nb = len(xs)
+    ptrs = (C.c_void_p * nb)(*[x.data_ptr() for x in xs])
+    st = lib().dfq_concat_q(nb, ptrs, (C.c_int * nb)(*Cs), (Fmt * nb)(*[fmt(f) for f in fs]), _ptr(y), fmt(f_y),
+                            pixels, _stream(stream))
+    _check(st, "dfq_concat_q")
+    return y
+
+
+def pool_q(x: torch.Tensor, mode: str, k: int, stride: int, pad: int, f_in: int, f_out: int,
+           out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    _dev(x, torch.int8, "x")
+    N, H, W, Cc = x.shape
+    P, Q = conv_out_hw(H, W, k, k, stride, pad)
+    y = out if out is not None else torch.empty((N, max(P, 0), max(Q, 0), Cc), dtype=torch.int8, device=x.device)
+    st = lib().dfq_pool_q(_ptr(x), _ptr(y), {"max": POOL_MAX, "avg": POOL_AVG}[mode], N, H, W, Cc, k, stride, pad,
+                          fmt(f_in), fmt(f_out), _stream(stream))
+    _check(st, "dfq_pool_q")
+    return y
+
+
+# ---- calibration building blocks ------------------------------------------------------ #
+def absmax_f32(x: torch.Tensor, out_dev: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Returns a one-element float32 device tensor (no synchronization)."""
+    _dev(x, torch.float32, "x")
+    out = out_dev if out_dev is not None else torch.empty(1, dtype=torch.float32, device=x.device)
+    _check(lib().dfq_absmax_f32(_ptr(x), x.numel(), _ptr(out), _stream(stream)), "dfq_absmax_f32")
+    return out
+
+
+def absmax_i32(x: torch.Tensor, relu: bool = False, out_dev: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Returns a one-element device tensor holding the maximum as uint32 bits (stored in int64-free
+    int32 storage; read it with ``absmax_i32_value``)."""
+    _dev(x, torch.int32, "x")
+    out = out_dev if out_dev is not None else torch.empty(1, dtype=torch.int32, device=x.device)
+    _check(lib().dfq_absmax_i32(_ptr(x), x.numel(), int(bool(relu)), _ptr(out), _stream(stream)), "dfq_absmax_i32")
+    return out
+
+
+def absmax_i32_value(out_dev: torch.Tensor) -> int:
+    """Host value of an absmax_i32 result (synchronizes)."""
+    return int(out_dev.cpu().numpy().view("uint32")[0])
+
+
+def fmt_from_absmax_f32(gamma: float) -> int:
+    f = Fmt()
+    _check(lib().dfq_fmt_from_absmax_f32(float(gamma), C.byref(f)), "dfq_fmt_from_absmax_f32")
+    return int(f.frac)
+
+
+def fmt_from_absmax_i32(m: int, acc_frac: int) -> int:
+    f = Fmt()
+    _check(lib().dfq_fmt_from_absmax_i32(int(m), int(acc_frac), C.byref(f)), "dfq_fmt_from_absmax_i32")
+    return int(f.frac)
+
+
+# ---- closed forms ------------------------------------------------------------------- #
+def beta_max(n, p): return int(lib().dfq_beta_max(n, p))
+def mac_acc_bits(N, bx, ex, by, ey): return int(lib().dfq_mac_acc_bits(N, bx, ex, by, ey))
+def mac_max_len(q, bx, ex, by, ey): return int(lib().dfq_mac_max_len(q, bx, ex, by, ey))
+def add_acc_bits(N, bx, ex): return int(lib().dfq_add_acc_bits(N, bx, ex))
+def add_max_len(q, bx, ex): return int(lib().dfq_add_max_len(q, bx, ex))

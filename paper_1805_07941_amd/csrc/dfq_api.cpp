@@ -1,0 +1,299 @@
+// C-ABI of libdfq: argument validation, kernel selection and the pure host functions.
+// Declarations and the contract of every call are in include/dfq.h.
+#include "dfq.h"
+
+#include <cmath>
+
+#include "dfq_host.hpp"
+
+using namespace dfq;
+
+namespace {
+
+inline bool fmt_ok(dfq_fmt f) { return f.bits == 8 && f.frac >= -32 && f.frac <= 32; }
+
+inline bool overlaps(const void *a, size_t na, const void *b, size_t nb)
+{
+    if (!a || !b || !na || !nb) return false;
+    uintptr_t pa = (uintptr_t)a, pb = (uintptr_t)b;
+    return pa < pb + nb && pb < pa + na;
+}
+
+inline dfq_status from_hip(hipError_t e) { return e == hipSuccess ? DFQ_OK : DFQ_EDEVICE; }
+
+inline int out_extent(int in, int pad, int k, int stride)
+{
+    long long span = (long long)in + 2LL * pad - k;
+    if (span < 0) return 0;
+    return (int)(span / stride) + 1;
+}
+
+// smallest q with 2^(q-1) >= m
+int width_for(unsigned long long m)
+{
+    int q = 1;
+    unsigned long long pw = 1;
+    while (pw < m) { pw <<= 1; q++; }
+    return q;
+}
+
+struct ConvCheck {
+    dfq_status st;
+    ConvArgs a;
+};
+
+ConvCheck check_conv(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int32_t *acc_out, int N, int H, int W,
+                     int C, int K, int R, int S, int stride, int pad, int groups, int ldy, dfq_fmt fi, dfq_fmt fw,
+                     dfq_fmt fo, int relu, bool need_ptrs)
+{
+    ConvCheck r{};
+    r.st = DFQ_OK;
+    if (need_ptrs && (!x || !w || (!y && !acc_out))) { r.st = DFQ_EINVAL; return r; }
+    if (N < 0) { r.st = DFQ_EINVAL; return r; }
+    if (H < 1 || W < 1 || C < 1 || K < 1 || R < 1 || S < 1 || stride < 1 || pad < 0 || groups < 1) { r.st = DFQ_ESHAPE; return r; }
+    if (C % groups || K % groups) { r.st = DFQ_ESHAPE; return r; }
+    int P = out_extent(H, pad, R, stride), Q = out_extent(W, pad, S, stride);
+    if (P < 1 || Q < 1) { r.st = DFQ_ESHAPE; return r; }
+    if (need_ptrs && y && ldy < K) { r.st = DFQ_ESHAPE; return r; }
+    if (!fmt_ok(fi) || !fmt_ok(fw) || !fmt_ok(fo)) { r.st = DFQ_EFMT; return r; }
+    long long kgemm = (long long)R * S * (C / groups);
+    // Eq. 9 with q = 32 and codes that may reach -128: the longest exact sum of products
+    if (kgemm > dfq_mac_max_len(32, 127, 1, 127, 1)) { r.st = DFQ_EUNSUPPORTED; return r; }
+    if ((long long)H * W * C >= (1LL << 31) || (long long)P * Q * (long long)(ldy > K ? ldy : K) >= (1LL << 31)) {
+        r.st = DFQ_EUNSUPPORTED;   // one image must be addressable with 32-bit offsets
+        return r;
+    }
+    r.a = ConvArgs{x, w, b, y, acc_out, N, H, W, C, K, R, S, stride, pad, groups, P, Q, ldy, fi.frac + fw.frac - fo.frac,
+                   relu ? 1 : 0};
+    if (need_ptrs) {
+        size_t nx = (size_t)N * H * W * C, npix = (size_t)N * P * Q;
+        if (overlaps(x, nx, y, npix * (size_t)ldy) || overlaps(x, nx, acc_out, npix * K * 4)) r.st = DFQ_EINVAL;
+    }
+    return r;
+}
+
+dfq_conv_variant select_variant(const ConvArgs &a)
+{
+    if (conv_depthwise_supports(a)) return DFQ_CONV_DEPTHWISE;
+    if (conv_mfma_supports(a)) return DFQ_CONV_MFMA;
+    if (conv_smallc_supports(a)) return DFQ_CONV_SMALLC;
+    return DFQ_CONV_DIRECT;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *dfq_status_string(dfq_status s)
+{
+    switch (s) {
+        case DFQ_OK: return "ok";
+        case DFQ_EINVAL: return "invalid argument";
+        case DFQ_ESHAPE: return "inconsistent shape";
+        case DFQ_EFMT: return "unsupported number format";
+        case DFQ_EUNSUPPORTED: return "no kernel for this request";
+        case DFQ_EDEVICE: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+dfq_status dfq_quantize(const float *x, int8_t *q, size_t n, dfq_fmt fmt, dfq_stream stream)
+{
+    if (!fmt_ok(fmt)) return DFQ_EFMT;
+    if (n == 0) return DFQ_OK;
+    if (!x || !q || overlaps(x, n * 4, q, n)) return DFQ_EINVAL;
+    return from_hip(launch_quantize(x, q, n, fmt.frac, (hipStream_t)stream));
+}
+
+dfq_status dfq_quantize_i32(const float *x, int32_t *q, size_t n, int32_t frac, dfq_stream stream)
+{
+    if (frac < -64 || frac > 64) return DFQ_EFMT;
+    if (n == 0) return DFQ_OK;
+    if (!x || !q || overlaps(x, n * 4, q, n * 4)) return DFQ_EINVAL;
+    return from_hip(launch_quantize_i32(x, q, n, frac, (hipStream_t)stream));
+}
+
+dfq_status dfq_dequantize(const int8_t *q, float *x, size_t n, dfq_fmt fmt, dfq_stream stream)
+{
+    if (!fmt_ok(fmt)) return DFQ_EFMT;
+    if (n == 0) return DFQ_OK;
+    if (!x || !q || overlaps(x, n * 4, q, n)) return DFQ_EINVAL;
+    return from_hip(launch_dequantize(q, x, n, fmt.frac, (hipStream_t)stream));
+}
+
+dfq_status dfq_conv_q_variant(dfq_conv_variant variant, const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y,
+                              int32_t *acc_out, int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
+                              int groups, int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu,
+                              dfq_stream stream)
+{
+    ConvCheck c = check_conv(x, w, b, y, acc_out, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, fmt_w, fmt_out,
+                             relu, true);
+    if (c.st != DFQ_OK) return c.st;
+    if (N == 0) return DFQ_OK;
+    if (variant == DFQ_CONV_AUTO) variant = select_variant(c.a);
+    hipStream_t st = (hipStream_t)stream;
+    switch (variant) {
+        case DFQ_CONV_DIRECT:
+            return from_hip(launch_conv_direct(c.a, st));
+        case DFQ_CONV_MFMA:
+            if (!conv_mfma_supports(c.a)) return DFQ_EUNSUPPORTED;
+            return from_hip(launch_conv_mfma(c.a, st));
+        case DFQ_CONV_DEPTHWISE:
+            if (!conv_depthwise_supports(c.a)) return DFQ_EUNSUPPORTED;
+            return from_hip(launch_conv_depthwise(c.a, st));
+        case DFQ_CONV_SMALLC:
+            if (!conv_smallc_supports(c.a)) return DFQ_EUNSUPPORTED;
+            return from_hip(launch_conv_smallc(c.a, st));
+        default:
+            return DFQ_EINVAL;
+    }
+}
+
+dfq_status dfq_conv_q(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int32_t *acc_out, int N, int H, int W,
+                      int C, int K, int R, int S, int stride, int pad, int groups, int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w,
+                      dfq_fmt fmt_out, int relu, dfq_stream stream)
+{
+    return dfq_conv_q_variant(DFQ_CONV_AUTO, x, w, b, y, acc_out, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in,
+                              fmt_w, fmt_out, relu, stream);
+}
+
+dfq_conv_variant dfq_conv_q_select(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups)
+{
+    dfq_fmt f{8, 0};
+    ConvCheck c = check_conv(nullptr, nullptr, nullptr, nullptr, nullptr, N, H, W, C, K, R, S, stride, pad, groups, K, f, f,
+                             f, 0, false);
+    if (c.st != DFQ_OK) return DFQ_CONV_AUTO;
+    return select_variant(c.a);
+}
+
+dfq_status dfq_eltwise_q(const int8_t *a, dfq_fmt fa, const int8_t *b, dfq_fmt fb, int8_t *y, dfq_fmt fy, int32_t *acc_out,
+                         size_t n, int relu, dfq_stream stream)
+{
+    if (!fmt_ok(fa) || !fmt_ok(fb) || !fmt_ok(fy)) return DFQ_EFMT;
+    int F = fa.frac > fb.frac ? fa.frac : fb.frac;
+    // Eq. 12: two codes of magnitude <= 2^7 shifted by <= 22 bits sum to at most 2^30
+    if (F - fa.frac > 22 || F - fb.frac > 22) return DFQ_EFMT;
+    if (n == 0) return DFQ_OK;
+    if (!a || !b || (!y && !acc_out)) return DFQ_EINVAL;
+    if (overlaps(a, n, y, n) || overlaps(b, n, y, n) || overlaps(a, n, acc_out, n * 4) || overlaps(b, n, acc_out, n * 4))
+        return DFQ_EINVAL;
+    return from_hip(launch_eltwise(a, fa.frac, b, fb.frac, y, fy.frac, acc_out, n, relu ? 1 : 0, (hipStream_t)stream));
+}
+
+dfq_status dfq_concat_q(int nbranch, const int8_t *const *xs, const int *Cs, const dfq_fmt *fs, int8_t *y, dfq_fmt fy,
+                        size_t pixels, dfq_stream stream)
+{
+    if (nbranch < 1 || nbranch > 8 || !xs || !Cs || !fs) return DFQ_EINVAL;
+    if (!fmt_ok(fy)) return DFQ_EFMT;
+    int fr[8];
+    long long ct = 0;
+    for (int i = 0; i < nbranch; i++) {
+        if (!fmt_ok(fs[i])) return DFQ_EFMT;
+        if (Cs[i] < 1) return DFQ_ESHAPE;
+        fr[i] = fs[i].frac;
+        ct += Cs[i];
+    }
+    if (ct >= (1LL << 31)) return DFQ_ESHAPE;
+    if (pixels == 0) return DFQ_OK;
+    if (!y) return DFQ_EINVAL;
+    for (int i = 0; i < nbranch; i++) {
+        if (!xs[i]) return DFQ_EINVAL;
+        if (overlaps(xs[i], pixels * (size_t)Cs[i], y, pixels * (size_t)ct)) return DFQ_EINVAL;
+    }
+    return from_hip(launch_concat(nbranch, xs, Cs, fr, y, fy.frac, pixels, (hipStream_t)stream));
+}
+
+dfq_status dfq_pool_q(const int8_t *x, int8_t *y, dfq_pool_mode mode, int N, int H, int W, int C, int k, int stride, int pad,
+                      dfq_fmt fin, dfq_fmt fout, dfq_stream stream)
+{
+    if (mode != DFQ_POOL_MAX && mode != DFQ_POOL_AVG) return DFQ_EINVAL;
+    if (N < 0) return DFQ_EINVAL;
+    if (H < 1 || W < 1 || C < 1 || k < 1 || k > 64 || stride < 1 || pad < 0 || pad >= k) return DFQ_ESHAPE;
+    int P = out_extent(H, pad, k, stride), Q = out_extent(W, pad, k, stride);
+    if (P < 1 || Q < 1) return DFQ_ESHAPE;
+    if (!fmt_ok(fin) || !fmt_ok(fout)) return DFQ_EFMT;
+    if (N == 0) return DFQ_OK;
+    if (!x || !y) return DFQ_EINVAL;
+    if (overlaps(x, (size_t)N * H * W * C, y, (size_t)N * P * Q * C)) return DFQ_EINVAL;
+    return from_hip(launch_pool(x, y, (int)mode, N, H, W, C, P, Q, k, stride, pad, fin.frac, fout.frac, (hipStream_t)stream));
+}
+
+dfq_status dfq_absmax_f32(const float *x, size_t n, float *out_dev, dfq_stream stream)
+{
+    if (!out_dev || (n && !x)) return DFQ_EINVAL;
+    return from_hip(launch_absmax_f32(x, n, out_dev, (hipStream_t)stream));
+}
+
+dfq_status dfq_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out_dev, dfq_stream stream)
+{
+    if (!out_dev || (n && !x)) return DFQ_EINVAL;
+    return from_hip(launch_absmax_i32(x, n, relu ? 1 : 0, out_dev, (hipStream_t)stream));
+}
+
+dfq_status dfq_fmt_from_absmax_f32(float gamma, dfq_fmt *out)
+{
+    if (!out) return DFQ_EINVAL;
+    if (!(gamma >= 0.0f) || std::isinf(gamma)) return DFQ_EINVAL;
+    // gamma * 2^f is exact in double, so the comparison needs no logarithm
+    int f = 32;
+    while (f > -32 && std::ldexp((double)gamma, f) > 127.0) f--;
+    out->bits = 8;
+    out->frac = f;
+    return DFQ_OK;
+}
+
+dfq_status dfq_fmt_from_absmax_i32(int64_t m, int32_t acc_frac, dfq_fmt *out)
+{
+    if (!out || m < 0) return DFQ_EINVAL;
+    int f = acc_frac > 32 ? 32 : acc_frac;
+    // lower f until m fits in 127 * 2^(acc_frac - f); m < 2^32 always fits once the gap is 26 bits
+    while (f > -32) {
+        int gap = acc_frac - f;
+        if (gap >= 40 || m <= ((int64_t)127 << gap)) break;
+        f--;
+    }
+    if (f < -32) f = -32;
+    out->bits = 8;
+    out->frac = f;
+    return DFQ_OK;
+}
+
+int64_t dfq_beta_max(int n, int p)
+{
+    if (n < 2 || n > 32 || p < 0 || p > n - 1) return -1;
+    if (p == n - 1) return ((int64_t)1 << (n - 1)) - 1;
+    int ebits = n - 1 - p;                    // exponent field width
+    if (ebits > 5) return -1;                 // result would not fit 64 bits
+    int emax = (1 << ebits) - 1;              // all-ones exponent is an ordinary number here
+    // largest magnitude: 2^(emax-1) * (2^p + (2^p - 1))
+    return ((int64_t)1 << (emax - 1)) * (((int64_t)1 << (p + 1)) - 1);
+}
+
+int dfq_mac_acc_bits(int64_t N, int64_t bx, int64_t ex, int64_t by, int64_t ey)
+{
+    if (N < 1 || bx < 1 || by < 1 || ex < 0 || ey < 0) return -1;
+    return width_for((unsigned long long)N * (unsigned long long)(bx + ex) * (unsigned long long)(by + ey) + 1ULL);
+}
+
+int64_t dfq_mac_max_len(int q, int64_t bx, int64_t ex, int64_t by, int64_t ey)
+{
+    if (q < 2 || q > 63 || bx < 1 || by < 1 || ex < 0 || ey < 0) return -1;
+    return (((int64_t)1 << (q - 1)) - 1) / ((bx + ex) * (by + ey));
+}
+
+int dfq_add_acc_bits(int64_t N, int64_t bx, int64_t ex)
+{
+    if (N < 1 || bx < 1 || ex < 0) return -1;
+    unsigned long long m = (unsigned long long)N * (unsigned long long)bx;
+    m += ex == 0 ? 1ULL : (unsigned long long)N * (unsigned long long)ex;
+    return width_for(m);
+}
+
+int64_t dfq_add_max_len(int q, int64_t bx, int64_t ex)
+{
+    if (q < 2 || q > 63 || bx < 1 || ex < 0) return -1;
+    if (ex == 0) return (((int64_t)1 << (q - 1)) - 1) / bx;
+    return ((int64_t)1 << (q - 1)) / (bx + ex);
+}
+
+}  // extern "C"

@@ -1,0 +1,45 @@
+// Host-side declarations shared by the translation units of libdfq: one launcher per
+// kernel family.  Launchers assume validated arguments and only enqueue work.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace dfq {
+
+// Geometry and formats of one convolution call (Eq. 6), after validation.
+struct ConvArgs {
+    const int8_t *x;
+    const int8_t *w;
+    const int32_t *b;    // may be null
+    int8_t *y;           // may be null when acc_out is set
+    int32_t *acc_out;    // may be null
+    int N, H, W, C, K, R, S, stride, pad, groups;
+    int P, Q;            // output extent
+    int ldy;             // bytes between consecutive output pixels of y
+    int shift;           // f_in + f_w - f_out
+    int relu;
+};
+
+hipError_t launch_quantize(const float *x, int8_t *q, size_t n, int frac, hipStream_t st);
+hipError_t launch_quantize_i32(const float *x, int32_t *q, size_t n, int frac, hipStream_t st);
+hipError_t launch_dequantize(const int8_t *q, float *x, size_t n, int frac, hipStream_t st);
+hipError_t launch_eltwise(const int8_t *a, int fa, const int8_t *b, int fb, int8_t *y, int fy, int32_t *acc, size_t n,
+                          int relu, hipStream_t st);
+hipError_t launch_concat(int nb, const int8_t *const *xs, const int *Cs, const int *fs, int8_t *y, int fy, size_t pixels,
+                         hipStream_t st);
+hipError_t launch_pool(const int8_t *x, int8_t *y, int mode, int N, int H, int W, int C, int P, int Q, int k, int stride,
+                       int pad, int fin, int fout, hipStream_t st);
+hipError_t launch_absmax_f32(const float *x, size_t n, float *out, hipStream_t st);
+hipError_t launch_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out, hipStream_t st);
+
+bool conv_direct_supports(const ConvArgs &a);
+hipError_t launch_conv_direct(const ConvArgs &a, hipStream_t st);
+bool conv_mfma_supports(const ConvArgs &a);
+hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st);
+bool conv_depthwise_supports(const ConvArgs &a);
+hipError_t launch_conv_depthwise(const ConvArgs &a, hipStream_t st);
+bool conv_smallc_supports(const ConvArgs &a);
+hipError_t launch_conv_smallc(const ConvArgs &a, hipStream_t st);
+
+}  // namespace dfq

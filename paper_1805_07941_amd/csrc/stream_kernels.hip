@@ -1,0 +1,420 @@
+// Bandwidth-bound kernels of the quantized path: float<->code conversion, scaled addition
+// (Eq. 10), concat with per-branch rescale, pooling, and the max-|.| reductions used by
+// calibration (Sec. 3).  Every kernel moves 16 bytes per lane per access where alignment
+// allows and falls back to narrower accesses otherwise; none keeps data in LDS because
+// nothing is reused.
+#include "dfq_device.hpp"
+#include "dfq_host.hpp"
+
+namespace dfq {
+
+static constexpr int kBlock = 256;
+
+static inline int grid_for(size_t work_items)
+{
+    size_t blocks = (work_items + kBlock - 1) / kBlock;
+    size_t cap = 256 * 16;  // 16 workgroups per compute unit, grid-stride beyond that
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    return (int)blocks;
+}
+
+// ------------------------------------------------------------------------------------------
+// quantize / dequantize
+// ------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ int quant_one(float x, float scale)
+{
+    // x * 2^f is exact in float (power-of-two scale) except on overflow, which saturates,
+    // and on underflow, which rounds to 0 either way.
+    float t = __builtin_rintf(x * scale);  // v_rndne_f32: ties to even
+    if (!(t == t)) return 0;               // NaN
+    t = fminf(fmaxf(t, -127.0f), 127.0f);
+    return (int)t;
+}
+
+__global__ void __launch_bounds__(kBlock) quantize_vec4(const float4 *__restrict__ x, uint32_t *__restrict__ q,
+                                                         size_t n4, float scale)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (size_t)gridDim.x * kBlock) {
+        float4 v = x[i];
+        q[i] = pack4(quant_one(v.x, scale), quant_one(v.y, scale), quant_one(v.z, scale), quant_one(v.w, scale));
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) quantize_scalar(const float *__restrict__ x, int8_t *__restrict__ q,
+                                                           size_t n, float scale)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock)
+        q[i] = (int8_t)quant_one(x[i], scale);
+}
+
+__global__ void __launch_bounds__(kBlock) quantize_i32_kernel(const float *__restrict__ x, int32_t *__restrict__ q,
+                                                               size_t n, float scale)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        float t = __builtin_rintf(x[i] * scale);   // exact product; overflow to Inf saturates below
+        int32_t c;
+        if (!(t == t)) c = 0;
+        else if (t >= 2147483648.0f) c = 2147483647;
+        else if (t <= -2147483648.0f) c = -2147483647;
+        else c = (int32_t)t;
+        q[i] = c;
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) dequantize_vec4(const uint32_t *__restrict__ q, float4 *__restrict__ x,
+                                                           size_t n4, float inv_scale)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (size_t)gridDim.x * kBlock) {
+        uint32_t w = q[i];
+        x[i] = make_float4((float)byte_of(w, 0) * inv_scale, (float)byte_of(w, 1) * inv_scale,
+                           (float)byte_of(w, 2) * inv_scale, (float)byte_of(w, 3) * inv_scale);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) dequantize_scalar(const int8_t *__restrict__ q, float *__restrict__ x,
+                                                             size_t n, float inv_scale)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock)
+        x[i] = (float)q[i] * inv_scale;
+}
+
+static inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+hipError_t launch_quantize(const float *x, int8_t *q, size_t n, int frac, hipStream_t st)
+{
+    float scale = ldexpf(1.0f, frac);
+    if (aligned(x, 16) && aligned(q, 4)) {
+        size_t n4 = n / 4;
+        if (n4) quantize_vec4<<<grid_for(n4), kBlock, 0, st>>>((const float4 *)x, (uint32_t *)q, n4, scale);
+        size_t tail = n - n4 * 4;
+        if (tail) quantize_scalar<<<1, kBlock, 0, st>>>(x + n4 * 4, q + n4 * 4, tail, scale);
+    } else {
+        quantize_scalar<<<grid_for(n), kBlock, 0, st>>>(x, q, n, scale);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_i32(const float *x, int32_t *q, size_t n, int frac, hipStream_t st)
+{
+    quantize_i32_kernel<<<grid_for(n), kBlock, 0, st>>>(x, q, n, ldexpf(1.0f, frac));
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize(const int8_t *q, float *x, size_t n, int frac, hipStream_t st)
+{
+    float inv = ldexpf(1.0f, -frac);
+    if (aligned(x, 16) && aligned(q, 4)) {
+        size_t n4 = n / 4;
+        if (n4) dequantize_vec4<<<grid_for(n4), kBlock, 0, st>>>((const uint32_t *)q, (float4 *)x, n4, inv);
+        size_t tail = n - n4 * 4;
+        if (tail) dequantize_scalar<<<1, kBlock, 0, st>>>(q + n4 * 4, x + n4 * 4, tail, inv);
+    } else {
+        dequantize_scalar<<<grid_for(n), kBlock, 0, st>>>(q, x, n, inv);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// eltwise_q: exact alignment to the finer scale, one add, one rounding
+// ------------------------------------------------------------------------------------------
+
+struct EltParams {
+    int sa, sb;   // left shifts that bring a and b to the common fractional length F
+    int s;        // F - f_y
+    int relu;
+};
+
+__device__ __forceinline__ int elt_one(int a, int b, const EltParams &p, int &sum_out)
+{
+    int sum = a * (1 << p.sa) + b * (1 << p.sb);
+    sum_out = sum;
+    if (p.relu) sum = max(sum, 0);
+    return requant8(sum, p.s);
+}
+
+template <bool kWantY, bool kWantAcc>
+__global__ void __launch_bounds__(kBlock) eltwise_vec16(const uint4 *__restrict__ a, const uint4 *__restrict__ b,
+                                                         uint4 *__restrict__ y, int4 *__restrict__ acc, size_t n16,
+                                                         EltParams p)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += (size_t)gridDim.x * kBlock) {
+        uint4 va = a[i], vb = b[i];
+        const uint32_t wa[4] = {va.x, va.y, va.z, va.w};
+        const uint32_t wb[4] = {vb.x, vb.y, vb.z, vb.w};
+        uint32_t out[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            int s0, s1, s2, s3;
+            int r0 = elt_one(byte_of(wa[j], 0), byte_of(wb[j], 0), p, s0);
+            int r1 = elt_one(byte_of(wa[j], 1), byte_of(wb[j], 1), p, s1);
+            int r2 = elt_one(byte_of(wa[j], 2), byte_of(wb[j], 2), p, s2);
+            int r3 = elt_one(byte_of(wa[j], 3), byte_of(wb[j], 3), p, s3);
+            out[j] = pack4(r0, r1, r2, r3);
+            if (kWantAcc) acc[i * 4 + j] = make_int4(s0, s1, s2, s3);
+        }
+        if (kWantY) y[i] = make_uint4(out[0], out[1], out[2], out[3]);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) eltwise_scalar(const int8_t *__restrict__ a, const int8_t *__restrict__ b,
+                                                          int8_t *__restrict__ y, int32_t *__restrict__ acc, size_t n,
+                                                          EltParams p)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        int sum;
+        int r = elt_one(a[i], b[i], p, sum);
+        if (acc) acc[i] = sum;
+        if (y) y[i] = (int8_t)r;
+    }
+}
+
+hipError_t launch_eltwise(const int8_t *a, int fa, const int8_t *b, int fb, int8_t *y, int fy, int32_t *acc, size_t n,
+                          int relu, hipStream_t st)
+{
+    int F = fa > fb ? fa : fb;
+    EltParams p{F - fa, F - fb, F - fy, relu};
+    bool vec = aligned(a, 16) && aligned(b, 16) && (!y || aligned(y, 16)) && (!acc || aligned(acc, 16));
+    size_t n16 = vec ? n / 16 : 0;
+    if (n16) {
+        int g = grid_for(n16);
+        if (y && acc) eltwise_vec16<true, true><<<g, kBlock, 0, st>>>((const uint4 *)a, (const uint4 *)b, (uint4 *)y, (int4 *)acc, n16, p);
+        else if (y) eltwise_vec16<true, false><<<g, kBlock, 0, st>>>((const uint4 *)a, (const uint4 *)b, (uint4 *)y, nullptr, n16, p);
+        else eltwise_vec16<false, true><<<g, kBlock, 0, st>>>((const uint4 *)a, (const uint4 *)b, nullptr, (int4 *)acc, n16, p);
+    }
+    size_t done = n16 * 16;
+    if (n > done)
+        eltwise_scalar<<<grid_for(n - done), kBlock, 0, st>>>(a + done, b + done, y ? y + done : nullptr,
+                                                               acc ? acc + done : nullptr, n - done, p);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// concat_q: one launch, every lane produces VEC output bytes of one branch
+// ------------------------------------------------------------------------------------------
+
+struct ConcatParams {
+    const int8_t *x[8];
+    int C[8];       // channels of each branch
+    int off[9];     // channel offset of each branch in y; off[nb] = total
+    int s[8];       // f_i - f_y
+    int nb;
+};
+
+template <int VEC>
+__global__ void __launch_bounds__(kBlock) concat_kernel(ConcatParams p, int8_t *__restrict__ y, size_t pixels)
+{
+    const int Ct = p.off[p.nb];
+    const int per_px = Ct / VEC;
+    const size_t total = pixels * (size_t)per_px;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (size_t)gridDim.x * kBlock) {
+        size_t px = i / per_px;
+        int c = (int)(i - px * per_px) * VEC;
+        int br = 0;
+#pragma unroll
+        for (int j = 1; j < 8; j++)
+            if (j < p.nb && c >= p.off[j]) br = j;
+        const int8_t *src = p.x[br] + px * (size_t)p.C[br] + (c - p.off[br]);
+        int8_t *dst = y + px * (size_t)Ct + c;
+        const int s = p.s[br];
+        if (VEC == 16) {
+            uint4 v = *(const uint4 *)src;
+            uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 4; j++)
+                w[j] = pack4(requant8(byte_of(w[j], 0), s), requant8(byte_of(w[j], 1), s),
+                             requant8(byte_of(w[j], 2), s), requant8(byte_of(w[j], 3), s));
+            *(uint4 *)dst = make_uint4(w[0], w[1], w[2], w[3]);
+        } else if (VEC == 4) {
+            uint32_t w = *(const uint32_t *)src;
+            *(uint32_t *)dst = pack4(requant8(byte_of(w, 0), s), requant8(byte_of(w, 1), s),
+                                     requant8(byte_of(w, 2), s), requant8(byte_of(w, 3), s));
+        } else {
+            *dst = (int8_t)requant8(*src, s);
+        }
+    }
+}
+
+hipError_t launch_concat(int nb, const int8_t *const *xs, const int *Cs, const int *fs, int8_t *y, int fy, size_t pixels,
+                         hipStream_t st)
+{
+    ConcatParams p{};
+    p.nb = nb;
+    int off = 0;
+    int vec = 16;
+    if (!aligned(y, 16)) vec = aligned(y, 4) ? 4 : 1;
+    for (int i = 0; i < nb; i++) {
+        p.x[i] = xs[i];
+        p.C[i] = Cs[i];
+        p.off[i] = off;
+        p.s[i] = fs[i] - fy;
+        off += Cs[i];
+        while (vec > 1 && (Cs[i] % vec || !aligned(xs[i], vec))) vec /= 4;
+    }
+    for (int i = nb; i <= 8; i++) p.off[i] = off;
+    size_t total = pixels * (size_t)(off / vec);
+    int g = grid_for(total);
+    if (vec == 16) concat_kernel<16><<<g, kBlock, 0, st>>>(p, y, pixels);
+    else if (vec == 4) concat_kernel<4><<<g, kBlock, 0, st>>>(p, y, pixels);
+    else concat_kernel<1><<<g, kBlock, 0, st>>>(p, y, pixels);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// pool_q
+// ------------------------------------------------------------------------------------------
+
+struct PoolParams {
+    int N, H, W, C, P, Q, k, stride, pad;
+    int mode;   // 0 max, 1 avg
+    int d;      // f_out - f_in
+};
+
+// (sum * 2^d) / (k*k) rounded to nearest, ties to even, clamped.  |sum| <= 128 * 4096.
+__device__ __forceinline__ int avg_round(int sum, int win, int d)
+{
+    if (d >= 32) return sum == 0 ? 0 : (sum > 0 ? 127 : -127);
+    if (d <= -40) return 0;
+    long long num = sum, den = win;
+    if (d >= 0) num <<= d; else den <<= -d;
+    long long t = num / den;
+    long long rem = num - t * den;
+    if (rem < 0) { t -= 1; rem += den; }          // floor
+    if (2 * rem > den || (2 * rem == den && (t & 1))) t += 1;
+    t = t > 127 ? 127 : (t < -127 ? -127 : t);
+    return (int)t;
+}
+
+template <int VEC>
+__global__ void __launch_bounds__(kBlock) pool_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y, PoolParams p)
+{
+    const int cv = p.C / VEC;
+    const size_t total = (size_t)p.N * p.P * p.Q * cv;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (size_t)gridDim.x * kBlock) {
+        int c = (int)(i % cv) * VEC;
+        size_t px = i / cv;
+        int q = (int)(px % p.Q);
+        size_t t = px / p.Q;
+        int pp = (int)(t % p.P);
+        int n = (int)(t / p.P);
+        int acc[VEC];
+#pragma unroll
+        for (int j = 0; j < VEC; j++) acc[j] = p.mode == 0 ? -1000 : 0;
+        for (int r = 0; r < p.k; r++) {
+            int ih = pp * p.stride - p.pad + r;
+            if (ih < 0 || ih >= p.H) continue;
+            for (int s = 0; s < p.k; s++) {
+                int iw = q * p.stride - p.pad + s;
+                if (iw < 0 || iw >= p.W) continue;
+                const int8_t *src = x + (((size_t)n * p.H + ih) * p.W + iw) * p.C + c;
+                int v[VEC];
+                if (VEC == 16) {
+                    uint4 u = *(const uint4 *)src;
+                    uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                    for (int j = 0; j < 16; j++) v[j] = byte_of(w[j / 4], j % 4);
+                } else if (VEC == 4) {
+                    uint32_t w = *(const uint32_t *)src;
+#pragma unroll
+                    for (int j = 0; j < 4; j++) v[j] = byte_of(w, j);
+                } else {
+                    v[0] = *src;
+                }
+                if (p.mode == 0) {
+#pragma unroll
+                    for (int j = 0; j < VEC; j++) acc[j] = max(acc[j], v[j]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < VEC; j++) acc[j] += v[j];
+                }
+            }
+        }
+        int out[VEC];
+#pragma unroll
+        for (int j = 0; j < VEC; j++)
+            out[j] = p.mode == 0 ? requant8(acc[j], -p.d) : avg_round(acc[j], p.k * p.k, p.d);
+        int8_t *dst = y + px * (size_t)p.C + c;
+        if (VEC == 16) {
+            *(uint4 *)dst = make_uint4(pack4(out[0], out[1], out[2], out[3]), pack4(out[4], out[5], out[6], out[7]),
+                                       pack4(out[8], out[9], out[10], out[11]), pack4(out[12], out[13], out[14], out[15]));
+        } else if (VEC == 4) {
+            *(uint32_t *)dst = pack4(out[0], out[1], out[2], out[3]);
+        } else {
+            *dst = (int8_t)out[0];
+        }
+    }
+}
+
+hipError_t launch_pool(const int8_t *x, int8_t *y, int mode, int N, int H, int W, int C, int P, int Q, int k, int stride,
+                       int pad, int fin, int fout, hipStream_t st)
+{
+    PoolParams p{N, H, W, C, P, Q, k, stride, pad, mode, fout - fin};
+    int vec = 16;
+    while (vec > 1 && (C % vec || !aligned(x, vec) || !aligned(y, vec))) vec /= 4;
+    size_t total = (size_t)N * P * Q * (C / vec);
+    int g = grid_for(total);
+    if (vec == 16) pool_kernel<16><<<g, kBlock, 0, st>>>(x, y, p);
+    else if (vec == 4) pool_kernel<4><<<g, kBlock, 0, st>>>(x, y, p);
+    else pool_kernel<1><<<g, kBlock, 0, st>>>(x, y, p);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// max |.| reductions.  The result scalar is first cleared by a one-lane kernel (not a memset,
+// so that the sequence can be captured into a HIP graph), then every workgroup folds its
+// share with one atomic max.  Non-negative floats order like their bit patterns.
+// ------------------------------------------------------------------------------------------
+
+__global__ void clear_u32(uint32_t *p) { *p = 0u; }
+
+__device__ __forceinline__ void block_max_to(uint32_t v, uint32_t *out)
+{
+    __shared__ uint32_t part[kBlock / kWave];
+    v = wave_max_u32(v);
+    if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x / kWave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t m = part[0];
+#pragma unroll
+        for (int i = 1; i < kBlock / kWave; i++) m = max(m, part[i]);
+        if (m) atomicMax(out, m);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) absmax_f32_kernel(const float *__restrict__ x, size_t n, uint32_t *out)
+{
+    uint32_t m = 0;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        float a = fabsf(x[i]);
+        if (a == a) m = max(m, __float_as_uint(a));   // skip NaN
+    }
+    block_max_to(m, out);
+}
+
+__global__ void __launch_bounds__(kBlock) absmax_i32_kernel(const int32_t *__restrict__ x, size_t n, int relu, uint32_t *out)
+{
+    uint32_t m = 0;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        int v = x[i];
+        uint32_t a = v >= 0 ? (uint32_t)v : (relu ? 0u : (uint32_t)0 - (uint32_t)v);
+        m = max(m, a);
+    }
+    block_max_to(m, out);
+}
+
+hipError_t launch_absmax_f32(const float *x, size_t n, float *out, hipStream_t st)
+{
+    clear_u32<<<1, 1, 0, st>>>((uint32_t *)out);
+    if (n) absmax_f32_kernel<<<grid_for(n), kBlock, 0, st>>>(x, n, (uint32_t *)out);
+    return hipGetLastError();
+}
+
+hipError_t launch_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out, hipStream_t st)
+{
+    clear_u32<<<1, 1, 0, st>>>(out);
+    if (n) absmax_i32_kernel<<<grid_for(n), kBlock, 0, st>>>(x, n, relu, out);
+    return hipGetLastError();
+}
+
+}  // namespace dfq

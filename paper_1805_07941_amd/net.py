@@ -1,0 +1,170 @@
+"""Runs a layer graph (``workloads.Net``) on the GPU through the dfq library: the
+single-batch calibration of Sec. 3 and plain inference.
+
+This is sequencing only: which library call comes next and which buffers it gets.  Format
+choices are made by ``dfq_fmt_from_absmax_*`` from thresholds the device kernels reduce;
+the only host work per layer during calibration is reading one scalar back.
+
+Order of the procedure (Sec. 3): weights get the smallest power-of-two scale that holds
+max |w| of the layer; the bias becomes an integer at the product scale of input and weights;
+every layer runs on its already-quantized upstream tensors ("bootstrap"); a layer's output
+format is chosen from its 32-bit accumulators after the ReLU ("lazy" thresholding) with a
+rescale factor in (0, 1]; element-wise adds rescale the exact aligned sum once; concat rescales
+its branches into the coarsest branch format; pooling keeps its input format.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, Optional
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class Quantized:
+    frac: Dict[str, int] = field(default_factory=dict)       # tensor name -> fractional length
+    w_frac: Dict[str, int] = field(default_factory=dict)     # conv node name -> weight fractional length
+    w: Dict[str, torch.Tensor] = field(default_factory=dict)  # int8 [K,R,S,Cg] on the device
+    b: Dict[str, torch.Tensor] = field(default_factory=dict)  # int32 [K] on the device
+
+
+def _read_f32(t: torch.Tensor) -> float:
+    return float(t.cpu()[0])
+
+
+def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True):
+    """x: float32 NHWC images (or int8 codes when the network takes codes).  Returns
+    (Quantized, dict of int8 tensors of the calibration batch)."""
+    qz = Quantized()
+    t: Dict[str, torch.Tensor] = {}
+    if net.input_is_int8:
+        qz.frac[net.input_name] = net.f_input_codes
+        t[net.input_name] = x
+    else:
+        if net.fixed_f_input is not None:
+            qz.frac[net.input_name] = net.fixed_f_input
+        else:
+            qz.frac[net.input_name] = B.fmt_from_absmax_f32(_read_f32(B.absmax_f32(x)))
+        t[net.input_name] = B.quantize(x, qz.frac[net.input_name])
+    last_use = _last_use(net)
+    for idx, nd in enumerate(net.nodes):
+        if nd.op == "conv":
+            src = nd.srcs[0]
+            f_in = qz.frac[src]
+            wf, bf = net.weights(nd)
+            wf = torch.from_numpy(wf).to(device)
+            bf = torch.from_numpy(bf).to(device)
+            f_w = B.fmt_from_absmax_f32(_read_f32(B.absmax_f32(wf)))
+            qz.w_frac[nd.name] = f_w
+            qz.w[nd.name] = B.quantize(wf, f_w)
+            qz.b[nd.name] = B.quantize_i32(bf, f_in + f_w)
+            w, b = qz.w[nd.name], qz.b[nd.name]
+            if nd.fixed_f_out is not None:
+                qz.frac[nd.dst] = nd.fixed_f_out
+            else:
+                _, acc = B.conv_q(t[src], w, b, f_in, f_w, 0, nd.stride, nd.pad, nd.groups, nd.relu,
+                                  want_y=False, want_acc=True)
+                m = B.absmax_i32_value(B.absmax_i32(acc, relu=nd.relu))
+                del acc
+                qz.frac[nd.dst] = B.fmt_from_absmax_i32(m, f_in + f_w)
+            t[nd.dst], _ = B.conv_q(t[src], w, b, f_in, f_w, qz.frac[nd.dst], nd.stride, nd.pad, nd.groups, nd.relu)
+        elif nd.op == "eltwise":
+            a, b2 = nd.srcs
+            fa, fb = qz.frac[a], qz.frac[b2]
+            _, acc = B.eltwise_q(t[a], fa, t[b2], fb, 0, nd.relu, want_y=False, want_acc=True)
+            m = B.absmax_i32_value(B.absmax_i32(acc, relu=nd.relu))
+            del acc
+            qz.frac[nd.dst] = B.fmt_from_absmax_i32(m, max(fa, fb))
+            t[nd.dst], _ = B.eltwise_q(t[a], fa, t[b2], fb, qz.frac[nd.dst], nd.relu)
+        elif nd.op == "concat":
+            fs = [qz.frac[s] for s in nd.srcs]
+            qz.frac[nd.dst] = nd.fixed_f_out if nd.fixed_f_out is not None else min(fs)
+            t[nd.dst] = B.concat_q([t[s] for s in nd.srcs], fs, qz.frac[nd.dst])
+        elif nd.op in ("maxpool", "avgpool"):
+            src = nd.srcs[0]
+            qz.frac[nd.dst] = qz.frac[src]
+            t[nd.dst] = B.pool_q(t[src], "max" if nd.op == "maxpool" else "avg", nd.R, nd.stride, nd.pad,
+                                 qz.frac[src], qz.frac[nd.dst])
+        else:
+            raise ValueError(nd.op)
+        if not keep_tensors:
+            for s in nd.srcs:
+                if last_use.get(s) == idx and s != net.output_name:
+                    t.pop(s, None)
+    return qz, t
+
+
+def _last_use(net) -> Dict[str, int]:
+    last = {}
+    for idx, nd in enumerate(net.nodes):
+        for s in nd.srcs:
+            last[s] = idx
+    return last
+
+
+class Plan:
+    """A calibrated network bound to preallocated device buffers for one batch size, so that
+    a pass is a fixed sequence of library calls with no allocation and no host
+    synchronization."""
+
+    def __init__(self, net, qz: Quantized, batch: int, device="cuda:0", keep_all: bool = True):
+        self.net, self.qz, self.batch, self.device = net, qz, batch, device
+        self.buf: Dict[str, torch.Tensor] = {}
+        H, W, Cc = net.shapes[net.input_name]
+        self.buf[net.input_name] = torch.empty((batch, H, W, Cc), dtype=torch.int8, device=device)
+        if keep_all:
+            for nd in net.nodes:
+                P, Q, K = net.shapes[nd.dst]
+                self.buf[nd.dst] = torch.empty((batch, P, Q, K), dtype=torch.int8, device=device)
+        else:
+            self._assign_pooled()
+        P, Q, K = net.shapes[net.output_name]
+        self.logits = torch.empty((batch, P * Q * K), dtype=torch.float32, device=device)
+
+    def _assign_pooled(self):
+        """Reuses buffers whose tensor is dead (sized in bytes), to keep the footprint small."""
+        net = self.net
+        last = _last_use(net)
+        free: list = []
+        owner: Dict[str, torch.Tensor] = {}
+        for idx, nd in enumerate(net.nodes):
+            P, Q, K = net.shapes[nd.dst]
+            need = self.batch * P * Q * K
+            pick = None
+            for i, st in enumerate(free):
+                if st.numel() >= need and (pick is None or st.numel() < free[pick].numel()):
+                    pick = i
+            storage = free.pop(pick) if pick is not None else torch.empty(need, dtype=torch.int8, device=self.device)
+            self.buf[nd.dst] = storage[:need].view(self.batch, P, Q, K)
+            owner[nd.dst] = storage
+            for s in nd.srcs:
+                if last.get(s) == idx and s != net.input_name and s != net.output_name:
+                    free.append(owner[s])
+
+    def run(self, x: torch.Tensor, stream=None) -> torch.Tensor:
+        """x: float32 images [batch,H,W,C] (or int8 codes).  Returns the float logits buffer."""
+        net, qz, t = self.net, self.qz, self.buf
+        if net.input_is_int8:
+            t[net.input_name] = x
+        else:
+            B.quantize(x, qz.frac[net.input_name], out=t[net.input_name], stream=stream)
+        for nd in net.nodes:
+            if nd.op == "conv":
+                src = nd.srcs[0]
+                B.conv_q(t[src], qz.w[nd.name], qz.b[nd.name], qz.frac[src], qz.w_frac[nd.name], qz.frac[nd.dst],
+                         nd.stride, nd.pad, nd.groups, nd.relu, out=t[nd.dst], stream=stream)
+            elif nd.op == "eltwise":
+                a, b2 = nd.srcs
+                B.eltwise_q(t[a], qz.frac[a], t[b2], qz.frac[b2], qz.frac[nd.dst], nd.relu, out=t[nd.dst], stream=stream)
+            elif nd.op == "concat":
+                B.concat_q([t[s] for s in nd.srcs], [qz.frac[s] for s in nd.srcs], qz.frac[nd.dst], out=t[nd.dst],
+                           stream=stream)
+            else:
+                src = nd.srcs[0]
+                B.pool_q(t[src], "max" if nd.op == "maxpool" else "avg", nd.R, nd.stride, nd.pad, qz.frac[src],
+                         qz.frac[nd.dst], out=t[nd.dst], stream=stream)
+        out = t[net.output_name]
+        B.dequantize(out.view(self.batch, -1), qz.frac[net.output_name], out=self.logits, stream=stream)
+        return self.logits

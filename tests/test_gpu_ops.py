@@ -1,0 +1,214 @@
+"""GPU parity: every library call against the CPU oracle, byte for byte, on the same seeded
+inputs.  All calls go through the C-ABI (via the ctypes binding)."""
+import itertools
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle as orc
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1805_07941_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+# ---------------------------------------------------------------------------------------- #
+def test_quantize_dequantize(B):
+    rng = np.random.default_rng(100)
+    for n, f in [(1, 0), (3, 4), (4099, 5), (1 << 20, -3), (12345, 12), (777, 32), (64, -32)]:
+        x = (rng.standard_normal(n) * 2.0 ** (-f + 5)).astype(np.float32)
+        k = min(n, 8)
+        x[:k] = np.array([np.nan, np.inf, -np.inf, 0.5 * 2.0 ** -f, 1.5 * 2.0 ** -f, -2.5 * 2.0 ** -f, 1e30, -1e30],
+                         np.float32)[:k]
+        q = B.quantize(dev(x), f)
+        q_ref = orc.quantize(x, f)
+        assert np.array_equal(host(q), q_ref), (n, f)
+        xd = B.dequantize(q, f)
+        assert np.array_equal(host(xd), orc.dequantize(q_ref, f))
+    # unaligned views take the narrow path
+    x = rng.standard_normal(1001).astype(np.float32)
+    xd = dev(x)
+    q = torch.empty(1004, dtype=torch.int8, device=DEV)
+    B.quantize(xd[1:], 4, out=q[3:1003])
+    assert np.array_equal(host(q[3:1003]), orc.quantize(x[1:], 4))
+    # empty
+    B.quantize(torch.empty(0, dtype=torch.float32, device=DEV), 3)
+
+
+def test_quantize_i32(B):
+    rng = np.random.default_rng(101)
+    x = (rng.standard_normal(5000) * 0.1).astype(np.float32)
+    x[:6] = [np.nan, np.inf, -np.inf, 1e30, -1e30, 0.5]
+    for f in (0, 11, 13, 31, 40, 64, -5):
+        assert np.array_equal(host(B.quantize_i32(dev(x), f)), orc.quantize_i32(x, f)), f
+
+
+def test_config0_every_variant(B):
+    c = wl.config0()
+    y_ref, acc_ref = orc.conv_q(c["x"], c["w"], c["b"], c["f_in"], c["f_w"], c["f_out"], c["stride"], c["pad"],
+                                c["groups"], c["relu"], want_acc=True)
+    ran = []
+    for variant in (B.CONV_AUTO, B.CONV_DIRECT, B.CONV_MFMA):
+        try:
+            y, acc = B.conv_q(dev(c["x"]), dev(c["w"]), dev(c["b"]), c["f_in"], c["f_w"], c["f_out"], c["stride"],
+                              c["pad"], c["groups"], c["relu"], want_acc=True, variant=variant)
+        except B.DfqError as e:
+            assert e.status == B.EUNSUPPORTED
+            continue
+        ran.append(variant)
+        assert np.array_equal(host(acc), acc_ref), B.CONV_VARIANT_NAMES[variant]
+        assert np.array_equal(host(y), y_ref), B.CONV_VARIANT_NAMES[variant]
+    assert B.CONV_AUTO in ran and B.CONV_DIRECT in ran
+
+
+def _rand_conv(rng, N, H, W, C, K, R, S, groups):
+    x = rng.integers(-128, 128, (N, H, W, C)).astype(np.int8)
+    w = rng.integers(-128, 128, (K, R, S, C // groups)).astype(np.int8)
+    b = rng.integers(-2 ** 20, 2 ** 20, (K,)).astype(np.int32)
+    return x, w, b
+
+
+CONV_SHAPES = [
+    # N  H   W   C    K   R  S  st pad groups
+    (1, 5, 5, 3, 4, 3, 3, 1, 1, 1),
+    (2, 9, 7, 16, 24, 3, 3, 1, 1, 1),
+    (2, 9, 7, 16, 24, 3, 3, 2, 1, 1),
+    (1, 12, 12, 32, 40, 1, 1, 1, 0, 1),
+    (3, 14, 14, 64, 64, 3, 3, 1, 1, 1),
+    (2, 14, 14, 64, 128, 1, 1, 2, 0, 1),
+    (1, 17, 13, 48, 80, 5, 5, 1, 2, 1),
+    (2, 8, 8, 128, 96, 3, 3, 2, 1, 1),
+    (1, 7, 7, 512, 200, 1, 1, 1, 0, 1),
+    (5, 1, 1, 256, 100, 1, 1, 1, 0, 1),          # fully connected
+    (1, 20, 20, 3, 32, 3, 3, 2, 1, 1),           # stem-like
+    (1, 23, 23, 3, 64, 7, 7, 2, 3, 1),           # stem-like 7x7
+    (2, 10, 10, 32, 32, 3, 3, 1, 1, 32),         # depthwise
+    (2, 11, 9, 64, 64, 3, 3, 2, 1, 64),          # depthwise stride 2
+    (1, 9, 9, 24, 24, 3, 3, 1, 1, 24),           # depthwise, C % 16 != 0
+    (1, 8, 8, 16, 32, 3, 3, 1, 1, 4),            # grouped
+    (1, 6, 6, 20, 10, 2, 3, 1, 1, 5),            # grouped, odd kernel
+    (1, 33, 31, 16, 16, 3, 3, 1, 0, 1),          # no padding
+    (1, 40, 40, 64, 256, 3, 3, 1, 1, 1),         # several tiles in both GEMM dimensions
+]
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv_q_random_shapes(B, shape):
+    N, H, W, C, K, R, S, st, pad, g = shape
+    rng = np.random.default_rng(abs(hash(shape)) % (2 ** 31))
+    x, w, b = _rand_conv(rng, N, H, W, C, K, R, S, g)
+    xd, wd, bd = dev(x), dev(w), dev(b)
+    variants = [B.CONV_AUTO, B.CONV_DIRECT, B.CONV_MFMA, B.CONV_DEPTHWISE, B.CONV_SMALLC]
+    first = True
+    for f_in, f_w, f_out, relu, bias in [(4, 7, 4, 1, True), (3, 6, 2, 0, True), (2, 2, 4, 0, False), (5, 5, -3, 1, True),
+                                         (1, 1, 6, 1, True)]:
+        y_ref, acc_ref = orc.conv_q(x, w, b if bias else None, f_in, f_w, f_out, st, pad, g, relu, want_acc=True)
+        for v in variants:
+            try:
+                y, acc = B.conv_q(xd, wd, bd if bias else None, f_in, f_w, f_out, st, pad, g, relu, want_acc=first,
+                                  variant=v)
+            except B.DfqError as e:
+                assert e.status == B.EUNSUPPORTED and v not in (B.CONV_AUTO, B.CONV_DIRECT)
+                continue
+            if first:
+                assert np.array_equal(host(acc), acc_ref), B.CONV_VARIANT_NAMES[v]
+            assert np.array_equal(host(y), y_ref), (B.CONV_VARIANT_NAMES[v], f_in, f_w, f_out, relu)
+        first = False
+
+
+def test_conv_q_writes_into_a_channel_slice(B):
+    rng = np.random.default_rng(102)
+    x, w, b = _rand_conv(rng, 2, 10, 10, 32, 48, 3, 3, 1)
+    wide = torch.full((2, 10, 10, 100), 99, dtype=torch.int8, device=DEV)
+    y_ref, _ = orc.conv_q(x, w, b, 4, 7, 3, 1, 1, 1, True)
+    for v in (B.CONV_AUTO, B.CONV_DIRECT):
+        wide.fill_(99)
+        B.conv_q(dev(x), dev(w), dev(b), 4, 7, 3, 1, 1, 1, True, out=wide.view(-1)[20:], ldy=100, variant=v)
+        got = host(wide)
+        assert np.array_equal(got[..., 20:68], y_ref)
+        assert np.all(got[..., :20] == 99) and np.all(got[..., 68:] == 99)
+
+
+def test_conv_q_shift_extremes(B):
+    rng = np.random.default_rng(103)
+    x, w, b = _rand_conv(rng, 1, 6, 6, 16, 16, 3, 3, 1)
+    for f_in, f_w, f_out in [(0, 0, 0), (0, 0, 5), (-3, -2, 4), (10, 10, -12), (16, 16, -1), (32, 32, -32), (0, 0, 32)]:
+        y_ref, _ = orc.conv_q(x, w, b, f_in, f_w, f_out, 1, 1, 1, False)
+        for v in (B.CONV_AUTO, B.CONV_DIRECT):
+            y, _ = B.conv_q(dev(x), dev(w), dev(b), f_in, f_w, f_out, 1, 1, 1, False, variant=v)
+            assert np.array_equal(host(y), y_ref), (f_in, f_w, f_out, v)
+
+
+def test_eltwise_q(B):
+    rng = np.random.default_rng(104)
+    for n in (1, 15, 16, 1000, 4096 + 7, 1 << 20):
+        a = rng.integers(-128, 128, n).astype(np.int8)
+        b = rng.integers(-128, 128, n).astype(np.int8)
+        for fa, fb, fy, relu in [(4, 4, 4, 0), (4, 4, 3, 1), (5, 2, 3, 0), (2, 6, 1, 1), (3, 4, 5, 0), (0, 7, -1, 0),
+                                 (-3, -1, -4, 1), (10, -12, 0, 0)]:
+            y_ref, acc_ref = orc.eltwise_q(a, fa, b, fb, fy, relu, want_acc=True)
+            y, acc = B.eltwise_q(dev(a), fa, dev(b), fb, fy, relu, want_acc=True)
+            assert np.array_equal(host(y), y_ref) and np.array_equal(host(acc), acc_ref), (n, fa, fb, fy, relu)
+            y, _ = B.eltwise_q(dev(a), fa, dev(b), fb, fy, relu)
+            assert np.array_equal(host(y), y_ref)
+    with pytest.raises(B.DfqError):
+        B.eltwise_q(dev(a), 30, dev(b), 0, 0)
+
+
+def test_concat_q(B):
+    rng = np.random.default_rng(105)
+    for lead, Cs in [((2, 5, 5), (64, 128, 32, 32)), ((1, 3, 3), (3, 1, 4)), ((1, 7, 7), (4, 8, 12)), ((3, 2, 2), (16,)),
+                     ((1, 28, 28), (64, 96, 16, 32, 48, 16, 16, 32))]:
+        xs = [rng.integers(-128, 128, lead + (c,)).astype(np.int8) for c in Cs]
+        fs = [int(v) for v in rng.integers(2, 7, len(Cs))]
+        for fy in (min(fs), min(fs) - 2, max(fs)):
+            y = B.concat_q([dev(x) for x in xs], fs, fy)
+            assert np.array_equal(host(y), orc.concat_q(xs, fs, fy)), (Cs, fs, fy)
+
+
+@pytest.mark.parametrize("mode", ["max", "avg"])
+def test_pool_q(B, mode):
+    rng = np.random.default_rng(106)
+    for (N, H, W, C), (k, st, pad) in itertools.product(
+            [(2, 14, 14, 64), (1, 9, 7, 3), (2, 8, 8, 20), (3, 7, 7, 128)],
+            [(3, 2, 1), (3, 1, 1), (2, 2, 0), (7, 1, 0), (1, 1, 0), (7, 7, 3)]):
+        x = rng.integers(-128, 128, (N, H, W, C)).astype(np.int8)
+        for f_in, f_out in [(4, 4), (4, 2), (3, 5), (0, -3)]:
+            y = B.pool_q(dev(x), mode, k, st, pad, f_in, f_out)
+            assert np.array_equal(host(y), orc.pool_q(x, mode, k, st, pad, f_in, f_out)), (N, H, W, C, k, st, pad, f_in, f_out)
+
+
+def test_absmax_and_formats(B):
+    rng = np.random.default_rng(107)
+    for n in (1, 63, 64, 1000, 1 << 20):
+        x = rng.standard_normal(n).astype(np.float32) * 7
+        if n > 3:
+            x[2] = np.nan
+        got = float(host(B.absmax_f32(dev(x)))[0])
+        assert got == orc.absmax_f32(x)
+        a = rng.integers(-2 ** 31, 2 ** 31, n).astype(np.int32)
+        for relu in (0, 1):
+            assert B.absmax_i32_value(B.absmax_i32(dev(a), relu)) == orc.absmax_i32(a, relu)
+    a = np.array([-2 ** 31, 5], np.int32)
+    assert B.absmax_i32_value(B.absmax_i32(dev(a))) == 2 ** 31
+    assert B.absmax_i32_value(B.absmax_i32(torch.empty(0, dtype=torch.int32, device=DEV))) == 0
