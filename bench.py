@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-inference hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch that is already resident in
+HBM: quantize the float images, run every int8 layer of the ResNet-50-shaped network
+(53 convolutions + the fully connected layer, 16 residual adds, max and average pooling),
+dequantize the logits.  Formats, integer weights and biases come from a single-batch
+calibration done before the timed region.
+
+Prints ONE JSON line.  `value` is int8 TOPS of the whole step (2 x multiply-accumulates of all
+convolution layers / step time); images/s, the roofline of the matrix-core convolution kernel
+(HIP events around each of its launches, inside the timed region) and the CPU oracle timed on a
+bounded sample of the same workload are carried alongside.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 matrix peak, published
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def conv_nodes(net):
+    return [nd for nd in net.nodes if nd.op == "conv"]
+
+
+def node_macs(net, nd):
+    C = net.shapes[nd.srcs[0]][2]
+    P, Q, K = net.shapes[nd.dst]
+    return P * Q * K * nd.R * nd.R * (C // nd.groups)
+
+
+def node_bytes(net, nd):
+    """Algorithmic HBM bytes per image of one conv: int8 input + int8 output (weights and bias
+    are added once per launch by the caller)."""
+    H, W, C = net.shapes[nd.srcs[0]]
+    P, Q, K = net.shapes[nd.dst]
+    return H * W * C + P * Q * K
+
+
+def cpu_baseline(net, batch_sample: int, calib_n: int):
+    """The oracle as it stands, on the host cores: inference of `batch_sample` images."""
+    import oracle as orc
+    import oracle.net as onet
+    x = net.input_float()
+    qz, _ = onet.calibrate(net, x[:calib_n])
+    xs = x[:batch_sample]
+    t0 = time.perf_counter()
+    t = onet.infer(net, qz, xs)
+    onet.logits(net, qz, t)
+    dt = time.perf_counter() - t0
+    macs = net.macs_per_image() * batch_sample
+    return dict(value=2 * macs / dt / 1e12, unit="TOPS", cores=orc.num_threads(), kind="oracle",
+                sample=f"inference of {batch_sample} of the {net.batch} images (same network, same formats rule), "
+                       f"{dt:.2f} s", images_per_s=batch_sample / dt)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--calib", type=int, default=8, help="images of the single calibration batch")
+    ap.add_argument("--cpu-sample", type=int, default=16, help="images the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-kernel-events", action="store_true", help="skip the per-launch events (pure step timing)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+              "(the path shards by batch with no exchange, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wl
+    from paper_1805_07941_amd import binding as B
+    from paper_1805_07941_amd import net as gnet
+
+    B.lib()
+    if not torch.cuda.is_available():
+        print("bench.py: needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    net = wl.resnet50(batch=args.batch)
+    x_host = net.input_float()
+    x = torch.from_numpy(x_host).to(dev)
+    qz, _ = gnet.calibrate(net, x[:args.calib].contiguous(), keep_tensors=False)
+    plan = gnet.Plan(net, qz, args.batch, keep_all=False)
+
+    convs = conv_nodes(net)
+    H0, W0, C0 = net.in_shape
+    variant_of = {}
+    for nd in convs:
+        H, W, C = net.shapes[nd.srcs[0]]
+        variant_of[nd.name] = B.conv_q_select(args.batch, H, W, C, nd.K, nd.R, nd.R, nd.stride, nd.pad, nd.groups)
+    mfma_nodes = [nd for nd in convs if variant_of[nd.name] == B.CONV_MFMA]
+
+    # instrumented pass: the same call sequence with an event pair around each MFMA convolution
+    events = []
+
+    def run_step(record: bool):
+        if not record:
+            plan.run(x)
+            return
+        netq, t = plan.qz, plan.buf
+        B.quantize(x, netq.frac[net.input_name], out=t[net.input_name])
+        for nd in net.nodes:
+            if nd.op == "conv":
+                src = nd.srcs[0]
+                mf = variant_of[nd.name] == B.CONV_MFMA
+                if mf:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                B.conv_q(t[src], netq.w[nd.name], netq.b[nd.name], netq.frac[src], netq.w_frac[nd.name],
+                         netq.frac[nd.dst], nd.stride, nd.pad, nd.groups, nd.relu, out=t[nd.dst])
+                if mf:
+                    e1.record()
+                    events.append((nd.name, e0, e1))
+            elif nd.op == "eltwise":
+                a, b2 = nd.srcs
+                B.eltwise_q(t[a], netq.frac[a], t[b2], netq.frac[b2], netq.frac[nd.dst], nd.relu, out=t[nd.dst])
+            else:
+                src = nd.srcs[0]
+                B.pool_q(t[src], "max" if nd.op == "maxpool" else "avg", nd.R, nd.stride, nd.pad, netq.frac[src],
+                         netq.frac[nd.dst], out=t[nd.dst])
+        out = t[net.output_name]
+        B.dequantize(out.view(args.batch, -1), netq.frac[net.output_name], out=plan.logits)
+
+    record = not args.no_kernel_events
+    for _ in range(args.warmup):
+        run_step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step(record)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    macs_step = net.macs_per_image() * args.batch
+    tops = 2 * macs_step / (ms_per_step * 1e-3) / 1e12
+    imgs = args.batch / (ms_per_step * 1e-3)
+
+    roofline = None
+    per_layer = []
+    if record and events:
+        dur = {}
+        for name, e0, e1 in events:
+            dur.setdefault(name, []).append(e0.elapsed_time(e1))
+        ops = 0.0
+        tsum = 0.0
+        for nd in mfma_nodes:
+            ms = sum(dur[nd.name]) / len(dur[nd.name])
+            o = 2.0 * node_macs(net, nd) * args.batch
+            C = net.shapes[nd.srcs[0]][2]
+            by = node_bytes(net, nd) * args.batch + nd.K * nd.R * nd.R * C + 4 * nd.K
+            ops += o
+            tsum += ms
+            per_layer.append(dict(layer=nd.name, us=round(ms * 1e3, 1), tops=round(o / ms / 1e9, 1),
+                                  gbs=round(by / ms / 1e6, 1)))
+        achieved = ops / (tsum * 1e-3) / 1e12
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "conv_mfma_traffic.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        roofline = dict(bound="mfma", kernel="conv_mfma_kernel (all instantiations, %d launches per step)" % len(mfma_nodes),
+                        achieved=round(achieved, 2), peak=INT8_MFMA_PEAK_TOPS, unit="TOP/s",
+                        frac=round(achieved / INT8_MFMA_PEAK_TOPS, 4), traffic=traffic,
+                        avg_launch_us=round(tsum / len(mfma_nodes) * 1e3, 2),
+                        ops_per_launch=ops / len(mfma_nodes), share_of_step=round(tsum / ms_per_step, 3))
+
+    cpu = None
+    if args.cpu_sample > 0:
+        cpu = cpu_baseline(net, min(args.cpu_sample, args.batch), min(args.calib, args.batch))
+
+    line = {
+        "metric": "int8 conv TOPS (2*MAC/s), whole quantized ResNet-50-shaped pass, b=%d" % args.batch,
+        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "configs[4]: ResNet-50-shaped int8 network, 224x224x3, batch %d, formats from a "
+                               "single-batch calibrate() on %d images" % (args.batch, args.calib),
+                   "global_batch": args.batch},
+        "images_per_s": round(imgs, 1),
+        "pct_int8_mfma_peak": round(100 * tops / INT8_MFMA_PEAK_TOPS, 2),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "mfma_layers": per_layer,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

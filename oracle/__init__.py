@@ -61,6 +61,8 @@ def lib():
         L.orc_conv_acc_at.argtypes = [_i8p, _i8p, _i32p] + [C.c_int] * 14
         L.orc_conv_q.restype = C.c_int
         L.orc_conv_q.argtypes = [_i8p, _i8p, _i32p, _i8p, _i32p] + [C.c_int] * 15
+        L.orc_requant_i32.restype = None
+        L.orc_requant_i32.argtypes = [_i32p, _i8p, C.c_size_t, C.c_int, C.c_int]
         L.orc_eltwise_q.restype = C.c_int
         L.orc_eltwise_q.argtypes = [_i8p, C.c_int, _i8p, C.c_int, _i8p, C.c_int, _i32p, C.c_size_t, C.c_int]
         L.orc_concat_q.restype = C.c_int
@@ -76,6 +78,8 @@ def lib():
         L.orc_frac_from_absmax_f32.argtypes = [C.c_float]
         L.orc_frac_from_absmax_i32.restype = C.c_int
         L.orc_frac_from_absmax_i32.argtypes = [C.c_int64, C.c_int]
+        L.orc_num_threads.restype = C.c_int
+        L.orc_num_threads.argtypes = []
         _lib = L
     return _lib
 
@@ -87,6 +91,10 @@ def _c(a: np.ndarray, dtype) -> np.ndarray:
 
 def _p(a, ptype):
     return None if a is None else a.ctypes.data_as(ptype)
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
 
 
 # ---- closed forms ---------------------------------------------------------- #
@@ -155,6 +163,14 @@ def conv_acc_at(x, w, b, stride, pad, groups, n, p, q, k) -> int:
     K, R, S, Cg = w.shape
     return int(lib().orc_conv_acc_at(_p(x, _i8p), _p(w, _i8p), _p(b, _i32p), N, H, W, Cc, K, R, S,
                                      stride, pad, groups, n, p, q, k))
+
+
+def requant_i32(acc, shift, relu=False):
+    """int32 accumulators -> int8 codes: ReLU, rounding shift, clamp."""
+    acc = _c(acc, np.int32)
+    y = np.empty(acc.shape, np.int8)
+    lib().orc_requant_i32(_p(acc, _i32p), _p(y, _i8p), acc.size, int(shift), int(bool(relu)))
+    return y
 
 
 def eltwise_q(a, f_a, b, f_b, f_y, relu=False, want_y=True, want_acc=False):

@@ -281,6 +281,17 @@ int orc_conv_q(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, in
     return overflow;
 }
 
+/* The last step of Eq. 6 on its own: y[i] = sat8(rne(relu ? max(acc[i],0) : acc[i], shift)).
+ * Lets calibration requantize accumulators it already holds instead of convolving again. */
+void orc_requant_i32(const int32_t *acc, int8_t *y, size_t n, int shift, int relu)
+{
+    for (size_t i = 0; i < n; i++) {
+        int64_t v = acc[i];
+        if (relu && v < 0) v = 0;
+        y[i] = (int8_t)orc_requant8(v, shift);
+    }
+}
+
 /* ------------------------------------------------------------------------- */
 /* Scaled addition (Eq. 10) and the joins built on it                          */
 /* ------------------------------------------------------------------------- */
@@ -436,3 +447,11 @@ int orc_frac_from_absmax_i32(int64_t m, int acc_frac)
     }
     return -32;
 }
+
+/* number of OpenMP threads the loops above use (reported next to oracle timings) */
+#ifdef _OPENMP
+#include <omp.h>
+int orc_num_threads(void) { return omp_get_max_threads(); }
+#else
+int orc_num_threads(void) { return 1; }
+#endif

@@ -65,17 +65,19 @@ def _forward(net, x, qz: Quantized, calibrating: bool):
                 qz.b[nd.name] = orc.quantize_i32(bf, f_in + f_w)
             f_w = qz.w_frac[nd.name]
             w, b = qz.w[nd.name], qz.b[nd.name]
-            if calibrating:
-                if nd.fixed_f_out is not None:
+            if calibrating and nd.fixed_f_out is None:
+                # threshold on the wide accumulator after the ReLU, then the one rescale of Eq. 6
+                _, acc = orc.conv_q(t[src], w, b, f_in, f_w, 0, nd.stride, nd.pad, nd.groups,
+                                    nd.relu, want_y=False, want_acc=True)
+                m = orc.absmax_i32(acc, relu=nd.relu)
+                qz.frac[nd.dst] = orc.frac_from_absmax_i32(m, f_in + f_w)
+                t[nd.dst] = orc.requant_i32(acc, f_in + f_w - qz.frac[nd.dst], nd.relu)
+                del acc
+            else:
+                if calibrating:
                     qz.frac[nd.dst] = nd.fixed_f_out
-                else:
-                    _, acc = orc.conv_q(t[src], w, b, f_in, f_w, 0, nd.stride, nd.pad, nd.groups,
-                                        nd.relu, want_y=False, want_acc=True)
-                    m = orc.absmax_i32(acc, relu=nd.relu)
-                    del acc
-                    qz.frac[nd.dst] = orc.frac_from_absmax_i32(m, f_in + f_w)
-            y, _ = orc.conv_q(t[src], w, b, f_in, f_w, qz.frac[nd.dst], nd.stride, nd.pad, nd.groups, nd.relu)
-            t[nd.dst] = y
+                t[nd.dst], _ = orc.conv_q(t[src], w, b, f_in, f_w, qz.frac[nd.dst], nd.stride, nd.pad,
+                                          nd.groups, nd.relu)
         elif nd.op == "eltwise":
             a, b = nd.srcs
             fa, fb = qz.frac[a], qz.frac[b]

@@ -1,0 +1,136 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, validates arguments before launching anything, and its pure host functions
+agree with the hand-worked closed forms."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "dfq.h")
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "closed_forms.txt")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1805_07941_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_1805_07941_amd import build
+        build.build(force=True)
+    binding.lib()
+    return binding
+
+
+def test_library_exports_every_declared_symbol(B):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(dfq_[a-z0-9_]+)\s*\(", text)))
+    assert len(declared) >= 19
+    L = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in dfq.h but not exported"
+    assert sorted(B.EXPORTS) == declared
+
+
+def test_status_strings(B):
+    assert B.status_string(B.OK) == "ok"
+    assert len({B.status_string(s) for s in range(6)}) == 6
+
+
+def test_closed_forms_match_golden(B):
+    fns = {"beta_max": B.beta_max, "mac_bits": B.mac_acc_bits, "mac_len": B.mac_max_len,
+           "add_bits": B.add_acc_bits, "add_len": B.add_max_len}
+    n = 0
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        kind, *vals = line.split()
+        *args, want = [int(v) for v in vals]
+        assert fns[kind](*args) == want, line
+        n += 1
+    assert n >= 20
+    assert B.beta_max(8, 9) == -1 and B.mac_acc_bits(0, 1, 0, 1, 0) == -1
+
+
+def test_format_from_thresholds(B):
+    f = B.fmt_from_absmax_f32
+    assert f(1.0) == 6 and f(1.99) == 5 and f(0.0) == 32 and f(127.0) == 0 and f(127.5) == -1 and f(1e30) == -32
+    for bad in (float("nan"), float("inf"), -1.0):
+        with pytest.raises(B.DfqError):
+            f(bad)
+    g = B.fmt_from_absmax_i32
+    assert g(0, 11) == 11 and g(127, 11) == 11 and g(128, 11) == 10 and g(254, 11) == 10 and g(255, 11) == 9
+    assert g(127 * 128, 11) == 4 and g(127 * 128 + 1, 11) == 3 and g(1, 40) == 32 and g(2 ** 31, -20) == -32
+    with pytest.raises(B.DfqError):
+        g(-1, 0)
+
+
+def _conv(B, **kw):
+    a = dict(x=1 << 20, w=2 << 20, b=None, y=3 << 20, acc=None, N=1, H=8, W=8, Cc=16, K=16, R=3, S=3, stride=1, pad=1,
+             groups=1, ldy=16, fi=4, fw=7, fo=4, bits=8)
+    a.update(kw)
+    fm = lambda f: B.Fmt(a["bits"], f)
+    return B.lib().dfq_conv_q(a["x"], a["w"], a["b"], a["y"], a["acc"], a["N"], a["H"], a["W"], a["Cc"], a["K"], a["R"],
+                              a["S"], a["stride"], a["pad"], a["groups"], a["ldy"], fm(a["fi"]), fm(a["fw"]), fm(a["fo"]),
+                              0, None)
+
+
+def test_conv_q_rejects_bad_arguments_before_launching(B):
+    # (pointers are fake non-null addresses: every case below must fail in validation)
+    assert _conv(B, x=None) == B.EINVAL
+    assert _conv(B, y=None) == B.EINVAL                       # neither y nor acc_out
+    assert _conv(B, N=-1) == B.EINVAL
+    assert _conv(B, Cc=0) == B.ESHAPE
+    assert _conv(B, groups=3) == B.ESHAPE                     # C % groups
+    assert _conv(B, K=20, groups=8, Cc=16, ldy=20) == B.ESHAPE  # K % groups
+    assert _conv(B, H=2, W=2, R=5, S=5, pad=0) == B.ESHAPE    # empty output
+    assert _conv(B, ldy=8) == B.ESHAPE                        # ldy < K
+    assert _conv(B, stride=0) == B.ESHAPE
+    assert _conv(B, bits=4) == B.EFMT
+    assert _conv(B, fi=33) == B.EFMT
+    assert _conv(B, Cc=16384, R=3, S=3) == B.EUNSUPPORTED     # 9*16384 products exceed Eq. 9's bound for 32 bits
+    assert _conv(B, y=1 << 20) == B.EINVAL                    # output aliases the input
+    assert _conv(B, N=0) == B.OK                              # empty batch: nothing to do
+
+
+def test_other_calls_reject_bad_arguments(B):
+    L = B.lib()
+    f = B.fmt
+    assert L.dfq_quantize(None, None, 0, f(4), None) == B.OK
+    assert L.dfq_quantize(None, 1 << 20, 16, f(4), None) == B.EINVAL
+    assert L.dfq_quantize(1 << 20, 2 << 20, 16, B.Fmt(16, 4), None) == B.EFMT
+    assert L.dfq_quantize(1 << 20, (1 << 20) + 8, 16, f(4), None) == B.EINVAL        # overlap
+    assert L.dfq_quantize_i32(1 << 20, 2 << 20, 16, 65, None) == B.EFMT
+    assert L.dfq_dequantize(1 << 20, 2 << 20, 16, f(-33), None) == B.EFMT
+    assert L.dfq_eltwise_q(1 << 20, f(30), 2 << 20, f(0), 3 << 20, f(0), None, 16, 0, None) == B.EFMT
+    assert L.dfq_eltwise_q(1 << 20, f(3), 2 << 20, f(3), None, f(3), None, 16, 0, None) == B.EINVAL
+    assert L.dfq_eltwise_q(1 << 20, f(3), 2 << 20, f(3), 1 << 20, f(3), None, 16, 0, None) == B.EINVAL  # in place
+    assert L.dfq_eltwise_q(None, f(3), None, f(3), None, f(3), None, 0, 0, None) == B.OK
+    assert L.dfq_pool_q(1 << 20, 2 << 20, 2, 1, 8, 8, 4, 3, 2, 1, f(4), f(4), None) == B.EINVAL          # bad mode
+    assert L.dfq_pool_q(1 << 20, 2 << 20, 0, 1, 8, 8, 4, 3, 2, 3, f(4), f(4), None) == B.ESHAPE          # pad >= k
+    assert L.dfq_pool_q(1 << 20, 2 << 20, 0, 1, 8, 8, 4, 65, 1, 0, f(4), f(4), None) == B.ESHAPE         # k > 64
+    assert L.dfq_pool_q(1 << 20, 2 << 20, 1, 1, 2, 2, 4, 3, 1, 0, f(4), f(4), None) == B.ESHAPE          # empty output
+    assert L.dfq_concat_q(0, None, None, None, None, f(4), 4, None) == B.EINVAL
+    ptrs = (C.c_void_p * 2)(1 << 20, 2 << 20)
+    Cs = (C.c_int * 2)(4, 0)
+    fs = (B.Fmt * 2)(f(3), f(4))
+    assert L.dfq_concat_q(2, ptrs, Cs, fs, 3 << 20, f(3), 4, None) == B.ESHAPE
+    assert L.dfq_absmax_f32(1 << 20, 4, None, None) == B.EINVAL
+    assert L.dfq_absmax_i32(None, 4, 0, 1 << 20, None) == B.EINVAL
+
+
+def test_kernel_selection(B):
+    s = B.conv_q_select
+    assert s(1, 56, 56, 64, 64, 3, 3, 1, 1, 1) == B.CONV_MFMA
+    assert s(1, 7, 7, 512, 2048, 1, 1, 1, 0, 1) == B.CONV_MFMA
+    assert s(1, 8, 8, 0, 4, 1, 1, 1, 0, 1) == B.CONV_AUTO          # invalid geometry
+    assert s(1, 8, 8, 20, 10, 2, 3, 1, 1, 5) == B.CONV_DIRECT      # small groups
+
+
+def test_binding_fails_loudly_without_the_library(B, monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libdfq.so")
+    with pytest.raises(RuntimeError):
+        B.lib()

@@ -1,0 +1,152 @@
+"""GPU parity on the five configurations: each side derives formats, integer weights and
+biases with its own implementation from the same seeded float tensors; every int8 tensor,
+every chosen format and the dequantized logits must agree exactly (tolerance 0).
+
+Full-size runs (the launch configuration the benchmark times) are checked on the images /
+output elements the oracle can afford: images are independent, so image i of a large GPU
+batch must equal the oracle's result for that image alone."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle as orc
+import oracle.net as onet
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def G():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1805_07941_amd import binding, net
+    binding.lib()
+    return binding, net
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def _derive_layer_oracle(L):
+    f_w = orc.frac_from_absmax_f32(orc.absmax_f32(L["w_float"]))
+    w = orc.quantize(L["w_float"], f_w)
+    b = orc.quantize_i32(L["b_float"], L["f_in"] + f_w)
+    return f_w, w, b
+
+
+def _derive_layer_gpu(B, L):
+    wf, bf = dev(L["w_float"]), dev(L["b_float"])
+    f_w = B.fmt_from_absmax_f32(float(host(B.absmax_f32(wf))[0]))
+    return f_w, B.quantize(wf, f_w), B.quantize_i32(bf, L["f_in"] + f_w)
+
+
+@pytest.mark.parametrize("i", range(5))
+def test_config1_layers_small_batch_every_byte(G, i):
+    B, _ = G
+    L = wl.config1_layer(i, batch=2)
+    f_w, w, b = _derive_layer_oracle(L)
+    gf_w, gw, gb = _derive_layer_gpu(B, L)
+    assert gf_w == f_w and np.array_equal(host(gw), w) and np.array_equal(host(gb), b)
+    _, acc = orc.conv_q(L["x"], w, b, L["f_in"], f_w, 0, 1, L["pad"], 1, True, want_y=False, want_acc=True)
+    f_out = orc.frac_from_absmax_i32(orc.absmax_i32(acc, relu=True), L["f_in"] + f_w)
+    y = orc.requant_i32(acc, L["f_in"] + f_w - f_out, True)
+    xd = dev(L["x"])
+    _, gacc = B.conv_q(xd, gw, gb, L["f_in"], gf_w, 0, 1, L["pad"], 1, True, want_y=False, want_acc=True)
+    gf_out = B.fmt_from_absmax_i32(B.absmax_i32_value(B.absmax_i32(gacc, relu=True)), L["f_in"] + gf_w)
+    assert gf_out == f_out
+    assert np.array_equal(host(gacc), acc)
+    for v in (B.CONV_AUTO, B.CONV_DIRECT):
+        gy, _ = B.conv_q(xd, gw, gb, L["f_in"], gf_w, gf_out, 1, L["pad"], 1, True, variant=v)
+        assert np.array_equal(host(gy), y)
+    assert np.abs(y).max() >= 64 and y.min() >= 0
+
+
+@pytest.mark.parametrize("batch", [32, 256])
+@pytest.mark.parametrize("i", range(5))
+def test_config1_layers_full_size_sampled(G, i, batch):
+    B, _ = G
+    L = wl.config1_layer(i, batch=batch)
+    f_w, w, b = _derive_layer_oracle(L)
+    x = L["x"]
+    N, H, W, C = x.shape
+    K = w.shape[0]
+    f_out = L["f_in"] + f_w - 7          # a fixed 7-bit rescale: full-size accumulators are not reduced on the CPU
+    gy, gacc = B.conv_q(dev(x), dev(w), dev(b), L["f_in"], f_w, f_out, 1, L["pad"], 1, True, want_acc=True)
+    gy, gacc = host(gy), host(gacc)
+    rng = np.random.default_rng(1000 + i)
+    pts = [(0, 0, 0, 0), (N - 1, H - 1, W - 1, K - 1), (N - 1, 0, W - 1, 0), (0, H - 1, 0, K - 1)]
+    pts += [tuple(int(v) for v in (rng.integers(N), rng.integers(H), rng.integers(W), rng.integers(K))) for _ in range(400)]
+    for (n, p, q, k) in pts:
+        a = orc.conv_acc_at(x, w, b, 1, L["pad"], 1, n, p, q, k)
+        assert int(gacc[n, p, q, k]) == a, (n, p, q, k)
+        assert int(gy[n, p, q, k]) == orc.requant8(max(a, 0), 7), (n, p, q, k)
+    # whole images against the oracle: the first and the last of the batch
+    for n in (0, N - 1):
+        y_ref, acc_ref = orc.conv_q(x[n:n + 1], w, b, L["f_in"], f_w, f_out, 1, L["pad"], 1, True, want_acc=True)
+        assert np.array_equal(gy[n:n + 1], y_ref) and np.array_equal(gacc[n:n + 1], acc_ref)
+    assert gy.min() >= 0 and gy.max() <= 127
+
+
+def _compare_calibration(net, qz_o, t_o, qz_g, t_g):
+    assert qz_g.frac == qz_o.frac
+    assert qz_g.w_frac == qz_o.w_frac
+    for name in qz_o.w:
+        assert np.array_equal(host(qz_g.w[name]), qz_o.w[name]), name
+        assert np.array_equal(host(qz_g.b[name]), qz_o.b[name]), name
+    for name in t_o:
+        assert np.array_equal(host(t_g[name]), t_o[name]), name
+
+
+def test_config2_inception_block(G):
+    B, gnet = G
+    net = wl.inception_block(batch=64)
+    x = net.input_int8()
+    calib = x[:4]
+    qz_o, t_o = onet.calibrate(net, calib)
+    qz_g, t_g = gnet.calibrate(net, dev(calib))
+    _compare_calibration(net, qz_o, t_o, qz_g, t_g)
+    # full batch on the GPU with those formats; three images checked against the oracle
+    plan = gnet.Plan(net, qz_g, 64)
+    plan.run(dev(x))
+    out = host(plan.buf[net.output_name])
+    assert out.shape == (64, 28, 28, 256)
+    for i in (0, 31, 63):
+        t = onet.infer(net, qz_o, x[i:i + 1])
+        for name in t:
+            if name != net.input_name:
+                assert np.array_equal(host(plan.buf[name][i:i + 1]), t[name]), (i, name)
+    assert int(np.abs(out).max()) > 0 and int(out.min()) >= 0      # every branch ends in a ReLU
+
+
+@pytest.mark.parametrize("which", ["mobilenet_v1", "resnet50"])
+def test_config3_and_4_networks(G, which):
+    B, gnet = G
+    batch = 128 if which == "mobilenet_v1" else 256
+    net = getattr(wl, which)(batch=batch)
+    x = net.input_float()
+    calib = x[:2]                          # a small single calibration batch keeps the oracle to seconds
+    qz_o, t_o = onet.calibrate(net, calib)
+    qz_g, t_g = gnet.calibrate(net, dev(calib))
+    _compare_calibration(net, qz_o, t_o, qz_g, t_g)
+    del t_g
+    plan = gnet.Plan(net, qz_g, batch)
+    logits = host(plan.run(dev(x)))
+    assert logits.shape == (batch, 1000) and np.isfinite(logits).all()
+    for i in (1, batch - 1):
+        t = onet.infer(net, qz_o, x[i:i + 1])
+        for name in t:
+            assert np.array_equal(host(plan.buf[name][i:i + 1]), t[name]), (i, name)
+        ref = onet.logits(net, qz_o, t)
+        assert np.array_equal(logits[i:i + 1], ref)        # absolute tolerance 0
+    # pooled buffers (the benchmark's memory plan) give the same logits
+    plan2 = gnet.Plan(net, qz_g, batch, keep_all=False)
+    assert np.array_equal(host(plan2.run(dev(x))), logits)
+    assert np.abs(logits).max() > 0

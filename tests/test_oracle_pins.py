@@ -479,3 +479,16 @@ def test_absmax():
     assert orc.absmax_i32(a) == 2 ** 31
     assert orc.absmax_i32(a, relu=True) == 5
     assert orc.absmax_i32(np.zeros(4, np.int32)) == 0
+
+
+def test_requant_i32_is_the_last_step_of_conv():
+    rng = np.random.default_rng(16)
+    x = rng.integers(-128, 128, (1, 6, 6, 8)).astype(np.int8)
+    w = rng.integers(-128, 128, (8, 3, 3, 8)).astype(np.int8)
+    b = rng.integers(-5000, 5000, 8).astype(np.int32)
+    for f_out, relu in [(4, 0), (2, 1), (12, 0), (-1, 1)]:
+        y, acc = orc.conv_q(x, w, b, 4, 7, f_out, 1, 1, 1, relu, want_acc=True)
+        assert np.array_equal(orc.requant_i32(acc, 11 - f_out, relu), y)
+        want = [_sat(_round_even(Fraction(max(int(v), 0) if relu else int(v)) / Fraction(2) ** (11 - f_out)))
+                for v in acc.ravel()]
+        assert y.ravel().tolist() == want
