@@ -19,13 +19,9 @@
 // such that those channels are 16 consecutive ones; the epilogue (bias, ReLU, rounding shift,
 // clamp: the rescale of Eq. 6 for power-of-two scales) then packs them into one 16-byte store.
 // The 32-bit sums never leave registers unless the caller asks for them (acc_out).
-#include "dfq_device.hpp"
-#include "dfq_host.hpp"
+#include "conv_epilogue.hpp"
 
 namespace dfq {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 
 namespace {
 
@@ -160,19 +156,23 @@ __global__ void __launch_bounds__(kThreads) conv_mfma_kernel(MfmaParams prm)
             if (!kHalfW || lrow < 32) ws[lds_slot(weight_row(lrow + 64 * i), piece)] = wreg[i];
     };
 
-    // ---- accumulators
-    v16i acc[CT][PT];
-#pragma unroll
-    for (int c = 0; c < CT; c++)
-#pragma unroll
-        for (int p = 0; p < PT; p++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[c][p][r] = 0;
-
     const int wp0 = (wave % WAVES_P) * WP;
     const int wc0 = (wave / WAVES_P) * WC;
     const int l32 = lane & 31, lh = lane >> 5;
     const int swz = (l32 >> 2) & 3;
+
+    // ---- accumulators start at the bias: register r of a lane belongs to channel kc + r
+    v16i acc[CT][PT];
+#pragma unroll
+    for (int c = 0; c < CT; c++) {
+        const int kc = k0 + wc0 + c * 32 + 16 * lh;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int bv = (a.b && kc + r < a.K) ? a.b[kc + r] : 0;
+#pragma unroll
+            for (int p = 0; p < PT; p++) acc[c][p][r] = bv;
+        }
+    }
 
     load_global();
     store_lds(0);
@@ -206,47 +206,16 @@ __global__ void __launch_bounds__(kThreads) conv_mfma_kernel(MfmaParams prm)
     }
 
     // ---- epilogue: lane holds, per (c, p) tile, channels kc..kc+15 of pixel m
-    const int s = a.shift;
+    Requant rq;
+    rq.init(a.shift, a.relu);
     const bool vec_ok = ((a.ldy & 15) == 0) && (((uintptr_t)a.y & 15) == 0);
 #pragma unroll
     for (int c = 0; c < CT; c++) {
         const int kc = k0 + wc0 + c * 32 + 16 * lh;
-        int bias[16];
-#pragma unroll
-        for (int r = 0; r < 16; r++) bias[r] = (a.b && kc + r < a.K) ? a.b[kc + r] : 0;
 #pragma unroll
         for (int p = 0; p < PT; p++) {
             const long long m = m0 + wp0 + p * 32 + l32;
-            if (m >= prm.M || kc >= a.K) continue;
-            int v[16];
-#pragma unroll
-            for (int r = 0; r < 16; r++) v[r] = acc[c][p][r] + bias[r];
-            const bool full = kc + 16 <= a.K;
-            if (a.acc_out) {
-                int32_t *dst = a.acc_out + (size_t)m * a.K + kc;
-                if (full && (a.K & 3) == 0) {
-#pragma unroll
-                    for (int r = 0; r < 16; r += 4) *(int4 *)(dst + r) = make_int4(v[r], v[r + 1], v[r + 2], v[r + 3]);
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; r++)
-                        if (kc + r < a.K) dst[r] = v[r];
-                }
-            }
-            if (a.y) {
-                int o[16];
-#pragma unroll
-                for (int r = 0; r < 16; r++) o[r] = requant8(a.relu ? max(v[r], 0) : v[r], s);
-                int8_t *dst = a.y + (size_t)m * a.ldy + kc;
-                if (full && vec_ok) {
-                    *(uint4 *)dst = make_uint4(pack4(o[0], o[1], o[2], o[3]), pack4(o[4], o[5], o[6], o[7]),
-                                               pack4(o[8], o[9], o[10], o[11]), pack4(o[12], o[13], o[14], o[15]));
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; r++)
-                        if (kc + r < a.K) dst[r] = (int8_t)o[r];
-                }
-            }
+            if (m < prm.M && kc < a.K) store_tile_lane(acc[c][p], a, rq, m, kc, vec_ok);
         }
     }
 }
