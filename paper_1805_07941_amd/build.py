@@ -18,7 +18,7 @@ LIB = os.path.join(HERE, "libdfq.so")
 OBJ = os.path.join(HERE, "_build")
 
 # -packed-fp32-ops off: packed FP32 forms are not to be generated on these machines.
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", INCLUDE, "-I", CSRC]
 

@@ -11,9 +11,10 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 // Per-launch constants of the requantization.  For 1 <= shift <= 23 the fast form is used:
-// the sum is first clamped to +-2^(shift+7) (anything beyond saturates anyway; with ReLU the
-// lower bound is 0), which makes  (v + 2^(shift-1) - 1 + bit_shift(v)) >> shift  overflow-free;
-// that expression is round-half-even of v / 2^shift for two's complement v.
+// the sum is first clamped to +-127 * 2^shift (anything beyond saturates to +-127 anyway; with
+// ReLU the lower bound is 0), which makes  (v + 2^(shift-1) - 1 + bit_shift(v)) >> shift
+// overflow-free and its result lie in [-127, 127] without a second clamp; that expression is
+// round-half-even of v / 2^shift for two's complement v.
 struct Requant {
     int shift;
     int relu;
@@ -26,63 +27,70 @@ struct Requant {
         shift = s;
         relu = r;
         fast = s >= 1 && s <= 23;
-        hi = fast ? (128 << s) : 0;
-        lo = fast ? (r ? 0 : -(128 << s)) : 0;
+        hi = fast ? (127 << s) : 0;
+        lo = fast ? (r ? 0 : -(127 << s)) : 0;
         bias_add = fast ? ((1 << (s - 1)) - 1) : 0;
     }
     __device__ __forceinline__ int fast_one(int v) const
     {
-        v = max(lo, min(v, hi));
-        int odd = (v >> shift) & 1;
-        int t = (v + bias_add + odd) >> shift;
-        return max(-127, min(t, 127));
+        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(v) : "v"(v), "s"(lo), "v"(hi));   // clamp to [lo, hi] (lo <= hi)
+        const int odd = (int)__builtin_amdgcn_ubfe((unsigned)v, (unsigned)shift, 1u);
+        return (v + bias_add + odd) >> shift;                      // v_add3_u32, v_ashrrev_i32
     }
     __device__ __forceinline__ int slow_one(int v) const { return requant8(relu ? max(v, 0) : v, shift); }
 };
 
+// four values in [-127, 127] -> one word of four int8
 __device__ __forceinline__ uint32_t pack4_clamped(int a, int b, int c, int d)
 {
-    // inputs already in [-127, 127]
-    uint32_t lo = (uint32_t)(a & 0xff) | ((uint32_t)(b & 0xff) << 8);
-    uint32_t hi = (uint32_t)(c & 0xff) | ((uint32_t)d << 8);
-    return lo | (hi << 16);
+    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);   // {a.b0, b.b0, 0, 0}
+    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);                                  // {lo.b0, lo.b1, hi.b0, hi.b1}
 }
 
 // One lane's share of a 32x32 accumulator tile: 16 consecutive output channels kc..kc+15 of
-// pixel m.  `v` already contains the bias.
-__device__ __forceinline__ void store_tile_lane(const v16i &v, const ConvArgs &a, const Requant &rq, long long m, int kc,
-                                                bool vec_ok)
+// pixel m.  `v` already contains the bias.  Hot form: whole 16-channel group inside K, aligned
+// output row, shift in the fast range, no accumulator dump.
+__device__ __forceinline__ void store_tile_lane_fast(const v16i &v, const ConvArgs &a, const Requant &rq, long long m, int kc)
 {
-    const bool full = kc + 16 <= a.K;
-    if (a.acc_out) {
-        int32_t *dst = a.acc_out + (size_t)m * a.K + kc;
-        if (full && (a.K & 3) == 0) {
+    int o[16];
 #pragma unroll
-            for (int r = 0; r < 16; r += 4) *(int4 *)(dst + r) = make_int4(v[r], v[r + 1], v[r + 2], v[r + 3]);
-        } else {
+    for (int r = 0; r < 16; r++) o[r] = rq.fast_one(v[r]);
+    *(uint4 *)(a.y + (size_t)m * a.ldy + kc) =
+        make_uint4(pack4_clamped(o[0], o[1], o[2], o[3]), pack4_clamped(o[4], o[5], o[6], o[7]),
+                   pack4_clamped(o[8], o[9], o[10], o[11]), pack4_clamped(o[12], o[13], o[14], o[15]));
+}
+
+// General form (ragged channel tail, unaligned rows, extreme shifts, accumulator dump).
+__device__ __forceinline__ void store_tile_lane_general(const v16i &v, const ConvArgs &a, int shift, int relu, long long m, int kc)
+{
 #pragma unroll
-            for (int r = 0; r < 16; r++)
-                if (kc + r < a.K) dst[r] = v[r];
+    for (int r = 0; r < 16; r++) {
+        if (kc + r < a.K) {
+            const int val = v[r];
+            if (a.acc_out) a.acc_out[(size_t)m * a.K + kc + r] = val;
+            if (a.y) a.y[(size_t)m * a.ldy + kc + r] = (int8_t)requant8(relu ? max(val, 0) : val, shift);
         }
     }
-    if (a.y) {
-        int o[16];
-        if (rq.fast) {
+}
+
+// true when every tile of a launch can take the hot form (k_end = end of the block's channel range)
+__device__ __forceinline__ bool epilogue_is_fast(const ConvArgs &a, const Requant &rq, int k_end)
+{
+    return rq.fast && !a.acc_out && a.y && ((a.ldy & 15) == 0) && (((uintptr_t)a.y & 15) == 0) && k_end <= a.K;
+}
+
+// Bias of channels kc..kc+15 (zeros where there is no bias or past K).
+__device__ __forceinline__ void load_bias16(const ConvArgs &a, int kc, int (&bv)[16])
+{
+    if (a.b && kc + 16 <= a.K && (((uintptr_t)a.b & 15) == 0) && (kc & 3) == 0) {
 #pragma unroll
-            for (int r = 0; r < 16; r++) o[r] = rq.fast_one(v[r]);
-        } else {
-#pragma unroll
-            for (int r = 0; r < 16; r++) o[r] = rq.slow_one(v[r]);
+        for (int r = 0; r < 16; r += 4) {
+            const int4 t = *(const int4 *)(a.b + kc + r);
+            bv[r] = t.x; bv[r + 1] = t.y; bv[r + 2] = t.z; bv[r + 3] = t.w;
         }
-        int8_t *dst = a.y + (size_t)m * a.ldy + kc;
-        if (full && vec_ok) {
-            *(uint4 *)dst = make_uint4(pack4_clamped(o[0], o[1], o[2], o[3]), pack4_clamped(o[4], o[5], o[6], o[7]),
-                                       pack4_clamped(o[8], o[9], o[10], o[11]), pack4_clamped(o[12], o[13], o[14], o[15]));
-        } else {
-#pragma unroll
-            for (int r = 0; r < 16; r++)
-                if (kc + r < a.K) dst[r] = (int8_t)o[r];
-        }
+    } else {
+        for (int r = 0; r < 16; r++) bv[r] = (a.b && kc + r < a.K) ? a.b[kc + r] : 0;
     }
 }
 

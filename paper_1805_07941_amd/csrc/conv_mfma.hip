@@ -7,153 +7,258 @@
 // that cover the same 16 values of j; taps outside the image are fetched as zeros (the code
 // of the value 0).  Nothing is materialized: the im2col matrix exists only as LDS tiles.
 //
-// Per workgroup (256 lanes = 4 wavefronts): a BP-pixel x BC-channel output tile; the j range
-// is walked in steps of 64 bytes through two LDS stages (one barrier per step; the global
-// loads of step i+1 are in flight while step i is multiplied).  LDS rows are 64 bytes with
-// the 16-byte piece index XOR-ed with bits of the row so that both the 128-bit stores and the
-// 128-bit operand reads spread over all banks without padding.
+// A workgroup (4 or 8 wavefronts) is persistent: it walks over BP-pixel x BC-channel output
+// tiles (tile numbers blockIdx, blockIdx + gridDim, ...).  The j range of each tile is walked
+// in steps of 64 bytes through a ring of LDS stages that is filled by direct global->LDS
+// buffer loads (no register staging) issued nstages-1 steps ahead - across tile boundaries, so
+// the first loads of the next tile are in flight while the current one is multiplied and
+// written out (HBM latency here is about four steps of matrix work).  A wavefront waits only
+// for the loads of the step it is about to multiply (its own counter of outstanding vector
+// memory operations, then one workgroup barrier per step).  Each wavefront-wide load fills 16
+// LDS rows of 64 bytes; which 16-byte piece of the step a lane fetches is XOR-ed with bits of
+// its row, so the 128-bit operand reads spread over all banks without padding.  Lanes whose
+// piece lies outside the image (padding), past the last pixel, past K or past R*S*C are given
+// an offset beyond the buffer's size: the hardware range check of buffer loads then writes
+// zeros into LDS for them, so padding costs no branch and no extra memory.
 //
 // Matrix instruction: v_mfma_i32_32x32x32_i8.  Output channels take the role of the rows of
 // the first operand and pixels the columns of the second, so a lane ends up holding, for one
 // pixel, accumulators of several channels.  Weight rows are placed in LDS in a permuted order
-// such that those channels are 16 consecutive ones; the epilogue (bias, ReLU, rounding shift,
-// clamp: the rescale of Eq. 6 for power-of-two scales) then packs them into one 16-byte store.
-// The 32-bit sums never leave registers unless the caller asks for them (acc_out).
+// such that those channels are 16 consecutive ones; the epilogue (ReLU, rounding shift, clamp:
+// the rescale of Eq. 6 for power-of-two scales; the bias is the accumulators' start value) then
+// packs them into one 16-byte store.  The 32-bit sums never leave registers unless the caller
+// asks for them (acc_out).
 #include "conv_epilogue.hpp"
+#include <cstdlib>
 
 namespace dfq {
 
 namespace {
 
-constexpr int kThreads = 256;
 constexpr int kStepBytes = 64;   // bytes of the reduction axis per LDS stage
 constexpr int kPieces = 4;       // 16-byte pieces per LDS row
+constexpr unsigned kOutOfRange = 0x80000000u;   // any offset with this bit set is past either buffer
 
 struct MfmaParams {
     ConvArgs a;
-    long long M;      // N*P*Q
+    int M;            // N*P*Q
     int Kgemm;        // R*S*C
     int nsteps;       // ceil(Kgemm / 64)
     int tiles_c;      // channel tiles
-    long long tiles_p;
+    int tiles;        // pixel tiles * channel tiles
+    int nstages;      // depth of the LDS ring
+    unsigned x_bytes, w_bytes;
+    FastDiv div_pq, div_q, div_tc;
 };
 
-// position of (row, piece) inside a tile of 64-byte rows, in 16-byte units
-__device__ __forceinline__ int lds_slot(int row, int piece) { return row * kPieces + (piece ^ ((row >> 2) & 3)); }
-
-// LDS row (MFMA row index) of weight row c within a 32-channel group, chosen so that the
-// accumulators a lane holds are those of 16 consecutive channels.
-__device__ __forceinline__ int weight_row(int c)
+// Buffer resource for raw byte addressing with range checking (stride 0: offsets >= bytes read as 0).
+__device__ __forceinline__ v4i make_rsrc(const void *base, unsigned bytes)
 {
-    int c32 = c & 31;
-    return (c & ~31) + 8 * ((c32 & 15) >> 2) + 4 * (c32 >> 4) + (c32 & 3);
+    const unsigned long long p = (unsigned long long)base;
+    v4i r;
+    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)(p & 0xffffffffu));
+    r.y = __builtin_amdgcn_readfirstlane((int)(unsigned)((p >> 32) & 0xffffu));
+    r.z = __builtin_amdgcn_readfirstlane((int)bytes);
+    r.w = __builtin_amdgcn_readfirstlane(0x00020000);   // 32-bit raw data format
+    return r;
 }
 
-template <int BP, int BC, int WAVES_P, int WAVES_C>
-__global__ void __launch_bounds__(kThreads) conv_mfma_kernel(MfmaParams prm)
+// Direct global -> LDS load of 16 bytes per lane: lane l's data lands at lds_base + 16*l; a lane
+// whose offset is outside the buffer gets zeros.  Issued through inline assembly so that the
+// compiler's own wait-count bookkeeping does not serialize it against later LDS reads;
+// completion is awaited explicitly with wait_loads<>().
+__device__ __forceinline__ void load_piece_to_lds(unsigned voffset, v4i rsrc, unsigned lds_base)
 {
-    static_assert(WAVES_P * WAVES_C == 4, "four wavefronts per workgroup");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" ::"v"(voffset), "s"(rsrc), "s"(lds_base)
+                 : "memory", "m0");
+}
+
+// wait until at most N vector-memory operations of this wavefront are outstanding
+template <int N>
+__device__ __forceinline__ void wait_loads()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+#ifdef DFQ_PROFILE_TS
+__device__ long long g_ts[64 * 8];
+__device__ long long g_wall[2048 * 4];
+#define DFQ_T(var) const long long var = clock64()
+#define DFQ_ACC(slot, t1, t0) ts_acc[slot] += (t1) - (t0)
+#else
+#define DFQ_T(var) do { } while (0)
+#define DFQ_ACC(slot, t1, t0) do { } while (0)
+#endif
+
+// wait until only the loads of the next `ahead` (0..4) steps, LP loads each, are outstanding
+template <int LP>
+__device__ __forceinline__ void wait_ahead(int ahead)
+{
+    switch (ahead) {
+        case 0: wait_loads<0>(); break;
+        case 1: wait_loads<LP>(); break;
+        case 2: wait_loads<2 * LP>(); break;
+        case 3: wait_loads<3 * LP>(); break;
+        default: wait_loads<4 * LP>(); break;
+    }
+}
+
+// UT ("uniform taps"): C is a multiple of 64, so a 64-byte step never straddles two taps and
+// the tap is the same for every lane; its bookkeeping then lives in scalar registers.
+template <int BP, int BC, int WAVES_P, int WAVES_C, bool UT>
+__global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(MfmaParams prm)
+{
+    constexpr int NW = WAVES_P * WAVES_C;                 // wavefronts per workgroup
+    static_assert(NW == 4 || NW == 8, "four or eight wavefronts per workgroup");
     constexpr int WP = BP / WAVES_P, WC = BC / WAVES_C;   // wavefront tile
     constexpr int PT = WP / 32, CT = WC / 32;             // 32x32 MFMA tiles per wavefront
-    constexpr int XI = BP / 64, WI = BC / 64 > 0 ? BC / 64 : 1;  // 16-byte loads per lane per step
-    constexpr bool kHalfW = BC < 64;                      // BC == 32: only half the lanes load weights
+    // 16-row chunks each wavefront loads per step; when there are fewer weight chunks than
+    // wavefronts only the first BC/16 wavefronts fetch one
+    constexpr int XS = BP / (16 * NW), WS = (BC + 16 * NW - 1) / (16 * NW);
+    constexpr bool kPartialW = BC < 16 * NW;
+    static_assert(XS * 16 * NW == BP && (kPartialW || WS * 16 * NW == BC) && BC % 16 == 0, "whole 16-row chunks");
+    constexpr int LPW = XS + WS;                          // loads per wavefront per step (with a weight chunk)
+    constexpr int STAGE_PIECES = (BP + BC) * kPieces;
     static_assert(WP % 32 == 0 && WC % 32 == 0, "tile shape");
+    static_assert(4 * LPW < 64, "outstanding loads must fit the 6-bit counter");
 
-    __shared__ uint4 lds[2][(BP + BC) * kPieces];
+    extern __shared__ uint4 lds[];   // nstages stages of (BP + BC) rows of 64 bytes, then BC bias words
 
     const ConvArgs &a = prm.a;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#ifdef DFQ_PROFILE_TS
+    if (tid == 0 && blockIdx.x < 2048) { g_wall[blockIdx.x * 4] = wall_clock64(); g_wall[blockIdx.x * 4 + 2] = __smid(); }
+#endif
+    const int nstages = prm.nstages;
+    const int nsteps = prm.nsteps;
+    const bool w_active = !kPartialW || wave < BC / 16;   // this wavefront fetches weight chunks
 
-    // ---- which tile: spread consecutive tile numbers over the 8 XCDs in contiguous runs, so
-    // that workgroups sharing input rows (neighbouring pixel tiles, all channel tiles of one
-    // pixel tile) meet in the same L2.
-    long long nblk = (long long)gridDim.x;
-    long long bid = blockIdx.x;
+    // ---- this workgroup's tiles: lb, lb + G, lb + 2G, ...  Workgroup ids are dealt round-robin
+    // to the 8 XCDs; renumbering them so that each XCD owns a contiguous run keeps tiles that
+    // share input rows (neighbouring pixel tiles, the channel tiles of one pixel tile) in one L2.
+    const int G = gridDim.x;
+    int lb = blockIdx.x;
     {
-        long long per = nblk / 8, rem = nblk % 8, xcd = bid % 8, idx = bid / 8;
-        bid = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+        const int per = G / 8, rem = G % 8, xcd = lb % 8, idx = lb / 8;
+        lb = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
     }
-    const int tile_c = (int)(bid % prm.tiles_c);
-    const long long tile_p = bid / prm.tiles_c;
-    const long long m0 = tile_p * BP;
-    const int k0 = tile_c * BC;
+    const int ntiles_mine = lb < prm.tiles ? (prm.tiles - lb + G - 1) / G : 0;
+    const int nitems = ntiles_mine * nsteps;
+    // G is a multiple of the number of channel tiles, so the channel tile never changes
+    const int k0 = (lb - fastdiv(lb, prm.div_tc) * prm.tiles_c) * BC;
 
-    // ---- per-lane load bookkeeping
-    const int piece = tid & 3;      // which 16 bytes of the 64-byte step
-    const int lrow = tid >> 2;      // 0..63
-    const int8_t *ximg[XI];
-    int ih0[XI], iw0[XI];
-    const long long PQ = (long long)a.P * a.Q;
+    const v4i xrsrc = make_rsrc(a.x, prm.x_bytes);
+    const v4i wrsrc = make_rsrc(a.w, prm.w_bytes);
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char *)(char *)&lds[0];
+    int *bias_lds = (int *)(lds + nstages * STAGE_PIECES);
+
+    // ---- bias of this channel tile into LDS (re-read at every tile start without touching the
+    // vector-memory counter that paces the load ring)
+    for (int i = tid; i < BC; i += NW * 64) bias_lds[i] = (a.b && k0 + i < a.K) ? a.b[k0 + i] : 0;
+
+    // ---- producer bookkeeping.  A wavefront-wide load covers rows 16*chunk .. 16*chunk+15 of
+    // the stage; lane l supplies row l/4, physical piece l%4, which holds logical piece
+    // (l%4) ^ ((row>>2)&3) - the same for every chunk of this lane.
+    const int lrow = lane >> 2;
+    const int lp = (lane & 3) ^ ((lane >> 4) & 3);
+    unsigned xoff[XS];               // byte offset of tap (0,0) of the lane's pixel, plus the lane's piece (mod 2^32)
+    uint32_t rinv[XS], cinv[XS];     // bit r / bit s set: that kernel row / column falls OUTSIDE the image
+    unsigned woff[WS];               // byte offset of the lane's weight row (+ piece), or out of range past K
 #pragma unroll
-    for (int i = 0; i < XI; i++) {
-        long long m = m0 + lrow + 64 * i;
-        if (m < prm.M) {
-            long long n = m / PQ;
-            int pq = (int)(m - n * PQ);
-            int p = pq / a.Q, q = pq - p * a.Q;
-            ximg[i] = a.x + (size_t)n * a.H * a.W * a.C;
-            ih0[i] = p * a.stride - a.pad;
-            iw0[i] = q * a.stride - a.pad;
+    for (int j = 0; j < WS; j++) {
+        // LDS row i = 8g + 4h + e of a 32-row group receives channel 16h + 4g + e: the matrix
+        // instruction then leaves 16 consecutive channels in each lane
+        const int rr = 16 * (wave + NW * j) + lrow;
+        const int i32 = rr & 31;
+        const int k = k0 + (rr & ~31) + 16 * ((i32 >> 2) & 1) + 4 * (i32 >> 3) + (i32 & 3);
+        woff[j] = k < a.K ? (unsigned)(k * prm.Kgemm) + (UT ? (unsigned)lp * 16u : 0u) : kOutOfRange;
+    }
+    // position on the reduction axis.  UT: scalar tap (sr, ss), scalar channel base scb, the lane's
+    // piece is already folded into xoff / woff.  Otherwise per lane: byte kb = step*64 + lp*16
+    // belongs to tap (tr, ts), channel tc.
+    int sr = 0, ss = 0, scb = 0, skb = 0;
+    int kb = 0, tr = 0, ts = 0, tc = 0;
+    int kb0 = lp * 16, tr0 = 0, ts0 = 0, tc0 = 0;
+    if (!UT) {
+        const int tap = kb0 / a.C;
+        tc0 = kb0 - tap * a.C;
+        tr0 = tap / a.S;
+        ts0 = tap - tr0 * a.S;
+    }
+    int p_tile = lb, p_step = 0;     // tile and step the producer will fetch next
+
+    auto begin_tile = [&]() {
+        const int m0 = fastdiv(p_tile, prm.div_tc) * BP;
+#pragma unroll
+        for (int j = 0; j < XS; j++) {
+            const int m = m0 + 16 * (wave + NW * j) + lrow;
+            const bool live = m < prm.M;
+            const int mi = live ? m : 0;
+            const int n = fastdiv(mi, prm.div_pq);
+            const int pq = mi - n * (a.P * a.Q);
+            const int p = fastdiv(pq, prm.div_q), q = pq - p * a.Q;
+            const int ih0 = p * a.stride - a.pad, iw0 = q * a.stride - a.pad;
+            xoff[j] = (unsigned)(((n * a.H + ih0) * a.W + iw0) * a.C) + (UT ? (unsigned)lp * 16u : 0u);
+            // kernel rows r with 0 <= ih0 + r < H are r in [rlo, rhi); likewise columns
+            const int rlo = max(0, -ih0), rhi = min(a.R, a.H - ih0);
+            const int clo = max(0, -iw0), chi = min(a.S, a.W - iw0);
+            rinv[j] = (live && rhi > rlo) ? ~(((1u << (rhi - rlo)) - 1u) << rlo) : 0xffffffffu;
+            cinv[j] = (chi > clo) ? ~(((1u << (chi - clo)) - 1u) << clo) : 0xffffffffu;
+        }
+        sr = 0; ss = 0; scb = 0; skb = 0;
+        kb = kb0; tr = tr0; ts = ts0; tc = tc0;
+    };
+
+    auto issue = [&](int stage) {
+        if (p_step == 0) begin_tile();
+        const unsigned sbase = lds_base + (unsigned)stage * (STAGE_PIECES * 16) + (unsigned)wave * 1024u;
+        if (UT) {
+            const unsigned soff = (unsigned)((sr * a.W + ss) * a.C + scb);
+#pragma unroll
+            for (int j = 0; j < XS; j++) {
+                const unsigned bad = (unsigned)(__builtin_amdgcn_sbfe((int)rinv[j], sr, 1) | __builtin_amdgcn_sbfe((int)cinv[j], ss, 1));
+                load_piece_to_lds((xoff[j] + soff) | bad, xrsrc, sbase + (unsigned)j * (NW * 1024u));
+            }
+            if (w_active) {
+#pragma unroll
+                for (int j = 0; j < WS; j++)
+                    load_piece_to_lds(woff[j] + (unsigned)skb, wrsrc, sbase + (unsigned)(BP * 64) + (unsigned)j * (NW * 1024u));
+            }
+            skb += kStepBytes;
+            scb += kStepBytes;
+            if (scb == a.C) {
+                scb = 0;
+                if (++ss == a.S) { ss = 0; ++sr; }
+            }
         } else {
-            ximg[i] = a.x;
-            ih0[i] = -(1 << 28);    // never inside the image
-            iw0[i] = 0;
+            const unsigned toff = (unsigned)((tr * a.W + ts) * a.C + tc);
+            const unsigned past = tr >= a.R ? 0xffffffffu : 0u;   // kb >= Kgemm
+            const unsigned rsh = (unsigned)tr & 31u, csh = (unsigned)ts & 31u;
+#pragma unroll
+            for (int j = 0; j < XS; j++) {
+                const unsigned bad = past | (0u - (((rinv[j] >> rsh) | (cinv[j] >> csh)) & 1u));
+                load_piece_to_lds((xoff[j] + toff) | bad, xrsrc, sbase + (unsigned)j * (NW * 1024u));
+            }
+            if (w_active) {
+#pragma unroll
+                for (int j = 0; j < WS; j++)
+                    load_piece_to_lds((woff[j] + (unsigned)kb) | past, wrsrc, sbase + (unsigned)(BP * 64) + (unsigned)j * (NW * 1024u));
+            }
+            kb += kStepBytes;
+            tc += kStepBytes;
+            for (int i = 0; i < kStepBytes / 16; i++) {   // a step crosses at most four taps (C >= 16)
+                const bool wrapc = tc >= a.C;
+                tc -= wrapc ? a.C : 0;
+                ts += wrapc ? 1 : 0;
+                const bool wraps = ts == a.S;
+                ts = wraps ? 0 : ts;
+                tr += wraps ? 1 : 0;
+            }
         }
-    }
-    const int8_t *wrow[WI];
-    bool wok[WI];
-#pragma unroll
-    for (int i = 0; i < WI; i++) {
-        int k = k0 + lrow + 64 * i;
-        wok[i] = k < a.K && (!kHalfW || lrow < 32);
-        wrow[i] = a.w + (size_t)(wok[i] ? k : 0) * prm.Kgemm;
-    }
-    // reduction-axis position of this lane's piece: byte kb = step*64 + piece*16 = (tap r,s; channel c)
-    int kb = piece * 16;
-    int tr, ts, tc;
-    {
-        int tap = kb / a.C;
-        tc = kb - tap * a.C;
-        tr = tap / a.S;
-        ts = tap - tr * a.S;
-    }
-
-    uint4 xreg[XI], wreg[WI];
-    auto load_global = [&]() {
-        const bool kin = tr < a.R;   // kb < Kgemm
-#pragma unroll
-        for (int i = 0; i < XI; i++) {
-            int ih = ih0[i] + tr, iw = iw0[i] + ts;
-            bool ok = kin && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (ok) v = *(const uint4 *)(ximg[i] + ((size_t)ih * a.W + iw) * a.C + tc);
-            xreg[i] = v;
-        }
-#pragma unroll
-        for (int i = 0; i < WI; i++) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (wok[i] && kin) v = *(const uint4 *)(wrow[i] + kb);
-            wreg[i] = v;
-        }
-    };
-    auto advance = [&]() {
-        kb += kStepBytes;
-        tc += kStepBytes;
-        while (tc >= a.C) {
-            tc -= a.C;
-            if (++ts == a.S) { ts = 0; ++tr; }
-        }
-    };
-    auto store_lds = [&](int buf) {
-        uint4 *xs = lds[buf];
-        uint4 *ws = xs + BP * kPieces;
-#pragma unroll
-        for (int i = 0; i < XI; i++) xs[lds_slot(lrow + 64 * i, piece)] = xreg[i];
-#pragma unroll
-        for (int i = 0; i < WI; i++)
-            if (!kHalfW || lrow < 32) ws[lds_slot(weight_row(lrow + 64 * i), piece)] = wreg[i];
+        if (++p_step == nsteps) { p_step = 0; p_tile += G; }
     };
 
     const int wp0 = (wave % WAVES_P) * WP;
@@ -161,78 +266,165 @@ __global__ void __launch_bounds__(kThreads) conv_mfma_kernel(MfmaParams prm)
     const int l32 = lane & 31, lh = lane >> 5;
     const int swz = (l32 >> 2) & 3;
 
-    // ---- accumulators start at the bias: register r of a lane belongs to channel kc + r
+    for (int i = 0; i < nstages - 1; i++)
+        if (i < nitems) issue(i);
+
+    Requant rq;
+    rq.init(a.shift, a.relu);
+    const bool fast = epilogue_is_fast(a, rq, k0 + BC);
+    __syncthreads();   // bias_lds complete
+
+    // accumulators start at the bias: register r of a lane belongs to channel kc + r
     v16i acc[CT][PT];
+    auto reset_acc = [&]() {
 #pragma unroll
-    for (int c = 0; c < CT; c++) {
-        const int kc = k0 + wc0 + c * 32 + 16 * lh;
+        for (int c = 0; c < CT; c++) {
+            const int4 *bp = (const int4 *)(bias_lds + wc0 + c * 32 + 16 * lh);
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int bv = (a.b && kc + r < a.K) ? a.b[kc + r] : 0;
+            for (int r4 = 0; r4 < 4; r4++) {
+                const int4 bv = bp[r4];
 #pragma unroll
-            for (int p = 0; p < PT; p++) acc[c][p][r] = bv;
+                for (int p = 0; p < PT; p++) {
+                    acc[c][p][4 * r4 + 0] = bv.x;
+                    acc[c][p][4 * r4 + 1] = bv.y;
+                    acc[c][p][4 * r4 + 2] = bv.z;
+                    acc[c][p][4 * r4 + 3] = bv.w;
+                }
+            }
         }
-    }
+    };
+    reset_acc();
 
-    load_global();
-    store_lds(0);
-    __syncthreads();
+#ifdef DFQ_PROFILE_TS
+    long long ts_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const long long t_begin = clock64();
+#endif
+    int stage = 0, c_step = 0, c_tile = lb;
+    for (int it = 0; it < nitems; it++) {
+        DFQ_T(t0);
+        // loads of the next `ahead` items may stay in flight
+        const int ahead = min(nstages - 2, nitems - 1 - it);
+        if (w_active) wait_ahead<LPW>(ahead);
+        else wait_ahead<XS>(ahead);
+        DFQ_T(t1);
+        __syncthreads();
+        DFQ_T(t2);
 
-    for (int step = 0; step < prm.nsteps; step++) {
-        const int buf = step & 1;
-        const bool more = step + 1 < prm.nsteps;
-        if (more) {
-            advance();
-            load_global();
-        }
-        const v4i *xs = (const v4i *)lds[buf];
+        const v4i *xs = (const v4i *)lds + stage * STAGE_PIECES;
         const v4i *ws = xs + BP * kPieces;
+        // operands of both halves of the step are requested up front: the second half arrives
+        // while the first is being multiplied
+        v4i wf[2][CT], xf[2][PT];
 #pragma unroll
         for (int kk = 0; kk < 2; kk++) {
             const int g = (kk * 2 + lh) ^ swz;
-            v4i wf[CT], xf[PT];
 #pragma unroll
-            for (int c = 0; c < CT; c++) wf[c] = ws[(wc0 + c * 32 + l32) * kPieces + g];
+            for (int c = 0; c < CT; c++) wf[kk][c] = ws[(wc0 + c * 32 + l32) * kPieces + g];
 #pragma unroll
-            for (int p = 0; p < PT; p++) xf[p] = xs[(wp0 + p * 32 + l32) * kPieces + g];
+            for (int p = 0; p < PT; p++) xf[kk][p] = xs[(wp0 + p * 32 + l32) * kPieces + g];
+        }
+#ifdef DFQ_PROFILE_TS
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#endif
+        DFQ_T(t3);
+#pragma unroll
+        for (int kk = 0; kk < 2; kk++) {
 #pragma unroll
             for (int c = 0; c < CT; c++)
 #pragma unroll
                 for (int p = 0; p < PT; p++)
-                    acc[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[c], xf[p], acc[c][p], 0, 0, 0);
+                    acc[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[kk][c], xf[kk][p], acc[c][p], 0, 0, 0);
+            // the refill of the stage consumed in the previous item is issued between the two
+            // halves, so its address arithmetic runs in the shadow of the matrix instructions
+            if (kk == 0 && it + nstages - 1 < nitems) issue(stage == 0 ? nstages - 1 : stage - 1);
         }
-        if (more) store_lds(buf ^ 1);
-        __syncthreads();
-    }
+        stage = stage + 1 == nstages ? 0 : stage + 1;
+        DFQ_T(t4);
+        DFQ_ACC(0, t1, t0); DFQ_ACC(1, t2, t1); DFQ_ACC(2, t3, t2); DFQ_ACC(3, t4, t3);
 
-    // ---- epilogue: lane holds, per (c, p) tile, channels kc..kc+15 of pixel m
-    Requant rq;
-    rq.init(a.shift, a.relu);
-    const bool vec_ok = ((a.ldy & 15) == 0) && (((uintptr_t)a.y & 15) == 0);
+        if (++c_step == nsteps) {
+            // ---- epilogue of this tile: lane holds, per (c, p), channels kc..kc+15 of pixel m
+            const int m0 = fastdiv(c_tile, prm.div_tc) * BP;
 #pragma unroll
-    for (int c = 0; c < CT; c++) {
-        const int kc = k0 + wc0 + c * 32 + 16 * lh;
+            for (int c = 0; c < CT; c++) {
+                const int kc = k0 + wc0 + c * 32 + 16 * lh;
 #pragma unroll
-        for (int p = 0; p < PT; p++) {
-            const long long m = m0 + wp0 + p * 32 + l32;
-            if (m < prm.M && kc < a.K) store_tile_lane(acc[c][p], a, rq, m, kc, vec_ok);
+                for (int p = 0; p < PT; p++) {
+                    const int m = m0 + wp0 + p * 32 + l32;
+                    if (m < prm.M) {
+                        if (fast) store_tile_lane_fast(acc[c][p], a, rq, m, kc);
+                        else if (kc < a.K) store_tile_lane_general(acc[c][p], a, a.shift, a.relu, m, kc);
+                    }
+                }
+            }
+            reset_acc();
+            c_step = 0;
+            c_tile += G;
+            DFQ_T(t5);
+            DFQ_ACC(4, t5, t4);
         }
     }
+#ifdef DFQ_PROFILE_TS
+    __builtin_amdgcn_s_waitcnt(0);
+    if (tid == 0 && blockIdx.x < 2048) g_wall[blockIdx.x * 4 + 1] = wall_clock64();
+    if ((tid & 63) == 0 && blockIdx.x < 8) {
+        ts_acc[5] = clock64() - t_begin;
+        ts_acc[6] = nitems;
+        for (int i = 0; i < 8; i++) g_ts[(blockIdx.x * NW + wave) % 64 * 8 + i] = ts_acc[i];
+    }
+#endif
 }
 
-template <int BP, int BC, int WAVES_P, int WAVES_C>
+constexpr int kNumCU = 256;
+constexpr int kLdsBytes = 160 * 1024;
+
+// PER_CU: workgroups of this shape that fit one compute unit (registers), 1 or 2
+template <int BP, int BC, int WAVES_P, int WAVES_C, int PER_CU>
 hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
 {
     MfmaParams prm;
     prm.a = a;
-    prm.M = (long long)a.N * a.P * a.Q;
+    const long long M = (long long)a.N * a.P * a.Q;
+    prm.M = (int)M;
     prm.Kgemm = a.R * a.S * a.C;
     prm.nsteps = (prm.Kgemm + kStepBytes - 1) / kStepBytes;
     prm.tiles_c = (a.K + BC - 1) / BC;
-    prm.tiles_p = (prm.M + BP - 1) / BP;
-    long long blocks = prm.tiles_p * prm.tiles_c;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C><<<(unsigned)blocks, kThreads, 0, st>>>(prm);
+    const long long tiles = ((M + BP - 1) / BP) * prm.tiles_c;
+    if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    prm.tiles = (int)tiles;
+    prm.x_bytes = (unsigned)((long long)a.N * a.H * a.W * a.C);
+    prm.w_bytes = (unsigned)((long long)a.K * prm.Kgemm);
+    prm.div_pq = make_fastdiv(a.P * a.Q);
+    prm.div_q = make_fastdiv(a.Q);
+    prm.div_tc = make_fastdiv(prm.tiles_c);
+
+    // Two workgroups per compute unit when there are enough tiles (one multiplies while the
+    // other writes out), each with as many ring stages as half the LDS holds; otherwise one
+    // workgroup per compute unit with a deeper ring.
+    constexpr int stage_bytes = (BP + BC) * kStepBytes;
+    constexpr int bias_bytes = BC * 4;
+    const int per_cu = (PER_CU == 2 && tiles > kNumCU) ? 2 : 1;
+    int grid = per_cu * kNumCU;
+    if (grid > prm.tiles) grid = prm.tiles;
+    grid = grid / prm.tiles_c * prm.tiles_c;            // the channel tile of a workgroup must not change
+    if (grid < prm.tiles_c) grid = prm.tiles_c;
+    int nstages = (kLdsBytes / per_cu - bias_bytes - 1024) / stage_bytes;
+    if (nstages > 6) nstages = 6;
+    const int items = prm.nsteps * ((prm.tiles + grid - 1) / grid);
+    if (nstages > items) nstages = items;
+    if (nstages < 2) nstages = 2;
+    prm.nstages = nstages;
+    const size_t lds_bytes = (size_t)nstages * stage_bytes + bias_bytes;
+
+    const bool ut = a.C % kStepBytes == 0;
+    auto kernel = ut ? conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, true> : conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, false>;
+    static hipError_t attr_ut = hipFuncSetAttribute((const void *)conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, true>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    static hipError_t attr_gen = hipFuncSetAttribute((const void *)conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, false>,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (attr_ut != hipSuccess) return attr_ut;
+    if (attr_gen != hipSuccess) return attr_gen;
+    kernel<<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
     return hipGetLastError();
 }
 
@@ -242,6 +434,11 @@ bool conv_mfma_supports(const ConvArgs &a)
 {
     if (a.groups != 1) return false;
     if (a.C % 16) return false;
+    if (a.R > 31 || a.S > 31) return false;     // per-pixel row / column validity masks are 32 bits wide
+    // 32-bit byte offsets with the top bit reserved for "out of range"
+    if ((long long)a.N * a.H * a.W * a.C >= (1LL << 31)) return false;
+    if ((long long)a.K * a.R * a.S * a.C >= (1LL << 31)) return false;
+    if ((long long)a.N * a.P * a.Q >= (1LL << 31) - 512) return false;
     if (((uintptr_t)a.x & 15) || ((uintptr_t)a.w & 15)) return false;
     if (a.acc_out && ((uintptr_t)a.acc_out & 15)) return false;
     return true;
@@ -249,9 +446,16 @@ bool conv_mfma_supports(const ConvArgs &a)
 
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st)
 {
-    if (a.K <= 32) return launch_cfg<256, 32, 4, 1>(a, st);
-    if (a.K <= 64) return launch_cfg<256, 64, 4, 1>(a, st);
-    return launch_cfg<128, 128, 2, 2>(a, st);
+    const char *e = getenv("DFQ_CFG");
+    const int cfg = e ? atoi(e) : 0;
+    if (a.K <= 64) {
+        if (cfg == 1) return launch_cfg<512, 64, 8, 1, 2>(a, st);
+        return launch_cfg<256, 64, 4, 1, 2>(a, st);
+    }
+    if (cfg == 1) return launch_cfg<256, 256, 2, 4, 1>(a, st);   // wave 128 x 64
+    if (cfg == 2) return launch_cfg<512, 128, 4, 2, 1>(a, st);   // wave 128 x 64
+    if (cfg == 3) return launch_cfg<256, 128, 2, 2, 2>(a, st);   // 4 waves, 128 x 64
+    return launch_cfg<256, 128, 4, 2, 2>(a, st);
 }
 
 }  // namespace dfq

@@ -66,17 +66,12 @@ __global__ void __launch_bounds__(kThreads) conv_smallc_kernel(SmallCParams prm)
 
     Requant rq;
     rq.init(a.shift, a.relu);
-    const bool vec_ok = ((a.ldy & 15) == 0) && (((uintptr_t)a.y & 15) == 0);
+    const bool fast = epilogue_is_fast(a, rq, k0 + BC);
     const v4i *wl = (const v4i *)wlds;
 
     int bias[CT][16];
 #pragma unroll
-    for (int c = 0; c < CT; c++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-            int k = k0 + c * 32 + 16 * lh + r;
-            bias[c][r] = (a.b && k < a.K) ? a.b[k] : 0;
-        }
+    for (int c = 0; c < CT; c++) load_bias16(a, k0 + c * 32 + 16 * lh, bias[c]);
 
     for (int tile = blockIdx.x; tile < prm.tiles_p; tile += gridDim.x) {
         const int mbase = tile * kTilePixels + wave * 64;
@@ -152,7 +147,10 @@ __global__ void __launch_bounds__(kThreads) conv_smallc_kernel(SmallCParams prm)
 #pragma unroll
             for (int p = 0; p < 2; p++) {
                 const int m = mbase + p * 32 + l32;
-                if (m < prm.M && kc < a.K) store_tile_lane(acc[c][p], a, rq, m, kc, vec_ok);
+                if (m < prm.M) {
+                    if (fast) store_tile_lane_fast(acc[c][p], a, rq, m, kc);
+                    else if (kc < a.K) store_tile_lane_general(acc[c][p], a, a.shift, a.relu, m, kc);
+                }
             }
         }
     }
