@@ -19,6 +19,8 @@ from typing import Dict, Optional
 
 import torch
 
+import ctypes as C
+
 from . import binding as B
 
 
@@ -122,6 +124,7 @@ class Plan:
             self._assign_pooled()
         P, Q, K = net.shapes[net.output_name]
         self.logits = torch.empty((batch, P * Q * K), dtype=torch.float32, device=device)
+        self._calls, self._calls_key, self._graph, self._keep = None, None, None, None
 
     def _assign_pooled(self):
         """Reuses buffers whose tensor is dead (sized in bytes), to keep the footprint small."""
@@ -143,28 +146,79 @@ class Plan:
                 if last.get(s) == idx and s != net.input_name and s != net.output_name:
                     free.append(owner[s])
 
-    def run(self, x: torch.Tensor, stream=None) -> torch.Tensor:
-        """x: float32 images [batch,H,W,C] (or int8 codes).  Returns the float logits buffer."""
+    # ---- execution -------------------------------------------------------------------- #
+    def _build_calls(self, x: torch.Tensor):
+        """The pass as a list of (C function, argument tuple) with every argument already
+        marshalled except the stream, which is appended at call time."""
+        L = B.lib()
         net, qz, t = self.net, self.qz, self.buf
+        calls = []
+        keep = []          # ctypes arrays referenced by pointer must outlive the calls
+        f = B.fmt
         if net.input_is_int8:
             t[net.input_name] = x
         else:
-            B.quantize(x, qz.frac[net.input_name], out=t[net.input_name], stream=stream)
+            calls.append((L.dfq_quantize, (x.data_ptr(), t[net.input_name].data_ptr(), x.numel(), f(qz.frac[net.input_name]))))
         for nd in net.nodes:
             if nd.op == "conv":
                 src = nd.srcs[0]
-                B.conv_q(t[src], qz.w[nd.name], qz.b[nd.name], qz.frac[src], qz.w_frac[nd.name], qz.frac[nd.dst],
-                         nd.stride, nd.pad, nd.groups, nd.relu, out=t[nd.dst], stream=stream)
+                N, H, W, Cc = t[src].shape
+                K = nd.K
+                calls.append((L.dfq_conv_q, (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(),
+                                             t[nd.dst].data_ptr(), None, N, H, W, Cc, K, nd.R, nd.R, nd.stride, nd.pad,
+                                             nd.groups, K, f(qz.frac[src]), f(qz.w_frac[nd.name]), f(qz.frac[nd.dst]),
+                                             int(nd.relu))))
             elif nd.op == "eltwise":
                 a, b2 = nd.srcs
-                B.eltwise_q(t[a], qz.frac[a], t[b2], qz.frac[b2], qz.frac[nd.dst], nd.relu, out=t[nd.dst], stream=stream)
+                calls.append((L.dfq_eltwise_q, (t[a].data_ptr(), f(qz.frac[a]), t[b2].data_ptr(), f(qz.frac[b2]),
+                                                t[nd.dst].data_ptr(), f(qz.frac[nd.dst]), None, t[a].numel(), int(nd.relu))))
             elif nd.op == "concat":
-                B.concat_q([t[s] for s in nd.srcs], [qz.frac[s] for s in nd.srcs], qz.frac[nd.dst], out=t[nd.dst],
-                           stream=stream)
+                nb = len(nd.srcs)
+                ptrs = (C.c_void_p * nb)(*[t[s].data_ptr() for s in nd.srcs])
+                Cs = (C.c_int * nb)(*[int(t[s].shape[-1]) for s in nd.srcs])
+                fs = (B.Fmt * nb)(*[f(qz.frac[s]) for s in nd.srcs])
+                keep.append((ptrs, Cs, fs))
+                pixels = t[nd.dst].numel() // t[nd.dst].shape[-1]
+                calls.append((L.dfq_concat_q, (nb, ptrs, Cs, fs, t[nd.dst].data_ptr(), f(qz.frac[nd.dst]), pixels)))
             else:
                 src = nd.srcs[0]
-                B.pool_q(t[src], "max" if nd.op == "maxpool" else "avg", nd.R, nd.stride, nd.pad, qz.frac[src],
-                         qz.frac[nd.dst], out=t[nd.dst], stream=stream)
+                N, H, W, Cc = t[src].shape
+                mode = B.POOL_MAX if nd.op == "maxpool" else B.POOL_AVG
+                calls.append((L.dfq_pool_q, (t[src].data_ptr(), t[nd.dst].data_ptr(), mode, N, H, W, Cc, nd.R, nd.stride,
+                                             nd.pad, f(qz.frac[src]), f(qz.frac[nd.dst]))))
         out = t[net.output_name]
-        B.dequantize(out.view(self.batch, -1), qz.frac[net.output_name], out=self.logits, stream=stream)
+        calls.append((L.dfq_dequantize, (out.data_ptr(), self.logits.data_ptr(), out.numel(), f(qz.frac[net.output_name]))))
+        self._keep = keep
+        return calls
+
+    def _calls_for(self, x: torch.Tensor):
+        key = (x.data_ptr(), tuple(x.shape))
+        if self._calls_key != key:
+            self._calls = self._build_calls(x)
+            self._calls_key = key
+            self._graph = None
+        return self._calls
+
+    def run(self, x: torch.Tensor, stream=None) -> torch.Tensor:
+        """One pass: x float32 images [batch,H,W,C] (or int8 codes).  Enqueues every library call
+        on the stream and returns the float logits buffer (no synchronization)."""
+        st = B._stream(stream)
+        for fn, args in self._calls_for(x):
+            rc = fn(*args, st)
+            if rc != B.OK:
+                raise B.DfqError(rc, fn.__name__)
+        return self.logits
+
+    def run_graph(self, x: torch.Tensor) -> torch.Tensor:
+        """Same pass replayed from a HIP graph captured on first use (the call sequence is fixed and
+        allocation-free, so it is capturable); removes the per-call launch cost."""
+        self._calls_for(x)
+        if self._graph is None:
+            self.run(x)                      # first use outside capture (one-time kernel attribute set-up)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                self.run(x)
+            self._graph = g
+        self._graph.replay()
         return self.logits

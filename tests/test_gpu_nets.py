@@ -150,3 +150,26 @@ def test_config3_and_4_networks(G, which):
     plan2 = gnet.Plan(net, qz_g, batch, keep_all=False)
     assert np.array_equal(host(plan2.run(dev(x))), logits)
     assert np.abs(logits).max() > 0
+
+
+def test_graph_replay_matches_eager(G):
+    """The captured call sequence must give the eager result on every replay, with eager work
+    and synchronizations in between."""
+    B, gnet = G
+    net = wl.resnet50(batch=8, hw=64, classes=100)
+    x = dev(net.input_float())
+    qz, _ = gnet.calibrate(net, x[:4].contiguous(), keep_tensors=False)
+    plan = gnet.Plan(net, qz, 8, keep_all=False)
+    eager = host(plan.run(x)).copy()
+    torch.cuda.synchronize()
+    for i in range(4):
+        plan.logits.zero_()
+        got = host(plan.run_graph(x))
+        assert np.array_equal(got, eager), i
+        # unrelated eager work between replays
+        y = B.quantize(x, 3)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(plan.run(x)), eager)
+    x2 = dev(net.input_float()[::-1].copy())
+    e2 = host(plan.run(x2)).copy()
+    assert np.array_equal(host(plan.run_graph(x2)), e2) and not np.array_equal(e2, eager)
