@@ -13,8 +13,9 @@
 // buffer loads (no register staging) issued nstages-1 steps ahead - across tile boundaries, so
 // the first loads of the next tile are in flight while the current one is multiplied and
 // written out (HBM latency here is about four steps of matrix work).  A wavefront waits only
-// for the loads of the step it is about to multiply (its own counter of outstanding vector
-// memory operations, then one workgroup barrier per step).  Each wavefront-wide load fills 16
+// for the loads of the step it is about to read (its own counter of outstanding vector memory
+// operations, then one workgroup barrier per step), and the operands of step i+1 are read from
+// LDS into a second register set while step i is multiplied.  Each wavefront-wide load fills 16
 // LDS rows of 64 bytes; which 16-byte piece of the step a lane fetches is XOR-ed with bits of
 // its row, so the 128-bit operand reads spread over all banks without padding.  Lanes whose
 // piece lies outside the image (padding), past the last pixel, past K or past R*S*C are given
@@ -29,7 +30,7 @@
 // packs them into one 16-byte store.  The 32-bit sums never leave registers unless the caller
 // asks for them (acc_out).
 #include "conv_epilogue.hpp"
-#include <cstdlib>
+#include <type_traits>
 
 namespace dfq {
 
@@ -38,6 +39,9 @@ namespace {
 constexpr int kStepBytes = 64;   // bytes of the reduction axis per LDS stage
 constexpr int kPieces = 4;       // 16-byte pieces per LDS row
 constexpr unsigned kOutOfRange = 0x80000000u;   // any offset with this bit set is past either buffer
+
+constexpr int kNumCU = 256;
+constexpr int kLdsBytes = 160 * 1024;
 
 struct MfmaParams {
     ConvArgs a;
@@ -48,7 +52,7 @@ struct MfmaParams {
     int tiles;        // pixel tiles * channel tiles
     int nstages;      // depth of the LDS ring
     unsigned x_bytes, w_bytes;
-    FastDiv div_pq, div_q, div_tc;
+    FastDiv div_pq, div_q, div_tc, div_ns, div_c, div_s;
 };
 
 // Buffer resource for raw byte addressing with range checking (stride 0: offsets >= bytes read as 0).
@@ -81,17 +85,7 @@ __device__ __forceinline__ void wait_loads()
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-#ifdef DFQ_PROFILE_TS
-__device__ long long g_ts[64 * 8];
-__device__ long long g_wall[2048 * 4];
-#define DFQ_T(var) const long long var = clock64()
-#define DFQ_ACC(slot, t1, t0) ts_acc[slot] += (t1) - (t0)
-#else
-#define DFQ_T(var) do { } while (0)
-#define DFQ_ACC(slot, t1, t0) do { } while (0)
-#endif
-
-// wait until only the loads of the next `ahead` (0..4) steps, LP loads each, are outstanding
+// wait until only the loads of the next `ahead` (0..5) steps, LP loads each, are outstanding
 template <int LP>
 __device__ __forceinline__ void wait_ahead(int ahead)
 {
@@ -100,15 +94,20 @@ __device__ __forceinline__ void wait_ahead(int ahead)
         case 1: wait_loads<LP>(); break;
         case 2: wait_loads<2 * LP>(); break;
         case 3: wait_loads<3 * LP>(); break;
-        default: wait_loads<4 * LP>(); break;
+        case 4: wait_loads<4 * LP>(); break;
+        default: wait_loads<5 * LP>(); break;
     }
 }
 
 // UT ("uniform taps"): C is a multiple of 64, so a 64-byte step never straddles two taps and
 // the tap is the same for every lane; its bookkeeping then lives in scalar registers.
-template <int BP, int BC, int WAVES_P, int WAVES_C, bool UT>
-__global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(MfmaParams prm)
+// GENERAL: the epilogue may meet a ragged channel tail, an unaligned or strided-odd output row, a
+// shift outside [1, 23] or an accumulator dump; the launcher picks the lean instantiation
+// (GENERAL = false) whenever none of these applies.  OCC: wavefronts per SIMD to fit registers for.
+template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool GENERAL, int OCC>
+__global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(MfmaParams prm)
 {
+    static_assert(NSTAGES >= 2 && NSTAGES <= 6, "ring depth");
     constexpr int NW = WAVES_P * WAVES_C;                 // wavefronts per workgroup
     static_assert(NW == 4 || NW == 8, "four or eight wavefronts per workgroup");
     constexpr int WP = BP / WAVES_P, WC = BC / WAVES_C;   // wavefront tile
@@ -121,7 +120,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(Mf
     constexpr int LPW = XS + WS;                          // loads per wavefront per step (with a weight chunk)
     constexpr int STAGE_PIECES = (BP + BC) * kPieces;
     static_assert(WP % 32 == 0 && WC % 32 == 0, "tile shape");
-    static_assert(4 * LPW < 64, "outstanding loads must fit the 6-bit counter");
+    static_assert(5 * LPW < 64, "outstanding loads must fit the 6-bit counter");
 
     extern __shared__ uint4 lds[];   // nstages stages of (BP + BC) rows of 64 bytes, then BC bias words
 
@@ -129,10 +128,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(Mf
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-#ifdef DFQ_PROFILE_TS
-    if (tid == 0 && blockIdx.x < 2048) { g_wall[blockIdx.x * 4] = wall_clock64(); g_wall[blockIdx.x * 4 + 2] = __smid(); }
-#endif
-    const int nstages = prm.nstages;
+    constexpr int nstages = NSTAGES;
     const int nsteps = prm.nsteps;
     const bool w_active = !kPartialW || wave < BC / 16;   // this wavefront fetches weight chunks
 
@@ -190,7 +186,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(Mf
     }
     int p_tile = lb, p_step = 0;     // tile and step the producer will fetch next
 
-    auto begin_tile = [&]() {
+    auto begin_tile = [&]() __attribute__((always_inline)) {
         const int m0 = fastdiv(p_tile, prm.div_tc) * BP;
 #pragma unroll
         for (int j = 0; j < XS; j++) {
@@ -208,13 +204,29 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(Mf
             rinv[j] = (live && rhi > rlo) ? ~(((1u << (rhi - rlo)) - 1u) << rlo) : 0xffffffffu;
             cinv[j] = (chi > clo) ? ~(((1u << (chi - clo)) - 1u) << clo) : 0xffffffffu;
         }
-        sr = 0; ss = 0; scb = 0; skb = 0;
-        kb = kb0; tr = tr0; ts = ts0; tc = tc0;
+        // The reduction of this tile starts at step p_tile mod nsteps and wraps around (an integer
+        // sum may be taken in any order): workgroups that run side by side then read different
+        // parts of the weight matrix at any moment instead of all hitting the same L2 lines.
+        const int s0 = p_tile - fastdiv(p_tile, prm.div_ns) * nsteps;
+        if (UT) {
+            skb = s0 * kStepBytes;
+            const int tap = fastdiv(skb, prm.div_c);
+            scb = skb - tap * a.C;
+            sr = fastdiv(tap, prm.div_s);
+            ss = tap - sr * a.S;
+        } else {
+            kb = kb0 + s0 * kStepBytes;
+            const int tap = fastdiv(kb, prm.div_c);
+            tc = kb - tap * a.C;
+            tr = fastdiv(tap, prm.div_s);
+            ts = tap - tr * a.S;
+        }
     };
 
-    auto issue = [&](int stage) {
+    auto issue = [&](int stage) __attribute__((always_inline)) {
         if (p_step == 0) begin_tile();
-        const unsigned sbase = lds_base + (unsigned)stage * (STAGE_PIECES * 16) + (unsigned)wave * 1024u;
+        const unsigned sbase = (unsigned)__builtin_amdgcn_readfirstlane(
+            (int)(lds_base + (unsigned)stage * (STAGE_PIECES * 16) + (unsigned)wave * 1024u));
         if (UT) {
             const unsigned soff = (unsigned)((sr * a.W + ss) * a.C + scb);
 #pragma unroll
@@ -233,6 +245,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(Mf
                 scb = 0;
                 if (++ss == a.S) { ss = 0; ++sr; }
             }
+            if (skb == prm.Kgemm) { skb = 0; sr = 0; }   // wrap to the first step (ss and scb are 0 here)
         } else {
             const unsigned toff = (unsigned)((tr * a.W + ts) * a.C + tc);
             const unsigned past = tr >= a.R ? 0xffffffffu : 0u;   // kb >= Kgemm
@@ -257,6 +270,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(Mf
                 ts = wraps ? 0 : ts;
                 tr += wraps ? 1 : 0;
             }
+            if (kb - kb0 >= nsteps * kStepBytes) { kb = kb0; tr = tr0; ts = ts0; tc = tc0; }   // wrap (uniform)
         }
         if (++p_step == nsteps) { p_step = 0; p_tile += G; }
     };
@@ -265,18 +279,17 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(Mf
     const int wc0 = (wave / WAVES_P) * WC;
     const int l32 = lane & 31, lh = lane >> 5;
     const int swz = (l32 >> 2) & 3;
-
+#pragma unroll
     for (int i = 0; i < nstages - 1; i++)
         if (i < nitems) issue(i);
 
     Requant rq;
     rq.init(a.shift, a.relu);
-    const bool fast = epilogue_is_fast(a, rq, k0 + BC);
     __syncthreads();   // bias_lds complete
 
     // accumulators start at the bias: register r of a lane belongs to channel kc + r
     v16i acc[CT][PT];
-    auto reset_acc = [&]() {
+    auto reset_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int c = 0; c < CT; c++) {
             const int4 *bp = (const int4 *)(bias_lds + wc0 + c * 32 + 16 * lh);
@@ -295,53 +308,29 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(Mf
     };
     reset_acc();
 
-#ifdef DFQ_PROFILE_TS
-    long long ts_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    const long long t_begin = clock64();
-#endif
-    int stage = 0, c_step = 0, c_tile = lb;
-    for (int it = 0; it < nitems; it++) {
-        DFQ_T(t0);
-        // loads of the next `ahead` items may stay in flight
-        const int ahead = min(nstages - 2, nitems - 1 - it);
-        if (w_active) wait_ahead<LPW>(ahead);
-        else wait_ahead<XS>(ahead);
-        DFQ_T(t1);
-        __syncthreads();
-        DFQ_T(t2);
-
+    // Operands of one step (both 32-byte halves) as the matrix instruction wants them.
+    struct Frags {
+        v4i w[2][CT];
+        v4i x[2][PT];
+    };
+    auto read_frags = [&](Frags &f, int stage) __attribute__((always_inline)) {
         const v4i *xs = (const v4i *)lds + stage * STAGE_PIECES;
         const v4i *ws = xs + BP * kPieces;
-        // operands of both halves of the step are requested up front: the second half arrives
-        // while the first is being multiplied
-        v4i wf[2][CT], xf[2][PT];
 #pragma unroll
         for (int kk = 0; kk < 2; kk++) {
             const int g = (kk * 2 + lh) ^ swz;
 #pragma unroll
-            for (int c = 0; c < CT; c++) wf[kk][c] = ws[(wc0 + c * 32 + l32) * kPieces + g];
+            for (int c = 0; c < CT; c++) f.w[kk][c] = ws[(wc0 + c * 32 + l32) * kPieces + g];
 #pragma unroll
-            for (int p = 0; p < PT; p++) xf[kk][p] = xs[(wp0 + p * 32 + l32) * kPieces + g];
+            for (int p = 0; p < PT; p++) f.x[kk][p] = xs[(wp0 + p * 32 + l32) * kPieces + g];
         }
-#ifdef DFQ_PROFILE_TS
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#endif
-        DFQ_T(t3);
-#pragma unroll
-        for (int kk = 0; kk < 2; kk++) {
-#pragma unroll
-            for (int c = 0; c < CT; c++)
-#pragma unroll
-                for (int p = 0; p < PT; p++)
-                    acc[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[kk][c], xf[kk][p], acc[c][p], 0, 0, 0);
-            // the refill of the stage consumed in the previous item is issued between the two
-            // halves, so its address arithmetic runs in the shadow of the matrix instructions
-            if (kk == 0 && it + nstages - 1 < nitems) issue(stage == 0 ? nstages - 1 : stage - 1);
-        }
-        stage = stage + 1 == nstages ? 0 : stage + 1;
-        DFQ_T(t4);
-        DFQ_ACC(0, t1, t0); DFQ_ACC(1, t2, t1); DFQ_ACC(2, t3, t2); DFQ_ACC(3, t4, t3);
+    };
+    // Workgroup barrier that first completes this wavefront's own LDS reads and waits for no
+    // vector-memory operation (the load ring is paced separately).
+    auto ring_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
+    int c_step = 0, c_tile = lb;
+    auto finish_item = [&]() __attribute__((always_inline)) {
         if (++c_step == nsteps) {
             // ---- epilogue of this tile: lane holds, per (c, p), channels kc..kc+15 of pixel m
             const int m0 = fastdiv(c_tile, prm.div_tc) * BP;
@@ -352,7 +341,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(Mf
                 for (int p = 0; p < PT; p++) {
                     const int m = m0 + wp0 + p * 32 + l32;
                     if (m < prm.M) {
-                        if (fast) store_tile_lane_fast(acc[c][p], a, rq, m, kc);
+                        if (!GENERAL) store_tile_lane_fast(acc[c][p], a, rq, m, kc);
                         else if (kc < a.K) store_tile_lane_general(acc[c][p], a, a.shift, a.relu, m, kc);
                     }
                 }
@@ -360,26 +349,62 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, 2) conv_mfma_kernel(Mf
             reset_acc();
             c_step = 0;
             c_tile += G;
-            DFQ_T(t5);
-            DFQ_ACC(4, t5, t4);
+        }
+    };
+    // One item: the stage is read into registers and multiplied; between the two halves the stage
+    // consumed by the previous item is refilled with the item nstages-1 ahead (REFILL), so the
+    // address arithmetic of the loads runs in the shadow of the matrix instructions.
+    auto do_item = [&](auto refill, int stage) __attribute__((always_inline)) {
+        ring_barrier();
+        Frags f;
+        read_frags(f, stage);
+#pragma unroll
+        for (int kk = 0; kk < 2; kk++) {
+#pragma unroll
+            for (int c = 0; c < CT; c++)
+#pragma unroll
+                for (int p = 0; p < PT; p++)
+                    acc[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.w[kk][c], f.x[kk][p], acc[c][p], 0, 0, 0);
+            if (decltype(refill)::value && kk == 0) issue(stage == 0 ? nstages - 1 : stage - 1);
+        }
+        finish_item();
+    };
+
+    // steady state: nstages-2 younger items stay in flight behind the one awaited; the refill is
+    // unconditional.  It is unrolled over the ring so that every LDS address and every load
+    // destination is a compile-time offset.  The last nstages-1 items drain the ring.
+    auto steady_wait = [&]() __attribute__((always_inline)) {
+        if (w_active) wait_loads<(nstages - 2) * LPW>();
+        else wait_loads<(nstages - 2) * XS>();
+    };
+    const int steady = nitems - (nstages - 1);
+    int it = 0;
+    for (; it + nstages <= steady; it += nstages) {
+#pragma unroll
+        for (int s = 0; s < nstages; s++) {
+            steady_wait();
+            do_item(std::true_type{}, s);
         }
     }
-#ifdef DFQ_PROFILE_TS
-    __builtin_amdgcn_s_waitcnt(0);
-    if (tid == 0 && blockIdx.x < 2048) g_wall[blockIdx.x * 4 + 1] = wall_clock64();
-    if ((tid & 63) == 0 && blockIdx.x < 8) {
-        ts_acc[5] = clock64() - t_begin;
-        ts_acc[6] = nitems;
-        for (int i = 0; i < 8; i++) g_ts[(blockIdx.x * NW + wave) % 64 * 8 + i] = ts_acc[i];
+    int stage = 0;   // it is a multiple of nstages here
+    for (; it < steady; it++) {
+        steady_wait();
+        do_item(std::true_type{}, stage);
+        stage = stage + 1 == nstages ? 0 : stage + 1;
     }
-#endif
+    for (; it < nitems; it++) {
+        const int ahead = nitems - 1 - it;
+        if (w_active) wait_ahead<LPW>(ahead);
+        else wait_ahead<XS>(ahead);
+        do_item(std::false_type{}, stage);
+        stage = stage + 1 == nstages ? 0 : stage + 1;
+    }
 }
 
-constexpr int kNumCU = 256;
-constexpr int kLdsBytes = 160 * 1024;
-
-// PER_CU: workgroups of this shape that fit one compute unit (registers), 1 or 2
-template <int BP, int BC, int WAVES_P, int WAVES_C, int PER_CU>
+// NSTAGES ring stages of (BP + BC) * 64 bytes plus the bias must fit the LDS share of a
+// workgroup: 160 KB / (workgroups per compute unit).
+// PER_CU: workgroups per compute unit the kernel is built and launched for (1 or 2)
+template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, int PER_CU>
 hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
 {
     MfmaParams prm;
@@ -392,38 +417,40 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     const long long tiles = ((M + BP - 1) / BP) * prm.tiles_c;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     prm.tiles = (int)tiles;
+    prm.nstages = NSTAGES;
     prm.x_bytes = (unsigned)((long long)a.N * a.H * a.W * a.C);
     prm.w_bytes = (unsigned)((long long)a.K * prm.Kgemm);
     prm.div_pq = make_fastdiv(a.P * a.Q);
     prm.div_q = make_fastdiv(a.Q);
     prm.div_tc = make_fastdiv(prm.tiles_c);
+    prm.div_ns = make_fastdiv(prm.nsteps);
+    prm.div_c = make_fastdiv(a.C);
+    prm.div_s = make_fastdiv(a.S);
 
-    // Two workgroups per compute unit when there are enough tiles (one multiplies while the
-    // other writes out), each with as many ring stages as half the LDS holds; otherwise one
-    // workgroup per compute unit with a deeper ring.
-    constexpr int stage_bytes = (BP + BC) * kStepBytes;
-    constexpr int bias_bytes = BC * 4;
-    const int per_cu = (PER_CU == 2 && tiles > kNumCU) ? 2 : 1;
-    int grid = per_cu * kNumCU;
+    int grid = PER_CU * kNumCU;
     if (grid > prm.tiles) grid = prm.tiles;
     grid = grid / prm.tiles_c * prm.tiles_c;            // the channel tile of a workgroup must not change
     if (grid < prm.tiles_c) grid = prm.tiles_c;
-    int nstages = (kLdsBytes / per_cu - bias_bytes - 1024) / stage_bytes;
-    if (nstages > 6) nstages = 6;
-    const int items = prm.nsteps * ((prm.tiles + grid - 1) / grid);
-    if (nstages > items) nstages = items;
-    if (nstages < 2) nstages = 2;
-    prm.nstages = nstages;
-    const size_t lds_bytes = (size_t)nstages * stage_bytes + bias_bytes;
+    constexpr size_t lds_bytes = (size_t)NSTAGES * (BP + BC) * kStepBytes + BC * 4;
+    static_assert(lds_bytes * PER_CU <= kLdsBytes, "rings do not fit the LDS");
 
     const bool ut = a.C % kStepBytes == 0;
-    auto kernel = ut ? conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, true> : conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, false>;
-    static hipError_t attr_ut = hipFuncSetAttribute((const void *)conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, true>,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    static hipError_t attr_gen = hipFuncSetAttribute((const void *)conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, false>,
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (attr_ut != hipSuccess) return attr_ut;
-    if (attr_gen != hipSuccess) return attr_gen;
+    const bool general = !(a.shift >= 1 && a.shift <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
+                           ((uintptr_t)a.y & 15) == 0 && a.K % BC == 0);
+    constexpr int occ = PER_CU * WAVES_P * WAVES_C / 4;
+    using K = void (*)(MfmaParams);
+    static const K kernels[4] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, occ>,
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, true, occ>,
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, occ>,
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, occ>};
+    static hipError_t attr[4] = {
+        hipFuncSetAttribute((const void *)kernels[0], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes),
+        hipFuncSetAttribute((const void *)kernels[1], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes),
+        hipFuncSetAttribute((const void *)kernels[2], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes),
+        hipFuncSetAttribute((const void *)kernels[3], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes)};
+    const int which = (ut ? 2 : 0) + (general ? 1 : 0);
+    if (attr[which] != hipSuccess) return attr[which];
+    K kernel = kernels[which];
     kernel<<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
     return hipGetLastError();
 }
@@ -446,16 +473,10 @@ bool conv_mfma_supports(const ConvArgs &a)
 
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st)
 {
-    const char *e = getenv("DFQ_CFG");
-    const int cfg = e ? atoi(e) : 0;
-    if (a.K <= 64) {
-        if (cfg == 1) return launch_cfg<512, 64, 8, 1, 2>(a, st);
-        return launch_cfg<256, 64, 4, 1, 2>(a, st);
-    }
-    if (cfg == 1) return launch_cfg<256, 256, 2, 4, 1>(a, st);   // wave 128 x 64
-    if (cfg == 2) return launch_cfg<512, 128, 4, 2, 1>(a, st);   // wave 128 x 64
-    if (cfg == 3) return launch_cfg<256, 128, 2, 2, 2>(a, st);   // 4 waves, 128 x 64
-    return launch_cfg<256, 128, 4, 2, 2>(a, st);
+    // 256 x 64 tiles (four wavefronts of 64 x 64) when there are at most 64 output channels,
+    // otherwise 256 x 128 (eight wavefronts of 64 x 64); three ring stages, two workgroups per CU
+    if (a.K <= 64) return launch_cfg<256, 64, 4, 1, 3, 2>(a, st);
+    return launch_cfg<256, 128, 4, 2, 3, 2>(a, st);
 }
 
 }  // namespace dfq
