@@ -118,7 +118,7 @@ def main():
                 src = nd.srcs[0]
                 mf = variant_of[nd.name] == B.CONV_MFMA
                 if mf:
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0, e1 = event_pool.pop(), event_pool.pop()
                     e0.record()
                 B.conv_q(t[src], netq.w[nd.name], netq.b[nd.name], netq.frac[src], netq.w_frac[nd.name],
                          netq.frac[nd.dst], nd.stride, nd.pad, nd.groups, nd.relu, out=t[nd.dst])
@@ -151,7 +151,9 @@ def main():
     # the matrix-core convolution kernel (events and kernels share torch's current stream).  A
     # short spin kernel first lets the host run ahead, so that the intervals hold no launch gaps.
     record = not args.no_kernel_events
+    event_pool = []
     if record:
+        event_pool = [torch.cuda.Event(enable_timing=True) for _ in range(2 * len(mfma_nodes) * args.steps)]
         for _ in range(args.steps):
             torch.cuda._sleep(6_000_000)
             run_step(True)
@@ -177,7 +179,8 @@ def main():
             ops += o
             tsum += ms
             per_layer.append(dict(layer=nd.name, us=round(ms * 1e3, 1), tops=round(o / ms / 1e9, 1),
-                                  gbs=round(by / ms / 1e6, 1)))
+                                  gbs=round(by / ms / 1e6, 1), min_us=round(min(dur[nd.name]) * 1e3, 1),
+                                  max_us=round(max(dur[nd.name]) * 1e3, 1)))
         achieved = ops / (tsum * 1e-3) / 1e12
         traffic = None
         tpath = os.path.join(ROOT, "profiles", "conv_mfma_traffic.json")

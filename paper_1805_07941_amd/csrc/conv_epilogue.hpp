@@ -37,6 +37,23 @@ struct Requant {
         const int odd = (int)__builtin_amdgcn_ubfe((unsigned)v, (unsigned)shift, 1u);
         return (v + bias_add + odd) >> shift;                      // v_add3_u32, v_ashrrev_i32
     }
+    // The same for four sums at once, the four results packed into one word of int8: the final
+    // shift writes its low byte straight into byte i of the word (sub-dword destination select).
+    __device__ __forceinline__ uint32_t fast_four(int v0, int v1, int v2, int v3) const
+    {
+        int t[4] = {v0, v1, v2, v3};
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            asm("v_med3_i32 %0, %1, %2, %3" : "=v"(t[i]) : "v"(t[i]), "s"(lo), "v"(hi));
+            t[i] = t[i] + bias_add + (int)__builtin_amdgcn_ubfe((unsigned)t[i], (unsigned)shift, 1u);
+        }
+        uint32_t w;
+        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD" : "=v"(w) : "v"(shift), "v"(t[0]));
+        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(shift), "v"(t[1]));
+        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(shift), "v"(t[2]));
+        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(shift), "v"(t[3]));
+        return w;
+    }
     __device__ __forceinline__ int slow_one(int v) const { return requant8(relu ? max(v, 0) : v, shift); }
 };
 
@@ -51,14 +68,14 @@ __device__ __forceinline__ uint32_t pack4_clamped(int a, int b, int c, int d)
 // One lane's share of a 32x32 accumulator tile: 16 consecutive output channels kc..kc+15 of
 // pixel m.  `v` already contains the bias.  Hot form: whole 16-channel group inside K, aligned
 // output row, shift in the fast range, no accumulator dump.
+__device__ __forceinline__ uint4 requant_tile_lane_fast(const v16i &v, const Requant &rq)
+{
+    return make_uint4(rq.fast_four(v[0], v[1], v[2], v[3]), rq.fast_four(v[4], v[5], v[6], v[7]),
+                      rq.fast_four(v[8], v[9], v[10], v[11]), rq.fast_four(v[12], v[13], v[14], v[15]));
+}
 __device__ __forceinline__ void store_tile_lane_fast(const v16i &v, const ConvArgs &a, const Requant &rq, long long m, int kc)
 {
-    int o[16];
-#pragma unroll
-    for (int r = 0; r < 16; r++) o[r] = rq.fast_one(v[r]);
-    *(uint4 *)(a.y + (size_t)m * a.ldy + kc) =
-        make_uint4(pack4_clamped(o[0], o[1], o[2], o[3]), pack4_clamped(o[4], o[5], o[6], o[7]),
-                   pack4_clamped(o[8], o[9], o[10], o[11]), pack4_clamped(o[12], o[13], o[14], o[15]));
+    *(uint4 *)(a.y + (size_t)m * a.ldy + kc) = requant_tile_lane_fast(v, rq);
 }
 
 // General form (ragged channel tail, unaligned rows, extreme shifts, accumulator dump).

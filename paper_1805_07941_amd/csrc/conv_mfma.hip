@@ -36,7 +36,7 @@ namespace dfq {
 
 namespace {
 
-constexpr int kStepBytes = 64;   // bytes of the reduction axis per LDS stage
+constexpr int kStepBytes = 64;   // bytes of the reduction axis per LDS stage (the width of an LDS row)
 constexpr int kPieces = 4;       // 16-byte pieces per LDS row
 constexpr unsigned kOutOfRange = 0x80000000u;   // any offset with this bit set is past either buffer
 
@@ -51,8 +51,8 @@ struct MfmaParams {
     int tiles_c;      // channel tiles
     int tiles;        // pixel tiles * channel tiles
     int nstages;      // depth of the LDS ring
-    unsigned x_bytes, w_bytes;
-    FastDiv div_pq, div_q, div_tc, div_ns, div_c, div_s;
+    unsigned x_bytes, w_bytes, y_bytes;
+    FastDiv div_pq, div_q, div_tc;
 };
 
 // Buffer resource for raw byte addressing with range checking (stride 0: offsets >= bytes read as 0).
@@ -77,6 +77,16 @@ __device__ __forceinline__ void load_piece_to_lds(unsigned voffset, v4i rsrc, un
                  : "memory", "m0");
 }
 
+// 16-byte store through a buffer resource: a lane whose offset is outside the buffer stores
+// nothing, so rows past the last pixel need no branch and every wavefront issues the same number
+// of stores per tile (the pacing of the load ring counts them).
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_piece(uint4 d, unsigned voffset, __amdgpu_buffer_rsrc_t rsrc)
+{
+    const v4u data = {d.x, d.y, d.z, d.w};
+    __builtin_amdgcn_raw_buffer_store_b128(data, rsrc, (int)voffset, 0, 0);
+}
+
 // wait until at most N vector-memory operations of this wavefront are outstanding
 template <int N>
 __device__ __forceinline__ void wait_loads()
@@ -99,28 +109,48 @@ __device__ __forceinline__ void wait_ahead(int ahead)
     }
 }
 
+// at most BASE + SP * cnt outstanding, for 0 <= cnt <= 5 (larger cnt waits as for 5)
+template <int BASE, int SP>
+__device__ __forceinline__ void wait_loads_plus(int cnt)
+{
+    static_assert(BASE + 5 * SP < 64, "vmcnt is a 6-bit counter");
+    switch (cnt) {
+        case 0: wait_loads<BASE>(); break;
+        case 1: wait_loads<BASE + SP>(); break;
+        case 2: wait_loads<BASE + 2 * SP>(); break;
+        case 3: wait_loads<BASE + 3 * SP>(); break;
+        case 4: wait_loads<BASE + 4 * SP>(); break;
+        default: wait_loads<BASE + 5 * SP>(); break;
+    }
+}
+
 // UT ("uniform taps"): C is a multiple of 64, so a 64-byte step never straddles two taps and
 // the tap is the same for every lane; its bookkeeping then lives in scalar registers.
+// PW ("pointwise", needs UT): R = S = 1, stride 1, no padding - output pixel m reads input pixel m,
+// so a tile needs no coordinate decoding and no border masks.
 // GENERAL: the epilogue may meet a ragged channel tail, an unaligned or strided-odd output row, a
 // shift outside [1, 23] or an accumulator dump; the launcher picks the lean instantiation
 // (GENERAL = false) whenever none of these applies.  OCC: wavefronts per SIMD to fit registers for.
-template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool GENERAL, int OCC>
+template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool PW, bool GENERAL, int OCC>
 __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(MfmaParams prm)
 {
     static_assert(NSTAGES >= 2 && NSTAGES <= 6, "ring depth");
+    static_assert(UT || !PW, "the pointwise form keeps its position in scalar registers");
     constexpr int NW = WAVES_P * WAVES_C;                 // wavefronts per workgroup
-    static_assert(NW == 4 || NW == 8, "four or eight wavefronts per workgroup");
+    static_assert(NW == 4 || NW == 8 || NW == 16, "4, 8 or 16 wavefronts per workgroup");
+    constexpr int RPC = 64 / kPieces;                     // LDS rows filled by one wavefront-wide load (a "chunk")
+    constexpr int KK = kStepBytes / 32;                   // matrix-instruction k-steps per stage
     constexpr int WP = BP / WAVES_P, WC = BC / WAVES_C;   // wavefront tile
     constexpr int PT = WP / 32, CT = WC / 32;             // 32x32 MFMA tiles per wavefront
-    // 16-row chunks each wavefront loads per step; when there are fewer weight chunks than
-    // wavefronts only the first BC/16 wavefronts fetch one
-    constexpr int XS = BP / (16 * NW), WS = (BC + 16 * NW - 1) / (16 * NW);
-    constexpr bool kPartialW = BC < 16 * NW;
-    static_assert(XS * 16 * NW == BP && (kPartialW || WS * 16 * NW == BC) && BC % 16 == 0, "whole 16-row chunks");
+    // chunks each wavefront loads per step; when there are fewer weight chunks than wavefronts
+    // only the first BC/RPC wavefronts fetch one
+    constexpr int XS = BP / (RPC * NW), WS = (BC + RPC * NW - 1) / (RPC * NW);
+    constexpr bool kPartialW = BC < RPC * NW;
+    static_assert(XS * RPC * NW == BP && (kPartialW || WS * RPC * NW == BC) && BC % 16 == 0, "whole chunks");
     constexpr int LPW = XS + WS;                          // loads per wavefront per step (with a weight chunk)
     constexpr int STAGE_PIECES = (BP + BC) * kPieces;
     static_assert(WP % 32 == 0 && WC % 32 == 0, "tile shape");
-    static_assert(5 * LPW < 64, "outstanding loads must fit the 6-bit counter");
+    static_assert(NSTAGES * LPW < 64, "outstanding loads must fit the 6-bit counter");
 
     extern __shared__ uint4 lds[];   // nstages stages of (BP + BC) rows of 64 bytes, then BC bias words
 
@@ -130,7 +160,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     constexpr int nstages = NSTAGES;
     const int nsteps = prm.nsteps;
-    const bool w_active = !kPartialW || wave < BC / 16;   // this wavefront fetches weight chunks
+    const bool w_active = !kPartialW || wave < BC / RPC;  // this wavefront fetches weight chunks
 
     // ---- this workgroup's tiles: lb, lb + G, lb + 2G, ...  Workgroup ids are dealt round-robin
     // to the 8 XCDs; renumbering them so that each XCD owns a contiguous run keeps tiles that
@@ -148,6 +178,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
 
     const v4i xrsrc = make_rsrc(a.x, prm.x_bytes);
     const v4i wrsrc = make_rsrc(a.w, prm.w_bytes);
+    const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, GENERAL ? 0 : (int)prm.y_bytes, 0x00020000);
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char *)(char *)&lds[0];
     int *bias_lds = (int *)(lds + nstages * STAGE_PIECES);
 
@@ -155,10 +186,11 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
     // vector-memory counter that paces the load ring)
     for (int i = tid; i < BC; i += NW * 64) bias_lds[i] = (a.b && k0 + i < a.K) ? a.b[k0 + i] : 0;
 
-    // ---- producer bookkeeping.  A wavefront-wide load covers rows 16*chunk .. 16*chunk+15 of
-    // the stage; lane l supplies row l/4, physical piece l%4, which holds logical piece
-    // (l%4) ^ ((row>>2)&3) - the same for every chunk of this lane.
-    const int lrow = lane >> 2;
+    // ---- producer bookkeeping.  A wavefront-wide load covers RPC consecutive rows (one chunk) of
+    // the stage; lane l supplies row l/4 of the chunk, physical piece l%4, which holds logical piece
+    // (l%4) ^ ((row>>2)&3) - the same for every chunk of this lane; 16 consecutive rows then put
+    // any one logical piece on 16 different bank groups.
+    const int lrow = lane / kPieces;
     const int lp = (lane & 3) ^ ((lane >> 4) & 3);
     unsigned xoff[XS];               // byte offset of tap (0,0) of the lane's pixel, plus the lane's piece (mod 2^32)
     uint32_t rinv[XS], cinv[XS];     // bit r / bit s set: that kernel row / column falls OUTSIDE the image
@@ -167,7 +199,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
     for (int j = 0; j < WS; j++) {
         // LDS row i = 8g + 4h + e of a 32-row group receives channel 16h + 4g + e: the matrix
         // instruction then leaves 16 consecutive channels in each lane
-        const int rr = 16 * (wave + NW * j) + lrow;
+        const int rr = RPC * (wave + NW * j) + lrow;
         const int i32 = rr & 31;
         const int k = k0 + (rr & ~31) + 16 * ((i32 >> 2) & 1) + 4 * (i32 >> 3) + (i32 & 3);
         woff[j] = k < a.K ? (unsigned)(k * prm.Kgemm) + (UT ? (unsigned)lp * 16u : 0u) : kOutOfRange;
@@ -190,8 +222,12 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
         const int m0 = fastdiv(p_tile, prm.div_tc) * BP;
 #pragma unroll
         for (int j = 0; j < XS; j++) {
-            const int m = m0 + 16 * (wave + NW * j) + lrow;
+            const int m = m0 + RPC * (wave + NW * j) + lrow;
             const bool live = m < prm.M;
+            if (PW) {
+                xoff[j] = live ? (unsigned)(m * a.C) + (unsigned)lp * 16u : kOutOfRange;
+                continue;
+            }
             const int mi = live ? m : 0;
             const int n = fastdiv(mi, prm.div_pq);
             const int pq = mi - n * (a.P * a.Q);
@@ -204,22 +240,11 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
             rinv[j] = (live && rhi > rlo) ? ~(((1u << (rhi - rlo)) - 1u) << rlo) : 0xffffffffu;
             cinv[j] = (chi > clo) ? ~(((1u << (chi - clo)) - 1u) << clo) : 0xffffffffu;
         }
-        // The reduction of this tile starts at step p_tile mod nsteps and wraps around (an integer
-        // sum may be taken in any order): workgroups that run side by side then read different
-        // parts of the weight matrix at any moment instead of all hitting the same L2 lines.
-        const int s0 = p_tile - fastdiv(p_tile, prm.div_ns) * nsteps;
+        // back to the first step of the reduction axis
         if (UT) {
-            skb = s0 * kStepBytes;
-            const int tap = fastdiv(skb, prm.div_c);
-            scb = skb - tap * a.C;
-            sr = fastdiv(tap, prm.div_s);
-            ss = tap - sr * a.S;
+            skb = 0; scb = 0; sr = 0; ss = 0;
         } else {
-            kb = kb0 + s0 * kStepBytes;
-            const int tap = fastdiv(kb, prm.div_c);
-            tc = kb - tap * a.C;
-            tr = fastdiv(tap, prm.div_s);
-            ts = tap - tr * a.S;
+            kb = kb0; tr = tr0; ts = ts0; tc = tc0;
         }
     };
 
@@ -228,10 +253,10 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
         const unsigned sbase = (unsigned)__builtin_amdgcn_readfirstlane(
             (int)(lds_base + (unsigned)stage * (STAGE_PIECES * 16) + (unsigned)wave * 1024u));
         if (UT) {
-            const unsigned soff = (unsigned)((sr * a.W + ss) * a.C + scb);
+            const unsigned soff = PW ? (unsigned)skb : (unsigned)((sr * a.W + ss) * a.C + scb);
 #pragma unroll
             for (int j = 0; j < XS; j++) {
-                const unsigned bad = (unsigned)(__builtin_amdgcn_sbfe((int)rinv[j], sr, 1) | __builtin_amdgcn_sbfe((int)cinv[j], ss, 1));
+                const unsigned bad = PW ? 0u : (unsigned)(__builtin_amdgcn_sbfe((int)rinv[j], sr, 1) | __builtin_amdgcn_sbfe((int)cinv[j], ss, 1));
                 load_piece_to_lds((xoff[j] + soff) | bad, xrsrc, sbase + (unsigned)j * (NW * 1024u));
             }
             if (w_active) {
@@ -240,12 +265,13 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
                     load_piece_to_lds(woff[j] + (unsigned)skb, wrsrc, sbase + (unsigned)(BP * 64) + (unsigned)j * (NW * 1024u));
             }
             skb += kStepBytes;
-            scb += kStepBytes;
-            if (scb == a.C) {
-                scb = 0;
-                if (++ss == a.S) { ss = 0; ++sr; }
+            if (!PW) {
+                scb += kStepBytes;
+                if (scb == a.C) {
+                    scb = 0;
+                    if (++ss == a.S) { ss = 0; ++sr; }
+                }
             }
-            if (skb == prm.Kgemm) { skb = 0; sr = 0; }   // wrap to the first step (ss and scb are 0 here)
         } else {
             const unsigned toff = (unsigned)((tr * a.W + ts) * a.C + tc);
             const unsigned past = tr >= a.R ? 0xffffffffu : 0u;   // kb >= Kgemm
@@ -270,7 +296,6 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
                 ts = wraps ? 0 : ts;
                 tr += wraps ? 1 : 0;
             }
-            if (kb - kb0 >= nsteps * kStepBytes) { kb = kb0; tr = tr0; ts = ts0; tc = tc0; }   // wrap (uniform)
         }
         if (++p_step == nsteps) { p_step = 0; p_tile += G; }
     };
@@ -279,8 +304,9 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
     const int wc0 = (wave / WAVES_P) * WC;
     const int l32 = lane & 31, lh = lane >> 5;
     const int swz = (l32 >> 2) & 3;
+    // every stage of the ring is filled before the first item is read
 #pragma unroll
-    for (int i = 0; i < nstages - 1; i++)
+    for (int i = 0; i < nstages; i++)
         if (i < nitems) issue(i);
 
     Requant rq;
@@ -308,41 +334,64 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
     };
     reset_acc();
 
-    // Operands of one step (both 32-byte halves) as the matrix instruction wants them.
-    struct Frags {
-        v4i w[2][CT];
-        v4i x[2][PT];
+    // Operands of one step as the matrix instruction wants them: one register set per 32-byte half.
+    struct Half {
+        v4i w[CT];
+        v4i x[PT];
     };
-    auto read_frags = [&](Frags &f, int stage) __attribute__((always_inline)) {
+    Half f0, f1;
+    auto read_half = [&](Half &f, int kk, int stage) __attribute__((always_inline)) {
         const v4i *xs = (const v4i *)lds + stage * STAGE_PIECES;
         const v4i *ws = xs + BP * kPieces;
+        const int g = (kk * 2 + lh) ^ swz;   // physical piece
 #pragma unroll
-        for (int kk = 0; kk < 2; kk++) {
-            const int g = (kk * 2 + lh) ^ swz;
+        for (int c = 0; c < CT; c++) f.w[c] = ws[(wc0 + c * 32 + l32) * kPieces + g];
 #pragma unroll
-            for (int c = 0; c < CT; c++) f.w[kk][c] = ws[(wc0 + c * 32 + l32) * kPieces + g];
+        for (int p = 0; p < PT; p++) f.x[p] = xs[(wp0 + p * 32 + l32) * kPieces + g];
+    };
+    auto mfma_half = [&](const Half &f) __attribute__((always_inline)) {
 #pragma unroll
-            for (int p = 0; p < PT; p++) f.x[kk][p] = xs[(wp0 + p * 32 + l32) * kPieces + g];
-        }
+        for (int c = 0; c < CT; c++)
+#pragma unroll
+            for (int p = 0; p < PT; p++)
+                acc[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.w[c], f.x[p], acc[c][p], 0, 0, 0);
     };
     // Workgroup barrier that first completes this wavefront's own LDS reads and waits for no
     // vector-memory operation (the load ring is paced separately).
     auto ring_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
+    // The pacing of the load ring counts outstanding vector-memory operations, and the stores
+    // of an epilogue are among them (loads and stores complete in issue order).  ep_hist has bit k
+    // set when item i-1-k ended a tile whose epilogue issued exactly kStoresPerTile stores; the
+    // loads awaited in item i were issued in item i+1-nstages ahead of that item's epilogue, so
+    // the epilogues of the last nstages-1 items are younger than they are.  Stores that are not
+    // counted only make a wait longer, never too short.
+    constexpr int kStoresPerTile = CT * PT;
+    constexpr unsigned kHistMask = (1u << (NSTAGES - 1)) - 1u;
+    unsigned ep_hist = 0;
+    const unsigned lane_yoff = (unsigned)((wp0 + l32) * a.ldy + k0 + wc0 + 16 * lh);   // lean form: y fits 31 bits
     int c_step = 0, c_tile = lb;
     auto finish_item = [&]() __attribute__((always_inline)) {
+        ep_hist = (ep_hist << 1) & kHistMask;
         if (++c_step == nsteps) {
             // ---- epilogue of this tile: lane holds, per (c, p), channels kc..kc+15 of pixel m
             const int m0 = fastdiv(c_tile, prm.div_tc) * BP;
+            if (!GENERAL) {
+                const unsigned tile_off = (unsigned)(m0 * a.ldy);
 #pragma unroll
-            for (int c = 0; c < CT; c++) {
-                const int kc = k0 + wc0 + c * 32 + 16 * lh;
+                for (int c = 0; c < CT; c++)
 #pragma unroll
-                for (int p = 0; p < PT; p++) {
-                    const int m = m0 + wp0 + p * 32 + l32;
-                    if (m < prm.M) {
-                        if (!GENERAL) store_tile_lane_fast(acc[c][p], a, rq, m, kc);
-                        else if (kc < a.K) store_tile_lane_general(acc[c][p], a, a.shift, a.relu, m, kc);
+                    for (int p = 0; p < PT; p++)
+                        store_piece(requant_tile_lane_fast(acc[c][p], rq), lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32), yrsrc);
+                ep_hist |= 1u;
+            } else {
+#pragma unroll
+                for (int c = 0; c < CT; c++) {
+                    const int kc = k0 + wc0 + c * 32 + 16 * lh;
+#pragma unroll
+                    for (int p = 0; p < PT; p++) {
+                        const int m = m0 + wp0 + p * 32 + l32;
+                        if (m < prm.M && kc < a.K) store_tile_lane_general(acc[c][p], a, a.shift, a.relu, m, kc);
                     }
                 }
             }
@@ -351,54 +400,74 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
             c_tile += G;
         }
     };
-    // One item: the stage is read into registers and multiplied; between the two halves the stage
-    // consumed by the previous item is refilled with the item nstages-1 ahead (REFILL), so the
-    // address arithmetic of the loads runs in the shadow of the matrix instructions.
-    auto do_item = [&](auto refill, int stage) __attribute__((always_inline)) {
-        ring_barrier();
-        Frags f;
-        read_frags(f, stage);
+    // Item i multiplies step i in KK = 2 k-steps of 32 bytes.  Two register sets alternate: while
+    // one is multiplied the other is filled with the operands two k-steps ahead, i.e. those of
+    // stage i+1.  Before the first read of stage i+1 the wavefront waits for its own loads of that
+    // stage and meets the others at the barrier; every wavefront has then also completed its last
+    // read of stage i, so REFILL may overwrite stage i with item i + nstages - it is issued behind
+    // the second k-step's matrix instructions, so that a wavefront held up at a full address queue
+    // of the memory pipeline still has its matrix work queued.  LDS latency, the barrier and the
+    // address arithmetic of the loads all run in the shadow of the matrix pipe.
+    auto do_item = [&](auto refill, auto has_next, auto wait, int stage) __attribute__((always_inline)) {
+        const int next = stage + 1 == nstages ? 0 : stage + 1;
 #pragma unroll
-        for (int kk = 0; kk < 2; kk++) {
-#pragma unroll
-            for (int c = 0; c < CT; c++)
-#pragma unroll
-                for (int p = 0; p < PT; p++)
-                    acc[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.w[kk][c], f.x[kk][p], acc[c][p], 0, 0, 0);
-            if (decltype(refill)::value && kk == 0) issue(stage == 0 ? nstages - 1 : stage - 1);
+        for (int kk = 0; kk < KK; kk++) {
+            Half &f = (kk & 1) ? f1 : f0;
+            mfma_half(f);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kk == KK - 2 && decltype(has_next)::value) {
+                wait();
+                ring_barrier();
+            }
+            if (kk == KK - 1 && decltype(refill)::value) issue(stage);
+            // the operands two k-steps ahead go into the registers just consumed
+            if (kk + 2 < KK) read_half(f, kk + 2, stage);
+            else if (decltype(has_next)::value) read_half(f, kk + 2 - KK, next);
+            __builtin_amdgcn_sched_barrier(0);
         }
         finish_item();
     };
 
-    // steady state: nstages-2 younger items stay in flight behind the one awaited; the refill is
-    // unconditional.  It is unrolled over the ring so that every LDS address and every load
-    // destination is a compile-time offset.  The last nstages-1 items drain the ring.
+    // steady state: after the wait nstages-2 younger items stay in flight, after the refill
+    // nstages-1.  Unrolled over the ring so that every LDS address and every load destination is
+    // a compile-time offset.  The last nstages items drain the ring.
     auto steady_wait = [&]() __attribute__((always_inline)) {
-        if (w_active) wait_loads<(nstages - 2) * LPW>();
-        else wait_loads<(nstages - 2) * XS>();
+        const int younger_epilogues = __builtin_popcount(ep_hist);
+        if (w_active) wait_loads_plus<(nstages - 2) * LPW, kStoresPerTile>(younger_epilogues);
+        else wait_loads_plus<(nstages - 2) * XS, kStoresPerTile>(younger_epilogues);
     };
-    const int steady = nitems - (nstages - 1);
+    auto drain_wait_for = [&](int ahead) __attribute__((always_inline)) {
+        if (w_active) wait_ahead<LPW>(ahead);
+        else wait_ahead<XS>(ahead);
+    };
+    if (nitems > 0) {
+        drain_wait_for(min(nitems, nstages) - 1);
+        ring_barrier();
+        read_half(f0, 0, 0);
+        read_half(f1, 1, 0);
+    }
+    const int steady = nitems - nstages;     // items that refill their stage
     int it = 0;
     for (; it + nstages <= steady; it += nstages) {
 #pragma unroll
-        for (int s = 0; s < nstages; s++) {
-            steady_wait();
-            do_item(std::true_type{}, s);
-        }
+        for (int s = 0; s < nstages; s++) do_item(std::true_type{}, std::true_type{}, steady_wait, s);
     }
     int stage = 0;   // it is a multiple of nstages here
     for (; it < steady; it++) {
-        steady_wait();
-        do_item(std::true_type{}, stage);
+        do_item(std::true_type{}, std::true_type{}, steady_wait, stage);
         stage = stage + 1 == nstages ? 0 : stage + 1;
     }
-    for (; it < nitems; it++) {
-        const int ahead = nitems - 1 - it;
-        if (w_active) wait_ahead<LPW>(ahead);
-        else wait_ahead<XS>(ahead);
-        do_item(std::false_type{}, stage);
+    for (; it < nitems - 1; it++) {
+        const int ahead = nitems - 2 - it;   // items younger than the one awaited
+        do_item(std::false_type{}, std::true_type{}, [&]() __attribute__((always_inline)) { drain_wait_for(ahead); }, stage);
         stage = stage + 1 == nstages ? 0 : stage + 1;
     }
+    if (it < nitems) do_item(std::false_type{}, std::false_type{}, steady_wait, stage);
+}
+
+inline hipError_t big_lds(void (*k)(MfmaParams))
+{
+    return hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
 }
 
 // NSTAGES ring stages of (BP + BC) * 64 bytes plus the bias must fit the LDS share of a
@@ -420,12 +489,11 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     prm.nstages = NSTAGES;
     prm.x_bytes = (unsigned)((long long)a.N * a.H * a.W * a.C);
     prm.w_bytes = (unsigned)((long long)a.K * prm.Kgemm);
+    const long long y_bytes = M * a.ldy;
+    prm.y_bytes = y_bytes < (1LL << 31) ? (unsigned)y_bytes : 0u;
     prm.div_pq = make_fastdiv(a.P * a.Q);
     prm.div_q = make_fastdiv(a.Q);
     prm.div_tc = make_fastdiv(prm.tiles_c);
-    prm.div_ns = make_fastdiv(prm.nsteps);
-    prm.div_c = make_fastdiv(a.C);
-    prm.div_s = make_fastdiv(a.S);
 
     int grid = PER_CU * kNumCU;
     if (grid > prm.tiles) grid = prm.tiles;
@@ -436,19 +504,19 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
 
     const bool ut = a.C % kStepBytes == 0;
     const bool general = !(a.shift >= 1 && a.shift <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
-                           ((uintptr_t)a.y & 15) == 0 && a.K % BC == 0);
+                           ((uintptr_t)a.y & 15) == 0 && a.K % BC == 0 && y_bytes < (1LL << 31));
     constexpr int occ = PER_CU * WAVES_P * WAVES_C / 4;
     using K = void (*)(MfmaParams);
-    static const K kernels[4] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, occ>,
-                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, true, occ>,
-                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, occ>,
-                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, occ>};
-    static hipError_t attr[4] = {
-        hipFuncSetAttribute((const void *)kernels[0], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes),
-        hipFuncSetAttribute((const void *)kernels[1], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes),
-        hipFuncSetAttribute((const void *)kernels[2], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes),
-        hipFuncSetAttribute((const void *)kernels[3], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes)};
-    const int which = (ut ? 2 : 0) + (general ? 1 : 0);
+    const bool pw = ut && a.R == 1 && a.S == 1 && a.stride == 1 && a.pad == 0;
+    static const K kernels[6] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, false, occ>,
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, true, occ>,
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, false, occ>,
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, true, occ>,
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, false, occ>,
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, true, occ>};
+    static const hipError_t attr[6] = {big_lds(kernels[0]), big_lds(kernels[1]), big_lds(kernels[2]),
+                                       big_lds(kernels[3]), big_lds(kernels[4]), big_lds(kernels[5])};
+    const int which = (pw ? 4 : ut ? 2 : 0) + (general ? 1 : 0);
     if (attr[which] != hipSuccess) return attr[which];
     K kernel = kernels[which];
     kernel<<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
