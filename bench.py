@@ -102,7 +102,8 @@ def main():
     for nd in convs:
         H, W, C = net.shapes[nd.srcs[0]]
         variant_of[nd.name] = B.conv_q_select(args.batch, H, W, C, nd.K, nd.R, nd.R, nd.stride, nd.pad, nd.groups)
-    mfma_nodes = [nd for nd in convs if variant_of[nd.name] == B.CONV_MFMA]
+    matrix_core = (B.CONV_MFMA, B.CONV_POINTWISE)   # the dense kernels on the int8 matrix cores
+    mfma_nodes = [nd for nd in convs if variant_of[nd.name] in matrix_core]
 
     # instrumented pass: the same call sequence with an event pair around each MFMA convolution
     events = []
@@ -116,7 +117,7 @@ def main():
         for nd in net.nodes:
             if nd.op == "conv":
                 src = nd.srcs[0]
-                mf = variant_of[nd.name] == B.CONV_MFMA
+                mf = variant_of[nd.name] in matrix_core
                 if mf:
                     e0, e1 = event_pool.pop(), event_pool.pop()
                     e0.record()
@@ -186,7 +187,7 @@ def main():
         tpath = os.path.join(ROOT, "profiles", "conv_mfma_traffic.json")
         if os.path.exists(tpath):
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        roofline = dict(bound="mfma", kernel="conv_mfma_kernel (all instantiations, %d launches per step)" % len(mfma_nodes),
+        roofline = dict(bound="mfma", kernel="conv_mfma_kernel + conv_pw_kernel (dense int8 matrix-core convolutions, %d launches per step)" % len(mfma_nodes),
                         achieved=round(achieved, 2), peak=INT8_MFMA_PEAK_TOPS, unit="TOP/s",
                         frac=round(achieved / INT8_MFMA_PEAK_TOPS, 4), traffic=traffic,
                         avg_launch_us=round(tsum / len(mfma_nodes) * 1e3, 2),

@@ -60,7 +60,11 @@ typedef enum {
     DFQ_CONV_DIRECT = 1,   /* one output element per lane; any shape */
     DFQ_CONV_MFMA = 2,     /* implicit GEMM on int8 MFMA; groups == 1, C % 16 == 0 */
     DFQ_CONV_DEPTHWISE = 3,/* groups == C == K, channel-vectorized VALU kernel; C % 4 == 0 */
-    DFQ_CONV_SMALLC = 4    /* implicit GEMM for few input channels (first layers); groups == 1, S*C <= 32 */
+    DFQ_CONV_SMALLC = 4,   /* implicit GEMM for few input channels (first layers); groups == 1, S*C <= 32 */
+    DFQ_CONV_POINTWISE = 5 /* int8 MFMA with the input tile resident in LDS; unpadded 1x1 stride 1, groups == 1,
+                              C in {64, 128, 192, 256}, K % 64 == 0, (K / (K % 128 ? 64 : 128)) * (C / 64) >= 2,
+                              16-byte aligned x, w, y, ldy % 16 == 0, rescale shift f_in + f_w - f_out in [1, 23],
+                              no acc_out */
 } dfq_conv_variant;
 
 typedef void *dfq_stream;
@@ -107,8 +111,9 @@ dfq_status dfq_conv_q_variant(dfq_conv_variant variant,
                               int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
                               int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu, dfq_stream stream);
 
-/* The variant dfq_conv_q would run for this geometry (host, pure); DFQ_CONV_AUTO if the
- * geometry is invalid. */
+/* The variant dfq_conv_q would run for this geometry (host, pure) when the tensors are 16-byte
+ * aligned, ldy == K, the rescale shift lies in [1, 23] and no accumulator dump is asked for;
+ * DFQ_CONV_AUTO if the geometry is invalid. */
 dfq_conv_variant dfq_conv_q_select(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups);
 
 /* ---- scaled addition (Sec. 2.2, Eq. 10) -------------------------------------------------

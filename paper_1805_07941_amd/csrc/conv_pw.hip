@@ -1,0 +1,395 @@
+// Pointwise quantized convolution (R = S = 1, stride 1, no padding, groups == 1) on the gfx950
+// int8 matrix cores, with the input tile resident in LDS.
+//
+// For a 1x1 kernel the sum of Eq. 6 is the plain matrix product  acc[k][m] = sum_c W[k][c] * X[m][c]
+// over the N*H*W pixels m.  With few input channels (C <= 256) each product term is cheap and the
+// layer is bound by memory traffic, so what matters is how often a byte travels from L2 to a
+// compute unit.  The general dense kernel gives every (pixel tile, channel tile) pair its own pass
+// over the input tile, i.e. K/BC passes per pixel tile.  Here a workgroup keeps the BP x C input
+// tile in LDS while it walks over the channel tiles of that pixel tile: the input is fetched once
+// per pixel tile (while the previous tile is still being multiplied: two input buffers), and only
+// the BC x 64-byte weight slabs stream through a small ring.
+//
+// Work is cut into units (pixel tile, channel tile), pixel tile major, and every workgroup takes
+// one contiguous, equally long run of units, so that the load is even although the number of
+// pixel tiles is not a multiple of the number of compute units; a run that starts in the middle
+// of a pixel tile fetches that input tile as well.
+//
+// The inner structure is that of the general dense kernel: items of one 64-byte step, operands of
+// the next item read into a second register set while the current one is multiplied, loads
+// issued nstages items ahead directly into LDS, one barrier per item, the epilogue (bias as
+// start value, ReLU, rounding shift, clamp: the rescale of Eq. 6 for power-of-two scales) in
+// registers, 16-byte stores.  Only the lean epilogue exists here; the launcher falls back to the
+// general kernel otherwise.
+#include "conv_ring.hpp"
+#include <type_traits>
+
+namespace dfq {
+
+namespace {
+
+struct PwParams {
+    ConvArgs a;
+    int M;            // N*H*W
+    int nsteps;       // C / 64
+    int tiles_c;      // K / BC
+    int units;        // pixel tiles * channel tiles
+    unsigned x_bytes, w_bytes, y_bytes;
+    FastDiv div_tc;
+};
+
+// at most BASE + SA * ca + SB * cb outstanding vector-memory operations, ca and cb in [0, 2]
+template <int BASE, int SA, int SB>
+__device__ __forceinline__ void wait_loads_plus2(int ca, int cb)
+{
+    switch (cb) {
+        case 0: wait_loads_plus<BASE, SA>(min(ca, 2)); break;
+        case 1: wait_loads_plus<BASE + SB, SA>(min(ca, 2)); break;
+        default: wait_loads_plus<BASE + 2 * SB, SA>(min(ca, 2)); break;
+    }
+}
+
+template <int BP, int BC, int WAVES_P, int WAVES_C, int OCC>
+__global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(PwParams prm)
+{
+    constexpr int NSTAGES = 3;                            // depth of the weight ring
+    constexpr int NW = WAVES_P * WAVES_C;                 // wavefronts per workgroup
+    static_assert(NW == 4 || NW == 8, "four or eight wavefronts per workgroup");
+    constexpr int WP = BP / WAVES_P, WC = BC / WAVES_C;   // wavefront tile
+    constexpr int PT = WP / 32, CT = WC / 32;             // 32x32 MFMA tiles per wavefront
+    constexpr int RPC = 64 / kPieces;                     // LDS rows filled by one wavefront-wide load
+    constexpr int XS = BP / (RPC * NW), WS = (BC + RPC * NW - 1) / (RPC * NW);
+    constexpr bool kPartialW = BC < RPC * NW;
+    static_assert(XS * RPC * NW == BP && (kPartialW || WS * RPC * NW == BC) && BC % 16 == 0, "whole chunks");
+    static_assert(WP % 32 == 0 && WC % 32 == 0, "tile shape");
+    constexpr int SLAB_PIECES = BP * kPieces;             // one 64-byte step of the input tile
+    constexpr int WSTAGE_PIECES = BC * kPieces;           // one 64-byte step of the weight tile
+
+    // LDS: input buffers [2][nsteps] slabs of BP rows x 64 bytes, weight ring [NSTAGES] slabs of BC rows
+    // x 64 bytes, bias of all K channels
+    extern __shared__ uint4 lds[];
+
+    const ConvArgs &a = prm.a;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nsteps = prm.nsteps;
+    const bool w_active = !kPartialW || wave < BC / RPC;
+
+    // ---- this workgroup's run of units.  Workgroup ids are dealt round-robin to the 8 XCDs;
+    // renumbering them so that each XCD owns a contiguous range keeps workgroups that share an
+    // input tile in one L2.
+    const int G = gridDim.x;
+    int lb = blockIdx.x;
+    {
+        const int per = G / 8, rem = G % 8, xcd = lb % 8, idx = lb / 8;
+        lb = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+    }
+    const int per_wg = prm.units / G, extra = prm.units % G;
+    const int u0 = lb * per_wg + min(lb, extra);
+    const int nunits = per_wg + (lb < extra ? 1 : 0);
+    const int nitems = nunits * nsteps;
+
+    const v4i xrsrc = make_rsrc(a.x, prm.x_bytes);
+    const v4i wrsrc = make_rsrc(a.w, prm.w_bytes);
+    const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, (int)prm.y_bytes, 0x00020000);
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char *)(char *)&lds[0];
+    const int ring_piece0 = 2 * nsteps * SLAB_PIECES;
+    int *bias_lds = (int *)(lds + ring_piece0 + NSTAGES * WSTAGE_PIECES);
+    for (int i = tid; i < a.K; i += NW * 64) bias_lds[i] = a.b ? a.b[i] : 0;
+
+    // ---- producer.  Lane l of a wavefront-wide load supplies row l/4 of a 16-row chunk, physical
+    // piece l%4, which holds logical piece (l%4) ^ ((row>>2)&3): 16 consecutive rows then put any
+    // one logical piece on 16 different bank groups.
+    const int lrow = lane / kPieces;
+    const int lp = (lane & 3) ^ ((lane >> 4) & 3);
+    unsigned xoff[XS];               // byte offset of the lane's pixel row (+ piece), or out of range past M
+    unsigned woff[WS];               // byte offset of the lane's weight row of channel tile 0 (+ piece)
+#pragma unroll
+    for (int j = 0; j < WS; j++) {
+        // LDS row i = 8g + 4h + e of a 32-row group receives channel 16h + 4g + e: the matrix
+        // instruction then leaves 16 consecutive channels in each lane
+        const int rr = RPC * (wave + NW * j) + lrow;
+        const int i32 = rr & 31;
+        const int k = (rr & ~31) + 16 * ((i32 >> 2) & 1) + 4 * (i32 >> 3) + (i32 & 3);
+        woff[j] = (unsigned)(k * a.C) + (unsigned)lp * 16u;
+    }
+    int p_pt, p_ct, p_step = 0, p_par = 0;   // unit, step and input buffer the producer fetches next
+    bool p_loadx = true;                     // that unit is the run's first of its pixel tile: fetch the input too
+    p_pt = fastdiv(u0, prm.div_tc);
+    p_ct = u0 - p_pt * prm.tiles_c;
+    unsigned p_hist = 0;                     // bit q: the q-th last issued item fetched input
+
+    auto issue = [&](int stage) __attribute__((always_inline)) {
+        if (p_step == 0 && p_loadx) {
+            const int m0 = p_pt * BP;
+#pragma unroll
+            for (int j = 0; j < XS; j++) {
+                const int m = m0 + RPC * (wave + NW * j) + lrow;
+                xoff[j] = m < prm.M ? (unsigned)(m * a.C) + (unsigned)lp * 16u : kOutOfRange;
+            }
+        }
+        const unsigned step_off = (unsigned)p_step * kStepBytes;
+        if (p_loadx) {
+            const unsigned xbase = (unsigned)__builtin_amdgcn_readfirstlane(
+                (int)(lds_base + (unsigned)((p_par * nsteps + p_step) * SLAB_PIECES) * 16u + (unsigned)wave * 1024u));
+#pragma unroll
+            for (int j = 0; j < XS; j++) load_piece_to_lds(xoff[j] + step_off, xrsrc, xbase + (unsigned)j * (NW * 1024u));
+        }
+        if (w_active) {
+            const unsigned wbase = (unsigned)__builtin_amdgcn_readfirstlane(
+                (int)(lds_base + (unsigned)(ring_piece0 + stage * WSTAGE_PIECES) * 16u + (unsigned)wave * 1024u));
+            const unsigned tile_off = (unsigned)(p_ct * BC * a.C) + step_off;
+#pragma unroll
+            for (int j = 0; j < WS; j++) load_piece_to_lds(woff[j] + tile_off, wrsrc, wbase + (unsigned)j * (NW * 1024u));
+        }
+        p_hist = (p_hist << 1) | (p_loadx ? 1u : 0u);
+        if (++p_step == nsteps) {
+            p_step = 0;
+            p_loadx = false;
+            if (++p_ct == prm.tiles_c) {
+                p_ct = 0;
+                ++p_pt;
+                p_par ^= 1;
+                p_loadx = true;
+            }
+        }
+    };
+
+    const int wp0 = (wave % WAVES_P) * WP;
+    const int wc0 = (wave / WAVES_P) * WC;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int swz = (l32 >> 2) & 3;
+#pragma unroll
+    for (int i = 0; i < NSTAGES; i++)
+        if (i < nitems) issue(i);
+
+    Requant rq;
+    rq.init(a.shift, a.relu);
+    __syncthreads();   // bias_lds complete
+
+    // consumer position: unit (c_pt, c_ct) and step of the item being multiplied; reader position:
+    // input buffer and step of the item whose operands are read next
+    int c_pt = fastdiv(u0, prm.div_tc);
+    int c_ct = u0 - c_pt * prm.tiles_c;
+    int c_step = 0;
+    int r_ct = c_ct, r_step = 0, r_par = 0;
+
+    // accumulators start at the bias: register r of a lane belongs to channel kc + r
+    v16i acc[CT][PT];
+    auto reset_acc = [&](int ct) __attribute__((always_inline)) {
+#pragma unroll
+        for (int c = 0; c < CT; c++) {
+            const int4 *bp = (const int4 *)(bias_lds + ct * BC + wc0 + c * 32 + 16 * lh);
+#pragma unroll
+            for (int r4 = 0; r4 < 4; r4++) {
+                const int4 bv = bp[r4];
+#pragma unroll
+                for (int p = 0; p < PT; p++) {
+                    acc[c][p][4 * r4 + 0] = bv.x;
+                    acc[c][p][4 * r4 + 1] = bv.y;
+                    acc[c][p][4 * r4 + 2] = bv.z;
+                    acc[c][p][4 * r4 + 3] = bv.w;
+                }
+            }
+        }
+    };
+    reset_acc(c_ct);
+
+    struct Half {
+        v4i w[CT];
+        v4i x[PT];
+    };
+    Half f0, f1;
+    // both halves of the reader's item; advances the reader afterwards when `advance`
+    auto read_half = [&](Half &f, int kk, int stage) __attribute__((always_inline)) {
+        const v4i *xs = (const v4i *)lds + (r_par * nsteps + r_step) * SLAB_PIECES;
+        const v4i *ws = (const v4i *)lds + ring_piece0 + stage * WSTAGE_PIECES;
+        const int g = (kk * 2 + lh) ^ swz;   // physical piece
+#pragma unroll
+        for (int c = 0; c < CT; c++) f.w[c] = ws[(wc0 + c * 32 + l32) * kPieces + g];
+#pragma unroll
+        for (int p = 0; p < PT; p++) f.x[p] = xs[(wp0 + p * 32 + l32) * kPieces + g];
+    };
+    auto advance_reader = [&]() __attribute__((always_inline)) {
+        if (++r_step == nsteps) {
+            r_step = 0;
+            if (++r_ct == prm.tiles_c) {
+                r_ct = 0;
+                r_par ^= 1;
+            }
+        }
+    };
+    auto mfma_half = [&](const Half &f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int c = 0; c < CT; c++)
+#pragma unroll
+            for (int p = 0; p < PT; p++)
+                acc[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.w[c], f.x[p], acc[c][p], 0, 0, 0);
+    };
+    auto ring_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+    // ep_hist: bit k set when item i-1-k ended a unit (its epilogue issued kStoresPerUnit stores)
+    constexpr int kStoresPerUnit = CT * PT;
+    constexpr unsigned kHistMask = (1u << (NSTAGES - 1)) - 1u;
+    unsigned ep_hist = 0;
+    const unsigned lane_yoff = (unsigned)((wp0 + l32) * a.ldy + wc0 + 16 * lh);
+    auto finish_item = [&]() __attribute__((always_inline)) {
+        ep_hist = (ep_hist << 1) & kHistMask;
+        if (++c_step == nsteps) {
+            const unsigned tile_off = (unsigned)(c_pt * BP * a.ldy + c_ct * BC);
+#pragma unroll
+            for (int c = 0; c < CT; c++)
+#pragma unroll
+                for (int p = 0; p < PT; p++)
+                    store_piece(requant_tile_lane_fast(acc[c][p], rq), lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32), yrsrc);
+            ep_hist |= 1u;
+            c_step = 0;
+            if (++c_ct == prm.tiles_c) {
+                c_ct = 0;
+                ++c_pt;
+            }
+            reset_acc(c_ct);
+        }
+    };
+    // Item i multiplies operands that are already in registers and meanwhile reads those of item
+    // i+1: after the first k-step's matrix instructions the wavefront waits for its own loads of
+    // item i+1 and meets the others at the barrier; every wavefront has then also finished reading
+    // the weight stage of item i, which REFILL overwrites with item i + NSTAGES.
+    auto do_item = [&](auto refill, auto has_next, auto wait, int stage) __attribute__((always_inline)) {
+        const int next = stage + 1 == NSTAGES ? 0 : stage + 1;
+        mfma_half(f0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (decltype(has_next)::value) {
+            wait();
+            ring_barrier();
+            read_half(f0, 0, next);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_half(f1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (decltype(refill)::value) issue(stage);
+        if (decltype(has_next)::value) {
+            read_half(f1, 1, next);
+            advance_reader();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        finish_item();
+    };
+
+    // Vector-memory operations younger than the loads of item i+1 when item i waits for them:
+    // the weight loads of items i+2 .. i+NSTAGES-1, the input loads of those of them that fetch
+    // input (p_hist), and the stores of the epilogues of items i+1-NSTAGES .. i-1 (ep_hist; an
+    // item refills before its epilogue).  Loads and stores complete in issue order; operations
+    // that are not counted only make the wait longer.
+    auto steady_wait = [&]() __attribute__((always_inline)) {
+        const int cx = __builtin_popcount(p_hist & ((1u << (NSTAGES - 2)) - 1u));
+        const int ce = __builtin_popcount(ep_hist);
+        if (w_active) wait_loads_plus2<(NSTAGES - 2) * WS, XS, kStoresPerUnit>(cx, ce);
+        else wait_loads_plus2<0, XS, kStoresPerUnit>(cx, ce);
+    };
+    if (nitems > 0) {
+        wait_loads<0>();
+        ring_barrier();
+        read_half(f0, 0, 0);
+        read_half(f1, 1, 0);
+        advance_reader();
+    }
+    const int steady = nitems - NSTAGES;     // items that refill their stage
+    int it = 0;
+    for (; it + NSTAGES <= steady; it += NSTAGES) {
+#pragma unroll
+        for (int s = 0; s < NSTAGES; s++) do_item(std::true_type{}, std::true_type{}, steady_wait, s);
+    }
+    int stage = 0;   // it is a multiple of NSTAGES here
+    for (; it < steady; it++) {
+        do_item(std::true_type{}, std::true_type{}, steady_wait, stage);
+        stage = stage + 1 == NSTAGES ? 0 : stage + 1;
+    }
+    for (; it < nitems - 1; it++) {
+        // the ring drains: input loads and stores are not counted, which only lengthens the wait
+        const int ahead = nitems - 2 - it;   // items younger than the one awaited
+        do_item(std::false_type{}, std::true_type{}, [&]() __attribute__((always_inline)) {
+            if (w_active) wait_ahead<WS>(ahead);
+            else wait_loads<0>();
+        }, stage);
+        stage = stage + 1 == NSTAGES ? 0 : stage + 1;
+    }
+    if (it < nitems) do_item(std::false_type{}, std::false_type{}, steady_wait, stage);
+}
+
+inline hipError_t big_lds_pw(void (*k)(PwParams))
+{
+    return hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+}
+
+template <int BP, int BC, int WAVES_P, int WAVES_C>
+size_t pw_lds_bytes(const ConvArgs &a)
+{
+    return (size_t)2 * BP * a.C + (size_t)3 * BC * kStepBytes + (size_t)a.K * 4;
+}
+
+template <int BP, int BC, int WAVES_P, int WAVES_C, int PER_CU>
+hipError_t launch_pw(const ConvArgs &a, hipStream_t st)
+{
+    PwParams prm;
+    prm.a = a;
+    const long long M = (long long)a.N * a.P * a.Q;
+    prm.M = (int)M;
+    prm.nsteps = a.C / kStepBytes;
+    prm.tiles_c = a.K / BC;
+    const long long units = ((M + BP - 1) / BP) * prm.tiles_c;
+    if (units > 0x7fffffffLL) return hipErrorInvalidValue;
+    prm.units = (int)units;
+    prm.x_bytes = (unsigned)(M * a.C);
+    prm.w_bytes = (unsigned)((long long)a.K * a.C);
+    prm.y_bytes = (unsigned)(M * a.ldy);
+    prm.div_tc = make_fastdiv(prm.tiles_c);
+    int grid = PER_CU * kNumCU;
+    if (grid > prm.units) grid = prm.units;
+    const size_t lds_bytes = pw_lds_bytes<BP, BC, WAVES_P, WAVES_C>(a);
+    if (lds_bytes * PER_CU > (size_t)kLdsBytes) return hipErrorInvalidValue;
+    constexpr int occ = PER_CU * WAVES_P * WAVES_C / 4;
+    static const hipError_t attr = big_lds_pw(conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, occ>);
+    if (attr != hipSuccess) return attr;
+    conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, occ><<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// The input-resident form applies to unpadded 1x1 stride-1 layers with C a multiple of 64 whose
+// double-buffered input tile fits LDS (C <= 256), whose epilogue is the lean one, and which have at
+// least two items per pixel tile (an input buffer is refilled two items ahead of its next use).
+bool conv_pw_geometry_ok(const ConvArgs &a)
+{
+    if (a.groups != 1 || a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0) return false;
+    if (a.C % kStepBytes || a.C > 256) return false;
+    if (a.K % 64 || a.K > 4096) return false;
+    const int bc = a.K % 128 == 0 ? 128 : 64;
+    if ((a.K / bc) * (a.C / kStepBytes) < 2) return false;
+    const long long M = (long long)a.N * a.P * a.Q;
+    if (M * a.C >= (1LL << 31) || M * (long long)(a.ldy > a.K ? a.ldy : a.K) >= (1LL << 31) || M >= (1LL << 31) - 512) return false;
+    return true;
+}
+
+bool conv_pw_supports(const ConvArgs &a)
+{
+    if (!conv_pw_geometry_ok(a)) return false;
+    if (!(a.shift >= 1 && a.shift <= 23) || a.acc_out || !a.y || (a.ldy & 15) || ((uintptr_t)a.y & 15)) return false;
+    if (((uintptr_t)a.x & 15) || ((uintptr_t)a.w & 15)) return false;
+    return true;
+}
+
+hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st)
+{
+    // as many workgroups per compute unit as the two input buffers leave room for
+    if (a.K % 128 == 0) {
+        if (a.C == 64) return launch_pw<256, 128, 4, 2, 2>(a, st);
+        return launch_pw<256, 128, 4, 2, 1>(a, st);
+    }
+    if (a.C <= 128) return launch_pw<256, 64, 4, 1, 2>(a, st);
+    return launch_pw<256, 64, 4, 1, 1>(a, st);
+}
+
+}  // namespace dfq

@@ -11,9 +11,9 @@
 // The pixel operand is read straight from global memory in matrix-operand layout (each lane
 // one unaligned 16-byte load per block; neighbouring output pixels overlap heavily, so these
 // hit in L1/L2); only the small packed weight tensor lives in LDS, loaded once per workgroup,
-// which then walks over pixel tiles (persistent grid).  Runs that cross the left or right
-// image border are assembled from clamped 4-byte loads shifted into place, which both
-// zero-fills the padding and keeps every access inside the tensor.
+// which then walks over pixel tiles (persistent grid).  A run that crosses the left or right
+// image border is read from the nearest 16 bytes inside the row and shifted into place, which
+// both zero-fills the padding and keeps every access inside the tensor.
 #include "conv_epilogue.hpp"
 
 namespace dfq {
@@ -33,7 +33,7 @@ struct SmallCParams {
 };
 
 template <int CT>   // channel tile = CT * 32
-__global__ void __launch_bounds__(kThreads) conv_smallc_kernel(SmallCParams prm)
+__global__ void __launch_bounds__(kThreads, 2) conv_smallc_kernel(SmallCParams prm)
 {
     constexpr int BC = CT * 32;
     extern __shared__ uint4 wlds[];   // [R][BC][2] 16-byte pieces, piece index XOR-ed with bit 3 of k
@@ -111,23 +111,18 @@ __global__ void __launch_bounds__(kThreads) conv_smallc_kernel(SmallCParams prm)
                 if (!any_border[p]) {
                     if (row_ok) __builtin_memcpy(&v, src, 16);
                 } else if (row_ok) {
-                    // piece covers row bytes [o, o+16); keep only those inside [0, rowlen)
+                    // piece covers row bytes [o, o+16); bytes outside [0, rowlen) are padding.  The
+                    // 16 bytes are read from the nearest position that lies wholly inside the row
+                    // and shifted into place, which zero-fills the padding.
                     const int o = rb[p] + 16 * lh;
-                    const int8_t *row0 = src - o;
-#pragma unroll
-                    for (int d = 0; d < 4; d++) {
-                        int od = o + 4 * d;
-                        uint32_t wv = 0;
-                        if (od > -4 && od < prm.rowlen) {
-                            int oc = min(max(od, 0), prm.rowlen - 4);
-                            uint32_t t;
-                            __builtin_memcpy(&t, row0 + oc, 4);
-                            if (od < 0) wv = t << (8 * (-od));                 // bytes before the row are zeros
-                            else if (od > oc) wv = t >> (8 * (od - oc));        // bytes past the row are zeros
-                            else wv = t;
-                        }
-                        v[d] = (int)wv;
-                    }
+                    const int oc = min(max(o, 0), prm.rowlen - 16);
+                    unsigned __int128 t;
+                    __builtin_memcpy(&t, src - o + oc, 16);
+                    const int sh = o - oc;          // > 0: piece starts right of what was read
+                    if (sh >= 16 || sh <= -16) t = 0;
+                    else if (sh > 0) t >>= 8 * sh;
+                    else if (sh < 0) t <<= 8 * (-sh);
+                    __builtin_memcpy(&v, &t, 16);
                 }
                 xf[p] = v;
             }
@@ -162,7 +157,7 @@ bool conv_smallc_supports(const ConvArgs &a)
 {
     if (a.groups != 1) return false;
     if (a.S * a.C > 32) return false;
-    if (a.W * a.C < 32) return false;                       // clamped border loads need a row of >= 32 bytes
+    if (a.W * a.C < 32) return false;                       // clamped border loads need a row of >= 16 bytes
     if ((long long)a.N * a.P * a.Q >= (1LL << 31) - 512) return false;
     if (a.acc_out && ((uintptr_t)a.acc_out & 15)) return false;
     return true;

@@ -72,9 +72,11 @@ ConvCheck check_conv(const int8_t *x, const int8_t *w, const int32_t *b, int8_t 
     return r;
 }
 
-dfq_conv_variant select_variant(const ConvArgs &a)
+// geometry_only: the pointers, row pitch and shift of `a` are placeholders
+dfq_conv_variant select_variant(const ConvArgs &a, bool geometry_only = false)
 {
     if (conv_depthwise_supports(a)) return DFQ_CONV_DEPTHWISE;
+    if (geometry_only ? conv_pw_geometry_ok(a) : conv_pw_supports(a)) return DFQ_CONV_POINTWISE;
     if (conv_mfma_supports(a)) return DFQ_CONV_MFMA;
     if (conv_smallc_supports(a)) return DFQ_CONV_SMALLC;
     return DFQ_CONV_DIRECT;
@@ -141,6 +143,9 @@ dfq_status dfq_conv_q_variant(dfq_conv_variant variant, const int8_t *x, const i
         case DFQ_CONV_DEPTHWISE:
             if (!conv_depthwise_supports(c.a)) return DFQ_EUNSUPPORTED;
             return from_hip(launch_conv_depthwise(c.a, st));
+        case DFQ_CONV_POINTWISE:
+            if (!conv_pw_supports(c.a)) return DFQ_EUNSUPPORTED;
+            return from_hip(launch_conv_pw(c.a, st));
         case DFQ_CONV_SMALLC:
             if (!conv_smallc_supports(c.a)) return DFQ_EUNSUPPORTED;
             return from_hip(launch_conv_smallc(c.a, st));
@@ -163,7 +168,7 @@ dfq_conv_variant dfq_conv_q_select(int N, int H, int W, int C, int K, int R, int
     ConvCheck c = check_conv(nullptr, nullptr, nullptr, nullptr, nullptr, N, H, W, C, K, R, S, stride, pad, groups, K, f, f,
                              f, 0, false);
     if (c.st != DFQ_OK) return DFQ_CONV_AUTO;
-    return select_variant(c.a);
+    return select_variant(c.a, true);
 }
 
 dfq_status dfq_eltwise_q(const int8_t *a, dfq_fmt fa, const int8_t *b, dfq_fmt fb, int8_t *y, dfq_fmt fy, int32_t *acc_out,

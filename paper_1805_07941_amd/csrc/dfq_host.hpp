@@ -39,6 +39,9 @@ bool conv_mfma_supports(const ConvArgs &a);
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st);
 bool conv_depthwise_supports(const ConvArgs &a);
 hipError_t launch_conv_depthwise(const ConvArgs &a, hipStream_t st);
+bool conv_pw_geometry_ok(const ConvArgs &a);
+bool conv_pw_supports(const ConvArgs &a);
+hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st);
 bool conv_smallc_supports(const ConvArgs &a);
 hipError_t launch_conv_smallc(const ConvArgs &a, hipStream_t st);
 

@@ -109,6 +109,13 @@ CONV_SHAPES = [
     (1, 6, 6, 20, 10, 2, 3, 1, 1, 5),            # grouped, odd kernel
     (1, 33, 31, 16, 16, 3, 3, 1, 0, 1),          # no padding
     (1, 40, 40, 64, 256, 3, 3, 1, 1, 1),         # several tiles in both GEMM dimensions
+    # unpadded 1x1 stride 1: the input-resident pointwise kernel (several pixel tiles, ragged last one)
+    (3, 19, 17, 64, 256, 1, 1, 1, 0, 1),
+    (2, 23, 21, 256, 384, 1, 1, 1, 0, 1),
+    (2, 30, 30, 128, 64, 1, 1, 1, 0, 1),
+    (1, 16, 16, 192, 192, 1, 1, 1, 0, 1),
+    (2, 14, 14, 256, 1024, 1, 1, 1, 0, 1),
+    (1, 9, 9, 512, 128, 1, 1, 1, 0, 1),          # C too large for it: general dense kernel
 ]
 
 
@@ -118,7 +125,7 @@ def test_conv_q_random_shapes(B, shape):
     rng = np.random.default_rng(abs(hash(shape)) % (2 ** 31))
     x, w, b = _rand_conv(rng, N, H, W, C, K, R, S, g)
     xd, wd, bd = dev(x), dev(w), dev(b)
-    variants = [B.CONV_AUTO, B.CONV_DIRECT, B.CONV_MFMA, B.CONV_DEPTHWISE, B.CONV_SMALLC]
+    variants = [B.CONV_AUTO, B.CONV_DIRECT, B.CONV_MFMA, B.CONV_DEPTHWISE, B.CONV_SMALLC, B.CONV_POINTWISE]
     first = True
     for f_in, f_w, f_out, relu, bias in [(4, 7, 4, 1, True), (3, 6, 2, 0, True), (2, 2, 4, 0, False), (5, 5, -3, 1, True),
                                          (1, 1, 6, 1, True)]:
