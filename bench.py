@@ -72,6 +72,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=128, help="images the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the per-launch events (pure step timing)")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a HIP graph")
+    ap.add_argument("--no-fuse", action="store_true", help="run every residual add as its own dfq_eltwise_q call")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
@@ -94,7 +95,7 @@ def main():
     x_host = net.input_float()
     x = torch.from_numpy(x_host).to(dev)
     qz, _ = gnet.calibrate(net, x[:args.calib].contiguous(), keep_tensors=False)
-    plan = gnet.Plan(net, qz, args.batch, keep_all=False)
+    plan = gnet.Plan(net, qz, args.batch, keep_all=False, fuse=not args.no_fuse)
 
     convs = conv_nodes(net)
     H0, W0, C0 = net.in_shape
@@ -105,36 +106,24 @@ def main():
     matrix_core = (B.CONV_MFMA, B.CONV_POINTWISE)   # the dense kernels on the int8 matrix cores
     mfma_nodes = [nd for nd in convs if variant_of[nd.name] in matrix_core]
 
-    # instrumented pass: the same call sequence with an event pair around each MFMA convolution
+    # instrumented pass: the plan's own call list with an event pair around each launch of the
+    # matrix-core convolution kernels
     events = []
+    mfma_names = {nd.name for nd in mfma_nodes}
 
-    def run_step(record: bool):
-        if not record:
-            plan.run(x)
-            return
-        netq, t = plan.qz, plan.buf
-        B.quantize(x, netq.frac[net.input_name], out=t[net.input_name])
-        for nd in net.nodes:
-            if nd.op == "conv":
-                src = nd.srcs[0]
-                mf = variant_of[nd.name] in matrix_core
-                if mf:
-                    e0, e1 = event_pool.pop(), event_pool.pop()
-                    e0.record()
-                B.conv_q(t[src], netq.w[nd.name], netq.b[nd.name], netq.frac[src], netq.w_frac[nd.name],
-                         netq.frac[nd.dst], nd.stride, nd.pad, nd.groups, nd.relu, out=t[nd.dst])
-                if mf:
-                    e1.record()
-                    events.append((nd.name, e0, e1))
-            elif nd.op == "eltwise":
-                a, b2 = nd.srcs
-                B.eltwise_q(t[a], netq.frac[a], t[b2], netq.frac[b2], netq.frac[nd.dst], nd.relu, out=t[nd.dst])
-            else:
-                src = nd.srcs[0]
-                B.pool_q(t[src], "max" if nd.op == "maxpool" else "avg", nd.R, nd.stride, nd.pad, netq.frac[src],
-                         netq.frac[nd.dst], out=t[nd.dst])
-        out = t[net.output_name]
-        B.dequantize(out.view(args.batch, -1), netq.frac[net.output_name], out=plan.logits)
+    def run_step_recorded():
+        st = B._stream(None)
+        for (fn, cargs), name in zip(plan._calls_for(x), plan.call_nodes):
+            mf = name in mfma_names and fn.__name__ in ("dfq_conv_q", "dfq_conv_q_add")
+            if mf:
+                e0, e1 = event_pool.pop(), event_pool.pop()
+                e0.record()
+            rc = fn(*cargs, st)
+            if rc != B.OK:
+                raise B.DfqError(rc, fn.__name__)
+            if mf:
+                e1.record()
+                events.append((name, e0, e1))
 
     # ---- timed region: exactly K steps, bracketed by synchronize on both sides
     step = (lambda: plan.run(x)) if args.no_graph else (lambda: plan.run_graph(x))
@@ -157,9 +146,11 @@ def main():
         event_pool = [torch.cuda.Event(enable_timing=True) for _ in range(2 * len(mfma_nodes) * args.steps)]
         for _ in range(args.steps):
             torch.cuda._sleep(6_000_000)
-            run_step(True)
+            run_step_recorded()
         torch.cuda.synchronize()
 
+    n_joins = sum(1 for nd in net.nodes if nd.op == "eltwise")
+    n_fused = sum(1 for fn, _ in plan._calls_for(x) if fn.__name__ == "dfq_conv_q_add")
     macs_step = net.macs_per_image() * args.batch
     tops = 2 * macs_step / (ms_per_step * 1e-3) / 1e12
     imgs = args.batch / (ms_per_step * 1e-3)
@@ -203,6 +194,8 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "launch": "per-call from Python" if args.no_graph else "HIP graph replay of the fixed call sequence",
+        "joins": "each residual add its own dfq_eltwise_q call" if args.no_fuse else
+                 "%d of %d residual adds run inside the convolution in front of them (dfq_conv_q_add)" % (n_fused, n_joins),
         "config": {"workload": "configs[4]: ResNet-50-shaped int8 network, 224x224x3, batch %d, formats from a "
                                "single-batch calibrate() on %d images" % (args.batch, args.calib),
                    "global_batch": args.batch},

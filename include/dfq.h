@@ -63,7 +63,7 @@ typedef enum {
     DFQ_CONV_SMALLC = 4,   /* implicit GEMM for few input channels (first layers); groups == 1, S*C <= 32 */
     DFQ_CONV_POINTWISE = 5 /* int8 MFMA with the input tile resident in LDS; unpadded 1x1 stride 1, groups == 1,
                               C in {64, 128, 192, 256}, K % 64 == 0, (K / (K % 128 ? 64 : 128)) * (C / 64) >= 2,
-                              16-byte aligned x, w, y, ldy % 16 == 0, rescale shift f_in + f_w - f_out in [1, 23],
+                              16-byte aligned x, w, y, ldy % 16 == 0, rescale shift f_in + f_w - f_out in [0, 23],
                               no acc_out */
 } dfq_conv_variant;
 
@@ -111,8 +111,24 @@ dfq_status dfq_conv_q_variant(dfq_conv_variant variant,
                               int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
                               int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu, dfq_stream stream);
 
+/* Convolution followed by an element-wise add, in one kernel (Sec. 3: adjacent operations are
+ * merged; Eq. 10 for the add).  The result is exactly that of
+ *     dfq_conv_q(x, w, b, t, NULL, ..., ldy = K, fmt_in, fmt_w, fmt_mid, relu_mid)   followed by
+ *     dfq_eltwise_q(t, fmt_mid, other, fmt_other, y, fmt_out, NULL, N*P*Q*K, relu_out)
+ * without the int8 tensor t ever being stored: each convolution result is rounded to fmt_mid in
+ * registers, aligned with the code of `other` at the finer of the two scales, and the sum is
+ * rounded once to fmt_out.  `other`: device, int8 [N, P, Q, K] with ld_other bytes between pixels
+ * (>= K), read only, must not overlap y or x.  All other arguments as for dfq_conv_q.
+ * Returns DFQ_EUNSUPPORTED - and does nothing - when no fused kernel covers the call (the caller
+ * then issues the two calls above); the fused kernel needs what DFQ_CONV_POINTWISE needs, `other`
+ * 16-byte aligned with ld_other % 16 == 0, and max(f_mid, f_other) - f_out in [0, 23]. */
+dfq_status dfq_conv_q_add(const int8_t *x, const int8_t *w, const int32_t *b, const int8_t *other, int8_t *y,
+                          int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                          int ldy, int ld_other, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_mid, int relu_mid,
+                          dfq_fmt fmt_other, dfq_fmt fmt_out, int relu_out, dfq_stream stream);
+
 /* The variant dfq_conv_q would run for this geometry (host, pure) when the tensors are 16-byte
- * aligned, ldy == K, the rescale shift lies in [1, 23] and no accumulator dump is asked for;
+ * aligned, ldy == K, the rescale shift lies in [0, 23] and no accumulator dump is asked for;
  * DFQ_CONV_AUTO if the geometry is invalid. */
 dfq_conv_variant dfq_conv_q_select(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups);
 

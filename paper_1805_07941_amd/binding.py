@@ -23,7 +23,7 @@ CONV_VARIANT_NAMES = {CONV_AUTO: "auto", CONV_DIRECT: "direct", CONV_MFMA: "mfma
 
 EXPORTS = [
     "dfq_status_string", "dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q",
-    "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
+    "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
     "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
 ]
@@ -66,6 +66,7 @@ def lib():
     L.dfq_conv_q.argtypes = conv_args
     L.dfq_conv_q_variant.argtypes = [i32] + conv_args
     L.dfq_conv_q_select.argtypes = [i32] * 10
+    L.dfq_conv_q_add.argtypes = [vp, vp, vp, vp, vp] + [i32] * 12 + [Fmt, Fmt, Fmt, i32, Fmt, Fmt, i32, vp]
     L.dfq_eltwise_q.argtypes = [vp, Fmt, vp, Fmt, vp, Fmt, vp, sz, i32, vp]
     L.dfq_concat_q.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, Fmt, sz, vp]
     L.dfq_pool_q.argtypes = [vp, vp, i32] + [i32] * 7 + [Fmt, Fmt, vp]
@@ -74,7 +75,7 @@ def lib():
     L.dfq_fmt_from_absmax_f32.argtypes = [C.c_float, C.POINTER(Fmt)]
     L.dfq_fmt_from_absmax_i32.argtypes = [i64, C.c_int32, C.POINTER(Fmt)]
     for name in ("dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q", "dfq_conv_q_variant",
-                 "dfq_conv_q_select", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q", "dfq_absmax_f32",
+                 "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q", "dfq_absmax_f32",
                  "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32"):
         getattr(L, name).restype = i32
     L.dfq_beta_max.restype = i64
@@ -170,6 +171,32 @@ def conv_q(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], f_in: in
                                   fmt(f_in), fmt(f_w), fmt(f_out), int(bool(relu)), _stream(stream))
     _check(st, "dfq_conv_q")
     return y, acc
+
+
+def conv_q_add(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], other: torch.Tensor, f_in: int, f_w: int,
+               f_mid: int, relu_mid: bool, f_other: int, f_out: int, relu_out: bool, stride: int = 1, pad: int = 0,
+               groups: int = 1, out: Optional[torch.Tensor] = None, stream=None):
+    """Convolution and the element-wise add behind it in one kernel: what conv_q(..., f_mid, relu_mid)
+    followed by eltwise_q(that, f_mid, other, f_other, f_out, relu_out) gives.  Returns the int8
+    result, or None when no fused kernel covers the call (nothing was launched)."""
+    _dev(x, torch.int8, "x"); _dev(w, torch.int8, "w"); _dev(other, torch.int8, "other")
+    if b is not None:
+        _dev(b, torch.int32, "b")
+    N, H, W, Cc = x.shape
+    K, R, S, Cg = w.shape
+    if Cg * groups != Cc:
+        raise DfqError(ESHAPE, "conv_q_add (weight shape does not match C/groups)")
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    if tuple(other.shape) != (N, P, Q, K):
+        raise DfqError(ESHAPE, "conv_q_add (second operand's shape)")
+    y = out if out is not None else torch.empty((N, P, Q, K), dtype=torch.int8, device=x.device)
+    st = lib().dfq_conv_q_add(_ptr(x), _ptr(w), _ptr(b), _ptr(other), _ptr(y), N, H, W, Cc, K, R, S, stride, pad, groups,
+                              K, K, fmt(f_in), fmt(f_w), fmt(f_mid), int(bool(relu_mid)), fmt(f_other), fmt(f_out),
+                              int(bool(relu_out)), _stream(stream))
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, "dfq_conv_q_add")
+    return y
 
 
 def conv_q_select(N, H, W, Cc, K, R, S, stride, pad, groups) -> int:

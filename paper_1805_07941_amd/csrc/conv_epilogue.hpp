@@ -10,31 +10,34 @@ namespace dfq {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-// Per-launch constants of the requantization.  For 1 <= shift <= 23 the fast form is used:
+// Per-launch constants of the requantization.  For 0 <= shift <= 23 the fast form is used:
 // the sum is first clamped to +-127 * 2^shift (anything beyond saturates to +-127 anyway; with
 // ReLU the lower bound is 0), which makes  (v + 2^(shift-1) - 1 + bit_shift(v)) >> shift
 // overflow-free and its result lie in [-127, 127] without a second clamp; that expression is
-// round-half-even of v / 2^shift for two's complement v.
+// round-half-even of v / 2^shift for two's complement v.  With shift == 0 nothing is rounded:
+// the added constant is 0 and the rounding bit is read with a field width of 0, i.e. as 0.
 struct Requant {
     int shift;
     int relu;
     int lo, hi;      // pre-clamp bounds (fast form)
     int bias_add;    // 2^(shift-1) - 1
+    unsigned odd_width;   // width of the field that holds bit `shift` of the sum: 1, or 0 when shift == 0
     bool fast;
 
     __device__ __forceinline__ void init(int s, int r)
     {
         shift = s;
         relu = r;
-        fast = s >= 1 && s <= 23;
+        fast = s >= 0 && s <= 23;
         hi = fast ? (127 << s) : 0;
         lo = fast ? (r ? 0 : -(127 << s)) : 0;
-        bias_add = fast ? ((1 << (s - 1)) - 1) : 0;
+        bias_add = (fast && s > 0) ? ((1 << (s - 1)) - 1) : 0;
+        odd_width = s > 0 ? 1u : 0u;
     }
     __device__ __forceinline__ int fast_one(int v) const
     {
         asm("v_med3_i32 %0, %1, %2, %3" : "=v"(v) : "v"(v), "s"(lo), "v"(hi));   // clamp to [lo, hi] (lo <= hi)
-        const int odd = (int)__builtin_amdgcn_ubfe((unsigned)v, (unsigned)shift, 1u);
+        const int odd = (int)__builtin_amdgcn_ubfe((unsigned)v, (unsigned)shift, odd_width);
         return (v + bias_add + odd) >> shift;                      // v_add3_u32, v_ashrrev_i32
     }
     // The same for four sums at once, the four results packed into one word of int8: the final
@@ -45,7 +48,7 @@ struct Requant {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             asm("v_med3_i32 %0, %1, %2, %3" : "=v"(t[i]) : "v"(t[i]), "s"(lo), "v"(hi));
-            t[i] = t[i] + bias_add + (int)__builtin_amdgcn_ubfe((unsigned)t[i], (unsigned)shift, 1u);
+            t[i] = t[i] + bias_add + (int)__builtin_amdgcn_ubfe((unsigned)t[i], (unsigned)shift, odd_width);
         }
         uint32_t w;
         asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD" : "=v"(w) : "v"(shift), "v"(t[0]));
@@ -72,6 +75,23 @@ __device__ __forceinline__ uint4 requant_tile_lane_fast(const v16i &v, const Req
 {
     return make_uint4(rq.fast_four(v[0], v[1], v[2], v[3]), rq.fast_four(v[4], v[5], v[6], v[7]),
                       rq.fast_four(v[8], v[9], v[10], v[11]), rq.fast_four(v[12], v[13], v[14], v[15]));
+}
+// The same followed by the fused add of Eq. 10: the sixteen int8 results of the convolution (kept as
+// integers, never stored) and the sixteen codes of the second operand in `other` are aligned to the
+// finer of their two scales, summed and rounded once more with rq2.
+__device__ __forceinline__ uint4 requant_add_tile_lane(const v16i &v, const Requant &rq, const v4i &other, int sa, int sb,
+                                                       const Requant &rq2)
+{
+    uint32_t out[4];
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        int t[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++)
+            t[e] = (int)((unsigned)rq.fast_one(v[4 * j + e]) << sa) + (int)((unsigned)byte_of((uint32_t)other[j], e) << sb);
+        out[j] = rq2.fast_four(t[0], t[1], t[2], t[3]);
+    }
+    return make_uint4(out[0], out[1], out[2], out[3]);
 }
 __device__ __forceinline__ void store_tile_lane_fast(const v16i &v, const ConvArgs &a, const Requant &rq, long long m, int kc)
 {

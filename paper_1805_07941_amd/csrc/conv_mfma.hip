@@ -53,7 +53,7 @@ struct MfmaParams {
 // PW ("pointwise", needs UT): R = S = 1, stride 1, no padding - output pixel m reads input pixel m,
 // so a tile needs no coordinate decoding and no border masks.
 // GENERAL: the epilogue may meet a ragged channel tail, an unaligned or strided-odd output row, a
-// shift outside [1, 23] or an accumulator dump; the launcher picks the lean instantiation
+// shift outside [0, 23] or an accumulator dump; the launcher picks the lean instantiation
 // (GENERAL = false) whenever none of these applies.  OCC: wavefronts per SIMD to fit registers for.
 template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool PW, bool GENERAL, int OCC>
 __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(MfmaParams prm)
@@ -427,7 +427,7 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     static_assert(lds_bytes * PER_CU <= kLdsBytes, "rings do not fit the LDS");
 
     const bool ut = a.C % kStepBytes == 0;
-    const bool general = !(a.shift >= 1 && a.shift <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
+    const bool general = !(a.shift >= 0 && a.shift <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
                            ((uintptr_t)a.y & 15) == 0 && a.K % BC == 0 && y_bytes < (1LL << 31));
     constexpr int occ = PER_CU * WAVES_P * WAVES_C / 4;
     using K = void (*)(MfmaParams);

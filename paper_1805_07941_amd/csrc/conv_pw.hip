@@ -34,22 +34,27 @@ struct PwParams {
     int nsteps;       // C / 64
     int tiles_c;      // K / BC
     int units;        // pixel tiles * channel tiles
-    unsigned x_bytes, w_bytes, y_bytes;
+    unsigned x_bytes, w_bytes, y_bytes, add_bytes;
     FastDiv div_tc;
 };
 
-// at most BASE + SA * ca + SB * cb outstanding vector-memory operations, ca and cb in [0, 2]
+// at most BASE + SA * ca + SB * cb outstanding vector-memory operations, ca in [0, 2], cb in [0, 4]
 template <int BASE, int SA, int SB>
 __device__ __forceinline__ void wait_loads_plus2(int ca, int cb)
 {
     switch (cb) {
         case 0: wait_loads_plus<BASE, SA>(min(ca, 2)); break;
         case 1: wait_loads_plus<BASE + SB, SA>(min(ca, 2)); break;
-        default: wait_loads_plus<BASE + 2 * SB, SA>(min(ca, 2)); break;
+        case 2: wait_loads_plus<BASE + 2 * SB, SA>(min(ca, 2)); break;
+        case 3: wait_loads_plus<BASE + 3 * SB, SA>(min(ca, 2)); break;
+        default: wait_loads_plus<BASE + 4 * SB, SA>(min(ca, 2)); break;
     }
 }
 
-template <int BP, int BC, int WAVES_P, int WAVES_C, int OCC>
+// FUSE: an element-wise add (Eq. 10) follows the convolution and is taken in the epilogue: the
+// second operand's 16 codes per lane and tile are fetched into registers one unit ahead, right
+// behind the stores of the previous unit's epilogue.
+template <int BP, int BC, int WAVES_P, int WAVES_C, bool FUSE, int OCC>
 __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(PwParams prm)
 {
     constexpr int NSTAGES = 3;                            // depth of the weight ring
@@ -61,6 +66,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
     constexpr int XS = BP / (RPC * NW), WS = (BC + RPC * NW - 1) / (RPC * NW);
     constexpr bool kPartialW = BC < RPC * NW;
     static_assert(XS * RPC * NW == BP && (kPartialW || WS * RPC * NW == BC) && BC % 16 == 0, "whole chunks");
+    static_assert(WS <= XS, "the wait for the second operand rounds the refill's loads down to 0, WS, XS or WS + XS");
     static_assert(WP % 32 == 0 && WC % 32 == 0, "tile shape");
     constexpr int SLAB_PIECES = BP * kPieces;             // one 64-byte step of the input tile
     constexpr int WSTAGE_PIECES = BC * kPieces;           // one 64-byte step of the weight tile
@@ -93,6 +99,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
     const v4i xrsrc = make_rsrc(a.x, prm.x_bytes);
     const v4i wrsrc = make_rsrc(a.w, prm.w_bytes);
     const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, (int)prm.y_bytes, 0x00020000);
+    const v4i arsrc = make_rsrc(FUSE ? a.add : a.x, FUSE ? prm.add_bytes : 0u);
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char *)(char *)&lds[0];
     const int ring_piece0 = 2 * nsteps * SLAB_PIECES;
     int *bias_lds = (int *)(lds + ring_piece0 + NSTAGES * WSTAGE_PIECES);
@@ -164,8 +171,9 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
     for (int i = 0; i < NSTAGES; i++)
         if (i < nitems) issue(i);
 
-    Requant rq;
+    Requant rq, rq2;
     rq.init(a.shift, a.relu);
+    rq2.init(FUSE ? a.add_shift : 1, a.add_relu);
     __syncthreads();   // bias_lds complete
 
     // consumer position: unit (c_pt, c_ct) and step of the item being multiplied; reader position:
@@ -229,20 +237,45 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
     };
     auto ring_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
-    // ep_hist: bit k set when item i-1-k ended a unit (its epilogue issued kStoresPerUnit stores)
+    // ep_hist: bit k set when item i-1-k ended a unit (its epilogue issued kStoresPerUnit stores
+    // and, with FUSE, behind them as many loads of the next unit's second operand)
     constexpr int kStoresPerUnit = CT * PT;
     constexpr unsigned kHistMask = (1u << (NSTAGES - 1)) - 1u;
     unsigned ep_hist = 0;
     const unsigned lane_yoff = (unsigned)((wp0 + l32) * a.ldy + wc0 + 16 * lh);
+    const unsigned lane_aoff = (unsigned)((wp0 + l32) * a.ldadd + wc0 + 16 * lh);
+    static_assert(!FUSE || CT * PT == 4, "the fused form handles four tiles per wavefront");
+    v4i other[4];                     // FUSE: the second operand of the current unit
+    int refill_ops = 0;               // vector-memory operations the refill of this item issued
+    int units_left = nunits;          // units not yet written out
+    auto fetch_other = [&]() __attribute__((always_inline)) {   // for unit (c_pt, c_ct)
+        const unsigned tile_off = (unsigned)(c_pt * BP * a.ldadd + c_ct * BC);
+#pragma unroll
+        for (int c = 0; c < CT; c++)
+#pragma unroll
+            for (int p = 0; p < PT; p++)
+                load_piece_to_regs(other[c * PT + p], lane_aoff + tile_off + (unsigned)(p * 32 * a.ldadd + c * 32), arsrc);
+    };
     auto finish_item = [&]() __attribute__((always_inline)) {
         ep_hist = (ep_hist << 1) & kHistMask;
         if (++c_step == nsteps) {
             const unsigned tile_off = (unsigned)(c_pt * BP * a.ldy + c_ct * BC);
+            if (FUSE) {
+                // the second operand was fetched at the end of the previous unit; of what was issued
+                // since, this item's refill is the youngest part
+                if (refill_ops >= WS + XS) wait_loads_for<WS + XS>(other[0], other[1], other[2], other[3]);
+                else if (refill_ops >= XS) wait_loads_for<XS>(other[0], other[1], other[2], other[3]);
+                else if (refill_ops >= WS) wait_loads_for<WS>(other[0], other[1], other[2], other[3]);
+                else wait_loads_for<0>(other[0], other[1], other[2], other[3]);
+            }
 #pragma unroll
             for (int c = 0; c < CT; c++)
 #pragma unroll
-                for (int p = 0; p < PT; p++)
-                    store_piece(requant_tile_lane_fast(acc[c][p], rq), lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32), yrsrc);
+                for (int p = 0; p < PT; p++) {
+                    const unsigned off = lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32);
+                    if (FUSE) store_piece(requant_add_tile_lane(acc[c][p], rq, other[c * PT + p], a.add_sa, a.add_sb, rq2), off, yrsrc);
+                    else store_piece(requant_tile_lane_fast(acc[c][p], rq), off, yrsrc);
+                }
             ep_hist |= 1u;
             c_step = 0;
             if (++c_ct == prm.tiles_c) {
@@ -250,6 +283,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
                 ++c_pt;
             }
             reset_acc(c_ct);
+            if (FUSE && --units_left > 0) fetch_other();
         }
     };
     // Item i multiplies operands that are already in registers and meanwhile reads those of item
@@ -268,7 +302,11 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
         __builtin_amdgcn_sched_barrier(0);
         mfma_half(f1);
         __builtin_amdgcn_sched_barrier(0);
-        if (decltype(refill)::value) issue(stage);
+        refill_ops = 0;
+        if (decltype(refill)::value) {
+            refill_ops = (w_active ? WS : 0) + (p_loadx ? XS : 0);
+            issue(stage);
+        }
         if (decltype(has_next)::value) {
             read_half(f1, 1, next);
             advance_reader();
@@ -279,15 +317,17 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
 
     // Vector-memory operations younger than the loads of item i+1 when item i waits for them:
     // the weight loads of items i+2 .. i+NSTAGES-1, the input loads of those of them that fetch
-    // input (p_hist), and the stores of the epilogues of items i+1-NSTAGES .. i-1 (ep_hist; an
-    // item refills before its epilogue).  Loads and stores complete in issue order; operations
-    // that are not counted only make the wait longer.
+    // input (p_hist), and the stores - with FUSE also the second-operand loads behind them - of
+    // the epilogues of items i+1-NSTAGES .. i-1 (ep_hist; an item refills before its epilogue).
+    // Loads and stores complete in issue order; operations that are not counted only make the
+    // wait longer.
     auto steady_wait = [&]() __attribute__((always_inline)) {
         const int cx = __builtin_popcount(p_hist & ((1u << (NSTAGES - 2)) - 1u));
-        const int ce = __builtin_popcount(ep_hist);
+        const int ce = __builtin_popcount(ep_hist) * (FUSE ? 2 : 1);
         if (w_active) wait_loads_plus2<(NSTAGES - 2) * WS, XS, kStoresPerUnit>(cx, ce);
         else wait_loads_plus2<0, XS, kStoresPerUnit>(cx, ce);
     };
+    if (FUSE && nitems > 0) fetch_other();
     if (nitems > 0) {
         wait_loads<0>();
         ring_barrier();
@@ -332,6 +372,7 @@ size_t pw_lds_bytes(const ConvArgs &a)
 template <int BP, int BC, int WAVES_P, int WAVES_C, int PER_CU>
 hipError_t launch_pw(const ConvArgs &a, hipStream_t st)
 {
+    constexpr bool kCanFuse = (BP / WAVES_P / 32) * (BC / WAVES_C / 32) == 4;
     PwParams prm;
     prm.a = a;
     const long long M = (long long)a.N * a.P * a.Q;
@@ -344,15 +385,25 @@ hipError_t launch_pw(const ConvArgs &a, hipStream_t st)
     prm.x_bytes = (unsigned)(M * a.C);
     prm.w_bytes = (unsigned)((long long)a.K * a.C);
     prm.y_bytes = (unsigned)(M * a.ldy);
+    prm.add_bytes = a.add ? (unsigned)(M * a.ldadd) : 0u;
     prm.div_tc = make_fastdiv(prm.tiles_c);
     int grid = PER_CU * kNumCU;
     if (grid > prm.units) grid = prm.units;
     const size_t lds_bytes = pw_lds_bytes<BP, BC, WAVES_P, WAVES_C>(a);
     if (lds_bytes * PER_CU > (size_t)kLdsBytes) return hipErrorInvalidValue;
     constexpr int occ = PER_CU * WAVES_P * WAVES_C / 4;
-    static const hipError_t attr = big_lds_pw(conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, occ>);
+    if (a.add) {
+        if constexpr (kCanFuse) {
+            static const hipError_t attr = big_lds_pw(conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, true, occ>);
+            if (attr != hipSuccess) return attr;
+            conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, true, occ><<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
+            return hipGetLastError();
+        }
+        return hipErrorInvalidValue;
+    }
+    static const hipError_t attr = big_lds_pw(conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, false, occ>);
     if (attr != hipSuccess) return attr;
-    conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, occ><<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
+    conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, false, occ><<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
     return hipGetLastError();
 }
 
@@ -376,8 +427,14 @@ bool conv_pw_geometry_ok(const ConvArgs &a)
 bool conv_pw_supports(const ConvArgs &a)
 {
     if (!conv_pw_geometry_ok(a)) return false;
-    if (!(a.shift >= 1 && a.shift <= 23) || a.acc_out || !a.y || (a.ldy & 15) || ((uintptr_t)a.y & 15)) return false;
+    if (!(a.shift >= 0 && a.shift <= 23) || a.acc_out || !a.y || (a.ldy & 15) || ((uintptr_t)a.y & 15)) return false;
     if (((uintptr_t)a.x & 15) || ((uintptr_t)a.w & 15)) return false;
+    if (a.add) {
+        // the fused add: second operand addressable like y, final shift in the range of the fast rounding
+        if (((uintptr_t)a.add & 15) || (a.ldadd & 15) || a.ldadd < a.K) return false;
+        if ((long long)a.N * a.P * a.Q * a.ldadd >= (1LL << 31)) return false;
+        if (!(a.add_shift >= 0 && a.add_shift <= 23) || a.add_sa < 0 || a.add_sa > 22 || a.add_sb < 0 || a.add_sb > 22) return false;
+    }
     return true;
 }
 

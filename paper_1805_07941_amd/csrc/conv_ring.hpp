@@ -45,6 +45,23 @@ __device__ __forceinline__ void store_piece(uint4 d, unsigned voffset, __amdgpu_
     __builtin_amdgcn_raw_buffer_store_b128(data, rsrc, (int)voffset, 0, 0);
 }
 
+// 16-byte load into registers through a buffer resource, outside the compiler's wait-count
+// bookkeeping like the LDS loads: the data may be used only behind wait_loads_for<N>() on the same
+// registers.  A lane whose offset is outside the buffer gets zeros.
+__device__ __forceinline__ void load_piece_to_regs(v4i &dst, unsigned voffset, v4i rsrc)
+{
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=&v"(dst) : "v"(voffset), "s"(rsrc) : "memory");
+}
+
+// wait until at most N vector-memory operations are outstanding; the registers passed are marked as
+// written here, so that no use of them can be scheduled ahead of the wait
+template <int N>
+__device__ __forceinline__ void wait_loads_for(v4i &a, v4i &b, v4i &c, v4i &d)
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt %4" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8)));
+}
+
 // wait until at most N vector-memory operations of this wavefront are outstanding
 template <int N>
 __device__ __forceinline__ void wait_loads()

@@ -19,6 +19,15 @@ struct ConvArgs {
     int ldy;             // bytes between consecutive output pixels of y
     int shift;           // f_in + f_w - f_out
     int relu;
+    // Fused element-wise add (Eq. 10) behind the convolution, or add == null: the convolution's
+    // own int8 result (format f_out, `shift` and `relu` above) and the int8 tensor `add` of the
+    // same pixels and channels are brought to their finer scale by left shifts, summed, and the
+    // sum is rounded once by add_shift into what is stored in y.
+    const int8_t *add = nullptr;
+    int ldadd = 0;               // bytes between consecutive pixels of `add`
+    int add_sa = 0, add_sb = 0;  // left shifts of the convolution result and of `add`
+    int add_shift = 0;           // finer scale's fractional length minus that of y
+    int add_relu = 0;
 };
 
 hipError_t launch_quantize(const float *x, int8_t *q, size_t n, int frac, hipStream_t st);

@@ -5,6 +5,7 @@
 // nothing is reused.
 #include "dfq_device.hpp"
 #include "dfq_host.hpp"
+#include "conv_epilogue.hpp"
 
 namespace dfq {
 
@@ -158,6 +159,31 @@ __global__ void __launch_bounds__(kBlock) eltwise_vec16(const uint4 *__restrict_
     }
 }
 
+// The common case - int8 result only, final shift in [0, 23] - with the branch-free rounding
+// shift of the convolution epilogue: per element two sign-extracting field reads, a shift, a
+// shift-add, then clamp / rounding bit / add / shift-into-byte.
+__global__ void __launch_bounds__(kBlock) eltwise_fast16(const uint4 *__restrict__ a, const uint4 *__restrict__ b,
+                                                          uint4 *__restrict__ y, size_t n16, EltParams p)
+{
+    Requant rq;
+    rq.init(p.s, p.relu);
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += (size_t)gridDim.x * kBlock) {
+        const uint4 va = a[i], vb = b[i];
+        const uint32_t wa[4] = {va.x, va.y, va.z, va.w};
+        const uint32_t wb[4] = {vb.x, vb.y, vb.z, vb.w};
+        uint32_t out[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            int t[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++)
+                t[e] = (int)((unsigned)byte_of(wa[j], e) << p.sa) + (int)((unsigned)byte_of(wb[j], e) << p.sb);
+            out[j] = rq.fast_four(t[0], t[1], t[2], t[3]);
+        }
+        y[i] = make_uint4(out[0], out[1], out[2], out[3]);
+    }
+}
+
 __global__ void __launch_bounds__(kBlock) eltwise_scalar(const int8_t *__restrict__ a, const int8_t *__restrict__ b,
                                                           int8_t *__restrict__ y, int32_t *__restrict__ acc, size_t n,
                                                           EltParams p)
@@ -179,7 +205,8 @@ hipError_t launch_eltwise(const int8_t *a, int fa, const int8_t *b, int fb, int8
     size_t n16 = vec ? n / 16 : 0;
     if (n16) {
         int g = grid_for(n16);
-        if (y && acc) eltwise_vec16<true, true><<<g, kBlock, 0, st>>>((const uint4 *)a, (const uint4 *)b, (uint4 *)y, (int4 *)acc, n16, p);
+        if (y && !acc && p.s >= 0 && p.s <= 23) eltwise_fast16<<<g, kBlock, 0, st>>>((const uint4 *)a, (const uint4 *)b, (uint4 *)y, n16, p);
+        else if (y && acc) eltwise_vec16<true, true><<<g, kBlock, 0, st>>>((const uint4 *)a, (const uint4 *)b, (uint4 *)y, (int4 *)acc, n16, p);
         else if (y) eltwise_vec16<true, false><<<g, kBlock, 0, st>>>((const uint4 *)a, (const uint4 *)b, (uint4 *)y, nullptr, n16, p);
         else eltwise_vec16<false, true><<<g, kBlock, 0, st>>>((const uint4 *)a, (const uint4 *)b, nullptr, (int4 *)acc, n16, p);
     }

@@ -111,8 +111,12 @@ class Plan:
     a pass is a fixed sequence of library calls with no allocation and no host
     synchronization."""
 
-    def __init__(self, net, qz: Quantized, batch: int, device="cuda:0", keep_all: bool = True):
+    def __init__(self, net, qz: Quantized, batch: int, device="cuda:0", keep_all: bool = True, fuse: bool = False):
+        """fuse: a convolution whose only consumer is the element-wise add that follows it directly
+        is run together with that add by one dfq_conv_q_add call where a fused kernel covers it
+        (same result; the convolution's own int8 tensor is then never produced)."""
         self.net, self.qz, self.batch, self.device = net, qz, batch, device
+        self.fused: Dict[int, int] = self._fusable_pairs() if fuse else {}   # conv node index -> add node index
         self.buf: Dict[str, torch.Tensor] = {}
         H, W, Cc = net.shapes[net.input_name]
         self.buf[net.input_name] = torch.empty((batch, H, W, Cc), dtype=torch.int8, device=device)
@@ -126,24 +130,52 @@ class Plan:
         self.logits = torch.empty((batch, P * Q * K), dtype=torch.float32, device=device)
         self._calls, self._calls_key, self._graph, self._keep = None, None, None, None
 
+    def _fusable_pairs(self) -> Dict[int, int]:
+        """Convolution nodes directly followed by an element-wise add that is the only reader of
+        their result, filtered by whether the library has a fused kernel for the call."""
+        net, qz = self.net, self.qz
+        readers: Dict[str, int] = {}
+        for nd in net.nodes:
+            for s in nd.srcs:
+                readers[s] = readers.get(s, 0) + 1
+        pairs = {}
+        for i in range(len(net.nodes) - 1):
+            c, e = net.nodes[i], net.nodes[i + 1]
+            if c.op != "conv" or e.op != "eltwise" or c.dst not in e.srcs or readers.get(c.dst, 0) != 1:
+                continue
+            if c.dst == net.output_name or e.srcs[0] == e.srcs[1]:
+                continue
+            pairs[i] = i + 1
+        return pairs
+
     def _assign_pooled(self):
         """Reuses buffers whose tensor is dead (sized in bytes), to keep the footprint small."""
         net = self.net
         last = _last_use(net)
         free: list = []
         owner: Dict[str, torch.Tensor] = {}
+        skip = set(self.fused.values())          # an add fused into its convolution: buffer taken at the convolution
         for idx, nd in enumerate(net.nodes):
-            P, Q, K = net.shapes[nd.dst]
+            if idx in skip:
+                for s in nd.srcs:
+                    if last.get(s) == idx and s in owner and s != net.input_name and s != net.output_name:
+                        free.append(owner[s])
+                continue
+            if idx in self.fused:
+                nd_dst = net.nodes[self.fused[idx]].dst
+            else:
+                nd_dst = nd.dst
+            P, Q, K = net.shapes[nd_dst]
             need = self.batch * P * Q * K
             pick = None
             for i, st in enumerate(free):
                 if st.numel() >= need and (pick is None or st.numel() < free[pick].numel()):
                     pick = i
             storage = free.pop(pick) if pick is not None else torch.empty(need, dtype=torch.int8, device=self.device)
-            self.buf[nd.dst] = storage[:need].view(self.batch, P, Q, K)
-            owner[nd.dst] = storage
+            self.buf[nd_dst] = storage[:need].view(self.batch, P, Q, K)
+            owner[nd_dst] = storage
             for s in nd.srcs:
-                if last.get(s) == idx and s != net.input_name and s != net.output_name:
+                if last.get(s) == idx and s in owner and s != net.input_name and s != net.output_name:
                     free.append(owner[s])
 
     # ---- execution -------------------------------------------------------------------- #
@@ -153,13 +185,41 @@ class Plan:
         L = B.lib()
         net, qz, t = self.net, self.qz, self.buf
         calls = []
+        names = []         # per call: the node it belongs to (None for the input and output conversions)
         keep = []          # ctypes arrays referenced by pointer must outlive the calls
         f = B.fmt
         if net.input_is_int8:
             t[net.input_name] = x
         else:
             calls.append((L.dfq_quantize, (x.data_ptr(), t[net.input_name].data_ptr(), x.numel(), f(qz.frac[net.input_name]))))
-        for nd in net.nodes:
+            names.append(None)
+        fused_adds = set()
+        for idx, nd in enumerate(net.nodes):
+            if idx in fused_adds:
+                continue
+            if nd.op == "conv" and idx in self.fused:
+                # one call for the convolution and the add behind it; probed once here, outside any
+                # capture: where no fused kernel covers the call, the two calls are issued instead
+                add = net.nodes[self.fused[idx]]
+                other = add.srcs[0] if add.srcs[1] == nd.dst else add.srcs[1]
+                src = nd.srcs[0]
+                N, H, W, Cc = t[src].shape
+                K = nd.K
+                args = (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(), t[other].data_ptr(),
+                        t[add.dst].data_ptr(), N, H, W, Cc, K, nd.R, nd.R, nd.stride, nd.pad, nd.groups, K, K,
+                        f(qz.frac[src]), f(qz.w_frac[nd.name]), f(qz.frac[nd.dst]), int(nd.relu), f(qz.frac[other]),
+                        f(qz.frac[add.dst]), int(add.relu))
+                rc = L.dfq_conv_q_add(*args, B._stream(None))
+                if rc == B.OK:
+                    calls.append((L.dfq_conv_q_add, args))
+                    names.append(nd.name)
+                    fused_adds.add(self.fused[idx])
+                    continue
+                if rc != B.EUNSUPPORTED:
+                    raise B.DfqError(rc, "dfq_conv_q_add")
+                if nd.dst not in t:
+                    P, Q, Kd = net.shapes[nd.dst]
+                    t[nd.dst] = torch.empty((self.batch, P, Q, Kd), dtype=torch.int8, device=self.device)
             if nd.op == "conv":
                 src = nd.srcs[0]
                 N, H, W, Cc = t[src].shape
@@ -186,9 +246,12 @@ class Plan:
                 mode = B.POOL_MAX if nd.op == "maxpool" else B.POOL_AVG
                 calls.append((L.dfq_pool_q, (t[src].data_ptr(), t[nd.dst].data_ptr(), mode, N, H, W, Cc, nd.R, nd.stride,
                                              nd.pad, f(qz.frac[src]), f(qz.frac[nd.dst]))))
+            names.append(nd.name)
         out = t[net.output_name]
         calls.append((L.dfq_dequantize, (out.data_ptr(), self.logits.data_ptr(), out.numel(), f(qz.frac[net.output_name]))))
+        names.append(None)
         self._keep = keep
+        self.call_nodes = names
         return calls
 
     def _calls_for(self, x: torch.Tensor):

@@ -152,6 +152,31 @@ def test_config3_and_4_networks(G, which):
     assert np.abs(logits).max() > 0
 
 
+def test_fused_joins_give_the_same_logits(G):
+    """A plan that runs each residual add inside the convolution in front of it must reproduce the
+    unfused plan bit for bit (and through it the oracle, which the test above pins)."""
+    B, gnet = G
+    net = wl.resnet50(batch=16, hw=96, classes=100)
+    x = dev(net.input_float())
+    qz, _ = gnet.calibrate(net, x[:4].contiguous(), keep_tensors=False)
+    plain = gnet.Plan(net, qz, 16)
+    fused = gnet.Plan(net, qz, 16, fuse=True)
+    ref = host(plain.run(x)).copy()
+    got = host(fused.run(x)).copy()
+    assert len(fused.fused) == 16
+    n_fused = sum(1 for fn, _ in fused._calls if fn.__name__ == "dfq_conv_q_add")
+    assert n_fused >= 4                              # joins behind pointwise layers with C <= 256 and a rounding step left
+    assert np.array_equal(got, ref) and np.abs(ref).max() > 0
+    # the add's output tensors agree as well
+    for i, j in fused.fused.items():
+        name = net.nodes[j].dst
+        assert np.array_equal(host(fused.buf[name]), host(plain.buf[name])), name
+    # pooled buffers, replayed from a graph
+    pooled = gnet.Plan(net, qz, 16, keep_all=False, fuse=True)
+    assert np.array_equal(host(pooled.run(x)), ref)
+    assert np.array_equal(host(pooled.run_graph(x)), ref)
+
+
 def test_graph_replay_matches_eager(G):
     """The captured call sequence must give the eager result on every replay, with eager work
     and synchronizations in between."""

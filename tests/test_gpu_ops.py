@@ -143,6 +143,35 @@ def test_conv_q_random_shapes(B, shape):
         first = False
 
 
+@pytest.mark.parametrize("shape", [(3, 19, 17, 64, 256), (2, 23, 21, 256, 384), (2, 30, 30, 128, 64), (2, 14, 14, 256, 1024)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_conv_q_add_equals_conv_then_eltwise(B, shape):
+    """The fused call against the oracle's convolution followed by the oracle's add, for format
+    combinations that put the finer scale on either operand, with and without the ReLUs."""
+    N, H, W, C, K = shape
+    rng = np.random.default_rng(sum(shape))
+    x, w, b = _rand_conv(rng, N, H, W, C, K, 1, 1, 1)
+    other = rng.integers(-128, 128, (N, H, W, K)).astype(np.int8)
+    xd, wd, bd, od = dev(x), dev(w), dev(b), dev(other)
+    ran = 0
+    for f_in, f_w, f_mid, relu_mid, f_other, f_out, relu_out in [(4, 7, 4, 0, 5, 3, 1), (3, 6, 2, 0, 1, 0, 1), (5, 5, 3, 1, 3, 2, 0),
+                                                              (4, 7, 5, 0, 2, 1, 1), (4, 7, 4, 0, 4, 4, 1)]:
+        mid, _ = orc.conv_q(x, w, b, f_in, f_w, f_mid, 1, 0, 1, bool(relu_mid))
+        ref, _ = orc.eltwise_q(mid, f_mid, other, f_other, f_out, bool(relu_out))
+        got = B.conv_q_add(xd, wd, bd, od, f_in, f_w, f_mid, bool(relu_mid), f_other, f_out, bool(relu_out))
+        assert got is not None
+        assert np.array_equal(host(got), ref), (f_in, f_w, f_mid, relu_mid, f_other, f_out, relu_out)
+        ran += 1
+    assert ran == 5
+
+
+def test_conv_q_add_declines_what_it_does_not_cover(B):
+    rng = np.random.default_rng(77)
+    x, w, b = _rand_conv(rng, 1, 8, 8, 64, 128, 3, 3, 1)          # 3x3: not a pointwise layer
+    other = dev(rng.integers(-128, 128, (1, 8, 8, 128)).astype(np.int8))
+    assert B.conv_q_add(dev(x), dev(w), dev(b), other, 4, 7, 4, False, 4, 3, True, 1, 1) is None
+
+
 def test_conv_q_writes_into_a_channel_slice(B):
     rng = np.random.default_rng(102)
     x, w, b = _rand_conv(rng, 2, 10, 10, 32, 48, 3, 3, 1)
