@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the per-launch events (pure step timing)")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a HIP graph")
     ap.add_argument("--no-fuse", action="store_true", help="run every residual add as its own dfq_eltwise_q call")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three 256 MiB device copies (a kernel of known traffic, to scale HBM counters by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
@@ -149,6 +151,14 @@ def main():
             run_step_recorded()
         torch.cuda.synchronize()
 
+    if args.copy_probe:
+        src = torch.zeros(256 << 20, dtype=torch.int8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            B.concat_q([src.view(-1, 16)], [0], 0, out=dst.view(-1, 16))   # format-preserving concat of one branch = a copy
+        torch.cuda.synchronize()
+        del src, dst
+
     n_joins = sum(1 for nd in net.nodes if nd.op == "eltwise")
     n_fused = sum(1 for fn, _ in plan._calls_for(x) if fn.__name__ == "dfq_conv_q_add")
     macs_step = net.macs_per_image() * args.batch
@@ -163,26 +173,47 @@ def main():
             dur.setdefault(name, []).append(e0.elapsed_time(e1))
         ops = 0.0
         tsum = 0.0
+        fused_names = {name for (fn, _), name in zip(plan._calls_for(x), plan.call_nodes) if fn.__name__ == "dfq_conv_q_add"}
+        # launches by what bounds them at the published peaks: ops / 5 POP/s against bytes / 8 TB/s
+        cls = {"mfma": dict(launches=0, ms=0.0, ops=0.0, bytes=0.0, roof_ms=0.0),
+               "hbm": dict(launches=0, ms=0.0, ops=0.0, bytes=0.0, roof_ms=0.0)}
         for nd in mfma_nodes:
             ms = sum(dur[nd.name]) / len(dur[nd.name])
             o = 2.0 * node_macs(net, nd) * args.batch
             C = net.shapes[nd.srcs[0]][2]
             by = node_bytes(net, nd) * args.batch + nd.K * nd.R * nd.R * C + 4 * nd.K
+            if nd.name in fused_names:            # the fused add reads one more tensor of the output's size
+                P, Q, K = net.shapes[nd.dst]
+                by += P * Q * K * args.batch
             ops += o
             tsum += ms
+            t_m, t_h = o / (INT8_MFMA_PEAK_TOPS * 1e12) * 1e3, by / (HBM_PEAK_GBS * 1e9) * 1e3
+            c = cls["mfma" if t_m >= t_h else "hbm"]
+            c["launches"] += 1; c["ms"] += ms; c["ops"] += o; c["bytes"] += by; c["roof_ms"] += max(t_m, t_h)
             per_layer.append(dict(layer=nd.name, us=round(ms * 1e3, 1), tops=round(o / ms / 1e9, 1),
                                   gbs=round(by / ms / 1e6, 1), min_us=round(min(dur[nd.name]) * 1e3, 1),
                                   max_us=round(max(dur[nd.name]) * 1e3, 1)))
         achieved = ops / (tsum * 1e-3) / 1e12
+        # HBM bytes per launch of these kernels as the memory counters saw them (the committed summary
+        # of two counter runs of this command, scaled by the copy probe), or null
         traffic = None
-        tpath = os.path.join(ROOT, "profiles", "conv_mfma_traffic.json")
+        tpath = os.path.join(ROOT, "profiles", "bench_resnet50_b256_hbm_traffic.txt")
         if os.path.exists(tpath):
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+            import re
+            m = re.search(r"^hbm_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(tpath).read(), re.M)
+            traffic = float(m.group(1)) if m else None
         roofline = dict(bound="mfma", kernel="conv_mfma_kernel + conv_pw_kernel (dense int8 matrix-core convolutions, %d launches per step)" % len(mfma_nodes),
                         achieved=round(achieved, 2), peak=INT8_MFMA_PEAK_TOPS, unit="TOP/s",
                         frac=round(achieved / INT8_MFMA_PEAK_TOPS, 4), traffic=traffic,
                         avg_launch_us=round(tsum / len(mfma_nodes) * 1e3, 2),
-                        ops_per_launch=ops / len(mfma_nodes), share_of_step=round(tsum / ms_per_step, 3))
+                        ops_per_launch=ops / len(mfma_nodes), share_of_step=round(tsum / ms_per_step, 3),
+                        by_bound={
+                            "mfma": dict(launches=cls["mfma"]["launches"], us=round(cls["mfma"]["ms"] * 1e3, 1),
+                                         achieved_tops=round(cls["mfma"]["ops"] / max(cls["mfma"]["ms"], 1e-9) / 1e9, 1),
+                                         frac=round(cls["mfma"]["roof_ms"] / max(cls["mfma"]["ms"], 1e-9), 4)),
+                            "hbm": dict(launches=cls["hbm"]["launches"], us=round(cls["hbm"]["ms"] * 1e3, 1),
+                                        achieved_gbs=round(cls["hbm"]["bytes"] / max(cls["hbm"]["ms"], 1e-9) / 1e6, 1),
+                                        frac=round(cls["hbm"]["roof_ms"] / max(cls["hbm"]["ms"], 1e-9), 4))})
 
     cpu = None
     if args.cpu_sample > 0:

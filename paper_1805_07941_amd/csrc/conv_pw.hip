@@ -442,7 +442,8 @@ hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st)
 {
     // as many workgroups per compute unit as the two input buffers leave room for
     if (a.K % 128 == 0) {
-        if (a.C == 64) return launch_pw<256, 128, 4, 2, 2>(a, st);
+        // (the fused epilogue needs more registers than four wavefronts per SIMD leave it)
+        if (a.C == 64 && !a.add) return launch_pw<256, 128, 4, 2, 2>(a, st);
         return launch_pw<256, 128, 4, 2, 1>(a, st);
     }
     if (a.C <= 128) return launch_pw<256, 64, 4, 1, 2>(a, st);
