@@ -465,10 +465,15 @@ bool conv_mfma_supports(const ConvArgs &a)
 
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st)
 {
-    // 256 x 64 tiles (four wavefronts of 64 x 64) when there are at most 64 output channels,
-    // otherwise 256 x 128 (eight wavefronts of 64 x 64); three ring stages, two workgroups per CU
-    if (a.K <= 64) return launch_cfg<256, 64, 4, 1, 3, 2>(a, st);
-    return launch_cfg<256, 128, 4, 2, 3, 2>(a, st);
+    // Wavefronts always own 64 x 64 outputs.  Measured choices at batch 256:
+    // K <= 64: 256 x 64 tiles (four wavefronts); for kernels larger than 1x1 three workgroups per CU
+    //          with a two-stage ring beat two with three stages (more independent workgroups to
+    //          overlap epilogues with matrix work);
+    // K > 64:  256 x 128 tiles (eight wavefronts), two workgroups per CU, for kernels larger than 1x1;
+    //          for 1x1 kernels (few items per tile) 128 x 128 tiles (four wavefronts), three per CU.
+    const bool pointwise = a.R == 1 && a.S == 1;
+    if (a.K <= 64) return pointwise ? launch_cfg<256, 64, 4, 1, 3, 2>(a, st) : launch_cfg<256, 64, 4, 1, 2, 3>(a, st);
+    return pointwise ? launch_cfg<128, 128, 2, 2, 3, 3>(a, st) : launch_cfg<256, 128, 4, 2, 3, 2>(a, st);
 }
 
 }  // namespace dfq
