@@ -102,6 +102,9 @@ CONV_SHAPES = [
     (5, 1, 1, 256, 100, 1, 1, 1, 0, 1),          # fully connected
     (1, 20, 20, 3, 32, 3, 3, 2, 1, 1),           # stem-like
     (1, 23, 23, 3, 64, 7, 7, 2, 3, 1),           # stem-like 7x7
+    (2, 72, 72, 3, 64, 7, 7, 2, 3, 1),           # stem-like, rows long enough for the row-staging kernel
+    (1, 40, 44, 3, 32, 3, 3, 1, 1, 1),           # the same kernel at stride 1, ragged last tile
+    (1, 70, 68, 4, 64, 5, 5, 2, 2, 1),           # spans too long for it: direct-load kernel
     (2, 10, 10, 32, 32, 3, 3, 1, 1, 32),         # depthwise
     (2, 11, 9, 64, 64, 3, 3, 2, 1, 64),          # depthwise stride 2
     (1, 9, 9, 24, 24, 3, 3, 1, 1, 24),           # depthwise, C % 16 != 0
