@@ -379,6 +379,8 @@ hipError_t launch_pool(const int8_t *x, int8_t *y, int mode, int N, int H, int W
     PoolParams p{N, H, W, C, P, Q, k, stride, pad, mode, fout - fin};
     int vec = 16;
     while (vec > 1 && (C % vec || !aligned(x, vec) || !aligned(y, vec))) vec /= 4;
+    // few outputs (a global pool): narrower lanes give the machine four times the wavefronts
+    if (vec == 16 && (size_t)N * P * Q * (C / 16) < (size_t)256 * 1024) vec = 4;
     size_t total = (size_t)N * P * Q * (C / vec);
     int g = grid_for(total);
     if (vec == 16) pool_kernel<16><<<g, kBlock, 0, st>>>(x, y, p);
