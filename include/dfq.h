@@ -62,7 +62,8 @@ typedef enum {
     DFQ_CONV_DEPTHWISE = 3,/* groups == C == K, channel-vectorized VALU kernel; C % 4 == 0 */
     DFQ_CONV_SMALLC = 4,   /* implicit GEMM for few input channels (first layers); groups == 1, S*C <= 32 */
     DFQ_CONV_POINTWISE = 5 /* int8 MFMA with the input tile resident in LDS; unpadded 1x1 stride 1, groups == 1,
-                              C in {64, 128, 192, 256}, K % 64 == 0, (K / (K % 128 ? 64 : 128)) * (C / 64) >= 2,
+                              C in {64, 128, 192, 256}, K % 64 == 0, K <= 4096, (K / BC) * (C / 64) >= 2 and
+                              512*C + 192*BC + 4*K <= 160 KB of LDS with BC = (K % 128 ? 64 : 128),
                               16-byte aligned x, w, y, ldy % 16 == 0, rescale shift f_in + f_w - f_out in [0, 23],
                               no acc_out */
 } dfq_conv_variant;

@@ -419,6 +419,7 @@ bool conv_pw_geometry_ok(const ConvArgs &a)
     if (a.K % 64 || a.K > 4096) return false;
     const int bc = a.K % 128 == 0 ? 128 : 64;
     if ((a.K / bc) * (a.C / kStepBytes) < 2) return false;
+    if ((size_t)2 * 256 * a.C + (size_t)3 * bc * kStepBytes + (size_t)a.K * 4 > (size_t)kLdsBytes) return false;   // input buffers, ring, bias
     const long long M = (long long)a.N * a.P * a.Q;
     if (M * a.C >= (1LL << 31) || M * (long long)(a.ldy > a.K ? a.ldy : a.K) >= (1LL << 31) || M >= (1LL << 31) - 512) return false;
     return true;

@@ -118,6 +118,7 @@ CONV_SHAPES = [
     (2, 30, 30, 128, 64, 1, 1, 1, 0, 1),
     (1, 16, 16, 192, 192, 1, 1, 1, 0, 1),
     (2, 14, 14, 256, 1024, 1, 1, 1, 0, 1),
+    (1, 3, 3, 64, 256, 1, 1, 1, 0, 1),           # fewer pixels than one tile
     (1, 9, 9, 512, 128, 1, 1, 1, 0, 1),          # C too large for it: general dense kernel
 ]
 
