@@ -52,8 +52,9 @@ __device__ __forceinline__ void wait_loads_plus2(int ca, int cb)
 }
 
 // FUSE: an element-wise add (Eq. 10) follows the convolution and is taken in the epilogue: the
-// second operand's 16 codes per lane and tile are fetched into registers one unit ahead, right
-// behind the stores of the previous unit's epilogue.
+// second operand's 16 codes per lane and tile are fetched into registers one unit ahead, at the
+// start of the previous unit's epilogue, so that even with one item per unit the whole epilogue
+// (a few microseconds of vector work) lies between the fetch and its use.
 template <int BP, int BC, int WAVES_P, int WAVES_C, bool FUSE, int OCC>
 __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(PwParams prm)
 {
@@ -238,35 +239,42 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
     auto ring_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
     // ep_hist: bit k set when item i-1-k ended a unit (its epilogue issued kStoresPerUnit stores
-    // and, with FUSE, behind them as many loads of the next unit's second operand)
+    // and, with FUSE, ahead of them as many loads of the next unit's second operand)
     constexpr int kStoresPerUnit = CT * PT;
     constexpr unsigned kHistMask = (1u << (NSTAGES - 1)) - 1u;
     unsigned ep_hist = 0;
     const unsigned lane_yoff = (unsigned)((wp0 + l32) * a.ldy + wc0 + 16 * lh);
     const unsigned lane_aoff = (unsigned)((wp0 + l32) * a.ldadd + wc0 + 16 * lh);
     static_assert(!FUSE || CT * PT == 4, "the fused form handles four tiles per wavefront");
-    v4i other[4];                     // FUSE: the second operand of the current unit
+    v4i other[4], other_next[4];      // FUSE: the second operand of the current unit / of the one after it
     int refill_ops = 0;               // vector-memory operations the refill of this item issued
     int units_left = nunits;          // units not yet written out
-    auto fetch_other = [&]() __attribute__((always_inline)) {   // for unit (c_pt, c_ct)
-        const unsigned tile_off = (unsigned)(c_pt * BP * a.ldadd + c_ct * BC);
+    auto fetch_other = [&](int pt, int ct) __attribute__((always_inline)) {
+        const unsigned tile_off = (unsigned)(pt * BP * a.ldadd + ct * BC);
 #pragma unroll
         for (int c = 0; c < CT; c++)
 #pragma unroll
             for (int p = 0; p < PT; p++)
-                load_piece_to_regs(other[c * PT + p], lane_aoff + tile_off + (unsigned)(p * 32 * a.ldadd + c * 32), arsrc);
+                load_piece_to_regs(other_next[c * PT + p], lane_aoff + tile_off + (unsigned)(p * 32 * a.ldadd + c * 32), arsrc);
     };
     auto finish_item = [&]() __attribute__((always_inline)) {
         ep_hist = (ep_hist << 1) & kHistMask;
         if (++c_step == nsteps) {
             const unsigned tile_off = (unsigned)(c_pt * BP * a.ldy + c_ct * BC);
             if (FUSE) {
-                // the second operand was fetched at the end of the previous unit; of what was issued
-                // since, this item's refill is the youngest part
-                if (refill_ops >= WS + XS) wait_loads_for<WS + XS>(other[0], other[1], other[2], other[3]);
-                else if (refill_ops >= XS) wait_loads_for<XS>(other[0], other[1], other[2], other[3]);
-                else if (refill_ops >= WS) wait_loads_for<WS>(other[0], other[1], other[2], other[3]);
-                else wait_loads_for<0>(other[0], other[1], other[2], other[3]);
+                // this unit's second operand was fetched at the start of the previous unit's epilogue (or
+                // ahead of the loop); that epilogue's stores and this item's refill are younger for certain
+                constexpr int S = kStoresPerUnit;
+                if (refill_ops >= WS + XS) wait_loads_for<WS + XS + S>(other_next[0], other_next[1], other_next[2], other_next[3]);
+                else if (refill_ops >= XS) wait_loads_for<XS + S>(other_next[0], other_next[1], other_next[2], other_next[3]);
+                else if (refill_ops >= WS) wait_loads_for<WS + S>(other_next[0], other_next[1], other_next[2], other_next[3]);
+                else wait_loads_for<S>(other_next[0], other_next[1], other_next[2], other_next[3]);
+#pragma unroll
+                for (int t = 0; t < 4; t++) other[t] = other_next[t];
+                if (--units_left > 0) {
+                    const bool wrap = c_ct + 1 == prm.tiles_c;
+                    fetch_other(wrap ? c_pt + 1 : c_pt, wrap ? 0 : c_ct + 1);
+                }
             }
 #pragma unroll
             for (int c = 0; c < CT; c++)
@@ -283,7 +291,6 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
                 ++c_pt;
             }
             reset_acc(c_ct);
-            if (FUSE && --units_left > 0) fetch_other();
         }
     };
     // Item i multiplies operands that are already in registers and meanwhile reads those of item
@@ -327,7 +334,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
         if (w_active) wait_loads_plus2<(NSTAGES - 2) * WS, XS, kStoresPerUnit>(cx, ce);
         else wait_loads_plus2<0, XS, kStoresPerUnit>(cx, ce);
     };
-    if (FUSE && nitems > 0) fetch_other();
+    if (FUSE && nitems > 0) fetch_other(c_pt, c_ct);
     if (nitems > 0) {
         wait_loads<0>();
         ring_barrier();
