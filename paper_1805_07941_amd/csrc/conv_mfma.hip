@@ -10,12 +10,13 @@
 // A workgroup (4 or 8 wavefronts) is persistent: it walks over BP-pixel x BC-channel output
 // tiles (tile numbers blockIdx, blockIdx + gridDim, ...).  The j range of each tile is walked
 // in steps of 64 bytes through a ring of LDS stages that is filled by direct global->LDS
-// buffer loads (no register staging) issued nstages-1 steps ahead - across tile boundaries, so
+// buffer loads (no register staging) issued nstages steps ahead - across tile boundaries, so
 // the first loads of the next tile are in flight while the current one is multiplied and
 // written out (HBM latency here is about four steps of matrix work).  A wavefront waits only
 // for the loads of the step it is about to read (its own counter of outstanding vector memory
-// operations, then one workgroup barrier per step), and the operands of step i+1 are read from
-// LDS into a second register set while step i is multiplied.  Each wavefront-wide load fills 16
+// operations, in which the stores of the epilogues are counted too, then one workgroup barrier
+// per step), and the operands of step i+1 are read from LDS into the registers of the half of
+// step i that has just been multiplied.  Each wavefront-wide load fills 16
 // LDS rows of 64 bytes; which 16-byte piece of the step a lane fetches is XOR-ed with bits of
 // its row, so the 128-bit operand reads spread over all banks without padding.  Lanes whose
 // piece lies outside the image (padding), past the last pixel, past K or past R*S*C are given
@@ -43,7 +44,6 @@ struct MfmaParams {
     int nsteps;       // ceil(Kgemm / 64)
     int tiles_c;      // channel tiles
     int tiles;        // pixel tiles * channel tiles
-    int nstages;      // depth of the LDS ring
     unsigned x_bytes, w_bytes, y_bytes;
     FastDiv div_pq, div_q, div_tc;
 };
@@ -410,7 +410,6 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     const long long tiles = ((M + BP - 1) / BP) * prm.tiles_c;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     prm.tiles = (int)tiles;
-    prm.nstages = NSTAGES;
     prm.x_bytes = (unsigned)((long long)a.N * a.H * a.W * a.C);
     prm.w_bytes = (unsigned)((long long)a.K * prm.Kgemm);
     const long long y_bytes = M * a.ldy;
