@@ -120,6 +120,10 @@ CONV_SHAPES = [
     (2, 14, 14, 256, 1024, 1, 1, 1, 0, 1),
     (1, 3, 3, 64, 256, 1, 1, 1, 0, 1),           # fewer pixels than one tile
     (1, 9, 9, 512, 128, 1, 1, 1, 0, 1),          # C too large for it: general dense kernel
+    # K a multiple of 256 and enough pixels for 192 tiles of 256 x 256: the dense kernel's largest tile shape
+    (4, 111, 112, 16, 256, 3, 3, 1, 1, 1),       # C % 64 != 0, ragged last pixel tile
+    (2, 112, 111, 64, 512, 1, 1, 1, 0, 1),       # two channel tiles, 1x1
+    (4, 112, 111, 64, 256, 3, 3, 1, 1, 1),       # 3x3, taps uniform per step
 ]
 
 
