@@ -73,6 +73,7 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the per-launch events (pure step timing)")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a HIP graph")
     ap.add_argument("--no-fuse", action="store_true", help="run every residual add as its own dfq_eltwise_q call")
+    ap.add_argument("--no-mfma-rate", action="store_true", help="skip the register-only matrix-instruction rate probe")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three 256 MiB device copies (a kernel of known traffic, to scale HBM counters by)")
     args = ap.parse_args()
@@ -159,6 +160,30 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- what the matrix instruction itself sustains on this chip for three kinds of operand data
+    # (register-only loop, nothing else running): the ceiling under the chip's power limit
+    mfma_rate = None
+    if not args.no_mfma_rate:
+        mid = [nd for nd in mfma_nodes if nd.R == 3 and net.shapes[nd.srcs[0]][2] == 256]
+        sink = torch.empty(2048 * 512, dtype=torch.int32, device=dev)
+        rnd_a = torch.randint(-128, 128, (1 << 16,), dtype=torch.int8, device=dev)
+        rnd_b = torch.randint(-128, 128, (1 << 16,), dtype=torch.int8, device=dev)
+        zero = torch.zeros(1 << 16, dtype=torch.int8, device=dev)
+        sets = [("zeros", zero, zero), ("uniform_random_int8", rnd_a, rnd_b)]
+        if mid:
+            nd = mid[len(mid) // 2]
+            sets.append(("network_data", qz.w[nd.name].reshape(-1), plan.buf[nd.srcs[0]].reshape(-1)))
+        mfma_rate = {"unit": "TOP/s", "what": "v_mfma_i32_32x32x32_i8 in a register-only loop, 2048 workgroups of 8 wavefronts; "
+                     "network_data = weights and input activations of a 3x3 layer of the pass"}
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for label, a_t, b_t in sets:
+            B.mfma_rate_probe(a_t, b_t, sink, 2048, 2000)          # warm-up: clocks settle under this load
+            e0.record()
+            ops_probe = B.mfma_rate_probe(a_t, b_t, sink, 2048, 8000)
+            e1.record()
+            torch.cuda.synchronize()
+            mfma_rate[label] = round(ops_probe / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+
     n_joins = sum(1 for nd in net.nodes if nd.op == "eltwise")
     n_fused = sum(1 for fn, _ in plan._calls_for(x) if fn.__name__ == "dfq_conv_q_add")
     macs_step = net.macs_per_image() * args.batch
@@ -213,7 +238,8 @@ def main():
                                          frac=round(cls["mfma"]["roof_ms"] / max(cls["mfma"]["ms"], 1e-9), 4)),
                             "hbm": dict(launches=cls["hbm"]["launches"], us=round(cls["hbm"]["ms"] * 1e3, 1),
                                         achieved_gbs=round(cls["hbm"]["bytes"] / max(cls["hbm"]["ms"], 1e-9) / 1e6, 1),
-                                        frac=round(cls["hbm"]["roof_ms"] / max(cls["hbm"]["ms"], 1e-9), 4))})
+                                        frac=round(cls["hbm"]["roof_ms"] / max(cls["hbm"]["ms"], 1e-9), 4))},
+                        mfma_rate_measured=mfma_rate)
 
     cpu = None
     if args.cpu_sample > 0:

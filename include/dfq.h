@@ -181,6 +181,18 @@ int64_t dfq_mac_max_len(int q, int64_t bx, int64_t ex, int64_t by, int64_t ey); 
 int     dfq_add_acc_bits(int64_t N, int64_t bx, int64_t ex);                            /* Eq. 12 */
 int64_t dfq_add_max_len(int q, int64_t bx, int64_t ex);                                 /* Eq. 13 */
 
+/* ---- measurement aid (no operation of the paper): rate of the int8 matrix instruction of the
+ * dense convolution kernels on caller-supplied operand bytes, in a loop that touches registers
+ * only.  The sustained rate depends on the operand values (the chip's power limit), so this is
+ * the ceiling a convolution on such data could reach with free operand delivery.
+ * a_codes: DEVICE, 16-byte aligned, at least 16 KiB read; b_codes: DEVICE, 16-byte aligned, at
+ * least 32 KiB read; sink: DEVICE, blocks * 512 words, overwritten (content meaningless).
+ * 1 <= blocks <= 65536 workgroups of eight wavefronts, 1 <= iters <= 2^24 rounds of eight
+ * instructions per wavefront.  *ops_out (host, may be NULL) receives the number of operations
+ * (2 per multiply-add) the launch performs; the caller times the launch on `stream`. */
+dfq_status dfq_mfma_rate_probe(const int8_t *a_codes, const int8_t *b_codes, int32_t *sink, int blocks,
+                               int iters, double *ops_out, dfq_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

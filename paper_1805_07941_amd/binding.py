@@ -24,7 +24,7 @@ CONV_VARIANT_NAMES = {CONV_AUTO: "auto", CONV_DIRECT: "direct", CONV_MFMA: "mfma
 EXPORTS = [
     "dfq_status_string", "dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q",
     "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
-    "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32",
+    "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_mfma_rate_probe",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
 ]
 
@@ -74,9 +74,10 @@ def lib():
     L.dfq_absmax_i32.argtypes = [vp, sz, i32, vp, vp]
     L.dfq_fmt_from_absmax_f32.argtypes = [C.c_float, C.POINTER(Fmt)]
     L.dfq_fmt_from_absmax_i32.argtypes = [i64, C.c_int32, C.POINTER(Fmt)]
+    L.dfq_mfma_rate_probe.argtypes = [vp, vp, vp, i32, i32, C.POINTER(C.c_double), vp]
     for name in ("dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q", "dfq_conv_q_variant",
                  "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q", "dfq_absmax_f32",
-                 "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32"):
+                 "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_mfma_rate_probe"):
         getattr(L, name).restype = i32
     L.dfq_beta_max.restype = i64
     L.dfq_beta_max.argtypes = [i32, i32]
@@ -264,6 +265,22 @@ def absmax_i32(x: torch.Tensor, relu: bool = False, out_dev: Optional[torch.Tens
     out = out_dev if out_dev is not None else torch.empty(1, dtype=torch.int32, device=x.device)
     _check(lib().dfq_absmax_i32(_ptr(x), x.numel(), int(bool(relu)), _ptr(out), _stream(stream)), "dfq_absmax_i32")
     return out
+
+
+def mfma_rate_probe(a_codes: torch.Tensor, b_codes: torch.Tensor, sink: torch.Tensor, blocks: int, iters: int,
+                    stream=None) -> float:
+    """Launches the register-only matrix-instruction loop on operand bytes taken from ``a_codes`` (first
+    16 KiB) and ``b_codes`` (first 32 KiB); returns the number of operations of the launch.  The caller
+    times it."""
+    _dev(a_codes, torch.int8, "a_codes")
+    _dev(b_codes, torch.int8, "b_codes")
+    _dev(sink, torch.int32, "sink")
+    if a_codes.numel() < 16384 or b_codes.numel() < 32768 or sink.numel() < blocks * 512:
+        raise ValueError("mfma_rate_probe: a_codes >= 16 KiB, b_codes >= 32 KiB, sink >= blocks * 512 words")
+    ops = C.c_double(0.0)
+    _check(lib().dfq_mfma_rate_probe(_ptr(a_codes), _ptr(b_codes), _ptr(sink), int(blocks), int(iters), C.byref(ops),
+                                     _stream(stream)), "dfq_mfma_rate_probe")
+    return ops.value
 
 
 def absmax_i32_value(out_dev: torch.Tensor) -> int:

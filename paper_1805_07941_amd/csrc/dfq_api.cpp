@@ -264,6 +264,16 @@ dfq_status dfq_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out_de
     return from_hip(launch_absmax_i32(x, n, relu ? 1 : 0, out_dev, (hipStream_t)stream));
 }
 
+dfq_status dfq_mfma_rate_probe(const int8_t *a_codes, const int8_t *b_codes, int32_t *sink, int blocks, int iters,
+                               double *ops_out, dfq_stream stream)
+{
+    if (!a_codes || !b_codes || !sink) return DFQ_EINVAL;
+    if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 24)) return DFQ_EINVAL;
+    if (((uintptr_t)a_codes & 15) || ((uintptr_t)b_codes & 15) || ((uintptr_t)sink & 3)) return DFQ_EINVAL;
+    if (ops_out) *ops_out = mfma_rate_probe_ops(blocks, iters);
+    return from_hip(launch_mfma_rate_probe(a_codes, b_codes, sink, blocks, iters, (hipStream_t)stream));
+}
+
 dfq_status dfq_fmt_from_absmax_f32(float gamma, dfq_fmt *out)
 {
     if (!out) return DFQ_EINVAL;

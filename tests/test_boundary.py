@@ -119,6 +119,9 @@ def test_other_calls_reject_bad_arguments(B):
     assert L.dfq_concat_q(2, ptrs, Cs, fs, 3 << 20, f(3), 4, None) == B.ESHAPE
     assert L.dfq_absmax_f32(1 << 20, 4, None, None) == B.EINVAL
     assert L.dfq_absmax_i32(None, 4, 0, 1 << 20, None) == B.EINVAL
+    assert L.dfq_mfma_rate_probe(None, 1 << 20, 2 << 20, 1, 1, None, None) == B.EINVAL
+    assert L.dfq_mfma_rate_probe(1 << 20, 2 << 20, 3 << 20, 0, 1, None, None) == B.EINVAL              # no workgroups
+    assert L.dfq_mfma_rate_probe(1 << 20, (2 << 20) + 4, 3 << 20, 1, 1, None, None) == B.EINVAL        # alignment
 
 
 def test_kernel_selection(B):

@@ -256,3 +256,15 @@ def test_absmax_and_formats(B):
     a = np.array([-2 ** 31, 5], np.int32)
     assert B.absmax_i32_value(B.absmax_i32(dev(a))) == 2 ** 31
     assert B.absmax_i32_value(B.absmax_i32(torch.empty(0, dtype=torch.int32, device=DEV))) == 0
+
+
+def test_mfma_rate_probe_runs_the_stated_work(B):
+    """The measurement aid: with all-ones operands every accumulator grows by 32 per instruction, so the
+    word each lane stores is 8 accumulators x 16 registers x 32 x iters; the reported operation count is
+    blocks x 8 wavefronts x iters x 8 instructions x 2*32^3."""
+    blocks, iters = 3, 5
+    ones = torch.ones(1 << 15, dtype=torch.int8, device="cuda:0")
+    sink = torch.zeros(blocks * 512, dtype=torch.int32, device="cuda:0")
+    ops = B.mfma_rate_probe(ones, ones, sink, blocks, iters)
+    assert ops == blocks * 8 * iters * 8 * 2 * 32 ** 3
+    assert np.array_equal(host(sink), np.full(blocks * 512, 8 * 16 * 32 * iters, dtype=np.int32))
