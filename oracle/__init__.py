@@ -61,6 +61,10 @@ def lib():
         L.orc_conv_acc_at.argtypes = [_i8p, _i8p, _i32p] + [C.c_int] * 14
         L.orc_conv_q.restype = C.c_int
         L.orc_conv_q.argtypes = [_i8p, _i8p, _i32p, _i8p, _i32p] + [C.c_int] * 15
+        L.orc_conv_q_pc.restype = C.c_int
+        L.orc_conv_q_pc.argtypes = [_i8p, _i8p, _i32p, _i8p, _i32p] + [C.c_int] * 12 + [_i32p, C.c_int, C.c_int]
+        L.orc_absmax_i32_channels.restype = None
+        L.orc_absmax_i32_channels.argtypes = [_i32p, C.c_size_t, C.c_int, C.c_int, C.POINTER(C.c_int64)]
         L.orc_requant_i32.restype = None
         L.orc_requant_i32.argtypes = [_i32p, _i8p, C.c_size_t, C.c_int, C.c_int]
         L.orc_eltwise_q.restype = C.c_int
@@ -137,7 +141,9 @@ def conv_out_hw(H, W, R, S, stride, pad):
 def conv_q(x, w, b, f_in, f_w, f_out, stride=1, pad=0, groups=1, relu=False,
            want_y=True, want_acc=False):
     """Returns (y, acc): y int8 [N,P,Q,K] at f_out (or None), acc int32 [N,P,Q,K]
-    including bias, before ReLU (or None).  Raises if an accumulator overflowed int32."""
+    including bias, before ReLU (or None).  Raises if an accumulator overflowed int32.
+    f_w: one fractional length for the layer, or a sequence of K (one per output channel;
+    b[k] is then at f_in + f_w[k])."""
     x = _c(x, np.int8); w = _c(w, np.int8)
     b = None if b is None else _c(b, np.int32)
     N, H, W, Cc = x.shape
@@ -146,9 +152,16 @@ def conv_q(x, w, b, f_in, f_w, f_out, stride=1, pad=0, groups=1, relu=False,
     P, Q = conv_out_hw(H, W, R, S, stride, pad)
     y = np.empty((N, P, Q, K), np.int8) if want_y else None
     acc = np.empty((N, P, Q, K), np.int32) if want_acc else None
-    rc = lib().orc_conv_q(_p(x, _i8p), _p(w, _i8p), _p(b, _i32p), _p(y, _i8p), _p(acc, _i32p),
-                          N, H, W, Cc, K, R, S, stride, pad, groups, K,
-                          int(f_in), int(f_w), int(f_out), int(bool(relu)))
+    if np.ndim(f_w) == 0:
+        rc = lib().orc_conv_q(_p(x, _i8p), _p(w, _i8p), _p(b, _i32p), _p(y, _i8p), _p(acc, _i32p),
+                              N, H, W, Cc, K, R, S, stride, pad, groups, K,
+                              int(f_in), int(f_w), int(f_out), int(bool(relu)))
+    else:
+        fw = _c(f_w, np.int32)
+        assert fw.shape == (K,), "one weight format per output channel"
+        rc = lib().orc_conv_q_pc(_p(x, _i8p), _p(w, _i8p), _p(b, _i32p), _p(y, _i8p), _p(acc, _i32p),
+                                 N, H, W, Cc, K, R, S, stride, pad, groups, K,
+                                 int(f_in), _p(fw, _i32p), int(f_out), int(bool(relu)))
     if rc < 0:
         raise ValueError("oracle conv_q: bad shape")
     if rc > 0:
@@ -222,6 +235,15 @@ def absmax_f32(x) -> float:
 def absmax_i32(x, relu=False) -> int:
     x = _c(x, np.int32)
     return int(lib().orc_absmax_i32(_p(x, _i32p), x.size, int(bool(relu))))
+
+
+def absmax_i32_channels(x, relu=False) -> np.ndarray:
+    """Per-channel maximum of |x| over all leading axes of an [..., K] int32 array (int64 [K])."""
+    x = _c(x, np.int32)
+    K = x.shape[-1]
+    out = np.zeros(K, np.int64)
+    lib().orc_absmax_i32_channels(_p(x, _i32p), x.size // K, K, int(bool(relu)), out.ctypes.data_as(C.POINTER(C.c_int64)))
+    return out
 
 
 def frac_from_absmax_f32(gamma: float) -> int:

@@ -281,6 +281,39 @@ int orc_conv_q(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, in
     return overflow;
 }
 
+/* The same layer with one weight format per output channel (Sec. 3, "Calibrating": weight
+ * thresholds are taken per output channel): f_w[k] is the fractional length of w[k][.][.][.],
+ * b[k] is at f_in + f_w[k], and the rescale of Eq. 6 for channel k is a rounding shift by
+ * f_in + f_w[k] - f_out.  Everything else as orc_conv_q. */
+int orc_conv_q_pc(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int32_t *acc_out,
+                  int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                  int ldy, int f_in, const int32_t *f_w, int f_out, int relu)
+{
+    conv_shape sh = {N, H, W, C, K, R, S, stride, pad, groups};
+    if (!conv_shape_ok(&sh) || ldy < K || !f_w) return -1;
+    int P = conv_out_dim(H, pad, R, stride);
+    int Q = conv_out_dim(W, pad, S, stride);
+    int overflow = 0;
+#pragma omp parallel for collapse(2) schedule(static) reduction(| : overflow)
+    for (int n = 0; n < N; n++) {
+        for (int p = 0; p < P; p++) {
+            for (int q = 0; q < Q; q++) {
+                size_t pix = ((size_t)n * P + p) * Q + q;
+                for (int k = 0; k < K; k++) {
+                    int64_t acc = conv_acc_one(x, w, b, &sh, n, p, q, k);
+                    if (acc > INT32_MAX || acc < INT32_MIN) overflow = 1;
+                    if (acc_out) acc_out[pix * K + k] = (int32_t)acc;
+                    if (y) {
+                        int64_t v = (relu && acc < 0) ? 0 : acc;
+                        y[pix * (size_t)ldy + k] = (int8_t)orc_requant8(v, f_in + f_w[k] - f_out);
+                    }
+                }
+            }
+        }
+    }
+    return overflow;
+}
+
 /* The last step of Eq. 6 on its own: y[i] = sat8(rne(relu ? max(acc[i],0) : acc[i], shift)).
  * Lets calibration requantize accumulators it already holds instead of convolving again. */
 void orc_requant_i32(const int32_t *acc, int8_t *y, size_t n, int shift, int relu)
@@ -419,6 +452,19 @@ int64_t orc_absmax_i32(const int32_t *x, size_t n, int relu)
         if (v > m) m = v;
     }
     return m;
+}
+
+/* the same maximum separately for each of the K channels of an [pixels][K] array */
+void orc_absmax_i32_channels(const int32_t *x, size_t pixels, int K, int relu, int64_t *out)
+{
+    for (int k = 0; k < K; k++) out[k] = 0;
+    for (size_t i = 0; i < pixels; i++) {
+        for (int k = 0; k < K; k++) {
+            int64_t v = x[i * (size_t)K + k];
+            if (v < 0) v = relu ? 0 : -v;
+            if (v > out[k]) out[k] = v;
+        }
+    }
 }
 
 /* largest f in [-32, 32] with gamma * 2^f <= 127 (the smallest power-of-two

@@ -3,8 +3,8 @@
 TEST INFRASTRUCTURE ONLY (see ``oracle/__init__.py``).  Follows the quantization
 procedure of Sec. 3 in the paper's order, one layer at a time:
 
-* weights: threshold = max |w| over the layer (the paper uses the maximum per
-  output channel; this build fixes one format per layer), smallest power-of-two
+* weights: threshold = max |w| over the layer, or - with ``per_channel=True``, the
+  paper's own rule - over each output channel separately; smallest power-of-two
   scale that holds it;
 * bias: an integer at the product scale of input and weights;
 * activations: "bootstrap" order - each layer's threshold is measured on the
@@ -33,7 +33,7 @@ class Quantized:
     """What calibration fixes for a network: per-tensor fractional lengths and the
     integer weights / biases of every conv node."""
     frac: Dict[str, int] = field(default_factory=dict)          # tensor name -> f
-    w_frac: Dict[str, int] = field(default_factory=dict)        # conv node name -> f_w
+    w_frac: Dict[str, object] = field(default_factory=dict)     # conv node name -> f_w (int, or int32 [K] per output channel)
     w: Dict[str, np.ndarray] = field(default_factory=dict)      # int8 [K,R,S,Cg]
     b: Dict[str, np.ndarray] = field(default_factory=dict)      # int32 [K] at f_in + f_w
 
@@ -51,13 +51,21 @@ def _input_codes(net, x, qz: Quantized, calibrating: bool):
     return orc.quantize(x, qz.frac[net.input_name])
 
 
-def _forward(net, x, qz: Quantized, calibrating: bool):
+def _forward(net, x, qz: Quantized, calibrating: bool, per_channel: bool = False):
     t = {net.input_name: _input_codes(net, x, qz, calibrating)}
     for nd in net.nodes:
         if nd.op == "conv":
             src = nd.srcs[0]
             f_in = qz.frac[src]
-            if calibrating:
+            if calibrating and per_channel:
+                # one threshold per output channel: channel k's weights and bias get their own scale
+                wf, bf = net.weights(nd)
+                f_wk = np.array([orc.frac_from_absmax_f32(orc.absmax_f32(wf[k])) for k in range(wf.shape[0])], np.int32)
+                qz.w_frac[nd.name] = f_wk
+                qz.w[nd.name] = np.stack([orc.quantize(wf[k], int(f_wk[k])) for k in range(wf.shape[0])])
+                qz.b[nd.name] = np.array([orc.quantize_i32(bf[k:k + 1], f_in + int(f_wk[k]))[0] for k in range(wf.shape[0])],
+                                         np.int32)
+            elif calibrating:
                 wf, bf = net.weights(nd)
                 f_w = orc.frac_from_absmax_f32(orc.absmax_f32(wf))
                 qz.w_frac[nd.name] = f_w
@@ -65,7 +73,17 @@ def _forward(net, x, qz: Quantized, calibrating: bool):
                 qz.b[nd.name] = orc.quantize_i32(bf, f_in + f_w)
             f_w = qz.w_frac[nd.name]
             w, b = qz.w[nd.name], qz.b[nd.name]
-            if calibrating and nd.fixed_f_out is None:
+            if calibrating and nd.fixed_f_out is None and np.ndim(f_w) == 1:
+                # channel k's accumulators are at f_in + f_w[k]: the output format is the finest one
+                # that holds every channel's post-ReLU maximum with a rescale factor in (0, 1]
+                _, acc = orc.conv_q(t[src], w, b, f_in, f_w, 0, nd.stride, nd.pad, nd.groups,
+                                    nd.relu, want_y=False, want_acc=True)
+                m = orc.absmax_i32_channels(acc, relu=nd.relu)
+                qz.frac[nd.dst] = min(orc.frac_from_absmax_i32(int(m[k]), f_in + int(f_w[k])) for k in range(len(m)))
+                del acc
+                t[nd.dst], _ = orc.conv_q(t[src], w, b, f_in, f_w, qz.frac[nd.dst], nd.stride, nd.pad,
+                                          nd.groups, nd.relu)
+            elif calibrating and nd.fixed_f_out is None:
                 # threshold on the wide accumulator after the ReLU, then the one rescale of Eq. 6
                 _, acc = orc.conv_q(t[src], w, b, f_in, f_w, 0, nd.stride, nd.pad, nd.groups,
                                     nd.relu, want_y=False, want_acc=True)
@@ -102,10 +120,11 @@ def _forward(net, x, qz: Quantized, calibrating: bool):
     return t
 
 
-def calibrate(net, x_calib):
-    """Chooses every format from ONE batch.  Returns (Quantized, tensors of that batch)."""
+def calibrate(net, x_calib, per_channel: bool = False):
+    """Chooses every format from ONE batch.  Returns (Quantized, tensors of that batch).
+    per_channel: one weight format per output channel (Sec. 3) instead of one per layer."""
     qz = Quantized()
-    t = _forward(net, x_calib, qz, calibrating=True)
+    t = _forward(net, x_calib, qz, calibrating=True, per_channel=per_channel)
     return qz, t
 
 

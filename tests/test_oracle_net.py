@@ -80,3 +80,43 @@ def test_workload_shapes():
     assert c0["x"].shape == (1, 32, 32, 16) and c0["w"].shape == (16, 3, 3, 16)
     l = wl.config1_layer(4, batch=1)
     assert l["x"].shape == (1, 7, 7, 512) and l["w_float"].shape == (2048, 1, 1, 512)
+
+
+@pytest.mark.parametrize("net", [wl.resnet50(batch=2, hw=32, classes=10), wl.mobilenet_v1(batch=2, hw=32, classes=10)],
+                         ids=lambda n: n.name)
+def test_per_channel_calibration(net):
+    """One weight format per output channel (the rule of Sec. 3): every channel's codes use their range,
+    the output format is the finest that clips no channel of the calibration batch, and inference on
+    the calibration batch reproduces its tensors."""
+    x = net.input_float()
+    qz, t = onet.calibrate(net, x, per_channel=True)
+    qz1, _ = onet.calibrate(net, x)
+    for nd in net.nodes:
+        if nd.op != "conv":
+            continue
+        f_wk = qz.w_frac[nd.name]
+        wf, _ = net.weights(nd)
+        assert f_wk.shape == (wf.shape[0],)
+        assert (f_wk >= qz1.w_frac[nd.name]).all()                 # never coarser than the per-layer format
+        for k in range(wf.shape[0]):
+            g = Fraction(float(np.abs(wf[k]).max()))
+            if g == 0:
+                continue
+            assert g * Fraction(2) ** int(f_wk[k]) <= 127 < g * Fraction(2) ** (int(f_wk[k]) + 1)
+        if nd.fixed_f_out is not None:
+            continue
+        f_in, f = qz.frac[nd.srcs[0]], qz.frac[nd.dst]
+        _, acc = orc.conv_q(t[nd.srcs[0]], qz.w[nd.name], qz.b[nd.name], 0, 0, 0, nd.stride, nd.pad, nd.groups,
+                            want_y=False, want_acc=True)
+        acc = acc.astype(np.int64)
+        if nd.relu:
+            acc = np.maximum(acc, 0)
+        m = np.abs(acc).reshape(-1, acc.shape[-1]).max(axis=0)
+        gam = [Fraction(int(m[k])) / Fraction(2) ** (f_in + int(f_wk[k])) for k in range(len(m))]
+        assert all(gk * Fraction(2) ** f <= 127 for gk in gam)
+        assert f <= f_in + int(f_wk.min())
+        if f < f_in + int(f_wk.min()):
+            assert any(gk * Fraction(2) ** (f + 1) > 127 for gk in gam)
+    t2 = onet.infer(net, qz, x)
+    for k in t:
+        assert np.array_equal(t[k], t2[k])

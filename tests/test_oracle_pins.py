@@ -492,3 +492,68 @@ def test_requant_i32_is_the_last_step_of_conv():
         want = [_sat(_round_even(Fraction(max(int(v), 0) if relu else int(v)) / Fraction(2) ** (11 - f_out)))
                 for v in acc.ravel()]
         assert y.ravel().tolist() == want
+
+
+# --------------------------------------------------------------------------- #
+# One weight format per output channel (Sec. 3: weight thresholds are taken per output channel)
+# --------------------------------------------------------------------------- #
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_per_channel_conv_matches_exact_rational_rescale(case):
+    """Channel k's accumulator stands for acc * 2^-(f_in + f_w[k]); the output is that value rounded
+    once (ties to even) onto the grid of f_out and clamped - evaluated here with big ints and Fractions."""
+    N, H, W, C, K, R, S, st, pad, g = case
+    rng = np.random.default_rng(1000 + sum(case))
+    x = rng.integers(-128, 128, (N, H, W, C)).astype(np.int8)
+    w = rng.integers(-128, 128, (K, R, S, C // g)).astype(np.int8)
+    b = rng.integers(-2 ** 20, 2 ** 20, (K,)).astype(np.int32)
+    want = _brute_conv(x, w, b, st, pad, g)
+    for f_in, f_out, relu in [(4, 4, 0), (3, 6, 1), (5, -2, 0)]:
+        f_w = rng.integers(2, 12, K).astype(np.int32)
+        y, acc = orc.conv_q(x, w, b, f_in, f_w, f_out, st, pad, g, relu, want_acc=True)
+        assert np.array_equal(acc.astype(object), want)
+        for k in range(K):
+            ref = np.vectorize(lambda a: _sat(_round_even(Fraction(max(a, 0) if relu else a) * Fraction(2) ** f_out /
+                                                          Fraction(2) ** (f_in + int(f_w[k])))))(want[..., k])
+            assert np.array_equal(y[..., k].astype(np.int64), ref.astype(np.int64)), k
+
+
+def test_per_channel_conv_reduces_to_the_per_layer_one():
+    """Equal formats in every channel give the per-layer result; in general channel k equals the
+    per-layer convolution run with f_w[k] (the per-layer function is pinned above)."""
+    rng = np.random.default_rng(77)
+    x = rng.integers(-128, 128, (2, 6, 7, 8)).astype(np.int8)
+    w = rng.integers(-128, 128, (5, 3, 3, 8)).astype(np.int8)
+    b = rng.integers(-5000, 5000, (5,)).astype(np.int32)
+    y0, _ = orc.conv_q(x, w, b, 4, 7, 3, 1, 1, 1, True)
+    y1, _ = orc.conv_q(x, w, b, 4, np.full(5, 7, np.int32), 3, 1, 1, 1, True)
+    assert np.array_equal(y0, y1)
+    f_w = np.array([3, 9, 7, 12, 5], np.int32)
+    y, _ = orc.conv_q(x, w, b, 4, f_w, 3, 2, 1, 1, False)
+    for k in range(5):
+        yk, _ = orc.conv_q(x, w, b, 4, int(f_w[k]), 3, 2, 1, 1, False)
+        assert np.array_equal(y[..., k], yk[..., k])
+
+
+def test_per_channel_scale_moves_between_codes_and_format():
+    """Doubling channel k's weight and bias codes while raising f_w[k] by one names the same real
+    weights, so the output cannot change - a per-layer format cannot express this."""
+    rng = np.random.default_rng(78)
+    x = rng.integers(-128, 128, (1, 5, 5, 4)).astype(np.int8)
+    w = rng.integers(-60, 61, (3, 3, 3, 4)).astype(np.int8)
+    b = rng.integers(-3000, 3000, (3,)).astype(np.int32)
+    f_w = np.array([6, 6, 6], np.int32)
+    y0, _ = orc.conv_q(x, w, b, 4, f_w, 2, 1, 1, 1, True)
+    w2, b2, f2 = w.copy(), b.copy(), f_w.copy()
+    w2[1] *= 2; b2[1] *= 2; f2[1] += 1
+    y1, _ = orc.conv_q(x, w2, b2, 4, f2, 2, 1, 1, 1, True)
+    assert np.array_equal(y0, y1)
+
+
+def test_absmax_per_channel():
+    a = np.array([[[1, -9, 0], [4, 2, -3]], [[-7, 8, 0], [2, 2, 2]]], np.int32)
+    assert orc.absmax_i32_channels(a).tolist() == [7, 9, 3]
+    assert orc.absmax_i32_channels(a, relu=True).tolist() == [4, 8, 2]
+    rng = np.random.default_rng(5)
+    r = rng.integers(-2 ** 31, 2 ** 31, (50, 7)).astype(np.int32)
+    assert orc.absmax_i32_channels(r).tolist() == [orc.absmax_i32(r[:, k]) for k in range(7)]
