@@ -112,6 +112,19 @@ dfq_status dfq_conv_q_variant(dfq_conv_variant variant,
                               int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
                               int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu, dfq_stream stream);
 
+/* The same layer with one weight format per OUTPUT CHANNEL (Sec. 3, "Calibrating": the weight
+ * thresholds are maxima per output channel).  frac_w: DEVICE array of K fractional lengths,
+ * 4-byte aligned, read by the kernel (the library cannot range-check it: every entry must lie
+ * in [-32, 32]; any integer shift is still well defined).  w[k][.][.][.] holds codes at
+ * frac_w[k], b[k] is at fmt_in.frac + frac_w[k], and channel k is rescaled by one rounding
+ * shift of fmt_in.frac + frac_w[k] - fmt_out.frac.  Everything else, including errors and the
+ * optional accumulator dump, as dfq_conv_q.  With equal entries the result is that of
+ * dfq_conv_q at that format. */
+dfq_status dfq_conv_q_pc(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int32_t *acc_out,
+                         int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                         int ldy, dfq_fmt fmt_in, const int32_t *frac_w, dfq_fmt fmt_out, int relu,
+                         dfq_stream stream);
+
 /* Convolution followed by an element-wise add, in one kernel (Sec. 3: adjacent operations are
  * merged; Eq. 10 for the add).  The result is exactly that of
  *     dfq_conv_q(x, w, b, t, NULL, ..., ldy = K, fmt_in, fmt_w, fmt_mid, relu_mid)   followed by
@@ -165,6 +178,25 @@ dfq_status dfq_pool_q(const int8_t *x, int8_t *y, dfq_pool_mode mode, int N, int
 dfq_status dfq_absmax_f32(const float *x, size_t n, float *out_dev, dfq_stream stream);
 /* max |x[i]| (as uint32; relu != 0: negative entries count as 0). */
 dfq_status dfq_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out_dev, dfq_stream stream);
+
+/* Row-wise forms for weights that take one format per output channel (Sec. 3): row r of
+ * x[rows][row_len] (weights: rows = K, row_len = R*S*C/groups; bias: row_len = 1).
+ * dfq_absmax_f32_rows: out_dev[r] = max |x[r][.]| (NaN ignored; 0 for row_len == 0).
+ * dfq_quantize_rows: q[r][i] = sat8(rne(x[r][i] * 2^frac[r])).
+ * dfq_quantize_i32_rows: q[r][i] = rne(x[r][i] * 2^(frac[r] + frac_add)) saturated to
+ * [-(2^31 - 1), 2^31 - 1], frac_add in [-64, 64].
+ * frac, out_dev: DEVICE arrays of `rows` entries (frac entries in [-32, 32], not checked). */
+dfq_status dfq_absmax_f32_rows(const float *x, size_t rows, size_t row_len, float *out_dev, dfq_stream stream);
+dfq_status dfq_quantize_rows(const float *x, int8_t *q, size_t rows, size_t row_len, const int32_t *frac,
+                             dfq_stream stream);
+dfq_status dfq_quantize_i32_rows(const float *x, int32_t *q, size_t rows, size_t row_len, const int32_t *frac,
+                                 int32_t frac_add, dfq_stream stream);
+
+/* The same maximum separately for each of the K channels of x[pixels][K] (per-channel weight
+ * formats put every channel's accumulators at a scale of their own, so the threshold of the
+ * layer's output is found channel by channel).  out_dev: K DEVICE words, overwritten. */
+dfq_status dfq_absmax_i32_channels(const int32_t *x, size_t pixels, int K, int relu, uint32_t *out_dev,
+                                   dfq_stream stream);
 
 /* gamma = alpha * beta_max (Sec. 2.1) solved for a power-of-two alpha: the largest frac in
  * [-32, 32] with gamma * 2^frac <= 127; gamma = 0 gives 32.  Host, pure.  DFQ_EINVAL for a

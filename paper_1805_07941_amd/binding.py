@@ -23,7 +23,7 @@ CONV_VARIANT_NAMES = {CONV_AUTO: "auto", CONV_DIRECT: "direct", CONV_MFMA: "mfma
 
 EXPORTS = [
     "dfq_status_string", "dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q",
-    "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
+    "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_absmax_i32_channels", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
     "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_mfma_rate_probe",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
 ]
@@ -65,6 +65,11 @@ def lib():
     conv_args = [vp, vp, vp, vp, vp] + [i32] * 11 + [Fmt, Fmt, Fmt, i32, vp]
     L.dfq_conv_q.argtypes = conv_args
     L.dfq_conv_q_variant.argtypes = [i32] + conv_args
+    L.dfq_conv_q_pc.argtypes = [vp, vp, vp, vp, vp] + [i32] * 11 + [Fmt, vp, Fmt, i32, vp]
+    L.dfq_absmax_i32_channels.argtypes = [vp, sz, i32, i32, vp, vp]
+    L.dfq_absmax_f32_rows.argtypes = [vp, sz, sz, vp, vp]
+    L.dfq_quantize_rows.argtypes = [vp, vp, sz, sz, vp, vp]
+    L.dfq_quantize_i32_rows.argtypes = [vp, vp, sz, sz, vp, i32, vp]
     L.dfq_conv_q_select.argtypes = [i32] * 10
     L.dfq_conv_q_add.argtypes = [vp, vp, vp, vp, vp] + [i32] * 12 + [Fmt, Fmt, Fmt, i32, Fmt, Fmt, i32, vp]
     L.dfq_eltwise_q.argtypes = [vp, Fmt, vp, Fmt, vp, Fmt, vp, sz, i32, vp]
@@ -77,7 +82,9 @@ def lib():
     L.dfq_mfma_rate_probe.argtypes = [vp, vp, vp, i32, i32, C.POINTER(C.c_double), vp]
     for name in ("dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q", "dfq_conv_q_variant",
                  "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q", "dfq_absmax_f32",
-                 "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_mfma_rate_probe"):
+                 "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_mfma_rate_probe",
+                 "dfq_conv_q_pc", "dfq_absmax_i32_channels", "dfq_absmax_f32_rows", "dfq_quantize_rows",
+                 "dfq_quantize_i32_rows"):
         getattr(L, name).restype = i32
     L.dfq_beta_max.restype = i64
     L.dfq_beta_max.argtypes = [i32, i32]
@@ -171,6 +178,35 @@ def conv_q(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], f_in: in
                                   N, H, W, Cc, K, R, S, stride, pad, groups, K if ldy is None else int(ldy),
                                   fmt(f_in), fmt(f_w), fmt(f_out), int(bool(relu)), _stream(stream))
     _check(st, "dfq_conv_q")
+    return y, acc
+
+
+def conv_q_pc(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], f_in: int, frac_w: torch.Tensor, f_out: int,
+              stride: int = 1, pad: int = 0, groups: int = 1, relu: bool = False,
+              out: Optional[torch.Tensor] = None, ldy: Optional[int] = None,
+              want_y: bool = True, want_acc: bool = False, acc_out: Optional[torch.Tensor] = None, stream=None):
+    """conv_q with one weight format per output channel: frac_w is an int32 device tensor [K];
+    b[k] is at f_in + frac_w[k].  Returns (y, acc)."""
+    _dev(x, torch.int8, "x"); _dev(w, torch.int8, "w"); _dev(frac_w, torch.int32, "frac_w")
+    if b is not None:
+        _dev(b, torch.int32, "b")
+    N, H, W, Cc = x.shape
+    K, R, S, Cg = w.shape
+    if Cg * groups != Cc:
+        raise DfqError(ESHAPE, "conv_q_pc (weight shape does not match C/groups)")
+    if tuple(frac_w.shape) != (K,):
+        raise DfqError(ESHAPE, "conv_q_pc (one weight format per output channel)")
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    y = out
+    if y is None and want_y:
+        y = torch.empty((N, max(P, 0), max(Q, 0), K), dtype=torch.int8, device=x.device)
+    acc = acc_out
+    if acc is None and want_acc:
+        acc = torch.empty((N, max(P, 0), max(Q, 0), K), dtype=torch.int32, device=x.device)
+    st = lib().dfq_conv_q_pc(_ptr(x), _ptr(w), _ptr(b), _ptr(y), _ptr(acc), N, H, W, Cc, K, R, S, stride, pad, groups,
+                             K if ldy is None else int(ldy), fmt(f_in), _ptr(frac_w), fmt(f_out), int(bool(relu)),
+                             _stream(stream))
+    _check(st, "dfq_conv_q_pc")
     return y, acc
 
 
@@ -281,6 +317,52 @@ def mfma_rate_probe(a_codes: torch.Tensor, b_codes: torch.Tensor, sink: torch.Te
     _check(lib().dfq_mfma_rate_probe(_ptr(a_codes), _ptr(b_codes), _ptr(sink), int(blocks), int(iters), C.byref(ops),
                                      _stream(stream)), "dfq_mfma_rate_probe")
     return ops.value
+
+
+def absmax_f32_rows(x: torch.Tensor, stream=None) -> torch.Tensor:
+    """max |.| of every row of a float32 [rows, ...] tensor: float32 device tensor [rows] (no synchronization)."""
+    _dev(x, torch.float32, "x")
+    rows = int(x.shape[0])
+    out = torch.zeros(rows, dtype=torch.float32, device=x.device)
+    _check(lib().dfq_absmax_f32_rows(_ptr(x), rows, x.numel() // max(rows, 1), _ptr(out), _stream(stream)),
+           "dfq_absmax_f32_rows")
+    return out
+
+
+def quantize_rows(x: torch.Tensor, frac: torch.Tensor, stream=None) -> torch.Tensor:
+    """int8 codes of a float32 [rows, ...] tensor, row r at fractional length frac[r] (int32 device tensor)."""
+    _dev(x, torch.float32, "x"); _dev(frac, torch.int32, "frac")
+    rows = int(x.shape[0])
+    q = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    _check(lib().dfq_quantize_rows(_ptr(x), _ptr(q), rows, x.numel() // max(rows, 1), _ptr(frac), _stream(stream)),
+           "dfq_quantize_rows")
+    return q
+
+
+def quantize_i32_rows(x: torch.Tensor, frac: torch.Tensor, frac_add: int, stream=None) -> torch.Tensor:
+    """int32 codes of a float32 [rows, ...] tensor, row r at fractional length frac[r] + frac_add."""
+    _dev(x, torch.float32, "x"); _dev(frac, torch.int32, "frac")
+    rows = int(x.shape[0])
+    q = torch.empty(x.shape, dtype=torch.int32, device=x.device)
+    _check(lib().dfq_quantize_i32_rows(_ptr(x), _ptr(q), rows, x.numel() // max(rows, 1), _ptr(frac), int(frac_add),
+                                       _stream(stream)), "dfq_quantize_i32_rows")
+    return q
+
+
+def absmax_i32_channels(x: torch.Tensor, relu: bool = False, out_dev: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Per-channel maxima of |x| over the leading axes of an int32 [..., K] tensor: K uint32 words in
+    an int32 device tensor (no synchronization; read with ``absmax_i32_channels_value``)."""
+    _dev(x, torch.int32, "x")
+    K = int(x.shape[-1])
+    out = out_dev if out_dev is not None else torch.empty(K, dtype=torch.int32, device=x.device)
+    _check(lib().dfq_absmax_i32_channels(_ptr(x), x.numel() // K, K, int(bool(relu)), _ptr(out), _stream(stream)),
+           "dfq_absmax_i32_channels")
+    return out
+
+
+def absmax_i32_channels_value(out_dev: torch.Tensor):
+    """Host values (numpy uint32 [K]) of an absmax_i32_channels result (synchronizes)."""
+    return out_dev.cpu().numpy().view("uint32")
 
 
 def absmax_i32_value(out_dev: torch.Tensor) -> int:

@@ -91,6 +91,11 @@ __global__ void __launch_bounds__(kThreads) conv_depthwise_kernel(DwParams prm)
             }
         }
         const size_t pix0 = ((size_t)n * a.P + p) * a.Q + q0;
+        int sh[4] = {a.shift, a.shift, a.shift, a.shift};   // one weight format per channel: each its own shift
+        if (a.frac_w) {
+#pragma unroll
+            for (int e = 0; e < 4; e++) sh[e] += a.frac_w[c + e];
+        }
 #pragma unroll
         for (int j = 0; j < TW; j++) {
             if (q0 + j >= a.Q) break;
@@ -98,7 +103,10 @@ __global__ void __launch_bounds__(kThreads) conv_depthwise_kernel(DwParams prm)
             if (a.y) {
                 int o[4];
 #pragma unroll
-                for (int e = 0; e < 4; e++) o[e] = rq.fast ? rq.fast_one(acc[j][e]) : rq.slow_one(acc[j][e]);
+                for (int e = 0; e < 4; e++) {
+                    if (a.frac_w) o[e] = requant8(a.relu ? max(acc[j][e], 0) : acc[j][e], sh[e]);
+                    else o[e] = rq.fast ? rq.fast_one(acc[j][e]) : rq.slow_one(acc[j][e]);
+                }
                 *(uint32_t *)(a.y + (pix0 + j) * (size_t)a.ldy + c) = pack4_clamped(o[0], o[1], o[2], o[3]);
             }
         }

@@ -37,7 +37,7 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(ConvArgs a)
         if (a.acc_out) a.acc_out[i] = acc;
         if (a.y) {
             if (a.relu) acc = max(acc, 0);
-            a.y[pix * (size_t)a.ldy + k] = (int8_t)requant8(acc, a.shift);
+            a.y[pix * (size_t)a.ldy + k] = (int8_t)requant8(acc, a.frac_w ? a.shift + a.frac_w[k] : a.shift);
         }
     }
 }

@@ -98,7 +98,8 @@ __device__ __forceinline__ void store_tile_lane_fast(const v16i &v, const ConvAr
     *(uint4 *)(a.y + (size_t)m * a.ldy + kc) = requant_tile_lane_fast(v, rq);
 }
 
-// General form (ragged channel tail, unaligned rows, extreme shifts, accumulator dump).
+// General form (ragged channel tail, unaligned rows, extreme shifts, accumulator dump, one weight
+// format per output channel).
 __device__ __forceinline__ void store_tile_lane_general(const v16i &v, const ConvArgs &a, int shift, int relu, long long m, int kc)
 {
 #pragma unroll
@@ -106,7 +107,8 @@ __device__ __forceinline__ void store_tile_lane_general(const v16i &v, const Con
         if (kc + r < a.K) {
             const int val = v[r];
             if (a.acc_out) a.acc_out[(size_t)m * a.K + kc + r] = val;
-            if (a.y) a.y[(size_t)m * a.ldy + kc + r] = (int8_t)requant8(relu ? max(val, 0) : val, shift);
+            const int s = a.frac_w ? shift + a.frac_w[kc + r] : shift;
+            if (a.y) a.y[(size_t)m * a.ldy + kc + r] = (int8_t)requant8(relu ? max(val, 0) : val, s);
         }
     }
 }
@@ -114,7 +116,7 @@ __device__ __forceinline__ void store_tile_lane_general(const v16i &v, const Con
 // true when every tile of a launch can take the hot form (k_end = end of the block's channel range)
 __device__ __forceinline__ bool epilogue_is_fast(const ConvArgs &a, const Requant &rq, int k_end)
 {
-    return rq.fast && !a.acc_out && a.y && ((a.ldy & 15) == 0) && (((uintptr_t)a.y & 15) == 0) && k_end <= a.K;
+    return rq.fast && !a.frac_w && !a.acc_out && a.y && ((a.ldy & 15) == 0) && (((uintptr_t)a.y & 15) == 0) && k_end <= a.K;
 }
 
 // Bias of channels kc..kc+15 (zeros where there is no bias or past K).

@@ -426,7 +426,7 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     static_assert(lds_bytes * PER_CU <= kLdsBytes, "rings do not fit the LDS");
 
     const bool ut = a.C % kStepBytes == 0;
-    const bool general = !(a.shift >= 0 && a.shift <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
+    const bool general = !(!a.frac_w && a.shift >= 0 && a.shift <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
                            ((uintptr_t)a.y & 15) == 0 && a.K % BC == 0 && y_bytes < (1LL << 31));
     constexpr int occ = PER_CU * WAVES_P * WAVES_C / 4;
     using K = void (*)(MfmaParams);

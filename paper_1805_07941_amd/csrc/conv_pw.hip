@@ -435,6 +435,7 @@ bool conv_pw_geometry_ok(const ConvArgs &a)
 bool conv_pw_supports(const ConvArgs &a)
 {
     if (!conv_pw_geometry_ok(a)) return false;
+    if (a.frac_w) return false;
     if (!(a.shift >= 0 && a.shift <= 23) || a.acc_out || !a.y || (a.ldy & 15) || ((uintptr_t)a.y & 15)) return false;
     if (((uintptr_t)a.x & 15) || ((uintptr_t)a.w & 15)) return false;
     if (a.add) {

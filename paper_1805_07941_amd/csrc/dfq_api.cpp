@@ -82,6 +82,29 @@ dfq_conv_variant select_variant(const ConvArgs &a, bool geometry_only = false)
     return DFQ_CONV_DIRECT;
 }
 
+dfq_status run_conv(dfq_conv_variant variant, const ConvArgs &a, hipStream_t st)
+{
+    if (variant == DFQ_CONV_AUTO) variant = select_variant(a);
+    switch (variant) {
+        case DFQ_CONV_DIRECT:
+            return from_hip(launch_conv_direct(a, st));
+        case DFQ_CONV_MFMA:
+            if (!conv_mfma_supports(a)) return DFQ_EUNSUPPORTED;
+            return from_hip(launch_conv_mfma(a, st));
+        case DFQ_CONV_DEPTHWISE:
+            if (!conv_depthwise_supports(a)) return DFQ_EUNSUPPORTED;
+            return from_hip(launch_conv_depthwise(a, st));
+        case DFQ_CONV_POINTWISE:
+            if (!conv_pw_supports(a)) return DFQ_EUNSUPPORTED;
+            return from_hip(launch_conv_pw(a, st));
+        case DFQ_CONV_SMALLC:
+            if (!conv_smallc_supports(a)) return DFQ_EUNSUPPORTED;
+            return from_hip(launch_conv_smallc(a, st));
+        default:
+            return DFQ_EINVAL;
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -132,26 +155,20 @@ dfq_status dfq_conv_q_variant(dfq_conv_variant variant, const int8_t *x, const i
                              relu, true);
     if (c.st != DFQ_OK) return c.st;
     if (N == 0) return DFQ_OK;
-    if (variant == DFQ_CONV_AUTO) variant = select_variant(c.a);
-    hipStream_t st = (hipStream_t)stream;
-    switch (variant) {
-        case DFQ_CONV_DIRECT:
-            return from_hip(launch_conv_direct(c.a, st));
-        case DFQ_CONV_MFMA:
-            if (!conv_mfma_supports(c.a)) return DFQ_EUNSUPPORTED;
-            return from_hip(launch_conv_mfma(c.a, st));
-        case DFQ_CONV_DEPTHWISE:
-            if (!conv_depthwise_supports(c.a)) return DFQ_EUNSUPPORTED;
-            return from_hip(launch_conv_depthwise(c.a, st));
-        case DFQ_CONV_POINTWISE:
-            if (!conv_pw_supports(c.a)) return DFQ_EUNSUPPORTED;
-            return from_hip(launch_conv_pw(c.a, st));
-        case DFQ_CONV_SMALLC:
-            if (!conv_smallc_supports(c.a)) return DFQ_EUNSUPPORTED;
-            return from_hip(launch_conv_smallc(c.a, st));
-        default:
-            return DFQ_EINVAL;
-    }
+    return run_conv(variant, c.a, (hipStream_t)stream);
+}
+
+dfq_status dfq_conv_q_pc(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int32_t *acc_out, int N, int H,
+                         int W, int C, int K, int R, int S, int stride, int pad, int groups, int ldy, dfq_fmt fmt_in,
+                         const int32_t *frac_w, dfq_fmt fmt_out, int relu, dfq_stream stream)
+{
+    ConvCheck c = check_conv(x, w, b, y, acc_out, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, dfq_fmt{8, 0},
+                             fmt_out, relu, true);
+    if (c.st != DFQ_OK) return c.st;
+    if (!frac_w || ((uintptr_t)frac_w & 3)) return DFQ_EINVAL;
+    if (N == 0) return DFQ_OK;
+    c.a.frac_w = frac_w;          // c.a.shift is f_in - f_out (the placeholder weight format has frac 0)
+    return run_conv(DFQ_CONV_AUTO, c.a, (hipStream_t)stream);
 }
 
 dfq_status dfq_conv_q(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int32_t *acc_out, int N, int H, int W,
@@ -262,6 +279,36 @@ dfq_status dfq_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out_de
 {
     if (!out_dev || (n && !x)) return DFQ_EINVAL;
     return from_hip(launch_absmax_i32(x, n, relu ? 1 : 0, out_dev, (hipStream_t)stream));
+}
+
+dfq_status dfq_quantize_rows(const float *x, int8_t *q, size_t rows, size_t row_len, const int32_t *frac, dfq_stream stream)
+{
+    if (rows == 0 || row_len == 0) return DFQ_OK;
+    if (!x || !q || !frac || overlaps(x, rows * row_len * 4, q, rows * row_len)) return DFQ_EINVAL;
+    return from_hip(launch_quantize_rows(x, q, rows, row_len, frac, (hipStream_t)stream));
+}
+
+dfq_status dfq_quantize_i32_rows(const float *x, int32_t *q, size_t rows, size_t row_len, const int32_t *frac,
+                                 int32_t frac_add, dfq_stream stream)
+{
+    if (frac_add < -64 || frac_add > 64) return DFQ_EFMT;
+    if (rows == 0 || row_len == 0) return DFQ_OK;
+    if (!x || !q || !frac || overlaps(x, rows * row_len * 4, q, rows * row_len * 4)) return DFQ_EINVAL;
+    return from_hip(launch_quantize_i32_rows(x, q, rows, row_len, frac, frac_add, (hipStream_t)stream));
+}
+
+dfq_status dfq_absmax_f32_rows(const float *x, size_t rows, size_t row_len, float *out_dev, dfq_stream stream)
+{
+    if (rows == 0) return DFQ_OK;
+    if (!out_dev || (row_len && !x)) return DFQ_EINVAL;
+    return from_hip(launch_absmax_f32_rows(x, rows, row_len, out_dev, (hipStream_t)stream));
+}
+
+dfq_status dfq_absmax_i32_channels(const int32_t *x, size_t pixels, int K, int relu, uint32_t *out_dev, dfq_stream stream)
+{
+    if (K < 1) return DFQ_ESHAPE;
+    if (!out_dev || (pixels && !x)) return DFQ_EINVAL;
+    return from_hip(launch_absmax_i32_channels(x, pixels, K, relu ? 1 : 0, out_dev, (hipStream_t)stream));
 }
 
 dfq_status dfq_mfma_rate_probe(const int8_t *a_codes, const int8_t *b_codes, int32_t *sink, int blocks, int iters,

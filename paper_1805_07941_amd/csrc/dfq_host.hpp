@@ -28,6 +28,10 @@ struct ConvArgs {
     int add_sa = 0, add_sb = 0;  // left shifts of the convolution result and of `add`
     int add_shift = 0;           // finer scale's fractional length minus that of y
     int add_relu = 0;
+    // One weight format per output channel (Sec. 3), or frac_w == null: a device array of K
+    // fractional lengths; `shift` then holds f_in - f_out and channel k is rescaled by a rounding
+    // shift of shift + frac_w[k] (its bias is at f_in + frac_w[k]).
+    const int32_t *frac_w = nullptr;
 };
 
 hipError_t launch_quantize(const float *x, int8_t *q, size_t n, int frac, hipStream_t st);
@@ -41,6 +45,11 @@ hipError_t launch_pool(const int8_t *x, int8_t *y, int mode, int N, int H, int W
                        int pad, int fin, int fout, hipStream_t st);
 hipError_t launch_absmax_f32(const float *x, size_t n, float *out, hipStream_t st);
 hipError_t launch_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out, hipStream_t st);
+hipError_t launch_quantize_rows(const float *x, int8_t *q, size_t rows, size_t row_len, const int32_t *frac, hipStream_t st);
+hipError_t launch_quantize_i32_rows(const float *x, int32_t *q, size_t rows, size_t row_len, const int32_t *frac, int frac_add,
+                                    hipStream_t st);
+hipError_t launch_absmax_f32_rows(const float *x, size_t rows, size_t row_len, float *out, hipStream_t st);
+hipError_t launch_absmax_i32_channels(const int32_t *x, size_t pixels, int K, int relu, uint32_t *out, hipStream_t st);
 
 bool conv_direct_supports(const ConvArgs &a);
 hipError_t launch_conv_direct(const ConvArgs &a, hipStream_t st);

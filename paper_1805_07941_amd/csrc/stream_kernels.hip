@@ -81,7 +81,47 @@ __global__ void __launch_bounds__(kBlock) dequantize_scalar(const int8_t *__rest
         x[i] = (float)q[i] * inv_scale;
 }
 
+// Row-wise forms for weights with one format per output channel: row r of x[rows][row_len] is
+// converted at the fractional length frac[r] (+ frac_add), read from device memory.
+__global__ void __launch_bounds__(kBlock) quantize_rows_kernel(const float *__restrict__ x, int8_t *__restrict__ q, size_t rows,
+                                                                size_t row_len, const int32_t *__restrict__ frac)
+{
+    const size_t n = rows * row_len;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock)
+        q[i] = (int8_t)quant_one(x[i], ldexpf(1.0f, frac[i / row_len]));
+}
+
+__global__ void __launch_bounds__(kBlock) quantize_i32_rows_kernel(const float *__restrict__ x, int32_t *__restrict__ q, size_t rows,
+                                                                    size_t row_len, const int32_t *__restrict__ frac, int frac_add)
+{
+    const size_t n = rows * row_len;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        // two exact power-of-two factors, so that a sum of fractional lengths beyond 127 cannot overflow the scale itself
+        const int f = frac[i / row_len] + frac_add;
+        float t = __builtin_rintf(x[i] * ldexpf(1.0f, f / 2) * ldexpf(1.0f, f - f / 2));
+        int32_t c;
+        if (!(t == t)) c = 0;
+        else if (t >= 2147483648.0f) c = 2147483647;
+        else if (t <= -2147483648.0f) c = -2147483647;
+        else c = (int32_t)t;
+        q[i] = c;
+    }
+}
+
 static inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+hipError_t launch_quantize_rows(const float *x, int8_t *q, size_t rows, size_t row_len, const int32_t *frac, hipStream_t st)
+{
+    quantize_rows_kernel<<<grid_for(rows * row_len), kBlock, 0, st>>>(x, q, rows, row_len, frac);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_i32_rows(const float *x, int32_t *q, size_t rows, size_t row_len, const int32_t *frac, int frac_add,
+                                    hipStream_t st)
+{
+    quantize_i32_rows_kernel<<<grid_for(rows * row_len), kBlock, 0, st>>>(x, q, rows, row_len, frac, frac_add);
+    return hipGetLastError();
+}
 
 hipError_t launch_quantize(const float *x, int8_t *q, size_t n, int frac, hipStream_t st)
 {
@@ -432,6 +472,67 @@ __global__ void __launch_bounds__(kBlock) absmax_i32_kernel(const int32_t *__res
     block_max_to(m, out);
 }
 
+// The same maximum per channel of an [pixels][K] array.  Thread t of the launch keeps channel
+// t % K and walks the pixel rows t / K, t / K + (threads / K), ... (neighbouring threads read
+// neighbouring channels of one row); with more channels than threads a thread takes several.
+__global__ void clear_u32_n(uint32_t *p, int n)
+{
+    const int i = blockIdx.x * kBlock + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+__global__ void __launch_bounds__(kBlock) absmax_i32_channels_kernel(const int32_t *__restrict__ x, size_t pixels, int K, int relu,
+                                                                      uint32_t *out)
+{
+    const size_t threads = (size_t)gridDim.x * kBlock;
+    const size_t t = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    auto fold = [&](size_t k, size_t first, size_t step) {
+        uint32_t m = 0;
+        for (size_t p = first; p < pixels; p += step) {
+            const int v = x[p * (size_t)K + k];
+            const uint32_t a = v >= 0 ? (uint32_t)v : (relu ? 0u : (uint32_t)0 - (uint32_t)v);
+            m = max(m, a);
+        }
+        if (m) atomicMax(out + k, m);
+    };
+    if (threads >= (size_t)K) {
+        const size_t rows = threads / (size_t)K;      // pixel rows in flight per pass
+        if (t / (size_t)K < rows) fold(t % (size_t)K, t / (size_t)K, rows);
+    } else {
+        for (size_t k = t; k < (size_t)K; k += threads) fold(k, 0, 1);
+    }
+}
+
+// max |.| of every row of x[rows][row_len]: one workgroup per row at a time, no atomics
+__global__ void __launch_bounds__(kBlock) absmax_f32_rows_kernel(const float *__restrict__ x, size_t rows, size_t row_len, uint32_t *out)
+{
+    __shared__ uint32_t part[kBlock / kWave];
+    for (size_t r = blockIdx.x; r < rows; r += gridDim.x) {
+        uint32_t m = 0;
+        for (size_t i = threadIdx.x; i < row_len; i += kBlock) {
+            float a = fabsf(x[r * row_len + i]);
+            if (a == a) m = max(m, __float_as_uint(a));   // skip NaN
+        }
+        m = wave_max_u32(m);
+        if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x / kWave] = m;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t t = part[0];
+#pragma unroll
+            for (int i = 1; i < kBlock / kWave; i++) t = max(t, part[i]);
+            out[r] = t;
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_absmax_f32_rows(const float *x, size_t rows, size_t row_len, float *out, hipStream_t st)
+{
+    size_t g = rows < 4096 ? rows : 4096;
+    absmax_f32_rows_kernel<<<(unsigned)g, kBlock, 0, st>>>(x, rows, row_len, (uint32_t *)out);
+    return hipGetLastError();
+}
+
 hipError_t launch_absmax_f32(const float *x, size_t n, float *out, hipStream_t st)
 {
     clear_u32<<<1, 1, 0, st>>>((uint32_t *)out);
@@ -443,6 +544,13 @@ hipError_t launch_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out
 {
     clear_u32<<<1, 1, 0, st>>>(out);
     if (n) absmax_i32_kernel<<<grid_for(n), kBlock, 0, st>>>(x, n, relu, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_absmax_i32_channels(const int32_t *x, size_t pixels, int K, int relu, uint32_t *out, hipStream_t st)
+{
+    clear_u32_n<<<(K + kBlock - 1) / kBlock, kBlock, 0, st>>>(out, K);
+    if (pixels) absmax_i32_channels_kernel<<<grid_for(pixels * (size_t)K), kBlock, 0, st>>>(x, pixels, K, relu, out);
     return hipGetLastError();
 }
 

@@ -6,7 +6,8 @@ choices are made by ``dfq_fmt_from_absmax_*`` from thresholds the device kernels
 the only host work per layer during calibration is reading one scalar back.
 
 Order of the procedure (Sec. 3): weights get the smallest power-of-two scale that holds
-max |w| of the layer; the bias becomes an integer at the product scale of input and weights;
+max |w| of the layer (or, with ``per_channel=True``, of each output channel - the paper's own
+rule); the bias becomes an integer at the product scale of input and weights;
 every layer runs on its already-quantized upstream tensors ("bootstrap"); a layer's output
 format is chosen from its 32-bit accumulators after the ReLU ("lazy" thresholding) with a
 rescale factor in (0, 1]; element-wise adds rescale the exact aligned sum once; concat rescales
@@ -17,6 +18,7 @@ from __future__ import annotations
 from dataclasses import dataclass, field
 from typing import Dict, Optional
 
+import numpy as np
 import torch
 
 import ctypes as C
@@ -27,7 +29,8 @@ from . import binding as B
 @dataclass
 class Quantized:
     frac: Dict[str, int] = field(default_factory=dict)       # tensor name -> fractional length
-    w_frac: Dict[str, int] = field(default_factory=dict)     # conv node name -> weight fractional length
+    w_frac: Dict[str, object] = field(default_factory=dict)  # conv node name -> weight fractional length (int, or numpy int32 [K])
+    w_frac_dev: Dict[str, torch.Tensor] = field(default_factory=dict)   # per-channel formats: the same [K] on the device
     w: Dict[str, torch.Tensor] = field(default_factory=dict)  # int8 [K,R,S,Cg] on the device
     b: Dict[str, torch.Tensor] = field(default_factory=dict)  # int32 [K] on the device
 
@@ -36,9 +39,10 @@ def _read_f32(t: torch.Tensor) -> float:
     return float(t.cpu()[0])
 
 
-def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True):
+def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True, per_channel: bool = False):
     """x: float32 NHWC images (or int8 codes when the network takes codes).  Returns
-    (Quantized, dict of int8 tensors of the calibration batch)."""
+    (Quantized, dict of int8 tensors of the calibration batch).
+    per_channel: one weight format per output channel instead of one per layer."""
     qz = Quantized()
     t: Dict[str, torch.Tensor] = {}
     if net.input_is_int8:
@@ -58,6 +62,30 @@ def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True):
             wf, bf = net.weights(nd)
             wf = torch.from_numpy(wf).to(device)
             bf = torch.from_numpy(bf).to(device)
+            if per_channel:
+                # channel k's weights and bias at their own scale; its accumulators are then at f_in + f_w[k],
+                # and the output format is the finest that holds every channel's maximum
+                gam = B.absmax_f32_rows(wf).cpu().numpy()
+                f_wk = np.array([B.fmt_from_absmax_f32(float(g)) for g in gam], np.int32)
+                fw_dev = torch.from_numpy(f_wk).to(device)
+                qz.w_frac[nd.name], qz.w_frac_dev[nd.name] = f_wk, fw_dev
+                qz.w[nd.name] = B.quantize_rows(wf, fw_dev)
+                qz.b[nd.name] = B.quantize_i32_rows(bf, fw_dev, f_in)
+                w, b = qz.w[nd.name], qz.b[nd.name]
+                if nd.fixed_f_out is not None:
+                    qz.frac[nd.dst] = nd.fixed_f_out
+                else:
+                    _, acc = B.conv_q_pc(t[src], w, b, f_in, fw_dev, 0, nd.stride, nd.pad, nd.groups, nd.relu,
+                                         want_y=False, want_acc=True)
+                    m = B.absmax_i32_channels_value(B.absmax_i32_channels(acc, relu=nd.relu))
+                    del acc
+                    qz.frac[nd.dst] = min(B.fmt_from_absmax_i32(int(m[k]), f_in + int(f_wk[k])) for k in range(len(m)))
+                t[nd.dst], _ = B.conv_q_pc(t[src], w, b, f_in, fw_dev, qz.frac[nd.dst], nd.stride, nd.pad, nd.groups, nd.relu)
+                if not keep_tensors:
+                    for s in nd.srcs:
+                        if last_use.get(s) == idx and s != net.output_name:
+                            t.pop(s, None)
+                continue
             f_w = B.fmt_from_absmax_f32(_read_f32(B.absmax_f32(wf)))
             qz.w_frac[nd.name] = f_w
             qz.w[nd.name] = B.quantize(wf, f_w)
@@ -145,6 +173,8 @@ class Plan:
                 continue
             if c.dst == net.output_name or e.srcs[0] == e.srcs[1]:
                 continue
+            if c.name in qz.w_frac_dev:      # the fused kernel takes one weight format per layer
+                continue
             pairs[i] = i + 1
         return pairs
 
@@ -220,7 +250,15 @@ class Plan:
                 if nd.dst not in t:
                     P, Q, Kd = net.shapes[nd.dst]
                     t[nd.dst] = torch.empty((self.batch, P, Q, Kd), dtype=torch.int8, device=self.device)
-            if nd.op == "conv":
+            if nd.op == "conv" and nd.name in qz.w_frac_dev:
+                src = nd.srcs[0]
+                N, H, W, Cc = t[src].shape
+                K = nd.K
+                calls.append((L.dfq_conv_q_pc, (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(),
+                                                t[nd.dst].data_ptr(), None, N, H, W, Cc, K, nd.R, nd.R, nd.stride, nd.pad,
+                                                nd.groups, K, f(qz.frac[src]), qz.w_frac_dev[nd.name].data_ptr(),
+                                                f(qz.frac[nd.dst]), int(nd.relu))))
+            elif nd.op == "conv":
                 src = nd.srcs[0]
                 N, H, W, Cc = t[src].shape
                 K = nd.K

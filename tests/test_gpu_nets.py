@@ -97,7 +97,9 @@ def test_config1_layers_full_size_sampled(G, i, batch):
 
 def _compare_calibration(net, qz_o, t_o, qz_g, t_g):
     assert qz_g.frac == qz_o.frac
-    assert qz_g.w_frac == qz_o.w_frac
+    assert qz_g.w_frac.keys() == qz_o.w_frac.keys()
+    for name in qz_o.w_frac:
+        assert np.array_equal(np.asarray(qz_g.w_frac[name]), np.asarray(qz_o.w_frac[name])), name
     for name in qz_o.w:
         assert np.array_equal(host(qz_g.w[name]), qz_o.w[name]), name
         assert np.array_equal(host(qz_g.b[name]), qz_o.b[name]), name
@@ -150,6 +152,32 @@ def test_config3_and_4_networks(G, which):
     plan2 = gnet.Plan(net, qz_g, batch, keep_all=False)
     assert np.array_equal(host(plan2.run(dev(x))), logits)
     assert np.abs(logits).max() > 0
+
+
+@pytest.mark.parametrize("which", ["mobilenet_v1", "resnet50"])
+def test_per_channel_weight_formats_networks(G, which):
+    """One weight format per output channel (Sec. 3): calibration and inference agree with the oracle
+    in every format, weight, bias, int8 tensor and logit."""
+    B, gnet = G
+    batch = 16
+    net = getattr(wl, which)(batch=batch, hw=96, classes=100)
+    x = net.input_float()
+    calib = x[:2]
+    qz_o, t_o = onet.calibrate(net, calib, per_channel=True)
+    qz_g, t_g = gnet.calibrate(net, dev(calib), per_channel=True)
+    _compare_calibration(net, qz_o, t_o, qz_g, t_g)
+    assert any(len(set(np.asarray(v).tolist())) > 1 for v in qz_o.w_frac.values())     # the formats do differ by channel
+    del t_g
+    for kw in (dict(), dict(keep_all=False, fuse=True)):
+        plan = gnet.Plan(net, qz_g, batch, **kw)
+        logits = host(plan.run(dev(x))).copy()
+        for i in (0, batch - 1):
+            t = onet.infer(net, qz_o, x[i:i + 1])
+            assert np.array_equal(logits[i:i + 1], onet.logits(net, qz_o, t))
+            if not kw:
+                for name in t:
+                    assert np.array_equal(host(plan.buf[name][i:i + 1]), t[name]), (i, name)
+        assert np.array_equal(host(plan.run_graph(dev(x))), logits)
 
 
 def test_fused_joins_give_the_same_logits(G):

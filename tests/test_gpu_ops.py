@@ -268,3 +268,69 @@ def test_mfma_rate_probe_runs_the_stated_work(B):
     ops = B.mfma_rate_probe(ones, ones, sink, blocks, iters)
     assert ops == blocks * 8 * iters * 8 * 2 * 32 ** 3
     assert np.array_equal(host(sink), np.full(blocks * 512, 8 * 16 * 32 * iters, dtype=np.int32))
+
+
+PC_SHAPES = [
+    # N  H   W   C    K   R  S  st pad groups
+    (1, 5, 5, 3, 4, 3, 3, 1, 1, 1),              # direct kernel
+    (2, 9, 7, 16, 24, 3, 3, 2, 1, 1),            # dense kernel, ragged channel tail
+    (3, 14, 14, 64, 64, 3, 3, 1, 1, 1),
+    (2, 23, 21, 256, 384, 1, 1, 1, 0, 1),        # pointwise geometry: the dense kernel takes it
+    (1, 9, 9, 512, 128, 1, 1, 1, 0, 1),
+    (1, 23, 23, 3, 64, 7, 7, 2, 3, 1),           # stem-like
+    (2, 72, 72, 3, 64, 7, 7, 2, 3, 1),           # stem-like, row-staging kernel
+    (2, 10, 10, 32, 32, 3, 3, 1, 1, 32),         # depthwise
+    (2, 11, 9, 64, 64, 3, 3, 2, 1, 64),          # depthwise stride 2
+    (1, 8, 8, 16, 32, 3, 3, 1, 1, 4),            # grouped
+    (5, 1, 1, 256, 100, 1, 1, 1, 0, 1),          # fully connected
+    (4, 223, 224, 64, 256, 1, 1, 2, 0, 1),       # enough tiles for the dense kernel's largest tile shape
+]
+
+
+@pytest.mark.parametrize("shape", PC_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv_q_per_channel_weight_formats(B, shape):
+    """dfq_conv_q_pc against the oracle: every channel rescaled by its own shift (Sec. 3), bytes and
+    accumulators identical; equal entries reproduce dfq_conv_q."""
+    N, H, W, C, K, R, S, st, pad, g = shape
+    rng = np.random.default_rng(abs(hash(("pc",) + shape)) % (2 ** 31))
+    x, w, b = _rand_conv(rng, N, H, W, C, K, R, S, g)
+    xd, wd, bd = dev(x), dev(w), dev(b)
+    for f_in, f_out, relu, lo, hi in [(4, 4, 1, 3, 11), (3, 2, 0, 0, 8), (5, -3, 1, 5, 9), (2, 6, 0, -2, 3)]:
+        f_w = rng.integers(lo, hi + 1, K).astype(np.int32)
+        y_ref, acc_ref = orc.conv_q(x, w, b, f_in, f_w, f_out, st, pad, g, relu, want_acc=True)
+        y, acc = B.conv_q_pc(xd, wd, bd, f_in, dev(f_w), f_out, st, pad, g, relu, want_acc=True)
+        assert np.array_equal(host(acc), acc_ref)
+        assert np.array_equal(host(y), y_ref), (f_in, f_out, relu)
+        y2, _ = B.conv_q_pc(xd, wd, bd, f_in, dev(f_w), f_out, st, pad, g, relu)       # without the accumulator dump
+        assert np.array_equal(host(y2), y_ref), (f_in, f_out, relu)
+    same = np.full(K, 7, np.int32)
+    y_pc, _ = B.conv_q_pc(xd, wd, bd, 4, dev(same), 3, st, pad, g, True)
+    y_pl, _ = B.conv_q(xd, wd, bd, 4, 7, 3, st, pad, g, True)
+    assert np.array_equal(host(y_pc), host(y_pl))
+
+
+def test_row_wise_weight_preparation(B):
+    """Per-row thresholds and conversions (weights with one format per output channel) against the
+    oracle's per-row calls."""
+    rng = np.random.default_rng(31)
+    wf = (rng.standard_normal((37, 3, 3, 5)) * rng.uniform(0.01, 3.0, (37, 1, 1, 1))).astype(np.float32)
+    wf[5] = 0.0
+    bf = (rng.standard_normal(37) * 0.3).astype(np.float32)
+    gam = host(B.absmax_f32_rows(dev(wf)))
+    assert np.array_equal(gam, np.array([orc.absmax_f32(wf[k]) for k in range(37)], np.float32))
+    f_w = np.array([orc.frac_from_absmax_f32(float(g)) for g in gam], np.int32)
+    assert [B.fmt_from_absmax_f32(float(g)) for g in gam] == f_w.tolist()
+    q = host(B.quantize_rows(dev(wf), dev(f_w)))
+    assert np.array_equal(q, np.stack([orc.quantize(wf[k], int(f_w[k])) for k in range(37)]))
+    for f_in in (-3, 4, 9):
+        qb = host(B.quantize_i32_rows(dev(bf), dev(f_w), f_in))
+        assert np.array_equal(qb, np.array([orc.quantize_i32(bf[k:k + 1], f_in + int(f_w[k]))[0] for k in range(37)], np.int32))
+
+
+def test_absmax_per_channel(B):
+    rng = np.random.default_rng(32)
+    for shape in [(3, 5, 7, 24), (1, 1, 1, 1000), (2, 9, 9, 3), (1, 300, 300, 16)]:
+        a = rng.integers(-2 ** 31, 2 ** 31, shape).astype(np.int32)
+        for relu in (False, True):
+            got = B.absmax_i32_channels_value(B.absmax_i32_channels(dev(a), relu=relu)).astype(np.int64)
+            assert np.array_equal(got, orc.absmax_i32_channels(a, relu=relu)), (shape, relu)
