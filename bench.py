@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the per-launch events (pure step timing)")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a HIP graph")
     ap.add_argument("--no-fuse", action="store_true", help="run every residual add as its own dfq_eltwise_q call")
+    ap.add_argument("--per-channel", action="store_true",
+                    help="one weight format per output channel (dfq_conv_q_pc) instead of one per layer")
     ap.add_argument("--no-mfma-rate", action="store_true", help="skip the register-only matrix-instruction rate probe")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three 256 MiB device copies (a kernel of known traffic, to scale HBM counters by)")
@@ -97,7 +99,7 @@ def main():
     net = wl.resnet50(batch=args.batch)
     x_host = net.input_float()
     x = torch.from_numpy(x_host).to(dev)
-    qz, _ = gnet.calibrate(net, x[:args.calib].contiguous(), keep_tensors=False)
+    qz, _ = gnet.calibrate(net, x[:args.calib].contiguous(), keep_tensors=False, per_channel=args.per_channel)
     plan = gnet.Plan(net, qz, args.batch, keep_all=False, fuse=not args.no_fuse)
 
     convs = conv_nodes(net)
@@ -117,7 +119,7 @@ def main():
     def run_step_recorded():
         st = B._stream(None)
         for (fn, cargs), name in zip(plan._calls_for(x), plan.call_nodes):
-            mf = name in mfma_names and fn.__name__ in ("dfq_conv_q", "dfq_conv_q_add")
+            mf = name in mfma_names and fn.__name__ in ("dfq_conv_q", "dfq_conv_q_add", "dfq_conv_q_pc")
             if mf:
                 e0, e1 = event_pool.pop(), event_pool.pop()
                 e0.record()
@@ -253,6 +255,7 @@ def main():
         "launch": "per-call from Python" if args.no_graph else "HIP graph replay of the fixed call sequence",
         "joins": "each residual add its own dfq_eltwise_q call" if args.no_fuse else
                  "%d of %d residual adds run inside the convolution in front of them (dfq_conv_q_add)" % (n_fused, n_joins),
+        "weight_formats": "one per output channel (dfq_conv_q_pc)" if args.per_channel else "one per layer",
         "config": {"workload": "configs[4]: ResNet-50-shaped int8 network, 224x224x3, batch %d, formats from a "
                                "single-batch calibrate() on %d images" % (args.batch, args.calib),
                    "global_batch": args.batch},

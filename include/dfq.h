@@ -114,16 +114,18 @@ dfq_status dfq_conv_q_variant(dfq_conv_variant variant,
 
 /* The same layer with one weight format per OUTPUT CHANNEL (Sec. 3, "Calibrating": the weight
  * thresholds are maxima per output channel).  frac_w: DEVICE array of K fractional lengths,
- * 4-byte aligned, read by the kernel (the library cannot range-check it: every entry must lie
- * in [-32, 32]; any integer shift is still well defined).  w[k][.][.][.] holds codes at
+ * 4-byte aligned, read by the kernel only.  frac_w_lo <= frac_w_hi, both in [-32, 32]: bounds
+ * the CALLER guarantees for every entry (it computed them); the library picks its kernel from
+ * them and cannot check the array itself - an entry outside the declared bounds gives an
+ * unspecified code for that channel (never a fault).  w[k][.][.][.] holds codes at
  * frac_w[k], b[k] is at fmt_in.frac + frac_w[k], and channel k is rescaled by one rounding
  * shift of fmt_in.frac + frac_w[k] - fmt_out.frac.  Everything else, including errors and the
  * optional accumulator dump, as dfq_conv_q.  With equal entries the result is that of
  * dfq_conv_q at that format. */
 dfq_status dfq_conv_q_pc(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int32_t *acc_out,
                          int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
-                         int ldy, dfq_fmt fmt_in, const int32_t *frac_w, dfq_fmt fmt_out, int relu,
-                         dfq_stream stream);
+                         int ldy, dfq_fmt fmt_in, const int32_t *frac_w, int frac_w_lo, int frac_w_hi,
+                         dfq_fmt fmt_out, int relu, dfq_stream stream);
 
 /* Convolution followed by an element-wise add, in one kernel (Sec. 3: adjacent operations are
  * merged; Eq. 10 for the add).  The result is exactly that of

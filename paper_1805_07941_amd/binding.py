@@ -65,7 +65,7 @@ def lib():
     conv_args = [vp, vp, vp, vp, vp] + [i32] * 11 + [Fmt, Fmt, Fmt, i32, vp]
     L.dfq_conv_q.argtypes = conv_args
     L.dfq_conv_q_variant.argtypes = [i32] + conv_args
-    L.dfq_conv_q_pc.argtypes = [vp, vp, vp, vp, vp] + [i32] * 11 + [Fmt, vp, Fmt, i32, vp]
+    L.dfq_conv_q_pc.argtypes = [vp, vp, vp, vp, vp] + [i32] * 11 + [Fmt, vp, i32, i32, Fmt, i32, vp]
     L.dfq_absmax_i32_channels.argtypes = [vp, sz, i32, i32, vp, vp]
     L.dfq_absmax_f32_rows.argtypes = [vp, sz, sz, vp, vp]
     L.dfq_quantize_rows.argtypes = [vp, vp, sz, sz, vp, vp]
@@ -184,9 +184,11 @@ def conv_q(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], f_in: in
 def conv_q_pc(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], f_in: int, frac_w: torch.Tensor, f_out: int,
               stride: int = 1, pad: int = 0, groups: int = 1, relu: bool = False,
               out: Optional[torch.Tensor] = None, ldy: Optional[int] = None,
-              want_y: bool = True, want_acc: bool = False, acc_out: Optional[torch.Tensor] = None, stream=None):
+              want_y: bool = True, want_acc: bool = False, acc_out: Optional[torch.Tensor] = None,
+              frac_w_range=None, stream=None):
     """conv_q with one weight format per output channel: frac_w is an int32 device tensor [K];
-    b[k] is at f_in + frac_w[k].  Returns (y, acc)."""
+    b[k] is at f_in + frac_w[k].  frac_w_range = (lowest, highest) entry as the caller knows them; read
+    back from the device (a synchronization) when not given.  Returns (y, acc)."""
     _dev(x, torch.int8, "x"); _dev(w, torch.int8, "w"); _dev(frac_w, torch.int32, "frac_w")
     if b is not None:
         _dev(b, torch.int32, "b")
@@ -203,9 +205,12 @@ def conv_q_pc(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], f_in:
     acc = acc_out
     if acc is None and want_acc:
         acc = torch.empty((N, max(P, 0), max(Q, 0), K), dtype=torch.int32, device=x.device)
+    if frac_w_range is None:
+        fh = frac_w.cpu()
+        frac_w_range = (int(fh.min()), int(fh.max()))
     st = lib().dfq_conv_q_pc(_ptr(x), _ptr(w), _ptr(b), _ptr(y), _ptr(acc), N, H, W, Cc, K, R, S, stride, pad, groups,
-                             K if ldy is None else int(ldy), fmt(f_in), _ptr(frac_w), fmt(f_out), int(bool(relu)),
-                             _stream(stream))
+                             K if ldy is None else int(ldy), fmt(f_in), _ptr(frac_w), int(frac_w_range[0]),
+                             int(frac_w_range[1]), fmt(f_out), int(bool(relu)), _stream(stream))
     _check(st, "dfq_conv_q_pc")
     return y, acc
 

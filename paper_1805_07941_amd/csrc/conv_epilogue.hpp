@@ -76,6 +76,28 @@ __device__ __forceinline__ uint4 requant_tile_lane_fast(const v16i &v, const Req
     return make_uint4(rq.fast_four(v[0], v[1], v[2], v[3]), rq.fast_four(v[4], v[5], v[6], v[7]),
                       rq.fast_four(v[8], v[9], v[10], v[11]), rq.fast_four(v[12], v[13], v[14], v[15]));
 }
+// The hot form with one weight format per output channel: the four sums belong to four channels,
+// each with its own shift s in [0, 23]; hi = 127 << s, badd = 2^(s-1) - 1 (0 for s = 0) come from a
+// per-channel table.  Same four instructions per value as the uniform form, operands in registers.
+__device__ __forceinline__ uint32_t requant_four_per_channel(int v0, int v1, int v2, int v3, const int4 &s, const int4 &hi,
+                                                             const int4 &badd, int relu)
+{
+    int t[4] = {v0, v1, v2, v3};
+    const int sv[4] = {s.x, s.y, s.z, s.w}, hv[4] = {hi.x, hi.y, hi.z, hi.w}, bv[4] = {badd.x, badd.y, badd.z, badd.w};
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int lo = relu ? 0 : -hv[i];
+        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(t[i]) : "v"(t[i]), "v"(lo), "v"(hv[i]));
+        t[i] = t[i] + bv[i] + (int)__builtin_amdgcn_ubfe((unsigned)t[i], (unsigned)sv[i], (unsigned)min(sv[i], 1));
+    }
+    uint32_t w;
+    asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD" : "=v"(w) : "v"(sv[0]), "v"(t[0]));
+    asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sv[1]), "v"(t[1]));
+    asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sv[2]), "v"(t[2]));
+    asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sv[3]), "v"(t[3]));
+    return w;
+}
+
 // The same followed by the fused add of Eq. 10: the sixteen int8 results of the convolution (kept as
 // integers, never stored) and the sixteen codes of the second operand in `other` are aligned to the
 // finer of their two scales, summed and rounded once more with rq2.

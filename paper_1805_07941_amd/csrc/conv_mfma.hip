@@ -55,9 +55,12 @@ struct MfmaParams {
 // GENERAL: the epilogue may meet a ragged channel tail, an unaligned or strided-odd output row, a
 // shift outside [0, 23] or an accumulator dump; the launcher picks the lean instantiation
 // (GENERAL = false) whenever none of these applies.  OCC: wavefronts per SIMD to fit registers for.
-template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool PW, bool GENERAL, int OCC>
+// PC (needs UT, excludes GENERAL): the lean epilogue with one weight format per output channel, every
+// channel's shift within [0, 23] (the caller of the library vouches for the range of the formats).
+template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool PW, bool GENERAL, int OCC, bool PC = false>
 __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(MfmaParams prm)
 {
+    static_assert(!PC || (UT && !GENERAL), "the per-channel lean form is built for uniform taps only");
     static_assert(NSTAGES >= 2 && NSTAGES <= 6, "ring depth");
     static_assert(UT || !PW, "the pointwise form keeps its position in scalar registers");
     constexpr int NW = WAVES_P * WAVES_C;                 // wavefronts per workgroup
@@ -76,7 +79,8 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
     static_assert(WP % 32 == 0 && WC % 32 == 0, "tile shape");
     static_assert(NSTAGES * LPW < 64, "outstanding loads must fit the 6-bit counter");
 
-    extern __shared__ uint4 lds[];   // nstages stages of (BP + BC) rows of 64 bytes, then BC bias words
+    extern __shared__ uint4 lds[];   // nstages stages of (BP + BC) rows of 64 bytes, then BC bias words, then 3 * BC words
+                                     // of per-channel rescale constants (used with one weight format per channel)
 
     const ConvArgs &a = prm.a;
     const int tid = threadIdx.x;
@@ -105,10 +109,20 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
     const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, GENERAL ? 0 : (int)prm.y_bytes, 0x00020000);
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char *)(char *)&lds[0];
     int *bias_lds = (int *)(lds + nstages * STAGE_PIECES);
+    int *pc_shift = bias_lds + BC, *pc_hi = pc_shift + BC, *pc_badd = pc_hi + BC;
 
     // ---- bias of this channel tile into LDS (re-read at every tile start without touching the
     // vector-memory counter that paces the load ring)
     for (int i = tid; i < BC; i += NW * 64) bias_lds[i] = (a.b && k0 + i < a.K) ? a.b[k0 + i] : 0;
+    // one weight format per output channel: rescale constants of every channel of the tile
+    if (PC) {
+        for (int i = tid; i < BC; i += NW * 64) {
+            const int sk = (a.shift + a.frac_w[k0 + i]) & 31;       // K % BC == 0 here; in [0, 23] by the caller's word
+            pc_shift[i] = sk;
+            pc_hi[i] = 127 << min(sk, 23);
+            pc_badd[i] = sk > 0 ? ((1 << (sk - 1)) - 1) : 0;
+        }
+    }
 
     // ---- producer bookkeeping.  A wavefront-wide load covers RPC consecutive rows (one chunk) of
     // the stage; lane l supplies row l/4 of the chunk, physical piece l%4, which holds logical piece
@@ -235,7 +249,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
 
     Requant rq;
     rq.init(a.shift, a.relu);
-    __syncthreads();   // bias_lds complete
+    __syncthreads();   // bias_lds and the per-channel constants complete
 
     // accumulators start at the bias: register r of a lane belongs to channel kc + r
     v16i acc[CT][PT];
@@ -302,11 +316,33 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
             const int m0 = fastdiv(c_tile, prm.div_tc) * BP;
             if (!GENERAL) {
                 const unsigned tile_off = (unsigned)(m0 * a.ldy);
+                if constexpr (PC) {
 #pragma unroll
-                for (int c = 0; c < CT; c++)
+                    for (int c = 0; c < CT; c++) {
+                        const int kr = wc0 + c * 32 + 16 * lh;
+                        uint32_t o[PT][4];
 #pragma unroll
-                    for (int p = 0; p < PT; p++)
-                        store_piece(requant_tile_lane_fast(acc[c][p], rq), lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32), yrsrc);
+                        for (int r4 = 0; r4 < 4; r4++) {
+                            const int4 sv = *(const int4 *)(pc_shift + kr + 4 * r4);
+                            const int4 hv = *(const int4 *)(pc_hi + kr + 4 * r4);
+                            const int4 bv = *(const int4 *)(pc_badd + kr + 4 * r4);
+#pragma unroll
+                            for (int p = 0; p < PT; p++)
+                                o[p][r4] = requant_four_per_channel(acc[c][p][4 * r4], acc[c][p][4 * r4 + 1], acc[c][p][4 * r4 + 2],
+                                                                    acc[c][p][4 * r4 + 3], sv, hv, bv, a.relu);
+                        }
+#pragma unroll
+                        for (int p = 0; p < PT; p++)
+                            store_piece(make_uint4(o[p][0], o[p][1], o[p][2], o[p][3]),
+                                        lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32), yrsrc);
+                    }
+                } else {
+#pragma unroll
+                    for (int c = 0; c < CT; c++)
+#pragma unroll
+                        for (int p = 0; p < PT; p++)
+                            store_piece(requant_tile_lane_fast(acc[c][p], rq), lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32), yrsrc);
+                }
                 ep_hist |= 1u;
             } else {
 #pragma unroll
@@ -394,8 +430,9 @@ inline hipError_t big_lds(void (*k)(MfmaParams))
     return hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
 }
 
-// NSTAGES ring stages of (BP + BC) * 64 bytes plus the bias must fit the LDS share of a
-// workgroup: 160 KB / (workgroups per compute unit).
+// NSTAGES ring stages of (BP + BC) * 64 bytes plus the bias and the per-channel rescale tables (four
+// words per channel of the tile) must fit the LDS share of a workgroup: 160 KB / (workgroups per
+// compute unit).
 // PER_CU: workgroups per compute unit the kernel is built and launched for (1 or 2)
 template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, int PER_CU>
 hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
@@ -422,24 +459,28 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     if (grid > prm.tiles) grid = prm.tiles;
     grid = grid / prm.tiles_c * prm.tiles_c;            // the channel tile of a workgroup must not change
     if (grid < prm.tiles_c) grid = prm.tiles_c;
-    constexpr size_t lds_bytes = (size_t)NSTAGES * (BP + BC) * kStepBytes + BC * 4;
+    constexpr size_t lds_bytes = (size_t)NSTAGES * (BP + BC) * kStepBytes + BC * 4 * 4;   // rings, bias, three per-channel tables
     static_assert(lds_bytes * PER_CU <= kLdsBytes, "rings do not fit the LDS");
 
     const bool ut = a.C % kStepBytes == 0;
-    const bool general = !(!a.frac_w && a.shift >= 0 && a.shift <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
+    // shifts the epilogue will meet: one, or with per-channel weight formats the declared range
+    const int s_lo = a.shift + (a.frac_w ? a.frac_w_lo : 0), s_hi = a.shift + (a.frac_w ? a.frac_w_hi : 0);
+    const bool general = !((!a.frac_w || ut) && s_lo >= 0 && s_hi <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
                            ((uintptr_t)a.y & 15) == 0 && a.K % BC == 0 && y_bytes < (1LL << 31));
     constexpr int occ = PER_CU * WAVES_P * WAVES_C / 4;
     using K = void (*)(MfmaParams);
     const bool pw = ut && a.R == 1 && a.S == 1 && a.stride == 1 && a.pad == 0;
-    static const K kernels[6] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, false, occ>,
+    static const K kernels[8] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, false, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, true, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, false, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, true, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, false, occ>,
-                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, true, occ>};
-    static const hipError_t attr[6] = {big_lds(kernels[0]), big_lds(kernels[1]), big_lds(kernels[2]),
-                                       big_lds(kernels[3]), big_lds(kernels[4]), big_lds(kernels[5])};
-    const int which = (pw ? 4 : ut ? 2 : 0) + (general ? 1 : 0);
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, true, occ>,
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, false, occ, true>,
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, false, occ, true>};
+    static const hipError_t attr[8] = {big_lds(kernels[0]), big_lds(kernels[1]), big_lds(kernels[2]), big_lds(kernels[3]),
+                                       big_lds(kernels[4]), big_lds(kernels[5]), big_lds(kernels[6]), big_lds(kernels[7])};
+    const int which = (!general && a.frac_w) ? (pw ? 7 : 6) : (pw ? 4 : ut ? 2 : 0) + (general ? 1 : 0);
     if (attr[which] != hipSuccess) return attr[which];
     K kernel = kernels[which];
     kernel<<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);

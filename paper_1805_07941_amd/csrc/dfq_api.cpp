@@ -160,14 +160,17 @@ dfq_status dfq_conv_q_variant(dfq_conv_variant variant, const int8_t *x, const i
 
 dfq_status dfq_conv_q_pc(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int32_t *acc_out, int N, int H,
                          int W, int C, int K, int R, int S, int stride, int pad, int groups, int ldy, dfq_fmt fmt_in,
-                         const int32_t *frac_w, dfq_fmt fmt_out, int relu, dfq_stream stream)
+                         const int32_t *frac_w, int frac_w_lo, int frac_w_hi, dfq_fmt fmt_out, int relu, dfq_stream stream)
 {
+    if (frac_w_lo > frac_w_hi || frac_w_lo < -32 || frac_w_hi > 32) return DFQ_EFMT;
     ConvCheck c = check_conv(x, w, b, y, acc_out, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, dfq_fmt{8, 0},
                              fmt_out, relu, true);
     if (c.st != DFQ_OK) return c.st;
     if (!frac_w || ((uintptr_t)frac_w & 3)) return DFQ_EINVAL;
     if (N == 0) return DFQ_OK;
     c.a.frac_w = frac_w;          // c.a.shift is f_in - f_out (the placeholder weight format has frac 0)
+    c.a.frac_w_lo = frac_w_lo;
+    c.a.frac_w_hi = frac_w_hi;
     return run_conv(DFQ_CONV_AUTO, c.a, (hipStream_t)stream);
 }
 

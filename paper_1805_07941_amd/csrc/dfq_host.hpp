@@ -30,8 +30,10 @@ struct ConvArgs {
     int add_relu = 0;
     // One weight format per output channel (Sec. 3), or frac_w == null: a device array of K
     // fractional lengths; `shift` then holds f_in - f_out and channel k is rescaled by a rounding
-    // shift of shift + frac_w[k] (its bias is at f_in + frac_w[k]).
+    // shift of shift + frac_w[k] (its bias is at f_in + frac_w[k]).  The host cannot read the array:
+    // kernels that need every shift in a certain range are chosen from the declared bounds.
     const int32_t *frac_w = nullptr;
+    int frac_w_lo = 0, frac_w_hi = 0;   // bounds the caller guarantees for the entries of frac_w
 };
 
 hipError_t launch_quantize(const float *x, int8_t *q, size_t n, int frac, hipStream_t st);

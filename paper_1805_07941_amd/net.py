@@ -76,11 +76,12 @@ def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True, 
                     qz.frac[nd.dst] = nd.fixed_f_out
                 else:
                     _, acc = B.conv_q_pc(t[src], w, b, f_in, fw_dev, 0, nd.stride, nd.pad, nd.groups, nd.relu,
-                                         want_y=False, want_acc=True)
+                                         want_y=False, want_acc=True, frac_w_range=(int(f_wk.min()), int(f_wk.max())))
                     m = B.absmax_i32_channels_value(B.absmax_i32_channels(acc, relu=nd.relu))
                     del acc
                     qz.frac[nd.dst] = min(B.fmt_from_absmax_i32(int(m[k]), f_in + int(f_wk[k])) for k in range(len(m)))
-                t[nd.dst], _ = B.conv_q_pc(t[src], w, b, f_in, fw_dev, qz.frac[nd.dst], nd.stride, nd.pad, nd.groups, nd.relu)
+                t[nd.dst], _ = B.conv_q_pc(t[src], w, b, f_in, fw_dev, qz.frac[nd.dst], nd.stride, nd.pad, nd.groups, nd.relu,
+                                           frac_w_range=(int(f_wk.min()), int(f_wk.max())))
                 if not keep_tensors:
                     for s in nd.srcs:
                         if last_use.get(s) == idx and s != net.output_name:
@@ -257,6 +258,7 @@ class Plan:
                 calls.append((L.dfq_conv_q_pc, (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(),
                                                 t[nd.dst].data_ptr(), None, N, H, W, Cc, K, nd.R, nd.R, nd.stride, nd.pad,
                                                 nd.groups, K, f(qz.frac[src]), qz.w_frac_dev[nd.name].data_ptr(),
+                                                int(qz.w_frac[nd.name].min()), int(qz.w_frac[nd.name].max()),
                                                 f(qz.frac[nd.dst]), int(nd.relu))))
             elif nd.op == "conv":
                 src = nd.srcs[0]
