@@ -317,19 +317,30 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
             if (!GENERAL) {
                 const unsigned tile_off = (unsigned)(m0 * a.ldy);
                 if constexpr (PC) {
+                    // groups of four channels; the constants of the next group are fetched while this one is
+                    // rescaled, and the scheduler is kept from hoisting all fetches to the front (registers)
+                    const int kr0 = wc0 + 16 * lh;
+                    int4 sv = *(const int4 *)(pc_shift + kr0), hv = *(const int4 *)(pc_hi + kr0), bv = *(const int4 *)(pc_badd + kr0);
 #pragma unroll
                     for (int c = 0; c < CT; c++) {
-                        const int kr = wc0 + c * 32 + 16 * lh;
                         uint32_t o[PT][4];
 #pragma unroll
                         for (int r4 = 0; r4 < 4; r4++) {
-                            const int4 sv = *(const int4 *)(pc_shift + kr + 4 * r4);
-                            const int4 hv = *(const int4 *)(pc_hi + kr + 4 * r4);
-                            const int4 bv = *(const int4 *)(pc_badd + kr + 4 * r4);
+                            const int g = c * 4 + r4 + 1;                       // next group
+                            const int kn = wc0 + (g / 4) * 32 + 16 * lh + 4 * (g % 4);
+                            int4 sn = sv, hn = hv, bn = bv;
+                            if (g < CT * 4) {
+                                sn = *(const int4 *)(pc_shift + kn);
+                                hn = *(const int4 *)(pc_hi + kn);
+                                bn = *(const int4 *)(pc_badd + kn);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                             for (int p = 0; p < PT; p++)
                                 o[p][r4] = requant_four_per_channel(acc[c][p][4 * r4], acc[c][p][4 * r4 + 1], acc[c][p][4 * r4 + 2],
                                                                     acc[c][p][4 * r4 + 3], sv, hv, bv, a.relu);
+                            __builtin_amdgcn_sched_barrier(0);
+                            sv = sn; hv = hn; bv = bn;
                         }
 #pragma unroll
                         for (int p = 0; p < PT; p++)
@@ -427,6 +438,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
 
 inline hipError_t big_lds(void (*k)(MfmaParams))
 {
+    if (!k) return hipSuccess;
     return hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
 }
 
@@ -434,6 +446,18 @@ inline hipError_t big_lds(void (*k)(MfmaParams))
 // words per channel of the tile) must fit the LDS share of a workgroup: 160 KB / (workgroups per
 // compute unit).
 // PER_CU: workgroups per compute unit the kernel is built and launched for (1 or 2)
+// The per-channel lean form holds a group's rescale constants in registers on top of everything
+// else: it is built for the tile shapes whose register budget has room for them (wavefront tiles of
+// 64 x 64 at no more than three wavefronts per SIMD).
+template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool PW, int OCC>
+constexpr void (*per_channel_kernel())(MfmaParams)
+{
+    if constexpr (OCC <= 3 && (BP / WAVES_P) * (BC / WAVES_C) <= 64 * 64)
+        return conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, PW, false, OCC, true>;
+    else
+        return nullptr;
+}
+
 template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, int PER_CU>
 hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
 {
@@ -462,13 +486,9 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     constexpr size_t lds_bytes = (size_t)NSTAGES * (BP + BC) * kStepBytes + BC * 4 * 4;   // rings, bias, three per-channel tables
     static_assert(lds_bytes * PER_CU <= kLdsBytes, "rings do not fit the LDS");
 
-    const bool ut = a.C % kStepBytes == 0;
-    // shifts the epilogue will meet: one, or with per-channel weight formats the declared range
-    const int s_lo = a.shift + (a.frac_w ? a.frac_w_lo : 0), s_hi = a.shift + (a.frac_w ? a.frac_w_hi : 0);
-    const bool general = !((!a.frac_w || ut) && s_lo >= 0 && s_hi <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
-                           ((uintptr_t)a.y & 15) == 0 && a.K % BC == 0 && y_bytes < (1LL << 31));
     constexpr int occ = PER_CU * WAVES_P * WAVES_C / 4;
     using K = void (*)(MfmaParams);
+    const bool ut = a.C % kStepBytes == 0;
     const bool pw = ut && a.R == 1 && a.S == 1 && a.stride == 1 && a.pad == 0;
     static const K kernels[8] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, false, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, true, occ>,
@@ -476,10 +496,14 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, true, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, false, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, true, occ>,
-                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, false, occ, true>,
-                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, false, occ, true>};
+                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, occ>(),
+                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, occ>()};
     static const hipError_t attr[8] = {big_lds(kernels[0]), big_lds(kernels[1]), big_lds(kernels[2]), big_lds(kernels[3]),
                                        big_lds(kernels[4]), big_lds(kernels[5]), big_lds(kernels[6]), big_lds(kernels[7])};
+    // shifts the epilogue will meet: one, or with per-channel weight formats the declared range
+    const int s_lo = a.shift + (a.frac_w ? a.frac_w_lo : 0), s_hi = a.shift + (a.frac_w ? a.frac_w_hi : 0);
+    const bool general = !((!a.frac_w || (ut && kernels[6])) && s_lo >= 0 && s_hi <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
+                           ((uintptr_t)a.y & 15) == 0 && a.K % BC == 0 && y_bytes < (1LL << 31));
     const int which = (!general && a.frac_w) ? (pw ? 7 : 6) : (pw ? 4 : ut ? 2 : 0) + (general ? 1 : 0);
     if (attr[which] != hipSuccess) return attr[which];
     K kernel = kernels[which];
@@ -517,6 +541,8 @@ hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st)
     // else:    256 x 128 tiles (eight wavefronts), two workgroups per CU, for kernels larger than 1x1;
     //          for 1x1 kernels (few items per tile) 128 x 128 tiles (four wavefronts), three per CU.
     const bool pointwise = a.R == 1 && a.S == 1;
+    // one weight format per output channel: the tile shapes for which that epilogue is built
+    if (a.frac_w && a.K > 64) return launch_cfg<128, 128, 2, 2, 3, 3>(a, st);
     if (a.K <= 64) return pointwise ? launch_cfg<256, 64, 4, 1, 3, 2>(a, st) : launch_cfg<256, 64, 4, 1, 2, 3>(a, st);
     if (a.K % 256 == 0 && (pointwise || a.stride == 1)) {
         const long long M = (long long)a.N * a.P * a.Q;
