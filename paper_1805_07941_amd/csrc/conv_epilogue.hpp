@@ -124,6 +124,23 @@ __device__ __forceinline__ void store_tile_lane_fast(const v16i &v, const ConvAr
 // format per output channel).
 __device__ __forceinline__ void store_tile_lane_general(const v16i &v, const ConvArgs &a, int shift, int relu, long long m, int kc)
 {
+    // a whole 16-channel group into an aligned row, no accumulator dump: any shifts, one 16-byte store
+    if (!a.acc_out && a.y && kc + 16 <= a.K && (((unsigned)a.ldy | (unsigned)kc) & 15u) == 0 && ((uintptr_t)a.y & 15) == 0) {
+        uint32_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            int q[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const int r = 4 * j + e;
+                const int s = a.frac_w ? shift + a.frac_w[kc + r] : shift;
+                q[e] = requant8(relu ? max(v[r], 0) : v[r], s);
+            }
+            o[j] = pack4_clamped(q[0], q[1], q[2], q[3]);
+        }
+        *(uint4 *)(a.y + (size_t)m * a.ldy + kc) = make_uint4(o[0], o[1], o[2], o[3]);
+        return;
+    }
 #pragma unroll
     for (int r = 0; r < 16; r++) {
         if (kc + r < a.K) {
