@@ -119,7 +119,7 @@ def main():
     def run_step_recorded():
         st = B._stream(None)
         for (fn, cargs), name in zip(plan._calls_for(x), plan.call_nodes):
-            mf = name in mfma_names and fn.__name__ in ("dfq_conv_q", "dfq_conv_q_add", "dfq_conv_q_pc")
+            mf = name in mfma_names and fn.__name__ in ("dfq_conv_q", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add")
             if mf:
                 e0, e1 = event_pool.pop(), event_pool.pop()
                 e0.record()
@@ -187,7 +187,7 @@ def main():
             mfma_rate[label] = round(ops_probe / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
 
     n_joins = sum(1 for nd in net.nodes if nd.op == "eltwise")
-    n_fused = sum(1 for fn, _ in plan._calls_for(x) if fn.__name__ == "dfq_conv_q_add")
+    n_fused = sum(1 for fn, _ in plan._calls_for(x) if fn.__name__ in ("dfq_conv_q_add", "dfq_conv_q_pc_add"))
     macs_step = net.macs_per_image() * args.batch
     tops = 2 * macs_step / (ms_per_step * 1e-3) / 1e12
     imgs = args.batch / (ms_per_step * 1e-3)
@@ -200,7 +200,7 @@ def main():
             dur.setdefault(name, []).append(e0.elapsed_time(e1))
         ops = 0.0
         tsum = 0.0
-        fused_names = {name for (fn, _), name in zip(plan._calls_for(x), plan.call_nodes) if fn.__name__ == "dfq_conv_q_add"}
+        fused_names = {name for (fn, _), name in zip(plan._calls_for(x), plan.call_nodes) if fn.__name__ in ("dfq_conv_q_add", "dfq_conv_q_pc_add")}
         # launches by what bounds them at the published peaks: ops / 5 POP/s against bytes / 8 TB/s
         cls = {"mfma": dict(launches=0, ms=0.0, ops=0.0, bytes=0.0, roof_ms=0.0),
                "hbm": dict(launches=0, ms=0.0, ops=0.0, bytes=0.0, roof_ms=0.0)}
@@ -254,7 +254,7 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "launch": "per-call from Python" if args.no_graph else "HIP graph replay of the fixed call sequence",
         "joins": "each residual add its own dfq_eltwise_q call" if args.no_fuse else
-                 "%d of %d residual adds run inside the convolution in front of them (dfq_conv_q_add)" % (n_fused, n_joins),
+                 "%d of %d residual adds run inside the convolution in front of them (%s)" % (n_fused, n_joins, "dfq_conv_q_pc_add" if args.per_channel else "dfq_conv_q_add"),
         "weight_formats": "one per output channel (dfq_conv_q_pc)" if args.per_channel else "one per layer",
         "config": {"workload": "configs[4]: ResNet-50-shaped int8 network, 224x224x3, batch %d, formats from a "
                                "single-batch calibrate() on %d images" % (args.batch, args.calib),

@@ -143,6 +143,15 @@ dfq_status dfq_conv_q_add(const int8_t *x, const int8_t *w, const int32_t *b, co
                           int ldy, int ld_other, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_mid, int relu_mid,
                           dfq_fmt fmt_other, dfq_fmt fmt_out, int relu_out, dfq_stream stream);
 
+/* dfq_conv_q_add with one weight format per output channel: the result of dfq_conv_q_pc(...,
+ * fmt_mid, relu_mid) followed by dfq_eltwise_q(., fmt_mid, other, fmt_other, y, fmt_out, ...).
+ * frac_w, frac_w_lo, frac_w_hi as in dfq_conv_q_pc; everything else as in dfq_conv_q_add. */
+dfq_status dfq_conv_q_pc_add(const int8_t *x, const int8_t *w, const int32_t *b, const int8_t *other, int8_t *y,
+                             int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                             int ldy, int ld_other, dfq_fmt fmt_in, const int32_t *frac_w, int frac_w_lo,
+                             int frac_w_hi, dfq_fmt fmt_mid, int relu_mid, dfq_fmt fmt_other, dfq_fmt fmt_out,
+                             int relu_out, dfq_stream stream);
+
 /* The variant dfq_conv_q would run for this geometry (host, pure) when the tensors are 16-byte
  * aligned, ldy == K, the rescale shift lies in [0, 23] and no accumulator dump is asked for;
  * DFQ_CONV_AUTO if the geometry is invalid. */

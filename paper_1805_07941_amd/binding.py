@@ -23,7 +23,7 @@ CONV_VARIANT_NAMES = {CONV_AUTO: "auto", CONV_DIRECT: "direct", CONV_MFMA: "mfma
 
 EXPORTS = [
     "dfq_status_string", "dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q",
-    "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_absmax_i32_channels", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
+    "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
     "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_mfma_rate_probe",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
 ]
@@ -66,6 +66,7 @@ def lib():
     L.dfq_conv_q.argtypes = conv_args
     L.dfq_conv_q_variant.argtypes = [i32] + conv_args
     L.dfq_conv_q_pc.argtypes = [vp, vp, vp, vp, vp] + [i32] * 11 + [Fmt, vp, i32, i32, Fmt, i32, vp]
+    L.dfq_conv_q_pc_add.argtypes = [vp, vp, vp, vp, vp] + [i32] * 12 + [Fmt, vp, i32, i32, Fmt, i32, Fmt, Fmt, i32, vp]
     L.dfq_absmax_i32_channels.argtypes = [vp, sz, i32, i32, vp, vp]
     L.dfq_absmax_f32_rows.argtypes = [vp, sz, sz, vp, vp]
     L.dfq_quantize_rows.argtypes = [vp, vp, sz, sz, vp, vp]
@@ -83,7 +84,7 @@ def lib():
     for name in ("dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q", "dfq_conv_q_variant",
                  "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q", "dfq_absmax_f32",
                  "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_mfma_rate_probe",
-                 "dfq_conv_q_pc", "dfq_absmax_i32_channels", "dfq_absmax_f32_rows", "dfq_quantize_rows",
+                 "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_absmax_f32_rows", "dfq_quantize_rows",
                  "dfq_quantize_i32_rows"):
         getattr(L, name).restype = i32
     L.dfq_beta_max.restype = i64
@@ -238,6 +239,31 @@ def conv_q_add(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], othe
     if st == EUNSUPPORTED:
         return None
     _check(st, "dfq_conv_q_add")
+    return y
+
+
+def conv_q_pc_add(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], other: torch.Tensor, f_in: int,
+                  frac_w: torch.Tensor, frac_w_range, f_mid: int, relu_mid: bool, f_other: int, f_out: int, relu_out: bool,
+                  out: Optional[torch.Tensor] = None, stream=None):
+    """conv_q_add with one weight format per output channel (1x1, stride 1, no padding).  Returns the int8
+    result, or None when no fused kernel covers the call (nothing was launched)."""
+    _dev(x, torch.int8, "x"); _dev(w, torch.int8, "w"); _dev(other, torch.int8, "other"); _dev(frac_w, torch.int32, "frac_w")
+    if b is not None:
+        _dev(b, torch.int32, "b")
+    N, H, W, Cc = x.shape
+    K, R, S, Cg = w.shape
+    if Cg != Cc or tuple(frac_w.shape) != (K,):
+        raise DfqError(ESHAPE, "conv_q_pc_add (weight or format shape)")
+    P, Q = conv_out_hw(H, W, R, S, 1, 0)
+    if tuple(other.shape) != (N, P, Q, K):
+        raise DfqError(ESHAPE, "conv_q_pc_add (second operand's shape)")
+    y = out if out is not None else torch.empty((N, P, Q, K), dtype=torch.int8, device=x.device)
+    st = lib().dfq_conv_q_pc_add(_ptr(x), _ptr(w), _ptr(b), _ptr(other), _ptr(y), N, H, W, Cc, K, R, S, 1, 0, 1, K, K,
+                                 fmt(f_in), _ptr(frac_w), int(frac_w_range[0]), int(frac_w_range[1]), fmt(f_mid),
+                                 int(bool(relu_mid)), fmt(f_other), fmt(f_out), int(bool(relu_out)), _stream(stream))
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, "dfq_conv_q_pc_add")
     return y
 
 

@@ -98,6 +98,28 @@ __device__ __forceinline__ uint32_t requant_four_per_channel(int v0, int v1, int
     return w;
 }
 
+// One sum of a channel with its own shift s in [0, 23] (hi = 127 << s, badd = 2^(s-1) - 1, or 0 for s = 0).
+__device__ __forceinline__ int requant_one_per_channel(int v, int s, int hi, int badd, int relu)
+{
+    const int lo = relu ? 0 : -hi;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(v) : "v"(v), "v"(lo), "v"(hi));
+    return (v + badd + (int)__builtin_amdgcn_ubfe((unsigned)v, (unsigned)s, (unsigned)min(s, 1))) >> s;
+}
+
+// Four channels' sums rescaled per channel, then the fused add of Eq. 10 with the four codes in `other`.
+__device__ __forceinline__ uint32_t requant_add_four_per_channel(int v0, int v1, int v2, int v3, const int4 &s, const int4 &hi,
+                                                                 const int4 &badd, int relu, uint32_t other, int sa, int sb,
+                                                                 const Requant &rq2)
+{
+    const int v[4] = {v0, v1, v2, v3};
+    const int sv[4] = {s.x, s.y, s.z, s.w}, hv[4] = {hi.x, hi.y, hi.z, hi.w}, bv[4] = {badd.x, badd.y, badd.z, badd.w};
+    int t[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++)
+        t[e] = (int)((unsigned)requant_one_per_channel(v[e], sv[e], hv[e], bv[e], relu) << sa) + (int)((unsigned)byte_of(other, e) << sb);
+    return rq2.fast_four(t[0], t[1], t[2], t[3]);
+}
+
 // The same followed by the fused add of Eq. 10: the sixteen int8 results of the convolution (kept as
 // integers, never stored) and the sixteen codes of the second operand in `other` are aligned to the
 // finer of their two scales, summed and rounded once more with rq2.

@@ -55,7 +55,9 @@ __device__ __forceinline__ void wait_loads_plus2(int ca, int cb)
 // second operand's 16 codes per lane and tile are fetched into registers one unit ahead, at the
 // start of the previous unit's epilogue, so that even with one item per unit the whole epilogue
 // (a few microseconds of vector work) lies between the fetch and its use.
-template <int BP, int BC, int WAVES_P, int WAVES_C, bool FUSE, int OCC>
+// PC: one weight format per output channel, every channel's shift within [0, 23]: shift, clamp bound
+// and rounding constant of all K channels sit in LDS behind the bias.
+template <int BP, int BC, int WAVES_P, int WAVES_C, bool FUSE, int OCC, bool PC = false>
 __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(PwParams prm)
 {
     constexpr int NSTAGES = 3;                            // depth of the weight ring
@@ -105,6 +107,15 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
     const int ring_piece0 = 2 * nsteps * SLAB_PIECES;
     int *bias_lds = (int *)(lds + ring_piece0 + NSTAGES * WSTAGE_PIECES);
     for (int i = tid; i < a.K; i += NW * 64) bias_lds[i] = a.b ? a.b[i] : 0;
+    int *pc_shift = bias_lds + a.K, *pc_hi = pc_shift + a.K, *pc_badd = pc_hi + a.K;
+    if (PC) {
+        for (int i = tid; i < a.K; i += NW * 64) {
+            const int sk = (a.shift + a.frac_w[i]) & 31;            // in [0, 23] by the caller's word
+            pc_shift[i] = sk;
+            pc_hi[i] = 127 << min(sk, 23);
+            pc_badd[i] = sk > 0 ? ((1 << (sk - 1)) - 1) : 0;
+        }
+    }
 
     // ---- producer.  Lane l of a wavefront-wide load supplies row l/4 of a 16-row chunk, physical
     // piece l%4, which holds logical piece (l%4) ^ ((row>>2)&3): 16 consecutive rows then put any
@@ -276,14 +287,41 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
                     fetch_other(wrap ? c_pt + 1 : c_pt, wrap ? 0 : c_ct + 1);
                 }
             }
+            if constexpr (PC) {
 #pragma unroll
-            for (int c = 0; c < CT; c++)
+                for (int c = 0; c < CT; c++) {
+                    const int kr = c_ct * BC + wc0 + c * 32 + 16 * lh;
+                    uint32_t o[PT][4];
 #pragma unroll
-                for (int p = 0; p < PT; p++) {
-                    const unsigned off = lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32);
-                    if (FUSE) store_piece(requant_add_tile_lane(acc[c][p], rq, other[c * PT + p], a.add_sa, a.add_sb, rq2), off, yrsrc);
-                    else store_piece(requant_tile_lane_fast(acc[c][p], rq), off, yrsrc);
+                    for (int r4 = 0; r4 < 4; r4++) {
+                        const int4 sv = *(const int4 *)(pc_shift + kr + 4 * r4);
+                        const int4 hv = *(const int4 *)(pc_hi + kr + 4 * r4);
+                        const int4 bv = *(const int4 *)(pc_badd + kr + 4 * r4);
+#pragma unroll
+                        for (int p = 0; p < PT; p++) {
+                            const v16i &v = acc[c][p];
+                            if (FUSE)
+                                o[p][r4] = requant_add_four_per_channel(v[4 * r4], v[4 * r4 + 1], v[4 * r4 + 2], v[4 * r4 + 3], sv, hv, bv,
+                                                                        a.relu, (uint32_t)other[c * PT + p][r4], a.add_sa, a.add_sb, rq2);
+                            else
+                                o[p][r4] = requant_four_per_channel(v[4 * r4], v[4 * r4 + 1], v[4 * r4 + 2], v[4 * r4 + 3], sv, hv, bv, a.relu);
+                        }
+                    }
+#pragma unroll
+                    for (int p = 0; p < PT; p++)
+                        store_piece(make_uint4(o[p][0], o[p][1], o[p][2], o[p][3]),
+                                    lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32), yrsrc);
                 }
+            } else {
+#pragma unroll
+                for (int c = 0; c < CT; c++)
+#pragma unroll
+                    for (int p = 0; p < PT; p++) {
+                        const unsigned off = lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32);
+                        if (FUSE) store_piece(requant_add_tile_lane(acc[c][p], rq, other[c * PT + p], a.add_sa, a.add_sb, rq2), off, yrsrc);
+                        else store_piece(requant_tile_lane_fast(acc[c][p], rq), off, yrsrc);
+                    }
+            }
             ep_hist |= 1u;
             c_step = 0;
             if (++c_ct == prm.tiles_c) {
@@ -373,10 +411,10 @@ inline hipError_t big_lds_pw(void (*k)(PwParams))
 template <int BP, int BC, int WAVES_P, int WAVES_C>
 size_t pw_lds_bytes(const ConvArgs &a)
 {
-    return (size_t)2 * BP * a.C + (size_t)3 * BC * kStepBytes + (size_t)a.K * 4;
+    return (size_t)2 * BP * a.C + (size_t)3 * BC * kStepBytes + (size_t)a.K * 4 * (a.frac_w ? 4 : 1);   // bias (+ three tables)
 }
 
-template <int BP, int BC, int WAVES_P, int WAVES_C, int PER_CU>
+template <int BP, int BC, int WAVES_P, int WAVES_C, int PER_CU, bool PC = false>
 hipError_t launch_pw(const ConvArgs &a, hipStream_t st)
 {
     constexpr bool kCanFuse = (BP / WAVES_P / 32) * (BC / WAVES_C / 32) == 4;
@@ -401,16 +439,16 @@ hipError_t launch_pw(const ConvArgs &a, hipStream_t st)
     constexpr int occ = PER_CU * WAVES_P * WAVES_C / 4;
     if (a.add) {
         if constexpr (kCanFuse) {
-            static const hipError_t attr = big_lds_pw(conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, true, occ>);
+            static const hipError_t attr = big_lds_pw(conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, true, occ, PC>);
             if (attr != hipSuccess) return attr;
-            conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, true, occ><<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
+            conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, true, occ, PC><<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
             return hipGetLastError();
         }
         return hipErrorInvalidValue;
     }
-    static const hipError_t attr = big_lds_pw(conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, false, occ>);
+    static const hipError_t attr = big_lds_pw(conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, false, occ, PC>);
     if (attr != hipSuccess) return attr;
-    conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, false, occ><<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
+    conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, false, occ, PC><<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
     return hipGetLastError();
 }
 
@@ -435,8 +473,13 @@ bool conv_pw_geometry_ok(const ConvArgs &a)
 bool conv_pw_supports(const ConvArgs &a)
 {
     if (!conv_pw_geometry_ok(a)) return false;
-    if (a.frac_w) return false;
-    if (!(a.shift >= 0 && a.shift <= 23) || a.acc_out || !a.y || (a.ldy & 15) || ((uintptr_t)a.y & 15)) return false;
+    if (a.frac_w) {
+        // per-channel weight formats: every declared shift in the lean range, and room for the tables
+        const int bc = a.K % 128 == 0 ? 128 : 64;
+        if ((size_t)2 * 256 * a.C + (size_t)3 * bc * kStepBytes + (size_t)a.K * 16 > (size_t)kLdsBytes) return false;
+        if (((uintptr_t)a.frac_w & 3) || a.shift + a.frac_w_lo < 0 || a.shift + a.frac_w_hi > 23) return false;
+    }
+    if (!(a.frac_w || (a.shift >= 0 && a.shift <= 23)) || a.acc_out || !a.y || (a.ldy & 15) || ((uintptr_t)a.y & 15)) return false;
     if (((uintptr_t)a.x & 15) || ((uintptr_t)a.w & 15)) return false;
     if (a.add) {
         // the fused add: second operand addressable like y, final shift in the range of the fast rounding
@@ -449,6 +492,12 @@ bool conv_pw_supports(const ConvArgs &a)
 
 hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st)
 {
+    if (a.frac_w) {
+        // the per-channel epilogue holds more registers: at most two wavefronts per SIMD
+        if (a.K % 128 == 0) return launch_pw<256, 128, 4, 2, 1, true>(a, st);
+        if (a.C <= 128) return launch_pw<256, 64, 4, 1, 2, true>(a, st);
+        return launch_pw<256, 64, 4, 1, 1, true>(a, st);
+    }
     // as many workgroups per compute unit as the two input buffers leave room for
     if (a.K % 128 == 0) {
         // (the fused epilogue needs more registers than four wavefronts per SIMD leave it)

@@ -105,6 +105,33 @@ dfq_status run_conv(dfq_conv_variant variant, const ConvArgs &a, hipStream_t st)
     }
 }
 
+// the part of the fused convolution + add calls behind the convolution's own checks
+dfq_status run_conv_add(ConvCheck &c, const int8_t *x, const int8_t *other, int8_t *y, int N, int H, int W, int C, int K,
+                        int ldy, int ld_other, dfq_fmt fmt_mid, dfq_fmt fmt_other, dfq_fmt fmt_out, int relu_out,
+                        dfq_stream stream)
+{
+    if (c.st != DFQ_OK) return c.st;
+    if (!fmt_ok(fmt_other) || !fmt_ok(fmt_out)) return DFQ_EFMT;
+    if (!y || !other) return DFQ_EINVAL;
+    if (ld_other < K) return DFQ_ESHAPE;
+    const int F = fmt_mid.frac > fmt_other.frac ? fmt_mid.frac : fmt_other.frac;
+    // Eq. 12: two codes of magnitude <= 2^7 shifted by <= 22 bits sum to at most 2^30
+    if (F - fmt_mid.frac > 22 || F - fmt_other.frac > 22) return DFQ_EFMT;
+    if (N == 0) return DFQ_OK;
+    const size_t npix = (size_t)N * c.a.P * c.a.Q;
+    if (overlaps(other, npix * (size_t)ld_other, y, npix * (size_t)ldy) ||
+        overlaps(other, npix * (size_t)ld_other, x, (size_t)N * H * W * C))
+        return DFQ_EINVAL;
+    c.a.add = other;
+    c.a.ldadd = ld_other;
+    c.a.add_sa = F - fmt_mid.frac;
+    c.a.add_sb = F - fmt_other.frac;
+    c.a.add_shift = F - fmt_out.frac;
+    c.a.add_relu = relu_out ? 1 : 0;
+    if (!conv_pw_supports(c.a)) return DFQ_EUNSUPPORTED;
+    return from_hip(launch_conv_pw(c.a, (hipStream_t)stream));
+}
+
 }  // namespace
 
 extern "C" {
@@ -189,26 +216,23 @@ dfq_status dfq_conv_q_add(const int8_t *x, const int8_t *w, const int32_t *b, co
 {
     ConvCheck c = check_conv(x, w, b, y, nullptr, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, fmt_w, fmt_mid,
                              relu_mid, true);
-    if (c.st != DFQ_OK) return c.st;
-    if (!fmt_ok(fmt_other) || !fmt_ok(fmt_out)) return DFQ_EFMT;
-    if (!y || !other) return DFQ_EINVAL;
-    if (ld_other < K) return DFQ_ESHAPE;
-    const int F = fmt_mid.frac > fmt_other.frac ? fmt_mid.frac : fmt_other.frac;
-    // Eq. 12: two codes of magnitude <= 2^7 shifted by <= 22 bits sum to at most 2^30
-    if (F - fmt_mid.frac > 22 || F - fmt_other.frac > 22) return DFQ_EFMT;
-    if (N == 0) return DFQ_OK;
-    const size_t npix = (size_t)N * c.a.P * c.a.Q;
-    if (overlaps(other, npix * (size_t)ld_other, y, npix * (size_t)ldy) ||
-        overlaps(other, npix * (size_t)ld_other, x, (size_t)N * H * W * C))
-        return DFQ_EINVAL;
-    c.a.add = other;
-    c.a.ldadd = ld_other;
-    c.a.add_sa = F - fmt_mid.frac;
-    c.a.add_sb = F - fmt_other.frac;
-    c.a.add_shift = F - fmt_out.frac;
-    c.a.add_relu = relu_out ? 1 : 0;
-    if (!conv_pw_supports(c.a)) return DFQ_EUNSUPPORTED;
-    return from_hip(launch_conv_pw(c.a, (hipStream_t)stream));
+    return run_conv_add(c, x, other, y, N, H, W, C, K, ldy, ld_other, fmt_mid, fmt_other, fmt_out, relu_out, stream);
+}
+
+dfq_status dfq_conv_q_pc_add(const int8_t *x, const int8_t *w, const int32_t *b, const int8_t *other, int8_t *y, int N,
+                             int H, int W, int C, int K, int R, int S, int stride, int pad, int groups, int ldy,
+                             int ld_other, dfq_fmt fmt_in, const int32_t *frac_w, int frac_w_lo, int frac_w_hi,
+                             dfq_fmt fmt_mid, int relu_mid, dfq_fmt fmt_other, dfq_fmt fmt_out, int relu_out,
+                             dfq_stream stream)
+{
+    if (frac_w_lo > frac_w_hi || frac_w_lo < -32 || frac_w_hi > 32) return DFQ_EFMT;
+    ConvCheck c = check_conv(x, w, b, y, nullptr, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, dfq_fmt{8, 0},
+                             fmt_mid, relu_mid, true);
+    if (c.st == DFQ_OK && (!frac_w || ((uintptr_t)frac_w & 3))) return DFQ_EINVAL;
+    c.a.frac_w = frac_w;
+    c.a.frac_w_lo = frac_w_lo;
+    c.a.frac_w_hi = frac_w_hi;
+    return run_conv_add(c, x, other, y, N, H, W, C, K, ldy, ld_other, fmt_mid, fmt_other, fmt_out, relu_out, stream);
 }
 
 dfq_conv_variant dfq_conv_q_select(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups)

@@ -174,8 +174,6 @@ class Plan:
                 continue
             if c.dst == net.output_name or e.srcs[0] == e.srcs[1]:
                 continue
-            if c.name in qz.w_frac_dev:      # the fused kernel takes one weight format per layer
-                continue
             pairs[i] = i + 1
         return pairs
 
@@ -236,13 +234,19 @@ class Plan:
                 src = nd.srcs[0]
                 N, H, W, Cc = t[src].shape
                 K = nd.K
-                args = (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(), t[other].data_ptr(),
-                        t[add.dst].data_ptr(), N, H, W, Cc, K, nd.R, nd.R, nd.stride, nd.pad, nd.groups, K, K,
-                        f(qz.frac[src]), f(qz.w_frac[nd.name]), f(qz.frac[nd.dst]), int(nd.relu), f(qz.frac[other]),
-                        f(qz.frac[add.dst]), int(add.relu))
-                rc = L.dfq_conv_q_add(*args, B._stream(None))
+                head = (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(), t[other].data_ptr(),
+                        t[add.dst].data_ptr(), N, H, W, Cc, K, nd.R, nd.R, nd.stride, nd.pad, nd.groups, K, K, f(qz.frac[src]))
+                tail = (f(qz.frac[nd.dst]), int(nd.relu), f(qz.frac[other]), f(qz.frac[add.dst]), int(add.relu))
+                if nd.name in qz.w_frac_dev:
+                    fn = L.dfq_conv_q_pc_add
+                    args = head + (qz.w_frac_dev[nd.name].data_ptr(), int(qz.w_frac[nd.name].min()),
+                                   int(qz.w_frac[nd.name].max())) + tail
+                else:
+                    fn = L.dfq_conv_q_add
+                    args = head + (f(qz.w_frac[nd.name]),) + tail
+                rc = fn(*args, B._stream(None))
                 if rc == B.OK:
-                    calls.append((L.dfq_conv_q_add, args))
+                    calls.append((fn, args))
                     names.append(nd.name)
                     fused_adds.add(self.fused[idx])
                     continue

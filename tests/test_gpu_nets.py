@@ -178,6 +178,8 @@ def test_per_channel_weight_formats_networks(G, which):
                 for name in t:
                     assert np.array_equal(host(plan.buf[name][i:i + 1]), t[name]), (i, name)
         assert np.array_equal(host(plan.run_graph(dev(x))), logits)
+        if kw and which == "resnet50":
+            assert sum(1 for fn, _ in plan._calls if fn.__name__ == "dfq_conv_q_pc_add") >= 4
 
 
 def test_fused_joins_give_the_same_logits(G):

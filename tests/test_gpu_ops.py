@@ -334,3 +334,28 @@ def test_absmax_per_channel(B):
         for relu in (False, True):
             got = B.absmax_i32_channels_value(B.absmax_i32_channels(dev(a), relu=relu)).astype(np.int64)
             assert np.array_equal(got, orc.absmax_i32_channels(a, relu=relu)), (shape, relu)
+
+
+@pytest.mark.parametrize("shape", [(3, 19, 17, 64, 256), (2, 23, 21, 128, 384), (2, 30, 30, 128, 64), (2, 14, 14, 256, 512)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_conv_q_pc_add_equals_the_two_calls(B, shape):
+    """The fused per-channel convolution + add against the oracle's two steps, and against the library's own."""
+    N, H, W, C, K = shape
+    rng = np.random.default_rng(abs(hash(("pcadd",) + shape)) % (2 ** 31))
+    x, w, b = _rand_conv(rng, N, H, W, C, K, 1, 1, 1)
+    other = rng.integers(-128, 128, (N, H, W, K)).astype(np.int8)
+    xd, wd, bd, od = dev(x), dev(w), dev(b), dev(other)
+    for f_in, f_mid, relu_mid, f_other, f_out, relu_out, lo, hi in [(4, 4, 0, 5, 3, 1, 4, 10), (3, 2, 1, 2, 2, 0, 1, 7),
+                                                                   (5, 6, 0, 3, 1, 1, 6, 12)]:
+        f_w = rng.integers(lo, hi + 1, K).astype(np.int32)
+        mid, _ = orc.conv_q(x, w, b, f_in, f_w, f_mid, 1, 0, 1, relu_mid)
+        ref, _ = orc.eltwise_q(mid, f_mid, other, f_other, f_out, relu_out)
+        got = B.conv_q_pc_add(xd, wd, bd, od, f_in, dev(f_w), (lo, hi), f_mid, relu_mid, f_other, f_out, relu_out)
+        assert got is not None, "the fused per-channel kernel should cover this call"
+        assert np.array_equal(host(got), ref), (f_in, f_mid, f_other, f_out)
+        # the unfused per-channel pointwise kernel on the same layer
+        y, _ = B.conv_q_pc(xd, wd, bd, f_in, dev(f_w), f_mid, 1, 0, 1, relu_mid, frac_w_range=(lo, hi))
+        assert np.array_equal(host(y), mid)
+    # shifts outside the lean range are declined, not mis-computed
+    f_w = np.full(K, 30, np.int32)
+    assert B.conv_q_pc_add(xd, wd, bd, od, 4, dev(f_w), (30, 30), 2, False, 3, 3, True) is None
