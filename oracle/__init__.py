@@ -258,3 +258,55 @@ def frac_from_absmax_i32(m: int, acc_frac: int) -> int:
     if f == -1000:
         raise ValueError("threshold must be non-negative")
     return f
+
+
+# ---- Algorithm 1: threshold search on a histogram of magnitudes ------------------ #
+# Readings taken where the algorithm leaves things open (each is restated in the design notes):
+#   x            the layer's 32-bit accumulators after the ReLU (the tensor whose threshold is sought);
+#   hist         at most NBINS = 2048 bins of power-of-two width 2^j over the integers |x|,
+#                j the smallest shift with (max|x| >> j) < NBINS; bin_edges[i] = i * 2^j;
+#   fpspace      the non-negative codes of the 8-bit format scaled to [0, 1]: k / 127, k = 0..127;
+#   measure      the area between the two distribution functions, sum |cdf - q| over the bins;
+#   gamma        the largest integer below bin_edges[i], but never above max|x|.
+NBINS = 2048
+N_CODES = 128
+
+
+def hist_i32(x, relu=False):
+    """Counts of |x| >> j per bin (uint64 [nb]), the shift j and max|x|; nb = (max|x| >> j) + 1 <= NBINS."""
+    a = np.abs(np.maximum(_c(x, np.int32).astype(np.int64), 0) if relu else _c(x, np.int32).astype(np.int64)).ravel()
+    m = int(a.max()) if a.size else 0
+    j = 0
+    while (m >> j) >= NBINS:
+        j += 1
+    nb = (m >> j) + 1
+    counts = np.bincount(a >> j, minlength=nb).astype(np.uint64)
+    return counts, j, m
+
+
+def threshold_search(counts, j, m):
+    """Algorithm 1 on a histogram: returns (gamma, delta), gamma an integer threshold in the units of x.
+    Candidates clip at bin edges i = 129 .. nb; a histogram with fewer bins than that is not clipped."""
+    counts = np.asarray(counts, np.float64)
+    nb = len(counts)
+    total = counts.sum()
+    if total == 0 or m == 0:
+        return 0, 0.0
+    pdf = counts / total
+    cdf = np.cumsum(pdf)
+    codes = np.arange(N_CODES, dtype=np.float64) / float(N_CODES - 1)        # fpspace(0, 1, 8, 7)
+    delta, gamma = np.inf, m                                                   # bin_edges[-1]: nothing clipped
+    for i in range(N_CODES + 1, nb + 1):
+        r = cdf.copy()
+        r[i - 1:] = 1.0
+        grid = np.linspace(0.0, 1.0, i)
+        r_interp = np.interp(codes, grid, r[:i])
+        q_interp = np.interp(grid, codes, r_interp)
+        q = r.copy()
+        q[:i] = q_interp
+        d = float(np.cumsum(np.abs(cdf - q))[-1])           # summed in bin order
+        if delta > d:
+            delta, gamma = d, min(i * (1 << j) - 1, m)
+    if delta == np.inf:
+        delta = 0.0
+    return int(gamma), float(delta)

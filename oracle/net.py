@@ -51,7 +51,16 @@ def _input_codes(net, x, qz: Quantized, calibrating: bool):
     return orc.quantize(x, qz.frac[net.input_name])
 
 
-def _forward(net, x, qz: Quantized, calibrating: bool, per_channel: bool = False):
+def _threshold(acc, relu, rule):
+    """The activation threshold of Sec. 3 in accumulator units: the maximum magnitude after the
+    ReLU ("maxabs"), or the result of the histogram search of Algorithm 1 ("search")."""
+    if rule == "maxabs":
+        return orc.absmax_i32(acc, relu=relu)
+    counts, j, m = orc.hist_i32(acc, relu=relu)
+    return orc.threshold_search(counts, j, m)[0]
+
+
+def _forward(net, x, qz: Quantized, calibrating: bool, per_channel: bool = False, rule: str = "maxabs"):
     t = {net.input_name: _input_codes(net, x, qz, calibrating)}
     for nd in net.nodes:
         if nd.op == "conv":
@@ -87,7 +96,7 @@ def _forward(net, x, qz: Quantized, calibrating: bool, per_channel: bool = False
                 # threshold on the wide accumulator after the ReLU, then the one rescale of Eq. 6
                 _, acc = orc.conv_q(t[src], w, b, f_in, f_w, 0, nd.stride, nd.pad, nd.groups,
                                     nd.relu, want_y=False, want_acc=True)
-                m = orc.absmax_i32(acc, relu=nd.relu)
+                m = _threshold(acc, nd.relu, rule)
                 qz.frac[nd.dst] = orc.frac_from_absmax_i32(m, f_in + f_w)
                 t[nd.dst] = orc.requant_i32(acc, f_in + f_w - qz.frac[nd.dst], nd.relu)
                 del acc
@@ -101,7 +110,7 @@ def _forward(net, x, qz: Quantized, calibrating: bool, per_channel: bool = False
             fa, fb = qz.frac[a], qz.frac[b]
             if calibrating:
                 _, acc = orc.eltwise_q(t[a], fa, t[b], fb, 0, nd.relu, want_y=False, want_acc=True)
-                m = orc.absmax_i32(acc, relu=nd.relu)
+                m = _threshold(acc, nd.relu, rule)
                 qz.frac[nd.dst] = orc.frac_from_absmax_i32(m, max(fa, fb))
             t[nd.dst], _ = orc.eltwise_q(t[a], fa, t[b], fb, qz.frac[nd.dst], nd.relu)
         elif nd.op == "concat":
@@ -120,11 +129,15 @@ def _forward(net, x, qz: Quantized, calibrating: bool, per_channel: bool = False
     return t
 
 
-def calibrate(net, x_calib, per_channel: bool = False):
+def calibrate(net, x_calib, per_channel: bool = False, rule: str = "maxabs"):
     """Chooses every format from ONE batch.  Returns (Quantized, tensors of that batch).
-    per_channel: one weight format per output channel (Sec. 3) instead of one per layer."""
+    per_channel: one weight format per output channel (Sec. 3) instead of one per layer.
+    rule: "maxabs" - activation thresholds are maxima; "search" - Algorithm 1 on a histogram of the
+    accumulators (per-layer weight formats only)."""
+    if rule not in ("maxabs", "search") or (rule == "search" and per_channel):
+        raise ValueError("rule must be 'maxabs' or 'search' (the search with per-layer weight formats)")
     qz = Quantized()
-    t = _forward(net, x_calib, qz, calibrating=True, per_channel=per_channel)
+    t = _forward(net, x_calib, qz, calibrating=True, per_channel=per_channel, rule=rule)
     return qz, t
 
 

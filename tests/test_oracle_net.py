@@ -120,3 +120,27 @@ def test_per_channel_calibration(net):
     t2 = onet.infer(net, qz, x)
     for k in t:
         assert np.array_equal(t[k], t2[k])
+
+
+def test_threshold_search_calibration():
+    """Activation thresholds from Algorithm 1 instead of the maximum: a threshold never exceeds the
+    maximum, so no format gets coarser; weights and the bootstrap order are unchanged."""
+    net = wl.resnet50(batch=2, hw=32, classes=10)
+    x = net.input_float()
+    qz0, _ = onet.calibrate(net, x)
+    qz, t = onet.calibrate(net, x, rule="search")
+    assert qz.w_frac[net.nodes[0].name] == qz0.w_frac[net.nodes[0].name]
+    finer = 0
+    for nd in net.nodes:
+        if nd.op in ("conv", "eltwise") and nd.fixed_f_out is None:
+            acc_frac = (qz.frac[nd.srcs[0]] + qz.w_frac[nd.name]) if nd.op == "conv" else max(qz.frac[s] for s in nd.srcs)
+            assert qz.frac[nd.dst] <= acc_frac
+        assert int(t[nd.dst].astype(np.int32).min()) >= -127
+    # the first layers see identical inputs under both rules: there the searched format is the same or finer
+    first = net.nodes[0]
+    assert qz.frac[first.dst] >= qz0.frac[first.dst]
+    t2 = onet.infer(net, qz, x)
+    for k in t:
+        assert np.array_equal(t[k], t2[k])
+    with pytest.raises(ValueError):
+        onet.calibrate(net, x, per_channel=True, rule="search")

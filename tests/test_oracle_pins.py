@@ -557,3 +557,91 @@ def test_absmax_per_channel():
     rng = np.random.default_rng(5)
     r = rng.integers(-2 ** 31, 2 ** 31, (50, 7)).astype(np.int32)
     assert orc.absmax_i32_channels(r).tolist() == [orc.absmax_i32(r[:, k]) for k in range(7)]
+
+
+# --------------------------------------------------------------------------- #
+# Algorithm 1: threshold search on a histogram of magnitudes
+# --------------------------------------------------------------------------- #
+
+def test_histogram_of_magnitudes():
+    rng = np.random.default_rng(41)
+    for hi, relu in [(100, False), (5000, True), (2 ** 20, False), (2 ** 31 - 1, True)]:
+        x = rng.integers(-hi, hi + 1, 3000).astype(np.int32)
+        counts, j, m = orc.hist_i32(x, relu=relu)
+        a = [max(int(v), 0) if relu else abs(int(v)) for v in x]
+        assert m == max(a)
+        assert (m >> j) < orc.NBINS and (j == 0 or (m >> (j - 1)) >= orc.NBINS)     # the smallest such shift
+        want = [0] * ((m >> j) + 1)
+        for v in a:
+            want[v >> j] += 1
+        assert counts.tolist() == want and int(counts.sum()) == len(x)
+    counts, j, m = orc.hist_i32(np.zeros(7, np.int32))
+    assert counts.tolist() == [7] and j == 0 and m == 0
+
+
+def _interp_by_definition(x, xp, fp):
+    """Piecewise-linear interpolation written out (xp increasing, x inside [xp[0], xp[-1]])."""
+    out = []
+    for v in x:
+        k = max(t for t in range(len(xp)) if xp[t] <= v)
+        if k == len(xp) - 1 or xp[k] == v:
+            out.append(fp[k])
+        else:
+            out.append(fp[k] + (fp[k + 1] - fp[k]) * (v - xp[k]) / (xp[k + 1] - xp[k]))
+    return out
+
+
+def _threshold_by_steps(counts, j, m):
+    """Algorithm 1 step by step in plain Python floats, with the readings listed in the oracle."""
+    nb, total = len(counts), float(sum(counts))
+    cdf, acc = [], 0.0
+    for c in counts:
+        acc += c / total
+        cdf.append(acc)
+    codes = [k / 127.0 for k in range(128)]
+    best, gamma = float("inf"), m
+    for i in range(129, nb + 1):
+        r = cdf[:i - 1] + [1.0] * (nb - i + 1)
+        grid = [t / (i - 1) for t in range(i)]
+        r_interp = _interp_by_definition(codes, grid, r[:i])
+        q = _interp_by_definition(grid, codes, r_interp) + r[i:]
+        d = sum(abs(a - b) for a, b in zip(cdf, q))
+        if best > d:
+            best, gamma = d, min(i * 2 ** j - 1, m)
+    return gamma, (0.0 if best == float("inf") else best)
+
+
+def test_threshold_search_follows_the_algorithm_step_by_step():
+    rng = np.random.default_rng(42)
+    for scale, n, top in [(40.0, 4000, 170), (25.0, 3000, 260), (300.0, 5000, 2500)]:
+        x = np.minimum(np.abs(rng.standard_normal(n) * scale), top).astype(np.int32)
+        x[0] = top
+        counts, j, m = orc.hist_i32(x)
+        gamma, delta = orc.threshold_search(counts, j, m)
+        g2, d2 = _threshold_by_steps([int(c) for c in counts], j, m)
+        assert gamma == g2 and abs(delta - d2) <= 1e-9 * max(1.0, d2)
+
+
+def test_threshold_search_properties():
+    rng = np.random.default_rng(43)
+    # too few bins to clip anything (the loop starts at 2^(n-1) + 1 = 129 bin edges): the maximum stays
+    x = rng.integers(0, 100, 1000).astype(np.int32)
+    counts, j, m = orc.hist_i32(x)
+    assert orc.threshold_search(counts, j, m) == (m, 0.0)
+    # an evenly filled range is not clipped (at most the partly filled last bin goes)
+    x = rng.integers(0, 100000, 300000).astype(np.int32)
+    counts, j, m = orc.hist_i32(x)
+    assert m - 2 * 2 ** j < orc.threshold_search(counts, j, m)[0] <= m
+    # one far outlier is clipped away, down to the smallest candidate, which still covers the bulk
+    x = np.abs(rng.standard_normal(100000) * 3000).astype(np.int32)
+    bulk = int(x.max())
+    x[0] = 2_000_000
+    counts, j, m = orc.hist_i32(x)
+    gamma, delta = orc.threshold_search(counts, j, m)
+    assert gamma == 129 * 2 ** j - 1 and bulk <= gamma < m and delta > 0
+    # doubling every value doubles the bin width and nothing else
+    c2, j2, m2 = orc.hist_i32(x * 2)
+    assert j2 == j + 1 and np.array_equal(c2, counts)
+    assert orc.threshold_search(c2, j2, m2)[0] == min(129 * 2 ** j2 - 1, m2)
+    # all zeros
+    assert orc.threshold_search(np.array([5], np.uint64), 0, 0) == (0, 0.0)
