@@ -209,6 +209,25 @@ dfq_status dfq_quantize_i32_rows(const float *x, int32_t *q, size_t rows, size_t
 dfq_status dfq_absmax_i32_channels(const int32_t *x, size_t pixels, int K, int relu, uint32_t *out_dev,
                                    dfq_stream stream);
 
+/* ---- Algorithm 1 (Sec. 3): a threshold from a histogram of magnitudes instead of the maximum --
+ * Readings where the algorithm is open: the tensor is a layer's int32 accumulators (after the
+ * ReLU when relu != 0); hist = DFQ_HIST_BINS bins of power-of-two width over the integers |x|;
+ * fpspace = the non-negative codes k / 127 of the 8-bit format; measure = sum over the bins of
+ * |cdf - q| (the area between the two distribution functions); the threshold of a candidate
+ * edge i is the largest integer below it, i * 2^shift - 1, capped at max|x|.
+ * dfq_hist_i32: hist_dev[b] = number of elements with (|x| >> shift) == b, DFQ_HIST_BINS DEVICE
+ * words, overwritten; the caller picks shift as the smallest with (max|x| >> shift) <
+ * DFQ_HIST_BINS (larger magnitudes would be counted in the last bin).  n < 2^32.
+ * dfq_threshold_search: host, pure, double precision, sums in bin order.  hist: HOST copy of the
+ * first nbins = (max_abs >> shift) + 1 words.  Candidates are the edges i = 129 .. nbins (with
+ * fewer bins nothing is clipped); the first candidate with the smallest measure wins.
+ * *gamma_out: the threshold in the units of x (0 for an all-zero tensor); *delta_out (may be
+ * NULL): its measure.  DFQ_ESHAPE if nbins does not match max_abs and shift. */
+#define DFQ_HIST_BINS 2048
+dfq_status dfq_hist_i32(const int32_t *x, size_t n, int relu, int shift, uint32_t *hist_dev, dfq_stream stream);
+dfq_status dfq_threshold_search(const uint32_t *hist, int nbins, int shift, int64_t max_abs, int64_t *gamma_out,
+                                double *delta_out);
+
 /* gamma = alpha * beta_max (Sec. 2.1) solved for a power-of-two alpha: the largest frac in
  * [-32, 32] with gamma * 2^frac <= 127; gamma = 0 gives 32.  Host, pure.  DFQ_EINVAL for a
  * negative, infinite or NaN gamma. */

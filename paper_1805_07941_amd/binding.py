@@ -23,7 +23,7 @@ CONV_VARIANT_NAMES = {CONV_AUTO: "auto", CONV_DIRECT: "direct", CONV_MFMA: "mfma
 
 EXPORTS = [
     "dfq_status_string", "dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q",
-    "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
+    "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_hist_i32", "dfq_threshold_search", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
     "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_mfma_rate_probe",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
 ]
@@ -68,6 +68,8 @@ def lib():
     L.dfq_conv_q_pc.argtypes = [vp, vp, vp, vp, vp] + [i32] * 11 + [Fmt, vp, i32, i32, Fmt, i32, vp]
     L.dfq_conv_q_pc_add.argtypes = [vp, vp, vp, vp, vp] + [i32] * 12 + [Fmt, vp, i32, i32, Fmt, i32, Fmt, Fmt, i32, vp]
     L.dfq_absmax_i32_channels.argtypes = [vp, sz, i32, i32, vp, vp]
+    L.dfq_hist_i32.argtypes = [vp, sz, i32, i32, vp, vp]
+    L.dfq_threshold_search.argtypes = [vp, i32, i32, i64, C.POINTER(i64), C.POINTER(C.c_double)]
     L.dfq_absmax_f32_rows.argtypes = [vp, sz, sz, vp, vp]
     L.dfq_quantize_rows.argtypes = [vp, vp, sz, sz, vp, vp]
     L.dfq_quantize_i32_rows.argtypes = [vp, vp, sz, sz, vp, i32, vp]
@@ -85,7 +87,7 @@ def lib():
                  "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q", "dfq_absmax_f32",
                  "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_mfma_rate_probe",
                  "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_absmax_f32_rows", "dfq_quantize_rows",
-                 "dfq_quantize_i32_rows"):
+                 "dfq_quantize_i32_rows", "dfq_hist_i32", "dfq_threshold_search"):
         getattr(L, name).restype = i32
     L.dfq_beta_max.restype = i64
     L.dfq_beta_max.argtypes = [i32, i32]
@@ -394,6 +396,36 @@ def absmax_i32_channels(x: torch.Tensor, relu: bool = False, out_dev: Optional[t
 def absmax_i32_channels_value(out_dev: torch.Tensor):
     """Host values (numpy uint32 [K]) of an absmax_i32_channels result (synchronizes)."""
     return out_dev.cpu().numpy().view("uint32")
+
+
+HIST_BINS = 2048
+
+
+def hist_shift(max_abs: int) -> int:
+    """The smallest shift with (max_abs >> shift) < HIST_BINS."""
+    j = 0
+    while (int(max_abs) >> j) >= HIST_BINS:
+        j += 1
+    return j
+
+
+def hist_i32(x: torch.Tensor, shift: int, relu: bool = False, out_dev: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Counts of (|x| >> shift) per bin: HIST_BINS uint32 words in an int32 device tensor (no synchronization)."""
+    _dev(x, torch.int32, "x")
+    out = out_dev if out_dev is not None else torch.empty(HIST_BINS, dtype=torch.int32, device=x.device)
+    _check(lib().dfq_hist_i32(_ptr(x), x.numel(), int(bool(relu)), int(shift), _ptr(out), _stream(stream)), "dfq_hist_i32")
+    return out
+
+
+def threshold_search(hist_host, shift: int, max_abs: int):
+    """Algorithm 1 on a host histogram (numpy uint32, at least (max_abs >> shift) + 1 entries): (gamma, delta)."""
+    import numpy as np
+    nb = (int(max_abs) >> int(shift)) + 1
+    h = np.ascontiguousarray(np.asarray(hist_host).view(np.uint32)[:nb])
+    g, d = C.c_int64(0), C.c_double(0.0)
+    _check(lib().dfq_threshold_search(h.ctypes.data_as(C.c_void_p), nb, int(shift), int(max_abs), C.byref(g), C.byref(d)),
+           "dfq_threshold_search")
+    return int(g.value), float(d.value)
 
 
 def absmax_i32_value(out_dev: torch.Tensor) -> int:

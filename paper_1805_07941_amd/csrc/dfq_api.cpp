@@ -3,6 +3,7 @@
 #include "dfq.h"
 
 #include <cmath>
+#include <vector>
 
 #include "dfq_host.hpp"
 
@@ -336,6 +337,69 @@ dfq_status dfq_absmax_i32_channels(const int32_t *x, size_t pixels, int K, int r
     if (K < 1) return DFQ_ESHAPE;
     if (!out_dev || (pixels && !x)) return DFQ_EINVAL;
     return from_hip(launch_absmax_i32_channels(x, pixels, K, relu ? 1 : 0, out_dev, (hipStream_t)stream));
+}
+
+dfq_status dfq_hist_i32(const int32_t *x, size_t n, int relu, int shift, uint32_t *hist_dev, dfq_stream stream)
+{
+    if (shift < 0 || shift > 31) return DFQ_EINVAL;
+    if (!hist_dev || (n && !x)) return DFQ_EINVAL;
+    if (n >= ((size_t)1 << 32)) return DFQ_EUNSUPPORTED;      // 32-bit counts
+    return from_hip(launch_hist_i32(x, n, relu ? 1 : 0, shift, hist_dev, (hipStream_t)stream));
+}
+
+// Algorithm 1 on a histogram.  All arithmetic in double, every sum in index order.
+dfq_status dfq_threshold_search(const uint32_t *hist, int nbins, int shift, int64_t max_abs, int64_t *gamma_out,
+                                double *delta_out)
+{
+    constexpr int kCodes = 128;                // non-negative codes of the 8-bit format
+    if (!hist || !gamma_out || nbins < 1 || nbins > 2048 || shift < 0 || shift > 31 || max_abs < 0) return DFQ_EINVAL;
+    if ((max_abs >> shift) != nbins - 1) return DFQ_ESHAPE;    // the last bin is the one that holds the maximum
+    double total = 0.0;
+    for (int t = 0; t < nbins; t++) total += (double)hist[t];
+    int64_t gamma = max_abs;                    // nothing clipped
+    double delta = 0.0;
+    if (total > 0.0 && max_abs > 0) {
+        std::vector<double> cdf(nbins), r(nbins), grid(nbins), q(nbins), codes(kCodes), r_at_code(kCodes);
+        double run = 0.0;
+        for (int t = 0; t < nbins; t++) {
+            run += (double)hist[t] / total;
+            cdf[t] = run;
+        }
+        for (int k = 0; k < kCodes; k++) codes[k] = (double)k / (double)(kCodes - 1);
+        // linear interpolation of (xp, fp) at x, xp increasing, x within [xp[0], xp[np-1]]; `at` remembers the
+        // segment of the previous (smaller) x
+        auto interp = [](double x, const double *xp, const double *fp, int np, int &at) {
+            while (at + 1 < np && xp[at + 1] <= x) at++;
+            if (at == np - 1 || xp[at] == x) return fp[at];
+            const double slope = (fp[at + 1] - fp[at]) / (xp[at + 1] - xp[at]);
+            return slope * (x - xp[at]) + fp[at];
+        };
+        bool found = false;
+        for (int i = kCodes + 1; i <= nbins; i++) {
+            // distribution function with everything from bin i-1 on moved into bin i-1 (clipped at edge i)
+            for (int t = 0; t < nbins; t++) r[t] = t < i - 1 ? cdf[t] : 1.0;
+            const double step = 1.0 / (double)(i - 1);
+            for (int t = 0; t < i; t++) grid[t] = (double)t * step;
+            grid[i - 1] = 1.0;
+            int at = 0;
+            for (int k = 0; k < kCodes; k++) r_at_code[k] = interp(codes[k], grid.data(), r.data(), i, at);
+            at = 0;
+            for (int t = 0; t < i; t++) q[t] = interp(grid[t], codes.data(), r_at_code.data(), kCodes, at);
+            double d = 0.0;
+            for (int t = 0; t < nbins; t++) d += std::fabs(cdf[t] - (t < i ? q[t] : r[t]));
+            if (!found || delta > d) {
+                found = true;
+                delta = d;
+                const int64_t edge = ((int64_t)i << shift) - 1;
+                gamma = edge < max_abs ? edge : max_abs;
+            }
+        }
+    } else {
+        gamma = 0;
+    }
+    *gamma_out = gamma;
+    if (delta_out) *delta_out = delta;
+    return DFQ_OK;
 }
 
 dfq_status dfq_mfma_rate_probe(const int8_t *a_codes, const int8_t *b_codes, int32_t *sink, int blocks, int iters,

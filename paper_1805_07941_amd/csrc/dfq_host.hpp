@@ -51,6 +51,7 @@ hipError_t launch_quantize_rows(const float *x, int8_t *q, size_t rows, size_t r
 hipError_t launch_quantize_i32_rows(const float *x, int32_t *q, size_t rows, size_t row_len, const int32_t *frac, int frac_add,
                                     hipStream_t st);
 hipError_t launch_absmax_f32_rows(const float *x, size_t rows, size_t row_len, float *out, hipStream_t st);
+hipError_t launch_hist_i32(const int32_t *x, size_t n, int relu, int shift, uint32_t *out, hipStream_t st);
 hipError_t launch_absmax_i32_channels(const int32_t *x, size_t pixels, int K, int relu, uint32_t *out, hipStream_t st);
 
 bool conv_direct_supports(const ConvArgs &a);

@@ -547,6 +547,37 @@ hipError_t launch_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out
     return hipGetLastError();
 }
 
+// Histogram of |x| >> shift over kHistBins bins (Algorithm 1, first step): each workgroup counts its
+// share in LDS and adds its non-empty bins to the result, which a small kernel cleared first.  A
+// magnitude beyond the last bin (a shift smaller than the caller was told to use) lands in the last bin.
+constexpr int kHistBins = 2048;
+
+__global__ void __launch_bounds__(kBlock) hist_i32_kernel(const int32_t *__restrict__ x, size_t n, int relu, int shift, uint32_t *out)
+{
+    __shared__ uint32_t bins[kHistBins];
+    for (int i = threadIdx.x; i < kHistBins; i += kBlock) bins[i] = 0u;
+    __syncthreads();
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        const int v = x[i];
+        const uint32_t a = v >= 0 ? (uint32_t)v : (relu ? 0u : (uint32_t)0 - (uint32_t)v);
+        atomicAdd(&bins[min(a >> shift, (uint32_t)(kHistBins - 1))], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kHistBins; i += kBlock)
+        if (bins[i]) atomicAdd(out + i, bins[i]);
+}
+
+hipError_t launch_hist_i32(const int32_t *x, size_t n, int relu, int shift, uint32_t *out, hipStream_t st)
+{
+    clear_u32_n<<<kHistBins / kBlock, kBlock, 0, st>>>(out, kHistBins);
+    if (n) {
+        int g = grid_for(n);
+        if (g > 1024) g = 1024;                 // every workgroup ends with up to 2048 atomics on the result
+        hist_i32_kernel<<<g, kBlock, 0, st>>>(x, n, relu, shift, out);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_absmax_i32_channels(const int32_t *x, size_t pixels, int K, int relu, uint32_t *out, hipStream_t st)
 {
     clear_u32_n<<<(K + kBlock - 1) / kBlock, kBlock, 0, st>>>(out, K);

@@ -39,10 +39,25 @@ def _read_f32(t: torch.Tensor) -> float:
     return float(t.cpu()[0])
 
 
-def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True, per_channel: bool = False):
+def _threshold(acc: torch.Tensor, relu: bool, rule: str) -> int:
+    """Activation threshold in accumulator units: the maximum magnitude after the ReLU, or - rule
+    "search" - Algorithm 1 on the histogram of the magnitudes (device histogram, host search)."""
+    m = B.absmax_i32_value(B.absmax_i32(acc, relu=relu))
+    if rule == "maxabs" or m == 0:
+        return m
+    j = B.hist_shift(m)
+    counts = B.hist_i32(acc, j, relu=relu).cpu().numpy()
+    return B.threshold_search(counts, j, m)[0]
+
+
+def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True, per_channel: bool = False,
+              rule: str = "maxabs"):
     """x: float32 NHWC images (or int8 codes when the network takes codes).  Returns
     (Quantized, dict of int8 tensors of the calibration batch).
-    per_channel: one weight format per output channel instead of one per layer."""
+    per_channel: one weight format per output channel instead of one per layer.
+    rule: "maxabs" (thresholds are maxima) or "search" (Algorithm 1; per-layer weight formats only)."""
+    if rule not in ("maxabs", "search") or (rule == "search" and per_channel):
+        raise ValueError("rule must be 'maxabs' or 'search' (the search with per-layer weight formats)")
     qz = Quantized()
     t: Dict[str, torch.Tensor] = {}
     if net.input_is_int8:
@@ -97,7 +112,7 @@ def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True, 
             else:
                 _, acc = B.conv_q(t[src], w, b, f_in, f_w, 0, nd.stride, nd.pad, nd.groups, nd.relu,
                                   want_y=False, want_acc=True)
-                m = B.absmax_i32_value(B.absmax_i32(acc, relu=nd.relu))
+                m = _threshold(acc, nd.relu, rule)
                 del acc
                 qz.frac[nd.dst] = B.fmt_from_absmax_i32(m, f_in + f_w)
             t[nd.dst], _ = B.conv_q(t[src], w, b, f_in, f_w, qz.frac[nd.dst], nd.stride, nd.pad, nd.groups, nd.relu)
@@ -105,7 +120,7 @@ def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True, 
             a, b2 = nd.srcs
             fa, fb = qz.frac[a], qz.frac[b2]
             _, acc = B.eltwise_q(t[a], fa, t[b2], fb, 0, nd.relu, want_y=False, want_acc=True)
-            m = B.absmax_i32_value(B.absmax_i32(acc, relu=nd.relu))
+            m = _threshold(acc, nd.relu, rule)
             del acc
             qz.frac[nd.dst] = B.fmt_from_absmax_i32(m, max(fa, fb))
             t[nd.dst], _ = B.eltwise_q(t[a], fa, t[b2], fb, qz.frac[nd.dst], nd.relu)

@@ -5,6 +5,7 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -119,6 +120,8 @@ def test_other_calls_reject_bad_arguments(B):
     assert L.dfq_concat_q(2, ptrs, Cs, fs, 3 << 20, f(3), 4, None) == B.ESHAPE
     assert L.dfq_absmax_f32(1 << 20, 4, None, None) == B.EINVAL
     assert L.dfq_absmax_i32(None, 4, 0, 1 << 20, None) == B.EINVAL
+    assert L.dfq_hist_i32(1 << 20, 4, 0, 32, 2 << 20, None) == B.EINVAL                               # shift
+    assert L.dfq_hist_i32(1 << 20, 4, 0, 3, None, None) == B.EINVAL
     assert L.dfq_mfma_rate_probe(None, 1 << 20, 2 << 20, 1, 1, None, None) == B.EINVAL
     assert L.dfq_mfma_rate_probe(1 << 20, 2 << 20, 3 << 20, 0, 1, None, None) == B.EINVAL              # no workgroups
     assert L.dfq_mfma_rate_probe(1 << 20, (2 << 20) + 4, 3 << 20, 1, 1, None, None) == B.EINVAL        # alignment
@@ -137,3 +140,30 @@ def test_binding_fails_loudly_without_the_library(B, monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libdfq.so")
     with pytest.raises(RuntimeError):
         B.lib()
+
+
+def test_threshold_search_is_host_code_and_matches_the_oracle(B):
+    """dfq_threshold_search needs no GPU: Algorithm 1 on host histograms against the oracle's search,
+    thresholds identical, measures to rounding."""
+    import oracle as orc
+    rng = np.random.default_rng(51)
+    cases = []
+    x = np.abs(rng.standard_normal(100000) * 3000).astype(np.int32); x[0] = 2_000_000
+    cases.append(x)
+    cases.append(rng.integers(0, 100000, 50000).astype(np.int32))
+    cases.append(np.abs(rng.standard_normal(20000) * 40).astype(np.int32))          # fewer than 129 bins... or a few more
+    cases.append((rng.exponential(500.0, 80000)).astype(np.int32))
+    cases.append(rng.integers(-2 ** 31, 2 ** 31, 30000).astype(np.int32))
+    cases.append(np.zeros(100, np.int32))
+    for x in cases:
+        counts, j, m = orc.hist_i32(x)
+        want_g, want_d = orc.threshold_search(counts, j, m)
+        got_g, got_d = B.threshold_search(counts.astype(np.uint32), j, m)
+        assert got_g == want_g
+        assert abs(got_d - want_d) <= 1e-12 * max(1.0, want_d)
+    L = B.lib()
+    h = (C.c_uint32 * 4)(1, 2, 3, 4)
+    g = C.c_int64(0)
+    assert L.dfq_threshold_search(h, 4, 0, 7, C.byref(g), None) == B.ESHAPE       # 7 >> 0 is not bin 3
+    assert L.dfq_threshold_search(h, 4, 1, 7, C.byref(g), None) == B.OK and g.value == 7
+    assert L.dfq_threshold_search(None, 4, 1, 7, C.byref(g), None) == B.EINVAL

@@ -182,6 +182,24 @@ def test_per_channel_weight_formats_networks(G, which):
             assert sum(1 for fn, _ in plan._calls if fn.__name__ == "dfq_conv_q_pc_add") >= 4
 
 
+def test_threshold_search_calibration_network(G):
+    """Calibration with Algorithm 1 as the threshold rule: same formats, weights and tensors as the oracle."""
+    B, gnet = G
+    net = wl.resnet50(batch=8, hw=64, classes=100)
+    x = net.input_float()
+    calib = x[:2]
+    qz_o, t_o = onet.calibrate(net, calib, rule="search")
+    qz_g, t_g = gnet.calibrate(net, dev(calib), rule="search")
+    _compare_calibration(net, qz_o, t_o, qz_g, t_g)
+    qz_m, _ = onet.calibrate(net, calib)
+    assert qz_o.frac != qz_m.frac                      # the rule does change some formats on this input
+    plan = gnet.Plan(net, qz_g, 8, keep_all=False, fuse=True)
+    logits = host(plan.run(dev(x)))
+    for i in (0, 7):
+        t = onet.infer(net, qz_o, x[i:i + 1])
+        assert np.array_equal(logits[i:i + 1], onet.logits(net, qz_o, t))
+
+
 def test_fused_joins_give_the_same_logits(G):
     """A plan that runs each residual add inside the convolution in front of it must reproduce the
     unfused plan bit for bit (and through it the oracle, which the test above pins)."""

@@ -359,3 +359,21 @@ def test_conv_q_pc_add_equals_the_two_calls(B, shape):
     # shifts outside the lean range are declined, not mis-computed
     f_w = np.full(K, 30, np.int32)
     assert B.conv_q_pc_add(xd, wd, bd, od, 4, dev(f_w), (30, 30), 2, False, 3, 3, True) is None
+
+
+def test_histogram_and_threshold_search(B):
+    """dfq_hist_i32 counts exactly what the oracle's histogram counts; the search on it gives the oracle's threshold."""
+    rng = np.random.default_rng(61)
+    xs = [np.abs(rng.standard_normal((4, 30, 30, 64)) * 5000).astype(np.int32),
+          rng.integers(-2 ** 31, 2 ** 31, (3, 7, 11, 24)).astype(np.int32),
+          (rng.standard_normal((2, 56, 56, 256)) * 1e5).astype(np.int32),
+          np.zeros((1, 3, 3, 8), np.int32)]
+    xs[0][0, 0, 0, 0] = 9_000_000
+    for x in xs:
+        for relu in (False, True):
+            counts, j, m = orc.hist_i32(x, relu=relu)
+            gm = B.absmax_i32_value(B.absmax_i32(dev(x), relu=relu))
+            assert gm == m and B.hist_shift(gm) == j
+            h = host(B.hist_i32(dev(x), j, relu=relu)).view(np.uint32)
+            assert np.array_equal(h[:len(counts)].astype(np.uint64), counts) and int(h[len(counts):].sum()) == 0
+            assert B.threshold_search(h, j, m)[0] == orc.threshold_search(counts, j, m)[0]
