@@ -461,14 +461,26 @@ __global__ void __launch_bounds__(kBlock) absmax_f32_kernel(const float *__restr
     block_max_to(m, out);
 }
 
+__device__ __forceinline__ uint32_t magnitude(int v, int relu)
+{
+    return v >= 0 ? (uint32_t)v : (relu ? 0u : (uint32_t)0 - (uint32_t)v);
+}
+
+// 16 bytes per lane and access where the array is aligned for it; the first lanes of the launch take the tail
 __global__ void __launch_bounds__(kBlock) absmax_i32_kernel(const int32_t *__restrict__ x, size_t n, int relu, uint32_t *out)
 {
     uint32_t m = 0;
-    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
-        int v = x[i];
-        uint32_t a = v >= 0 ? (uint32_t)v : (relu ? 0u : (uint32_t)0 - (uint32_t)v);
-        m = max(m, a);
+    const size_t t = (size_t)blockIdx.x * kBlock + threadIdx.x, threads = (size_t)gridDim.x * kBlock;
+    size_t n4 = 0;
+    if (((uintptr_t)x & 15) == 0) {
+        n4 = n / 4;
+        const int4 *x4 = (const int4 *)x;
+        for (size_t i = t; i < n4; i += threads) {
+            const int4 v = x4[i];
+            m = max(max(m, magnitude(v.x, relu)), max(magnitude(v.y, relu), max(magnitude(v.z, relu), magnitude(v.w, relu))));
+        }
     }
+    for (size_t i = n4 * 4 + t; i < n; i += threads) m = max(m, magnitude(x[i], relu));
     block_max_to(m, out);
 }
 
@@ -557,11 +569,18 @@ __global__ void __launch_bounds__(kBlock) hist_i32_kernel(const int32_t *__restr
     __shared__ uint32_t bins[kHistBins];
     for (int i = threadIdx.x; i < kHistBins; i += kBlock) bins[i] = 0u;
     __syncthreads();
-    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
-        const int v = x[i];
-        const uint32_t a = v >= 0 ? (uint32_t)v : (relu ? 0u : (uint32_t)0 - (uint32_t)v);
-        atomicAdd(&bins[min(a >> shift, (uint32_t)(kHistBins - 1))], 1u);
+    const size_t t = (size_t)blockIdx.x * kBlock + threadIdx.x, threads = (size_t)gridDim.x * kBlock;
+    auto count = [&](int v) { atomicAdd(&bins[min(magnitude(v, relu) >> shift, (uint32_t)(kHistBins - 1))], 1u); };
+    size_t n4 = 0;
+    if (((uintptr_t)x & 15) == 0) {
+        n4 = n / 4;
+        const int4 *x4 = (const int4 *)x;
+        for (size_t i = t; i < n4; i += threads) {
+            const int4 v = x4[i];
+            count(v.x); count(v.y); count(v.z); count(v.w);
+        }
     }
+    for (size_t i = n4 * 4 + t; i < n; i += threads) count(x[i]);
     __syncthreads();
     for (int i = threadIdx.x; i < kHistBins; i += kBlock)
         if (bins[i]) atomicAdd(out + i, bins[i]);
