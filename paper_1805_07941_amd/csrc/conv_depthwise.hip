@@ -5,10 +5,15 @@
 //
 // A lane owns 4 consecutive channels (one 32-bit word of an NHWC pixel) and TW consecutive
 // output pixels of one output row; consecutive lanes take consecutive channel words, so every
-// load and store of a wavefront covers whole pixels contiguously.  Each input word is loaded
-// once per lane and reused for every tap and output pixel it feeds; weights sit in LDS
-// transposed to [tap][channel] so that one word read gives the 4 channels' weights of a tap.
-// The 32-bit sums stay in registers through bias, ReLU, rounding shift and clamp.
+// load and store of a wavefront covers whole pixels contiguously.  All input words of an item
+// (R rows x IW columns) are fetched up front by range-checked buffer loads - positions in the
+// padding get an out-of-range offset and arrive as zeros, so there is no branch between the
+// loads and they are all in flight together.  The words of four neighbouring columns are then
+// transposed in registers (byte permutes) into one word per channel holding that channel's
+// four neighbouring pixels; an output's three taps of a kernel row are a byte-aligned window of
+// two such words, and one v_dot4_i32_i8 with the row's three weights (fourth factor zero)
+// accumulates them.  Weights sit in LDS as one such word per (kernel row, channel).  The 32-bit
+// sums stay in registers through bias, ReLU, rounding shift and clamp.
 #include "conv_epilogue.hpp"
 
 namespace dfq {
@@ -21,40 +26,61 @@ struct DwParams {
     ConvArgs a;
     int cw;            // C / 4
     int qblocks;       // ceil(Q / TW)
-    long long items;   // N * P * qblocks * cw
+    int items;         // N * P * qblocks * cw (below 2^31)
+    unsigned x_bytes;  // size of the input (below 2^31: larger offsets mean "outside")
+    FastDiv div_cw, div_qb, div_p;
 };
 
 template <int R, int S, int ST, int TW>
 __global__ void __launch_bounds__(kThreads) conv_depthwise_kernel(DwParams prm)
 {
+    static_assert(S == 3 && (ST == 1 || ST == 2), "windows of three taps inside eight columns");
     constexpr int IW = (TW - 1) * ST + S;   // input columns one lane touches per kernel row
-    extern __shared__ uint32_t wt[];        // [R*S][C/4] words: weights of 4 channels for one tap
+    static_assert(IW <= 6, "two column blocks: columns 0-3 and 4-5");
+    extern __shared__ uint32_t wt[];        // [R][C] words: (w[c][r][0], w[c][r][1], w[c][r][2], 0)
 
     const ConvArgs &a = prm.a;
-    // transpose w[c][tap] -> wt[tap][c]
-    {
-        int8_t *wb = (int8_t *)wt;
-        const int total = R * S * a.C;
-        for (int i = threadIdx.x; i < total; i += kThreads) {
-            int c = i / (R * S), tap = i - c * (R * S);
-            wb[tap * a.C + c] = a.w[i];
-        }
+    for (int c = threadIdx.x; c < a.C; c += kThreads) {
+        // the channel's R*S weight bytes, all loads in flight together
+        uint32_t wb[R * S];
+#pragma unroll
+        for (int i = 0; i < R * S; i++) wb[i] = (uint8_t)a.w[(size_t)c * (R * S) + i];
+#pragma unroll
+        for (int r = 0; r < R; r++) wt[r * a.C + c] = wb[r * S] | (wb[r * S + 1] << 8) | (wb[r * S + 2] << 16);
     }
     __syncthreads();
 
     Requant rq;
     rq.init(a.shift, a.relu);
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)prm.x_bytes, 0x00020000);
 
-    for (long long it = (long long)blockIdx.x * kThreads + threadIdx.x; it < prm.items; it += (long long)gridDim.x * kThreads) {
-        const int cwi = (int)(it % prm.cw);
-        long long t = it / prm.cw;
-        const int qb = (int)(t % prm.qblocks);
-        t /= prm.qblocks;
-        const int p = (int)(t % a.P);
-        const int n = (int)(t / a.P);
+    for (int it = blockIdx.x * kThreads + threadIdx.x; it < prm.items; it += gridDim.x * kThreads) {
+        // it = ((n * P + p) * qblocks + qb) * cw + cwi, taken apart with multiply-high divisions
+        int t = fastdiv(it, prm.div_cw);
+        const int cwi = it - t * prm.cw;
+        const int t2 = fastdiv(t, prm.div_qb);
+        const int qb = t - t2 * prm.qblocks;
+        const int n = fastdiv(t2, prm.div_p);
+        const int p = t2 - n * a.P;
         const int c = cwi * 4;
         const int q0 = qb * TW;
         const int iw_first = q0 * ST - a.pad;
+
+        // ---- every input word of the item, zeros where the window leaves the image
+        uint32_t xw[R][6];
+#pragma unroll
+        for (int r = 0; r < R; r++) {
+            const int ih = p * ST - a.pad + r;
+            const bool rowok = (unsigned)ih < (unsigned)a.H;
+            const unsigned rowoff = (unsigned)(((n * a.H + ih) * a.W) * a.C + c);
+#pragma unroll
+            for (int j = 0; j < 6; j++) {
+                const int iw = iw_first + j;
+                const bool ok = j < IW && rowok && (unsigned)iw < (unsigned)a.W;
+                xw[r][j] = j < IW ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(xr, ok ? (int)(rowoff + (unsigned)(iw * a.C)) : (int)0x80000000, 0, 0)
+                                  : 0u;
+            }
+        }
 
         int acc[TW][4];
         {
@@ -63,32 +89,30 @@ __global__ void __launch_bounds__(kThreads) conv_depthwise_kernel(DwParams prm)
 #pragma unroll
             for (int j = 0; j < TW; j++) { acc[j][0] = bv.x; acc[j][1] = bv.y; acc[j][2] = bv.z; acc[j][3] = bv.w; }
         }
-        const int8_t *img = a.x + (size_t)n * a.H * a.W * a.C + c;
 #pragma unroll
         for (int r = 0; r < R; r++) {
-            const int ih = p * ST - a.pad + r;
-            if ((unsigned)ih >= (unsigned)a.H) continue;
-            const int8_t *row = img + (size_t)ih * a.W * a.C;
-            int xv[IW][4];
+            const uint4 wq = *(const uint4 *)(wt + r * a.C + c);
+            const uint32_t wrow[4] = {wq.x, wq.y, wq.z, wq.w};
+            // columns 0-3 transposed: lo[e] = (x0.e, x1.e, x2.e, x3.e); columns 4-5: hi[e] = (x4.e, x5.e, 0, 0)
+            const uint32_t ab_l = __builtin_amdgcn_perm(xw[r][1], xw[r][0], 0x05010400u), ab_h = __builtin_amdgcn_perm(xw[r][1], xw[r][0], 0x07030602u);
+            const uint32_t cd_l = __builtin_amdgcn_perm(xw[r][3], xw[r][2], 0x05010400u), cd_h = __builtin_amdgcn_perm(xw[r][3], xw[r][2], 0x07030602u);
+            uint32_t lo[4], hi[4];
+            lo[0] = __builtin_amdgcn_perm(cd_l, ab_l, 0x05040100u);
+            lo[1] = __builtin_amdgcn_perm(cd_l, ab_l, 0x07060302u);
+            lo[2] = __builtin_amdgcn_perm(cd_h, ab_h, 0x05040100u);
+            lo[3] = __builtin_amdgcn_perm(cd_h, ab_h, 0x07060302u);
+            hi[0] = __builtin_amdgcn_perm(xw[r][5], xw[r][4], 0x0c0c0400u);
+            hi[1] = __builtin_amdgcn_perm(xw[r][5], xw[r][4], 0x0c0c0501u);
+            hi[2] = __builtin_amdgcn_perm(xw[r][5], xw[r][4], 0x0c0c0602u);
+            hi[3] = __builtin_amdgcn_perm(xw[r][5], xw[r][4], 0x0c0c0703u);
 #pragma unroll
-            for (int j = 0; j < IW; j++) {
-                const int iw = iw_first + j;
-                uint32_t w32 = 0;
-                if ((unsigned)iw < (unsigned)a.W) w32 = *(const uint32_t *)(row + (size_t)iw * a.C);
+            for (int j = 0; j < TW; j++)
 #pragma unroll
-                for (int e = 0; e < 4; e++) xv[j][e] = byte_of(w32, e);
-            }
-#pragma unroll
-            for (int s = 0; s < S; s++) {
-                const uint32_t ww = wt[(r * S + s) * prm.cw + cwi];
-                int wv[4];
-#pragma unroll
-                for (int e = 0; e < 4; e++) wv[e] = byte_of(ww, e);
-#pragma unroll
-                for (int j = 0; j < TW; j++)
-#pragma unroll
-                    for (int e = 0; e < 4; e++) acc[j][e] += xv[j * ST + s][e] * wv[e];
-            }
+                for (int e = 0; e < 4; e++) {
+                    // pixels j*ST .. j*ST+3 of channel e; the fourth meets the zero in the weight word
+                    const uint32_t win = j * ST == 0 ? lo[e] : __builtin_amdgcn_alignbyte(hi[e], lo[e], j * ST);
+                    acc[j][e] = __builtin_amdgcn_sdot4((int)win, (int)wrow[e], acc[j][e], false);
+                }
         }
         const size_t pix0 = ((size_t)n * a.P + p) * a.Q + q0;
         int sh[4] = {a.shift, a.shift, a.shift, a.shift};   // one weight format per channel: each its own shift
@@ -120,11 +144,17 @@ hipError_t launch_dw(const ConvArgs &a, hipStream_t st)
     prm.a = a;
     prm.cw = a.C / 4;
     prm.qblocks = (a.Q + TW - 1) / TW;
-    prm.items = (long long)a.N * a.P * prm.qblocks * prm.cw;
-    long long blocks = (prm.items + kThreads - 1) / kThreads;
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    const long long items = (long long)a.N * a.P * prm.qblocks * prm.cw;
+    if (items >= (1LL << 31) - 256 * 16 * kThreads) return hipErrorInvalidValue;   // conv_depthwise_supports() rules this out
+    prm.items = (int)items;
+    prm.x_bytes = (unsigned)((long long)a.N * a.H * a.W * a.C);
+    prm.div_cw = make_fastdiv(prm.cw);
+    prm.div_qb = make_fastdiv(prm.qblocks);
+    prm.div_p = make_fastdiv(a.P);
+    long long blocks = (items + kThreads - 1) / kThreads;
+    if (blocks > 256 * 8) blocks = 256 * 8;   // every block first gathers the weights of all channels: few, long-lived blocks
     if (blocks < 1) blocks = 1;
-    size_t lds = (size_t)R * S * a.C;
+    size_t lds = (size_t)R * a.C * 4;
     conv_depthwise_kernel<R, S, ST, TW><<<(unsigned)blocks, kThreads, lds, st>>>(prm);
     return hipGetLastError();
 }
@@ -136,7 +166,10 @@ bool conv_depthwise_supports(const ConvArgs &a)
     if (a.groups != a.C || a.K != a.C) return false;
     if (a.C % 4) return false;
     if (a.R != 3 || a.S != 3 || (a.stride != 1 && a.stride != 2)) return false;
-    if (a.C * 9 > 48 * 1024) return false;
+    if (a.C * 12 > 48 * 1024) return false;                                      // weight words in LDS
+    if ((long long)a.N * a.H * a.W * a.C >= (1LL << 31)) return false;           // 31-bit byte offsets into the input
+    // work items (4 channels x up to 4 pixels each) are numbered with 31 bits
+    if ((long long)a.N * a.P * ((a.Q + 1) / 2) * (a.C / 4) >= (1LL << 31) - 256 * 16 * 256) return false;
     if (((uintptr_t)a.x & 3) || (a.y && (((uintptr_t)a.y & 3) || (a.ldy & 3)))) return false;
     if (a.b && ((uintptr_t)a.b & 15)) return false;
     if (a.acc_out && ((uintptr_t)a.acc_out & 15)) return false;
