@@ -115,10 +115,10 @@ __global__ void __launch_bounds__(kThreads) conv_depthwise_kernel(DwParams prm)
                 }
         }
         const size_t pix0 = ((size_t)n * a.P + p) * a.Q + q0;
-        int sh[4] = {a.shift, a.shift, a.shift, a.shift};   // one weight format per channel: each its own shift
+        ChannelRequant cr[4];                                // one weight format per channel: each its own shift
         if (a.frac_w) {
 #pragma unroll
-            for (int e = 0; e < 4; e++) sh[e] += a.frac_w[c + e];
+            for (int e = 0; e < 4; e++) cr[e].init(a.shift + a.frac_w[c + e]);
         }
 #pragma unroll
         for (int j = 0; j < TW; j++) {
@@ -128,7 +128,7 @@ __global__ void __launch_bounds__(kThreads) conv_depthwise_kernel(DwParams prm)
                 int o[4];
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
-                    if (a.frac_w) o[e] = requant8(a.relu ? max(acc[j][e], 0) : acc[j][e], sh[e]);
+                    if (a.frac_w) o[e] = cr[e].apply(acc[j][e], a.relu);
                     else o[e] = rq.fast ? rq.fast_one(acc[j][e]) : rq.slow_one(acc[j][e]);
                 }
                 *(uint32_t *)(a.y + (pix0 + j) * (size_t)a.ldy + c) = pack4_clamped(o[0], o[1], o[2], o[3]);

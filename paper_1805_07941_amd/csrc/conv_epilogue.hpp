@@ -106,6 +106,24 @@ __device__ __forceinline__ int requant_one_per_channel(int v, int s, int hi, int
     return (v + badd + (int)__builtin_amdgcn_ubfe((unsigned)v, (unsigned)s, (unsigned)min(s, 1))) >> s;
 }
 
+// Rescale of one channel whose shift is only known at run time: the four-instruction form when the shift
+// lies in [0, 23], the general rounding otherwise.
+struct ChannelRequant {
+    int s, hi, badd;
+    bool fast;
+    __device__ __forceinline__ void init(int shift)
+    {
+        s = shift;
+        fast = (unsigned)shift <= 23u;
+        hi = 127 << (fast ? shift : 0);
+        badd = (fast && shift > 0) ? ((1 << (shift - 1)) - 1) : 0;
+    }
+    __device__ __forceinline__ int apply(int v, int relu) const
+    {
+        return fast ? requant_one_per_channel(v, s, hi, badd, relu) : requant8(relu ? max(v, 0) : v, s);
+    }
+};
+
 // Four channels' sums rescaled per channel, then the fused add of Eq. 10 with the four codes in `other`.
 __device__ __forceinline__ uint32_t requant_add_four_per_channel(int v0, int v1, int v2, int v3, const int4 &s, const int4 &hi,
                                                                  const int4 &badd, int relu, uint32_t other, int sa, int sb,
@@ -155,8 +173,9 @@ __device__ __forceinline__ void store_tile_lane_general(const v16i &v, const Con
 #pragma unroll
             for (int e = 0; e < 4; e++) {
                 const int r = 4 * j + e;
-                const int s = a.frac_w ? shift + a.frac_w[kc + r] : shift;
-                q[e] = requant8(relu ? max(v[r], 0) : v[r], s);
+                ChannelRequant cr;
+                cr.init(a.frac_w ? shift + a.frac_w[kc + r] : shift);
+                q[e] = cr.apply(v[r], relu);
             }
             o[j] = pack4_clamped(q[0], q[1], q[2], q[3]);
         }
@@ -172,6 +191,32 @@ __device__ __forceinline__ void store_tile_lane_general(const v16i &v, const Con
             if (a.y) a.y[(size_t)m * a.ldy + kc + r] = (int8_t)requant8(relu ? max(val, 0) : val, s);
         }
     }
+}
+
+// One weight format per output channel with the lane's 16 shifts already in registers: whole 16-channel
+// group, aligned row, no accumulator dump - one 16-byte store, no loads.
+__device__ __forceinline__ void store_tile_lane_per_channel(const v16i &v, const ConvArgs &a, const int (&shifts)[16], int relu,
+                                                            long long m, int kc)
+{
+    uint32_t o[4];
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        int q[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            ChannelRequant cr;
+            cr.init(shifts[4 * j + e]);
+            q[e] = cr.apply(v[4 * j + e], relu);
+        }
+        o[j] = pack4_clamped(q[0], q[1], q[2], q[3]);
+    }
+    *(uint4 *)(a.y + (size_t)m * a.ldy + kc) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// the conditions of store_tile_lane_per_channel for a block whose channel range ends at k_end
+__device__ __forceinline__ bool epilogue_is_per_channel_packed(const ConvArgs &a, int k_end)
+{
+    return a.frac_w && !a.acc_out && a.y && ((a.ldy & 15) == 0) && (((uintptr_t)a.y & 15) == 0) && k_end <= a.K;
 }
 
 // true when every tile of a launch can take the hot form (k_end = end of the block's channel range)

@@ -55,12 +55,12 @@ struct MfmaParams {
 // GENERAL: the epilogue may meet a ragged channel tail, an unaligned or strided-odd output row, a
 // shift outside [0, 23] or an accumulator dump; the launcher picks the lean instantiation
 // (GENERAL = false) whenever none of these applies.  OCC: wavefronts per SIMD to fit registers for.
-// PC (needs UT, excludes GENERAL): the lean epilogue with one weight format per output channel, every
+// PC (excludes GENERAL): the lean epilogue with one weight format per output channel, every
 // channel's shift within [0, 23] (the caller of the library vouches for the range of the formats).
 template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool PW, bool GENERAL, int OCC, bool PC = false>
 __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(MfmaParams prm)
 {
-    static_assert(!PC || (UT && !GENERAL), "the per-channel lean form is built for uniform taps only");
+    static_assert(!PC || !GENERAL, "the per-channel form is a lean one");
     static_assert(NSTAGES >= 2 && NSTAGES <= 6, "ring depth");
     static_assert(UT || !PW, "the pointwise form keeps its position in scalar registers");
     constexpr int NW = WAVES_P * WAVES_C;                 // wavefronts per workgroup
@@ -449,11 +449,11 @@ inline hipError_t big_lds(void (*k)(MfmaParams))
 // The per-channel lean form holds a group's rescale constants in registers on top of everything
 // else: it is built for the tile shapes whose register budget has room for them (wavefront tiles of
 // 64 x 64 at no more than three wavefronts per SIMD).
-template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool PW, int OCC>
+template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool PW, int OCC>
 constexpr void (*per_channel_kernel())(MfmaParams)
 {
     if constexpr (OCC <= 3 && (BP / WAVES_P) * (BC / WAVES_C) <= 64 * 64)
-        return conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, PW, false, OCC, true>;
+        return conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, UT, PW, false, OCC, true>;
     else
         return nullptr;
 }
@@ -490,21 +490,23 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     using K = void (*)(MfmaParams);
     const bool ut = a.C % kStepBytes == 0;
     const bool pw = ut && a.R == 1 && a.S == 1 && a.stride == 1 && a.pad == 0;
-    static const K kernels[8] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, false, occ>,
+    static const K kernels[9] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, false, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, true, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, false, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, true, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, false, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, true, occ>,
-                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, occ>(),
-                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, occ>()};
-    static const hipError_t attr[8] = {big_lds(kernels[0]), big_lds(kernels[1]), big_lds(kernels[2]), big_lds(kernels[3]),
-                                       big_lds(kernels[4]), big_lds(kernels[5]), big_lds(kernels[6]), big_lds(kernels[7])};
+                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, occ>(),
+                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, occ>(),
+                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, occ>()};
+    static const hipError_t attr[9] = {big_lds(kernels[0]), big_lds(kernels[1]), big_lds(kernels[2]), big_lds(kernels[3]),
+                                       big_lds(kernels[4]), big_lds(kernels[5]), big_lds(kernels[6]), big_lds(kernels[7]),
+                                       big_lds(kernels[8])};
     // shifts the epilogue will meet: one, or with per-channel weight formats the declared range
     const int s_lo = a.shift + (a.frac_w ? a.frac_w_lo : 0), s_hi = a.shift + (a.frac_w ? a.frac_w_hi : 0);
-    const bool general = !((!a.frac_w || (ut && kernels[6])) && s_lo >= 0 && s_hi <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
+    const bool general = !((!a.frac_w || kernels[6]) && s_lo >= 0 && s_hi <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
                            ((uintptr_t)a.y & 15) == 0 && a.K % BC == 0 && y_bytes < (1LL << 31));
-    const int which = (!general && a.frac_w) ? (pw ? 7 : 6) : (pw ? 4 : ut ? 2 : 0) + (general ? 1 : 0);
+    const int which = (!general && a.frac_w) ? (pw ? 7 : ut ? 6 : 8) : (pw ? 4 : ut ? 2 : 0) + (general ? 1 : 0);
     if (attr[which] != hipSuccess) return attr[which];
     K kernel = kernels[which];
     kernel<<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);

@@ -76,6 +76,14 @@ __global__ void __launch_bounds__(kThreads, 2) conv_smallc_kernel(SmallCParams p
     Requant rq;
     rq.init(a.shift, a.relu);
     const bool fast = epilogue_is_fast(a, rq, k0 + BC);
+    // one weight format per output channel: a lane's channels are the same for every tile, so their
+    // shifts are read once
+    const bool pc_packed = epilogue_is_per_channel_packed(a, k0 + BC);
+    __shared__ int pc_shift[CT * 32];
+    if (pc_packed) {
+        for (int i = threadIdx.x; i < CT * 32; i += blockDim.x) pc_shift[i] = a.shift + a.frac_w[k0 + i];
+        __syncthreads();
+    }
     const v4i *wl = (const v4i *)wlds;
 
     int bias[CT][16];
@@ -153,6 +161,15 @@ __global__ void __launch_bounds__(kThreads, 2) conv_smallc_kernel(SmallCParams p
                 const int m = mbase + p * 32 + l32;
                 if (m < prm.M) {
                     if (fast) store_tile_lane_fast(acc[c][p], a, rq, m, kc);
+                    else if (pc_packed) {
+                        int sh[16];
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; r4++) {
+                            const int4 t = *(const int4 *)(pc_shift + c * 32 + 16 * lh + 4 * r4);
+                            sh[4 * r4] = t.x; sh[4 * r4 + 1] = t.y; sh[4 * r4 + 2] = t.z; sh[4 * r4 + 3] = t.w;
+                        }
+                        store_tile_lane_per_channel(acc[c][p], a, sh, a.relu, m, kc);
+                    }
                     else if (kc < a.K) store_tile_lane_general(acc[c][p], a, a.shift, a.relu, m, kc);
                 }
             }
@@ -209,6 +226,14 @@ __global__ void __launch_bounds__(kThreads, 2) conv_smallc_rows_kernel(SmallCRow
     Requant rq;
     rq.init(a.shift, a.relu);
     const bool fast = epilogue_is_fast(a, rq, k0 + BC);
+    // one weight format per output channel: a lane's channels are the same for every tile, so their
+    // shifts are read once
+    const bool pc_packed = epilogue_is_per_channel_packed(a, k0 + BC);
+    __shared__ int pc_shift[CT * 32];
+    if (pc_packed) {
+        for (int i = threadIdx.x; i < CT * 32; i += blockDim.x) pc_shift[i] = a.shift + a.frac_w[k0 + i];
+        __syncthreads();
+    }
     const v4i *wl = (const v4i *)wlds;
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char *)(char *)&wlds[0];
     const unsigned span_base = (unsigned)(a.R * BC * 32) + (unsigned)wave * (unsigned)(2 * a.R * 2 * kGroupBytes);
@@ -347,6 +372,15 @@ __global__ void __launch_bounds__(kThreads, 2) conv_smallc_rows_kernel(SmallCRow
                 const int m = mbase + p * 32 + l32;
                 if (m < prm.M) {
                     if (fast) store_tile_lane_fast(acc[c][p], a, rq, m, kc);
+                    else if (pc_packed) {
+                        int sh[16];
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; r4++) {
+                            const int4 t = *(const int4 *)(pc_shift + c * 32 + 16 * lh + 4 * r4);
+                            sh[4 * r4] = t.x; sh[4 * r4 + 1] = t.y; sh[4 * r4 + 2] = t.z; sh[4 * r4 + 3] = t.w;
+                        }
+                        store_tile_lane_per_channel(acc[c][p], a, sh, a.relu, m, kc);
+                    }
                     else if (kc < a.K) store_tile_lane_general(acc[c][p], a, a.shift, a.relu, m, kc);
                 }
             }
