@@ -160,6 +160,7 @@ class Plan:
         is run together with that add by one dfq_conv_q_add call where a fused kernel covers it
         (same result; the convolution's own int8 tensor is then never produced)."""
         self.net, self.qz, self.batch, self.device = net, qz, batch, device
+        self.order = list(range(len(net.nodes)))                             # node indices in execution order
         self.fused: Dict[int, int] = self._fusable_pairs() if fuse else {}   # conv node index -> add node index
         self.buf: Dict[str, torch.Tensor] = {}
         H, W, Cc = net.shapes[net.input_name]
@@ -174,32 +175,53 @@ class Plan:
         self.logits = torch.empty((batch, P * Q * K), dtype=torch.float32, device=device)
         self._calls, self._calls_key, self._graph, self._keep = None, None, None, None
 
+    def _pointwise_geometry(self, nd) -> bool:
+        H, W, Cc = self.net.shapes[nd.srcs[0]]
+        return B.conv_q_select(self.batch, H, W, Cc, nd.K, nd.R, nd.R, nd.stride, nd.pad, nd.groups) == B.CONV_POINTWISE
+
     def _fusable_pairs(self) -> Dict[int, int]:
         """Convolution nodes directly followed by an element-wise add that is the only reader of
-        their result, filtered by whether the library has a fused kernel for the call."""
+        their result (whether the library has a fused kernel for the call is probed when the call list
+        is built).  Where an add is fed by two convolutions listed as (c, p, add), only c has the
+        geometry of the fused kernel and p does not depend on c, the two are run as (p, c + add):
+        self.order is changed accordingly."""
         net, qz = self.net, self.qz
         readers: Dict[str, int] = {}
         for nd in net.nodes:
             for s in nd.srcs:
                 readers[s] = readers.get(s, 0) + 1
         pairs = {}
-        for i in range(len(net.nodes) - 1):
-            c, e = net.nodes[i], net.nodes[i + 1]
-            if c.op != "conv" or e.op != "eltwise" or c.dst not in e.srcs or readers.get(c.dst, 0) != 1:
+        for j in range(1, len(net.nodes)):
+            e = net.nodes[j]
+            if e.op != "eltwise" or e.srcs[0] == e.srcs[1]:
                 continue
-            if c.dst == net.output_name or e.srcs[0] == e.srcs[1]:
-                continue
-            pairs[i] = i + 1
+            c = net.nodes[j - 1]
+            ok = c.op == "conv" and c.dst in e.srcs and readers.get(c.dst, 0) == 1 and c.dst != net.output_name
+            if j >= 2 and ok and not self._pointwise_geometry(c):
+                # the convolution in front of the add is not one the fused kernel takes: maybe the one before it is
+                c2 = net.nodes[j - 2]
+                if (c2.op == "conv" and {c.dst, c2.dst} == set(e.srcs) and readers.get(c2.dst, 0) == 1
+                        and c2.dst not in c.srcs and c2.dst != net.output_name and self._pointwise_geometry(c2)):
+                    at = self.order.index(j - 2)
+                    self.order[at], self.order[at + 1] = j - 1, j - 2
+                    pairs[j - 2] = j
+                    continue
+            if ok:
+                pairs[j - 1] = j
         return pairs
 
     def _assign_pooled(self):
         """Reuses buffers whose tensor is dead (sized in bytes), to keep the footprint small."""
         net = self.net
-        last = _last_use(net)
+        last: Dict[str, int] = {}                # tensor name -> node index of its last reader in execution order
+        for idx in self.order:
+            for s in net.nodes[idx].srcs:
+                last[s] = idx
         free: list = []
         owner: Dict[str, torch.Tensor] = {}
         skip = set(self.fused.values())          # an add fused into its convolution: buffer taken at the convolution
-        for idx, nd in enumerate(net.nodes):
+        for idx in self.order:
+            nd = net.nodes[idx]
             if idx in skip:
                 for s in nd.srcs:
                     if last.get(s) == idx and s in owner and s != net.input_name and s != net.output_name:
@@ -238,7 +260,8 @@ class Plan:
             calls.append((L.dfq_quantize, (x.data_ptr(), t[net.input_name].data_ptr(), x.numel(), f(qz.frac[net.input_name]))))
             names.append(None)
         fused_adds = set()
-        for idx, nd in enumerate(net.nodes):
+        for idx in self.order:
+            nd = net.nodes[idx]
             if idx in fused_adds:
                 continue
             if nd.op == "conv" and idx in self.fused:

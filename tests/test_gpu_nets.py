@@ -212,6 +212,9 @@ def test_fused_joins_give_the_same_logits(G):
     ref = host(plain.run(x)).copy()
     got = host(fused.run(x)).copy()
     assert len(fused.fused) == 16
+    # first blocks of the later stages list (c, projection, add): only c fits the fused kernel, so the plan
+    # runs the projection first and c together with the add
+    assert fused.order != sorted(fused.order) and sorted(fused.order) == list(range(len(net.nodes)))
     n_fused = sum(1 for fn, _ in fused._calls if fn.__name__ == "dfq_conv_q_add")
     assert n_fused >= 4                              # joins behind pointwise layers with C <= 256 and a rounding step left
     assert np.array_equal(got, ref) and np.abs(ref).max() > 0
