@@ -413,10 +413,86 @@ __global__ void __launch_bounds__(kBlock) pool_kernel(const int8_t *__restrict__
     }
 }
 
+// 3x3 max pooling, 16 channels per lane: window positions in the padding are replaced by the nearest
+// position inside the image, which lies in the same window (pad < k), so the nine 16-byte loads are
+// unconditional and all in flight together; the running maxima are kept as one integer per channel and
+// updated straight from the bytes of the loaded words (sub-dword operand select with sign extension:
+// one instruction per byte and window position, no unpacking).
+struct MaxPool3Params {
+    PoolParams p;
+    int cv;              // C / 16
+    int total;           // N * P * Q * cv (below 2^31)
+    FastDiv div_cv, div_q, div_p;
+};
+
+template <int E>
+__device__ __forceinline__ int max_with_byte(int acc, uint32_t w)
+{
+    if constexpr (E == 0) asm("v_max_i32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(acc) : "v"(acc), "v"(w));
+    else if constexpr (E == 1) asm("v_max_i32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(acc) : "v"(acc), "v"(w));
+    else if constexpr (E == 2) asm("v_max_i32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(acc) : "v"(acc), "v"(w));
+    else asm("v_max_i32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(acc) : "v"(acc), "v"(w));
+    return acc;
+}
+
+__global__ void __launch_bounds__(kBlock) maxpool3_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y, MaxPool3Params prm)
+{
+    const PoolParams &p = prm.p;
+    for (int i = blockIdx.x * kBlock + threadIdx.x; i < prm.total; i += gridDim.x * kBlock) {
+        const int px = fastdiv(i, prm.div_cv);
+        const int c = (i - px * prm.cv) * 16;
+        const int t = fastdiv(px, prm.div_q);
+        const int q = px - t * p.Q;
+        const int n = fastdiv(t, prm.div_p);
+        const int pp = t - n * p.P;
+        uint4 u[9];
+#pragma unroll
+        for (int r = 0; r < 3; r++) {
+            const int ih = min(max(pp * p.stride - p.pad + r, 0), p.H - 1);
+#pragma unroll
+            for (int s2 = 0; s2 < 3; s2++) {
+                const int iw = min(max(q * p.stride - p.pad + s2, 0), p.W - 1);
+                u[r * 3 + s2] = *(const uint4 *)(x + (((size_t)n * p.H + ih) * p.W + iw) * p.C + c);
+            }
+        }
+        int acc[16];
+#pragma unroll
+        for (int j = 0; j < 16; j++) acc[j] = -128;
+#pragma unroll
+        for (int k = 0; k < 9; k++) {
+            const uint32_t w[4] = {u[k].x, u[k].y, u[k].z, u[k].w};
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                acc[4 * j + 0] = max_with_byte<0>(acc[4 * j + 0], w[j]);
+                acc[4 * j + 1] = max_with_byte<1>(acc[4 * j + 1], w[j]);
+                acc[4 * j + 2] = max_with_byte<2>(acc[4 * j + 2], w[j]);
+                acc[4 * j + 3] = max_with_byte<3>(acc[4 * j + 3], w[j]);
+            }
+        }
+        int out[16];
+#pragma unroll
+        for (int j = 0; j < 16; j++) out[j] = p.d == 0 ? max(acc[j], -127) : requant8(acc[j], -p.d);
+        *(uint4 *)(y + (size_t)px * p.C + c) = make_uint4(pack4(out[0], out[1], out[2], out[3]), pack4(out[4], out[5], out[6], out[7]),
+                                                         pack4(out[8], out[9], out[10], out[11]), pack4(out[12], out[13], out[14], out[15]));
+    }
+}
+
 hipError_t launch_pool(const int8_t *x, int8_t *y, int mode, int N, int H, int W, int C, int P, int Q, int k, int stride,
                        int pad, int fin, int fout, hipStream_t st)
 {
     PoolParams p{N, H, W, C, P, Q, k, stride, pad, mode, fout - fin};
+    if (mode == 0 && k == 3 && C % 16 == 0 && aligned(x, 16) && aligned(y, 16) &&
+        (long long)N * P * Q * (C / 16) < (1LL << 31) - 256LL * 16 * kBlock && (long long)N * P * Q * (C / 16) >= 16 * 1024) {
+        MaxPool3Params prm;
+        prm.p = p;
+        prm.cv = C / 16;
+        prm.total = (int)((long long)N * P * Q * prm.cv);
+        prm.div_cv = make_fastdiv(prm.cv);
+        prm.div_q = make_fastdiv(Q);
+        prm.div_p = make_fastdiv(P);
+        maxpool3_kernel<<<grid_for((size_t)prm.total), kBlock, 0, st>>>(x, y, prm);
+        return hipGetLastError();
+    }
     int vec = 16;
     while (vec > 1 && (C % vec || !aligned(x, vec) || !aligned(y, vec))) vec /= 4;
     // few outputs (a global pool): narrower lanes give the machine four times the wavefronts

@@ -242,6 +242,18 @@ def test_pool_q(B, mode):
             assert np.array_equal(host(y), orc.pool_q(x, mode, k, st, pad, f_in, f_out)), (N, H, W, C, k, st, pad, f_in, f_out)
 
 
+def test_max_pool_3x3_large(B):
+    """Enough outputs for the specialized 3x3 max-pool kernel: all-negative data (a window position in the
+    padding must never win), borders on every side, strides 1 and 2, every rescale direction."""
+    rng = np.random.default_rng(108)
+    for (N, H, W, C), (st, pad) in itertools.product([(8, 65, 67, 64), (3, 40, 41, 256)], [(2, 1), (1, 1), (2, 0), (1, 2), (3, 2)]):
+        for lo, hi in [(-128, 128), (-128, -100)]:
+            x = rng.integers(lo, hi, (N, H, W, C)).astype(np.int8)
+            for f_in, f_out in [(4, 4), (4, 2), (3, 5)]:
+                y = B.pool_q(dev(x), "max", 3, st, pad, f_in, f_out)
+                assert np.array_equal(host(y), orc.pool_q(x, "max", 3, st, pad, f_in, f_out)), (N, H, W, C, st, pad, f_in, f_out)
+
+
 def test_absmax_and_formats(B):
     rng = np.random.default_rng(107)
     for n in (1, 63, 64, 1000, 1 << 20):
