@@ -477,10 +477,58 @@ __global__ void __launch_bounds__(kBlock) maxpool3_kernel(const int8_t *__restri
     }
 }
 
+// Global average pooling (the window is the whole image, one output pixel): a lane sums 4 channels over
+// all H*W pixels, seven loads in flight at a time, bytes added straight out of the loaded words.
+template <int E>
+__device__ __forceinline__ int add_byte(int acc, uint32_t w)
+{
+    if constexpr (E == 0) asm("v_add_u32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(acc) : "v"(acc), "v"(w));
+    else if constexpr (E == 1) asm("v_add_u32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(acc) : "v"(acc), "v"(w));
+    else if constexpr (E == 2) asm("v_add_u32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(acc) : "v"(acc), "v"(w));
+    else asm("v_add_u32_sdwa %0, %1, sext(%2) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(acc) : "v"(acc), "v"(w));
+    return acc;
+}
+
+__global__ void __launch_bounds__(kBlock) avgpool_global_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y, int N, int pixels,
+                                                                 int C, int d)
+{
+    const int cw = C / 4;
+    const int i = blockIdx.x * kBlock + threadIdx.x;
+    if (i >= N * cw) return;
+    const int n = i / cw, c = (i - n * cw) * 4;
+    const uint32_t *src = (const uint32_t *)(x + (size_t)n * pixels * C + c);
+    const size_t step = (size_t)C / 4;            // words between consecutive pixels
+    int acc[4] = {0, 0, 0, 0};
+    int px = 0;
+    for (; px + 7 <= pixels; px += 7) {
+        uint32_t w[7];
+#pragma unroll
+        for (int j = 0; j < 7; j++) w[j] = src[(size_t)(px + j) * step];
+#pragma unroll
+        for (int j = 0; j < 7; j++) {
+            acc[0] = add_byte<0>(acc[0], w[j]); acc[1] = add_byte<1>(acc[1], w[j]);
+            acc[2] = add_byte<2>(acc[2], w[j]); acc[3] = add_byte<3>(acc[3], w[j]);
+        }
+    }
+    for (; px < pixels; px++) {
+        const uint32_t w = src[(size_t)px * step];
+        acc[0] = add_byte<0>(acc[0], w); acc[1] = add_byte<1>(acc[1], w);
+        acc[2] = add_byte<2>(acc[2], w); acc[3] = add_byte<3>(acc[3], w);
+    }
+    *(uint32_t *)(y + (size_t)n * C + c) = pack4(avg_round(acc[0], pixels, d), avg_round(acc[1], pixels, d),
+                                                 avg_round(acc[2], pixels, d), avg_round(acc[3], pixels, d));
+}
+
 hipError_t launch_pool(const int8_t *x, int8_t *y, int mode, int N, int H, int W, int C, int P, int Q, int k, int stride,
                        int pad, int fin, int fout, hipStream_t st)
 {
     PoolParams p{N, H, W, C, P, Q, k, stride, pad, mode, fout - fin};
+    if (mode == 1 && k == H && k == W && pad == 0 && C % 4 == 0 && aligned(x, 4) && aligned(y, 4) &&
+        (long long)N * (C / 4) < (1LL << 31) - kBlock) {
+        const int lanes = N * (C / 4);
+        avgpool_global_kernel<<<(lanes + kBlock - 1) / kBlock, kBlock, 0, st>>>(x, y, N, H * W, C, fout - fin);
+        return hipGetLastError();
+    }
     if (mode == 0 && k == 3 && C % 16 == 0 && aligned(x, 16) && aligned(y, 16) &&
         (long long)N * P * Q * (C / 16) < (1LL << 31) - 256LL * 16 * kBlock && (long long)N * P * Q * (C / 16) >= 16 * 1024) {
         MaxPool3Params prm;
