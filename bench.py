@@ -62,6 +62,56 @@ def cpu_baseline(net, batch_sample: int, calib_n: int):
                        f"{dt:.2f} s", images_per_s=batch_sample / dt)
 
 
+def bench_layers(args):
+    """The five dense layers of configs[1] on their own at the given batch: formats from the library's own
+    single-batch calibration of each layer, four rotating sets of input / output buffers (together larger
+    than the 256 MB last-level cache at batch 256), HIP events over 20 launches.  One JSON line."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    from paper_1805_07941_amd import binding as B
+
+    dev = "cuda:0"
+    rows = []
+    for i in range(5):
+        L = wl.config1_layer(i, batch=args.batch)
+        wf, bf = torch.from_numpy(L["w_float"]).to(dev), torch.from_numpy(L["b_float"]).to(dev)
+        f_in, pad = L["f_in"], L["pad"]
+        f_w = B.fmt_from_absmax_f32(float(B.absmax_f32(wf).cpu()[0]))
+        w, b = B.quantize(wf, f_w), B.quantize_i32(bf, f_in + f_w)
+        x0 = torch.from_numpy(L["x"]).to(dev)
+        _, acc = B.conv_q(x0[:8].contiguous(), w, b, f_in, f_w, 0, 1, pad, 1, True, want_y=False, want_acc=True)
+        f_out = B.fmt_from_absmax_i32(B.absmax_i32_value(B.absmax_i32(acc, relu=True)), f_in + f_w)
+        del acc
+        nset = 4
+        xs = [x0] + [x0.roll(k + 1, 0).contiguous() for k in range(nset - 1)]
+        N, H, W, C = x0.shape
+        K, R = w.shape[0], w.shape[1]
+        ys = [torch.empty((N, H, W, K), dtype=torch.int8, device=dev) for _ in range(nset)]
+        for k in range(3):
+            B.conv_q(xs[k % nset], w, b, f_in, f_w, f_out, 1, pad, 1, True, out=ys[k % nset])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        iters = 20
+        e0.record()
+        for k in range(iters):
+            B.conv_q(xs[k % nset], w, b, f_in, f_w, f_out, 1, pad, 1, True, out=ys[k % nset])
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        ops = 2.0 * N * H * W * K * R * R * C
+        by = x0.numel() + ys[0].numel() + w.numel() + 4 * K
+        t_roof = max(ops / (INT8_MFMA_PEAK_TOPS * 1e12), by / (HBM_PEAK_GBS * 1e9)) * 1e3
+        rows.append(dict(layer=L["name"], shape="%dx%dx%d -> %d, %dx%d" % (H, W, C, K, R, R),
+                         kernel=B.CONV_VARIANT_NAMES[B.conv_q_select(N, H, W, C, K, R, R, 1, pad, 1)], us=round(ms * 1e3, 1),
+                         tops=round(ops / ms / 1e9, 1), gbs=round(by / ms / 1e6, 1),
+                         pct_mfma_peak=round(100 * ops / ms / 1e9 / INT8_MFMA_PEAK_TOPS, 1),
+                         pct_hbm_peak=round(100 * by / ms / 1e6 / HBM_PEAK_GBS, 1), pct_roofline=round(100 * t_roof / ms, 1)))
+        del xs, ys, x0
+    print(json.dumps({"metric": "int8 conv TOPS per dense layer of configs[1], standalone, b=%d" % args.batch, "unit": "TOPS",
+                      "n_gpus": 1, "dtype": "int8", "data": "synthetic", "buffers": "4 rotating sets per layer", "layers": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -75,6 +125,8 @@ def main():
     ap.add_argument("--no-fuse", action="store_true", help="run every residual add as its own dfq_eltwise_q call")
     ap.add_argument("--per-channel", action="store_true",
                     help="one weight format per output channel (dfq_conv_q_pc) instead of one per layer")
+    ap.add_argument("--layers", action="store_true",
+                    help="instead of the network pass: time the five dense layers of configs[1] on their own at --batch")
     ap.add_argument("--no-mfma-rate", action="store_true", help="skip the register-only matrix-instruction rate probe")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three 256 MiB device copies (a kernel of known traffic, to scale HBM counters by)")
@@ -95,6 +147,9 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.layers:
+        bench_layers(args)
+        return
 
     net = wl.resnet50(batch=args.batch)
     x_host = net.input_float()
