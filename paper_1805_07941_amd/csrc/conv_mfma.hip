@@ -99,8 +99,16 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
         const int per = G / 8, rem = G % 8, xcd = lb % 8, idx = lb / 8;
         lb = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
     }
-    const int ntiles_mine = lb < prm.tiles ? (prm.tiles - lb + G - 1) / G : 0;
+    // The last, incomplete round of tiles: dealt by the raw workgroup id (round-robin over the XCDs) when
+    // there is a single channel tile, so that the extra tiles spread over all XCDs and CUs instead of
+    // falling on the first XCDs' contiguous runs (with several channel tiles the workgroup keeps its
+    // strided sequence, which keeps its channel tile).
+    const int last_round0 = prm.tiles / G * G;                       // first tile of the incomplete round
+    const bool deal_last = prm.tiles_c == 1;
+    const int ntiles_mine = deal_last ? prm.tiles / G + ((int)blockIdx.x < prm.tiles - last_round0 ? 1 : 0)
+                                      : (lb < prm.tiles ? (prm.tiles - lb + G - 1) / G : 0);
     const int nitems = ntiles_mine * nsteps;
+    const int last_tile = last_round0 + (int)blockIdx.x;             // this workgroup's tile of that round, if any
     // G is a multiple of the number of channel tiles, so the channel tile never changes
     const int k0 = (lb - fastdiv(lb, prm.div_tc) * prm.tiles_c) * BC;
 
@@ -235,7 +243,11 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
                 tr += wraps ? 1 : 0;
             }
         }
-        if (++p_step == nsteps) { p_step = 0; p_tile += G; }
+        if (++p_step == nsteps) {
+            p_step = 0;
+            p_tile += G;
+            if (deal_last && p_tile >= last_round0) p_tile = last_tile;
+        }
     };
 
     const int wp0 = (wave % WAVES_P) * WP;
@@ -369,6 +381,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
             reset_acc();
             c_step = 0;
             c_tile += G;
+            if (deal_last && c_tile >= last_round0) c_tile = last_tile;
         }
     };
     // Item i multiplies step i in KK = 2 k-steps of 32 bytes.  Two register sets alternate: while
