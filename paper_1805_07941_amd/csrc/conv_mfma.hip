@@ -99,16 +99,20 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
         const int per = G / 8, rem = G % 8, xcd = lb % 8, idx = lb / 8;
         lb = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
     }
-    // The last, incomplete round of tiles: dealt by the raw workgroup id (round-robin over the XCDs) when
-    // there is a single channel tile, so that the extra tiles spread over all XCDs and CUs instead of
-    // falling on the first XCDs' contiguous runs (with several channel tiles the workgroup keeps its
-    // strided sequence, which keeps its channel tile).
+    // The last, incomplete round of tiles is dealt round-robin over the XCDs instead of following the
+    // contiguous runs (which would put all extra tiles on the first XCDs): extra tile number j goes to
+    // the workgroup with raw id b = 8 * idx + xcd where j = (idx / tc) * 8 * tc + xcd * tc + idx % tc
+    // (tc = channel tiles): consecutive j cycle through the channel tiles, then the XCDs, and j has the
+    // workgroup's own channel tile.  Needs G to be a multiple of 8 * tc; otherwise the strided sequence
+    // lb, lb + G, ... is kept for the last round too.
     const int last_round0 = prm.tiles / G * G;                       // first tile of the incomplete round
-    const bool deal_last = prm.tiles_c == 1;
-    const int ntiles_mine = deal_last ? prm.tiles / G + ((int)blockIdx.x < prm.tiles - last_round0 ? 1 : 0)
+    const bool deal_last = G % (8 * prm.tiles_c) == 0;
+    const int my_extra = ((int)blockIdx.x / 8 / prm.tiles_c) * 8 * prm.tiles_c + ((int)blockIdx.x % 8) * prm.tiles_c +
+                         ((int)blockIdx.x / 8) % prm.tiles_c;
+    const int ntiles_mine = deal_last ? prm.tiles / G + (my_extra < prm.tiles - last_round0 ? 1 : 0)
                                       : (lb < prm.tiles ? (prm.tiles - lb + G - 1) / G : 0);
     const int nitems = ntiles_mine * nsteps;
-    const int last_tile = last_round0 + (int)blockIdx.x;             // this workgroup's tile of that round, if any
+    const int last_tile = last_round0 + my_extra;                    // this workgroup's tile of that round, if any
     // G is a multiple of the number of channel tiles, so the channel tile never changes
     const int k0 = (lb - fastdiv(lb, prm.div_tc) * prm.tiles_c) * BC;
 
