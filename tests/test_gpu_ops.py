@@ -120,6 +120,12 @@ CONV_SHAPES = [
     (2, 14, 14, 256, 1024, 1, 1, 1, 0, 1),
     (1, 3, 3, 64, 256, 1, 1, 1, 0, 1),           # fewer pixels than one tile
     (1, 9, 9, 512, 128, 1, 1, 1, 0, 1),          # C too large for it: general dense kernel
+    # 3x3 stride 1 pad 1 with whole channel chunks on degenerate images
+    (2, 9, 7, 128, 128, 3, 3, 1, 1, 1),          # image rows much shorter than a tile
+    (5, 3, 1, 64, 64, 3, 3, 1, 1, 1),            # one column: every pixel is at both borders
+    (3, 1, 5, 64, 128, 3, 3, 1, 1, 1),           # one row: kernel rows 0 and 2 are all padding
+    (1, 37, 29, 256, 256, 3, 3, 1, 1, 1),        # ragged last tile, four channel chunks
+    (2, 30, 33, 192, 384, 3, 3, 1, 1, 1),        # three chunks, three channel tiles
     # K a multiple of 256 and enough pixels for 192 tiles of 256 x 256: the dense kernel's largest tile shape
     (4, 111, 112, 16, 256, 3, 3, 1, 1, 1),       # C % 64 != 0, ragged last pixel tile
     (2, 112, 111, 64, 512, 1, 1, 1, 0, 1),       # two channel tiles, 1x1
