@@ -494,7 +494,11 @@ hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st)
 {
     if (a.frac_w) {
         // the per-channel epilogue holds more registers: at most two wavefronts per SIMD
-        if (a.K % 128 == 0) return launch_pw<256, 128, 4, 2, 1, true>(a, st);
+        if (a.K % 128 == 0) {
+            // (two workgroups per CU only while both sets of per-channel tables fit)
+            if (a.add && a.C <= 128 && 2 * pw_lds_bytes<128, 128, 2, 2>(a) <= (size_t)kLdsBytes) return launch_pw<128, 128, 2, 2, 2, true>(a, st);
+            return launch_pw<256, 128, 4, 2, 1, true>(a, st);
+        }
         if (a.C <= 128) return launch_pw<256, 64, 4, 1, 2, true>(a, st);
         return launch_pw<256, 64, 4, 1, 1, true>(a, st);
     }
