@@ -95,6 +95,51 @@ def test_config1_layers_full_size_sampled(G, i, batch):
     assert gy.min() >= 0 and gy.max() <= 127
 
 
+@pytest.mark.parametrize("i", [1, 3, 4])
+def test_config1_layers_full_size_per_channel_sampled(G, i):
+    """The full-size layers (batch 256, the benchmark's launch configuration) with one weight format per output
+    channel: sampled accumulators and outputs against the oracle's single-element routines, two whole images."""
+    B, _ = G
+    L = wl.config1_layer(i, batch=256)
+    wf, bf = L["w_float"], L["b_float"]
+    K = wf.shape[0]
+    f_wk = np.array([orc.frac_from_absmax_f32(orc.absmax_f32(wf[k])) for k in range(K)], np.int32)
+    w = np.stack([orc.quantize(wf[k], int(f_wk[k])) for k in range(K)])
+    b = np.array([orc.quantize_i32(bf[k:k + 1], L["f_in"] + int(f_wk[k]))[0] for k in range(K)], np.int32)
+    x = L["x"]
+    N, H, W, C = x.shape
+    f_out = L["f_in"] + int(f_wk.min()) - 7
+    gy, gacc = B.conv_q_pc(dev(x), dev(w), dev(b), L["f_in"], dev(f_wk), f_out, 1, L["pad"], 1, True, want_acc=True)
+    gy2, _ = B.conv_q_pc(dev(x), dev(w), dev(b), L["f_in"], dev(f_wk), f_out, 1, L["pad"], 1, True)      # the lean kernel
+    gy, gy2, gacc = host(gy), host(gy2), host(gacc)
+    assert np.array_equal(gy, gy2)
+    rng = np.random.default_rng(2000 + i)
+    pts = [(0, 0, 0, 0), (N - 1, H - 1, W - 1, K - 1)]
+    pts += [tuple(int(v) for v in (rng.integers(N), rng.integers(H), rng.integers(W), rng.integers(K))) for _ in range(300)]
+    for (n, p, q, k) in pts:
+        a = orc.conv_acc_at(x, w, b, 1, L["pad"], 1, n, p, q, k)
+        assert int(gacc[n, p, q, k]) == a, (n, p, q, k)
+        assert int(gy[n, p, q, k]) == orc.requant8(max(a, 0), L["f_in"] + int(f_wk[k]) - f_out), (n, p, q, k)
+    for n in (0, N - 1):
+        y_ref, _ = orc.conv_q(x[n:n + 1], w, b, L["f_in"], f_wk, f_out, 1, L["pad"], 1, True)
+        assert np.array_equal(gy[n:n + 1], y_ref)
+
+
+def test_histogram_at_full_size(G):
+    """The histogram of Algorithm 1 on a tensor of the benchmark's largest size (205 M accumulators)."""
+    B, _ = G
+    g = torch.Generator(device=DEV)
+    g.manual_seed(7)
+    x = (torch.randn(256 * 56 * 56 * 256, device=DEV, generator=g) * 30000).to(torch.int32)
+    xh = host(x)
+    counts, j, m = orc.hist_i32(xh, relu=True)
+    gm = B.absmax_i32_value(B.absmax_i32(x, relu=True))
+    assert gm == m
+    h = host(B.hist_i32(x, j, relu=True)).view(np.uint32)
+    assert np.array_equal(h[:len(counts)].astype(np.uint64), counts) and int(h.astype(np.uint64).sum()) == x.numel()
+    assert B.threshold_search(h, j, m)[0] == orc.threshold_search(counts, j, m)[0]
+
+
 def _compare_calibration(net, qz_o, t_o, qz_g, t_g):
     assert qz_g.frac == qz_o.frac
     assert qz_g.w_frac.keys() == qz_o.w_frac.keys()
