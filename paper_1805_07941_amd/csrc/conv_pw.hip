@@ -499,7 +499,7 @@ hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st)
             if (a.add && a.C <= 128 && 2 * pw_lds_bytes<128, 128, 2, 2>(a) <= (size_t)kLdsBytes) return launch_pw<128, 128, 2, 2, 2, true>(a, st);
             return launch_pw<256, 128, 4, 2, 1, true>(a, st);
         }
-        if (a.C <= 128) return launch_pw<256, 64, 4, 1, 2, true>(a, st);
+        if (a.C <= 128 && 2 * pw_lds_bytes<256, 64, 4, 1>(a) <= (size_t)kLdsBytes) return launch_pw<256, 64, 4, 1, 2, true>(a, st);
         return launch_pw<256, 64, 4, 1, 1, true>(a, st);
     }
     // as many workgroups per compute unit as the two input buffers leave room for
@@ -510,7 +510,7 @@ hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st)
         if (a.add && a.C <= 128) return launch_pw<128, 128, 2, 2, 2>(a, st);
         return launch_pw<256, 128, 4, 2, 1>(a, st);
     }
-    if (a.C <= 128) return launch_pw<256, 64, 4, 1, 2>(a, st);
+    if (a.C <= 128 && 2 * pw_lds_bytes<256, 64, 4, 1>(a) <= (size_t)kLdsBytes) return launch_pw<256, 64, 4, 1, 2>(a, st);
     return launch_pw<256, 64, 4, 1, 1>(a, st);
 }
 

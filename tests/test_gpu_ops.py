@@ -119,6 +119,7 @@ CONV_SHAPES = [
     (1, 16, 16, 192, 192, 1, 1, 1, 0, 1),
     (2, 14, 14, 256, 1024, 1, 1, 1, 0, 1),
     (1, 3, 3, 64, 256, 1, 1, 1, 0, 1),           # fewer pixels than one tile
+    (1, 10, 10, 128, 1088, 1, 1, 1, 0, 1),       # K a multiple of 64 only and large: one workgroup per CU for LDS
     (1, 9, 9, 512, 128, 1, 1, 1, 0, 1),          # C too large for it: general dense kernel
     # 3x3 stride 1 pad 1 with whole channel chunks on degenerate images
     (2, 9, 7, 128, 128, 3, 3, 1, 1, 1),          # image rows much shorter than a tile
