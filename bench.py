@@ -45,19 +45,19 @@ def node_bytes(net, nd):
     return H * W * C + P * Q * K
 
 
-def cpu_baseline(net, batch_sample: int, calib_n: int):
+def cpu_baseline(net, batch_sample: int, calib_n: int, per_channel: bool = False):
     """The oracle as it stands, on the host cores: inference of `batch_sample` images."""
     import oracle as orc
     import oracle.net as onet
     x = net.input_float()
-    qz, _ = onet.calibrate(net, x[:calib_n])
+    qz, _ = onet.calibrate(net, x[:calib_n], per_channel=per_channel)
     xs = x[:batch_sample]
     t0 = time.perf_counter()
     t = onet.infer(net, qz, xs)
-    onet.logits(net, qz, t)
+    ref_logits = onet.logits(net, qz, t)
     dt = time.perf_counter() - t0
     macs = net.macs_per_image() * batch_sample
-    return dict(value=2 * macs / dt / 1e12, unit="TOPS", cores=orc.num_threads(), kind="oracle",
+    return ref_logits, dict(value=2 * macs / dt / 1e12, unit="TOPS", cores=orc.num_threads(), kind="oracle",
                 sample=f"inference of {batch_sample} of the {net.batch} images (same network, same formats rule), "
                        f"{dt:.2f} s", images_per_s=batch_sample / dt)
 
@@ -298,9 +298,18 @@ def main():
                                         frac=round(cls["hbm"]["roof_ms"] / max(cls["hbm"]["ms"], 1e-9), 4))},
                         mfma_rate_measured=mfma_rate)
 
-    cpu = None
+    # ---- outside the timed region: the oracle on a bounded sample of the same images, as the CPU baseline and
+    # as the check of what was timed - the logits the timed plan produced for those images must equal the
+    # oracle's exactly (the oracle calibrates for itself, so formats, weights and every layer are covered)
+    cpu, parity_checked = None, None
     if args.cpu_sample > 0:
-        cpu = cpu_baseline(net, min(args.cpu_sample, args.batch), min(args.calib, args.batch))
+        import numpy as np
+        n_cpu = min(args.cpu_sample, args.batch)
+        ref_logits, cpu = cpu_baseline(net, n_cpu, min(args.calib, args.batch), per_channel=args.per_channel)
+        gpu_logits = step().cpu().numpy()[:n_cpu]
+        equal = int(sum(bool(np.array_equal(gpu_logits[i], ref_logits[i])) for i in range(n_cpu)))
+        parity_checked = dict(images=n_cpu, images_with_identical_logits=equal, tolerance=0,
+                              what="float logits of the timed plan (same launch path) against the CPU oracle's")
 
     line = {
         "metric": "int8 conv TOPS (2*MAC/s), whole quantized ResNet-50-shaped pass, b=%d" % args.batch,
@@ -318,9 +327,13 @@ def main():
         "pct_int8_mfma_peak": round(100 * tops / INT8_MFMA_PEAK_TOPS, 2),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "parity_checked": parity_checked,
         "mfma_layers": per_layer,
     }
     print(json.dumps(line))
+    if parity_checked is not None and parity_checked["images_with_identical_logits"] != parity_checked["images"]:
+        print("bench.py: the timed plan's logits differ from the oracle's", file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

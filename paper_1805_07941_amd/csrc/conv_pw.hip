@@ -53,8 +53,8 @@ __device__ __forceinline__ void wait_loads_plus2(int ca, int cb)
 
 // FUSE: an element-wise add (Eq. 10) follows the convolution and is taken in the epilogue: the
 // second operand's 16 codes per lane and tile are fetched into registers one unit ahead, at the
-// start of the previous unit's epilogue, so that even with one item per unit the whole epilogue
-// (a few microseconds of vector work) lies between the fetch and its use.
+// start of the previous unit's epilogue, and awaited at that epilogue's end, so that the whole
+// epilogue (a few microseconds of vector work) covers the fetch.
 // PC: one weight format per output channel, every channel's shift within [0, 23]: shift, clamp bound
 // and rounding constant of all K channels sit in LDS behind the bias.
 template <int BP, int BC, int WAVES_P, int WAVES_C, bool FUSE, int OCC, bool PC = false>
@@ -249,8 +249,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
     };
     auto ring_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
-    // ep_hist: bit k set when item i-1-k ended a unit (its epilogue issued kStoresPerUnit stores
-    // and, with FUSE, ahead of them as many loads of the next unit's second operand)
+    // ep_hist: bit k set when item i-1-k ended a unit (its epilogue issued kStoresPerUnit stores)
     constexpr int kStoresPerUnit = CT * PT;
     constexpr unsigned kHistMask = (1u << (NSTAGES - 1)) - 1u;
     unsigned ep_hist = 0;
@@ -258,10 +257,11 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
     const unsigned lane_aoff = (unsigned)((wp0 + l32) * a.ldadd + wc0 + 16 * lh);
     static_assert(!FUSE || CT * PT == 4, "the fused form handles four tiles per wavefront");
     v4i other[4], other_next[4];      // FUSE: the second operand of the current unit / of the one after it
-    int refill_ops = 0;               // vector-memory operations the refill of this item issued
     int units_left = nunits;          // units not yet written out
-    auto fetch_other = [&](int pt, int ct) __attribute__((always_inline)) {
-        const unsigned tile_off = (unsigned)(pt * BP * a.ldadd + ct * BC);
+    // `live` false: every lane gets an offset past the buffer (zeros arrive, nothing is read), so that the
+    // fetch needs no branch of its own.
+    auto fetch_other = [&](int pt, int ct, bool live) __attribute__((always_inline)) {
+        const unsigned tile_off = live ? (unsigned)(pt * BP * a.ldadd + ct * BC) : kOutOfRange;
 #pragma unroll
         for (int c = 0; c < CT; c++)
 #pragma unroll
@@ -273,19 +273,17 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
         if (++c_step == nsteps) {
             const unsigned tile_off = (unsigned)(c_pt * BP * a.ldy + c_ct * BC);
             if (FUSE) {
-                // this unit's second operand was fetched at the start of the previous unit's epilogue (or
-                // ahead of the loop); that epilogue's stores and this item's refill are younger for certain
-                constexpr int S = kStoresPerUnit;
-                if (refill_ops >= WS + XS) wait_loads_for<WS + XS + S>(other_next[0], other_next[1], other_next[2], other_next[3]);
-                else if (refill_ops >= XS) wait_loads_for<XS + S>(other_next[0], other_next[1], other_next[2], other_next[3]);
-                else if (refill_ops >= WS) wait_loads_for<WS + S>(other_next[0], other_next[1], other_next[2], other_next[3]);
-                else wait_loads_for<S>(other_next[0], other_next[1], other_next[2], other_next[3]);
+                // The second operand of this unit is complete in other_next: its loads were awaited at the end of
+                // the previous unit's epilogue (or ahead of the loop).  The loads of the next unit's are issued here
+                // and awaited at the end of this epilogue, behind its stores - both inside this one block of
+                // straight-line code: the registers are written behind the compiler's back, so a register copy or
+                // a spill between a load and its wait (as register allocation inserts them where values cross
+                // loop boundaries) would read them too early.
 #pragma unroll
                 for (int t = 0; t < 4; t++) other[t] = other_next[t];
-                if (--units_left > 0) {
-                    const bool wrap = c_ct + 1 == prm.tiles_c;
-                    fetch_other(wrap ? c_pt + 1 : c_pt, wrap ? 0 : c_ct + 1);
-                }
+                --units_left;
+                const bool wrap = c_ct + 1 == prm.tiles_c;
+                fetch_other(wrap ? c_pt + 1 : c_pt, wrap ? 0 : c_ct + 1, units_left > 0);
             }
             if constexpr (PC) {
 #pragma unroll
@@ -322,6 +320,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
                         else store_piece(requant_tile_lane_fast(acc[c][p], rq), off, yrsrc);
                     }
             }
+            if (FUSE) wait_loads_for<kStoresPerUnit>(other_next[0], other_next[1], other_next[2], other_next[3]);
             ep_hist |= 1u;
             c_step = 0;
             if (++c_ct == prm.tiles_c) {
@@ -347,11 +346,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
         __builtin_amdgcn_sched_barrier(0);
         mfma_half(f1);
         __builtin_amdgcn_sched_barrier(0);
-        refill_ops = 0;
-        if (decltype(refill)::value) {
-            refill_ops = (w_active ? WS : 0) + (p_loadx ? XS : 0);
-            issue(stage);
-        }
+        if (decltype(refill)::value) issue(stage);
         if (decltype(has_next)::value) {
             read_half(f1, 1, next);
             advance_reader();
@@ -362,18 +357,22 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
 
     // Vector-memory operations younger than the loads of item i+1 when item i waits for them:
     // the weight loads of items i+2 .. i+NSTAGES-1, the input loads of those of them that fetch
-    // input (p_hist), and the stores - with FUSE also the second-operand loads behind them - of
-    // the epilogues of items i+1-NSTAGES .. i-1 (ep_hist; an item refills before its epilogue).
+    // input (p_hist), and the stores of the epilogues of items i+1-NSTAGES .. i-1 (ep_hist; an
+    // item refills before its epilogue; with FUSE an epilogue's second-operand loads precede its
+    // stores and are complete when it ends).
     // Loads and stores complete in issue order; operations that are not counted only make the
     // wait longer.
     auto steady_wait = [&]() __attribute__((always_inline)) {
         const int cx = __builtin_popcount(p_hist & ((1u << (NSTAGES - 2)) - 1u));
-        const int ce = __builtin_popcount(ep_hist) * (FUSE ? 2 : 1);
+        const int ce = __builtin_popcount(ep_hist);
         if (w_active) wait_loads_plus2<(NSTAGES - 2) * WS, XS, kStoresPerUnit>(cx, ce);
         else wait_loads_plus2<0, XS, kStoresPerUnit>(cx, ce);
     };
-    if (FUSE && nitems > 0) fetch_other(c_pt, c_ct);
     if (nitems > 0) {
+        if (FUSE) {
+            fetch_other(c_pt, c_ct, true);
+            wait_loads_for<0>(other_next[0], other_next[1], other_next[2], other_next[3]);
+        }
         wait_loads<0>();
         ring_barrier();
         read_half(f0, 0, 0);

@@ -174,6 +174,7 @@ class Plan:
         P, Q, K = net.shapes[net.output_name]
         self.logits = torch.empty((batch, P * Q * K), dtype=torch.float32, device=device)
         self._calls, self._calls_key, self._graph, self._keep = None, None, None, None
+        self._fused_ran = None                   # after the call list is built: results of convolutions that ran fused
 
     def _pointwise_geometry(self, nd) -> bool:
         H, W, Cc = self.net.shapes[nd.srcs[0]]
@@ -243,6 +244,16 @@ class Plan:
             for s in nd.srcs:
                 if last.get(s) == idx and s in owner and s != net.input_name and s != net.output_name:
                     free.append(owner[s])
+
+    def resident(self):
+        """Names of the tensors whose buffer still holds them after a pass (with pooled buffers a dead
+        tensor's storage is handed to a later one; a fused convolution's own result is never stored)."""
+        skip = {self.net.nodes[i].dst for i in self.fused} if self._fused_ran is None else self._fused_ran
+        last_at: Dict[int, str] = {}
+        for name, tns in self.buf.items():          # insertion order = execution order
+            if name not in skip:
+                last_at[tns.data_ptr()] = name
+        return [n for n in self.buf if n not in skip and last_at[self.buf[n].data_ptr()] == n]
 
     # ---- execution -------------------------------------------------------------------- #
     def _build_calls(self, x: torch.Tensor):
@@ -333,6 +344,7 @@ class Plan:
         calls.append((L.dfq_dequantize, (out.data_ptr(), self.logits.data_ptr(), out.numel(), f(qz.frac[net.output_name]))))
         names.append(None)
         self._keep = keep
+        self._fused_ran = {net.nodes[i].dst for i, j in self.fused.items() if j in fused_adds}
         self.call_nodes = names
         return calls
 

@@ -185,7 +185,7 @@ def test_config3_and_4_networks(G, which):
     _compare_calibration(net, qz_o, t_o, qz_g, t_g)
     del t_g
     plan = gnet.Plan(net, qz_g, batch)
-    logits = host(plan.run(dev(x)))
+    logits = host(plan.run(dev(x))).copy()
     assert logits.shape == (batch, 1000) and np.isfinite(logits).all()
     for i in (1, batch - 1):
         t = onet.infer(net, qz_o, x[i:i + 1])
@@ -197,6 +197,48 @@ def test_config3_and_4_networks(G, which):
     plan2 = gnet.Plan(net, qz_g, batch, keep_all=False)
     assert np.array_equal(host(plan2.run(dev(x))), logits)
     assert np.abs(logits).max() > 0
+    del plan, plan2
+    _check_benchmark_plan(gnet, net, qz_g, qz_o, x, logits, batch)
+
+
+def _check_benchmark_plan(gnet, net, qz_g, qz_o, x, logits_unfused, batch, min_fused=0):
+    """The plan exactly as bench.py builds and times it - pooled buffers, joins fused into the convolutions in front of
+    them, replayed from a HIP graph, at the full batch: logits of the whole batch against the unfused plan's (when
+    given), and for three images the logits and every tensor still resident after the pass against the oracle."""
+    xd = dev(x)
+    plan = gnet.Plan(net, qz_g, batch, keep_all=False, fuse=True)
+    for rep in range(2):                                  # the capture run and one replay
+        got = host(plan.run_graph(xd)).copy()
+        if logits_unfused is not None:
+            assert np.array_equal(got, logits_unfused), rep
+    n_fused = sum(1 for fn, _ in plan._calls if fn.__name__ in ("dfq_conv_q_add", "dfq_conv_q_pc_add"))
+    assert n_fused >= min_fused, n_fused
+    names = plan.resident()
+    assert net.output_name in names
+    for i in (0, batch // 2 + 1, batch - 1):
+        t = onet.infer(net, qz_o, x[i:i + 1])
+        assert np.array_equal(got[i:i + 1], onet.logits(net, qz_o, t)), i          # absolute tolerance 0
+        for name in names:
+            if name != net.input_name or not net.input_is_int8:
+                assert np.array_equal(host(plan.buf[name][i:i + 1]), t[name]), (i, name)
+    return n_fused
+
+
+def test_resnet50_benchmark_plan_per_channel_full_batch(G):
+    """bench.py --per-channel: the ResNet-50-shaped network at batch 256 with one weight format per output channel,
+    pooled buffers, fused joins, graph replay."""
+    B, gnet = G
+    net = wl.resnet50(batch=256)
+    x = net.input_float()
+    calib = x[:2]
+    qz_o, t_o = onet.calibrate(net, calib, per_channel=True)
+    qz_g, t_g = gnet.calibrate(net, dev(calib), per_channel=True, keep_tensors=False)
+    assert qz_g.frac == qz_o.frac
+    for name in qz_o.w:
+        assert np.array_equal(host(qz_g.w[name]), qz_o.w[name]) and np.array_equal(host(qz_g.b[name]), qz_o.b[name]), name
+        assert np.array_equal(np.asarray(qz_g.w_frac[name]), np.asarray(qz_o.w_frac[name])), name
+    del t_o, t_g
+    _check_benchmark_plan(gnet, net, qz_g, qz_o, x, None, 256, min_fused=4)
 
 
 @pytest.mark.parametrize("which", ["mobilenet_v1", "resnet50"])

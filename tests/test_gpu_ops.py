@@ -396,3 +396,144 @@ def test_histogram_and_threshold_search(B):
             h = host(B.hist_i32(dev(x), j, relu=relu)).view(np.uint32)
             assert np.array_equal(h[:len(counts)].astype(np.uint64), counts) and int(h[len(counts):].sum()) == 0
             assert B.threshold_search(h, j, m)[0] == orc.threshold_search(counts, j, m)[0]
+
+
+# ---------------------------------------------------------------------------------------- #
+# The fused convolution + add at the sizes the benchmark launches it with: many more units
+# than workgroups, so every workgroup walks a run of units (second operand fetched one unit
+# ahead, input buffers handed over between pixel tiles, stores of earlier epilogues in flight).
+def _scaled_pointwise_case(rng, N, H, C, K):
+    """int8 tensors of a 1x1 layer whose accumulators have a standard deviation near 2^9 * sqrt(C),
+    so that a shift of s = 10 + log2(C)/2 - 3 leaves most outputs unsaturated."""
+    x = np.clip(np.rint(rng.standard_normal((N, H, H, C), dtype=np.float32) * 16), -128, 127).astype(np.int8)
+    w = np.clip(np.rint(rng.standard_normal((K, 1, 1, C), dtype=np.float32) * 32), -128, 127).astype(np.int8)
+    b = rng.integers(-2 ** 12, 2 ** 12, (K,)).astype(np.int32)
+    other = np.clip(np.rint(rng.standard_normal((N, H, H, K), dtype=np.float32) * 40), -128, 127).astype(np.int8)
+    s = 4 + int(round(np.log2(C) / 2))            # accumulator std ~ 16 * 32 * sqrt(C) = 2^(9 + log2(C)/2) -> codes of std ~ 32
+    return x, w, b, other, s
+
+
+@pytest.mark.parametrize("per_channel", [False, True], ids=["per_layer", "per_channel"])
+@pytest.mark.parametrize("shape", [(56, 64, 256), (28, 128, 512), (14, 256, 1024)], ids=lambda s: "x".join(map(str, s)))
+def test_conv_q_add_full_size_sampled(B, shape, per_channel):
+    """dfq_conv_q_add / dfq_conv_q_pc_add at batch 256 (the benchmark's launch configuration): 400 sampled outputs
+    through the oracle's single-element convolution, its rounding and its add; two whole images; and the whole
+    tensor against the library's own unfused pair of calls."""
+    H, C, K = shape
+    N = 256
+    rng = np.random.default_rng(5000 + H)
+    x, w, b, other, s = _scaled_pointwise_case(rng, N, H, C, K)
+    f_in, f_mid, f_other, f_out, relu_mid, relu_out = 4, 3, 4, 3, False, True
+    if per_channel:
+        f_w = (f_mid - f_in + s + rng.integers(-1, 2, K)).astype(np.int32)      # shifts s-1 .. s+1 by channel
+        shifts = f_in + f_w - f_mid
+    else:
+        f_w = f_mid - f_in + s
+        shifts = np.full(K, s)
+    xd, wd, bd, od = dev(x), dev(w), dev(b), dev(other)
+    if per_channel:
+        fwd = dev(f_w)
+        rngw = (int(f_w.min()), int(f_w.max()))
+        got = B.conv_q_pc_add(xd, wd, bd, od, f_in, fwd, rngw, f_mid, relu_mid, f_other, f_out, relu_out)
+        if got is None:
+            # the per-channel tables of this layer do not fit LDS beside the input buffers: the caller's two calls
+            assert (C, K) == (256, 1024)
+            mid_g, _ = B.conv_q_pc(xd, wd, bd, f_in, fwd, f_mid, 1, 0, 1, relu_mid, frac_w_range=rngw)
+            got, _ = B.eltwise_q(mid_g, f_mid, od, f_other, f_out, relu_out)
+        else:
+            mid_g, _ = B.conv_q_pc(xd, wd, bd, f_in, fwd, f_mid, 1, 0, 1, relu_mid, frac_w_range=rngw)
+            two, _ = B.eltwise_q(mid_g, f_mid, od, f_other, f_out, relu_out)
+            assert torch.equal(got, two)
+    else:
+        got = B.conv_q_add(xd, wd, bd, od, f_in, f_w, f_mid, relu_mid, f_other, f_out, relu_out)
+        assert got is not None
+        mid_g, _ = B.conv_q(xd, wd, bd, f_in, f_w, f_mid, 1, 0, 1, relu_mid)
+        two, _ = B.eltwise_q(mid_g, f_mid, od, f_other, f_out, relu_out)
+        assert torch.equal(got, two)
+    got = host(got)
+    pts = [(0, 0, 0, 0), (N - 1, H - 1, H - 1, K - 1), (N - 1, 0, H - 1, 0), (0, H - 1, 0, K - 1)]
+    pts += [tuple(int(v) for v in (rng.integers(N), rng.integers(H), rng.integers(H), rng.integers(K))) for _ in range(400)]
+    mids = np.array([orc.requant8(orc.conv_acc_at(x, w, b, 1, 0, 1, n, p, q, k), int(shifts[k])) for (n, p, q, k) in pts], np.int8)
+    oth = np.array([other[pt] for pt in pts], np.int8)
+    ref, _ = orc.eltwise_q(mids, f_mid, oth, f_other, f_out, relu_out)
+    assert np.array_equal(np.array([got[pt] for pt in pts], np.int8), ref)
+    assert np.abs(mids).max() > 16 and (np.abs(mids) == 127).mean() < 0.1        # the rounding is exercised, not the clamp
+    for n in (0, N - 1):
+        mid, _ = orc.conv_q(x[n:n + 1], w, b, f_in, f_w, f_mid, 1, 0, 1, relu_mid)
+        ref, _ = orc.eltwise_q(mid, f_mid, other[n:n + 1], f_other, f_out, relu_out)
+        assert np.array_equal(got[n:n + 1], ref), n
+
+
+def _ties_bias(rng, K, s):
+    """Bias values that are exact ties or near-ties of a rounding shift by s, with quotients inside [-127, 127]."""
+    t = rng.integers(-120, 121, K).astype(np.int64)
+    half = (1 << (s - 1)) if s > 0 else 0
+    kind = rng.integers(0, 4, K)
+    off = np.where(kind == 0, half, np.where(kind == 1, half - 1, np.where(kind == 2, half + 1, rng.integers(0, max(1 << s, 1), K))))
+    v = t * (1 << s) + off
+    return np.clip(v, -2 ** 31 + 2 ** 24, 2 ** 31 - 2 ** 24).astype(np.int32)
+
+
+@pytest.mark.parametrize("s", [0, 1, 2, 14, 21, 22, 23, 24])
+def test_lean_epilogue_shift_edges(B, s):
+    """The four-instruction rounding of the matrix-core kernels over the whole range it is declared for (shift 0 .. 23)
+    and the hand-over to the general rounding at 24, on layers that take the lean epilogue (whole channel tiles, aligned
+    rows, no accumulator dump).  The accumulators are dominated by a bias built from ties and near-ties of the shift,
+    so the results are spread over [-127, 127] instead of saturating."""
+    rng = np.random.default_rng(600 + s)
+    cases = [(2, 20, 20, 64, 128, 3, 1, 1, B.CONV_MFMA), (2, 20, 20, 64, 64, 3, 1, 1, B.CONV_MFMA),
+             (1, 24, 24, 128, 256, 1, 1, 0, B.CONV_MFMA), (2, 33, 31, 64, 256, 1, 1, 0, B.CONV_POINTWISE),
+             (1, 40, 40, 256, 128, 1, 1, 0, B.CONV_POINTWISE), (2, 30, 30, 128, 64, 1, 1, 0, B.CONV_POINTWISE)]
+    for (N, H, W, C, K, R, st, pad, variant) in cases:
+        x = rng.integers(-3, 4, (N, H, W, C)).astype(np.int8)
+        w = rng.integers(-3, 4, (K, R, R, C)).astype(np.int8)
+        b = _ties_bias(rng, K, s)
+        f_in, f_w = 6, 12
+        f_out = f_in + f_w - s
+        for relu in (False, True):
+            ref, _ = orc.conv_q(x, w, b, f_in, f_w, f_out, st, pad, 1, relu)
+            if variant == B.CONV_POINTWISE and s > 23:
+                with pytest.raises(B.DfqError):
+                    B.conv_q(dev(x), dev(w), dev(b), f_in, f_w, f_out, st, pad, 1, relu, variant=variant)
+                continue
+            y, _ = B.conv_q(dev(x), dev(w), dev(b), f_in, f_w, f_out, st, pad, 1, relu, variant=variant)
+            assert np.array_equal(host(y), ref), (N, H, W, C, K, R, s, relu)
+            y, _ = B.conv_q(dev(x), dev(w), dev(b), f_in, f_w, f_out, st, pad, 1, relu)
+            assert np.array_equal(host(y), ref), (N, H, W, C, K, R, s, relu, "auto")
+            assert (np.abs(ref) == 127).mean() < 0.5
+        # one weight format per output channel with shifts from 0 (or s - 3) up to s
+        lo = max(0, s - 3)
+        sk = rng.integers(lo, s + 1, K)
+        sk[:2] = (lo, s)
+        f_wk = (f_out - f_in + sk).astype(np.int32)
+        bk = np.array([_ties_bias(rng, 1, int(v))[0] for v in sk], np.int32)
+        ref, _ = orc.conv_q(x, w, bk, f_in, f_wk, f_out, st, pad, 1, True)
+        y, _ = B.conv_q_pc(dev(x), dev(w), dev(bk), f_in, dev(f_wk), f_out, st, pad, 1, True,
+                           frac_w_range=(int(f_wk.min()), int(f_wk.max())))
+        assert np.array_equal(host(y), ref), (N, H, W, C, K, R, s, "per channel")
+
+
+@pytest.mark.parametrize("sa,sb,add_shift", [(22, 0, 23), (0, 22, 23), (21, 0, 22), (0, 21, 23), (0, 0, 23), (1, 0, 0), (0, 1, 1)])
+def test_fused_add_alignment_and_shift_edges(B, sa, sb, add_shift):
+    """dfq_conv_q_add / dfq_conv_q_pc_add with the alignment shifts of Eq. 10 at their largest (21, 22) and the final
+    rounding shift at the end of the lean range (23): against the oracle's convolution followed by its add."""
+    rng = np.random.default_rng(700 + 31 * sa + 7 * sb + add_shift)
+    N, H, W, C, K = 2, 21, 19, 128, 256
+    x, w, b, other, s = _scaled_pointwise_case(rng, N, H, C, K)
+    x = x[:, :, :W].copy(); other = other[:, :, :W].copy()
+    F = 22                                   # the finer of the two scales
+    f_mid, f_other, f_out = F - sa, F - sb, F - add_shift
+    f_in = 4
+    f_w = f_mid - f_in + s
+    xd, wd, bd, od = dev(x), dev(w), dev(b), dev(other)
+    for relu_mid, relu_out in [(False, True), (True, False)]:
+        mid, _ = orc.conv_q(x, w, b, f_in, f_w, f_mid, 1, 0, 1, relu_mid)
+        ref, _ = orc.eltwise_q(mid, f_mid, other, f_other, f_out, relu_out)
+        got = B.conv_q_add(xd, wd, bd, od, f_in, f_w, f_mid, relu_mid, f_other, f_out, relu_out)
+        assert got is not None and np.array_equal(host(got), ref), (sa, sb, add_shift, relu_mid, relu_out)
+        f_wk = (f_w + rng.integers(-2, 3, K)).astype(np.int32)
+        mid, _ = orc.conv_q(x, w, b, f_in, f_wk, f_mid, 1, 0, 1, relu_mid)
+        ref, _ = orc.eltwise_q(mid, f_mid, other, f_other, f_out, relu_out)
+        got = B.conv_q_pc_add(xd, wd, bd, od, f_in, dev(f_wk), (int(f_wk.min()), int(f_wk.max())), f_mid, relu_mid, f_other,
+                              f_out, relu_out)
+        assert got is not None and np.array_equal(host(got), ref), (sa, sb, add_shift, relu_mid, relu_out, "per channel")
