@@ -140,6 +140,7 @@ def main():
     import workloads as wl
     from paper_1805_07941_amd import binding as B
     from paper_1805_07941_amd import net as gnet
+    from paper_1805_07941_amd import probe
 
     B.lib()
     if not torch.cuda.is_available():
@@ -234,9 +235,9 @@ def main():
                      "network_data = weights and input activations of a 3x3 layer of the pass"}
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         for label, a_t, b_t in sets:
-            B.mfma_rate_probe(a_t, b_t, sink, 2048, 2000)          # warm-up: clocks settle under this load
+            probe.mfma_rate(a_t, b_t, sink, 2048, 2000)          # warm-up: clocks settle under this load
             e0.record()
-            ops_probe = B.mfma_rate_probe(a_t, b_t, sink, 2048, 8000)
+            ops_probe = probe.mfma_rate(a_t, b_t, sink, 2048, 8000)
             e1.record()
             torch.cuda.synchronize()
             mfma_rate[label] = round(ops_probe / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)

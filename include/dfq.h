@@ -218,12 +218,16 @@ dfq_status dfq_absmax_i32_channels(const int32_t *x, size_t pixels, int K, int r
  * dfq_hist_i32: hist_dev[b] = number of elements with (|x| >> shift) == b, DFQ_HIST_BINS DEVICE
  * words, overwritten; the caller picks shift as the smallest with (max|x| >> shift) <
  * DFQ_HIST_BINS (larger magnitudes would be counted in the last bin).  n < 2^32.
- * dfq_threshold_search: host, pure, double precision, sums in bin order.  hist: HOST copy of the
+ * dfq_threshold_search: host, pure, double precision, sums in bin order, fixed-size storage on the
+ * stack (about 17 KB; no allocation).  hist: HOST copy of the
  * first nbins = (max_abs >> shift) + 1 words.  Candidates are the edges i = 129 .. nbins (with
  * fewer bins nothing is clipped); the first candidate with the smallest measure wins.
  * *gamma_out: the threshold in the units of x (0 for an all-zero tensor); *delta_out (may be
  * NULL): its measure.  DFQ_ESHAPE if nbins does not match max_abs and shift. */
 #define DFQ_HIST_BINS 2048
+/* The bin width the histogram of a tensor with this maximum takes: the smallest shift with
+ * (max_abs >> shift) < DFQ_HIST_BINS.  Host, pure; -1 for a negative max_abs. */
+int dfq_hist_shift(int64_t max_abs);
 dfq_status dfq_hist_i32(const int32_t *x, size_t n, int relu, int shift, uint32_t *hist_dev, dfq_stream stream);
 dfq_status dfq_threshold_search(const uint32_t *hist, int nbins, int shift, int64_t max_abs, int64_t *gamma_out,
                                 double *delta_out);
@@ -235,6 +239,14 @@ dfq_status dfq_fmt_from_absmax_f32(float gamma, dfq_fmt *out);
 /* Integer form for accumulators held at acc_frac: the largest frac <= acc_frac (rescale factor
  * in (0, 1], Sec. 3) with m * 2^(frac - acc_frac) <= 127, floored at -32.  Host, pure. */
 dfq_status dfq_fmt_from_absmax_i32(int64_t m, int32_t acc_frac, dfq_fmt *out);
+/* The output format of a layer whose weights have one format per output channel (Sec. 3): channel k's
+ * accumulators are at frac_in + frac_w[k], and the layer's int8 output gets the finest format that holds
+ * every channel's threshold m[k] with a rescale factor in (0, 1] - the smallest of the per-channel results
+ * of dfq_fmt_from_absmax_i32(m[k], frac_in + frac_w[k]).  m (as dfq_absmax_i32_channels leaves it, copied
+ * to the host) and frac_w: HOST arrays of K entries.  Host, pure.  DFQ_EFMT for an entry of frac_w outside
+ * [-32, 32]. */
+dfq_status dfq_fmt_from_absmax_i32_channels(const uint32_t *m, int K, int32_t frac_in, const int32_t *frac_w,
+                                            dfq_fmt *out);
 
 /* ---- closed forms of Sec. 2 (host, pure; return -1 on invalid arguments) ----------------- */
 int64_t dfq_beta_max(int n, int p);                                        /* Eq. 5, equality case */
@@ -242,18 +254,6 @@ int     dfq_mac_acc_bits(int64_t N, int64_t bx, int64_t ex, int64_t by, int64_t 
 int64_t dfq_mac_max_len(int q, int64_t bx, int64_t ex, int64_t by, int64_t ey);        /* Eq. 9 */
 int     dfq_add_acc_bits(int64_t N, int64_t bx, int64_t ex);                            /* Eq. 12 */
 int64_t dfq_add_max_len(int q, int64_t bx, int64_t ex);                                 /* Eq. 13 */
-
-/* ---- measurement aid (no operation of the paper): rate of the int8 matrix instruction of the
- * dense convolution kernels on caller-supplied operand bytes, in a loop that touches registers
- * only.  The sustained rate depends on the operand values (the chip's power limit), so this is
- * the ceiling a convolution on such data could reach with free operand delivery.
- * a_codes: DEVICE, 16-byte aligned, at least 16 KiB read; b_codes: DEVICE, 16-byte aligned, at
- * least 32 KiB read; sink: DEVICE, blocks * 512 words, overwritten (content meaningless).
- * 1 <= blocks <= 65536 workgroups of eight wavefronts, 1 <= iters <= 2^24 rounds of eight
- * instructions per wavefront.  *ops_out (host, may be NULL) receives the number of operations
- * (2 per multiply-add) the launch performs; the caller times the launch on `stream`. */
-dfq_status dfq_mfma_rate_probe(const int8_t *a_codes, const int8_t *b_codes, int32_t *sink, int blocks,
-                               int iters, double *ops_out, dfq_stream stream);
 
 #ifdef __cplusplus
 }

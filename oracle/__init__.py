@@ -284,6 +284,20 @@ def hist_i32(x, relu=False):
     return counts, j, m
 
 
+def _clipped_and_requantized(cdf, i, levels):
+    """Algorithm 1's two reference curves for the candidate that keeps the first i bins.
+    r: the distribution function with all mass from bin i-1 on moved into bin i-1 (clipping at edge i).
+    q: r as an 8-bit format over the clipped range [0, 1] can hold it - sampled at the format's levels,
+    then brought back onto the bin grid by linear interpolation; beyond the kept bins q is r."""
+    r = cdf.copy()
+    r[i - 1:] = 1.0
+    bins_on_unit_range = np.linspace(0.0, 1.0, i)
+    r_at_levels = np.interp(levels, bins_on_unit_range, r[:i])
+    q = r.copy()
+    q[:i] = np.interp(bins_on_unit_range, levels, r_at_levels)
+    return r, q
+
+
 def threshold_search(counts, j, m):
     """Algorithm 1 on a histogram: returns (gamma, delta), gamma an integer threshold in the units of x.
     Candidates clip at bin edges i = 129 .. nb; a histogram with fewer bins than that is not clipped."""
@@ -292,21 +306,12 @@ def threshold_search(counts, j, m):
     total = counts.sum()
     if total == 0 or m == 0:
         return 0, 0.0
-    pdf = counts / total
-    cdf = np.cumsum(pdf)
-    codes = np.arange(N_CODES, dtype=np.float64) / float(N_CODES - 1)        # fpspace(0, 1, 8, 7)
-    delta, gamma = np.inf, m                                                   # bin_edges[-1]: nothing clipped
+    cdf = np.cumsum(counts / total)
+    levels = np.arange(N_CODES, dtype=np.float64) / float(N_CODES - 1)       # the non-negative 8-bit codes on [0, 1]
+    gamma, delta = m, None                                                     # no candidate: nothing is clipped
     for i in range(N_CODES + 1, nb + 1):
-        r = cdf.copy()
-        r[i - 1:] = 1.0
-        grid = np.linspace(0.0, 1.0, i)
-        r_interp = np.interp(codes, grid, r[:i])
-        q_interp = np.interp(grid, codes, r_interp)
-        q = r.copy()
-        q[:i] = q_interp
-        d = float(np.cumsum(np.abs(cdf - q))[-1])           # summed in bin order
-        if delta > d:
-            delta, gamma = d, min(i * (1 << j) - 1, m)
-    if delta == np.inf:
-        delta = 0.0
-    return int(gamma), float(delta)
+        _, q = _clipped_and_requantized(cdf, i, levels)
+        d = float(np.cumsum(np.abs(cdf - q))[-1])                              # the measure, summed in bin order
+        if delta is None or delta > d:
+            gamma, delta = min(i * (1 << j) - 1, m), d
+    return int(gamma), float(0.0 if delta is None else delta)

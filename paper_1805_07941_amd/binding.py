@@ -24,7 +24,7 @@ CONV_VARIANT_NAMES = {CONV_AUTO: "auto", CONV_DIRECT: "direct", CONV_MFMA: "mfma
 EXPORTS = [
     "dfq_status_string", "dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q",
     "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_hist_i32", "dfq_threshold_search", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
-    "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_mfma_rate_probe",
+    "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_hist_shift", "dfq_fmt_from_absmax_i32_channels",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
 ]
 
@@ -82,10 +82,12 @@ def lib():
     L.dfq_absmax_i32.argtypes = [vp, sz, i32, vp, vp]
     L.dfq_fmt_from_absmax_f32.argtypes = [C.c_float, C.POINTER(Fmt)]
     L.dfq_fmt_from_absmax_i32.argtypes = [i64, C.c_int32, C.POINTER(Fmt)]
-    L.dfq_mfma_rate_probe.argtypes = [vp, vp, vp, i32, i32, C.POINTER(C.c_double), vp]
+    L.dfq_fmt_from_absmax_i32_channels.argtypes = [vp, i32, C.c_int32, vp, C.POINTER(Fmt)]
+    L.dfq_hist_shift.argtypes = [i64]
+    L.dfq_hist_shift.restype = i32
     for name in ("dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q", "dfq_conv_q_variant",
                  "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q", "dfq_absmax_f32",
-                 "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_mfma_rate_probe",
+                 "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_fmt_from_absmax_i32_channels",
                  "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_absmax_f32_rows", "dfq_quantize_rows",
                  "dfq_quantize_i32_rows", "dfq_hist_i32", "dfq_threshold_search"):
         getattr(L, name).restype = i32
@@ -336,22 +338,6 @@ def absmax_i32(x: torch.Tensor, relu: bool = False, out_dev: Optional[torch.Tens
     return out
 
 
-def mfma_rate_probe(a_codes: torch.Tensor, b_codes: torch.Tensor, sink: torch.Tensor, blocks: int, iters: int,
-                    stream=None) -> float:
-    """Launches the register-only matrix-instruction loop on operand bytes taken from ``a_codes`` (first
-    16 KiB) and ``b_codes`` (first 32 KiB); returns the number of operations of the launch.  The caller
-    times it."""
-    _dev(a_codes, torch.int8, "a_codes")
-    _dev(b_codes, torch.int8, "b_codes")
-    _dev(sink, torch.int32, "sink")
-    if a_codes.numel() < 16384 or b_codes.numel() < 32768 or sink.numel() < blocks * 512:
-        raise ValueError("mfma_rate_probe: a_codes >= 16 KiB, b_codes >= 32 KiB, sink >= blocks * 512 words")
-    ops = C.c_double(0.0)
-    _check(lib().dfq_mfma_rate_probe(_ptr(a_codes), _ptr(b_codes), _ptr(sink), int(blocks), int(iters), C.byref(ops),
-                                     _stream(stream)), "dfq_mfma_rate_probe")
-    return ops.value
-
-
 def absmax_f32_rows(x: torch.Tensor, stream=None) -> torch.Tensor:
     """max |.| of every row of a float32 [rows, ...] tensor: float32 device tensor [rows] (no synchronization)."""
     _dev(x, torch.float32, "x")
@@ -403,9 +389,9 @@ HIST_BINS = 2048
 
 def hist_shift(max_abs: int) -> int:
     """The smallest shift with (max_abs >> shift) < HIST_BINS."""
-    j = 0
-    while (int(max_abs) >> j) >= HIST_BINS:
-        j += 1
+    j = int(lib().dfq_hist_shift(int(max_abs)))
+    if j < 0:
+        raise DfqError(EINVAL, "dfq_hist_shift")
     return j
 
 
@@ -442,6 +428,21 @@ def fmt_from_absmax_f32(gamma: float) -> int:
 def fmt_from_absmax_i32(m: int, acc_frac: int) -> int:
     f = Fmt()
     _check(lib().dfq_fmt_from_absmax_i32(int(m), int(acc_frac), C.byref(f)), "dfq_fmt_from_absmax_i32")
+    return int(f.frac)
+
+
+def fmt_from_absmax_i32_channels(m_host, f_in: int, frac_w_host) -> int:
+    """Output format of a layer with one weight format per output channel from the per-channel thresholds
+    (numpy uint32 [K], as ``absmax_i32_channels_value`` returns them) and the per-channel weight formats
+    (numpy int32 [K])."""
+    import numpy as np
+    m = np.ascontiguousarray(m_host, np.uint32)
+    fw = np.ascontiguousarray(frac_w_host, np.int32)
+    if m.shape != fw.shape or m.ndim != 1:
+        raise DfqError(ESHAPE, "fmt_from_absmax_i32_channels (one threshold and one format per channel)")
+    f = Fmt()
+    _check(lib().dfq_fmt_from_absmax_i32_channels(m.ctypes.data_as(C.c_void_p), int(m.shape[0]), int(f_in),
+                                                  fw.ctypes.data_as(C.c_void_p), C.byref(f)), "dfq_fmt_from_absmax_i32_channels")
     return int(f.frac)
 
 

@@ -1,4 +1,4 @@
-"""Builds libdfq.so (HIP kernels + C-ABI) for gfx950, in-tree, with hipcc.
+"""Builds libdfq.so (HIP kernels + C-ABI) and libdfq_probe.so (a benchmark aid) for gfx950, in-tree, with hipcc.
 
 ``python -m paper_1805_07941_amd.build`` or ``build()``; no GPU is needed to compile.
 """
@@ -15,6 +15,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libdfq.so")
+PROBE_SRC = os.path.join(HERE, "probe", "mfma_rate_probe.hip")   # measurement aid, a library of its own
+PROBE_LIB = os.path.join(HERE, "libdfq_probe.so")
 OBJ = os.path.join(HERE, "_build")
 
 # -packed-fp32-ops off: packed FP32 forms are not to be generated on these machines.
@@ -38,8 +40,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     """Compiles every source and links libdfq.so.  With force=False, only when a source or
     header is newer than the library."""
     srcs = sources()
-    deps = srcs + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(INCLUDE, "*.h"))
-    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
+    deps = srcs + [PROBE_SRC] + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(INCLUDE, "*.h"))
+    if not force and os.path.exists(LIB) and os.path.exists(PROBE_LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
     os.makedirs(OBJ, exist_ok=True)
     hipcc = _hipcc()
@@ -55,12 +57,13 @@ def build(force: bool = True, verbose: bool = False) -> str:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        objs = list(ex.map(compile_one, srcs))
-    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs,
-                       capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stderr)
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs) + 1)) as ex:
+        objs = list(ex.map(compile_one, srcs + [PROBE_SRC]))
+    for lib, parts in ((LIB, objs[:-1]), (PROBE_LIB, objs[-1:])):
+        r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + parts,
+                           capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stderr)
     return LIB
 
 

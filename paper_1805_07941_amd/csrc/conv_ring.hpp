@@ -47,7 +47,10 @@ __device__ __forceinline__ void store_piece(uint4 d, unsigned voffset, __amdgpu_
 
 // 16-byte load into registers through a buffer resource, outside the compiler's wait-count
 // bookkeeping like the LDS loads: the data may be used only behind wait_loads_for<N>() on the same
-// registers.  A lane whose offset is outside the buffer gets zeros.
+// registers, and that wait must follow in the SAME block of straight-line code - the compiler
+// believes the registers are written at once, so any register copy or spill it places between the
+// load and the wait (loop boundaries, merges of branches) would read them too early.  A lane whose
+// offset is outside the buffer gets zeros.
 __device__ __forceinline__ void load_piece_to_regs(v4i &dst, unsigned voffset, v4i rsrc)
 {
     asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=&v"(dst) : "v"(voffset), "s"(rsrc) : "memory");

@@ -409,6 +409,7 @@ bool conv_smallc_supports(const ConvArgs &a)
 {
     if (a.groups != 1) return false;
     if (a.S * a.C > 32) return false;
+    if ((size_t)a.R * (a.K > 32 ? 64 : 32) * 32 > 64 * 1024) return false;   // the packed weights of a channel tile live in LDS
     if (a.W * a.C < 32) return false;                       // clamped border loads need a row of >= 16 bytes
     if ((long long)a.N * a.P * a.Q >= (1LL << 31) - 512) return false;
     if (a.acc_out && ((uintptr_t)a.acc_out & 15)) return false;

@@ -3,7 +3,6 @@
 #include "dfq.h"
 
 #include <cmath>
-#include <vector>
 
 #include "dfq_host.hpp"
 
@@ -347,69 +346,80 @@ dfq_status dfq_hist_i32(const int32_t *x, size_t n, int relu, int shift, uint32_
     return from_hip(launch_hist_i32(x, n, relu ? 1 : 0, shift, hist_dev, (hipStream_t)stream));
 }
 
-// Algorithm 1 on a histogram.  All arithmetic in double, every sum in index order.
+int dfq_hist_shift(int64_t max_abs)
+{
+    if (max_abs < 0) return -1;
+    int j = 0;
+    while ((max_abs >> j) >= DFQ_HIST_BINS) j++;
+    return j;
+}
+
+// Algorithm 1 on a histogram.  All arithmetic in double, every sum in index order, fixed-size storage.
+//
+// A candidate clips at bin edge i (i bins kept).  Its clipped distribution function r has r[t] = cdf[t] for
+// t < i-1 and 1 from bin i-1 on.  The 8-bit format offers the 128 levels k/127 of the clipped range [0, 1]; on the
+// bin grid t/(i-1) the quantized distribution function q is r sampled at the levels and linearly interpolated back
+// to the grid.  Both interpolations walk two increasing sequences, so each is one merge pass.  The candidate's
+// distance is the area between cdf and q over the kept bins plus the area between cdf and 1 over the clipped ones,
+// added up in bin order.
 dfq_status dfq_threshold_search(const uint32_t *hist, int nbins, int shift, int64_t max_abs, int64_t *gamma_out,
                                 double *delta_out)
 {
-    constexpr int kCodes = 128;                // non-negative codes of the 8-bit format
-    if (!hist || !gamma_out || nbins < 1 || nbins > 2048 || shift < 0 || shift > 31 || max_abs < 0) return DFQ_EINVAL;
+    constexpr int kLevels = 128;               // non-negative codes of the 8-bit format
+    if (!hist || !gamma_out || nbins < 1 || nbins > DFQ_HIST_BINS || shift < 0 || shift > 31 || max_abs < 0) return DFQ_EINVAL;
     if ((max_abs >> shift) != nbins - 1) return DFQ_ESHAPE;    // the last bin is the one that holds the maximum
     double total = 0.0;
     for (int t = 0; t < nbins; t++) total += (double)hist[t];
-    int64_t gamma = max_abs;                    // nothing clipped
-    double delta = 0.0;
-    if (total > 0.0 && max_abs > 0) {
-        std::vector<double> cdf(nbins), r(nbins), grid(nbins), q(nbins), codes(kCodes), r_at_code(kCodes);
-        double run = 0.0;
-        for (int t = 0; t < nbins; t++) {
-            run += (double)hist[t] / total;
-            cdf[t] = run;
+    if (!(total > 0.0) || max_abs == 0) {
+        *gamma_out = 0;
+        if (delta_out) *delta_out = 0.0;
+        return DFQ_OK;
+    }
+    double cdf[DFQ_HIST_BINS];
+    double at_level[kLevels];                  // the clipped distribution function sampled at level k/127
+    double run = 0.0;
+    for (int t = 0; t < nbins; t++) {
+        run += (double)hist[t] / total;
+        cdf[t] = run;
+    }
+    int64_t gamma = max_abs;                   // fewer bins than 129: nothing is clipped
+    double best = 0.0;
+    bool have = false;
+    for (int i = kLevels + 1; i <= nbins; i++) {
+        const int last = i - 1;                // index of the bin that receives the clipped mass; grid point t is t / last
+        auto r = [&](int t) { return t < last ? cdf[t] : 1.0; };
+        auto grid = [&](int t) { return t == last ? 1.0 : (double)t * (1.0 / (double)last); };
+        // sample r at the levels: level k lies in grid segment [seg, seg + 1]
+        int seg = 0;
+        for (int k = 0; k < kLevels; k++) {
+            const double lv = (double)k / (double)(kLevels - 1);
+            while (seg + 1 < i && grid(seg + 1) <= lv) seg++;
+            if (seg == last || grid(seg) == lv) at_level[k] = r(seg);
+            else at_level[k] = (r(seg + 1) - r(seg)) / (grid(seg + 1) - grid(seg)) * (lv - grid(seg)) + r(seg);
         }
-        for (int k = 0; k < kCodes; k++) codes[k] = (double)k / (double)(kCodes - 1);
-        // linear interpolation of (xp, fp) at x, xp increasing, x within [xp[0], xp[np-1]]; `at` remembers the
-        // segment of the previous (smaller) x
-        auto interp = [](double x, const double *xp, const double *fp, int np, int &at) {
-            while (at + 1 < np && xp[at + 1] <= x) at++;
-            if (at == np - 1 || xp[at] == x) return fp[at];
-            const double slope = (fp[at + 1] - fp[at]) / (xp[at + 1] - xp[at]);
-            return slope * (x - xp[at]) + fp[at];
-        };
-        bool found = false;
-        for (int i = kCodes + 1; i <= nbins; i++) {
-            // distribution function with everything from bin i-1 on moved into bin i-1 (clipped at edge i)
-            for (int t = 0; t < nbins; t++) r[t] = t < i - 1 ? cdf[t] : 1.0;
-            const double step = 1.0 / (double)(i - 1);
-            for (int t = 0; t < i; t++) grid[t] = (double)t * step;
-            grid[i - 1] = 1.0;
-            int at = 0;
-            for (int k = 0; k < kCodes; k++) r_at_code[k] = interp(codes[k], grid.data(), r.data(), i, at);
-            at = 0;
-            for (int t = 0; t < i; t++) q[t] = interp(grid[t], codes.data(), r_at_code.data(), kCodes, at);
-            double d = 0.0;
-            for (int t = 0; t < nbins; t++) d += std::fabs(cdf[t] - (t < i ? q[t] : r[t]));
-            if (!found || delta > d) {
-                found = true;
-                delta = d;
-                const int64_t edge = ((int64_t)i << shift) - 1;
-                gamma = edge < max_abs ? edge : max_abs;
-            }
+        // back to the grid and the distance over the kept bins
+        double d = 0.0;
+        int k = 0;
+        for (int t = 0; t < i; t++) {
+            const double g = grid(t);
+            while (k + 1 < kLevels && (double)(k + 1) / (double)(kLevels - 1) <= g) k++;
+            const double lk = (double)k / (double)(kLevels - 1);
+            double q;
+            if (k == kLevels - 1 || lk == g) q = at_level[k];
+            else q = (at_level[k + 1] - at_level[k]) / ((double)(k + 1) / (double)(kLevels - 1) - lk) * (g - lk) + at_level[k];
+            d += std::fabs(cdf[t] - q);
         }
-    } else {
-        gamma = 0;
+        for (int t = i; t < nbins; t++) d += std::fabs(cdf[t] - 1.0);
+        if (!have || best > d) {
+            have = true;
+            best = d;
+            const int64_t edge = ((int64_t)i << shift) - 1;
+            gamma = edge < max_abs ? edge : max_abs;
+        }
     }
     *gamma_out = gamma;
-    if (delta_out) *delta_out = delta;
+    if (delta_out) *delta_out = best;
     return DFQ_OK;
-}
-
-dfq_status dfq_mfma_rate_probe(const int8_t *a_codes, const int8_t *b_codes, int32_t *sink, int blocks, int iters,
-                               double *ops_out, dfq_stream stream)
-{
-    if (!a_codes || !b_codes || !sink) return DFQ_EINVAL;
-    if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 24)) return DFQ_EINVAL;
-    if (((uintptr_t)a_codes & 15) || ((uintptr_t)b_codes & 15) || ((uintptr_t)sink & 3)) return DFQ_EINVAL;
-    if (ops_out) *ops_out = mfma_rate_probe_ops(blocks, iters);
-    return from_hip(launch_mfma_rate_probe(a_codes, b_codes, sink, blocks, iters, (hipStream_t)stream));
 }
 
 dfq_status dfq_fmt_from_absmax_f32(float gamma, dfq_fmt *out)
@@ -435,6 +445,22 @@ dfq_status dfq_fmt_from_absmax_i32(int64_t m, int32_t acc_frac, dfq_fmt *out)
         f--;
     }
     if (f < -32) f = -32;
+    out->bits = 8;
+    out->frac = f;
+    return DFQ_OK;
+}
+
+dfq_status dfq_fmt_from_absmax_i32_channels(const uint32_t *m, int K, int32_t frac_in, const int32_t *frac_w, dfq_fmt *out)
+{
+    if (!m || !frac_w || !out || K < 1) return DFQ_EINVAL;
+    int f = 32;
+    for (int k = 0; k < K; k++) {
+        if (frac_w[k] < -32 || frac_w[k] > 32) return DFQ_EFMT;
+        dfq_fmt fk;
+        const dfq_status st = dfq_fmt_from_absmax_i32((int64_t)m[k], frac_in + frac_w[k], &fk);
+        if (st != DFQ_OK) return st;
+        if (fk.frac < f) f = fk.frac;
+    }
     out->bits = 8;
     out->frac = f;
     return DFQ_OK;

@@ -66,10 +66,4 @@ hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st);
 bool conv_smallc_supports(const ConvArgs &a);
 hipError_t launch_conv_smallc(const ConvArgs &a, hipStream_t st);
 
-size_t mfma_rate_probe_a_bytes();
-size_t mfma_rate_probe_b_bytes();
-size_t mfma_rate_probe_sink_words(int blocks);
-double mfma_rate_probe_ops(int blocks, int iters);
-hipError_t launch_mfma_rate_probe(const int8_t *a, const int8_t *b, int32_t *sink, int blocks, int iters, hipStream_t st);
-
 }  // namespace dfq

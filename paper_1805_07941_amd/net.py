@@ -94,7 +94,7 @@ def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True, 
                                          want_y=False, want_acc=True, frac_w_range=(int(f_wk.min()), int(f_wk.max())))
                     m = B.absmax_i32_channels_value(B.absmax_i32_channels(acc, relu=nd.relu))
                     del acc
-                    qz.frac[nd.dst] = min(B.fmt_from_absmax_i32(int(m[k]), f_in + int(f_wk[k])) for k in range(len(m)))
+                    qz.frac[nd.dst] = B.fmt_from_absmax_i32_channels(m, f_in, f_wk)
                 t[nd.dst], _ = B.conv_q_pc(t[src], w, b, f_in, fw_dev, qz.frac[nd.dst], nd.stride, nd.pad, nd.groups, nd.relu,
                                            frac_w_range=(int(f_wk.min()), int(f_wk.max())))
                 if not keep_tensors:

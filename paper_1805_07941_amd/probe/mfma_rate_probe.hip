@@ -4,12 +4,17 @@
 // word per lane is stored at the end so the work cannot be discarded.  The rate a chip sustains
 // depends on the operand values (switching activity under its power limit), so this gives the
 // ceiling a convolution on the same data could reach if operand delivery were free.
-#include "conv_epilogue.hpp"
-#include "dfq_host.hpp"
+//
+// Built into a library of its own (libdfq_probe.so, include/dfq_probe.h); libdfq.so does not contain it.
+#include "dfq_probe.h"
 
-namespace dfq {
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
 namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kProbeThreads = 512;    // eight wavefronts: two per SIMD
 constexpr int kProbeA = 2, kProbeB = 4;
@@ -47,18 +52,14 @@ __global__ void __launch_bounds__(kProbeThreads, 1) mfma_rate_probe_kernel(const
 
 }  // namespace
 
-size_t mfma_rate_probe_a_bytes() { return (size_t)kProbeA * kProbeThreads * 16; }
-size_t mfma_rate_probe_b_bytes() { return (size_t)kProbeB * kProbeThreads * 16; }
-size_t mfma_rate_probe_sink_words(int blocks) { return (size_t)blocks * kProbeThreads; }
-double mfma_rate_probe_ops(int blocks, int iters)
+extern "C" int dfq_probe_mfma_rate(const int8_t *a_codes, const int8_t *b_codes, int32_t *sink, int blocks, int iters,
+                                   double *ops_out, void *stream)
 {
-    return (double)blocks * (kProbeThreads / 64) * (double)iters * (kProbeA * kProbeB) * (2.0 * 32 * 32 * 32);
+    if (!a_codes || !b_codes || !sink) return 1;
+    if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 24)) return 1;
+    if (((uintptr_t)a_codes & 15) || ((uintptr_t)b_codes & 15) || ((uintptr_t)sink & 3)) return 1;
+    if (ops_out) *ops_out = (double)blocks * (kProbeThreads / 64) * (double)iters * (kProbeA * kProbeB) * (2.0 * 32 * 32 * 32);
+    mfma_rate_probe_kernel<<<(unsigned)blocks, kProbeThreads, 0, (hipStream_t)stream>>>((const v4i *)a_codes, (const v4i *)b_codes,
+                                                                                          sink, iters);
+    return hipGetLastError() == hipSuccess ? 0 : 5;
 }
-
-hipError_t launch_mfma_rate_probe(const int8_t *a, const int8_t *b, int32_t *sink, int blocks, int iters, hipStream_t st)
-{
-    mfma_rate_probe_kernel<<<(unsigned)blocks, kProbeThreads, 0, st>>>((const v4i *)a, (const v4i *)b, sink, iters);
-    return hipGetLastError();
-}
-
-}  // namespace dfq

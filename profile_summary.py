@@ -1,7 +1,7 @@
 """Turns rocprofv3 CSV output into the short text summaries kept under profiles/.
 
-    python -m paper_1805_07941_amd.profile_summary stats <..._kernel_stats.csv> <..._kernel_trace.csv> <out.txt> --cmd "<command>"
-    python -m paper_1805_07941_amd.profile_summary traffic <fetch_counter_collection.csv> <write_counter_collection.csv>
+    python profile_summary.py stats <..._kernel_stats.csv> <..._kernel_trace.csv> <out.txt> --cmd "<command>"
+    python profile_summary.py traffic <fetch_counter_collection.csv> <write_counter_collection.csv>
            <out.txt> --cmd "<command>" [--launches-per-step 53] [--copy-bytes 268435456]
 
 `stats`: per-kernel call count and durations of the whole run, and the kernels of the last full

@@ -23,15 +23,32 @@ def B():
     return binding
 
 
-def test_library_exports_every_declared_symbol(B):
-    text = open(HEADER).read()
+def _declared(header):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = sorted(set(re.findall(r"\b(dfq_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(dfq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(B):
+    declared = _declared(HEADER)
     assert len(declared) >= 19
     L = C.CDLL(B.LIB_PATH)
     for name in declared:
         assert hasattr(L, name), f"{name} declared in dfq.h but not exported"
     assert sorted(B.EXPORTS) == declared
+    # every header under include/ is covered: the only other one declares the benchmark aid of libdfq_probe.so
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["dfq.h", "dfq_probe.h"]
+    from paper_1805_07941_amd import probe
+    declared_p = _declared(os.path.join(ROOT, "include", "dfq_probe.h"))
+    LP = C.CDLL(probe.LIB_PATH)
+    for name in declared_p:
+        assert hasattr(LP, name), f"{name} declared in dfq_probe.h but not exported"
+        assert not hasattr(L, name), f"{name} is a measurement aid and must stay out of libdfq.so"
+    assert sorted(probe.EXPORTS) == declared_p
+    P = probe.lib()
+    assert P.dfq_probe_mfma_rate(None, 1 << 20, 2 << 20, 1, 1, None, None) == 1
+    assert P.dfq_probe_mfma_rate(1 << 20, 2 << 20, 3 << 20, 0, 1, None, None) == 1              # no workgroups
+    assert P.dfq_probe_mfma_rate(1 << 20, (2 << 20) + 4, 3 << 20, 1, 1, None, None) == 1        # alignment
 
 
 def test_status_strings(B):
@@ -66,6 +83,23 @@ def test_format_from_thresholds(B):
     assert g(127 * 128, 11) == 4 and g(127 * 128 + 1, 11) == 3 and g(1, 40) == 32 and g(2 ** 31, -20) == -32
     with pytest.raises(B.DfqError):
         g(-1, 0)
+    # one weight format per output channel: the smallest of the per-channel results
+    import oracle as orc
+    rng = np.random.default_rng(17)
+    for K in (1, 7, 64):
+        m = rng.integers(0, 2 ** 31, K).astype(np.uint32)
+        m[0] = 0
+        fw = rng.integers(-3, 12, K).astype(np.int32)
+        for f_in in (-2, 4, 9):
+            want = min(orc.frac_from_absmax_i32(int(m[k]), f_in + int(fw[k])) for k in range(K))
+            assert B.fmt_from_absmax_i32_channels(m, f_in, fw) == want
+    assert B.fmt_from_absmax_i32_channels(np.array([127, 128], np.uint32), 4, np.array([7, 7], np.int32)) == 10
+    assert B.fmt_from_absmax_i32_channels(np.array([127, 128], np.uint32), 4, np.array([7, 9], np.int32)) == 11
+    with pytest.raises(B.DfqError):
+        B.fmt_from_absmax_i32_channels(np.array([1], np.uint32), 0, np.array([40], np.int32))
+    # bin width of the histogram of Algorithm 1
+    assert [B.hist_shift(v) for v in (0, 2047, 2048, 4095, 4096, 2 ** 31)] == [0, 0, 1, 1, 2, 21]
+    assert B.lib().dfq_hist_shift(-1) == -1
 
 
 def _conv(B, **kw):
@@ -122,9 +156,6 @@ def test_other_calls_reject_bad_arguments(B):
     assert L.dfq_absmax_i32(None, 4, 0, 1 << 20, None) == B.EINVAL
     assert L.dfq_hist_i32(1 << 20, 4, 0, 32, 2 << 20, None) == B.EINVAL                               # shift
     assert L.dfq_hist_i32(1 << 20, 4, 0, 3, None, None) == B.EINVAL
-    assert L.dfq_mfma_rate_probe(None, 1 << 20, 2 << 20, 1, 1, None, None) == B.EINVAL
-    assert L.dfq_mfma_rate_probe(1 << 20, 2 << 20, 3 << 20, 0, 1, None, None) == B.EINVAL              # no workgroups
-    assert L.dfq_mfma_rate_probe(1 << 20, (2 << 20) + 4, 3 << 20, 1, 1, None, None) == B.EINVAL        # alignment
 
 
 def test_kernel_selection(B):
@@ -161,6 +192,16 @@ def test_threshold_search_is_host_code_and_matches_the_oracle(B):
         got_g, got_d = B.threshold_search(counts.astype(np.uint32), j, m)
         assert got_g == want_g
         assert abs(got_d - want_d) <= 1e-12 * max(1.0, want_d)
+    # the hand-worked histograms (derivation beside the oracle's pin of the same name)
+    A = 10 ** 6
+    counts = np.zeros(2048, np.uint32); counts[0] = A; counts[1] = A; counts[-1] = 1
+    c0, c1 = A / (2 * A + 1.0), 2 * A / (2 * A + 1.0)
+    g_, d_ = B.threshold_search(counts, 0, 2047)
+    want = (c1 - c0) / 128 + (1 - c1) * (1919 + 1 / 128)
+    assert g_ == 128 and abs(d_ - want) <= 1e-9 * want
+    counts = np.zeros(256, np.uint32); counts[0] = 1000; counts[-1] = 1
+    g_, d_ = B.threshold_search(counts, 0, 255)
+    assert g_ == 255 and abs(d_ - (1 / 1001.0) * 129 / 255) <= 1e-9 * d_
     L = B.lib()
     h = (C.c_uint32 * 4)(1, 2, 3, 4)
     g = C.c_int64(0)

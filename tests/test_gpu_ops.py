@@ -284,7 +284,8 @@ def test_mfma_rate_probe_runs_the_stated_work(B):
     blocks, iters = 3, 5
     ones = torch.ones(1 << 15, dtype=torch.int8, device="cuda:0")
     sink = torch.zeros(blocks * 512, dtype=torch.int32, device="cuda:0")
-    ops = B.mfma_rate_probe(ones, ones, sink, blocks, iters)
+    from paper_1805_07941_amd import probe
+    ops = probe.mfma_rate(ones, ones, sink, blocks, iters)
     assert ops == blocks * 8 * iters * 8 * 2 * 32 ** 3
     assert np.array_equal(host(sink), np.full(blocks * 512, 8 * 16 * 32 * iters, dtype=np.int32))
 

@@ -622,6 +622,39 @@ def test_threshold_search_follows_the_algorithm_step_by_step():
         assert gamma == g2 and abs(delta - d2) <= 1e-9 * max(1.0, d2)
 
 
+def test_threshold_search_hand_worked_histograms():
+    """Three histograms whose search result is derived on paper (bin width 1, A elements per low bin, one element in
+    the last bin).  With levels k/127 and the kept bins t/(i-1) on [0, 1], the requantized curve q differs from the
+    data's distribution function only where a grid point falls strictly between two levels that hold different values.
+
+    (a) 130 bins, A in bin 0: c = A/(A+1).  Keeping all 130 bins, the only such point is t = 128
+        (128/129 - 126/127 = 2/(129*127), i.e. 2/129 of the way from level 126 to level 127): delta = (1-c) * 2/129.
+        Clipping to 129 bins costs (1-c) at the bin that receives the clipped mass alone.  So gamma = max = 129.
+    (b) 256 bins, A in bin 0: points t = 253 and 254 lie 1/255 and 128/255 of the way: delta = (1-c) * 129/255, again
+        less than the (1-c) per clipped bin of any smaller candidate.  gamma = 255.
+    (c) 2048 bins, A in bins 0 and 1 each: c0 = A/(2A+1), c1 = 2A/(2A+1).  Keeping 129 bins, level k lies between grid
+        points k and k+1, so q follows the data except at t = 1 ((c1-c0)/128 short of c1) and t = 127 ((1-c1)/128 above
+        c1); bin 128 and the 1918 clipped bins below the last one are off by (1-c1) each:
+        delta = (c1-c0)/128 + (1-c1) * (1919 + 1/128).  Every larger candidate i pays at least
+        (c1-c0) * (1 - 127/(i-1)) >= (c1-c0) * 2/129 at t = 1, which is more for large A.  gamma = 129 - 1 = 128."""
+    A = 1000
+    c = A / (A + 1.0)
+    for nb, want_delta in [(130, (1 - c) * 2 / 129), (256, (1 - c) * 129 / 255)]:
+        counts = np.zeros(nb, np.uint64); counts[0] = A; counts[-1] = 1
+        gamma, delta = orc.threshold_search(counts, 0, nb - 1)
+        assert gamma == nb - 1 and abs(delta - want_delta) <= 1e-9 * want_delta, (nb, gamma, delta)
+    A = 10 ** 6                        # (c) needs 1919 / (2A+1) < (c1-c0) * (2/129 - 1/128), i.e. A > 249 000
+    counts = np.zeros(2048, np.uint64); counts[0] = A; counts[1] = A; counts[-1] = 1
+    c0, c1 = A / (2 * A + 1.0), 2 * A / (2 * A + 1.0)
+    gamma, delta = orc.threshold_search(counts, 0, 2047)
+    want = (c1 - c0) / 128 + (1 - c1) * (1919 + 1 / 128)
+    assert gamma == 128 and abs(delta - want) <= 1e-9 * want, (gamma, delta, want)
+    # the same three through the histogram front end (bin width 2: thresholds double, measures stay)
+    x = np.concatenate([np.zeros(A, np.int32), np.ones(A, np.int32) * 2, np.array([4094], np.int32)])
+    cnt, j, m = orc.hist_i32(x)
+    assert j == 1 and m == 4094 and orc.threshold_search(cnt, j, m)[0] == 129 * 2 - 1
+
+
 def test_threshold_search_properties():
     rng = np.random.default_rng(43)
     # too few bins to clip anything (the loop starts at 2^(n-1) + 1 = 129 bin edges): the maximum stays
