@@ -136,8 +136,10 @@ dfq_status dfq_conv_q_pc(const int8_t *x, const int8_t *w, const int32_t *b, int
  * rounded once to fmt_out.  `other`: device, int8 [N, P, Q, K] with ld_other bytes between pixels
  * (>= K), read only, must not overlap y or x.  All other arguments as for dfq_conv_q.
  * Returns DFQ_EUNSUPPORTED - and does nothing - when no fused kernel covers the call (the caller
- * then issues the two calls above); the fused kernel needs what DFQ_CONV_POINTWISE needs, `other`
- * 16-byte aligned with ld_other % 16 == 0, and max(f_mid, f_other) - f_out in [0, 23]. */
+ * then issues the two calls above).  Fused kernels exist for unpadded 1x1 stride-1 layers with
+ * groups == 1 that either meet what DFQ_CONV_POINTWISE needs, or have C % 64 == 0, K % 256 == 0,
+ * 16-byte aligned x, w, y, ldy % 16 == 0 and a rescale shift in [0, 23]; both need `other` 16-byte
+ * aligned with ld_other % 16 == 0, and max(f_mid, f_other) - f_out in [0, 23]. */
 dfq_status dfq_conv_q_add(const int8_t *x, const int8_t *w, const int32_t *b, const int8_t *other, int8_t *y,
                           int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
                           int ldy, int ld_other, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_mid, int relu_mid,

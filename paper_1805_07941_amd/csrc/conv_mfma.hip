@@ -44,7 +44,7 @@ struct MfmaParams {
     int nsteps;       // ceil(Kgemm / 64)
     int tiles_c;      // channel tiles
     int tiles;        // pixel tiles * channel tiles
-    unsigned x_bytes, w_bytes, y_bytes;
+    unsigned x_bytes, w_bytes, y_bytes, add_bytes;
     FastDiv div_pq, div_q, div_tc;
 };
 
@@ -57,10 +57,17 @@ struct MfmaParams {
 // (GENERAL = false) whenever none of these applies.  OCC: wavefronts per SIMD to fit registers for.
 // PC (excludes GENERAL): the lean epilogue with one weight format per output channel, every
 // channel's shift within [0, 23] (the caller of the library vouches for the range of the formats).
-template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool PW, bool GENERAL, int OCC, bool PC = false>
+// FUSE (excludes GENERAL): an element-wise add (Eq. 10) follows the convolution and is taken in the
+// epilogue: the second operand's 16 codes per lane and 32 x 32 tile are loaded at the start of the
+// epilogue - ordinary loads the compiler tracks, all issued before the first is used - the
+// convolution result is rounded to its own format in registers, aligned with the operand at the
+// finer scale and the sum rounded once more.
+template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool PW, bool GENERAL, int OCC, bool PC = false,
+          bool FUSE = false>
 __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(MfmaParams prm)
 {
     static_assert(!PC || !GENERAL, "the per-channel form is a lean one");
+    static_assert(!FUSE || !GENERAL, "the fused add exists in the lean forms only");
     static_assert(NSTAGES >= 2 && NSTAGES <= 6, "ring depth");
     static_assert(UT || !PW, "the pointwise form keeps its position in scalar registers");
     constexpr int NW = WAVES_P * WAVES_C;                 // wavefronts per workgroup
@@ -119,6 +126,8 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
     const v4i xrsrc = make_rsrc(a.x, prm.x_bytes);
     const v4i wrsrc = make_rsrc(a.w, prm.w_bytes);
     const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, GENERAL ? 0 : (int)prm.y_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(FUSE ? a.add : a.x), 0,
+                                                                           FUSE ? (int)prm.add_bytes : 0, 0x00020000);
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char *)(char *)&lds[0];
     int *bias_lds = (int *)(lds + nstages * STAGE_PIECES);
     int *pc_shift = bias_lds + BC, *pc_hi = pc_shift + BC, *pc_badd = pc_hi + BC;
@@ -263,8 +272,9 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
     for (int i = 0; i < nstages; i++)
         if (i < nitems) issue(i);
 
-    Requant rq;
+    Requant rq, rq2;
     rq.init(a.shift, a.relu);
+    rq2.init(FUSE ? a.add_shift : 1, a.add_relu);
     __syncthreads();   // bias_lds and the per-channel constants complete
 
     // accumulators start at the bias: register r of a lane belongs to channel kc + r
@@ -324,6 +334,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
     constexpr unsigned kHistMask = (1u << (NSTAGES - 1)) - 1u;
     unsigned ep_hist = 0;
     const unsigned lane_yoff = (unsigned)((wp0 + l32) * a.ldy + k0 + wc0 + 16 * lh);   // lean form: y fits 31 bits
+    const unsigned lane_aoff = (unsigned)((wp0 + l32) * a.ldadd + k0 + wc0 + 16 * lh);
     int c_step = 0, c_tile = lb;
     auto finish_item = [&]() __attribute__((always_inline)) {
         ep_hist = (ep_hist << 1) & kHistMask;
@@ -332,6 +343,17 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
             const int m0 = fastdiv(c_tile, prm.div_tc) * BP;
             if (!GENERAL) {
                 const unsigned tile_off = (unsigned)(m0 * a.ldy);
+                v4u other[FUSE ? CT * PT : 1];
+                if constexpr (FUSE) {
+                    // rows past the last pixel are outside the buffer: zeros arrive, and their stores are dropped
+                    const unsigned add_off = lane_aoff + (unsigned)(m0 * a.ldadd);
+#pragma unroll
+                    for (int c = 0; c < CT; c++)
+#pragma unroll
+                        for (int p = 0; p < PT; p++)
+                            other[c * PT + p] = __builtin_amdgcn_raw_buffer_load_b128(arsrc, (int)(add_off + (unsigned)(p * 32 * a.ldadd + c * 32)), 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 if constexpr (PC) {
                     // groups of four channels; the constants of the next group are fetched while this one is
                     // rescaled, and the scheduler is kept from hoisting all fetches to the front (registers)
@@ -352,9 +374,15 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
                             }
                             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                            for (int p = 0; p < PT; p++)
-                                o[p][r4] = requant_four_per_channel(acc[c][p][4 * r4], acc[c][p][4 * r4 + 1], acc[c][p][4 * r4 + 2],
-                                                                    acc[c][p][4 * r4 + 3], sv, hv, bv, a.relu);
+                            for (int p = 0; p < PT; p++) {
+                                if constexpr (FUSE)
+                                    o[p][r4] = requant_add_four_per_channel(acc[c][p][4 * r4], acc[c][p][4 * r4 + 1], acc[c][p][4 * r4 + 2],
+                                                                            acc[c][p][4 * r4 + 3], sv, hv, bv, a.relu, other[c * PT + p][r4],
+                                                                            a.add_sa, a.add_sb, rq2);
+                                else
+                                    o[p][r4] = requant_four_per_channel(acc[c][p][4 * r4], acc[c][p][4 * r4 + 1], acc[c][p][4 * r4 + 2],
+                                                                        acc[c][p][4 * r4 + 3], sv, hv, bv, a.relu);
+                            }
                             __builtin_amdgcn_sched_barrier(0);
                             sv = sn; hv = hn; bv = bn;
                         }
@@ -367,8 +395,16 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
 #pragma unroll
                     for (int c = 0; c < CT; c++)
 #pragma unroll
-                        for (int p = 0; p < PT; p++)
-                            store_piece(requant_tile_lane_fast(acc[c][p], rq), lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32), yrsrc);
+                        for (int p = 0; p < PT; p++) {
+                            const unsigned off = lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32);
+                            if constexpr (FUSE) {
+                                const v4i oth = {(int)other[c * PT + p][0], (int)other[c * PT + p][1], (int)other[c * PT + p][2],
+                                                 (int)other[c * PT + p][3]};
+                                store_piece(requant_add_tile_lane(acc[c][p], rq, oth, a.add_sa, a.add_sb, rq2), off, yrsrc);
+                            } else {
+                                store_piece(requant_tile_lane_fast(acc[c][p], rq), off, yrsrc);
+                            }
+                        }
                 }
                 ep_hist |= 1u;
             } else {
@@ -466,11 +502,11 @@ inline hipError_t big_lds(void (*k)(MfmaParams))
 // The per-channel lean form holds a group's rescale constants in registers on top of everything
 // else: it is built for the tile shapes whose register budget has room for them (wavefront tiles of
 // 64 x 64 at no more than three wavefronts per SIMD).
-template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool PW, int OCC>
+template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool PW, int OCC, bool FUSE = false>
 constexpr void (*per_channel_kernel())(MfmaParams)
 {
     if constexpr (OCC <= 3 && (BP / WAVES_P) * (BC / WAVES_C) <= 64 * 64)
-        return conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, UT, PW, false, OCC, true>;
+        return conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, UT, PW, false, OCC, true, FUSE>;
     else
         return nullptr;
 }
@@ -492,6 +528,7 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     prm.w_bytes = (unsigned)((long long)a.K * prm.Kgemm);
     const long long y_bytes = M * a.ldy;
     prm.y_bytes = y_bytes < (1LL << 31) ? (unsigned)y_bytes : 0u;
+    prm.add_bytes = a.add ? (unsigned)(M * a.ldadd) : 0u;
     prm.div_pq = make_fastdiv(a.P * a.Q);
     prm.div_q = make_fastdiv(a.Q);
     prm.div_tc = make_fastdiv(prm.tiles_c);
@@ -507,7 +544,7 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     using K = void (*)(MfmaParams);
     const bool ut = a.C % kStepBytes == 0;
     const bool pw = ut && a.R == 1 && a.S == 1 && a.stride == 1 && a.pad == 0;
-    static const K kernels[9] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, false, occ>,
+    static const K kernels[11] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, false, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, true, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, false, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, true, occ>,
@@ -515,15 +552,23 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, true, occ>,
                                  per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, occ>(),
                                  per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, occ>(),
-                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, occ>()};
-    static const hipError_t attr[9] = {big_lds(kernels[0]), big_lds(kernels[1]), big_lds(kernels[2]), big_lds(kernels[3]),
-                                       big_lds(kernels[4]), big_lds(kernels[5]), big_lds(kernels[6]), big_lds(kernels[7]),
-                                       big_lds(kernels[8])};
+                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, occ>(),
+                                 // unpadded 1x1 stride-1 layers with the add behind them fused into the epilogue
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, false, occ, false, true>,
+                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, occ, true>()};
+    static const hipError_t attr[11] = {big_lds(kernels[0]), big_lds(kernels[1]), big_lds(kernels[2]), big_lds(kernels[3]),
+                                        big_lds(kernels[4]), big_lds(kernels[5]), big_lds(kernels[6]), big_lds(kernels[7]),
+                                        big_lds(kernels[8]), big_lds(kernels[9]), big_lds(kernels[10])};
     // shifts the epilogue will meet: one, or with per-channel weight formats the declared range
     const int s_lo = a.shift + (a.frac_w ? a.frac_w_lo : 0), s_hi = a.shift + (a.frac_w ? a.frac_w_hi : 0);
     const bool general = !((!a.frac_w || kernels[6]) && s_lo >= 0 && s_hi <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
                            ((uintptr_t)a.y & 15) == 0 && a.K % BC == 0 && y_bytes < (1LL << 31));
-    const int which = (!general && a.frac_w) ? (pw ? 7 : ut ? 6 : 8) : (pw ? 4 : ut ? 2 : 0) + (general ? 1 : 0);
+    int which = (!general && a.frac_w) ? (pw ? 7 : ut ? 6 : 8) : (pw ? 4 : ut ? 2 : 0) + (general ? 1 : 0);
+    if (a.add) {
+        // conv_mfma_fuses() has vouched for the lean pointwise form
+        if (general || !pw || (a.frac_w && !kernels[10])) return hipErrorInvalidValue;
+        which = a.frac_w ? 10 : 9;
+    }
     if (attr[which] != hipSuccess) return attr[which];
     K kernel = kernels[which];
     kernel<<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
@@ -543,6 +588,22 @@ bool conv_mfma_supports(const ConvArgs &a)
     if ((long long)a.N * a.P * a.Q >= (1LL << 31) - 512) return false;
     if (((uintptr_t)a.x & 15) || ((uintptr_t)a.w & 15)) return false;
     if (a.acc_out && ((uintptr_t)a.acc_out & 15)) return false;
+    return true;
+}
+
+// The fused add (a.add set) exists for unpadded 1x1 stride-1 layers with whole 64-byte steps and whole
+// channel tiles of any tile shape (K a multiple of 256), in the lean epilogue.
+bool conv_mfma_fuses(const ConvArgs &a)
+{
+    if (!a.add || !conv_mfma_supports(a)) return false;
+    if (a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 || a.C % kStepBytes || a.K % 256) return false;
+    const int s_lo = a.shift + (a.frac_w ? a.frac_w_lo : 0), s_hi = a.shift + (a.frac_w ? a.frac_w_hi : 0);
+    if (s_lo < 0 || s_hi > 23 || a.acc_out || !a.y || (a.ldy & 15) || ((uintptr_t)a.y & 15)) return false;
+    const long long M = (long long)a.N * a.P * a.Q;
+    if (M * a.ldy >= (1LL << 31) || M * a.ldadd >= (1LL << 31)) return false;
+    if (a.frac_w && M <= 1024) return false;      // the tile shape for very few pixels has no per-channel lean form
+    if (((uintptr_t)a.add & 15) || (a.ldadd & 15) || a.ldadd < a.K) return false;
+    if (!(a.add_shift >= 0 && a.add_shift <= 23) || a.add_sa < 0 || a.add_sa > 22 || a.add_sb < 0 || a.add_sb > 22) return false;
     return true;
 }
 

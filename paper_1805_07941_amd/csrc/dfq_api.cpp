@@ -128,8 +128,9 @@ dfq_status run_conv_add(ConvCheck &c, const int8_t *x, const int8_t *other, int8
     c.a.add_sb = F - fmt_other.frac;
     c.a.add_shift = F - fmt_out.frac;
     c.a.add_relu = relu_out ? 1 : 0;
-    if (!conv_pw_supports(c.a)) return DFQ_EUNSUPPORTED;
-    return from_hip(launch_conv_pw(c.a, (hipStream_t)stream));
+    if (conv_pw_supports(c.a)) return from_hip(launch_conv_pw(c.a, (hipStream_t)stream));
+    if (conv_mfma_fuses(c.a)) return from_hip(launch_conv_mfma(c.a, (hipStream_t)stream));
+    return DFQ_EUNSUPPORTED;
 }
 
 }  // namespace

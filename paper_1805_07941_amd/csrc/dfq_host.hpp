@@ -57,6 +57,7 @@ hipError_t launch_absmax_i32_channels(const int32_t *x, size_t pixels, int K, in
 bool conv_direct_supports(const ConvArgs &a);
 hipError_t launch_conv_direct(const ConvArgs &a, hipStream_t st);
 bool conv_mfma_supports(const ConvArgs &a);
+bool conv_mfma_fuses(const ConvArgs &a);     // a.add set: the dense kernel has a fused form for this call
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st);
 bool conv_depthwise_supports(const ConvArgs &a);
 hipError_t launch_conv_depthwise(const ConvArgs &a, hipStream_t st);

@@ -176,16 +176,18 @@ class Plan:
         self._calls, self._calls_key, self._graph, self._keep = None, None, None, None
         self._fused_ran = None                   # after the call list is built: results of convolutions that ran fused
 
-    def _pointwise_geometry(self, nd) -> bool:
-        H, W, Cc = self.net.shapes[nd.srcs[0]]
-        return B.conv_q_select(self.batch, H, W, Cc, nd.K, nd.R, nd.R, nd.stride, nd.pad, nd.groups) == B.CONV_POINTWISE
+    @staticmethod
+    def _plain_pointwise(nd) -> bool:
+        """A 1x1 convolution at stride 1 without padding or groups: the kind of layer the library's fused
+        convolution + add calls exist for."""
+        return nd.op == "conv" and nd.R == 1 and nd.stride == 1 and nd.pad == 0 and nd.groups == 1
 
     def _fusable_pairs(self) -> Dict[int, int]:
         """Convolution nodes directly followed by an element-wise add that is the only reader of
         their result (whether the library has a fused kernel for the call is probed when the call list
-        is built).  Where an add is fed by two convolutions listed as (c, p, add), only c has the
-        geometry of the fused kernel and p does not depend on c, the two are run as (p, c + add):
-        self.order is changed accordingly."""
+        is built).  Where an add is fed by two convolutions listed as (c, p, add), only c is a plain
+        pointwise layer and p does not depend on c, the two are run as (p, c + add): self.order is
+        changed accordingly."""
         net, qz = self.net, self.qz
         readers: Dict[str, int] = {}
         for nd in net.nodes:
@@ -198,11 +200,11 @@ class Plan:
                 continue
             c = net.nodes[j - 1]
             ok = c.op == "conv" and c.dst in e.srcs and readers.get(c.dst, 0) == 1 and c.dst != net.output_name
-            if j >= 2 and ok and not self._pointwise_geometry(c):
-                # the convolution in front of the add is not one the fused kernel takes: maybe the one before it is
+            if j >= 2 and ok and not self._plain_pointwise(c):
+                # the convolution in front of the add is not one a fused call takes: maybe the one before it is
                 c2 = net.nodes[j - 2]
                 if (c2.op == "conv" and {c.dst, c2.dst} == set(e.srcs) and readers.get(c2.dst, 0) == 1
-                        and c2.dst not in c.srcs and c2.dst != net.output_name and self._pointwise_geometry(c2)):
+                        and c2.dst not in c.srcs and c2.dst != net.output_name and self._plain_pointwise(c2)):
                     at = self.order.index(j - 2)
                     self.order[at], self.order[at + 1] = j - 1, j - 2
                     pairs[j - 2] = j

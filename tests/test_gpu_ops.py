@@ -158,7 +158,8 @@ def test_conv_q_random_shapes(B, shape):
         first = False
 
 
-@pytest.mark.parametrize("shape", [(3, 19, 17, 64, 256), (2, 23, 21, 256, 384), (2, 30, 30, 128, 64), (2, 14, 14, 256, 1024)],
+@pytest.mark.parametrize("shape", [(3, 19, 17, 64, 256), (2, 23, 21, 256, 384), (2, 30, 30, 128, 64), (2, 14, 14, 256, 1024),
+                                   (3, 7, 7, 512, 2048), (5, 21, 19, 320, 256), (40, 14, 14, 1024, 512)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_conv_q_add_equals_conv_then_eltwise(B, shape):
     """The fused call against the oracle's convolution followed by the oracle's add, for format
@@ -356,7 +357,8 @@ def test_absmax_per_channel(B):
             assert np.array_equal(got, orc.absmax_i32_channels(a, relu=relu)), (shape, relu)
 
 
-@pytest.mark.parametrize("shape", [(3, 19, 17, 64, 256), (2, 23, 21, 128, 384), (2, 30, 30, 128, 64), (2, 14, 14, 256, 512)],
+@pytest.mark.parametrize("shape", [(3, 19, 17, 64, 256), (2, 23, 21, 128, 384), (2, 30, 30, 128, 64), (2, 14, 14, 256, 512),
+                                   (30, 7, 7, 512, 2048), (9, 14, 14, 256, 1024), (40, 14, 14, 1024, 512)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_conv_q_pc_add_equals_the_two_calls(B, shape):
     """The fused per-channel convolution + add against the oracle's two steps, and against the library's own."""
@@ -415,7 +417,7 @@ def _scaled_pointwise_case(rng, N, H, C, K):
 
 
 @pytest.mark.parametrize("per_channel", [False, True], ids=["per_layer", "per_channel"])
-@pytest.mark.parametrize("shape", [(56, 64, 256), (28, 128, 512), (14, 256, 1024)], ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("shape", [(56, 64, 256), (28, 128, 512), (14, 256, 1024), (7, 512, 2048)], ids=lambda s: "x".join(map(str, s)))
 def test_conv_q_add_full_size_sampled(B, shape, per_channel):
     """dfq_conv_q_add / dfq_conv_q_pc_add at batch 256 (the benchmark's launch configuration): 400 sampled outputs
     through the oracle's single-element convolution, its rounding and its add; two whole images; and the whole
@@ -436,15 +438,10 @@ def test_conv_q_add_full_size_sampled(B, shape, per_channel):
         fwd = dev(f_w)
         rngw = (int(f_w.min()), int(f_w.max()))
         got = B.conv_q_pc_add(xd, wd, bd, od, f_in, fwd, rngw, f_mid, relu_mid, f_other, f_out, relu_out)
-        if got is None:
-            # the per-channel tables of this layer do not fit LDS beside the input buffers: the caller's two calls
-            assert (C, K) == (256, 1024)
-            mid_g, _ = B.conv_q_pc(xd, wd, bd, f_in, fwd, f_mid, 1, 0, 1, relu_mid, frac_w_range=rngw)
-            got, _ = B.eltwise_q(mid_g, f_mid, od, f_other, f_out, relu_out)
-        else:
-            mid_g, _ = B.conv_q_pc(xd, wd, bd, f_in, fwd, f_mid, 1, 0, 1, relu_mid, frac_w_range=rngw)
-            two, _ = B.eltwise_q(mid_g, f_mid, od, f_other, f_out, relu_out)
-            assert torch.equal(got, two)
+        assert got is not None          # (256 -> 1024 and 512 -> 2048 run in the general dense kernel's fused form)
+        mid_g, _ = B.conv_q_pc(xd, wd, bd, f_in, fwd, f_mid, 1, 0, 1, relu_mid, frac_w_range=rngw)
+        two, _ = B.eltwise_q(mid_g, f_mid, od, f_other, f_out, relu_out)
+        assert torch.equal(got, two)
     else:
         got = B.conv_q_add(xd, wd, bd, od, f_in, f_w, f_mid, relu_mid, f_other, f_out, relu_out)
         assert got is not None
