@@ -174,6 +174,12 @@ dfq_status dfq_eltwise_q(const int8_t *a, dfq_fmt fa, const int8_t *b, dfq_fmt f
  * Cs, fs: HOST arrays.  y: [pixels][sum Cs].  1 <= nbranch <= 8. */
 dfq_status dfq_concat_q(int nbranch, const int8_t *const *xs, const int *Cs, const dfq_fmt *fs,
                         int8_t *y, dfq_fmt fy, size_t pixels, dfq_stream stream);
+/* The same into a channel slice of a wider tensor: y[px * ldy + off_i + c], ldy >= sum Cs bytes between
+ * pixels.  With it a join can be assembled in pieces: branches whose producing convolution already
+ * writes the joined format go straight into their slice (ldy of dfq_conv_q) - the explicit downscale in
+ * front of a join that Sec. 3 describes - and only the others pass through this call. */
+dfq_status dfq_concat_q_into(int nbranch, const int8_t *const *xs, const int *Cs, const dfq_fmt *fs,
+                             int8_t *y, int ldy, dfq_fmt fy, size_t pixels, dfq_stream stream);
 
 /* ---- pooling (the paper names max-pool among the layers that may need an explicit
  * downscale, Sec. 3, and gives no arithmetic; average follows Eq. 10) -------------------
@@ -191,6 +197,17 @@ dfq_status dfq_pool_q(const int8_t *x, int8_t *y, dfq_pool_mode mode, int N, int
 dfq_status dfq_absmax_f32(const float *x, size_t n, float *out_dev, dfq_stream stream);
 /* max |x[i]| (as uint32; relu != 0: negative entries count as 0). */
 dfq_status dfq_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out_dev, dfq_stream stream);
+
+/* ---- preprocessing (Sec. 3: neighbouring linear operations are combined before quantizing) ----
+ * Folds a per-channel affine layer z = scale[k] * y + shift[k] that follows a convolution (batch norm in its
+ * inference form, a scale layer) into the convolution's FLOAT weights and bias:
+ *   w_out[k][i] = w[k][i] * scale[k],   b_out[k] = b[k] * scale[k] + shift[k]
+ * each product and the sum rounded to float separately.  w, w_out: [rows][row_len]; b (NULL = zeros), shift (NULL =
+ * zeros), scale, b_out: [rows]; all DEVICE.  b_out may be NULL only if b and shift are.  In place (w_out == w,
+ * b_out == b) is allowed; partial overlap is DFQ_EINVAL.  The folded layer is then calibrated and quantized like
+ * any other; the quantized network has no scale layers left. */
+dfq_status dfq_fold_scale_f32(const float *w, const float *b, size_t rows, size_t row_len, const float *scale,
+                              const float *shift, float *w_out, float *b_out, dfq_stream stream);
 
 /* Row-wise forms for weights that take one format per output channel (Sec. 3): row r of
  * x[rows][row_len] (weights: rows = K, row_len = R*S*C/groups; bias: row_len = 1).

@@ -82,6 +82,8 @@ def lib():
         L.orc_frac_from_absmax_f32.argtypes = [C.c_float]
         L.orc_frac_from_absmax_i32.restype = C.c_int
         L.orc_frac_from_absmax_i32.argtypes = [C.c_int64, C.c_int]
+        L.orc_fold_scale.restype = None
+        L.orc_fold_scale.argtypes = [_f32p, _f32p, C.c_size_t, C.c_size_t, _f32p, _f32p, _f32p, _f32p]
         L.orc_num_threads.restype = C.c_int
         L.orc_num_threads.argtypes = []
         _lib = L
@@ -224,6 +226,20 @@ def pool_q(x, mode, k, stride, pad, f_in, f_out):
     if rc:
         raise ValueError("oracle pool_q: bad arguments")
     return y
+
+
+def fold_scale(w, b, scale, shift):
+    """A per-channel affine layer behind a convolution folded into its float weights and bias:
+    (w * scale[k], b * scale + shift), float32."""
+    w = _c(w, np.float32); scale = _c(scale, np.float32)
+    rows = w.shape[0]
+    b = None if b is None else _c(b, np.float32)
+    shift = None if shift is None else _c(shift, np.float32)
+    w_out = np.empty_like(w)
+    b_out = np.empty(rows, np.float32)
+    lib().orc_fold_scale(_p(w, _f32p), _p(b, _f32p), rows, w.size // max(rows, 1), _p(scale, _f32p), _p(shift, _f32p),
+                         _p(w_out, _f32p), _p(b_out, _f32p))
+    return w_out, b_out
 
 
 # ---- calibration building blocks ---------------------------------------------- #

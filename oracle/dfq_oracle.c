@@ -501,3 +501,24 @@ int orc_num_threads(void) { return omp_get_max_threads(); }
 #else
 int orc_num_threads(void) { return 1; }
 #endif
+
+
+/* ---- preprocessing: a per-channel affine layer behind a convolution folded into its float weights (Sec. 3:
+ * neighbouring linear operations are combined before quantizing).  z = scale[k]*(w[k].x + b[k]) + shift[k]
+ * = (scale[k]*w[k]).x + (scale[k]*b[k] + shift[k]).  Single precision, as the weights are; every product and
+ * the sum rounded separately (volatile keeps the compiler from contracting them). */
+void orc_fold_scale(const float *w, const float *b, size_t rows, size_t row_len, const float *scale, const float *shift,
+                    float *w_out, float *b_out)
+{
+    for (size_t r = 0; r < rows; r++) {
+        for (size_t i = 0; i < row_len; i++) {
+            volatile float p = w[r * row_len + i] * scale[r];
+            w_out[r * row_len + i] = p;
+        }
+        if (b_out) {
+            volatile float p = (b ? b[r] : 0.0f) * scale[r];
+            volatile float q = p + (shift ? shift[r] : 0.0f);
+            b_out[r] = q;
+        }
+    }
+}

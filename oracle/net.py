@@ -13,7 +13,10 @@ procedure of Sec. 3 in the paper's order, one layer at a time:
   is the accumulator rescaled (by a factor in (0, 1]) into the int8 output format;
 * joins: element-wise add aligns both inputs exactly and rescales the sum once
   (Eq. 10); concat rescales every branch into the coarsest branch format;
-  max / average pooling keep their input format.
+  max / average pooling keep their input format.  With ``match_joins=True`` the
+  scales of a concat's inputs are matched at calibration time instead (Sec. 3:
+  the explicit downscale in front of a join): a convolution that feeds only the
+  concat rounds its accumulators straight to the concat's format, once.
 
 End-to-end results have no pin outside this file ("parity unpinned"); each
 ingredient it calls is pinned separately.
@@ -51,6 +54,16 @@ def _input_codes(net, x, qz: Quantized, calibrating: bool):
     return orc.quantize(x, qz.frac[net.input_name])
 
 
+def _float_weights(net, nd):
+    """Float weights and bias of a convolution as they are quantized: with the affine layer behind it (if
+    the network has such layers) folded in first - linear neighbours are combined before quantizing."""
+    wf, bf = net.weights(nd)
+    if getattr(net, "scale_layers", False):
+        scale, shift = net.scale_shift(nd)
+        wf, bf = orc.fold_scale(wf, bf, scale, shift)
+    return wf, bf
+
+
 def _threshold(acc, relu, rule):
     """The activation threshold of Sec. 3 in accumulator units: the maximum magnitude after the
     ReLU ("maxabs"), or the result of the histogram search of Algorithm 1 ("search")."""
@@ -60,22 +73,28 @@ def _threshold(acc, relu, rule):
     return orc.threshold_search(counts, j, m)[0]
 
 
-def _forward(net, x, qz: Quantized, calibrating: bool, per_channel: bool = False, rule: str = "maxabs"):
+def _forward(net, x, qz: Quantized, calibrating: bool, per_channel: bool = False, rule: str = "maxabs",
+             match_joins: bool = False):
     t = {net.input_name: _input_codes(net, x, qz, calibrating)}
+    readers = {}
+    for nd in net.nodes:
+        for s in nd.srcs:
+            readers[s] = readers.get(s, 0) + 1
+    producer = {nd.dst: nd for nd in net.nodes}
     for nd in net.nodes:
         if nd.op == "conv":
             src = nd.srcs[0]
             f_in = qz.frac[src]
             if calibrating and per_channel:
                 # one threshold per output channel: channel k's weights and bias get their own scale
-                wf, bf = net.weights(nd)
+                wf, bf = _float_weights(net, nd)
                 f_wk = np.array([orc.frac_from_absmax_f32(orc.absmax_f32(wf[k])) for k in range(wf.shape[0])], np.int32)
                 qz.w_frac[nd.name] = f_wk
                 qz.w[nd.name] = np.stack([orc.quantize(wf[k], int(f_wk[k])) for k in range(wf.shape[0])])
                 qz.b[nd.name] = np.array([orc.quantize_i32(bf[k:k + 1], f_in + int(f_wk[k]))[0] for k in range(wf.shape[0])],
                                          np.int32)
             elif calibrating:
-                wf, bf = net.weights(nd)
+                wf, bf = _float_weights(net, nd)
                 f_w = orc.frac_from_absmax_f32(orc.absmax_f32(wf))
                 qz.w_frac[nd.name] = f_w
                 qz.w[nd.name] = orc.quantize(wf, f_w)
@@ -117,6 +136,16 @@ def _forward(net, x, qz: Quantized, calibrating: bool, per_channel: bool = False
             fs = [qz.frac[s] for s in nd.srcs]
             if calibrating:
                 qz.frac[nd.dst] = nd.fixed_f_out if nd.fixed_f_out is not None else min(fs)
+                if match_joins:
+                    # every convolution that works for this concat alone takes the concat's format: its
+                    # accumulators are rounded once, to the joined scale (never a finer one than its own)
+                    for s in nd.srcs:
+                        pr = producer.get(s)
+                        if pr is not None and pr.op == "conv" and readers[s] == 1 and qz.frac[s] > qz.frac[nd.dst]:
+                            qz.frac[s] = qz.frac[nd.dst]
+                            t[s], _ = orc.conv_q(t[pr.srcs[0]], qz.w[pr.name], qz.b[pr.name], qz.frac[pr.srcs[0]],
+                                                 qz.w_frac[pr.name], qz.frac[s], pr.stride, pr.pad, pr.groups, pr.relu)
+                    fs = [qz.frac[s] for s in nd.srcs]
             t[nd.dst] = orc.concat_q([t[s] for s in nd.srcs], fs, qz.frac[nd.dst])
         elif nd.op in ("maxpool", "avgpool"):
             src = nd.srcs[0]
@@ -129,15 +158,16 @@ def _forward(net, x, qz: Quantized, calibrating: bool, per_channel: bool = False
     return t
 
 
-def calibrate(net, x_calib, per_channel: bool = False, rule: str = "maxabs"):
+def calibrate(net, x_calib, per_channel: bool = False, rule: str = "maxabs", match_joins: bool = False):
     """Chooses every format from ONE batch.  Returns (Quantized, tensors of that batch).
     per_channel: one weight format per output channel (Sec. 3) instead of one per layer.
     rule: "maxabs" - activation thresholds are maxima; "search" - Algorithm 1 on a histogram of the
-    accumulators (per-layer weight formats only)."""
+    accumulators (per-layer weight formats only).
+    match_joins: convolutions that feed only a concat produce the concat's format directly."""
     if rule not in ("maxabs", "search") or (rule == "search" and per_channel):
         raise ValueError("rule must be 'maxabs' or 'search' (the search with per-layer weight formats)")
     qz = Quantized()
-    t = _forward(net, x_calib, qz, calibrating=True, per_channel=per_channel, rule=rule)
+    t = _forward(net, x_calib, qz, calibrating=True, per_channel=per_channel, rule=rule, match_joins=match_joins)
     return qz, t
 
 

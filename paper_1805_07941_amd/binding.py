@@ -23,7 +23,7 @@ CONV_VARIANT_NAMES = {CONV_AUTO: "auto", CONV_DIRECT: "direct", CONV_MFMA: "mfma
 
 EXPORTS = [
     "dfq_status_string", "dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q",
-    "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_hist_i32", "dfq_threshold_search", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q",
+    "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_hist_i32", "dfq_threshold_search", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_fold_scale_f32", "dfq_eltwise_q", "dfq_concat_q", "dfq_concat_q_into", "dfq_pool_q",
     "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_hist_shift", "dfq_fmt_from_absmax_i32_channels",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
 ]
@@ -73,10 +73,12 @@ def lib():
     L.dfq_absmax_f32_rows.argtypes = [vp, sz, sz, vp, vp]
     L.dfq_quantize_rows.argtypes = [vp, vp, sz, sz, vp, vp]
     L.dfq_quantize_i32_rows.argtypes = [vp, vp, sz, sz, vp, i32, vp]
+    L.dfq_fold_scale_f32.argtypes = [vp, vp, sz, sz, vp, vp, vp, vp, vp]
     L.dfq_conv_q_select.argtypes = [i32] * 10
     L.dfq_conv_q_add.argtypes = [vp, vp, vp, vp, vp] + [i32] * 12 + [Fmt, Fmt, Fmt, i32, Fmt, Fmt, i32, vp]
     L.dfq_eltwise_q.argtypes = [vp, Fmt, vp, Fmt, vp, Fmt, vp, sz, i32, vp]
     L.dfq_concat_q.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, Fmt, sz, vp]
+    L.dfq_concat_q_into.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, i32, Fmt, sz, vp]
     L.dfq_pool_q.argtypes = [vp, vp, i32] + [i32] * 7 + [Fmt, Fmt, vp]
     L.dfq_absmax_f32.argtypes = [vp, sz, vp, vp]
     L.dfq_absmax_i32.argtypes = [vp, sz, i32, vp, vp]
@@ -86,10 +88,10 @@ def lib():
     L.dfq_hist_shift.argtypes = [i64]
     L.dfq_hist_shift.restype = i32
     for name in ("dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q", "dfq_conv_q_variant",
-                 "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_pool_q", "dfq_absmax_f32",
+                 "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_concat_q_into", "dfq_pool_q", "dfq_absmax_f32",
                  "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_fmt_from_absmax_i32_channels",
                  "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_absmax_f32_rows", "dfq_quantize_rows",
-                 "dfq_quantize_i32_rows", "dfq_hist_i32", "dfq_threshold_search"):
+                 "dfq_quantize_i32_rows", "dfq_hist_i32", "dfq_threshold_search", "dfq_fold_scale_f32"):
         getattr(L, name).restype = i32
     L.dfq_beta_max.restype = i64
     L.dfq_beta_max.argtypes = [i32, i32]
@@ -288,6 +290,25 @@ def eltwise_q(a: torch.Tensor, f_a: int, b: torch.Tensor, f_b: int, f_y: int, re
     return y, acc
 
 
+def concat_q_into(xs: Sequence[torch.Tensor], fs: Sequence[int], f_y: int, out: torch.Tensor, ch_off: int, stream=None):
+    """Branches xs (each [..., C_i]) rescaled into the channels ch_off .. ch_off + sum C_i of the wider tensor `out`."""
+    for i, x in enumerate(xs):
+        _dev(x, torch.int8, f"xs[{i}]")
+    _dev(out, torch.int8, "out")
+    lead = tuple(xs[0].shape[:-1])
+    if any(tuple(x.shape[:-1]) != lead for x in xs) or tuple(out.shape[:-1]) != lead:
+        raise DfqError(ESHAPE, "concat_q_into (pixel grids differ)")
+    Cs = [int(x.shape[-1]) for x in xs]
+    if ch_off < 0 or ch_off + sum(Cs) > out.shape[-1]:
+        raise DfqError(ESHAPE, "concat_q_into (slice outside the destination)")
+    nb = len(xs)
+    ptrs = (C.c_void_p * nb)(*[x.data_ptr() for x in xs])
+    st = lib().dfq_concat_q_into(nb, ptrs, (C.c_int * nb)(*Cs), (Fmt * nb)(*[fmt(f) for f in fs]), out.data_ptr() + int(ch_off),
+                                 int(out.shape[-1]), fmt(f_y), out.numel() // out.shape[-1], _stream(stream))
+    _check(st, "dfq_concat_q_into")
+    return out
+
+
 def concat_q(xs: Sequence[torch.Tensor], fs: Sequence[int], f_y: int, out: Optional[torch.Tensor] = None,
              stream=None) -> torch.Tensor:
     for i, x in enumerate(xs):
@@ -366,6 +387,25 @@ def quantize_i32_rows(x: torch.Tensor, frac: torch.Tensor, frac_add: int, stream
     _check(lib().dfq_quantize_i32_rows(_ptr(x), _ptr(q), rows, x.numel() // max(rows, 1), _ptr(frac), int(frac_add),
                                        _stream(stream)), "dfq_quantize_i32_rows")
     return q
+
+
+def fold_scale(w: torch.Tensor, b: Optional[torch.Tensor], scale: torch.Tensor, shift: Optional[torch.Tensor], stream=None):
+    """Float weights [rows, ...] and bias [rows] with the per-row affine layer behind the convolution folded in:
+    (w * scale[row], b * scale + shift) as new float32 device tensors."""
+    _dev(w, torch.float32, "w"); _dev(scale, torch.float32, "scale")
+    rows = int(w.shape[0])
+    for t_, name in ((b, "b"), (shift, "shift")):
+        if t_ is not None:
+            _dev(t_, torch.float32, name)
+            if tuple(t_.shape) != (rows,):
+                raise DfqError(ESHAPE, "fold_scale (one bias / shift per row)")
+    if tuple(scale.shape) != (rows,):
+        raise DfqError(ESHAPE, "fold_scale (one scale per row)")
+    w_out = torch.empty_like(w)
+    b_out = torch.empty(rows, dtype=torch.float32, device=w.device)
+    _check(lib().dfq_fold_scale_f32(_ptr(w), _ptr(b), rows, w.numel() // max(rows, 1), _ptr(scale), _ptr(shift), _ptr(w_out),
+                                    _ptr(b_out), _stream(stream)), "dfq_fold_scale_f32")
+    return w_out, b_out
 
 
 def absmax_i32_channels(x: torch.Tensor, relu: bool = False, out_dev: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

@@ -259,8 +259,8 @@ dfq_status dfq_eltwise_q(const int8_t *a, dfq_fmt fa, const int8_t *b, dfq_fmt f
     return from_hip(launch_eltwise(a, fa.frac, b, fb.frac, y, fy.frac, acc_out, n, relu ? 1 : 0, (hipStream_t)stream));
 }
 
-dfq_status dfq_concat_q(int nbranch, const int8_t *const *xs, const int *Cs, const dfq_fmt *fs, int8_t *y, dfq_fmt fy,
-                        size_t pixels, dfq_stream stream)
+dfq_status dfq_concat_q_into(int nbranch, const int8_t *const *xs, const int *Cs, const dfq_fmt *fs, int8_t *y, int ldy,
+                             dfq_fmt fy, size_t pixels, dfq_stream stream)
 {
     if (nbranch < 1 || nbranch > 8 || !xs || !Cs || !fs) return DFQ_EINVAL;
     if (!fmt_ok(fy)) return DFQ_EFMT;
@@ -272,14 +272,24 @@ dfq_status dfq_concat_q(int nbranch, const int8_t *const *xs, const int *Cs, con
         fr[i] = fs[i].frac;
         ct += Cs[i];
     }
-    if (ct >= (1LL << 31)) return DFQ_ESHAPE;
+    if (ct >= (1LL << 31) || ldy < ct) return DFQ_ESHAPE;
     if (pixels == 0) return DFQ_OK;
     if (!y) return DFQ_EINVAL;
     for (int i = 0; i < nbranch; i++) {
         if (!xs[i]) return DFQ_EINVAL;
-        if (overlaps(xs[i], pixels * (size_t)Cs[i], y, pixels * (size_t)ct)) return DFQ_EINVAL;
+        if (overlaps(xs[i], pixels * (size_t)Cs[i], y, (pixels - 1) * (size_t)ldy + (size_t)ct)) return DFQ_EINVAL;
     }
-    return from_hip(launch_concat(nbranch, xs, Cs, fr, y, fy.frac, pixels, (hipStream_t)stream));
+    return from_hip(launch_concat(nbranch, xs, Cs, fr, y, ldy, fy.frac, pixels, (hipStream_t)stream));
+}
+
+dfq_status dfq_concat_q(int nbranch, const int8_t *const *xs, const int *Cs, const dfq_fmt *fs, int8_t *y, dfq_fmt fy,
+                        size_t pixels, dfq_stream stream)
+{
+    long long ct = 0;
+    if (nbranch >= 1 && nbranch <= 8 && Cs)
+        for (int i = 0; i < nbranch; i++) ct += Cs[i] > 0 ? Cs[i] : 0;
+    if (ct >= (1LL << 31)) return DFQ_ESHAPE;
+    return dfq_concat_q_into(nbranch, xs, Cs, fs, y, (int)ct, fy, pixels, stream);
 }
 
 dfq_status dfq_pool_q(const int8_t *x, int8_t *y, dfq_pool_mode mode, int N, int H, int W, int C, int k, int stride, int pad,
@@ -323,6 +333,18 @@ dfq_status dfq_quantize_i32_rows(const float *x, int32_t *q, size_t rows, size_t
     if (rows == 0 || row_len == 0) return DFQ_OK;
     if (!x || !q || !frac || overlaps(x, rows * row_len * 4, q, rows * row_len * 4)) return DFQ_EINVAL;
     return from_hip(launch_quantize_i32_rows(x, q, rows, row_len, frac, frac_add, (hipStream_t)stream));
+}
+
+dfq_status dfq_fold_scale_f32(const float *w, const float *b, size_t rows, size_t row_len, const float *scale, const float *shift,
+                              float *w_out, float *b_out, dfq_stream stream)
+{
+    if (rows == 0) return DFQ_OK;
+    if (!scale || (row_len && (!w || !w_out))) return DFQ_EINVAL;
+    if (!b_out && (b || shift)) return DFQ_EINVAL;               // a bias or shift was given but there is nowhere to put the result
+    // in place (w_out == w, b_out == b) is fine: every element is read once, by the lane that writes it
+    if ((w_out != w && overlaps(w, rows * row_len * 4, w_out, rows * row_len * 4)) || (b_out && b_out != b && overlaps(b, rows * 4, b_out, rows * 4)))
+        return DFQ_EINVAL;
+    return from_hip(launch_fold_scale(w, b, rows, row_len, scale, shift, w_out, b_out, (hipStream_t)stream));
 }
 
 dfq_status dfq_absmax_f32_rows(const float *x, size_t rows, size_t row_len, float *out_dev, dfq_stream stream)

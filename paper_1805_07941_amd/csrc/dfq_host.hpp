@@ -41,8 +41,8 @@ hipError_t launch_quantize_i32(const float *x, int32_t *q, size_t n, int frac, h
 hipError_t launch_dequantize(const int8_t *q, float *x, size_t n, int frac, hipStream_t st);
 hipError_t launch_eltwise(const int8_t *a, int fa, const int8_t *b, int fb, int8_t *y, int fy, int32_t *acc, size_t n,
                           int relu, hipStream_t st);
-hipError_t launch_concat(int nb, const int8_t *const *xs, const int *Cs, const int *fs, int8_t *y, int fy, size_t pixels,
-                         hipStream_t st);
+hipError_t launch_concat(int nb, const int8_t *const *xs, const int *Cs, const int *fs, int8_t *y, int ldy, int fy,
+                         size_t pixels, hipStream_t st);
 hipError_t launch_pool(const int8_t *x, int8_t *y, int mode, int N, int H, int W, int C, int P, int Q, int k, int stride,
                        int pad, int fin, int fout, hipStream_t st);
 hipError_t launch_absmax_f32(const float *x, size_t n, float *out, hipStream_t st);
@@ -50,6 +50,8 @@ hipError_t launch_absmax_i32(const int32_t *x, size_t n, int relu, uint32_t *out
 hipError_t launch_quantize_rows(const float *x, int8_t *q, size_t rows, size_t row_len, const int32_t *frac, hipStream_t st);
 hipError_t launch_quantize_i32_rows(const float *x, int32_t *q, size_t rows, size_t row_len, const int32_t *frac, int frac_add,
                                     hipStream_t st);
+hipError_t launch_fold_scale(const float *w, const float *b, size_t rows, size_t row_len, const float *scale, const float *shift,
+                             float *w_out, float *b_out, hipStream_t st);
 hipError_t launch_absmax_f32_rows(const float *x, size_t rows, size_t row_len, float *out, hipStream_t st);
 hipError_t launch_hist_i32(const int32_t *x, size_t n, int relu, int shift, uint32_t *out, hipStream_t st);
 hipError_t launch_absmax_i32_channels(const int32_t *x, size_t pixels, int K, int relu, uint32_t *out, hipStream_t st);

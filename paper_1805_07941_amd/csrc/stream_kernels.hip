@@ -108,7 +108,37 @@ __global__ void __launch_bounds__(kBlock) quantize_i32_rows_kernel(const float *
     }
 }
 
+// Folding a per-channel affine layer (batch norm in its inference form, a scale layer) that follows a convolution
+// into the convolution's float weights and bias, before anything is quantized: w'[k][.] = w[k][.] * scale[k],
+// b'[k] = b[k] * scale[k] + shift[k].  Every product and the sum are rounded to float separately (no fused
+// multiply-add), so that the result does not depend on how the compiler contracts the expression.
+__global__ void __launch_bounds__(kBlock) fold_scale_kernel(const float *__restrict__ w, const float *__restrict__ b, size_t rows,
+                                                             size_t row_len, const float *__restrict__ scale,
+                                                             const float *__restrict__ shift, float *__restrict__ w_out,
+                                                             float *__restrict__ b_out)
+{
+#pragma clang fp contract(off)
+    const size_t n = rows * row_len;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n + rows; i += (size_t)gridDim.x * kBlock) {
+        if (i < n) {
+            w_out[i] = w[i] * scale[i / row_len];
+        } else if (b_out) {
+            const size_t r = i - n;
+            float prod = (b ? b[r] : 0.0f) * scale[r];
+            asm volatile("" : "+v"(prod));        // the product is rounded on its own: no fused multiply-add
+            b_out[r] = prod + (shift ? shift[r] : 0.0f);
+        }
+    }
+}
+
 static inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+hipError_t launch_fold_scale(const float *w, const float *b, size_t rows, size_t row_len, const float *scale, const float *shift,
+                             float *w_out, float *b_out, hipStream_t st)
+{
+    fold_scale_kernel<<<grid_for(rows * row_len + rows), kBlock, 0, st>>>(w, b, rows, row_len, scale, shift, w_out, b_out);
+    return hipGetLastError();
+}
 
 hipError_t launch_quantize_rows(const float *x, int8_t *q, size_t rows, size_t row_len, const int32_t *frac, hipStream_t st)
 {
@@ -269,8 +299,9 @@ struct ConcatParams {
     int nb;
 };
 
+// ldy: bytes between consecutive pixels of y (>= the branches' channels together)
 template <int VEC>
-__global__ void __launch_bounds__(kBlock) concat_kernel(ConcatParams p, int8_t *__restrict__ y, size_t pixels)
+__global__ void __launch_bounds__(kBlock) concat_kernel(ConcatParams p, int8_t *__restrict__ y, size_t pixels, int ldy)
 {
     const int Ct = p.off[p.nb];
     const int per_px = Ct / VEC;
@@ -283,7 +314,7 @@ __global__ void __launch_bounds__(kBlock) concat_kernel(ConcatParams p, int8_t *
         for (int j = 1; j < 8; j++)
             if (j < p.nb && c >= p.off[j]) br = j;
         const int8_t *src = p.x[br] + px * (size_t)p.C[br] + (c - p.off[br]);
-        int8_t *dst = y + px * (size_t)Ct + c;
+        int8_t *dst = y + px * (size_t)ldy + c;
         const int s = p.s[br];
         if (VEC == 16) {
             uint4 v = *(const uint4 *)src;
@@ -303,14 +334,14 @@ __global__ void __launch_bounds__(kBlock) concat_kernel(ConcatParams p, int8_t *
     }
 }
 
-hipError_t launch_concat(int nb, const int8_t *const *xs, const int *Cs, const int *fs, int8_t *y, int fy, size_t pixels,
-                         hipStream_t st)
+hipError_t launch_concat(int nb, const int8_t *const *xs, const int *Cs, const int *fs, int8_t *y, int ldy, int fy,
+                         size_t pixels, hipStream_t st)
 {
     ConcatParams p{};
     p.nb = nb;
     int off = 0;
     int vec = 16;
-    if (!aligned(y, 16)) vec = aligned(y, 4) ? 4 : 1;
+    if (!aligned(y, 16) || ldy % 16) vec = (aligned(y, 4) && ldy % 4 == 0) ? 4 : 1;
     for (int i = 0; i < nb; i++) {
         p.x[i] = xs[i];
         p.C[i] = Cs[i];
@@ -322,9 +353,9 @@ hipError_t launch_concat(int nb, const int8_t *const *xs, const int *Cs, const i
     for (int i = nb; i <= 8; i++) p.off[i] = off;
     size_t total = pixels * (size_t)(off / vec);
     int g = grid_for(total);
-    if (vec == 16) concat_kernel<16><<<g, kBlock, 0, st>>>(p, y, pixels);
-    else if (vec == 4) concat_kernel<4><<<g, kBlock, 0, st>>>(p, y, pixels);
-    else concat_kernel<1><<<g, kBlock, 0, st>>>(p, y, pixels);
+    if (vec == 16) concat_kernel<16><<<g, kBlock, 0, st>>>(p, y, pixels, ldy);
+    else if (vec == 4) concat_kernel<4><<<g, kBlock, 0, st>>>(p, y, pixels, ldy);
+    else concat_kernel<1><<<g, kBlock, 0, st>>>(p, y, pixels, ldy);
     return hipGetLastError();
 }
 

@@ -51,11 +51,15 @@ def _threshold(acc: torch.Tensor, relu: bool, rule: str) -> int:
 
 
 def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True, per_channel: bool = False,
-              rule: str = "maxabs"):
+              rule: str = "maxabs", match_joins: bool = False):
     """x: float32 NHWC images (or int8 codes when the network takes codes).  Returns
     (Quantized, dict of int8 tensors of the calibration batch).
     per_channel: one weight format per output channel instead of one per layer.
-    rule: "maxabs" (thresholds are maxima) or "search" (Algorithm 1; per-layer weight formats only)."""
+    rule: "maxabs" (thresholds are maxima) or "search" (Algorithm 1; per-layer weight formats only).
+    match_joins: the scales of a concat's inputs are matched at calibration time (Sec. 3: the explicit
+    downscale in front of a join) - a convolution that feeds only the concat takes the concat's format and
+    rounds its accumulators once, to that scale (a Plan built with fuse=True then lets it write straight
+    into the joined tensor)."""
     if rule not in ("maxabs", "search") or (rule == "search" and per_channel):
         raise ValueError("rule must be 'maxabs' or 'search' (the search with per-layer weight formats)")
     qz = Quantized()
@@ -70,6 +74,13 @@ def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True, 
             qz.frac[net.input_name] = B.fmt_from_absmax_f32(_read_f32(B.absmax_f32(x)))
         t[net.input_name] = B.quantize(x, qz.frac[net.input_name])
     last_use = _last_use(net)
+    if match_joins:
+        keep_tensors = True          # a branch convolution is run again when its concat is reached
+    readers: Dict[str, int] = {}
+    for nd in net.nodes:
+        for s in nd.srcs:
+            readers[s] = readers.get(s, 0) + 1
+    producer = {nd.dst: nd for nd in net.nodes}
     for idx, nd in enumerate(net.nodes):
         if nd.op == "conv":
             src = nd.srcs[0]
@@ -77,6 +88,10 @@ def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True, 
             wf, bf = net.weights(nd)
             wf = torch.from_numpy(wf).to(device)
             bf = torch.from_numpy(bf).to(device)
+            if getattr(net, "scale_layers", False):
+                # the affine layer behind the convolution is folded into the float weights before they are quantized
+                scale, shift = net.scale_shift(nd)
+                wf, bf = B.fold_scale(wf, bf, torch.from_numpy(scale).to(device), torch.from_numpy(shift).to(device))
             if per_channel:
                 # channel k's weights and bias at their own scale; its accumulators are then at f_in + f_w[k],
                 # and the output format is the finest that holds every channel's maximum
@@ -127,6 +142,21 @@ def calibrate(net, x: torch.Tensor, device="cuda:0", keep_tensors: bool = True, 
         elif nd.op == "concat":
             fs = [qz.frac[s] for s in nd.srcs]
             qz.frac[nd.dst] = nd.fixed_f_out if nd.fixed_f_out is not None else min(fs)
+            if match_joins:
+                for s in nd.srcs:
+                    pr = producer.get(s)
+                    if pr is not None and pr.op == "conv" and readers[s] == 1 and qz.frac[s] > qz.frac[nd.dst]:
+                        qz.frac[s] = qz.frac[nd.dst]
+                        psrc = pr.srcs[0]
+                        if pr.name in qz.w_frac_dev:
+                            fwk = qz.w_frac[pr.name]
+                            t[s], _ = B.conv_q_pc(t[psrc], qz.w[pr.name], qz.b[pr.name], qz.frac[psrc], qz.w_frac_dev[pr.name],
+                                                  qz.frac[s], pr.stride, pr.pad, pr.groups, pr.relu,
+                                                  frac_w_range=(int(fwk.min()), int(fwk.max())))
+                        else:
+                            t[s], _ = B.conv_q(t[psrc], qz.w[pr.name], qz.b[pr.name], qz.frac[psrc], qz.w_frac[pr.name],
+                                               qz.frac[s], pr.stride, pr.pad, pr.groups, pr.relu)
+                fs = [qz.frac[s] for s in nd.srcs]
             t[nd.dst] = B.concat_q([t[s] for s in nd.srcs], fs, qz.frac[nd.dst])
         elif nd.op in ("maxpool", "avgpool"):
             src = nd.srcs[0]
@@ -156,19 +186,27 @@ class Plan:
     synchronization."""
 
     def __init__(self, net, qz: Quantized, batch: int, device="cuda:0", keep_all: bool = True, fuse: bool = False):
-        """fuse: a convolution whose only consumer is the element-wise add that follows it directly
-        is run together with that add by one dfq_conv_q_add call where a fused kernel covers it
-        (same result; the convolution's own int8 tensor is then never produced)."""
+        """fuse: the joins are merged into the convolutions in front of them (Sec. 3) where that gives the
+        same bytes.  A convolution whose only consumer is the element-wise add that follows it directly
+        is run together with that add by one dfq_conv_q_add call where a fused kernel covers it (the
+        convolution's own int8 tensor is then never produced).  A convolution that feeds only a concat
+        and already produces the concat's format writes straight into its channel slice of the joined
+        tensor (no rescale is due, so no copy either); only the other branches pass through
+        dfq_concat_q_into."""
         self.net, self.qz, self.batch, self.device = net, qz, batch, device
         self.order = list(range(len(net.nodes)))                             # node indices in execution order
         self.fused: Dict[int, int] = self._fusable_pairs() if fuse else {}   # conv node index -> add node index
+        self.slice_of: Dict[str, tuple] = self._direct_concat_branches() if fuse else {}   # tensor -> (joined tensor, channel offset)
         self.buf: Dict[str, torch.Tensor] = {}
         H, W, Cc = net.shapes[net.input_name]
         self.buf[net.input_name] = torch.empty((batch, H, W, Cc), dtype=torch.int8, device=device)
         if keep_all:
             for nd in net.nodes:
-                P, Q, K = net.shapes[nd.dst]
-                self.buf[nd.dst] = torch.empty((batch, P, Q, K), dtype=torch.int8, device=device)
+                if nd.dst not in self.slice_of:
+                    P, Q, K = net.shapes[nd.dst]
+                    self.buf[nd.dst] = torch.empty((batch, P, Q, K), dtype=torch.int8, device=device)
+            for name, (dst, off) in self.slice_of.items():
+                self.buf[name] = self.buf[dst][..., off:off + net.shapes[name][2]]
         else:
             self._assign_pooled()
         P, Q, K = net.shapes[net.output_name]
@@ -213,6 +251,27 @@ class Plan:
                 pairs[j - 1] = j
         return pairs
 
+    def _direct_concat_branches(self) -> Dict[str, tuple]:
+        """Concat inputs that a convolution produces for the concat alone, in the concat's own format."""
+        net, qz = self.net, self.qz
+        readers: Dict[str, int] = {}
+        for nd in net.nodes:
+            for s in nd.srcs:
+                readers[s] = readers.get(s, 0) + 1
+        producer = {nd.dst: nd for nd in net.nodes}
+        out = {}
+        for nd in net.nodes:
+            if nd.op != "concat" or len(set(nd.srcs)) != len(nd.srcs):
+                continue
+            off = 0
+            for s in nd.srcs:
+                pr = producer.get(s)
+                if (pr is not None and pr.op == "conv" and readers.get(s, 0) == 1 and s != net.output_name
+                        and qz.frac[s] == qz.frac[nd.dst]):
+                    out[s] = (nd.dst, off)
+                off += net.shapes[s][2]
+        return out
+
     def _assign_pooled(self):
         """Reuses buffers whose tensor is dead (sized in bytes), to keep the footprint small."""
         net = self.net
@@ -234,6 +293,20 @@ class Plan:
                 nd_dst = net.nodes[self.fused[idx]].dst
             else:
                 nd_dst = nd.dst
+            view_of = None
+            if nd_dst in self.slice_of:
+                # a branch written straight into the joined tensor: that tensor's buffer is taken now
+                view_of = nd_dst
+                nd_dst = self.slice_of[view_of][0]
+            if nd_dst in owner:
+                # (the joined tensor of a concat whose buffer an earlier branch already took)
+                if view_of is not None:
+                    off = self.slice_of[view_of][1]
+                    self.buf[view_of] = self.buf[nd_dst][..., off:off + net.shapes[view_of][2]]
+                for s in nd.srcs:
+                    if last.get(s) == idx and s in owner and s != net.input_name and s != net.output_name:
+                        free.append(owner[s])
+                continue
             P, Q, K = net.shapes[nd_dst]
             need = self.batch * P * Q * K
             pick = None
@@ -243,6 +316,9 @@ class Plan:
             storage = free.pop(pick) if pick is not None else torch.empty(need, dtype=torch.int8, device=self.device)
             self.buf[nd_dst] = storage[:need].view(self.batch, P, Q, K)
             owner[nd_dst] = storage
+            if view_of is not None:
+                off = self.slice_of[view_of][1]
+                self.buf[view_of] = self.buf[nd_dst][..., off:off + net.shapes[view_of][2]]
             for s in nd.srcs:
                 if last.get(s) == idx and s in owner and s != net.input_name and s != net.output_name:
                     free.append(owner[s])
@@ -253,9 +329,10 @@ class Plan:
         skip = {self.net.nodes[i].dst for i in self.fused} if self._fused_ran is None else self._fused_ran
         last_at: Dict[int, str] = {}
         for name, tns in self.buf.items():          # insertion order = execution order
-            if name not in skip:
+            if name not in skip and name not in self.slice_of:
                 last_at[tns.data_ptr()] = name
-        return [n for n in self.buf if n not in skip and last_at[self.buf[n].data_ptr()] == n]
+        own = [n for n in self.buf if n not in skip and n not in self.slice_of and last_at[self.buf[n].data_ptr()] == n]
+        return own + [n for n, (dst, _) in self.slice_of.items() if dst in own]
 
     # ---- execution -------------------------------------------------------------------- #
     def _build_calls(self, x: torch.Tensor):
@@ -273,6 +350,11 @@ class Plan:
             calls.append((L.dfq_quantize, (x.data_ptr(), t[net.input_name].data_ptr(), x.numel(), f(qz.frac[net.input_name]))))
             names.append(None)
         fused_adds = set()
+
+        def ldy_of(name, K):
+            # bytes between pixels of a convolution's output: its own channels, or the joined tensor's
+            return int(t[self.slice_of[name][0]].shape[-1]) if name in self.slice_of else K
+
         for idx in self.order:
             nd = net.nodes[idx]
             if idx in fused_adds:
@@ -312,7 +394,7 @@ class Plan:
                 K = nd.K
                 calls.append((L.dfq_conv_q_pc, (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(),
                                                 t[nd.dst].data_ptr(), None, N, H, W, Cc, K, nd.R, nd.R, nd.stride, nd.pad,
-                                                nd.groups, K, f(qz.frac[src]), qz.w_frac_dev[nd.name].data_ptr(),
+                                                nd.groups, ldy_of(nd.dst, K), f(qz.frac[src]), qz.w_frac_dev[nd.name].data_ptr(),
                                                 int(qz.w_frac[nd.name].min()), int(qz.w_frac[nd.name].max()),
                                                 f(qz.frac[nd.dst]), int(nd.relu))))
             elif nd.op == "conv":
@@ -321,20 +403,35 @@ class Plan:
                 K = nd.K
                 calls.append((L.dfq_conv_q, (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(),
                                              t[nd.dst].data_ptr(), None, N, H, W, Cc, K, nd.R, nd.R, nd.stride, nd.pad,
-                                             nd.groups, K, f(qz.frac[src]), f(qz.w_frac[nd.name]), f(qz.frac[nd.dst]),
+                                             nd.groups, ldy_of(nd.dst, K), f(qz.frac[src]), f(qz.w_frac[nd.name]), f(qz.frac[nd.dst]),
                                              int(nd.relu))))
             elif nd.op == "eltwise":
                 a, b2 = nd.srcs
                 calls.append((L.dfq_eltwise_q, (t[a].data_ptr(), f(qz.frac[a]), t[b2].data_ptr(), f(qz.frac[b2]),
                                                 t[nd.dst].data_ptr(), f(qz.frac[nd.dst]), None, t[a].numel(), int(nd.relu))))
             elif nd.op == "concat":
-                nb = len(nd.srcs)
-                ptrs = (C.c_void_p * nb)(*[t[s].data_ptr() for s in nd.srcs])
-                Cs = (C.c_int * nb)(*[int(t[s].shape[-1]) for s in nd.srcs])
-                fs = (B.Fmt * nb)(*[f(qz.frac[s]) for s in nd.srcs])
-                keep.append((ptrs, Cs, fs))
-                pixels = t[nd.dst].numel() // t[nd.dst].shape[-1]
-                calls.append((L.dfq_concat_q, (nb, ptrs, Cs, fs, t[nd.dst].data_ptr(), f(qz.frac[nd.dst]), pixels)))
+                # runs of neighbouring branches that still need the rescale (or a copy); branches their
+                # convolution wrote straight into the joined tensor are already in place
+                Ct = int(t[nd.dst].shape[-1])
+                pixels = t[nd.dst].numel() // Ct
+                runs, off = [], 0
+                for s in nd.srcs:
+                    if s not in self.slice_of:
+                        if runs and runs[-1][1] == off:
+                            runs[-1][2].append(s)
+                            runs[-1][1] = off + int(t[s].shape[-1])
+                        else:
+                            runs.append([off, off + int(t[s].shape[-1]), [s]])
+                    off += int(t[s].shape[-1])
+                for start, _, members in runs:
+                    nb = len(members)
+                    ptrs = (C.c_void_p * nb)(*[t[s].data_ptr() for s in members])
+                    Cs = (C.c_int * nb)(*[int(t[s].shape[-1]) for s in members])
+                    fs = (B.Fmt * nb)(*[f(qz.frac[s]) for s in members])
+                    keep.append((ptrs, Cs, fs))
+                    calls.append((L.dfq_concat_q_into, (nb, ptrs, Cs, fs, t[nd.dst].data_ptr() + start, Ct, f(qz.frac[nd.dst]), pixels)))
+                    names.append(nd.name)
+                continue
             else:
                 src = nd.srcs[0]
                 N, H, W, Cc = t[src].shape

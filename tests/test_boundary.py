@@ -152,7 +152,16 @@ def test_other_calls_reject_bad_arguments(B):
     Cs = (C.c_int * 2)(4, 0)
     fs = (B.Fmt * 2)(f(3), f(4))
     assert L.dfq_concat_q(2, ptrs, Cs, fs, 3 << 20, f(3), 4, None) == B.ESHAPE
+    Cs2 = (C.c_int * 2)(4, 8)
+    assert L.dfq_concat_q_into(2, ptrs, Cs2, fs, 3 << 20, 11, f(3), 4, None) == B.ESHAPE              # row pitch below the channels
+    assert L.dfq_concat_q_into(2, ptrs, Cs2, fs, None, 16, f(3), 4, None) == B.EINVAL
+    assert L.dfq_concat_q_into(2, ptrs, Cs2, fs, (1 << 20) + 8, 16, f(3), 4, None) == B.EINVAL          # overlaps a branch
+    assert L.dfq_concat_q_into(2, ptrs, Cs2, fs, None, 16, f(3), 0, None) == B.OK
     assert L.dfq_absmax_f32(1 << 20, 4, None, None) == B.EINVAL
+    assert L.dfq_fold_scale_f32(1 << 20, None, 4, 8, None, None, 2 << 20, None, None) == B.EINVAL       # no scale
+    assert L.dfq_fold_scale_f32(1 << 20, 5 << 20, 4, 8, 3 << 20, None, 2 << 20, None, None) == B.EINVAL  # bias but no b_out
+    assert L.dfq_fold_scale_f32(1 << 20, None, 4, 8, 3 << 20, None, (1 << 20) + 16, None, None) == B.EINVAL   # partial overlap
+    assert L.dfq_fold_scale_f32(None, None, 0, 8, None, None, None, None, None) == B.OK
     assert L.dfq_absmax_i32(None, 4, 0, 1 << 20, None) == B.EINVAL
     assert L.dfq_hist_i32(1 << 20, 4, 0, 32, 2 << 20, None) == B.EINVAL                               # shift
     assert L.dfq_hist_i32(1 << 20, 4, 0, 3, None, None) == B.EINVAL

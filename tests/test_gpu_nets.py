@@ -173,6 +173,39 @@ def test_config2_inception_block(G):
     assert int(np.abs(out).max()) > 0 and int(out.min()) >= 0      # every branch ends in a ReLU
 
 
+@pytest.mark.parametrize("match_joins", [False, True], ids=["rescaling_concat", "matched_join_scales"])
+def test_config2_branches_written_into_the_joined_tensor(G, match_joins):
+    """Plan(fuse=True): a branch convolution whose format is the concat's writes straight into its channel slice (row
+    pitch of the joined tensor); with match_joins calibration (Sec. 3: input scales of a join are matched) that holds
+    for every branch and no concat kernel runs.  Formats, tensors and the joined output against the oracle."""
+    B, gnet = G
+    net = wl.inception_block(batch=64)
+    x = net.input_int8()
+    calib = x[:4]
+    qz_o, t_o = onet.calibrate(net, calib, match_joins=match_joins)
+    qz_g, t_g = gnet.calibrate(net, dev(calib), match_joins=match_joins)
+    _compare_calibration(net, qz_o, t_o, qz_g, t_g)
+    cat = net.nodes[-1]
+    if match_joins:
+        assert all(qz_o.frac[s] == qz_o.frac[cat.dst] for s in cat.srcs)
+    for keep_all in (True, False):
+        plan = gnet.Plan(net, qz_g, 64, keep_all=keep_all, fuse=True)
+        n_direct = len(plan.slice_of)
+        assert n_direct == (4 if match_joins else sum(1 for s in cat.srcs if qz_o.frac[s] == qz_o.frac[cat.dst])) and n_direct >= 1
+        for rep in range(2):
+            plan.buf[cat.dst].fill_(55)
+            plan.run_graph(dev(x)) if rep else plan.run(dev(x))
+            out = host(plan.buf[net.output_name])
+            for i in (0, 17, 63):
+                t = onet.infer(net, qz_o, x[i:i + 1])
+                assert np.array_equal(out[i:i + 1], t[net.output_name]), (keep_all, rep, i)
+                for name in plan.resident():
+                    if name != net.input_name:
+                        assert np.array_equal(host(plan.buf[name][i:i + 1]), t[name]), (i, name)
+        n_concat = sum(1 for fn, _ in plan._calls if fn.__name__.startswith("dfq_concat_q"))
+        assert n_concat == (0 if match_joins else 1) or n_direct < 4
+
+
 @pytest.mark.parametrize("which", ["mobilenet_v1", "resnet50"])
 def test_config3_and_4_networks(G, which):
     B, gnet = G
@@ -267,6 +300,23 @@ def test_per_channel_weight_formats_networks(G, which):
         assert np.array_equal(host(plan.run_graph(dev(x))), logits)
         if kw and which == "resnet50":
             assert sum(1 for fn, _ in plan._calls if fn.__name__ == "dfq_conv_q_pc_add") >= 4
+
+
+def test_network_with_scale_layers_folded(G):
+    """A ResNet-50-shaped network with an affine layer behind every convolution: both sides fold it into the float weights
+    with their own code before quantizing; formats, integer weights, tensors and logits agree."""
+    B, gnet = G
+    net = wl.resnet50(batch=8, hw=64, classes=100, scale_layers=True)
+    x = net.input_float()
+    calib = x[:2]
+    qz_o, t_o = onet.calibrate(net, calib)
+    qz_g, t_g = gnet.calibrate(net, dev(calib))
+    _compare_calibration(net, qz_o, t_o, qz_g, t_g)
+    plan = gnet.Plan(net, qz_g, 8, keep_all=False, fuse=True)
+    logits = host(plan.run(dev(x)))
+    for i in (0, 7):
+        t = onet.infer(net, qz_o, x[i:i + 1])
+        assert np.array_equal(logits[i:i + 1], onet.logits(net, qz_o, t))
 
 
 def test_threshold_search_calibration_network(G):

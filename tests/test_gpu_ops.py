@@ -238,6 +238,23 @@ def test_concat_q(B):
             assert np.array_equal(host(y), orc.concat_q(xs, fs, fy)), (Cs, fs, fy)
 
 
+def test_concat_q_into_a_channel_slice(B):
+    """A group of branches rescaled into a channel slice of a wider tensor: the slice equals the oracle's concat of
+    those branches, everything else is untouched."""
+    rng = np.random.default_rng(109)
+    for lead, Cs, Ct, off in [((2, 5, 5), (64, 32), 256, 128), ((1, 7, 7), (4, 8), 40, 12), ((3, 2, 2), (3, 5), 21, 7),
+                              ((2, 28, 28), (16,), 256, 240)]:
+        xs = [rng.integers(-128, 128, lead + (c,)).astype(np.int8) for c in Cs]
+        fs = [int(v) for v in rng.integers(2, 7, len(Cs))]
+        for fy in (min(fs), min(fs) - 3):
+            wide = torch.full(lead + (Ct,), 77, dtype=torch.int8, device=DEV)
+            B.concat_q_into([dev(x) for x in xs], fs, fy, wide, off)
+            got = host(wide)
+            n = sum(Cs)
+            assert np.array_equal(got[..., off:off + n], orc.concat_q(xs, fs, fy)), (Cs, fs, fy)
+            assert np.all(got[..., :off] == 77) and np.all(got[..., off + n:] == 77)
+
+
 @pytest.mark.parametrize("mode", ["max", "avg"])
 def test_pool_q(B, mode):
     rng = np.random.default_rng(106)
@@ -346,6 +363,20 @@ def test_row_wise_weight_preparation(B):
     for f_in in (-3, 4, 9):
         qb = host(B.quantize_i32_rows(dev(bf), dev(f_w), f_in))
         assert np.array_equal(qb, np.array([orc.quantize_i32(bf[k:k + 1], f_in + int(f_w[k]))[0] for k in range(37)], np.int32))
+
+
+def test_fold_scale(B):
+    """The folding pre-pass (affine layer behind a convolution into its float weights) bit for bit against the oracle."""
+    rng = np.random.default_rng(33)
+    for shape in [(37, 3, 3, 5), (64, 1, 1, 64), (1000, 2048), (3, 7, 7, 3)]:
+        w = (rng.standard_normal(shape) * rng.uniform(0.01, 3.0, (shape[0],) + (1,) * (len(shape) - 1))).astype(np.float32)
+        b = (rng.standard_normal(shape[0]) * 0.3).astype(np.float32)
+        scale = (rng.random(shape[0]) + 0.5).astype(np.float32)
+        shift = (rng.standard_normal(shape[0]) * 0.1).astype(np.float32)
+        for bb, sh in [(b, shift), (None, shift), (b, None), (None, None)]:
+            w_ref, b_ref = orc.fold_scale(w, bb, scale, sh)
+            w_g, b_g = B.fold_scale(dev(w), None if bb is None else dev(bb), dev(scale), None if sh is None else dev(sh))
+            assert np.array_equal(host(w_g), w_ref) and np.array_equal(host(b_g), b_ref), (shape, bb is None, sh is None)
 
 
 def test_absmax_per_channel(B):

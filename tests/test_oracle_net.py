@@ -144,3 +144,61 @@ def test_threshold_search_calibration():
         assert np.array_equal(t[k], t2[k])
     with pytest.raises(ValueError):
         onet.calibrate(net, x, per_channel=True, rule="search")
+
+
+def test_matched_join_scales():
+    """match_joins (Sec. 3: the scales of a join's inputs are matched; explicit downscale in front of the join): every
+    convolution that feeds only the concat ends at the concat's format, its slice of the joined tensor is its
+    accumulator rounded ONCE to that format (Fraction check on sampled elements), the concat is then a plain copy,
+    and nothing upstream of the branches changes."""
+    net = wl.inception_block(batch=2, hw=8)
+    x = net.input_int8()
+    qz0, t0 = onet.calibrate(net, x)
+    qz1, t1 = onet.calibrate(net, x, match_joins=True)
+    cat = net.nodes[-1]
+    f_cat = qz1.frac[cat.dst]
+    assert f_cat == qz0.frac[cat.dst] == min(qz0.frac[s] for s in cat.srcs)
+    assert any(qz0.frac[s] != f_cat for s in cat.srcs)                     # the default calibration does rescale some branch
+    producer = {nd.dst: nd for nd in net.nodes}
+    off = 0
+    rng = np.random.default_rng(5)
+    for s in cat.srcs:
+        nd = producer[s]
+        assert qz1.frac[s] == f_cat
+        assert np.array_equal(t1[cat.dst][..., off:off + nd.K], t1[s])         # copy, no second rounding
+        src = nd.srcs[0]
+        assert np.array_equal(t1[src], t0[src]) and qz1.frac[src] == qz0.frac[src]
+        _, acc = orc.conv_q(t1[src], qz1.w[nd.name], qz1.b[nd.name], 0, 0, 0, nd.stride, nd.pad, nd.groups, want_y=False,
+                            want_acc=True)
+        f_acc = qz1.frac[src] + qz1.w_frac[nd.name]
+        flat, out = acc.reshape(-1), t1[s].reshape(-1)
+        for i in rng.integers(0, flat.size, 200):
+            v = Fraction(max(int(flat[i]), 0) if nd.relu else int(flat[i])) * Fraction(2) ** (f_cat - f_acc)
+            lo = v.numerator // v.denominator
+            r = v - lo
+            want = lo + (1 if (r > Fraction(1, 2) or (r == Fraction(1, 2) and lo % 2)) else 0)
+            assert int(out[i]) == max(-127, min(127, want))
+        off += nd.K
+    # inference reproduces the calibration tensors with the matched formats as well
+    t2 = onet.infer(net, qz1, x)
+    for k in t1:
+        assert np.array_equal(t1[k], t2[k])
+
+
+def test_scale_layers_are_folded_before_quantizing():
+    """A network with an affine layer behind every convolution calibrates through the folding pre-pass: the integer
+    weights are the quantized folded weights, and the folding changes them."""
+    plain = wl.resnet50(batch=2, hw=32, classes=10)
+    net = wl.resnet50(batch=2, hw=32, classes=10, scale_layers=True)
+    x = net.input_float()
+    qz, t = onet.calibrate(net, x)
+    qz0, _ = onet.calibrate(plain, x)
+    nd = net.nodes[0]
+    wf, bf = net.weights(nd)
+    scale, shift = net.scale_shift(nd)
+    w2, b2 = orc.fold_scale(wf, bf, scale, shift)
+    f_w = orc.frac_from_absmax_f32(orc.absmax_f32(w2))
+    assert qz.w_frac[nd.name] == f_w and np.array_equal(qz.w[nd.name], orc.quantize(w2, f_w))
+    assert np.array_equal(qz.b[nd.name], orc.quantize_i32(b2, qz.frac["input"] + f_w))
+    assert not np.array_equal(qz.w[nd.name], qz0.w[nd.name])
+    assert np.isfinite(onet.logits(net, qz, t)).all()

@@ -678,3 +678,41 @@ def test_threshold_search_properties():
     assert orc.threshold_search(c2, j2, m2)[0] == min(129 * 2 ** j2 - 1, m2)
     # all zeros
     assert orc.threshold_search(np.array([5], np.uint64), 0, 0) == (0, 0.0)
+
+
+# --------------------------------------------------------------------------- #
+# Preprocessing: an affine layer behind a convolution folded into its weights (Sec. 3)
+# --------------------------------------------------------------------------- #
+
+def test_fold_scale_is_the_affine_layer_applied_to_the_convolution():
+    """z = scale[k] * (sum_j w[k][j] x[j] + b[k]) + shift[k] must equal the convolution with the folded weights:
+    checked in double precision on random data (the folded float32 values are within half an ulp of the exact
+    products), exactly for power-of-two scales, and row by row (the scale belongs to the OUTPUT channel)."""
+    rng = np.random.default_rng(77)
+    K, R, C = 6, 3, 5
+    w = rng.standard_normal((K, R, R, C)).astype(np.float32)
+    b = rng.standard_normal(K).astype(np.float32)
+    scale = (rng.random(K) + 0.5).astype(np.float32)
+    shift = (rng.standard_normal(K) * 0.1).astype(np.float32)
+    w2, b2 = orc.fold_scale(w, b, scale, shift)
+    x = rng.standard_normal((40, R * R * C))
+    y = x @ w.reshape(K, -1).astype(np.float64).T + b.astype(np.float64)
+    z = y * scale.astype(np.float64) + shift.astype(np.float64)
+    z2 = x @ w2.reshape(K, -1).astype(np.float64).T + b2.astype(np.float64)
+    assert np.abs(z - z2).max() <= 1e-6 * np.abs(x).sum(axis=1).max()
+    # half-ulp bound element by element, against the exact rational product
+    for k, i in [(0, 0), (3, 17), (5, 44)]:
+        exact = Fraction(float(w.reshape(K, -1)[k, i])) * Fraction(float(scale[k]))
+        got = Fraction(float(w2.reshape(K, -1)[k, i]))
+        assert abs(got - exact) <= abs(exact) * Fraction(1, 2 ** 24)
+    exact_b = Fraction(float(np.float32(b[2]) * np.float32(scale[2]))) + Fraction(float(shift[2]))     # product rounded first
+    assert abs(Fraction(float(b2[2])) - exact_b) <= abs(exact_b) * Fraction(1, 2 ** 24)
+    # powers of two: exact
+    p2 = np.array([0.5, 2.0, 1.0, 4.0, 0.25, 8.0], np.float32)
+    w3, b3 = orc.fold_scale(w, b, p2, None)
+    assert np.array_equal(w3, w * p2[:, None, None, None]) and np.array_equal(b3, b * p2)
+    # the scale of row k touches row k only; no bias and no shift give a zero bias
+    one_hot = np.ones(K, np.float32); one_hot[4] = 3.0
+    w4, b4 = orc.fold_scale(w, None, one_hot, None)
+    assert np.array_equal(w4[:4], w[:4]) and np.array_equal(w4[5], w[5]) and not np.array_equal(w4[4], w[4])
+    assert np.array_equal(b4, np.zeros(K, np.float32))

@@ -118,6 +118,8 @@ class Net:
     fixed_f_input: Optional[int] = None
     input_is_int8: bool = False
     f_input_codes: int = 0
+    scale_layers: bool = False          # every convolution is followed by a per-channel affine layer (batch norm
+                                        # in its inference form); each side folds it into the float weights itself
 
     # ---- construction helpers -------------------------------------------- #
     def _next_widx(self) -> int:
@@ -174,6 +176,15 @@ class Net:
         b = _rng(self.config, nd.widx + 1).standard_normal((nd.K,), dtype=np.float32) * np.float32(0.1)
         return w, b
 
+    def scale_shift(self, nd: Node):
+        """Parameters of the affine layer behind convolution nd (when the network has them): per output channel a
+        scale drawn uniformly from [0.5, 1.5) and a shift drawn from N(0, 0.1), float32."""
+        assert nd.op == "conv" and self.scale_layers
+        r = _rng(self.config, 5000 + nd.widx)
+        scale = (np.float32(0.5) + r.random((nd.K,), dtype=np.float32)).astype(np.float32)
+        shift = r.standard_normal((nd.K,), dtype=np.float32) * np.float32(0.1)
+        return scale, shift
+
     def macs_per_image(self) -> int:
         total = 0
         for nd in self.nodes:
@@ -203,10 +214,10 @@ def inception_block(batch: int = 64, hw: int = 28) -> Net:
     return net
 
 
-def mobilenet_v1(batch: int = 128, hw: int = 224, classes: int = 1000) -> Net:
+def mobilenet_v1(batch: int = 128, hw: int = 224, classes: int = 1000, scale_layers: bool = False) -> Net:
     """Config 3: 3x3/2 stem to 32, 13 depthwise-separable blocks, global average
     pool, fully connected layer.  Input N(0,1) images quantized at f = 5."""
-    net = Net(3, "mobilenet_v1", batch, (hw, hw, 3), fixed_f_input=5)
+    net = Net(3, "mobilenet_v1", batch, (hw, hw, 3), fixed_f_input=5, scale_layers=scale_layers)
     net.shapes["input"] = net.in_shape
     t = net.conv("stem", "input", 32, 3, stride=2, pad=1)
     widths = [64, 128, 128, 256, 256, 512, 512, 512, 512, 512, 512, 1024, 1024]
@@ -221,11 +232,11 @@ def mobilenet_v1(batch: int = 128, hw: int = 224, classes: int = 1000) -> Net:
     return net
 
 
-def resnet50(batch: int = 256, hw: int = 224, classes: int = 1000) -> Net:
+def resnet50(batch: int = 256, hw: int = 224, classes: int = 1000, scale_layers: bool = False) -> Net:
     """Config 4: 7x7/2 stem, 3x3/2 max-pool, bottleneck stages [3,4,6,3] (stride on
     the 3x3), projection shortcut on the first block of each stage, residual
     joins with ReLU, global average pool, fully connected layer."""
-    net = Net(4, "resnet50", batch, (hw, hw, 3))
+    net = Net(4, "resnet50", batch, (hw, hw, 3), scale_layers=scale_layers)
     net.shapes["input"] = net.in_shape
     t = net.conv("stem", "input", 64, 7, stride=2, pad=3)
     t = net.pool("maxpool", "pool1", t, 3, 2, pad=1)
