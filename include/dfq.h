@@ -85,6 +85,22 @@ dfq_status dfq_quantize_i32(const float *x, int32_t *q, size_t n, int32_t frac, 
 /* x[i] = q[i] * 2^-frac, exact in float. */
 dfq_status dfq_dequantize(const int8_t *q, float *x, size_t n, dfq_fmt fmt, dfq_stream stream);
 
+/* ---- the general (n, p) dynamic floating-point codes (Sec. 2.1, Eq. 1-5) ----------------------------
+ * A code has nbits <= 8 bits in one byte (upper bits zero): bit nbits-1 the sign, bits nbits-2 .. p the exponent
+ * field e (Eq. 4; none when p == nbits-1), bits p-1 .. 0 the significand field m.  Sign and magnitude (Eq. 2):
+ *   value = (-1)^sign * 2^-frac * (e == 0 ? m : 2^(e-1) * (2^p + m))
+ * with subnormals and with every exponent code a number (no infinities, no NaNs: the paper's default), so the
+ * largest value is 2^-frac * beta_max(nbits, p) (Eq. 5; dfq_beta_max).  nbits = 8, p = 6 or 7 is the int8 format
+ * of the rest of this library in sign-and-magnitude dress; p = 4 and p = 3 are the 8-bit members Sec. 5 reports
+ * as the most accurate.
+ * dfq_quantize_np: clamp to +-beta_max * 2^-frac, divide by 2^-frac, round to the nearest representable value
+ * (ties to the even significand); NaN -> code 0, +-Inf saturate; the code of -0 is never written.
+ * dfq_dequantize_np: the value above, exact in float (bits above nbits are ignored).
+ * 2 <= nbits <= 8, 0 <= p <= nbits-1, at most 5 exponent bits, frac in [-32, 32]: DFQ_EFMT otherwise.
+ * x: n floats, codes: n bytes, both DEVICE.  n == 0 is a no-op. */
+dfq_status dfq_quantize_np(const float *x, uint8_t *codes, size_t n, int nbits, int p, int frac, dfq_stream stream);
+dfq_status dfq_dequantize_np(const uint8_t *codes, float *x, size_t n, int nbits, int p, int frac, dfq_stream stream);
+
 /* ---- convolution / inner product (Sec. 2.2, Eq. 6) -------------------------------------
  * acc[n,p,q,k] = sum_{r,s,c} x[n, p*stride-pad+r, q*stride-pad+s, g*Cg+c] * w[k,r,s,c] + b[k]
  * with Cg = C/groups, g = k / (K/groups); taps outside the image contribute 0.

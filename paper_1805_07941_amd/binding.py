@@ -22,7 +22,7 @@ CONV_VARIANT_NAMES = {CONV_AUTO: "auto", CONV_DIRECT: "direct", CONV_MFMA: "mfma
                       CONV_DEPTHWISE: "depthwise", CONV_SMALLC: "smallc", CONV_POINTWISE: "pointwise"}
 
 EXPORTS = [
-    "dfq_status_string", "dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_conv_q",
+    "dfq_status_string", "dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_quantize_np", "dfq_dequantize_np", "dfq_conv_q",
     "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_hist_i32", "dfq_threshold_search", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_fold_scale_f32", "dfq_eltwise_q", "dfq_concat_q", "dfq_concat_q_into", "dfq_pool_q",
     "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_hist_shift", "dfq_fmt_from_absmax_i32_channels",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
@@ -62,6 +62,8 @@ def lib():
     L.dfq_quantize.argtypes = [vp, vp, sz, Fmt, vp]
     L.dfq_quantize_i32.argtypes = [vp, vp, sz, C.c_int32, vp]
     L.dfq_dequantize.argtypes = [vp, vp, sz, Fmt, vp]
+    L.dfq_quantize_np.argtypes = [vp, vp, sz, i32, i32, i32, vp]
+    L.dfq_dequantize_np.argtypes = [vp, vp, sz, i32, i32, i32, vp]
     conv_args = [vp, vp, vp, vp, vp] + [i32] * 11 + [Fmt, Fmt, Fmt, i32, vp]
     L.dfq_conv_q.argtypes = conv_args
     L.dfq_conv_q_variant.argtypes = [i32] + conv_args
@@ -91,7 +93,8 @@ def lib():
                  "dfq_conv_q_select", "dfq_conv_q_add", "dfq_eltwise_q", "dfq_concat_q", "dfq_concat_q_into", "dfq_pool_q", "dfq_absmax_f32",
                  "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_fmt_from_absmax_i32_channels",
                  "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_absmax_f32_rows", "dfq_quantize_rows",
-                 "dfq_quantize_i32_rows", "dfq_hist_i32", "dfq_threshold_search", "dfq_fold_scale_f32"):
+                 "dfq_quantize_i32_rows", "dfq_hist_i32", "dfq_threshold_search", "dfq_fold_scale_f32", "dfq_quantize_np",
+                 "dfq_dequantize_np"):
         getattr(L, name).restype = i32
     L.dfq_beta_max.restype = i64
     L.dfq_beta_max.argtypes = [i32, i32]
@@ -151,6 +154,21 @@ def dequantize(q: torch.Tensor, frac: int, out: Optional[torch.Tensor] = None, s
     _dev(q, torch.int8, "q")
     x = out if out is not None else torch.empty(q.shape, dtype=torch.float32, device=q.device)
     _check(lib().dfq_dequantize(_ptr(q), _ptr(x), q.numel(), fmt(frac), _stream(stream)), "dfq_dequantize")
+    return x
+
+
+def quantize_np(x: torch.Tensor, nbits: int, p: int, frac: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """float32 -> (nbits, p) dynamic floating-point codes (Eq. 2), one per byte (uint8 tensor)."""
+    _dev(x, torch.float32, "x")
+    q = out if out is not None else torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    _check(lib().dfq_quantize_np(_ptr(x), _ptr(q), x.numel(), int(nbits), int(p), int(frac), _stream(stream)), "dfq_quantize_np")
+    return q
+
+
+def dequantize_np(q: torch.Tensor, nbits: int, p: int, frac: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    _dev(q, torch.uint8, "q")
+    x = out if out is not None else torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    _check(lib().dfq_dequantize_np(_ptr(q), _ptr(x), q.numel(), int(nbits), int(p), int(frac), _stream(stream)), "dfq_dequantize_np")
     return x
 
 

@@ -174,6 +174,27 @@ dfq_status dfq_dequantize(const int8_t *q, float *x, size_t n, dfq_fmt fmt, dfq_
     return from_hip(launch_dequantize(q, x, n, fmt.frac, (hipStream_t)stream));
 }
 
+static bool np_ok(int nbits, int p, int frac)
+{
+    return nbits >= 2 && nbits <= 8 && p >= 0 && p <= nbits - 1 && nbits - 1 - p <= 5 && frac >= -32 && frac <= 32;
+}
+
+dfq_status dfq_quantize_np(const float *x, uint8_t *codes, size_t n, int nbits, int p, int frac, dfq_stream stream)
+{
+    if (!np_ok(nbits, p, frac)) return DFQ_EFMT;
+    if (n == 0) return DFQ_OK;
+    if (!x || !codes || overlaps(x, n * 4, codes, n)) return DFQ_EINVAL;
+    return from_hip(launch_quantize_np(x, codes, n, nbits, p, frac, (hipStream_t)stream));
+}
+
+dfq_status dfq_dequantize_np(const uint8_t *codes, float *x, size_t n, int nbits, int p, int frac, dfq_stream stream)
+{
+    if (!np_ok(nbits, p, frac)) return DFQ_EFMT;
+    if (n == 0) return DFQ_OK;
+    if (!x || !codes || overlaps(x, n * 4, codes, n)) return DFQ_EINVAL;
+    return from_hip(launch_dequantize_np(codes, x, n, nbits, p, frac, (hipStream_t)stream));
+}
+
 dfq_status dfq_conv_q_variant(dfq_conv_variant variant, const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y,
                               int32_t *acc_out, int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
                               int groups, int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu,

@@ -39,6 +39,8 @@ struct ConvArgs {
 hipError_t launch_quantize(const float *x, int8_t *q, size_t n, int frac, hipStream_t st);
 hipError_t launch_quantize_i32(const float *x, int32_t *q, size_t n, int frac, hipStream_t st);
 hipError_t launch_dequantize(const int8_t *q, float *x, size_t n, int frac, hipStream_t st);
+hipError_t launch_quantize_np(const float *x, uint8_t *q, size_t n, int nbits, int p, int frac, hipStream_t st);
+hipError_t launch_dequantize_np(const uint8_t *q, float *x, size_t n, int nbits, int p, int frac, hipStream_t st);
 hipError_t launch_eltwise(const int8_t *a, int fa, const int8_t *b, int fb, int8_t *y, int fy, int32_t *acc, size_t n,
                           int relu, hipStream_t st);
 hipError_t launch_concat(int nb, const int8_t *const *xs, const int *Cs, const int *fs, int8_t *y, int ldy, int fy,

@@ -81,6 +81,76 @@ __global__ void __launch_bounds__(kBlock) dequantize_scalar(const int8_t *__rest
         x[i] = (float)q[i] * inv_scale;
 }
 
+// ------------------------------------------------------------------------------------------
+// General (n, p) dynamic floating-point codes (Sec. 2.1, Eq. 1-5), n <= 8: one byte per code, bit n-1 the
+// sign, bits n-2 .. p the exponent field e, bits p-1 .. 0 the significand field m; value
+// 2^-frac * (e == 0 ? m : 2^(e-1) * (2^p + m)), every exponent code a number.
+// ------------------------------------------------------------------------------------------
+struct NpFmt {
+    int n, p;
+    float scale;      // 2^frac (quantize) or 2^-frac (dequantize)
+    float beta_max;   // Eq. 5; p+1 significant bits, exact in float
+};
+
+// Nearest representable magnitude, ties to the even significand.  v = |x| * 2^frac is exact in float; below
+// 2^(p+1) the representable values are the integers, in [2^(p+k), 2^(p+k+1)) the multiples of 2^k, so the
+// value is brought to an integer grid by an exact power-of-two factor, rounded by v_rndne_f32 and scaled back.
+__device__ __forceinline__ uint32_t np_quant_one(float x, const NpFmt &f)
+{
+    float v = x * f.scale;
+    if (!(v == v)) return 0u;                                        // NaN
+    const float a = fminf(fabsf(v), f.beta_max);
+    const int ex = (int)((__float_as_uint(a) >> 23) & 0xffu) - 127;  // floor(log2 a) for a >= 2^-126
+    const int k = max(ex - f.p, 0);
+    float r = ldexpf(__builtin_rintf(ldexpf(a, -k)), k);
+    r = fminf(r, f.beta_max);
+    if (r == 0.0f) return 0u;                                        // no negative zero
+    const uint32_t bits = __float_as_uint(r);
+    const int er = (int)((bits >> 23) & 0xffu) - 127;                // r = 2^er * 1.fraction, at most p fraction bits set
+    uint32_t code;
+    if (er < f.p) code = (uint32_t)(int)r;                           // subnormal: e = 0, m = r
+    else code = ((uint32_t)(er - f.p + 1) << f.p) | ((bits >> (23 - f.p)) & ((1u << f.p) - 1u));
+    return code | (v < 0.0f ? (1u << (f.n - 1)) : 0u);
+}
+
+__device__ __forceinline__ float np_dequant_one(uint32_t code, const NpFmt &f)
+{
+    const uint32_t m = code & ((1u << f.p) - 1u);
+    const uint32_t e = (code >> f.p) & ((1u << (f.n - 1 - f.p)) - 1u);   // no exponent field when p = n-1
+    const float mag = e == 0 ? (float)m : ldexpf((float)((1u << f.p) + m), (int)e - 1);
+    const float val = mag * f.scale;
+    return ((code >> (f.n - 1)) & 1u) ? -val : val;
+}
+
+__global__ void __launch_bounds__(kBlock) quantize_np_vec4(const float4 *__restrict__ x, uint32_t *__restrict__ q, size_t n4, NpFmt f)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (size_t)gridDim.x * kBlock) {
+        const float4 v = x[i];
+        q[i] = np_quant_one(v.x, f) | (np_quant_one(v.y, f) << 8) | (np_quant_one(v.z, f) << 16) | (np_quant_one(v.w, f) << 24);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) quantize_np_scalar(const float *__restrict__ x, uint8_t *__restrict__ q, size_t n, NpFmt f)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock)
+        q[i] = (uint8_t)np_quant_one(x[i], f);
+}
+
+__global__ void __launch_bounds__(kBlock) dequantize_np_vec4(const uint32_t *__restrict__ q, float4 *__restrict__ x, size_t n4, NpFmt f)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (size_t)gridDim.x * kBlock) {
+        const uint32_t w = q[i];
+        x[i] = make_float4(np_dequant_one(w & 0xffu, f), np_dequant_one((w >> 8) & 0xffu, f), np_dequant_one((w >> 16) & 0xffu, f),
+                           np_dequant_one(w >> 24, f));
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) dequantize_np_scalar(const uint8_t *__restrict__ q, float *__restrict__ x, size_t n, NpFmt f)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock)
+        x[i] = np_dequant_one(q[i], f);
+}
+
 // Row-wise forms for weights with one format per output channel: row r of x[rows][row_len] is
 // converted at the fractional length frac[r] (+ frac_add), read from device memory.
 __global__ void __launch_bounds__(kBlock) quantize_rows_kernel(const float *__restrict__ x, int8_t *__restrict__ q, size_t rows,
@@ -170,6 +240,45 @@ hipError_t launch_quantize(const float *x, int8_t *q, size_t n, int frac, hipStr
 hipError_t launch_quantize_i32(const float *x, int32_t *q, size_t n, int frac, hipStream_t st)
 {
     quantize_i32_kernel<<<grid_for(n), kBlock, 0, st>>>(x, q, n, ldexpf(1.0f, frac));
+    return hipGetLastError();
+}
+
+static NpFmt make_npfmt(int nbits, int p, int frac_signed)
+{
+    NpFmt f;
+    f.n = nbits;
+    f.p = p;
+    f.scale = ldexpf(1.0f, frac_signed);
+    const int emax = p == nbits - 1 ? 1 : (1 << (nbits - 1 - p)) - 1;
+    f.beta_max = p == nbits - 1 ? (float)((1 << (nbits - 1)) - 1) : ldexpf((float)((1 << (p + 1)) - 1), emax - 1);
+    return f;
+}
+
+hipError_t launch_quantize_np(const float *x, uint8_t *q, size_t n, int nbits, int p, int frac, hipStream_t st)
+{
+    const NpFmt f = make_npfmt(nbits, p, frac);
+    if (aligned(x, 16) && aligned(q, 4)) {
+        size_t n4 = n / 4;
+        if (n4) quantize_np_vec4<<<grid_for(n4), kBlock, 0, st>>>((const float4 *)x, (uint32_t *)q, n4, f);
+        size_t tail = n - n4 * 4;
+        if (tail) quantize_np_scalar<<<1, kBlock, 0, st>>>(x + n4 * 4, q + n4 * 4, tail, f);
+    } else {
+        quantize_np_scalar<<<grid_for(n), kBlock, 0, st>>>(x, q, n, f);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize_np(const uint8_t *q, float *x, size_t n, int nbits, int p, int frac, hipStream_t st)
+{
+    const NpFmt f = make_npfmt(nbits, p, -frac);
+    if (aligned(x, 16) && aligned(q, 4)) {
+        size_t n4 = n / 4;
+        if (n4) dequantize_np_vec4<<<grid_for(n4), kBlock, 0, st>>>((const uint32_t *)q, (float4 *)x, n4, f);
+        size_t tail = n - n4 * 4;
+        if (tail) dequantize_np_scalar<<<1, kBlock, 0, st>>>(q + n4 * 4, x + n4 * 4, tail, f);
+    } else {
+        dequantize_np_scalar<<<grid_for(n), kBlock, 0, st>>>(q, x, n, f);
+    }
     return hipGetLastError();
 }
 

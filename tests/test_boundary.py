@@ -138,6 +138,14 @@ def test_other_calls_reject_bad_arguments(B):
     assert L.dfq_quantize(1 << 20, 2 << 20, 16, B.Fmt(16, 4), None) == B.EFMT
     assert L.dfq_quantize(1 << 20, (1 << 20) + 8, 16, f(4), None) == B.EINVAL        # overlap
     assert L.dfq_quantize_i32(1 << 20, 2 << 20, 16, 65, None) == B.EFMT
+    assert L.dfq_quantize_np(1 << 20, 2 << 20, 16, 9, 4, 0, None) == B.EFMT                      # more than 8 bits
+    assert L.dfq_quantize_np(1 << 20, 2 << 20, 16, 8, 8, 0, None) == B.EFMT                      # p > n - 1
+    assert L.dfq_quantize_np(1 << 20, 2 << 20, 16, 8, 1, 0, None) == B.EFMT                      # six exponent bits
+    assert L.dfq_quantize_np(1 << 20, 2 << 20, 16, 8, 4, 33, None) == B.EFMT
+    assert L.dfq_quantize_np(1 << 20, None, 16, 8, 4, 0, None) == B.EINVAL
+    assert L.dfq_quantize_np(None, None, 0, 8, 4, 0, None) == B.OK
+    assert L.dfq_dequantize_np(1 << 20, (1 << 20) + 4, 16, 8, 4, 0, None) == B.EINVAL            # overlap
+    assert L.dfq_dequantize_np(1 << 20, 2 << 20, 16, 1, 0, 0, None) == B.EFMT
     assert L.dfq_dequantize(1 << 20, 2 << 20, 16, f(-33), None) == B.EFMT
     assert L.dfq_eltwise_q(1 << 20, f(30), 2 << 20, f(0), 3 << 20, f(0), None, 16, 0, None) == B.EFMT
     assert L.dfq_eltwise_q(1 << 20, f(3), 2 << 20, f(3), None, f(3), None, 16, 0, None) == B.EINVAL

@@ -55,6 +55,39 @@ def test_quantize_dequantize(B):
     B.quantize(torch.empty(0, dtype=torch.float32, device=DEV), 3)
 
 
+@pytest.mark.parametrize("n,p", [(8, 4), (8, 3), (8, 2), (8, 7), (8, 6), (8, 5), (6, 0), (7, 3), (6, 3), (5, 1), (4, 0), (2, 1), (2, 0)])
+def test_quantize_dequantize_np(B, n, p):
+    """The general (n, p) dynamic floating-point codes (Sec. 2.1): conversion kernels against the oracle, code for code -
+    random data over the whole range, every midpoint between neighbouring values (ties), every code, specials."""
+    import oracle.npfmt as F
+    rng = np.random.default_rng(1000 * n + p)
+    bm = F.beta_max(n, p)
+    reps = sorted(F.decode(c, n, p) for c in range(1 << (n - 1)))
+    for frac in (0, 5, -3, 32, -32):
+        gamma = bm * 2.0 ** -frac
+        x = (rng.standard_normal(1 << 16) * gamma / 3).astype(np.float32)
+        x[:4096] = (rng.standard_normal(4096) * 3.0 * 2.0 ** -frac).astype(np.float32)            # subnormal range
+        mids = np.array([(a + b) / 2.0 for a, b in zip(reps, reps[1:])], np.float64) * 2.0 ** -frac
+        sp = np.array([np.nan, np.inf, -np.inf, 3e38, -3e38, 0.0, -0.0, 1e-45, -1e-45, gamma, -gamma, gamma * 1.01], np.float32)
+        x = np.concatenate([x, mids.astype(np.float32), -mids.astype(np.float32), sp, np.array(reps, np.float64).astype(np.float32) * np.float32(2.0 ** -frac)])
+        codes_ref, _ = F.quantize(x, n, p, frac)
+        q = B.quantize_np(dev(x), n, p, frac)
+        assert np.array_equal(host(q), codes_ref.astype(np.uint8)), (n, p, frac)
+        assert np.array_equal(host(B.dequantize_np(q, n, p, frac)), F.dequantize(codes_ref, n, p, frac))
+        allc = np.arange(1 << n, dtype=np.uint8) if n < 8 else np.arange(256, dtype=np.uint8)
+        assert np.array_equal(host(B.dequantize_np(dev(allc), n, p, frac)), F.dequantize(allc, n, p, frac))
+    # unaligned views and a ragged tail take the narrow path
+    x = (rng.standard_normal(1003) * bm / 4).astype(np.float32)
+    q = torch.zeros(1010, dtype=torch.uint8, device=DEV)
+    B.quantize_np(dev(x)[1:], n, p, 0, out=q[3:1005])
+    assert np.array_equal(host(q[3:1005]), F.quantize(x[1:], n, p, 0)[0].astype(np.uint8))
+    B.quantize_np(torch.empty(0, dtype=torch.float32, device=DEV), n, p, 0)
+    with pytest.raises(B.DfqError):
+        B.quantize_np(dev(x), 9, 4, 0)
+    with pytest.raises(B.DfqError):
+        B.quantize_np(dev(x), 8, 1, 0)          # six exponent bits
+
+
 def test_quantize_i32(B):
     rng = np.random.default_rng(101)
     x = (rng.standard_normal(5000) * 0.1).astype(np.float32)
