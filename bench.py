@@ -73,8 +73,9 @@ def bench_layers(args):
 
     dev = "cuda:0"
     rows = []
-    for i in range(5):
-        L = wl.config1_layer(i, batch=args.batch)
+    layer_set = wl.RESNET_3X3_SET if args.layer_set == "3x3" else wl.RESNET_LAYER_SET
+    for i in range(len(layer_set)):
+        L = wl.config1_layer(i, batch=args.batch, layer_set=layer_set)
         wf, bf = torch.from_numpy(L["w_float"]).to(dev), torch.from_numpy(L["b_float"]).to(dev)
         f_in, pad = L["f_in"], L["pad"]
         f_w = B.fmt_from_absmax_f32(float(B.absmax_f32(wf).cpu()[0]))
@@ -92,7 +93,7 @@ def bench_layers(args):
             B.conv_q(xs[k % nset], w, b, f_in, f_w, f_out, 1, pad, 1, True, out=ys[k % nset])
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        iters = 20
+        iters = args.steps
         e0.record()
         for k in range(iters):
             B.conv_q(xs[k % nset], w, b, f_in, f_w, f_out, 1, pad, 1, True, out=ys[k % nset])
@@ -108,7 +109,8 @@ def bench_layers(args):
                          pct_mfma_peak=round(100 * ops / ms / 1e9 / INT8_MFMA_PEAK_TOPS, 1),
                          pct_hbm_peak=round(100 * by / ms / 1e6 / HBM_PEAK_GBS, 1), pct_roofline=round(100 * t_roof / ms, 1)))
         del xs, ys, x0
-    print(json.dumps({"metric": "int8 conv TOPS per dense layer of configs[1], standalone, b=%d" % args.batch, "unit": "TOPS",
+    what = "the four 3x3 shapes of the ResNet-50-shaped network" if args.layer_set == "3x3" else "configs[1]"
+    print(json.dumps({"metric": "int8 conv TOPS per dense layer of %s, standalone, b=%d" % (what, args.batch), "unit": "TOPS",
                       "n_gpus": 1, "dtype": "int8", "data": "synthetic", "buffers": "4 rotating sets per layer", "layers": rows}))
 
 
@@ -127,6 +129,10 @@ def main():
                     help="one weight format per output channel (dfq_conv_q_pc) instead of one per layer")
     ap.add_argument("--layers", action="store_true",
                     help="instead of the network pass: time the five dense layers of configs[1] on their own at --batch")
+    ap.add_argument("--layer-set", choices=["config1", "3x3"], default="config1",
+                    help="with --layers: the five layers of configs[1], or the four 3x3 shapes of the ResNet-50-shaped network")
+    ap.add_argument("--launch-classes", default=None,
+                    help="write the per-pass order of the matrix-core launches with their roofline class (JSON) to this file")
     ap.add_argument("--no-mfma-rate", action="store_true", help="skip the register-only matrix-instruction rate probe")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three 256 MiB device copies (a kernel of known traffic, to scale HBM counters by)")
@@ -248,7 +254,7 @@ def main():
     tops = 2 * macs_step / (ms_per_step * 1e-3) / 1e12
     imgs = args.batch / (ms_per_step * 1e-3)
 
-    roofline = None
+    roofline, roofline_other = None, None
     per_layer = []
     if record and events:
         dur = {}
@@ -258,6 +264,7 @@ def main():
         tsum = 0.0
         fused_names = {name for (fn, _), name in zip(plan._calls_for(x), plan.call_nodes) if fn.__name__ in ("dfq_conv_q_add", "dfq_conv_q_pc_add")}
         # launches by what bounds them at the published peaks: ops / 5 POP/s against bytes / 8 TB/s
+        layer_class = {}
         cls = {"mfma": dict(launches=0, ms=0.0, ops=0.0, bytes=0.0, roof_ms=0.0),
                "hbm": dict(launches=0, ms=0.0, ops=0.0, bytes=0.0, roof_ms=0.0)}
         for nd in mfma_nodes:
@@ -271,33 +278,50 @@ def main():
             ops += o
             tsum += ms
             t_m, t_h = o / (INT8_MFMA_PEAK_TOPS * 1e12) * 1e3, by / (HBM_PEAK_GBS * 1e9) * 1e3
-            c = cls["mfma" if t_m >= t_h else "hbm"]
+            layer_class[nd.name] = "mfma" if t_m >= t_h else "hbm"
+            c = cls[layer_class[nd.name]]
             c["launches"] += 1; c["ms"] += ms; c["ops"] += o; c["bytes"] += by; c["roof_ms"] += max(t_m, t_h)
-            per_layer.append(dict(layer=nd.name, us=round(ms * 1e3, 1), tops=round(o / ms / 1e9, 1),
+            per_layer.append(dict(layer=nd.name, bound=layer_class[nd.name], us=round(ms * 1e3, 1), tops=round(o / ms / 1e9, 1),
                                   gbs=round(by / ms / 1e6, 1), min_us=round(min(dur[nd.name]) * 1e3, 1),
                                   max_us=round(max(dur[nd.name]) * 1e3, 1)))
-        achieved = ops / (tsum * 1e-3) / 1e12
-        # HBM bytes per launch of these kernels as the memory counters saw them (the committed summary
-        # of two counter runs of this command, scaled by the copy probe), or null
-        traffic = None
+        # HBM bytes per launch as the memory counters saw them, per class: the committed summary of two counter
+        # runs of this command (FETCH_SIZE, WRITE_SIZE, each scaled by the copy probe), or null
+        traffic = {"hbm": None, "mfma": None, "source": None}
         tpath = os.path.join(ROOT, "profiles", "bench_resnet50_b256_hbm_traffic.txt")
         if os.path.exists(tpath):
             import re
-            m = re.search(r"^hbm_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(tpath).read(), re.M)
-            traffic = float(m.group(1)) if m else None
-        roofline = dict(bound="mfma", kernel="conv_mfma_kernel + conv_pw_kernel (dense int8 matrix-core convolutions, %d launches per step)" % len(mfma_nodes),
-                        achieved=round(achieved, 2), peak=INT8_MFMA_PEAK_TOPS, unit="TOP/s",
-                        frac=round(achieved / INT8_MFMA_PEAK_TOPS, 4), traffic=traffic,
-                        avg_launch_us=round(tsum / len(mfma_nodes) * 1e3, 2),
-                        ops_per_launch=ops / len(mfma_nodes), share_of_step=round(tsum / ms_per_step, 3),
-                        by_bound={
-                            "mfma": dict(launches=cls["mfma"]["launches"], us=round(cls["mfma"]["ms"] * 1e3, 1),
-                                         achieved_tops=round(cls["mfma"]["ops"] / max(cls["mfma"]["ms"], 1e-9) / 1e9, 1),
-                                         frac=round(cls["mfma"]["roof_ms"] / max(cls["mfma"]["ms"], 1e-9), 4)),
-                            "hbm": dict(launches=cls["hbm"]["launches"], us=round(cls["hbm"]["ms"] * 1e3, 1),
-                                        achieved_gbs=round(cls["hbm"]["bytes"] / max(cls["hbm"]["ms"], 1e-9) / 1e6, 1),
-                                        frac=round(cls["hbm"]["roof_ms"] / max(cls["hbm"]["ms"], 1e-9), 4))},
-                        mfma_rate_measured=mfma_rate)
+            txt = open(tpath).read()
+            for c in ("hbm", "mfma"):
+                m = re.search(r"^hbm_bytes_per_launch_%s_bound\s*=\s*([0-9.eE+]+)" % c, txt, re.M)
+                traffic[c] = float(m.group(1)) if m else None
+            traffic["source"] = "profiles/bench_resnet50_b256_hbm_traffic.txt (counter runs of this command; not measured by this run)"
+
+        def cls_obj(c, label):
+            d = cls[c]
+            n = max(d["launches"], 1)
+            if c == "mfma":
+                ach, peak, unit = d["ops"] / max(d["ms"], 1e-9) / 1e9, INT8_MFMA_PEAK_TOPS, "TOP/s"
+            else:
+                ach, peak, unit = d["bytes"] / max(d["ms"], 1e-9) / 1e6, HBM_PEAK_GBS, "GB/s"
+            return dict(bound=c, kernel=label % d["launches"], achieved=round(ach, 1), peak=peak, unit=unit,
+                        frac=round(ach / peak, 4), traffic=traffic[c], traffic_source=traffic["source"],
+                        launches=d["launches"], avg_launch_us=round(d["ms"] / n * 1e3, 2),
+                        algorithmic_bytes_per_launch=round(d["bytes"] / n), ops_per_launch=round(d["ops"] / n),
+                        share_of_step=round(d["ms"] / ms_per_step, 3))
+
+        hbm_obj = cls_obj("hbm", "conv_pw_kernel / conv_mfma_kernel: the %d launches per step that 8 TB/s bounds before 5 POP/s does "
+                                 "(1x1 layers of stages 2-4 and the joins fused into them)")
+        mfma_obj = cls_obj("mfma", "conv_mfma_kernel: the %d launches per step that 5 POP/s bounds (3x3 layers, stage-5 1x1 layers, FC)")
+        # `roofline` is the class that takes more of the step; the other one is carried beside it
+        roofline, roofline_other = (hbm_obj, mfma_obj) if cls["hbm"]["ms"] >= cls["mfma"]["ms"] else (mfma_obj, hbm_obj)
+        roofline["min_roofline_frac_all_%d_launches" % len(mfma_nodes)] = round((cls["hbm"]["roof_ms"] + cls["mfma"]["roof_ms"]) / tsum, 4)
+        roofline["mfma_rate_measured"] = mfma_rate
+        if args.launch_classes:
+            order = []
+            for (fn, _), name in zip(plan._calls_for(x), plan.call_nodes):
+                if name in mfma_names and fn.__name__ in ("dfq_conv_q", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add"):
+                    order.append(dict(layer=name, bound=layer_class[name]))
+            json.dump(order, open(args.launch_classes, "w"))
 
     # ---- outside the timed region: the oracle on a bounded sample of the same images, as the CPU baseline and
     # as the check of what was timed - the logits the timed plan produced for those images must equal the
@@ -327,6 +351,7 @@ def main():
         "images_per_s": round(imgs, 1),
         "pct_int8_mfma_peak": round(100 * tops / INT8_MFMA_PEAK_TOPS, 2),
         "roofline": roofline,
+        "roofline_other_class": roofline_other,
         "cpu_baseline": cpu,
         "parity_checked": parity_checked,
         "mfma_layers": per_layer,

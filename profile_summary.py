@@ -2,7 +2,9 @@
 
     python profile_summary.py stats <..._kernel_stats.csv> <..._kernel_trace.csv> <out.txt> --cmd "<command>"
     python profile_summary.py traffic <fetch_counter_collection.csv> <write_counter_collection.csv>
-           <out.txt> --cmd "<command>" [--launches-per-step 53] [--copy-bytes 268435456]
+           <out.txt> --cmd "<command>" --classes <launch_classes.json> [--copy-bytes 268435456]
+    python profile_summary.py counters <out.txt> <counter_collection.csv> ... --cmd "<command>" [--cmd ...]
+    python profile_summary.py layers <out.txt> <bench_layers.json> ... --cmd "<command>" [--cmd ...]
 
 `stats`: per-kernel call count and durations of the whole run, and the kernels of the last full
 pass (between the last two launches of the input quantization).
@@ -10,7 +12,11 @@ pass (between the last two launches of the input quantization).
 WRITE_SIZE counters (KiB per dispatch), each scaled by what the same counter reads for the copy
 probe of known size that `bench.py --copy-probe` runs (concat_kernel: reads and writes
 --copy-bytes each).  Averages are taken over the last --launches-per-step launches, i.e. one pass
-at the benchmark's batch size.
+at the benchmark's batch size, separately for the launches that the HBM roofline bounds and for those that
+the matrix-core roofline bounds (`bench.py --launch-classes` writes which launch of a pass is which).
+`layers`: the JSON lines of `bench.py --layers` runs as one table.
+`counters`: per kernel, the average per dispatch of every counter found in the given collection files
+(one file per `rocprofv3 --pmc` run), and the ratios the design notes quote.
 """
 from __future__ import annotations
 
@@ -81,24 +87,84 @@ def per_dispatch(path, counter):
 
 
 def cmd_traffic(a):
+    import json
+    classes = json.load(open(a.classes))                     # per-pass order of the matrix-core launches
+    n = len(classes)
     out = ["HBM traffic of the matrix-core convolution kernels from rocprofv3 counters",
            "commands (run from /tmp with TMPDIR=/tmp on the MI355X box), one counter per run:", "  " + a.cmd.replace("COUNTER", "FETCH_SIZE"),
-           "  " + a.cmd.replace("COUNTER", "WRITE_SIZE"), ""]
-    total = 0.0
+           "  " + a.cmd.replace("COUNTER", "WRITE_SIZE"),
+           f"launches of one pass: {n} ({sum(1 for c in classes if c['bound'] == 'hbm')} bound by the HBM roofline at the published peaks, "
+           f"{sum(1 for c in classes if c['bound'] == 'mfma')} by the matrix-core roofline)", ""]
+    total = {"hbm": 0.0, "mfma": 0.0, "all": 0.0}
     for path, counter, label in ((a.fetch_csv, "FETCH_SIZE", "read"), (a.write_csv, "WRITE_SIZE", "written")):
         disp = per_dispatch(path, counter)
-        copies = [v for n, v in disp if "concat_kernel" in n]
-        convs = [v for n, v in disp if is_conv(n)][-a.launches_per_step:]
+        copies = [v for nm, v in disp if "concat_kernel" in nm]
+        convs = [v for nm, v in disp if is_conv(nm)][-n:]
+        assert len(convs) == n, "fewer convolution dispatches than one pass has launches"
         copy_kib = sum(copies) / len(copies)
         factor = (a.copy_bytes / 1024.0) / copy_kib
-        conv_kib = sum(convs) / len(convs)
-        total += conv_kib * factor * 1024.0
         out.append(f"{counter}: copy probe ({len(copies)} launches, {a.copy_bytes} bytes {label} each) reads {copy_kib:.0f} KiB per launch "
                    f"-> scale factor {factor:.4f}")
-        out.append(f"{counter}: convolution kernels, last {len(convs)} launches: {conv_kib:.0f} KiB per launch raw, "
-                   f"{conv_kib * factor:.0f} KiB scaled")
+        for c in ("hbm", "mfma", "all"):
+            sel = [v for v, k in zip(convs, classes) if c == "all" or k["bound"] == c]
+            kib = sum(sel) / max(len(sel), 1)
+            total[c] += kib * factor * 1024.0
+            out.append(f"{counter}: {len(sel):3d} launches ({c:4s}): {kib:.0f} KiB per launch raw, {kib * factor:.0f} KiB scaled")
     out.append("")
-    out.append(f"hbm_bytes_per_launch = {total:.0f}")
+    out.append(f"hbm_bytes_per_launch_hbm_bound = {total['hbm']:.0f}")
+    out.append(f"hbm_bytes_per_launch_mfma_bound = {total['mfma']:.0f}")
+    out.append(f"hbm_bytes_per_launch = {total['all']:.0f}")
+    open(a.out, "w").write("\n".join(out) + "\n")
+
+
+def cmd_counters(a):
+    per = collections.OrderedDict()         # kernel -> counter -> [sum over dispatches, dispatches]
+    for path in a.csvs:
+        seen = collections.OrderedDict()
+        for r in csv.DictReader(open(path)):
+            key = (int(r["Dispatch_Id"]), r["Counter_Name"])
+            e = seen.setdefault(key, [short(r["Kernel_Name"]), 0.0])
+            e[1] += float(r["Counter_Value"])
+        for (_, counter), (kernel, v) in seen.items():
+            if a.only and a.only not in kernel:
+                continue
+            e = per.setdefault(kernel, collections.OrderedDict()).setdefault(counter, [0.0, 0])
+            e[0] += v; e[1] += 1
+    out = ["rocprofv3 counters per kernel (average per dispatch over all dispatches of the run)",
+           "commands (run from /tmp with TMPDIR=/tmp on the MI355X box), one counter group per run:"]
+    out += ["  " + c for c in a.cmd]
+    out.append("")
+    for kernel, ctr in per.items():
+        if max(e[1] for e in ctr.values()) < a.min_dispatches:
+            continue                          # (calibration launches of the general epilogue and the like)
+        out.append(kernel)
+        avg = {c: e[0] / e[1] for c, e in ctr.items()}
+        for c, e in ctr.items():
+            out.append(f"    {c:32s} {avg[c]:16.1f}   ({e[1]} dispatches)")
+        if "SQ_BUSY_CYCLES" in avg and "SQ_VALU_MFMA_BUSY_CYCLES" in avg and avg["SQ_BUSY_CYCLES"] > 0:
+            out.append(f"    matrix pipe busy / SQ busy cycles        {avg['SQ_VALU_MFMA_BUSY_CYCLES'] / avg['SQ_BUSY_CYCLES']:.3f}")
+        if "SQ_WAVE_CYCLES" in avg and avg["SQ_WAVE_CYCLES"] > 0:
+            for c in ("SQ_WAIT_INST_LDS", "SQ_WAIT_INST_ANY", "SQ_WAIT_ANY", "SQ_ACTIVE_INST_LDS", "SQ_ACTIVE_INST_VALU", "SQ_INST_CYCLES_VMEM"):
+                if c in avg:
+                    out.append(f"    {c} / SQ_WAVE_CYCLES{'':10s} {avg[c] / avg['SQ_WAVE_CYCLES']:.3f}")
+        if "SQ_LDS_BANK_CONFLICT" in avg and avg.get("SQ_LDS_IDX_ACTIVE", 0) > 0:
+            out.append(f"    LDS bank conflict cycles / active        {avg['SQ_LDS_BANK_CONFLICT'] / avg['SQ_LDS_IDX_ACTIVE']:.4f}")
+        out.append("")
+    open(a.out, "w").write("\n".join(out) + "\n")
+
+
+def cmd_layers(a):
+    import json
+    out = ["standalone layer timings (bench.py --layers: formats from the library's own calibration of each layer, four rotating",
+           "buffer sets per layer, HIP events over the launches)", "commands:"]
+    out += ["  " + c for c in a.cmd]
+    for path in a.jsons:
+        d = json.loads([x for x in open(path) if x.startswith("{")][-1])
+        out += ["", d["metric"]]
+        out.append(f"  {'layer':20s} {'shape':28s} {'kernel':10s} {'us':>7s} {'TOPS':>8s} {'GB/s':>8s} {'%mfma':>6s} {'%hbm':>6s} {'%roof':>6s}")
+        for r in d["layers"]:
+            out.append(f"  {r['layer']:20s} {r['shape']:28s} {r['kernel']:10s} {r['us']:7.1f} {r['tops']:8.1f} {r['gbs']:8.1f} "
+                       f"{r['pct_mfma_peak']:6.1f} {r['pct_hbm_peak']:6.1f} {r['pct_roofline']:6.1f}")
     open(a.out, "w").write("\n".join(out) + "\n")
 
 
@@ -109,10 +175,16 @@ def main():
     s.add_argument("stats_csv"); s.add_argument("trace_csv"); s.add_argument("out"); s.add_argument("--cmd", required=True)
     t = sub.add_parser("traffic")
     t.add_argument("fetch_csv"); t.add_argument("write_csv"); t.add_argument("out"); t.add_argument("--cmd", required=True)
-    t.add_argument("--launches-per-step", type=int, default=53)
+    t.add_argument("--classes", required=True)
     t.add_argument("--copy-bytes", type=int, default=256 << 20)
+    c = sub.add_parser("counters")
+    c.add_argument("out"); c.add_argument("csvs", nargs="+"); c.add_argument("--cmd", action="append", required=True)
+    c.add_argument("--only", default="conv_", help="keep kernels whose name contains this")
+    c.add_argument("--min-dispatches", type=int, default=3, help="skip kernels launched fewer times than this")
+    l = sub.add_parser("layers")
+    l.add_argument("out"); l.add_argument("jsons", nargs="+"); l.add_argument("--cmd", action="append", required=True)
     a = ap.parse_args()
-    (cmd_stats if a.what == "stats" else cmd_traffic)(a)
+    {"stats": cmd_stats, "traffic": cmd_traffic, "counters": cmd_counters, "layers": cmd_layers}[a.what](a)
 
 
 if __name__ == "__main__":

@@ -68,12 +68,22 @@ RESNET_LAYER_SET = [
 ]
 
 
-def config1_layer(i: int, batch: int = 32) -> dict:
+# the four 3x3 shapes of the ResNet-50-shaped network (stride 1), drawn like the layers of config 1
+RESNET_3X3_SET = [
+    ("s2_3x3_64_64",     56,  64,   64,  3),
+    ("s3_3x3_128_128",   28, 128,  128,  3),
+    ("s4_3x3_256_256",   14, 256,  256,  3),
+    ("s5_3x3_512_512",    7, 512,  512,  3),
+]
+
+
+def config1_layer(i: int, batch: int = 32, layer_set=None) -> dict:
     """Layer i of the set: int8 input at a per-layer f_in in {2..6}, float He-normal
     weights, float N(0, 0.1) bias; stride 1, pad R//2, ReLU.  The weight format,
-    the integer bias and f_out are for each implementation to derive."""
-    name, H, C, K, R = RESNET_LAYER_SET[i]
-    base = 10 * i
+    the integer bias and f_out are for each implementation to derive.
+    layer_set: RESNET_LAYER_SET (config 1, the default) or RESNET_3X3_SET (tensor indices from 100)."""
+    name, H, C, K, R = (layer_set or RESNET_LAYER_SET)[i]
+    base = 10 * i + (100 if layer_set is RESNET_3X3_SET else 0)
     f_in = int(_rng(1, base + 0).integers(2, 7))
     x = int8_activations(1, base + 1, (batch, H, H, C), f_in)
     w = (_rng(1, base + 2).standard_normal((K, R, R, C), dtype=np.float32)
