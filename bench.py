@@ -238,15 +238,17 @@ def main():
             nd = mid[len(mid) // 2]
             sets.append(("network_data", qz.w[nd.name].reshape(-1), plan.buf[nd.srcs[0]].reshape(-1)))
         mfma_rate = {"unit": "TOP/s", "what": "v_mfma_i32_32x32x32_i8 in a register-only loop, 2048 workgroups of 8 wavefronts; "
-                     "network_data = weights and input activations of a 3x3 layer of the pass"}
+                     "network_data = weights and input activations of a 3x3 layer of the pass; item_loop_* = the dense kernel's "
+                     "item pipeline (matrix instructions + barrier + LDS operand reads, no global loads) on the same data"}
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         for label, a_t, b_t in sets:
-            probe.mfma_rate(a_t, b_t, sink, 2048, 2000)          # warm-up: clocks settle under this load
-            e0.record()
-            ops_probe = probe.mfma_rate(a_t, b_t, sink, 2048, 8000)
-            e1.record()
-            torch.cuda.synchronize()
-            mfma_rate[label] = round(ops_probe / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+            for prefix, fn, n_warm, n_run in (("", probe.mfma_rate, 2000, 8000), ("item_loop_", probe.item_loop_rate, 1000, 4000)):
+                fn(a_t, b_t, sink, 2048, n_warm)          # warm-up: clocks settle under this load
+                e0.record()
+                ops_probe = fn(a_t, b_t, sink, 2048, n_run)
+                e1.record()
+                torch.cuda.synchronize()
+                mfma_rate[prefix + label] = round(ops_probe / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
 
     n_joins = sum(1 for nd in net.nodes if nd.op == "eltwise")
     n_fused = sum(1 for fn, _ in plan._calls_for(x) if fn.__name__ in ("dfq_conv_q_add", "dfq_conv_q_pc_add"))

@@ -61,6 +61,8 @@ typedef enum {
     DFQ_CONV_MFMA = 2,     /* implicit GEMM on int8 MFMA; groups == 1, C % 16 == 0 */
     DFQ_CONV_DEPTHWISE = 3,/* groups == C == K, channel-vectorized VALU kernel; C % 4 == 0 */
     DFQ_CONV_SMALLC = 4,   /* implicit GEMM for few input channels (first layers); groups == 1, S*C <= 32 */
+    DFQ_CONV_GROUPED = 6,  /* 1 < groups with (C/groups) % 4 == 0: vector-ALU kernel (4-way int8 dot products, weights in LDS);
+                              S in {1, 3, 5, 7}, stride 1 or 2, K*R*S*C/groups <= 64 KB, 4-byte aligned x and w */
     DFQ_CONV_POINTWISE = 5 /* int8 MFMA with the input tile resident in LDS; unpadded 1x1 stride 1, groups == 1,
                               C in {64, 128, 192, 256}, K % 64 == 0, K <= 4096, (K / BC) * (C / 64) >= 2 and
                               512*C + 192*BC + 4*K <= 160 KB of LDS with BC = (K % 128 ? 64 : 128),

@@ -24,6 +24,14 @@ extern "C" {
 int dfq_probe_mfma_rate(const int8_t *a_codes, const int8_t *b_codes, int32_t *sink, int blocks, int iters,
                         double *ops_out, void *stream);
 
+/* The same measurement for the item pipeline of the dense convolution kernel with its global loads left out: a
+ * workgroup of eight wavefronts on a 256 x 256 tile, three LDS stages filled once from the operand bytes, and per
+ * 64-byte step and wavefront sixteen matrix instructions, one workgroup barrier and twelve 128-bit LDS reads in the
+ * kernel's order - the ceiling of that kernel on such data with free loads, prologue and epilogue.  Arguments and
+ * return value as above (steps = reduction steps per workgroup; *ops_out = blocks * 8 * steps * 16 instructions). */
+int dfq_probe_item_loop_rate(const int8_t *a_codes, const int8_t *b_codes, int32_t *sink, int blocks, int steps,
+                             double *ops_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

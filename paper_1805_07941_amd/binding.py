@@ -17,9 +17,10 @@ LIB_PATH = os.path.join(_HERE, "libdfq.so")
 
 OK, EINVAL, ESHAPE, EFMT, EUNSUPPORTED, EDEVICE = range(6)
 POOL_MAX, POOL_AVG = 0, 1
-CONV_AUTO, CONV_DIRECT, CONV_MFMA, CONV_DEPTHWISE, CONV_SMALLC, CONV_POINTWISE = range(6)
+CONV_AUTO, CONV_DIRECT, CONV_MFMA, CONV_DEPTHWISE, CONV_SMALLC, CONV_POINTWISE, CONV_GROUPED = range(7)
 CONV_VARIANT_NAMES = {CONV_AUTO: "auto", CONV_DIRECT: "direct", CONV_MFMA: "mfma",
-                      CONV_DEPTHWISE: "depthwise", CONV_SMALLC: "smallc", CONV_POINTWISE: "pointwise"}
+                      CONV_DEPTHWISE: "depthwise", CONV_SMALLC: "smallc", CONV_POINTWISE: "pointwise",
+                      CONV_GROUPED: "grouped"}
 
 EXPORTS = [
     "dfq_status_string", "dfq_quantize", "dfq_quantize_i32", "dfq_dequantize", "dfq_quantize_np", "dfq_dequantize_np", "dfq_conv_q",

@@ -79,6 +79,7 @@ dfq_conv_variant select_variant(const ConvArgs &a, bool geometry_only = false)
     if (geometry_only ? conv_pw_geometry_ok(a) : conv_pw_supports(a)) return DFQ_CONV_POINTWISE;
     if (conv_mfma_supports(a)) return DFQ_CONV_MFMA;
     if (conv_smallc_supports(a)) return DFQ_CONV_SMALLC;
+    if (conv_grouped_supports(a)) return DFQ_CONV_GROUPED;
     return DFQ_CONV_DIRECT;
 }
 
@@ -100,6 +101,9 @@ dfq_status run_conv(dfq_conv_variant variant, const ConvArgs &a, hipStream_t st)
         case DFQ_CONV_SMALLC:
             if (!conv_smallc_supports(a)) return DFQ_EUNSUPPORTED;
             return from_hip(launch_conv_smallc(a, st));
+        case DFQ_CONV_GROUPED:
+            if (!conv_grouped_supports(a)) return DFQ_EUNSUPPORTED;
+            return from_hip(launch_conv_grouped(a, st));
         default:
             return DFQ_EINVAL;
     }

@@ -68,6 +68,8 @@ hipError_t launch_conv_depthwise(const ConvArgs &a, hipStream_t st);
 bool conv_pw_geometry_ok(const ConvArgs &a);
 bool conv_pw_supports(const ConvArgs &a);
 hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st);
+bool conv_grouped_supports(const ConvArgs &a);
+hipError_t launch_conv_grouped(const ConvArgs &a, hipStream_t st);
 bool conv_smallc_supports(const ConvArgs &a);
 hipError_t launch_conv_smallc(const ConvArgs &a, hipStream_t st);
 

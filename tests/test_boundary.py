@@ -180,7 +180,9 @@ def test_kernel_selection(B):
     assert s(1, 56, 56, 64, 64, 3, 3, 1, 1, 1) == B.CONV_MFMA
     assert s(1, 7, 7, 512, 2048, 1, 1, 1, 0, 1) == B.CONV_MFMA
     assert s(1, 8, 8, 0, 4, 1, 1, 1, 0, 1) == B.CONV_AUTO          # invalid geometry
-    assert s(1, 8, 8, 20, 10, 2, 3, 1, 1, 5) == B.CONV_DIRECT      # small groups
+    assert s(1, 8, 8, 20, 10, 2, 3, 1, 1, 5) == B.CONV_GROUPED     # groups of four channels
+    assert s(1, 8, 8, 15, 10, 2, 3, 1, 1, 5) == B.CONV_DIRECT      # groups of three channels: no kernel but the direct one
+    assert s(1, 8, 8, 64, 64, 3, 3, 1, 1, 64) == B.CONV_DEPTHWISE
 
 
 def test_binding_fails_loudly_without_the_library(B, monkeypatch):

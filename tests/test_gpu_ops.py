@@ -143,6 +143,13 @@ CONV_SHAPES = [
     (1, 9, 9, 24, 24, 3, 3, 1, 1, 24),           # depthwise, C % 16 != 0
     (1, 8, 8, 16, 32, 3, 3, 1, 1, 4),            # grouped
     (1, 6, 6, 20, 10, 2, 3, 1, 1, 5),            # grouped, odd kernel
+    (2, 19, 17, 128, 128, 3, 3, 1, 1, 32),       # grouped: 32 groups of 4 channels, ragged row blocks
+    (2, 19, 17, 128, 256, 3, 3, 2, 1, 16),       # grouped, stride 2, 8 input and 16 output channels per group
+    (1, 14, 14, 256, 256, 3, 3, 1, 1, 8),        # grouped, 32 channels per group
+    (3, 9, 11, 64, 96, 5, 5, 1, 2, 4),           # grouped 5x5
+    (2, 13, 13, 96, 48, 1, 1, 1, 0, 12),         # grouped 1x1
+    (1, 12, 10, 24, 36, 7, 7, 2, 3, 3),          # grouped 7x7 stride 2
+    (1, 9, 9, 12, 8, 3, 3, 1, 1, 4),             # groups of three channels: direct kernel
     (1, 33, 31, 16, 16, 3, 3, 1, 0, 1),          # no padding
     (1, 40, 40, 64, 256, 3, 3, 1, 1, 1),         # several tiles in both GEMM dimensions
     # unpadded 1x1 stride 1: the input-resident pointwise kernel (several pixel tiles, ragged last one)
@@ -173,7 +180,7 @@ def test_conv_q_random_shapes(B, shape):
     rng = np.random.default_rng(abs(hash(shape)) % (2 ** 31))
     x, w, b = _rand_conv(rng, N, H, W, C, K, R, S, g)
     xd, wd, bd = dev(x), dev(w), dev(b)
-    variants = [B.CONV_AUTO, B.CONV_DIRECT, B.CONV_MFMA, B.CONV_DEPTHWISE, B.CONV_SMALLC, B.CONV_POINTWISE]
+    variants = [B.CONV_AUTO, B.CONV_DIRECT, B.CONV_MFMA, B.CONV_DEPTHWISE, B.CONV_SMALLC, B.CONV_POINTWISE, B.CONV_GROUPED]
     first = True
     for f_in, f_w, f_out, relu, bias in [(4, 7, 4, 1, True), (3, 6, 2, 0, True), (2, 2, 4, 0, False), (5, 5, -3, 1, True),
                                          (1, 1, 6, 1, True)]:
@@ -339,6 +346,11 @@ def test_mfma_rate_probe_runs_the_stated_work(B):
     ops = probe.mfma_rate(ones, ones, sink, blocks, iters)
     assert ops == blocks * 8 * iters * 8 * 2 * 32 ** 3
     assert np.array_equal(host(sink), np.full(blocks * 512, 8 * 16 * 32 * iters, dtype=np.int32))
+    # the item-pipeline loop: 16 instructions per step and wavefront on all-ones operands, plus the two operand words the
+    # sink adds so that the last reads cannot be dropped (four bytes of ones each: 0x01010101)
+    ops = probe.item_loop_rate(ones, ones, sink, blocks, iters)
+    assert ops == blocks * 8 * iters * 16 * 2 * 32 ** 3
+    assert np.array_equal(host(sink), np.full(blocks * 512, 8 * 16 * 32 * 2 * iters + 2 * 0x01010101, dtype=np.int32))
 
 
 PC_SHAPES = [
@@ -353,6 +365,7 @@ PC_SHAPES = [
     (2, 10, 10, 32, 32, 3, 3, 1, 1, 32),         # depthwise
     (2, 11, 9, 64, 64, 3, 3, 2, 1, 64),          # depthwise stride 2
     (1, 8, 8, 16, 32, 3, 3, 1, 1, 4),            # grouped
+    (2, 19, 17, 128, 256, 3, 3, 2, 1, 16),       # grouped, stride 2
     (5, 1, 1, 256, 100, 1, 1, 1, 0, 1),          # fully connected
     (4, 223, 224, 64, 256, 1, 1, 2, 0, 1),       # enough tiles for the dense kernel's largest tile shape
 ]
