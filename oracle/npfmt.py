@@ -19,8 +19,8 @@ Readings:
   -3*2^p + 2^p = -2^(p+1), the two's complement weight of a (p+2)-bit number whose bit p is the
   hidden one; for e = 0 there is no hidden bit, and the same printed weight would leave a gap
   between -2^p and -2^(p+1): read there as -2^p (a (p+1)-bit two's complement number).
-* Conversion (Sec. 3: clamp to [-gamma, gamma], divide by alpha, "several more steps in order to
-  round"): gamma = alpha * beta_max; the quotient is rounded to the NEAREST representable beta, a
+* Conversion (Sec. 3: clamp to [-gamma, gamma], divide by alpha, then rounding steps the paper does not
+  spell out): gamma = alpha * beta_max; the quotient is rounded to the NEAREST representable beta, a
   tie going to the neighbour with the even significand field (IEEE 754's default, of which the
   format is declared an extension); NaN converts to 0.  The converter emits sign-and-magnitude
   codes (the symmetric set); -0 is never emitted.

@@ -1,6 +1,6 @@
 """Pins of the (n, p) dynamic floating-point oracle (Sec. 2.1, Eq. 1-5) against what the paper and the
-mathematics fix: Eq. 5's closed form (golden values), the code sets the paper names (p = 6 "a.k.a. int8",
-p = 2 "a.k.a. truncated half-precision"), IEEE binary16 as numpy implements it (the (16, 10) member of the
+mathematics fix: Eq. 5's closed form (golden values), the code sets the paper names (Sec. 5: p = 6 is int8,
+p = 2 a half-precision float cut to its top byte), IEEE binary16 as numpy implements it (the (16, 10) member of the
 family without its infinities), ordinary two's complement, and the properties of round-to-nearest."""
 import os
 from fractions import Fraction
@@ -51,12 +51,12 @@ def test_code_set_structure(n, p):
 
 
 def test_the_formats_the_paper_names():
-    # "p = 6, a.k.a. int8" (Sec. 5) and p = n - 1: the integers -127 .. 127, sign and magnitude
+    # p = 6 (which Sec. 5 equates with int8) and p = n - 1: the integers -127 .. 127, sign and magnitude
     for p in (6, 7):
         assert sorted(F.decode(c, 8, p) for c in range(256)) == sorted(list(range(-127, 128)) + [0])
     # Eq. 3 with p = n - 1 is ordinary two's complement
     assert [F.decode_twos(c, 8, 7) for c in range(256)] == np.arange(256, dtype=np.uint8).view(np.int8).tolist()
-    # "p = 2, a.k.a. truncated half-precision": the top byte of an IEEE binary16, scaled by 2^16; and (16, 10) IS binary16
+    # p = 2 (Sec. 5: a truncated half-precision float): the top byte of an IEEE binary16, scaled by 2^16; and (16, 10) IS binary16
     # scaled by 2^24 - on every code that binary16 does not spend on infinities and NaNs
     for c in range(256):
         if (c >> 2) & 31 != 31:
