@@ -1,0 +1,426 @@
+// Convolution on 8-bit dynamic floating-point codes with up to twelve-bit integers (Sec. 2.1: (8, p) with p >= 4,
+// |beta| <= beta_max(8, 4) = 1984), exact as Eq. 6 asks for, on the int8 matrix cores.
+//
+// Eq. 6 sums the integer products beta_x * beta_w without loss; for (8, 4) operands Eq. 8 gives 36 bits for the deepest
+// reduction of a ResNet-50-shaped network (3 x 3 x 512 terms), and Eq. 9 allows a 32-bit accumulator 545 terms only.
+// The chip has no matrix instruction with 12-bit operands, but the sum splits exactly into sums it has: write every
+// operand in two sign-and-magnitude digits of base 64,
+//     beta = 64 * h + l,   |h| <= 31, |l| <= 63   (both of the sign of beta),
+// then  sum beta_x beta_w = 4096 * A + 64 * B + C  with  A = sum h_x h_w,  C = sum l_x l_w,  B = sum (h_x l_w + l_x h_w),
+// and B = D - A - C with D = sum (h_x + l_x)(h_w + l_w)  (|h + l| <= 94 is an int8 too): three int8 matrix products
+// per block instead of four.  A, C and D are int32 accumulators (|D| <= 8836 per term: exact for reductions of up to
+// 29 277 terms, checked by the launcher); once per tile they are combined in 64-bit arithmetic,
+//     sum = 64 * (63 * A + D - C) + C,
+// the bias is added, ReLU applied, and the value times 2^-shift is rounded ONCE to the output format: nearest
+// representable integer, ties to the even significand field, saturation at +-beta_max.
+//
+// Tensors of this path travel between kernels as their two digit planes (int8 each, NHWC / [K][R][S][C]): a code is
+// decoded once, by the kernel that produces it (np_digits_kernel for inputs and weights, the epilogue here for
+// activations), not once per use; the third operand h + l of the weights is a plane of its own (weights are
+// static), that of the activations is formed in registers from the two planes (a carry-free byte-wise add, six
+// instructions per 4 codes).  The epilogue writes the digit planes of its result for the next layer and, if asked,
+// the codes themselves.
+//
+// conv_np_mfma_kernel: implicit GEMM, one tile of BP pixels x BC channels per workgroup of four wavefronts, the
+// reduction axis in 64-byte steps through a ring of three LDS stages of (2 BP + 3 BC) rows filled by direct
+// global -> LDS loads two steps ahead; rows are 64 bytes with the 16-byte pieces XOR-swizzled as in the int8 kernels.
+// conv_np_direct_kernel: one output per lane, any geometry (groups, C not a multiple of 64).
+#include "conv_ring.hpp"
+
+namespace dfq {
+
+namespace {
+
+// ---- scalar pieces ------------------------------------------------------------------------------------------------
+
+struct NpRound {
+    int shift;          // f_x + f_w - f_y
+    int p;              // significand bits of the output format
+    float beta_max;     // Eq. 5 for the output format (at most 12 bits: exact in float)
+    int relu;
+};
+
+// The accumulator value v times 2^-shift, rounded to the nearest integer representable with p + 1 significant bits
+// (step 1 below 2^(p+1)), ties to the even significand, magnitude clamped to beta_max.  |v| < 2^62.
+// The magnitude is first cut to 23 bits with a sticky bit for what was cut (the rounding position is at least 15
+// bits above it), which a float holds exactly; the rest is the conversion of a float to the format: scale by an exact
+// power of two so that the step becomes 1, round to nearest even, scale back.
+__device__ __forceinline__ int np_round_acc(long long v, const NpRound &f)
+{
+    if (f.relu && v < 0) v = 0;
+    const bool neg = v < 0;
+    const unsigned long long a = neg ? (unsigned long long)(-v) : (unsigned long long)v;
+    const int lz = a ? __clzll((long long)a) : 64;
+    const int t = max(41 - lz, 0);                       // bits to cut: the leading bit goes to position 22
+    unsigned m = (unsigned)(a >> t);
+    if (((unsigned long long)m << t) != a) m |= 1u;      // sticky
+    float x = ldexpf((float)m, t - f.shift);
+    x = fminf(x, f.beta_max);
+    const int ex = (int)((__float_as_uint(x) >> 23) & 0xffu) - 127;
+    const int k = max(ex - f.p, 0);
+    float r = ldexpf(__builtin_rintf(ldexpf(x, -k)), k);
+    r = fminf(r, f.beta_max);
+    const int beta = (int)r;
+    return neg ? -beta : beta;
+}
+
+// Eq. 2 inverted: the sign-and-magnitude code of a representable integer (8 bits, p significand bits); +0 for 0.
+__device__ __forceinline__ unsigned np_code_of(int beta, int p)
+{
+    const int mag = beta < 0 ? -beta : beta;
+    if (mag == 0) return 0u;
+    const int msb = 31 - __clz(mag);
+    const unsigned code = msb < p ? (unsigned)mag : (((unsigned)(msb - p + 1) << p) | (((unsigned)mag >> (msb - p)) & ((1u << p) - 1u)));
+    return code | (beta < 0 ? 0x80u : 0u);
+}
+
+// Eq. 2: the integer of a code of the format (8, p)
+__device__ __forceinline__ int np_beta_of(unsigned code, int p)
+{
+    const unsigned m = code & ((1u << p) - 1u);
+    const unsigned e = (code >> p) & ((1u << (7 - p)) - 1u);
+    const int mag = e ? (int)(((1u << p) + m) << (e - 1)) : (int)m;
+    return (code & 0x80u) ? -mag : mag;
+}
+
+__device__ __forceinline__ void np_split(int beta, int &h, int &l)
+{
+    const int mag = beta < 0 ? -beta : beta;
+    const int hu = mag >> 6, lu = mag & 63;
+    h = beta < 0 ? -hu : hu;
+    l = beta < 0 ? -lu : lu;
+}
+
+// byte-wise h + l of four int8 pairs (no carry between bytes; every true sum fits a byte)
+__device__ __forceinline__ int add_bytes(int h, int l)
+{
+    return (int)((((unsigned)h & 0x7f7f7f7fu) + ((unsigned)l & 0x7f7f7f7fu)) ^ (((unsigned)h ^ (unsigned)l) & 0x80808080u));
+}
+
+// ---- codes -> digit planes ----------------------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(256) np_digits_kernel(const uint8_t *__restrict__ codes, size_t n, int p, int8_t *__restrict__ hi,
+                                                        int8_t *__restrict__ lo, int8_t *__restrict__ sum)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        int h, l;
+        np_split(np_beta_of(codes[i], p), h, l);
+        hi[i] = (int8_t)h;
+        lo[i] = (int8_t)l;
+        if (sum) sum[i] = (int8_t)(h + l);
+    }
+}
+
+// ---- direct form --------------------------------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(256) conv_np_direct_kernel(NpConvArgs a)
+{
+    const int Cg = a.C / a.groups;
+    const int Kg = a.K / a.groups;
+    const size_t total = (size_t)a.N * a.P * a.Q * a.K;
+    NpRound rnd = {a.shift, a.p_y, (float)a.beta_max, a.relu};
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int k = (int)(i % a.K);
+        const size_t pix = i / a.K;
+        const int q = (int)(pix % a.Q);
+        const size_t t = pix / a.Q;
+        const int p = (int)(t % a.P);
+        const int n = (int)(t / a.P);
+        const int g = k / Kg;
+        long long acc = a.b ? (long long)a.b[k] : 0;
+        for (int r = 0; r < a.R; r++) {
+            const int ih = p * a.stride - a.pad + r;
+            if (ih < 0 || ih >= a.H) continue;
+            for (int s = 0; s < a.S; s++) {
+                const int iw = q * a.stride - a.pad + s;
+                if (iw < 0 || iw >= a.W) continue;
+                const size_t xo = (((size_t)n * a.H + ih) * a.W + iw) * a.C + (size_t)g * Cg;
+                const size_t wo = (((size_t)k * a.R + r) * a.S + s) * Cg;
+                for (int c = 0; c < Cg; c++)
+                    acc += (long long)((64 * (int)a.xh[xo + c] + (int)a.xl[xo + c]) * (64 * (int)a.wh[wo + c] + (int)a.wl[wo + c]));
+            }
+        }
+        const int beta = np_round_acc(acc, rnd);
+        if (a.y) a.y[i] = (uint8_t)np_code_of(beta, a.p_y);
+        int h, l;
+        np_split(beta, h, l);
+        if (a.yh) a.yh[i] = (int8_t)h;
+        if (a.yl) a.yl[i] = (int8_t)l;
+    }
+}
+
+// ---- matrix-core form ---------------------------------------------------------------------------------------------
+
+struct NpConvParams {
+    NpConvArgs a;
+    int M;                  // N * P * Q output pixels
+    int nitems;             // 64-byte steps of the reduction: R * S * C / 64
+    int csteps;             // C / 64
+    int tiles_c;            // channel tiles
+    unsigned x_bytes, w_bytes;
+    FastDiv div_q, div_p, div_tc;
+};
+
+template <int BP, int BC>
+__global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
+{
+    constexpr int NSTAGES = 3;
+    constexpr int ROWS = 2 * BP + 3 * BC;                 // LDS rows of 64 bytes per stage: x_h, x_l, w_h, w_l, w_s
+    constexpr int XH = 0, XL = BP, WH = 2 * BP, WL = 2 * BP + BC, WS = 2 * BP + 2 * BC;
+    constexpr int XJ = BP / 64, WJ = BC / 64;             // 16-row chunks per wavefront, operand plane and step
+    constexpr int LPW = 2 * XJ + 3 * WJ;                  // loads per wavefront and step
+    static_assert(BP % 64 == 0 && BC % 64 == 0, "whole chunks for four wavefronts");
+    constexpr int WP = BP / 2, WC = BC / 2;               // wavefront tile (2 x 2 wavefronts)
+    constexpr int PT = WP / 32, CT = WC / 32;
+    static_assert(PT * CT == 4, "twelve accumulator tiles per wavefront");
+
+    extern __shared__ uint4 lds[];
+    const NpConvArgs &a = prm.a;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // tile of this workgroup: ids are dealt round-robin to the 8 XCDs; renumbered so that each XCD owns a contiguous
+    // range, the channel tiles of one pixel tile (same input rows) then meet in one L2
+    const int G = gridDim.x;
+    int lb = blockIdx.x;
+    {
+        const int per = G / 8, rem = G % 8, xcd = lb % 8, idx = lb / 8;
+        lb = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+    }
+    const int pt = fastdiv(lb, prm.div_tc);
+    const int ct = lb - pt * prm.tiles_c;
+
+    const v4i xh_rsrc = make_rsrc(a.xh, prm.x_bytes), xl_rsrc = make_rsrc(a.xl, prm.x_bytes);
+    const v4i wh_rsrc = make_rsrc(a.wh, prm.w_bytes), wl_rsrc = make_rsrc(a.wl, prm.w_bytes), ws_rsrc = make_rsrc(a.ws, prm.w_bytes);
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char *)(char *)&lds[0];
+
+    // ---- producer: lane l of a wavefront-wide load supplies row l/4 of a 16-row chunk, physical piece l%4, which holds
+    // logical piece (l%4) ^ ((row>>2)&3)
+    const int lrow = lane >> 2;
+    const int lp = (lane & 3) ^ ((lane >> 4) & 3);
+    int ih0[XJ], iw0[XJ], xbase[XJ];
+#pragma unroll
+    for (int j = 0; j < XJ; j++) {
+        const int m = pt * BP + 16 * (wave + 4 * j) + lrow;
+        if (m < prm.M) {
+            const int t = fastdiv(m, prm.div_q);
+            const int oq = m - t * a.Q;
+            const int n = fastdiv(t, prm.div_p);
+            const int op = t - n * a.P;
+            ih0[j] = op * a.stride - a.pad;
+            iw0[j] = oq * a.stride - a.pad;
+            xbase[j] = ((n * a.H + ih0[j]) * a.W + iw0[j]) * a.C + lp * 16;
+        } else {
+            ih0[j] = -(1 << 28);      // no kernel row is inside the image
+            iw0[j] = 0;
+            xbase[j] = 0;
+        }
+    }
+    unsigned woff[WJ];
+#pragma unroll
+    for (int j = 0; j < WJ; j++) {
+        // LDS row i = 8g + 4h + e of a 32-row group receives channel 16h + 4g + e: the matrix instruction then leaves 16
+        // consecutive channels in each lane
+        const int rr = 16 * (wave + 4 * j) + lrow;
+        const int i32 = rr & 31;
+        const int k = ct * BC + (rr & ~31) + 16 * ((i32 >> 2) & 1) + 4 * (i32 >> 3) + (i32 & 3);
+        woff[j] = k < a.K ? (unsigned)(k * (a.R * a.S * a.C) + lp * 16) : kOutOfRange;
+    }
+    int p_r = 0, p_s = 0, p_c = 0, p_it = 0;     // kernel row, kernel column, channel step and index of the step fetched next
+    auto issue = [&](int stage) __attribute__((always_inline)) {
+        const int tap_off = (p_r * a.W + p_s) * a.C + p_c * kStepBytes;
+        const unsigned sbase = lds_base + (unsigned)(stage * ROWS) * 64u + (unsigned)wave * 1024u;
+#pragma unroll
+        for (int j = 0; j < XJ; j++) {
+            const bool ok = (unsigned)(ih0[j] + p_r) < (unsigned)a.H && (unsigned)(iw0[j] + p_s) < (unsigned)a.W;
+            const unsigned off = ok ? (unsigned)(xbase[j] + tap_off) : kOutOfRange;
+            load_piece_to_lds(off, xh_rsrc, (unsigned)__builtin_amdgcn_readfirstlane((int)(sbase + (unsigned)(XH * 64 + j * 4096))));
+            load_piece_to_lds(off, xl_rsrc, (unsigned)__builtin_amdgcn_readfirstlane((int)(sbase + (unsigned)(XL * 64 + j * 4096))));
+        }
+        const unsigned step_off = (unsigned)p_it * kStepBytes;
+#pragma unroll
+        for (int j = 0; j < WJ; j++) {
+            load_piece_to_lds(woff[j] + step_off, wh_rsrc, (unsigned)__builtin_amdgcn_readfirstlane((int)(sbase + (unsigned)(WH * 64 + j * 4096))));
+            load_piece_to_lds(woff[j] + step_off, wl_rsrc, (unsigned)__builtin_amdgcn_readfirstlane((int)(sbase + (unsigned)(WL * 64 + j * 4096))));
+            load_piece_to_lds(woff[j] + step_off, ws_rsrc, (unsigned)__builtin_amdgcn_readfirstlane((int)(sbase + (unsigned)(WS * 64 + j * 4096))));
+        }
+        ++p_it;
+        if (++p_c == prm.csteps) {
+            p_c = 0;
+            if (++p_s == a.S) {
+                p_s = 0;
+                ++p_r;
+            }
+        }
+    };
+
+    // ---- consumer
+    const int wp0 = (wave & 1) * WP, wc0 = (wave >> 1) * WC;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int swz = (l32 >> 2) & 3;
+    v16i accA[CT][PT], accC[CT][PT], accD[CT][PT];
+#pragma unroll
+    for (int c = 0; c < CT; c++)
+#pragma unroll
+        for (int p = 0; p < PT; p++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) accA[c][p][r] = accC[c][p][r] = accD[c][p][r] = 0;
+
+    const int nitems = prm.nitems;
+    if (nitems > 0) issue(0);
+    if (nitems > 1) issue(1);
+    int stage = 0;
+    for (int it = 0; it < nitems; it++) {
+        // the loads of step `it` (this wavefront's) have landed; behind the barrier everybody's have, and everybody has
+        // finished reading step it - 1, whose stage step it + 2 is about to overwrite
+        if (it + 1 < nitems) wait_loads<LPW>();
+        else wait_loads<0>();
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (it + 2 < nitems) issue(stage >= 1 ? stage - 1 : NSTAGES - 1);
+        const v4i *st = (const v4i *)lds + stage * ROWS * kPieces;
+#pragma unroll
+        for (int kk = 0; kk < 2; kk++) {
+            const int g = (kk * 2 + lh) ^ swz;
+            v4i wh[CT], wl[CT], ws[CT], xh[PT], xl[PT], xs[PT];
+#pragma unroll
+            for (int c = 0; c < CT; c++) {
+                const int row = wc0 + c * 32 + l32;
+                wh[c] = st[(WH + row) * kPieces + g];
+                wl[c] = st[(WL + row) * kPieces + g];
+                ws[c] = st[(WS + row) * kPieces + g];
+            }
+#pragma unroll
+            for (int p = 0; p < PT; p++) {
+                const int row = wp0 + p * 32 + l32;
+                xh[p] = st[(XH + row) * kPieces + g];
+                xl[p] = st[(XL + row) * kPieces + g];
+#pragma unroll
+                for (int d = 0; d < 4; d++) xs[p][d] = add_bytes(xh[p][d], xl[p][d]);
+            }
+#pragma unroll
+            for (int c = 0; c < CT; c++)
+#pragma unroll
+                for (int p = 0; p < PT; p++) {
+                    accA[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wh[c], xh[p], accA[c][p], 0, 0, 0);
+                    accC[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wl[c], xl[p], accC[c][p], 0, 0, 0);
+                    accD[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws[c], xs[p], accD[c][p], 0, 0, 0);
+                }
+        }
+        stage = stage + 1 == NSTAGES ? 0 : stage + 1;
+    }
+
+    // ---- epilogue: register r of a lane belongs to channel kc + r of pixel m
+    const NpRound rnd = {a.shift, a.p_y, (float)a.beta_max, a.relu};
+#pragma unroll
+    for (int c = 0; c < CT; c++) {
+        const int kc = ct * BC + wc0 + c * 32 + 16 * lh;
+        if (kc >= a.K) continue;
+        int bias[16];
+#pragma unroll
+        for (int r4 = 0; r4 < 4; r4++) {
+            const int4 bv = a.b ? *(const int4 *)(a.b + kc + 4 * r4) : make_int4(0, 0, 0, 0);
+            bias[4 * r4 + 0] = bv.x;
+            bias[4 * r4 + 1] = bv.y;
+            bias[4 * r4 + 2] = bv.z;
+            bias[4 * r4 + 3] = bv.w;
+        }
+#pragma unroll
+        for (int p = 0; p < PT; p++) {
+            const int m = pt * BP + wp0 + p * 32 + l32;
+            uint32_t oc[4], oh[4], ol[4];
+#pragma unroll
+            for (int r4 = 0; r4 < 4; r4++) {
+                uint32_t wc = 0, whi = 0, wlo = 0;
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const int r = 4 * r4 + e;
+                    const int A = accA[c][p][r], Cc = accC[c][p][r], D = accD[c][p][r];
+                    const int T = 63 * A + D - Cc;
+                    const long long sum = (long long)T * 64 + (long long)Cc + (long long)bias[r];
+                    const int beta = np_round_acc(sum, rnd);
+                    int h, l;
+                    np_split(beta, h, l);
+                    wc |= np_code_of(beta, a.p_y) << (8 * e);
+                    whi |= ((uint32_t)h & 0xffu) << (8 * e);
+                    wlo |= ((uint32_t)l & 0xffu) << (8 * e);
+                }
+                oc[r4] = wc;
+                oh[r4] = whi;
+                ol[r4] = wlo;
+            }
+            if (m < prm.M) {
+                const size_t o = (size_t)m * a.K + kc;
+                if (a.y) *(uint4 *)(a.y + o) = make_uint4(oc[0], oc[1], oc[2], oc[3]);
+                if (a.yh) *(uint4 *)(a.yh + o) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+                if (a.yl) *(uint4 *)(a.yl + o) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+            }
+        }
+    }
+}
+
+template <int BP, int BC>
+hipError_t launch_np_mfma(const NpConvArgs &a, hipStream_t st)
+{
+    NpConvParams prm;
+    prm.a = a;
+    const long long M = (long long)a.N * a.P * a.Q;
+    prm.M = (int)M;
+    prm.csteps = a.C / kStepBytes;
+    prm.nitems = a.R * a.S * prm.csteps;
+    prm.tiles_c = (a.K + BC - 1) / BC;
+    prm.x_bytes = (unsigned)((long long)a.N * a.H * a.W * a.C);
+    prm.w_bytes = (unsigned)((long long)a.K * a.R * a.S * a.C);
+    prm.div_q = make_fastdiv(a.Q);
+    prm.div_p = make_fastdiv(a.P);
+    prm.div_tc = make_fastdiv(prm.tiles_c);
+    const long long tiles = ((M + BP - 1) / BP) * prm.tiles_c;
+    if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    constexpr size_t lds_bytes = (size_t)3 * (2 * BP + 3 * BC) * 64;
+    static_assert(lds_bytes <= (size_t)kLdsBytes, "three stages fit");
+    static const hipError_t attr = hipFuncSetAttribute((const void *)conv_np_mfma_kernel<BP, BC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (attr != hipSuccess) return attr;
+    conv_np_mfma_kernel<BP, BC><<<(unsigned)tiles, 256, lds_bytes, st>>>(prm);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// The matrix-core form takes dense layers whose reduction runs in whole 64-byte steps and whose three int32
+// accumulators cannot overflow; byte offsets are 32-bit; outputs are written 16 channels at a time.
+bool conv_np_mfma_supports(const NpConvArgs &a)
+{
+    if (a.groups != 1 || a.C % kStepBytes || a.K % 16) return false;
+    if ((long long)a.R * a.S * a.C > 29277) return false;                                   // |D| <= 8836 per term stays below 2^31 - |A|, |C| terms
+    if ((long long)a.N * a.H * a.W * a.C >= (1LL << 31) - (1 << 24)) return false;
+    if ((long long)a.K * a.R * a.S * a.C >= (1LL << 31) - (1 << 24)) return false;
+    if ((long long)a.N * a.P * a.Q >= (1LL << 31) - 512) return false;
+    const uintptr_t al = (uintptr_t)a.xh | (uintptr_t)a.xl | (uintptr_t)a.wh | (uintptr_t)a.wl | (uintptr_t)a.ws | (uintptr_t)a.y | (uintptr_t)a.yh |
+                         (uintptr_t)a.yl | (uintptr_t)a.b;
+    return (al & 15) == 0;
+}
+
+hipError_t launch_conv_np_mfma(const NpConvArgs &a, hipStream_t st)
+{
+    if (a.K <= 64) return launch_np_mfma<256, 64>(a, st);
+    return launch_np_mfma<128, 128>(a, st);
+}
+
+hipError_t launch_conv_np_direct(const NpConvArgs &a, hipStream_t st)
+{
+    size_t total = (size_t)a.N * a.P * a.Q * a.K;
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    conv_np_direct_kernel<<<(int)blocks, 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, int8_t *sum, hipStream_t st)
+{
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    np_digits_kernel<<<(int)blocks, 256, 0, st>>>(codes, n, p, hi, lo, sum);
+    return hipGetLastError();
+}
+
+}  // namespace dfq

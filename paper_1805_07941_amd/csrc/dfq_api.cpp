@@ -199,6 +199,71 @@ dfq_status dfq_dequantize_np(const uint8_t *codes, float *x, size_t n, int nbits
     return from_hip(launch_dequantize_np(codes, x, n, nbits, p, frac, (hipStream_t)stream));
 }
 
+dfq_status dfq_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, int8_t *sum, dfq_stream stream)
+{
+    if (p < 4 || p > 7) return DFQ_EFMT;
+    if (n == 0) return DFQ_OK;
+    if (!codes || !hi || !lo) return DFQ_EINVAL;
+    if (overlaps(codes, n, hi, n) || overlaps(codes, n, lo, n) || overlaps(codes, n, sum, n) || overlaps(hi, n, lo, n) ||
+        overlaps(hi, n, sum, n) || overlaps(lo, n, sum, n))
+        return DFQ_EINVAL;
+    return from_hip(launch_np_digits(codes, n, p, hi, lo, sum, (hipStream_t)stream));
+}
+
+static dfq_status check_conv_np(NpConvArgs &a, int frac_x, int frac_w, int frac_y)
+{
+    if (!a.xh || !a.xl || !a.wh || !a.wl || !a.ws || (!a.y && !a.yh && !a.yl)) return DFQ_EINVAL;
+    if ((a.yh == nullptr) != (a.yl == nullptr)) return DFQ_EINVAL;
+    if (a.N < 0) return DFQ_EINVAL;
+    if (a.H < 1 || a.W < 1 || a.C < 1 || a.K < 1 || a.R < 1 || a.S < 1 || a.stride < 1 || a.pad < 0 || a.groups < 1) return DFQ_ESHAPE;
+    if (a.C % a.groups || a.K % a.groups) return DFQ_ESHAPE;
+    a.P = out_extent(a.H, a.pad, a.R, a.stride);
+    a.Q = out_extent(a.W, a.pad, a.S, a.stride);
+    if (a.P < 1 || a.Q < 1) return DFQ_ESHAPE;
+    if (a.p_y < 4 || a.p_y > 7) return DFQ_EFMT;
+    if (frac_x < -32 || frac_x > 32 || frac_w < -32 || frac_w > 32 || frac_y < -32 || frac_y > 32) return DFQ_EFMT;
+    a.shift = frac_x + frac_w - frac_y;
+    if (a.shift < -16 || a.shift > 48) return DFQ_EFMT;
+    // Eq. 8 with the largest twelve-bit operands: the sum plus a 32-bit bias must stay below 2^62
+    if ((long long)a.R * a.S * (a.C / a.groups) > (1LL << 36)) return DFQ_EUNSUPPORTED;
+    if ((long long)a.H * a.W * a.C >= (1LL << 31) || (long long)a.P * a.Q * a.K >= (1LL << 31)) return DFQ_EUNSUPPORTED;
+    a.beta_max = (int)dfq_beta_max(8, a.p_y);
+    const size_t nx = (size_t)a.N * a.H * a.W * a.C, ny = (size_t)a.N * a.P * a.Q * a.K;
+    const void *outs[3] = {a.y, a.yh, a.yl};
+    for (int i = 0; i < 3; i++) {
+        if (overlaps(outs[i], ny, a.xh, nx) || overlaps(outs[i], ny, a.xl, nx)) return DFQ_EINVAL;
+        for (int j = i + 1; j < 3; j++)
+            if (overlaps(outs[i], ny, outs[j], ny)) return DFQ_EINVAL;
+    }
+    return DFQ_OK;
+}
+
+dfq_status dfq_conv_np_variant(dfq_conv_variant variant, const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl,
+                               const int8_t *ws, const int32_t *b, uint8_t *y, int8_t *yh, int8_t *yl, int N, int H, int W, int C,
+                               int K, int R, int S, int stride, int pad, int groups, int frac_x, int frac_w, int frac_y, int p_y,
+                               int relu, dfq_stream stream)
+{
+    NpConvArgs a{xh, xl, wh, wl, ws, b, y, yh, yl, N, H, W, C, K, R, S, stride, pad, groups, 0, 0, 0, p_y, 0, relu ? 1 : 0};
+    const dfq_status st = check_conv_np(a, frac_x, frac_w, frac_y);
+    if (st != DFQ_OK) return st;
+    if (N == 0) return DFQ_OK;
+    if (variant == DFQ_CONV_AUTO) variant = conv_np_mfma_supports(a) ? DFQ_CONV_MFMA : DFQ_CONV_DIRECT;
+    if (variant == DFQ_CONV_MFMA) {
+        if (!conv_np_mfma_supports(a)) return DFQ_EUNSUPPORTED;
+        return from_hip(launch_conv_np_mfma(a, (hipStream_t)stream));
+    }
+    if (variant == DFQ_CONV_DIRECT) return from_hip(launch_conv_np_direct(a, (hipStream_t)stream));
+    return DFQ_EINVAL;
+}
+
+dfq_status dfq_conv_np(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int8_t *ws, const int32_t *b,
+                       uint8_t *y, int8_t *yh, int8_t *yl, int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
+                       int groups, int frac_x, int frac_w, int frac_y, int p_y, int relu, dfq_stream stream)
+{
+    return dfq_conv_np_variant(DFQ_CONV_AUTO, xh, xl, wh, wl, ws, b, y, yh, yl, N, H, W, C, K, R, S, stride, pad, groups, frac_x, frac_w,
+                               frac_y, p_y, relu, stream);
+}
+
 dfq_status dfq_conv_q_variant(dfq_conv_variant variant, const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y,
                               int32_t *acc_out, int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
                               int groups, int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu,

@@ -36,6 +36,22 @@ struct ConvArgs {
     int frac_w_lo = 0, frac_w_hi = 0;   // bounds the caller guarantees for the entries of frac_w
 };
 
+// One convolution on 8-bit dynamic floating-point codes with p >= 4 significand bits (Eq. 6 on integers of up to
+// twelve bits), operands and results as base-64 digit planes: beta = 64 * h + l, h and l of the sign of beta.
+struct NpConvArgs {
+    const int8_t *xh, *xl;         // input digit planes, NHWC
+    const int8_t *wh, *wl, *ws;    // weight digit planes and their byte-wise sum h + l, [K][R][S][C/groups]
+    const int32_t *b;              // bias at f_x + f_w, may be null
+    uint8_t *y;                    // output codes (Eq. 2), may be null
+    int8_t *yh, *yl;               // output digit planes, may be null
+    int N, H, W, C, K, R, S, stride, pad, groups;
+    int P, Q;
+    int shift;                     // f_x + f_w - f_y
+    int p_y;                       // significand bits of the output format (8, p_y)
+    int beta_max;                  // Eq. 5 for the output format
+    int relu;
+};
+
 hipError_t launch_quantize(const float *x, int8_t *q, size_t n, int frac, hipStream_t st);
 hipError_t launch_quantize_i32(const float *x, int32_t *q, size_t n, int frac, hipStream_t st);
 hipError_t launch_dequantize(const int8_t *q, float *x, size_t n, int frac, hipStream_t st);
@@ -70,6 +86,10 @@ bool conv_pw_supports(const ConvArgs &a);
 hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st);
 bool conv_grouped_supports(const ConvArgs &a);
 hipError_t launch_conv_grouped(const ConvArgs &a, hipStream_t st);
+bool conv_np_mfma_supports(const NpConvArgs &a);
+hipError_t launch_conv_np_mfma(const NpConvArgs &a, hipStream_t st);
+hipError_t launch_conv_np_direct(const NpConvArgs &a, hipStream_t st);
+hipError_t launch_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, int8_t *sum, hipStream_t st);
 bool conv_smallc_supports(const ConvArgs &a);
 hipError_t launch_conv_smallc(const ConvArgs &a, hipStream_t st);
 

@@ -130,6 +130,38 @@ def test_conv_q_rejects_bad_arguments_before_launching(B):
     assert _conv(B, N=0) == B.OK                              # empty batch: nothing to do
 
 
+def test_conv_np_rejects_bad_arguments_before_launching(B):
+    """(fake non-null addresses, 16-byte aligned and far apart: every case below must fail in validation)"""
+    L = B.lib()
+
+    def call(variant=B.CONV_AUTO, xh=1 << 20, xl=2 << 20, wh=3 << 20, wl=4 << 20, ws=5 << 20, b=None, y=6 << 20, yh=7 << 20, yl=8 << 20,
+             N=1, H=8, W=8, Cc=64, K=16, R=3, S=3, stride=1, pad=1, groups=1, fx=8, fw=8, fy=3, p_y=4, relu=0):
+        return L.dfq_conv_np_variant(variant, xh, xl, wh, wl, ws, b, y, yh, yl, N, H, W, Cc, K, R, S, stride, pad, groups, fx, fw, fy, p_y,
+                                     relu, None)
+
+    assert call(xh=None) == B.EINVAL and call(ws=None) == B.EINVAL
+    assert call(y=None, yh=None, yl=None) == B.EINVAL              # no output at all
+    assert call(yl=None) == B.EINVAL                               # one plane without the other
+    assert call(N=-1) == B.EINVAL
+    assert call(Cc=0) == B.ESHAPE and call(groups=3) == B.ESHAPE and call(H=1, W=1, pad=0) == B.ESHAPE and call(stride=0) == B.ESHAPE
+    assert call(p_y=3) == B.EFMT and call(p_y=8) == B.EFMT         # (8, 3) integers need 18 bits: not this path
+    assert call(fx=33) == B.EFMT
+    assert call(fx=32, fw=32, fy=-32) == B.EFMT                    # shift 96
+    assert call(fx=-32, fw=0, fy=0) == B.EFMT                      # shift -32
+    assert call(y=1 << 20) == B.EINVAL and call(yh=6 << 20) == B.EINVAL      # output over input, output over output
+    assert call(variant=B.CONV_MFMA, Cc=48) == B.EUNSUPPORTED      # reduction not in whole 64-byte steps
+    assert call(variant=B.CONV_MFMA, K=24) == B.EUNSUPPORTED
+    assert call(variant=B.CONV_MFMA, groups=2) == B.EUNSUPPORTED
+    assert call(variant=B.CONV_MFMA, xl=(2 << 20) + 4) == B.EUNSUPPORTED     # alignment
+    assert call(variant=B.CONV_MFMA, Cc=4096, R=3, S=3) == B.EUNSUPPORTED    # 36864 terms: the int32 partial sums could overflow
+    assert call(variant=B.CONV_DEPTHWISE) == B.EINVAL
+    assert call(N=0) == B.OK
+    assert L.dfq_np_digits(1 << 20, 16, 3, 2 << 20, 3 << 20, None, None) == B.EFMT
+    assert L.dfq_np_digits(None, 16, 4, 2 << 20, 3 << 20, None, None) == B.EINVAL
+    assert L.dfq_np_digits(1 << 20, 16, 4, 1 << 20, 3 << 20, None, None) == B.EINVAL     # in place
+    assert L.dfq_np_digits(1 << 20, 0, 4, 2 << 20, 3 << 20, None, None) == B.OK
+
+
 def test_other_calls_reject_bad_arguments(B):
     L = B.lib()
     f = B.fmt
