@@ -301,8 +301,12 @@ dfq_status dfq_fmt_from_absmax_i32_channels(const uint32_t *m, int K, int32_t fr
  *   both or neither NULL; at least one output.  frac_* in [-32, 32], frac_x + frac_w - frac_y in [-16, 48], p_y in
  *   [4, 7]: DFQ_EFMT otherwise.  Geometry and status codes as dfq_conv_q.  Outputs must not overlap inputs or each other.
  *   N == 0 is a no-op.
- * dfq_conv_np_variant: DFQ_CONV_MFMA (groups == 1, C % 64 == 0, K % 16 == 0, R*S*C <= 29277, all pointers 16-byte
+ * dfq_conv_np_variant: DFQ_CONV_MFMA (groups == 1, C % 64 == 0, K % 16 == 0, R*S*C <= 13000, all pointers 16-byte
  *   aligned; DFQ_EUNSUPPORTED otherwise) or DFQ_CONV_DIRECT (any geometry); DFQ_CONV_AUTO picks MFMA when it applies. */
+/* gamma = alpha * beta_max (Sec. 2.1) solved for a power-of-two alpha in the general family: the largest frac in
+ * [-32, 32] with gamma * 2^frac <= beta_max(nbits, p); gamma = 0 gives 32.  Host, pure.  DFQ_EINVAL for a negative,
+ * infinite or NaN gamma, DFQ_EFMT for a format dfq_quantize_np does not take. */
+dfq_status dfq_np_frac_from_absmax_f32(float gamma, int nbits, int p, int32_t *frac_out);
 dfq_status dfq_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, int8_t *sum, dfq_stream stream);
 dfq_status dfq_conv_np(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int8_t *ws, const int32_t *b,
                        uint8_t *y, int8_t *yh, int8_t *yl, int N, int H, int W, int C, int K, int R, int S, int stride, int pad,

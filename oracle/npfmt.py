@@ -121,3 +121,18 @@ def dequantize(codes, n: int, p: int, frac: int) -> np.ndarray:
     dec = np.frompyfunc(lambda c: decode(int(c), n, p), 1, 1)
     beta = dec(codes).astype(np.float64) if codes.size else np.zeros(codes.shape, np.float64)
     return np.ldexp(beta, -int(frac)).astype(np.float32)
+
+
+def frac_from_absmax(gamma: float, n: int, p: int) -> int:
+    """gamma = alpha * beta_max (Sec. 2.1) with alpha = 2^-frac: the largest frac in [-32, 32] that does not clip the
+    threshold, gamma * 2^frac <= beta_max (the rule of the int8 path, applied to the format's own beta_max)."""
+    _check(n, p)
+    gamma = float(np.float32(gamma))
+    if not (gamma >= 0.0) or np.isinf(gamma):
+        raise ValueError("threshold must be finite and non-negative")
+    from fractions import Fraction
+    bm = beta_max(n, p)
+    for f in range(32, -33, -1):
+        if Fraction(gamma) * Fraction(2) ** f <= bm:
+            return f
+    return -32

@@ -27,7 +27,7 @@ EXPORTS = [
     "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_hist_i32", "dfq_threshold_search", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_fold_scale_f32", "dfq_eltwise_q", "dfq_concat_q", "dfq_concat_q_into", "dfq_pool_q",
     "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_hist_shift", "dfq_fmt_from_absmax_i32_channels",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
-    "dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant",
+    "dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32",
 ]
 
 
@@ -92,7 +92,8 @@ def lib():
     L.dfq_np_digits.argtypes = [vp, sz, i32, vp, vp, vp, vp]
     L.dfq_conv_np.argtypes = [vp] * 9 + [i32] * 15 + [vp]
     L.dfq_conv_np_variant.argtypes = [i32] + [vp] * 9 + [i32] * 15 + [vp]
-    for name in ("dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant"):
+    L.dfq_np_frac_from_absmax_f32.argtypes = [C.c_float, i32, i32, C.POINTER(C.c_int32)]
+    for name in ("dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32"):
         getattr(L, name).restype = i32
     L.dfq_hist_shift.argtypes = [i64]
     L.dfq_hist_shift.restype = i32
@@ -524,6 +525,12 @@ def fmt_from_absmax_f32(gamma: float) -> int:
     f = Fmt()
     _check(lib().dfq_fmt_from_absmax_f32(float(gamma), C.byref(f)), "dfq_fmt_from_absmax_f32")
     return int(f.frac)
+
+
+def np_frac_from_absmax_f32(gamma: float, nbits: int, p: int) -> int:
+    f = C.c_int32()
+    _check(lib().dfq_np_frac_from_absmax_f32(float(gamma), int(nbits), int(p), C.byref(f)), "dfq_np_frac_from_absmax_f32")
+    return int(f.value)
 
 
 def fmt_from_absmax_i32(m: int, acc_frac: int) -> int:

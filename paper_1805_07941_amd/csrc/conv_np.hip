@@ -9,7 +9,7 @@
 // then  sum beta_x beta_w = 4096 * A + 64 * B + C  with  A = sum h_x h_w,  C = sum l_x l_w,  B = sum (h_x l_w + l_x h_w),
 // and B = D - A - C with D = sum (h_x + l_x)(h_w + l_w)  (|h + l| <= 94 is an int8 too): three int8 matrix products
 // per block instead of four.  A, C and D are int32 accumulators (|D| <= 8836 per term: exact for reductions of up to
-// 29 277 terms, checked by the launcher); once per tile they are combined in 64-bit arithmetic,
+// 13 000 terms, checked by the launcher); once per tile they are combined in 64-bit arithmetic,
 //     sum = 64 * (63 * A + D - C) + C,
 // the bias is added, ReLU applied, and the value times 2^-shift is rounded ONCE to the output format: nearest
 // representable integer, ties to the even significand field, saturation at +-beta_max.
@@ -25,6 +25,8 @@
 // reduction axis in 64-byte steps through a ring of three LDS stages of (2 BP + 3 BC) rows filled by direct
 // global -> LDS loads two steps ahead; rows are 64 bytes with the 16-byte pieces XOR-swizzled as in the int8 kernels.
 // conv_np_direct_kernel: one output per lane, any geometry (groups, C not a multiple of 64).
+#include <type_traits>
+
 #include "conv_ring.hpp"
 
 namespace dfq {
@@ -64,6 +66,64 @@ __device__ __forceinline__ int np_round_acc(long long v, const NpRound &f)
     return neg ? -beta : beta;
 }
 
+// The same rounding for the matrix-core kernel's epilogue when 7 <= shift <= 36, in 32-bit integers.  The accumulator is
+// 64 * T + c with T and c int32; with hi = c >> 6 (floor) its value is (T + hi + f) * 64 for a fraction f in [0, 1) that
+// is nonzero iff c & 63 is.  The integer a = 2 * (T + hi) + (f != 0) has the sign of the accumulator and |a| is its
+// magnitude in units of 32 with the last bit sticky (odd: strictly between the even neighbours) - all a rounding needs
+// whose kept bits end at least two places above it: the results are integers and one unit of a is 2^(5 - shift) <= 1/4.
+// With L the leading bit of |a| the value lies in binade e = L + 5 - shift, the step is 2^k with k = max(e - p, 0), so
+// r = shift - 5 + k bits of |a| go: q = (|a| + 2^(r-1) - 1 + bit_r(|a|)) >> r is round-half-even, and the result is
+// q * 2^k (q = 2^(p+1) after a carry is the first value of the next binade), clamped at beta_max.  2 <= r <= 31, and
+// |T + hi| < 2^30 by the launcher's bound on the reduction length.  Returns the magnitude; sgn = 0 or -1.
+struct NpFast {
+    int c0;          // 36 - shift - p
+    int sm5;         // shift - 5
+    unsigned bmax;
+};
+
+__device__ __forceinline__ unsigned np_round_fast(int T, int c, const NpFast &f, int &sgn)
+{
+    const int w = T + (c >> 6);
+    const int a = w + w + ((c & 63) != 0 ? 1 : 0);
+    sgn = a >> 31;
+    const unsigned mag = (unsigned)((a ^ sgn) - sgn);
+    int lz;
+    asm("v_ffbh_u32 %0, %1" : "=v"(lz) : "v"(mag));      // leading zeros; -1 for 0 (then q = 0 whatever r is)
+    const int k = max(f.c0 - lz, 0);
+    const int r = k + f.sm5;
+    const unsigned odd = __builtin_amdgcn_ubfe(mag, (unsigned)r, 1u);
+    const unsigned hm1 = (1u << (r - 1)) - 1u;
+    const unsigned q = (mag + hm1 + odd) >> r;
+    return min(q << k, f.bmax);
+}
+
+// byte E of w = low byte of (v >> sh), of (v & msk), of (x - y): the operation writes its result's low byte straight
+// into the packed word (sub-dword destination select), the other bytes are kept
+template <int E>
+__device__ __forceinline__ void put_shr(uint32_t &w, unsigned sh, unsigned v)
+{
+    if constexpr (E == 0) asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sh), "v"(v));
+    if constexpr (E == 1) asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sh), "v"(v));
+    if constexpr (E == 2) asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sh), "v"(v));
+    if constexpr (E == 3) asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sh), "v"(v));
+}
+template <int E>
+__device__ __forceinline__ void put_and(uint32_t &w, unsigned msk, unsigned v)
+{
+    if constexpr (E == 0) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(msk), "v"(v));
+    if constexpr (E == 1) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(msk), "v"(v));
+    if constexpr (E == 2) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(msk), "v"(v));
+    if constexpr (E == 3) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(msk), "v"(v));
+}
+template <int E>
+__device__ __forceinline__ void put_sub(uint32_t &w, unsigned x, unsigned y)
+{
+    if constexpr (E == 0) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(x), "v"(y));
+    if constexpr (E == 1) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(x), "v"(y));
+    if constexpr (E == 2) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(x), "v"(y));
+    if constexpr (E == 3) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(x), "v"(y));
+}
+
 // Eq. 2 inverted: the sign-and-magnitude code of a representable integer (8 bits, p significand bits); +0 for 0.
 __device__ __forceinline__ unsigned np_code_of(int beta, int p)
 {
@@ -89,6 +149,36 @@ __device__ __forceinline__ void np_split(int beta, int &h, int &l)
     const int hu = mag >> 6, lu = mag & 63;
     h = beta < 0 ? -hu : hu;
     l = beta < 0 ? -lu : lu;
+}
+
+// Four neighbouring channels of one pixel: accumulators -> one packed word of codes, of high digits, of low digits.
+// FAST: 7 <= shift <= 36 (32-bit rounding above), else the 64-bit form; RELU and CODES (codes wanted) as template
+// parameters keep the sign handling and the encoding out of the variants that do not need them.
+template <bool FAST, bool RELU, bool CODES, int E>
+__device__ __forceinline__ void np_finish_one(int A, int Cc, int D, int bias, const NpRound &rnd, const NpFast &fr, int p_y, uint32_t &wc,
+                                              uint32_t &whi, uint32_t &wlo)
+{
+    const int T = (A << 6) + D - (A + Cc);               // 63 A + D - C
+    unsigned mag;
+    int sgn;
+    if constexpr (FAST) {
+        // (the bias joins both parts: |C| + 63 and |T| + |bias| / 64 stay inside 32 bits)
+        mag = np_round_fast(T + (bias >> 6), Cc + (bias & 63), fr, sgn);
+    } else {
+        const int beta = np_round_acc((long long)T * 64 + (long long)Cc + (long long)bias, rnd);
+        sgn = beta >> 31;
+        mag = (unsigned)((beta ^ sgn) - sgn);
+    }
+    if constexpr (RELU) {
+        mag &= ~(unsigned)sgn;
+        put_shr<E>(whi, 6u, mag);
+        put_and<E>(wlo, 63u, mag);
+        if constexpr (CODES) wc |= np_code_of((int)mag, p_y) << (8 * E);
+    } else {
+        put_sub<E>(whi, (mag >> 6) ^ (unsigned)sgn, (unsigned)sgn);
+        put_sub<E>(wlo, (mag & 63u) ^ (unsigned)sgn, (unsigned)sgn);
+        if constexpr (CODES) wc |= (np_code_of((int)mag, p_y) | (mag ? ((unsigned)sgn & 0x80u) : 0u)) << (8 * E);
+    }
 }
 
 // byte-wise h + l of four int8 pairs (no carry between bytes; every true sum fits a byte)
@@ -312,50 +402,61 @@ __global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
 
     // ---- epilogue: register r of a lane belongs to channel kc + r of pixel m
     const NpRound rnd = {a.shift, a.p_y, (float)a.beta_max, a.relu};
+    const NpFast fr = {36 - a.shift - a.p_y, a.shift - 5, (unsigned)a.beta_max};
+    auto finish = [&](auto fast, auto relu, auto codes) __attribute__((always_inline)) {
+        constexpr bool FAST = decltype(fast)::value, RELU = decltype(relu)::value, CODES = decltype(codes)::value;
 #pragma unroll
-    for (int c = 0; c < CT; c++) {
-        const int kc = ct * BC + wc0 + c * 32 + 16 * lh;
-        if (kc >= a.K) continue;
-        int bias[16];
-#pragma unroll
-        for (int r4 = 0; r4 < 4; r4++) {
-            const int4 bv = a.b ? *(const int4 *)(a.b + kc + 4 * r4) : make_int4(0, 0, 0, 0);
-            bias[4 * r4 + 0] = bv.x;
-            bias[4 * r4 + 1] = bv.y;
-            bias[4 * r4 + 2] = bv.z;
-            bias[4 * r4 + 3] = bv.w;
-        }
-#pragma unroll
-        for (int p = 0; p < PT; p++) {
-            const int m = pt * BP + wp0 + p * 32 + l32;
-            uint32_t oc[4], oh[4], ol[4];
+        for (int c = 0; c < CT; c++) {
+            const int kc = ct * BC + wc0 + c * 32 + 16 * lh;
+            if (kc >= a.K) continue;
+            int bias[16];
 #pragma unroll
             for (int r4 = 0; r4 < 4; r4++) {
-                uint32_t wc = 0, whi = 0, wlo = 0;
-#pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    const int r = 4 * r4 + e;
-                    const int A = accA[c][p][r], Cc = accC[c][p][r], D = accD[c][p][r];
-                    const int T = 63 * A + D - Cc;
-                    const long long sum = (long long)T * 64 + (long long)Cc + (long long)bias[r];
-                    const int beta = np_round_acc(sum, rnd);
-                    int h, l;
-                    np_split(beta, h, l);
-                    wc |= np_code_of(beta, a.p_y) << (8 * e);
-                    whi |= ((uint32_t)h & 0xffu) << (8 * e);
-                    wlo |= ((uint32_t)l & 0xffu) << (8 * e);
-                }
-                oc[r4] = wc;
-                oh[r4] = whi;
-                ol[r4] = wlo;
+                const int4 bv = a.b ? *(const int4 *)(a.b + kc + 4 * r4) : make_int4(0, 0, 0, 0);
+                bias[4 * r4 + 0] = bv.x;
+                bias[4 * r4 + 1] = bv.y;
+                bias[4 * r4 + 2] = bv.z;
+                bias[4 * r4 + 3] = bv.w;
             }
-            if (m < prm.M) {
-                const size_t o = (size_t)m * a.K + kc;
-                if (a.y) *(uint4 *)(a.y + o) = make_uint4(oc[0], oc[1], oc[2], oc[3]);
-                if (a.yh) *(uint4 *)(a.yh + o) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
-                if (a.yl) *(uint4 *)(a.yl + o) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+#pragma unroll
+            for (int p = 0; p < PT; p++) {
+                const int m = pt * BP + wp0 + p * 32 + l32;
+                uint32_t oc[4], oh[4], ol[4];
+#pragma unroll
+                for (int r4 = 0; r4 < 4; r4++) {
+                    uint32_t wc = 0, whi = 0, wlo = 0;
+                    const int r = 4 * r4;
+                    np_finish_one<FAST, RELU, CODES, 0>(accA[c][p][r + 0], accC[c][p][r + 0], accD[c][p][r + 0], bias[r + 0], rnd, fr, a.p_y, wc, whi, wlo);
+                    np_finish_one<FAST, RELU, CODES, 1>(accA[c][p][r + 1], accC[c][p][r + 1], accD[c][p][r + 1], bias[r + 1], rnd, fr, a.p_y, wc, whi, wlo);
+                    np_finish_one<FAST, RELU, CODES, 2>(accA[c][p][r + 2], accC[c][p][r + 2], accD[c][p][r + 2], bias[r + 2], rnd, fr, a.p_y, wc, whi, wlo);
+                    np_finish_one<FAST, RELU, CODES, 3>(accA[c][p][r + 3], accC[c][p][r + 3], accD[c][p][r + 3], bias[r + 3], rnd, fr, a.p_y, wc, whi, wlo);
+                    oc[r4] = wc;
+                    oh[r4] = whi;
+                    ol[r4] = wlo;
+                }
+                if (m < prm.M) {
+                    const size_t o = (size_t)m * a.K + kc;
+                    if (CODES) *(uint4 *)(a.y + o) = make_uint4(oc[0], oc[1], oc[2], oc[3]);
+                    if (a.yh) *(uint4 *)(a.yh + o) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+                    if (a.yl) *(uint4 *)(a.yl + o) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+                }
             }
         }
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    if (a.shift >= 7 && a.shift <= 36) {
+        if (a.y) {
+            if (a.relu) finish(T_{}, T_{}, T_{});
+            else finish(T_{}, F_{}, T_{});
+        } else {
+            if (a.relu) finish(T_{}, T_{}, F_{});
+            else finish(T_{}, F_{}, F_{});
+        }
+    } else {
+        // rare: no downscale to speak of, or one beyond 36 bits; sign handling and encoding always in
+        if (a.y) finish(F_{}, F_{}, T_{});
+        else finish(F_{}, F_{}, F_{});
     }
 }
 
@@ -391,7 +492,7 @@ hipError_t launch_np_mfma(const NpConvArgs &a, hipStream_t st)
 bool conv_np_mfma_supports(const NpConvArgs &a)
 {
     if (a.groups != 1 || a.C % kStepBytes || a.K % 16) return false;
-    if ((long long)a.R * a.S * a.C > 29277) return false;                                   // |D| <= 8836 per term stays below 2^31 - |A|, |C| terms
+    if ((long long)a.R * a.S * a.C > 13000) return false;        // |63 A + D - C| <= 73348 per term: stays below 2^30 (the epilogue doubles it)
     if ((long long)a.N * a.H * a.W * a.C >= (1LL << 31) - (1 << 24)) return false;
     if ((long long)a.K * a.R * a.S * a.C >= (1LL << 31) - (1 << 24)) return false;
     if ((long long)a.N * a.P * a.Q >= (1LL << 31) - 512) return false;

@@ -547,6 +547,18 @@ dfq_status dfq_fmt_from_absmax_f32(float gamma, dfq_fmt *out)
     return DFQ_OK;
 }
 
+dfq_status dfq_np_frac_from_absmax_f32(float gamma, int nbits, int p, int32_t *frac_out)
+{
+    if (!frac_out) return DFQ_EINVAL;
+    if (!(gamma >= 0.0f) || std::isinf(gamma)) return DFQ_EINVAL;
+    if (!np_ok(nbits, p, 0)) return DFQ_EFMT;
+    const double bmax = (double)dfq_beta_max(nbits, p);
+    int f = 32;
+    while (f > -32 && std::ldexp((double)gamma, f) > bmax) f--;
+    *frac_out = f;
+    return DFQ_OK;
+}
+
 dfq_status dfq_fmt_from_absmax_i32(int64_t m, int32_t acc_frac, dfq_fmt *out)
 {
     if (!out || m < 0) return DFQ_EINVAL;

@@ -153,13 +153,27 @@ def test_conv_np_rejects_bad_arguments_before_launching(B):
     assert call(variant=B.CONV_MFMA, K=24) == B.EUNSUPPORTED
     assert call(variant=B.CONV_MFMA, groups=2) == B.EUNSUPPORTED
     assert call(variant=B.CONV_MFMA, xl=(2 << 20) + 4) == B.EUNSUPPORTED     # alignment
-    assert call(variant=B.CONV_MFMA, Cc=4096, R=3, S=3) == B.EUNSUPPORTED    # 36864 terms: the int32 partial sums could overflow
+    assert call(variant=B.CONV_MFMA, Cc=1472, R=3, S=3) == B.EUNSUPPORTED    # 13248 terms: the int32 partial sums could overflow
     assert call(variant=B.CONV_DEPTHWISE) == B.EINVAL
     assert call(N=0) == B.OK
     assert L.dfq_np_digits(1 << 20, 16, 3, 2 << 20, 3 << 20, None, None) == B.EFMT
     assert L.dfq_np_digits(None, 16, 4, 2 << 20, 3 << 20, None, None) == B.EINVAL
     assert L.dfq_np_digits(1 << 20, 16, 4, 1 << 20, 3 << 20, None, None) == B.EINVAL     # in place
     assert L.dfq_np_digits(1 << 20, 0, 4, 2 << 20, 3 << 20, None, None) == B.OK
+
+
+def test_np_frac_from_absmax_matches_the_oracle(B):
+    import oracle.npfmt as F
+    rng = np.random.default_rng(9)
+    for g in list(np.exp(rng.uniform(-20, 20, 400)).astype(np.float32)) + [0.0, 1984.0, 1985.0, 127.0, 1e38]:
+        for n, p in [(8, 4), (8, 3), (8, 7), (5, 1)]:
+            assert B.np_frac_from_absmax_f32(float(g), n, p) == F.frac_from_absmax(float(g), n, p)
+    out = C.c_int32()
+    L = B.lib()
+    assert L.dfq_np_frac_from_absmax_f32(-1.0, 8, 4, C.byref(out)) == B.EINVAL
+    assert L.dfq_np_frac_from_absmax_f32(float("nan"), 8, 4, C.byref(out)) == B.EINVAL
+    assert L.dfq_np_frac_from_absmax_f32(1.0, 9, 4, C.byref(out)) == B.EFMT
+    assert L.dfq_np_frac_from_absmax_f32(1.0, 8, 4, None) == B.EINVAL
 
 
 def test_other_calls_reject_bad_arguments(B):

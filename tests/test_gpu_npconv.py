@@ -96,6 +96,10 @@ MFMA_CASES = [
     (1, 9, 9, 64, 16, 3, 3, 1, 0, 4, 4, 4, 0, False, "gauss"),           # no padding, shift 0: saturation everywhere
     (1, 5, 5, 64, 16, 3, 3, 1, 1, 4, 4, 4, -3, False, "small"),          # upscale
     (1, 5, 5, 64, 16, 3, 3, 1, 1, 4, 4, 4, 30, False, "gauss"),          # everything among the subnormals / zero
+    (2, 9, 7, 64, 32, 3, 3, 1, 1, 4, 4, 4, 7, False, "small"),           # the smallest shift of the 32-bit epilogue
+    (2, 9, 7, 64, 32, 3, 3, 1, 1, 4, 4, 4, 6, True, "small"),            # ... and the one below it
+    (1, 6, 6, 128, 48, 3, 3, 1, 1, 4, 4, 5, 36, False, "extreme"),       # the largest, and the one above it
+    (1, 6, 6, 128, 48, 3, 3, 1, 1, 4, 4, 5, 37, True, "extreme"),
 ]
 
 
@@ -118,14 +122,14 @@ def test_conv_np_against_oracle(B, case):
         w = np.where(rng.integers(0, 2, (K, 1, 1, 1)) == 1, 0x7f, 0xff).astype(np.uint8) * np.ones((K, R, S, C), np.uint8)
         w[K // 2:] = np.where(rng.integers(0, 2, (K - K // 2, R, S, C)) == 1, 0x7f, 0xff).astype(np.uint8)
     b = rng.integers(-(1 << 20), 1 << 20, K)
-    f_x, f_w = 9, shift - 9 + 3
-    f_y = 3
+    f_x, f_w = 9, min(shift - 9 + 3, 32)
+    f_y = f_x + f_w - shift
     for variant in (B.CONV_MFMA, B.CONV_DIRECT):
         ry, rbeta = run_both(B, x, px, w, pw, b, f_x, f_w, f_y, p_y, stride, pad, 1, relu, variant)
     if data == "extreme":
         _, _, acc = NC.conv_np(x, (8, px), w, (8, pw), b, shift, (8, p_y), stride, pad, 1, relu)
-        assert np.abs(acc).max() > 1 << 33                                   # the case means what it says
-    if shift not in (0, 30, -3):
+        assert np.abs(acc).max() > 1 << 32                                   # the case means what it says
+    if data in ("gauss", "uniform") and shift not in (0, 30):
         mags = np.abs(rbeta)
         assert (mags > 0).mean() > 0.2 and (mags == F.beta_max(8, p_y)).mean() < 0.5       # neither all zero nor all saturated
     # without bias, codes only / digits only
@@ -137,6 +141,54 @@ def test_conv_np_against_oracle(B, case):
     assert np.array_equal(host(y1), ry0)
     eh, el = digits_of(rb0)
     assert np.array_equal(host(yh2), eh) and np.array_equal(host(yl2), el)
+
+
+@pytest.mark.parametrize("shift,p_y,relu", [(7, 4, False), (8, 4, True), (13, 5, False), (20, 4, False), (31, 4, True), (36, 4, False),
+                                             (37, 4, False), (6, 4, False), (3, 6, True), (0, 4, False), (-2, 4, False), (16, 7, False)])
+def test_conv_np_rounding_on_chosen_accumulators(B, shift, p_y, relu):
+    """Accumulator values placed on and next to every tie and every representable value of the output format (and beyond
+    saturation), up to 2^33 in magnitude: 1 x 1 convolution over 1024 channels of codes +-beta_max, n of them nonzero
+    in channel k's weights, plus a bias that fills in the rest: acc = +-1984^2 * n + bias."""
+    rng = np.random.default_rng(1000 + shift)
+    reps = sorted(F.decode(c, 8, p_y) for c in range(128))
+    grid = set()
+    for a_, b_ in zip(reps, reps[1:]):
+        for num in (2 * a_, a_ + b_, 2 * b_):                       # value, midpoint, next value - all times two
+            v2 = num * 2 ** shift if shift >= 0 else None
+            if v2 is None:
+                if (num % (2 ** (1 - shift))) == 0:
+                    base = [num // (2 ** (1 - shift))]
+                else:
+                    base = [num // (2 ** (1 - shift)), num // (2 ** (1 - shift)) + 1]
+            elif v2 % 2 == 0:
+                base = [v2 // 2]
+            else:
+                base = [v2 // 2, v2 // 2 + 1]
+            for v in base:
+                grid.update((v - 1, v, v + 1, -v, -v - 1, -v + 1))
+    top = reps[-1] * 2 ** max(shift, 0)
+    grid.update(int(top * f) for f in (1.001, 1.02, 1.5, 3.0))
+    C, cap = 1024, 1984 * 1984 * 1024 + (1 << 31) - 1
+    vals = sorted(v for v in grid if abs(v) <= cap)
+    vals += [int(v) for v in rng.integers(-cap, cap, 500)]
+    K = (len(vals) + 15) // 16 * 16
+    vals += [0] * (K - len(vals))
+    vals = np.array(vals, dtype=np.int64)
+    n1 = np.clip(np.rint(np.abs(vals) / 1984.0 ** 2), 0, C).astype(np.int64)
+    sg = np.where(vals < 0, -1, 1)
+    bias = vals - sg * n1 * 1984 * 1984
+    assert np.abs(bias).max() < 1 << 31
+    w = np.zeros((K, 1, 1, C), np.uint8)
+    for k in range(K):
+        w[k, 0, 0, :n1[k]] = 0x7f if sg[k] > 0 else 0xff
+    x = np.full((2, 1, 3, C), 0x7f, np.uint8)
+    f_x = 9
+    f_w = min(shift - 9 + 3, 32)
+    f_y = f_x + f_w - shift
+    for variant in (B.CONV_MFMA, B.CONV_DIRECT):
+        _, _ = run_both(B, x, 4, w, 4, bias, f_x, f_w, f_y, p_y, 1, 0, 1, relu, variant)
+    _, _, acc = NC.conv_np(x, (8, 4), w, (8, 4), bias, shift, (8, p_y), 1, 0, 1, relu)
+    assert np.array_equal(acc[0, 0, 0], vals)
 
 
 DIRECT_CASES = [

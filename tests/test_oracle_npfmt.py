@@ -141,3 +141,26 @@ def test_int8_member_agrees_with_the_int8_oracle():
     for f in (0, 4, 7):
         assert np.array_equal(F.quantize(x, 8, 7, f)[1], orc.quantize(x, f).astype(np.int64))
         assert np.array_equal(F.quantize(x, 8, 6, f)[1], orc.quantize(x, f).astype(np.int64))
+
+
+def test_frac_from_absmax_hand_values_and_the_int8_rule():
+    """The threshold-to-scale rule on the general family: hand-worked values, the int8 path's rule (pinned on its own) for
+    the member that is int8, and the two properties that define it (the threshold is not clipped; one more bit would clip)."""
+    import oracle
+    assert F.frac_from_absmax(1984.0, 8, 4) == 0 and F.frac_from_absmax(1985.0, 8, 4) == -1
+    assert F.frac_from_absmax(1.0, 8, 4) == 10            # 1024 <= 1984 < 2048
+    assert F.frac_from_absmax(3.9, 8, 4) == 8             # 3.9 * 512 = 1996.8 is too much
+    assert F.frac_from_absmax(0.0, 8, 4) == 32 and F.frac_from_absmax(1e30, 8, 4) == -32
+    assert F.frac_from_absmax(0.25, 8, 3) == 19           # beta_max(8, 3) = 245760 = 0.46875 * 2^19
+    rng = np.random.default_rng(5)
+    for g in np.exp(rng.uniform(-15, 15, 300)).astype(np.float32):
+        assert F.frac_from_absmax(g, 8, 7) == oracle.frac_from_absmax_f32(float(g))
+        for n, p in [(8, 4), (8, 3), (6, 2)]:
+            f = F.frac_from_absmax(g, n, p)
+            bm = F.beta_max(n, p)
+            if -32 < f:
+                assert Fraction(float(g)) * Fraction(2) ** f <= bm
+            if f < 32:
+                assert Fraction(float(g)) * Fraction(2) ** (f + 1) > bm
+    with pytest.raises(ValueError):
+        F.frac_from_absmax(float("nan"), 8, 4)
