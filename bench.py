@@ -167,7 +167,7 @@ def bench_layers_np(args):
         by = 2 * xh.numel() + 2 * outs[0][1].numel() + 3 * wh.numel() + 4 * K
         t_roof = max(3 * ops / (INT8_MFMA_PEAK_TOPS * 1e12), by / (HBM_PEAK_GBS * 1e9)) * 1e3
         nonzero = float((outs[0][1] != 0).logical_or(outs[0][2] != 0).float().mean().cpu())
-        rows.append(dict(layer=L["name"], shape="%dx%dx%d -> %d, %dx%d" % (H, W, C, K, R, R), us=round(ms * 1e3, 1),
+        rows.append(dict(layer=L["name"], shape="%dx%dx%d -> %d, %dx%d" % (H, W, C, K, R, R), kernel="np-mfma", us=round(ms * 1e3, 1),
                          tops=round(ops / ms / 1e9, 1), int8_matrix_tops=round(3 * ops / ms / 1e9, 1), gbs=round(by / ms / 1e6, 1),
                          pct_mfma_peak=round(100 * 3 * ops / ms / 1e9 / INT8_MFMA_PEAK_TOPS, 1),
                          pct_hbm_peak=round(100 * by / ms / 1e6 / HBM_PEAK_GBS, 1), pct_roofline=round(100 * t_roof / ms, 1),
