@@ -292,11 +292,10 @@ dfq_status dfq_fmt_from_absmax_i32_channels(const uint32_t *m, int K, int32_t fr
  * beta_y = acc * 2^-(frac_x + frac_w - frac_y) rounded once to the nearest integer representable in (8, p_y), ties to
  * the even significand field, saturated at +-beta_max(8, p_y).
  * On this path a tensor is held as two int8 DIGIT PLANES of its integers, beta = 64 * hi + lo with hi and lo of the
- * sign of beta (|hi| <= 31, |lo| <= 63), same shape and layout as the tensor (NHWC, [K][R][S][C/groups]); weights
- * also carry the plane sum = hi + lo.  The matrix-core kernel multiplies the planes as int8 matrices (three products
- * per block) and recombines them exactly.
- * dfq_np_digits: codes of (8, p), 4 <= p <= 7 (DFQ_EFMT otherwise), to planes; `sum` may be NULL.  n bytes each, DEVICE.
- * dfq_conv_np: xh, xl: input planes; wh, wl, ws: weight planes; b: int32 bias at frac_x + frac_w or NULL;
+ * sign of beta (|hi| <= 31, |lo| <= 63), same shape and layout as the tensor (NHWC, [K][R][S][C/groups]).  The
+ * matrix-core kernel multiplies the planes as int8 matrices (four products per block) and recombines them exactly.
+ * dfq_np_digits: codes of (8, p), 4 <= p <= 7 (DFQ_EFMT otherwise), to planes.  n bytes each, DEVICE, no overlap.
+ * dfq_conv_np: xh, xl: input planes; wh, wl: weight planes; b: int32 bias at frac_x + frac_w or NULL;
  *   y: output codes (Eq. 2 sign-and-magnitude bytes, the code of -0 never written) or NULL; yh, yl: output planes,
  *   both or neither NULL; at least one output.  frac_* in [-32, 32], frac_x + frac_w - frac_y in [-16, 48], p_y in
  *   [4, 7]: DFQ_EFMT otherwise.  Geometry and status codes as dfq_conv_q.  Outputs must not overlap inputs or each other.
@@ -307,14 +306,14 @@ dfq_status dfq_fmt_from_absmax_i32_channels(const uint32_t *m, int K, int32_t fr
  * [-32, 32] with gamma * 2^frac <= beta_max(nbits, p); gamma = 0 gives 32.  Host, pure.  DFQ_EINVAL for a negative,
  * infinite or NaN gamma, DFQ_EFMT for a format dfq_quantize_np does not take. */
 dfq_status dfq_np_frac_from_absmax_f32(float gamma, int nbits, int p, int32_t *frac_out);
-dfq_status dfq_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, int8_t *sum, dfq_stream stream);
-dfq_status dfq_conv_np(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int8_t *ws, const int32_t *b,
-                       uint8_t *y, int8_t *yh, int8_t *yl, int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
-                       int groups, int frac_x, int frac_w, int frac_y, int p_y, int relu, dfq_stream stream);
+dfq_status dfq_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, dfq_stream stream);
+dfq_status dfq_conv_np(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int32_t *b, uint8_t *y,
+                       int8_t *yh, int8_t *yl, int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                       int frac_x, int frac_w, int frac_y, int p_y, int relu, dfq_stream stream);
 dfq_status dfq_conv_np_variant(dfq_conv_variant variant, const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl,
-                               const int8_t *ws, const int32_t *b, uint8_t *y, int8_t *yh, int8_t *yl, int N, int H, int W, int C,
-                               int K, int R, int S, int stride, int pad, int groups, int frac_x, int frac_w, int frac_y, int p_y,
-                               int relu, dfq_stream stream);
+                               const int32_t *b, uint8_t *y, int8_t *yh, int8_t *yl, int N, int H, int W, int C, int K, int R, int S,
+                               int stride, int pad, int groups, int frac_x, int frac_w, int frac_y, int p_y, int relu,
+                               dfq_stream stream);
 
 /* ---- closed forms of Sec. 2 (host, pure; return -1 on invalid arguments) ----------------- */
 int64_t dfq_beta_max(int n, int p);                                        /* Eq. 5, equality case */

@@ -89,9 +89,9 @@ def lib():
     L.dfq_fmt_from_absmax_f32.argtypes = [C.c_float, C.POINTER(Fmt)]
     L.dfq_fmt_from_absmax_i32.argtypes = [i64, C.c_int32, C.POINTER(Fmt)]
     L.dfq_fmt_from_absmax_i32_channels.argtypes = [vp, i32, C.c_int32, vp, C.POINTER(Fmt)]
-    L.dfq_np_digits.argtypes = [vp, sz, i32, vp, vp, vp, vp]
-    L.dfq_conv_np.argtypes = [vp] * 9 + [i32] * 15 + [vp]
-    L.dfq_conv_np_variant.argtypes = [i32] + [vp] * 9 + [i32] * 15 + [vp]
+    L.dfq_np_digits.argtypes = [vp, sz, i32, vp, vp, vp]
+    L.dfq_conv_np.argtypes = [vp] * 8 + [i32] * 15 + [vp]
+    L.dfq_conv_np_variant.argtypes = [i32] + [vp] * 8 + [i32] * 15 + [vp]
     L.dfq_np_frac_from_absmax_f32.argtypes = [C.c_float, i32, i32, C.POINTER(C.c_int32)]
     for name in ("dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32"):
         getattr(L, name).restype = i32
@@ -180,28 +180,27 @@ def dequantize_np(q: torch.Tensor, nbits: int, p: int, frac: int, out: Optional[
     return x
 
 
-def np_digits(codes: torch.Tensor, p: int, want_sum: bool = False, stream=None):
-    """(8, p) codes (uint8) -> digit planes (hi, lo[, hi + lo]) of their integers beta = 64 * hi + lo (int8 tensors)."""
+def np_digits(codes: torch.Tensor, p: int, stream=None):
+    """(8, p) codes (uint8) -> digit planes (hi, lo) of their integers beta = 64 * hi + lo (int8 tensors)."""
     _dev(codes, torch.uint8, "codes")
     hi = torch.empty(codes.shape, dtype=torch.int8, device=codes.device)
     lo = torch.empty_like(hi)
-    sm = torch.empty_like(hi) if want_sum else None
-    _check(lib().dfq_np_digits(_ptr(codes), codes.numel(), int(p), _ptr(hi), _ptr(lo), _ptr(sm), _stream(stream)), "dfq_np_digits")
-    return (hi, lo, sm) if want_sum else (hi, lo)
+    _check(lib().dfq_np_digits(_ptr(codes), codes.numel(), int(p), _ptr(hi), _ptr(lo), _stream(stream)), "dfq_np_digits")
+    return hi, lo
 
 
-def conv_np(xh: torch.Tensor, xl: torch.Tensor, wh: torch.Tensor, wl: torch.Tensor, ws: torch.Tensor, b: Optional[torch.Tensor],
+def conv_np(xh: torch.Tensor, xl: torch.Tensor, wh: torch.Tensor, wl: torch.Tensor, b: Optional[torch.Tensor],
             f_x: int, f_w: int, f_y: int, p_y: int, stride: int = 1, pad: int = 0, groups: int = 1, relu: bool = False,
             want_codes: bool = True, want_digits: bool = True, variant: int = CONV_AUTO, out=None, stream=None):
-    """Convolution on (8, p >= 4) codes held as digit planes.  xh, xl [N,H,W,C] int8; wh, wl, ws [K,R,S,C/groups] int8;
+    """Convolution on (8, p >= 4) codes held as digit planes.  xh, xl [N,H,W,C] int8; wh, wl [K,R,S,C/groups] int8;
     b [K] int32 or None.  Returns (codes uint8 or None, yh, yl or None, None); `out` = (codes, yh, yl) supplies buffers."""
-    for t, name in ((xh, "xh"), (xl, "xl"), (wh, "wh"), (wl, "wl"), (ws, "ws")):
+    for t, name in ((xh, "xh"), (xl, "xl"), (wh, "wh"), (wl, "wl")):
         _dev(t, torch.int8, name)
     if b is not None:
         _dev(b, torch.int32, "b")
     N, H, W, Cc = xh.shape
     K, R, S, Cg = wh.shape
-    if Cg * groups != Cc or xl.shape != xh.shape or wl.shape != wh.shape or ws.shape != wh.shape:
+    if Cg * groups != Cc or xl.shape != xh.shape or wl.shape != wh.shape:
         raise ValueError("operand shapes do not match")
     P, Q = conv_out_hw(H, W, R, S, stride, pad)
     if out is not None:
@@ -210,7 +209,7 @@ def conv_np(xh: torch.Tensor, xl: torch.Tensor, wh: torch.Tensor, wl: torch.Tens
         y = torch.empty((N, P, Q, K), dtype=torch.uint8, device=xh.device) if want_codes else None
         yh = torch.empty((N, P, Q, K), dtype=torch.int8, device=xh.device) if want_digits else None
         yl = torch.empty((N, P, Q, K), dtype=torch.int8, device=xh.device) if want_digits else None
-    _check(lib().dfq_conv_np_variant(int(variant), _ptr(xh), _ptr(xl), _ptr(wh), _ptr(wl), _ptr(ws), _ptr(b), _ptr(y), _ptr(yh), _ptr(yl),
+    _check(lib().dfq_conv_np_variant(int(variant), _ptr(xh), _ptr(xl), _ptr(wh), _ptr(wl), _ptr(b), _ptr(y), _ptr(yh), _ptr(yl),
                                      N, H, W, Cc, K, R, S, int(stride), int(pad), int(groups), int(f_x), int(f_w), int(f_y), int(p_y),
                                      int(bool(relu)), _stream(stream)), "dfq_conv_np")
     return y, yh, yl

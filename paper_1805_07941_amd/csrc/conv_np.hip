@@ -6,24 +6,24 @@
 // The chip has no matrix instruction with 12-bit operands, but the sum splits exactly into sums it has: write every
 // operand in two sign-and-magnitude digits of base 64,
 //     beta = 64 * h + l,   |h| <= 31, |l| <= 63   (both of the sign of beta),
-// then  sum beta_x beta_w = 4096 * A + 64 * B + C  with  A = sum h_x h_w,  C = sum l_x l_w,  B = sum (h_x l_w + l_x h_w),
-// and B = D - A - C with D = sum (h_x + l_x)(h_w + l_w)  (|h + l| <= 94 is an int8 too): three int8 matrix products
-// per block instead of four.  A, C and D are int32 accumulators (|D| <= 8836 per term: exact for reductions of up to
-// 13 000 terms, checked by the launcher); once per tile they are combined in 64-bit arithmetic,
-//     sum = 64 * (63 * A + D - C) + C,
+// then  sum beta_x beta_w = 4096 * A + 64 * B + C  with  A = sum h_x h_w,  B = sum (h_x l_w + l_x h_w),  C = sum l_x l_w:
+// four int8 matrix products per block into three int32 accumulator sets (|B| <= 3906 per term: 64 A + B stays below
+// 2^30 for reductions of up to 13 000 terms, checked by the launcher); once per tile they are combined,
+//     sum = 64 * (64 * A + B) + C,
 // the bias is added, ReLU applied, and the value times 2^-shift is rounded ONCE to the output format: nearest
 // representable integer, ties to the even significand field, saturation at +-beta_max.
+// (B = D - A - C with D = sum (h_x + l_x)(h_w + l_w), |h + l| <= 94, needs three products only; built and measured
+// 8-10 % slower: the sums h + l are a fifth operand plane through LDS for the weights and a byte-wise add per use
+// for the activations, and the kernel is not bound by the matrix pipe alone.)
 //
 // Tensors of this path travel between kernels as their two digit planes (int8 each, NHWC / [K][R][S][C]): a code is
 // decoded once, by the kernel that produces it (np_digits_kernel for inputs and weights, the epilogue here for
-// activations), not once per use; the third operand h + l of the weights is a plane of its own (weights are
-// static), that of the activations is formed in registers from the two planes (a carry-free byte-wise add, six
-// instructions per 4 codes).  The epilogue writes the digit planes of its result for the next layer and, if asked,
-// the codes themselves.
+// activations), not once per use.  The epilogue writes the digit planes of its result for the next layer and, if
+// asked, the codes themselves.
 //
 // conv_np_mfma_kernel: implicit GEMM, one tile of BP pixels x BC channels per workgroup of four wavefronts, the
-// reduction axis in 64-byte steps through a ring of three LDS stages of (2 BP + 3 BC) rows filled by direct
-// global -> LDS loads two steps ahead; rows are 64 bytes with the 16-byte pieces XOR-swizzled as in the int8 kernels.
+// reduction axis in 64-byte steps through a ring of three LDS stages of 2 (BP + BC) rows filled by direct
+// global -> LDS loads three steps ahead; rows are 64 bytes with the 16-byte pieces XOR-swizzled as in the int8 kernels.
 // conv_np_direct_kernel: one output per lane, any geometry (groups, C not a multiple of 64).
 #include <type_traits>
 
@@ -155,10 +155,10 @@ __device__ __forceinline__ void np_split(int beta, int &h, int &l)
 // FAST: 7 <= shift <= 36 (32-bit rounding above), else the 64-bit form; RELU and CODES (codes wanted) as template
 // parameters keep the sign handling and the encoding out of the variants that do not need them.
 template <bool FAST, bool RELU, bool CODES, int E>
-__device__ __forceinline__ void np_finish_one(int A, int Cc, int D, int bias, const NpRound &rnd, const NpFast &fr, int p_y, uint32_t &wc,
+__device__ __forceinline__ void np_finish_one(int A, int Cc, int Bm, int bias, const NpRound &rnd, const NpFast &fr, int p_y, uint32_t &wc,
                                               uint32_t &whi, uint32_t &wlo)
 {
-    const int T = (A << 6) + D - (A + Cc);               // 63 A + D - C
+    const int T = (A << 6) + Bm;                         // 64 A + B
     unsigned mag;
     int sgn;
     if constexpr (FAST) {
@@ -181,23 +181,16 @@ __device__ __forceinline__ void np_finish_one(int A, int Cc, int D, int bias, co
     }
 }
 
-// byte-wise h + l of four int8 pairs (no carry between bytes; every true sum fits a byte)
-__device__ __forceinline__ int add_bytes(int h, int l)
-{
-    return (int)((((unsigned)h & 0x7f7f7f7fu) + ((unsigned)l & 0x7f7f7f7fu)) ^ (((unsigned)h ^ (unsigned)l) & 0x80808080u));
-}
-
 // ---- codes -> digit planes ----------------------------------------------------------------------------------------
 
 __global__ void __launch_bounds__(256) np_digits_kernel(const uint8_t *__restrict__ codes, size_t n, int p, int8_t *__restrict__ hi,
-                                                        int8_t *__restrict__ lo, int8_t *__restrict__ sum)
+                                                        int8_t *__restrict__ lo)
 {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
         int h, l;
         np_split(np_beta_of(codes[i], p), h, l);
         hi[i] = (int8_t)h;
         lo[i] = (int8_t)l;
-        if (sum) sum[i] = (int8_t)(h + l);
     }
 }
 
@@ -255,10 +248,10 @@ template <int BP, int BC>
 __global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
 {
     constexpr int NSTAGES = 3;
-    constexpr int ROWS = 2 * BP + 3 * BC;                 // LDS rows of 64 bytes per stage: x_h, x_l, w_h, w_l, w_s
-    constexpr int XH = 0, XL = BP, WH = 2 * BP, WL = 2 * BP + BC, WS = 2 * BP + 2 * BC;
+    constexpr int ROWS = 2 * BP + 2 * BC;                 // LDS rows of 64 bytes per stage: x_h, x_l, w_h, w_l
+    constexpr int XH = 0, XL = BP, WH = 2 * BP, WL = 2 * BP + BC;
     constexpr int XJ = BP / 64, WJ = BC / 64;             // 16-row chunks per wavefront, operand plane and step
-    constexpr int LPW = 2 * XJ + 3 * WJ;                  // loads per wavefront and step
+    constexpr int LPW = 2 * XJ + 2 * WJ;                  // loads per wavefront and step
     static_assert(BP % 64 == 0 && BC % 64 == 0, "whole chunks for four wavefronts");
     constexpr int WP = BP / 2, WC = BC / 2;               // wavefront tile (2 x 2 wavefronts)
     constexpr int PT = WP / 32, CT = WC / 32;
@@ -282,7 +275,7 @@ __global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
     const int ct = lb - pt * prm.tiles_c;
 
     const v4i xh_rsrc = make_rsrc(a.xh, prm.x_bytes), xl_rsrc = make_rsrc(a.xl, prm.x_bytes);
-    const v4i wh_rsrc = make_rsrc(a.wh, prm.w_bytes), wl_rsrc = make_rsrc(a.wl, prm.w_bytes), ws_rsrc = make_rsrc(a.ws, prm.w_bytes);
+    const v4i wh_rsrc = make_rsrc(a.wh, prm.w_bytes), wl_rsrc = make_rsrc(a.wl, prm.w_bytes);
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char *)(char *)&lds[0];
 
     // ---- producer: lane l of a wavefront-wide load supplies row l/4 of a 16-row chunk, physical piece l%4, which holds
@@ -333,7 +326,6 @@ __global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
         for (int j = 0; j < WJ; j++) {
             load_piece_to_lds(woff[j] + step_off, wh_rsrc, (unsigned)__builtin_amdgcn_readfirstlane((int)(sbase + (unsigned)(WH * 64 + j * 4096))));
             load_piece_to_lds(woff[j] + step_off, wl_rsrc, (unsigned)__builtin_amdgcn_readfirstlane((int)(sbase + (unsigned)(WL * 64 + j * 4096))));
-            load_piece_to_lds(woff[j] + step_off, ws_rsrc, (unsigned)__builtin_amdgcn_readfirstlane((int)(sbase + (unsigned)(WS * 64 + j * 4096))));
         }
         ++p_it;
         if (++p_c == prm.csteps) {
@@ -349,55 +341,88 @@ __global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
     const int wp0 = (wave & 1) * WP, wc0 = (wave >> 1) * WC;
     const int l32 = lane & 31, lh = lane >> 5;
     const int swz = (l32 >> 2) & 3;
-    v16i accA[CT][PT], accC[CT][PT], accD[CT][PT];
+    v16i accA[CT][PT], accC[CT][PT], accB[CT][PT];
 #pragma unroll
     for (int c = 0; c < CT; c++)
 #pragma unroll
         for (int p = 0; p < PT; p++)
 #pragma unroll
-            for (int r = 0; r < 16; r++) accA[c][p][r] = accC[c][p][r] = accD[c][p][r] = 0;
+            for (int r = 0; r < 16; r++) accA[c][p][r] = accC[c][p][r] = accB[c][p][r] = 0;
 
-    const int nitems = prm.nitems;
-    if (nitems > 0) issue(0);
-    if (nitems > 1) issue(1);
-    int stage = 0;
-    for (int it = 0; it < nitems; it++) {
-        // the loads of step `it` (this wavefront's) have landed; behind the barrier everybody's have, and everybody has
-        // finished reading step it - 1, whose stage step it + 2 is about to overwrite
-        if (it + 1 < nitems) wait_loads<LPW>();
-        else wait_loads<0>();
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        if (it + 2 < nitems) issue(stage >= 1 ? stage - 1 : NSTAGES - 1);
+    // Operands of one 32-byte half of a step.  Step i multiplies operands that are already in registers and meanwhile
+    // reads those of step i+1: after the first half's matrix instructions the wavefront waits for its own loads of step
+    // i+1 and meets the others at the barrier (every wavefront has then also finished reading step i, whose stage the
+    // refill overwrites with step i+3), reads the first half of step i+1 into the registers just consumed, issues the
+    // second half, refills, and reads the second half.
+    struct Half {
+        v4i wh[CT], wl[CT];
+        v4i xh[PT], xl[PT];
+    };
+    Half f0, f1;
+    auto read_half = [&](Half &f, int kk, int stage) __attribute__((always_inline)) {
         const v4i *st = (const v4i *)lds + stage * ROWS * kPieces;
+        const int g = (kk * 2 + lh) ^ swz;
 #pragma unroll
-        for (int kk = 0; kk < 2; kk++) {
-            const int g = (kk * 2 + lh) ^ swz;
-            v4i wh[CT], wl[CT], ws[CT], xh[PT], xl[PT], xs[PT];
+        for (int c = 0; c < CT; c++) {
+            const int row = wc0 + c * 32 + l32;
+            f.wh[c] = st[(WH + row) * kPieces + g];
+            f.wl[c] = st[(WL + row) * kPieces + g];
+        }
+#pragma unroll
+        for (int p = 0; p < PT; p++) {
+            const int row = wp0 + p * 32 + l32;
+            f.xh[p] = st[(XH + row) * kPieces + g];
+            f.xl[p] = st[(XL + row) * kPieces + g];
+        }
+    };
+    auto mfma_half = [&](const Half &f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < PT; p++)
 #pragma unroll
             for (int c = 0; c < CT; c++) {
-                const int row = wc0 + c * 32 + l32;
-                wh[c] = st[(WH + row) * kPieces + g];
-                wl[c] = st[(WL + row) * kPieces + g];
-                ws[c] = st[(WS + row) * kPieces + g];
+                accA[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.wh[c], f.xh[p], accA[c][p], 0, 0, 0);
+                accC[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.wl[c], f.xl[p], accC[c][p], 0, 0, 0);
+                accB[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.wh[c], f.xl[p], accB[c][p], 0, 0, 0);
+                accB[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.wl[c], f.xh[p], accB[c][p], 0, 0, 0);
             }
+    };
+    auto ring_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+    const int nitems = prm.nitems;
 #pragma unroll
-            for (int p = 0; p < PT; p++) {
-                const int row = wp0 + p * 32 + l32;
-                xh[p] = st[(XH + row) * kPieces + g];
-                xl[p] = st[(XL + row) * kPieces + g];
-#pragma unroll
-                for (int d = 0; d < 4; d++) xs[p][d] = add_bytes(xh[p][d], xl[p][d]);
-            }
-#pragma unroll
-            for (int c = 0; c < CT; c++)
-#pragma unroll
-                for (int p = 0; p < PT; p++) {
-                    accA[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wh[c], xh[p], accA[c][p], 0, 0, 0);
-                    accC[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wl[c], xl[p], accC[c][p], 0, 0, 0);
-                    accD[c][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ws[c], xs[p], accD[c][p], 0, 0, 0);
-                }
+    for (int i = 0; i < NSTAGES; i++)
+        if (i < nitems) issue(i);
+    if (nitems > 0) {
+        // step 0 has landed when at most the loads of steps 1 and 2 are outstanding
+        if (nitems > 2) wait_loads<2 * LPW>();
+        else if (nitems > 1) wait_loads<LPW>();
+        else wait_loads<0>();
+        ring_barrier();
+        read_half(f0, 0, 0);
+        read_half(f1, 1, 0);
+    }
+    int stage = 0;
+    for (int it = 0; it < nitems; it++) {
+        const int next = stage + 1 == NSTAGES ? 0 : stage + 1;
+        const bool has_next = it + 1 < nitems;
+        mfma_half(f0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (has_next) {
+            // loads younger than those of step it+1: those of step it+2 (step it+3 is issued below)
+            if (it + 2 < nitems) wait_loads<LPW>();
+            else wait_loads<0>();
+            ring_barrier();
+            read_half(f0, 0, next);
         }
-        stage = stage + 1 == NSTAGES ? 0 : stage + 1;
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_half(f1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (has_next) {
+            if (it + NSTAGES < nitems) issue(stage);
+            read_half(f1, 1, next);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        stage = next;
     }
 
     // ---- epilogue: register r of a lane belongs to channel kc + r of pixel m
@@ -426,10 +451,10 @@ __global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
                 for (int r4 = 0; r4 < 4; r4++) {
                     uint32_t wc = 0, whi = 0, wlo = 0;
                     const int r = 4 * r4;
-                    np_finish_one<FAST, RELU, CODES, 0>(accA[c][p][r + 0], accC[c][p][r + 0], accD[c][p][r + 0], bias[r + 0], rnd, fr, a.p_y, wc, whi, wlo);
-                    np_finish_one<FAST, RELU, CODES, 1>(accA[c][p][r + 1], accC[c][p][r + 1], accD[c][p][r + 1], bias[r + 1], rnd, fr, a.p_y, wc, whi, wlo);
-                    np_finish_one<FAST, RELU, CODES, 2>(accA[c][p][r + 2], accC[c][p][r + 2], accD[c][p][r + 2], bias[r + 2], rnd, fr, a.p_y, wc, whi, wlo);
-                    np_finish_one<FAST, RELU, CODES, 3>(accA[c][p][r + 3], accC[c][p][r + 3], accD[c][p][r + 3], bias[r + 3], rnd, fr, a.p_y, wc, whi, wlo);
+                    np_finish_one<FAST, RELU, CODES, 0>(accA[c][p][r + 0], accC[c][p][r + 0], accB[c][p][r + 0], bias[r + 0], rnd, fr, a.p_y, wc, whi, wlo);
+                    np_finish_one<FAST, RELU, CODES, 1>(accA[c][p][r + 1], accC[c][p][r + 1], accB[c][p][r + 1], bias[r + 1], rnd, fr, a.p_y, wc, whi, wlo);
+                    np_finish_one<FAST, RELU, CODES, 2>(accA[c][p][r + 2], accC[c][p][r + 2], accB[c][p][r + 2], bias[r + 2], rnd, fr, a.p_y, wc, whi, wlo);
+                    np_finish_one<FAST, RELU, CODES, 3>(accA[c][p][r + 3], accC[c][p][r + 3], accB[c][p][r + 3], bias[r + 3], rnd, fr, a.p_y, wc, whi, wlo);
                     oc[r4] = wc;
                     oh[r4] = whi;
                     ol[r4] = wlo;
@@ -477,7 +502,7 @@ hipError_t launch_np_mfma(const NpConvArgs &a, hipStream_t st)
     prm.div_tc = make_fastdiv(prm.tiles_c);
     const long long tiles = ((M + BP - 1) / BP) * prm.tiles_c;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    constexpr size_t lds_bytes = (size_t)3 * (2 * BP + 3 * BC) * 64;
+    constexpr size_t lds_bytes = (size_t)3 * (2 * BP + 2 * BC) * 64;
     static_assert(lds_bytes <= (size_t)kLdsBytes, "three stages fit");
     static const hipError_t attr = hipFuncSetAttribute((const void *)conv_np_mfma_kernel<BP, BC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (attr != hipSuccess) return attr;
@@ -492,11 +517,11 @@ hipError_t launch_np_mfma(const NpConvArgs &a, hipStream_t st)
 bool conv_np_mfma_supports(const NpConvArgs &a)
 {
     if (a.groups != 1 || a.C % kStepBytes || a.K % 16) return false;
-    if ((long long)a.R * a.S * a.C > 13000) return false;        // |63 A + D - C| <= 73348 per term: stays below 2^30 (the epilogue doubles it)
+    if ((long long)a.R * a.S * a.C > 13000) return false;        // |64 A + B| <= 65410 per term: stays below 2^30 (the epilogue doubles it)
     if ((long long)a.N * a.H * a.W * a.C >= (1LL << 31) - (1 << 24)) return false;
     if ((long long)a.K * a.R * a.S * a.C >= (1LL << 31) - (1 << 24)) return false;
     if ((long long)a.N * a.P * a.Q >= (1LL << 31) - 512) return false;
-    const uintptr_t al = (uintptr_t)a.xh | (uintptr_t)a.xl | (uintptr_t)a.wh | (uintptr_t)a.wl | (uintptr_t)a.ws | (uintptr_t)a.y | (uintptr_t)a.yh |
+    const uintptr_t al = (uintptr_t)a.xh | (uintptr_t)a.xl | (uintptr_t)a.wh | (uintptr_t)a.wl | (uintptr_t)a.y | (uintptr_t)a.yh |
                          (uintptr_t)a.yl | (uintptr_t)a.b;
     return (al & 15) == 0;
 }
@@ -516,11 +541,11 @@ hipError_t launch_conv_np_direct(const NpConvArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, int8_t *sum, hipStream_t st)
+hipError_t launch_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, hipStream_t st)
 {
     size_t blocks = (n + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
-    np_digits_kernel<<<(int)blocks, 256, 0, st>>>(codes, n, p, hi, lo, sum);
+    np_digits_kernel<<<(int)blocks, 256, 0, st>>>(codes, n, p, hi, lo);
     return hipGetLastError();
 }
 

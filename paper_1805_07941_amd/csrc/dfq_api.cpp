@@ -199,20 +199,18 @@ dfq_status dfq_dequantize_np(const uint8_t *codes, float *x, size_t n, int nbits
     return from_hip(launch_dequantize_np(codes, x, n, nbits, p, frac, (hipStream_t)stream));
 }
 
-dfq_status dfq_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, int8_t *sum, dfq_stream stream)
+dfq_status dfq_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, dfq_stream stream)
 {
     if (p < 4 || p > 7) return DFQ_EFMT;
     if (n == 0) return DFQ_OK;
     if (!codes || !hi || !lo) return DFQ_EINVAL;
-    if (overlaps(codes, n, hi, n) || overlaps(codes, n, lo, n) || overlaps(codes, n, sum, n) || overlaps(hi, n, lo, n) ||
-        overlaps(hi, n, sum, n) || overlaps(lo, n, sum, n))
-        return DFQ_EINVAL;
-    return from_hip(launch_np_digits(codes, n, p, hi, lo, sum, (hipStream_t)stream));
+    if (overlaps(codes, n, hi, n) || overlaps(codes, n, lo, n) || overlaps(hi, n, lo, n)) return DFQ_EINVAL;
+    return from_hip(launch_np_digits(codes, n, p, hi, lo, (hipStream_t)stream));
 }
 
 static dfq_status check_conv_np(NpConvArgs &a, int frac_x, int frac_w, int frac_y)
 {
-    if (!a.xh || !a.xl || !a.wh || !a.wl || !a.ws || (!a.y && !a.yh && !a.yl)) return DFQ_EINVAL;
+    if (!a.xh || !a.xl || !a.wh || !a.wl || (!a.y && !a.yh && !a.yl)) return DFQ_EINVAL;
     if ((a.yh == nullptr) != (a.yl == nullptr)) return DFQ_EINVAL;
     if (a.N < 0) return DFQ_EINVAL;
     if (a.H < 1 || a.W < 1 || a.C < 1 || a.K < 1 || a.R < 1 || a.S < 1 || a.stride < 1 || a.pad < 0 || a.groups < 1) return DFQ_ESHAPE;
@@ -239,11 +237,11 @@ static dfq_status check_conv_np(NpConvArgs &a, int frac_x, int frac_w, int frac_
 }
 
 dfq_status dfq_conv_np_variant(dfq_conv_variant variant, const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl,
-                               const int8_t *ws, const int32_t *b, uint8_t *y, int8_t *yh, int8_t *yl, int N, int H, int W, int C,
-                               int K, int R, int S, int stride, int pad, int groups, int frac_x, int frac_w, int frac_y, int p_y,
-                               int relu, dfq_stream stream)
+                               const int32_t *b, uint8_t *y, int8_t *yh, int8_t *yl, int N, int H, int W, int C, int K, int R, int S,
+                               int stride, int pad, int groups, int frac_x, int frac_w, int frac_y, int p_y, int relu,
+                               dfq_stream stream)
 {
-    NpConvArgs a{xh, xl, wh, wl, ws, b, y, yh, yl, N, H, W, C, K, R, S, stride, pad, groups, 0, 0, 0, p_y, 0, relu ? 1 : 0};
+    NpConvArgs a{xh, xl, wh, wl, b, y, yh, yl, N, H, W, C, K, R, S, stride, pad, groups, 0, 0, 0, p_y, 0, relu ? 1 : 0};
     const dfq_status st = check_conv_np(a, frac_x, frac_w, frac_y);
     if (st != DFQ_OK) return st;
     if (N == 0) return DFQ_OK;
@@ -256,11 +254,11 @@ dfq_status dfq_conv_np_variant(dfq_conv_variant variant, const int8_t *xh, const
     return DFQ_EINVAL;
 }
 
-dfq_status dfq_conv_np(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int8_t *ws, const int32_t *b,
-                       uint8_t *y, int8_t *yh, int8_t *yl, int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
-                       int groups, int frac_x, int frac_w, int frac_y, int p_y, int relu, dfq_stream stream)
+dfq_status dfq_conv_np(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int32_t *b, uint8_t *y,
+                       int8_t *yh, int8_t *yl, int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                       int frac_x, int frac_w, int frac_y, int p_y, int relu, dfq_stream stream)
 {
-    return dfq_conv_np_variant(DFQ_CONV_AUTO, xh, xl, wh, wl, ws, b, y, yh, yl, N, H, W, C, K, R, S, stride, pad, groups, frac_x, frac_w,
+    return dfq_conv_np_variant(DFQ_CONV_AUTO, xh, xl, wh, wl, b, y, yh, yl, N, H, W, C, K, R, S, stride, pad, groups, frac_x, frac_w,
                                frac_y, p_y, relu, stream);
 }
 

@@ -40,7 +40,7 @@ struct ConvArgs {
 // twelve bits), operands and results as base-64 digit planes: beta = 64 * h + l, h and l of the sign of beta.
 struct NpConvArgs {
     const int8_t *xh, *xl;         // input digit planes, NHWC
-    const int8_t *wh, *wl, *ws;    // weight digit planes and their byte-wise sum h + l, [K][R][S][C/groups]
+    const int8_t *wh, *wl;         // weight digit planes, [K][R][S][C/groups]
     const int32_t *b;              // bias at f_x + f_w, may be null
     uint8_t *y;                    // output codes (Eq. 2), may be null
     int8_t *yh, *yl;               // output digit planes, may be null
@@ -89,7 +89,7 @@ hipError_t launch_conv_grouped(const ConvArgs &a, hipStream_t st);
 bool conv_np_mfma_supports(const NpConvArgs &a);
 hipError_t launch_conv_np_mfma(const NpConvArgs &a, hipStream_t st);
 hipError_t launch_conv_np_direct(const NpConvArgs &a, hipStream_t st);
-hipError_t launch_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, int8_t *sum, hipStream_t st);
+hipError_t launch_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, hipStream_t st);
 bool conv_smallc_supports(const ConvArgs &a);
 hipError_t launch_conv_smallc(const ConvArgs &a, hipStream_t st);
 

@@ -134,12 +134,12 @@ def test_conv_np_rejects_bad_arguments_before_launching(B):
     """(fake non-null addresses, 16-byte aligned and far apart: every case below must fail in validation)"""
     L = B.lib()
 
-    def call(variant=B.CONV_AUTO, xh=1 << 20, xl=2 << 20, wh=3 << 20, wl=4 << 20, ws=5 << 20, b=None, y=6 << 20, yh=7 << 20, yl=8 << 20,
+    def call(variant=B.CONV_AUTO, xh=1 << 20, xl=2 << 20, wh=3 << 20, wl=4 << 20, b=None, y=6 << 20, yh=7 << 20, yl=8 << 20,
              N=1, H=8, W=8, Cc=64, K=16, R=3, S=3, stride=1, pad=1, groups=1, fx=8, fw=8, fy=3, p_y=4, relu=0):
-        return L.dfq_conv_np_variant(variant, xh, xl, wh, wl, ws, b, y, yh, yl, N, H, W, Cc, K, R, S, stride, pad, groups, fx, fw, fy, p_y,
+        return L.dfq_conv_np_variant(variant, xh, xl, wh, wl, b, y, yh, yl, N, H, W, Cc, K, R, S, stride, pad, groups, fx, fw, fy, p_y,
                                      relu, None)
 
-    assert call(xh=None) == B.EINVAL and call(ws=None) == B.EINVAL
+    assert call(xh=None) == B.EINVAL and call(wl=None) == B.EINVAL
     assert call(y=None, yh=None, yl=None) == B.EINVAL              # no output at all
     assert call(yl=None) == B.EINVAL                               # one plane without the other
     assert call(N=-1) == B.EINVAL
@@ -156,10 +156,10 @@ def test_conv_np_rejects_bad_arguments_before_launching(B):
     assert call(variant=B.CONV_MFMA, Cc=1472, R=3, S=3) == B.EUNSUPPORTED    # 13248 terms: the int32 partial sums could overflow
     assert call(variant=B.CONV_DEPTHWISE) == B.EINVAL
     assert call(N=0) == B.OK
-    assert L.dfq_np_digits(1 << 20, 16, 3, 2 << 20, 3 << 20, None, None) == B.EFMT
-    assert L.dfq_np_digits(None, 16, 4, 2 << 20, 3 << 20, None, None) == B.EINVAL
-    assert L.dfq_np_digits(1 << 20, 16, 4, 1 << 20, 3 << 20, None, None) == B.EINVAL     # in place
-    assert L.dfq_np_digits(1 << 20, 0, 4, 2 << 20, 3 << 20, None, None) == B.OK
+    assert L.dfq_np_digits(1 << 20, 16, 3, 2 << 20, 3 << 20, None) == B.EFMT
+    assert L.dfq_np_digits(None, 16, 4, 2 << 20, 3 << 20, None) == B.EINVAL
+    assert L.dfq_np_digits(1 << 20, 16, 4, 1 << 20, 3 << 20, None) == B.EINVAL     # in place
+    assert L.dfq_np_digits(1 << 20, 0, 4, 2 << 20, 3 << 20, None) == B.OK
 
 
 def test_np_frac_from_absmax_matches_the_oracle(B):

@@ -53,10 +53,9 @@ def test_np_digits_every_code(B):
     for p in (4, 5, 6, 7):
         codes = np.arange(256, dtype=np.uint8)
         beta = np.array([F.decode(int(c), 8, p) for c in codes])
-        hi, lo, sm = B.np_digits(dev(codes), p, want_sum=True)
+        hi, lo = B.np_digits(dev(codes), p)
         eh, el = digits_of(beta)
         assert np.array_equal(host(hi), eh) and np.array_equal(host(lo), el)
-        assert np.array_equal(host(sm).astype(np.int64), eh.astype(np.int64) + el)
         assert np.array_equal(64 * host(hi).astype(np.int64) + host(lo), beta)
         # a long ragged array
         rng = np.random.default_rng(p)
@@ -70,8 +69,8 @@ def test_np_digits_every_code(B):
 
 def run_both(B, x, px, w, pw, b, f_x, f_w, f_y, p_y, stride, pad, groups, relu, variant):
     xh, xl = B.np_digits(dev(x), px)
-    wh, wl, ws = B.np_digits(dev(w), pw, want_sum=True)
-    y, yh, yl = B.conv_np(xh, xl, wh, wl, ws, None if b is None else dev(b.astype(np.int32)), f_x, f_w, f_y, p_y, stride, pad,
+    wh, wl = B.np_digits(dev(w), pw)
+    y, yh, yl = B.conv_np(xh, xl, wh, wl, None if b is None else dev(b.astype(np.int32)), f_x, f_w, f_y, p_y, stride, pad,
                           groups, relu, variant=variant)
     torch.cuda.synchronize()
     ry, rbeta, _ = NC.conv_np(x, (8, px), w, (8, pw), b, f_x + f_w - f_y, (8, p_y), stride, pad, groups, relu)
@@ -134,9 +133,9 @@ def test_conv_np_against_oracle(B, case):
         assert (mags > 0).mean() > 0.2 and (mags == F.beta_max(8, p_y)).mean() < 0.5       # neither all zero nor all saturated
     # without bias, codes only / digits only
     xh, xl = B.np_digits(dev(x), px)
-    wh, wl, ws = B.np_digits(dev(w), pw, want_sum=True)
-    y1, _, _ = B.conv_np(xh, xl, wh, wl, ws, None, f_x, f_w, f_y, p_y, stride, pad, 1, relu, want_digits=False)
-    _, yh2, yl2 = B.conv_np(xh, xl, wh, wl, ws, None, f_x, f_w, f_y, p_y, stride, pad, 1, relu, want_codes=False)
+    wh, wl = B.np_digits(dev(w), pw)
+    y1, _, _ = B.conv_np(xh, xl, wh, wl, None, f_x, f_w, f_y, p_y, stride, pad, 1, relu, want_digits=False)
+    _, yh2, yl2 = B.conv_np(xh, xl, wh, wl, None, f_x, f_w, f_y, p_y, stride, pad, 1, relu, want_codes=False)
     ry0, rb0, _ = NC.conv_np(x, (8, px), w, (8, pw), None, shift, (8, p_y), stride, pad, 1, relu)
     assert np.array_equal(host(y1), ry0)
     eh, el = digits_of(rb0)
@@ -210,9 +209,9 @@ def test_conv_np_direct_geometries(B, case):
     shift = int(np.ceil(np.log2(R * S * (C // groups)))) // 2 + 12
     run_both(B, x, 4, w, 4, b, 10, shift - 10 + 2, 2, 4, stride, pad, groups, True, B.CONV_AUTO)
     xh, xl = B.np_digits(dev(x), 4)
-    wh, wl, ws = B.np_digits(dev(w), 4, want_sum=True)
+    wh, wl = B.np_digits(dev(w), 4)
     with pytest.raises(B.DfqError) as e:
-        B.conv_np(xh, xl, wh, wl, ws, None, 10, 5, 2, 4, stride, pad, groups, variant=B.CONV_MFMA)
+        B.conv_np(xh, xl, wh, wl, None, 10, 5, 2, 4, stride, pad, groups, variant=B.CONV_MFMA)
     assert e.value.status == B.EUNSUPPORTED
 
 
@@ -238,8 +237,8 @@ def test_three_layers_through_digit_planes(B):
         w_codes = F.quantize(wf, 8, 4, f_w)[0].astype(np.uint8)
         b = np.rint(rng.standard_normal(K) * 0.05 * 2.0 ** (f_in + f_w)).astype(np.int64)
         f_y = 8
-        wh, wl, ws = B.np_digits(B.quantize_np(dev(wf), 8, 4, f_w), 4, want_sum=True)
-        y, xh, xl = B.conv_np(xh, xl, wh, wl, ws, dev(b.astype(np.int32)), f_in, f_w, f_y, 4, 1, R // 2, 1, relu=(i < 2))
+        wh, wl = B.np_digits(B.quantize_np(dev(wf), 8, 4, f_w), 4)
+        y, xh, xl = B.conv_np(xh, xl, wh, wl, dev(b.astype(np.int32)), f_in, f_w, f_y, 4, 1, R // 2, 1, relu=(i < 2))
         ref, rbeta, _ = NC.conv_np(ref, (8, 4), w_codes, (8, 4), b, f_in + f_w - f_y, (8, 4), 1, R // 2, 1, relu=(i < 2))
         assert np.array_equal(host(y), ref), i
         assert (np.abs(rbeta) > 0).mean() > 0.3
@@ -261,8 +260,8 @@ def test_conv_np_full_size_sampled(B, shape):
     b = rng.integers(-(1 << 16), 1 << 16, K)
     shift = 10 + int(round(0.5 * np.log2(R * R * C))) + 5
     xh, xl = B.np_digits(x.to(DEV), 4)
-    wh, wl, ws = B.np_digits(dev(w), 4, want_sum=True)
-    y, yh, yl = B.conv_np(xh, xl, wh, wl, ws, dev(b.astype(np.int32)), shift, 0, 0, 4, 1, R // 2, 1, relu=True)
+    wh, wl = B.np_digits(dev(w), 4)
+    y, yh, yl = B.conv_np(xh, xl, wh, wl, dev(b.astype(np.int32)), shift, 0, 0, 4, 1, R // 2, 1, relu=True)
     torch.cuda.synchronize()
     gy = host(y)
     xn = x.numpy()
