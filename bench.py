@@ -358,7 +358,8 @@ def main():
         # runs of this command (FETCH_SIZE, WRITE_SIZE, each scaled by the copy probe), or null
         traffic = {"hbm": None, "mfma": None, "source": None}
         tpath = os.path.join(ROOT, "profiles", "bench_resnet50_b256_hbm_traffic.txt")
-        if os.path.exists(tpath):
+        # (the summary covers the default command only: batch 256, per-layer formats, fused joins)
+        if os.path.exists(tpath) and args.batch == 256 and not args.no_fuse and not args.per_channel:
             import re
             txt = open(tpath).read()
             for c in ("hbm", "mfma"):

@@ -5,6 +5,7 @@
            <out.txt> --cmd "<command>" --classes <launch_classes.json> [--copy-bytes 268435456]
     python profile_summary.py counters <out.txt> <counter_collection.csv> ... --cmd "<command>" [--cmd ...]
     python profile_summary.py layers <out.txt> <bench_layers.json> ... --cmd "<command>" [--cmd ...]
+    python profile_summary.py variants <out.txt> <bench.log> ... --cmd "<command>" [--cmd ...]
 
 `stats`: per-kernel call count and durations of the whole run, and the kernels of the last full
 pass (between the last two launches of the input quantization).
@@ -49,6 +50,11 @@ def cmd_stats(a):
     for k, e in agg.items():
         out.append(f"{k:88s} {e[0]:6d} {e[1] / 1e3:10.1f} {e[1] / e[0] / 1e3:9.2f} {e[2] / 1e3:9.2f} {e[3] / 1e3:9.2f} {e[4]:6.2f}")
     out.append("")
+    if a.no_pass:
+        out.append("The totals include set-up and warm-up launches of the same command (the minima of the convolution kernels are the")
+        out.append("calibration launches on 8 images).")
+        open(a.out, "w").write("\n".join(out) + "\n")
+        return
     out.append("The totals include the untimed calibration pass, plan set-up and warm-up of the same command.")
     tr = list(csv.DictReader(open(a.trace_csv)))
     tr.sort(key=lambda r: int(r["Start_Timestamp"]))
@@ -168,11 +174,29 @@ def cmd_layers(a):
     open(a.out, "w").write("\n".join(out) + "\n")
 
 
+def cmd_variants(a):
+    import json
+    out = ["bench.py lines of the benchmark's variants (same box, back to back), the fields that differ", "commands:"]
+    out += ["  " + c for c in a.cmd]
+    out.append("")
+    for path in a.logs:
+        d = json.loads([x for x in open(path) if x.startswith("{")][-1])
+        r, o = d.get("roofline", {}), d.get("roofline_other_class", {})
+        out.append(f"weight formats: {d.get('weight_formats')}; joins: {d.get('joins')}")
+        out.append(f"  {d['ms_per_step']:.4f} ms per step, {d['value']:.1f} {d['unit']}, {d.get('images_per_s', 0):.0f} images/s")
+        out.append(f"  parity_checked: {d.get('parity_checked')}")
+        out.append(f"  roofline ({r.get('bound')}): {r.get('achieved')} {r.get('unit')} = {r.get('frac')} of {r.get('peak')}; other class ({o.get('bound')}): "
+                   f"{o.get('achieved')} {o.get('unit')} = {o.get('frac')} of {o.get('peak')}")
+        out.append("")
+    open(a.out, "w").write("\n".join(out) + "\n")
+
+
 def main():
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="what", required=True)
     s = sub.add_parser("stats")
     s.add_argument("stats_csv"); s.add_argument("trace_csv"); s.add_argument("out"); s.add_argument("--cmd", required=True)
+    s.add_argument("--no-pass", action="store_true", help="the command is not the network benchmark: no per-pass section")
     t = sub.add_parser("traffic")
     t.add_argument("fetch_csv"); t.add_argument("write_csv"); t.add_argument("out"); t.add_argument("--cmd", required=True)
     t.add_argument("--classes", required=True)
@@ -183,8 +207,10 @@ def main():
     c.add_argument("--min-dispatches", type=int, default=3, help="skip kernels launched fewer times than this")
     l = sub.add_parser("layers")
     l.add_argument("out"); l.add_argument("jsons", nargs="+"); l.add_argument("--cmd", action="append", required=True)
+    v = sub.add_parser("variants")
+    v.add_argument("out"); v.add_argument("logs", nargs="+"); v.add_argument("--cmd", action="append", required=True)
     a = ap.parse_args()
-    {"stats": cmd_stats, "traffic": cmd_traffic, "counters": cmd_counters, "layers": cmd_layers}[a.what](a)
+    {"stats": cmd_stats, "traffic": cmd_traffic, "counters": cmd_counters, "layers": cmd_layers, "variants": cmd_variants}[a.what](a)
 
 
 if __name__ == "__main__":
