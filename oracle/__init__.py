@@ -65,6 +65,8 @@ def lib():
         L.orc_conv_q_pc.argtypes = [_i8p, _i8p, _i32p, _i8p, _i32p] + [C.c_int] * 12 + [_i32p, C.c_int, C.c_int]
         L.orc_absmax_i32_channels.restype = None
         L.orc_absmax_i32_channels.argtypes = [_i32p, C.c_size_t, C.c_int, C.c_int, C.POINTER(C.c_int64)]
+        L.orc_add_lazy.restype = C.c_int
+        L.orc_add_lazy.argtypes = [_i32p, _i8p, _i8p, C.c_size_t, C.c_int, C.c_int, C.c_int]
         L.orc_requant_i32.restype = None
         L.orc_requant_i32.argtypes = [_i32p, _i8p, C.c_size_t, C.c_int, C.c_int]
         L.orc_eltwise_q.restype = C.c_int
@@ -185,6 +187,21 @@ def requant_i32(acc, shift, relu=False):
     acc = _c(acc, np.int32)
     y = np.empty(acc.shape, np.int8)
     lib().orc_requant_i32(_p(acc, _i32p), _p(y, _i8p), acc.size, int(shift), int(bool(relu)))
+    return y
+
+
+def conv_q_add_lazy(x, w, b, other, f_in, f_w, f_other, f_out, stride=1, pad=0, groups=1, relu=False):
+    """Convolution + element-wise add with a single rounding: the convolution's accumulator (at f_in + f_w, never
+    rounded to a format of its own) plus `other` (int8 [N,P,Q,K] at f_other <= f_in + f_w, at most 22 bits coarser)
+    brought to the accumulator's scale, ReLU on the sum if asked, one rounding shift to f_out."""
+    _, acc = conv_q(x, w, b, f_in, f_w, 0, stride, pad, groups, False, want_y=False, want_acc=True)
+    other = _c(other, np.int8)
+    assert other.shape == acc.shape
+    y = np.empty(acc.shape, np.int8)
+    rc = lib().orc_add_lazy(_p(acc, _i32p), _p(other, _i8p), _p(y, _i8p), acc.size, int(f_in + f_w - f_other),
+                            int(f_in + f_w - f_out), int(bool(relu)))
+    if rc:
+        raise ValueError("oracle conv_q_add_lazy: the second operand must be 0..22 bits coarser than the accumulator")
     return y
 
 

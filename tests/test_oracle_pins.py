@@ -716,3 +716,48 @@ def test_fold_scale_is_the_affine_layer_applied_to_the_convolution():
     w4, b4 = orc.fold_scale(w, None, one_hot, None)
     assert np.array_equal(w4[:4], w[:4]) and np.array_equal(w4[5], w[5]) and not np.array_equal(w4[4], w[4])
     assert np.array_equal(b4, np.zeros(K, np.float32))
+
+
+def test_conv_q_add_lazy_is_one_rounding_of_the_exact_sum():
+    """The single-rounding join against exact rationals: value = acc * 2^-(f_in+f_w) + other * 2^-f_other, rounded once
+    (nearest, ties to even) to f_out and clamped; where the convolution's own format loses nothing it must coincide with
+    the two-rounding form (Eq. 6 then Eq. 10), and on a constructed case it must differ from it."""
+    from fractions import Fraction
+    rng = np.random.default_rng(404)
+    N, H, W, C, K = 1, 3, 4, 8, 5
+    x = rng.integers(-128, 128, (N, H, W, C)).astype(np.int8)
+    w = rng.integers(-128, 128, (K, 1, 1, C)).astype(np.int8)
+    b = rng.integers(-2000, 2000, K).astype(np.int32)
+    other = rng.integers(-128, 128, (N, H, W, K)).astype(np.int8)
+    for f_in, f_w, f_other, f_out, relu in [(4, 7, 5, 3, False), (4, 7, 5, 3, True), (3, 6, 9, 2, False), (5, 5, -2, -4, False),
+                                            (6, 8, 4, 14, False), (2, 2, 4, 4, True)]:
+        y = orc.conv_q_add_lazy(x, w, b, other, f_in, f_w, f_other, f_out, relu=relu)
+        for idx in np.ndindex(N, H, W, K):
+            n, p, q, k = idx
+            acc = orc.conv_acc_at(x, w, b, 1, 0, 1, n, p, q, k)
+            val = Fraction(acc, 1) / Fraction(2) ** (f_in + f_w) + Fraction(int(other[idx])) / Fraction(2) ** f_other
+            if relu:
+                val = max(val, Fraction(0))
+            scaled = val * Fraction(2) ** f_out
+            lo = scaled.numerator // scaled.denominator
+            frac = scaled - lo
+            r = lo + (1 if frac > Fraction(1, 2) or (frac == Fraction(1, 2) and lo % 2) else 0)
+            assert y[idx] == max(-127, min(127, r)), (idx, acc, int(other[idx]))
+    # a convolution format as fine as the accumulator: nothing is lost by the first rounding, both forms agree
+    xs = rng.integers(-3, 4, (1, 2, 2, 4)).astype(np.int8)
+    ws = rng.integers(-3, 4, (3, 1, 1, 4)).astype(np.int8)
+    os_ = rng.integers(-100, 100, (1, 2, 2, 3)).astype(np.int8)
+    mid, _ = orc.conv_q(xs, ws, None, 2, 3, 5)
+    two, _ = orc.eltwise_q(mid, 5, os_, 4, 3, False)
+    assert np.array_equal(orc.conv_q_add_lazy(xs, ws, None, os_, 2, 3, 4, 3), two)
+    # acc = 3 at scale 2^-2 (0.75), other = 1 at 2^0: two roundings give rne(rne(0.75) + 1) = 2, one rounding rne(1.75) = 2;
+    # acc = 2 (0.5): rne(0.5) = 0 -> 0 + 1 = 1, but one rounding of 1.5 gives 2
+    one = np.ones((1, 1, 1, 1), np.int8)
+    for a_, want_two, want_one in [(3, 2, 2), (2, 1, 2), (6, 3, 2), (-2, 1, 0)]:
+        xa = np.full((1, 1, 1, 1), a_, np.int8)
+        mid, _ = orc.conv_q(xa, one, None, 1, 1, 0)
+        two, _ = orc.eltwise_q(mid, 0, one, 0, 0, False)
+        assert int(two[0, 0, 0, 0]) == want_two
+        assert int(orc.conv_q_add_lazy(xa, one, None, one, 1, 1, 0, 0)[0, 0, 0, 0]) == want_one
+    with pytest.raises(ValueError):
+        orc.conv_q_add_lazy(x, w, b, other, 1, 1, 5, 0)          # second operand finer than the accumulator
