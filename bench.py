@@ -46,7 +46,7 @@ def node_bytes(net, nd):
     return H * W * C + P * Q * K
 
 
-def cpu_baseline(net, batch_sample: int, calib_n: int, per_channel: bool = False):
+def cpu_baseline(net, batch_sample: int, calib_n: int, per_channel: bool = False, lazy_joins: bool = False):
     """The oracle as it stands, on the host cores: inference of `batch_sample` images."""
     import oracle as orc
     import oracle.net as onet
@@ -54,7 +54,7 @@ def cpu_baseline(net, batch_sample: int, calib_n: int, per_channel: bool = False
     qz, _ = onet.calibrate(net, x[:calib_n], per_channel=per_channel)
     xs = x[:batch_sample]
     t0 = time.perf_counter()
-    t = onet.infer(net, qz, xs)
+    t = onet.infer(net, qz, xs, lazy_joins=lazy_joins)
     ref_logits = onet.logits(net, qz, t)
     dt = time.perf_counter() - t0
     macs = net.macs_per_image() * batch_sample
@@ -191,6 +191,9 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the per-launch events (pure step timing)")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a HIP graph")
     ap.add_argument("--no-fuse", action="store_true", help="run every residual add as its own dfq_eltwise_q call")
+    ap.add_argument("--lazy-joins", action="store_true",
+                    help="take the residual adds with a single rounding (dfq_conv_q_add_lazy: the accumulator meets the second "
+                         "operand at its own scale) - a different arithmetic from the default, checked against the oracle in that mode")
     ap.add_argument("--per-channel", action="store_true",
                     help="one weight format per output channel (dfq_conv_q_pc) instead of one per layer")
     ap.add_argument("--layers", action="store_true",
@@ -230,7 +233,10 @@ def main():
     x_host = net.input_float()
     x = torch.from_numpy(x_host).to(dev)
     qz, _ = gnet.calibrate(net, x[:args.calib].contiguous(), keep_tensors=False, per_channel=args.per_channel)
-    plan = gnet.Plan(net, qz, args.batch, keep_all=False, fuse=not args.no_fuse)
+    if args.lazy_joins and (args.no_fuse or args.per_channel):
+        print("bench.py: --lazy-joins goes with fused joins and one weight format per layer", file=sys.stderr)
+        sys.exit(2)
+    plan = gnet.Plan(net, qz, args.batch, keep_all=False, fuse=not args.no_fuse, lazy_joins=args.lazy_joins)
 
     convs = conv_nodes(net)
     H0, W0, C0 = net.in_shape
@@ -249,7 +255,7 @@ def main():
     def run_step_recorded():
         st = B._stream(None)
         for (fn, cargs), name in zip(plan._calls_for(x), plan.call_nodes):
-            mf = name in mfma_names and fn.__name__ in ("dfq_conv_q", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add")
+            mf = name in mfma_names and fn.__name__ in ("dfq_conv_q", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_conv_q_add_lazy")
             if mf:
                 e0, e1 = event_pool.pop(), event_pool.pop()
                 e0.record()
@@ -319,7 +325,7 @@ def main():
                 mfma_rate[prefix + label] = round(ops_probe / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
 
     n_joins = sum(1 for nd in net.nodes if nd.op == "eltwise")
-    n_fused = sum(1 for fn, _ in plan._calls_for(x) if fn.__name__ in ("dfq_conv_q_add", "dfq_conv_q_pc_add"))
+    n_fused = sum(1 for fn, _ in plan._calls_for(x) if fn.__name__ in ("dfq_conv_q_add", "dfq_conv_q_pc_add", "dfq_conv_q_add_lazy"))
     macs_step = net.macs_per_image() * args.batch
     tops = 2 * macs_step / (ms_per_step * 1e-3) / 1e12
     imgs = args.batch / (ms_per_step * 1e-3)
@@ -332,7 +338,7 @@ def main():
             dur.setdefault(name, []).append(e0.elapsed_time(e1))
         ops = 0.0
         tsum = 0.0
-        fused_names = {name for (fn, _), name in zip(plan._calls_for(x), plan.call_nodes) if fn.__name__ in ("dfq_conv_q_add", "dfq_conv_q_pc_add")}
+        fused_names = {name for (fn, _), name in zip(plan._calls_for(x), plan.call_nodes) if fn.__name__ in ("dfq_conv_q_add", "dfq_conv_q_pc_add", "dfq_conv_q_add_lazy")}
         # launches by what bounds them at the published peaks: ops / 5 POP/s against bytes / 8 TB/s
         layer_class = {}
         cls = {"mfma": dict(launches=0, ms=0.0, ops=0.0, bytes=0.0, roof_ms=0.0),
@@ -359,7 +365,7 @@ def main():
         traffic = {"hbm": None, "mfma": None, "source": None}
         tpath = os.path.join(ROOT, "profiles", "bench_resnet50_b256_hbm_traffic.txt")
         # (the summary covers the default command only: batch 256, per-layer formats, fused joins)
-        if os.path.exists(tpath) and args.batch == 256 and not args.no_fuse and not args.per_channel:
+        if os.path.exists(tpath) and args.batch == 256 and not args.no_fuse and not args.per_channel and not args.lazy_joins:
             import re
             txt = open(tpath).read()
             for c in ("hbm", "mfma"):
@@ -390,7 +396,7 @@ def main():
         if args.launch_classes:
             order = []
             for (fn, _), name in zip(plan._calls_for(x), plan.call_nodes):
-                if name in mfma_names and fn.__name__ in ("dfq_conv_q", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add"):
+                if name in mfma_names and fn.__name__ in ("dfq_conv_q", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_conv_q_add_lazy"):
                     order.append(dict(layer=name, bound=layer_class[name]))
             json.dump(order, open(args.launch_classes, "w"))
 
@@ -401,7 +407,7 @@ def main():
     if args.cpu_sample > 0:
         import numpy as np
         n_cpu = min(args.cpu_sample, args.batch)
-        ref_logits, cpu = cpu_baseline(net, n_cpu, min(args.calib, args.batch), per_channel=args.per_channel)
+        ref_logits, cpu = cpu_baseline(net, n_cpu, min(args.calib, args.batch), per_channel=args.per_channel, lazy_joins=args.lazy_joins)
         gpu_logits = step().cpu().numpy()[:n_cpu]
         equal = int(sum(bool(np.array_equal(gpu_logits[i], ref_logits[i])) for i in range(n_cpu)))
         parity_checked = dict(images=n_cpu, images_with_identical_logits=equal, tolerance=0,
@@ -414,7 +420,9 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "launch": "per-call from Python" if args.no_graph else "HIP graph replay of the fixed call sequence",
         "joins": "each residual add its own dfq_eltwise_q call" if args.no_fuse else
-                 "%d of %d residual adds run inside the convolution in front of them (%s)" % (n_fused, n_joins, "dfq_conv_q_pc_add" if args.per_channel else "dfq_conv_q_add"),
+                 "%d of %d residual adds run inside the convolution in front of them (%s)" % (n_fused, n_joins, "dfq_conv_q_pc_add" if args.per_channel else
+                                                                                              "dfq_conv_q_add_lazy: ONE rounding per join, a different arithmetic from the default" if args.lazy_joins
+                                                                                              else "dfq_conv_q_add"),
         "weight_formats": "one per output channel (dfq_conv_q_pc)" if args.per_channel else "one per layer",
         "config": {"workload": "configs[4]: ResNet-50-shaped int8 network, 224x224x3, batch %d, formats from a "
                                "single-batch calibrate() on %d images" % (args.batch, args.calib),

@@ -163,6 +163,21 @@ dfq_status dfq_conv_q_add(const int8_t *x, const int8_t *w, const int32_t *b, co
                           int ldy, int ld_other, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_mid, int relu_mid,
                           dfq_fmt fmt_other, dfq_fmt fmt_out, int relu_out, dfq_stream stream);
 
+/* Convolution followed by an element-wise add with ONE rounding (Sec. 3: thresholding is delayed as long as possible
+ * so that low bits are not dropped early): the convolution's accumulator (Eq. 6 with bias, at fmt_in.frac + fmt_w.frac;
+ * it gets no format of its own and no ReLU) and the code of `other` brought to that scale by the exact factor
+ * 2^(fmt_in.frac + fmt_w.frac - fmt_other.frac) are summed without loss, ReLU acts on the sum if relu_out, and
+ *     y = sat8(rne(sum, fmt_in.frac + fmt_w.frac - fmt_out.frac)).
+ * A different arithmetic from dfq_conv_q_add (which rounds the convolution's result to fmt_mid first, as Eq. 6
+ * followed by Eq. 10 on stored tensors does): results agree where the first rounding loses nothing and are the more
+ * accurate ones elsewhere.  fmt_other must be 0 .. 22 bits coarser than the accumulator (DFQ_EFMT otherwise).  Same
+ * kernels, argument conventions and DFQ_EUNSUPPORTED rule as dfq_conv_q_add (the final shift must lie in [0, 23]);
+ * one weight format per layer only. */
+dfq_status dfq_conv_q_add_lazy(const int8_t *x, const int8_t *w, const int32_t *b, const int8_t *other, int8_t *y,
+                               int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                               int ldy, int ld_other, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_other, dfq_fmt fmt_out,
+                               int relu_out, dfq_stream stream);
+
 /* dfq_conv_q_add with one weight format per output channel: the result of dfq_conv_q_pc(...,
  * fmt_mid, relu_mid) followed by dfq_eltwise_q(., fmt_mid, other, fmt_other, y, fmt_out, ...).
  * frac_w, frac_w_lo, frac_w_hi as in dfq_conv_q_pc; everything else as in dfq_conv_q_add. */

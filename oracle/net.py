@@ -73,15 +73,48 @@ def _threshold(acc, relu, rule):
     return orc.threshold_search(counts, j, m)[0]
 
 
+def lazy_pairs(net):
+    """The joins that are taken at the accumulator's scale when inference runs with lazy_joins: an element-wise add of two
+    different tensors one of which is the result of a convolution without activation that nothing else reads - the
+    first such source in the add's own order.  Returns {name of the add node: (convolution node, the other source)}."""
+    readers = {}
+    for nd in net.nodes:
+        for s in nd.srcs:
+            readers[s] = readers.get(s, 0) + 1
+    producer = {nd.dst: nd for nd in net.nodes}
+    pairs = {}
+    for e in net.nodes:
+        if e.op != "eltwise" or e.srcs[0] == e.srcs[1]:
+            continue
+        for i, s in enumerate(e.srcs):
+            c = producer.get(s)
+            if c is not None and c.op == "conv" and not c.relu and readers[s] == 1 and s != net.output_name:
+                pairs[e.name] = (c, e.srcs[1 - i])
+                break
+    return pairs
+
+
 def _forward(net, x, qz: Quantized, calibrating: bool, per_channel: bool = False, rule: str = "maxabs",
-             match_joins: bool = False):
+             match_joins: bool = False, lazy_joins: bool = False):
     t = {net.input_name: _input_codes(net, x, qz, calibrating)}
     readers = {}
     for nd in net.nodes:
         for s in nd.srcs:
             readers[s] = readers.get(s, 0) + 1
     producer = {nd.dst: nd for nd in net.nodes}
+    lazy = lazy_pairs(net) if (lazy_joins and not calibrating) else {}
+    lazy_convs = {c.name for c, _ in lazy.values()}
     for nd in net.nodes:
+        if nd.op == "conv" and nd.name in lazy_convs:
+            continue                      # its accumulator goes straight into the join below; no tensor of its own
+        if nd.op == "eltwise" and nd.name in lazy:
+            c, other = lazy[nd.name]
+            if np.ndim(qz.w_frac[c.name]) != 0:
+                raise ValueError("lazy joins need one weight format per layer")
+            src = c.srcs[0]
+            t[nd.dst] = orc.conv_q_add_lazy(t[src], qz.w[c.name], qz.b[c.name], t[other], qz.frac[src], qz.w_frac[c.name],
+                                            qz.frac[other], qz.frac[nd.dst], c.stride, c.pad, c.groups, relu=nd.relu)
+            continue
         if nd.op == "conv":
             src = nd.srcs[0]
             f_in = qz.frac[src]
@@ -171,9 +204,12 @@ def calibrate(net, x_calib, per_channel: bool = False, rule: str = "maxabs", mat
     return qz, t
 
 
-def infer(net, qz: Quantized, x):
-    """Runs the calibrated network; returns the dict of int8 tensors."""
-    return _forward(net, x, qz, calibrating=False)
+def infer(net, qz: Quantized, x, lazy_joins: bool = False):
+    """Runs the calibrated network; returns the dict of int8 tensors.
+    lazy_joins: the joins lazy_pairs() lists are taken with a single rounding (the convolution's accumulator meets the
+    other operand at its own scale; the convolution's int8 tensor does not exist).  The formats are those of the
+    ordinary calibration."""
+    return _forward(net, x, qz, calibrating=False, lazy_joins=lazy_joins)
 
 
 def logits(net, qz: Quantized, tensors) -> np.ndarray:

@@ -27,7 +27,7 @@ EXPORTS = [
     "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_hist_i32", "dfq_threshold_search", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_fold_scale_f32", "dfq_eltwise_q", "dfq_concat_q", "dfq_concat_q_into", "dfq_pool_q",
     "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_hist_shift", "dfq_fmt_from_absmax_i32_channels",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
-    "dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32",
+    "dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32", "dfq_conv_q_add_lazy",
 ]
 
 
@@ -80,6 +80,8 @@ def lib():
     L.dfq_fold_scale_f32.argtypes = [vp, vp, sz, sz, vp, vp, vp, vp, vp]
     L.dfq_conv_q_select.argtypes = [i32] * 10
     L.dfq_conv_q_add.argtypes = [vp, vp, vp, vp, vp] + [i32] * 12 + [Fmt, Fmt, Fmt, i32, Fmt, Fmt, i32, vp]
+    L.dfq_conv_q_add_lazy.argtypes = [vp, vp, vp, vp, vp] + [i32] * 12 + [Fmt, Fmt, Fmt, Fmt, i32, vp]
+    L.dfq_conv_q_add_lazy.restype = i32
     L.dfq_eltwise_q.argtypes = [vp, Fmt, vp, Fmt, vp, Fmt, vp, sz, i32, vp]
     L.dfq_concat_q.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, Fmt, sz, vp]
     L.dfq_concat_q_into.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, i32, Fmt, sz, vp]
@@ -306,6 +308,30 @@ def conv_q_add(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], othe
     if st == EUNSUPPORTED:
         return None
     _check(st, "dfq_conv_q_add")
+    return y
+
+
+def conv_q_add_lazy(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], other: torch.Tensor, f_in: int, f_w: int,
+                    f_other: int, f_out: int, relu_out: bool, stride: int = 1, pad: int = 0, groups: int = 1,
+                    out: Optional[torch.Tensor] = None, stream=None):
+    """Convolution + element-wise add with a single rounding (the accumulator and `other` summed at the accumulator's
+    scale).  Returns the int8 result, or None when no fused kernel covers the call (nothing was launched)."""
+    _dev(x, torch.int8, "x"); _dev(w, torch.int8, "w"); _dev(other, torch.int8, "other")
+    if b is not None:
+        _dev(b, torch.int32, "b")
+    N, H, W, Cc = x.shape
+    K, R, S, Cg = w.shape
+    if Cg * groups != Cc:
+        raise DfqError(ESHAPE, "conv_q_add_lazy (weight shape does not match C/groups)")
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    if tuple(other.shape) != (N, P, Q, K):
+        raise DfqError(ESHAPE, "conv_q_add_lazy (second operand's shape)")
+    y = out if out is not None else torch.empty((N, P, Q, K), dtype=torch.int8, device=x.device)
+    st = lib().dfq_conv_q_add_lazy(_ptr(x), _ptr(w), _ptr(b), _ptr(other), _ptr(y), N, H, W, Cc, K, R, S, stride, pad, groups,
+                                   K, K, fmt(f_in), fmt(f_w), fmt(f_other), fmt(f_out), int(bool(relu_out)), _stream(stream))
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, "dfq_conv_q_add_lazy")
     return y
 
 

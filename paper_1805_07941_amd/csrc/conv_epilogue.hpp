@@ -155,6 +155,24 @@ __device__ __forceinline__ uint4 requant_add_tile_lane(const v16i &v, const Requ
     }
     return make_uint4(out[0], out[1], out[2], out[3]);
 }
+// The single-rounding form of convolution + add: the accumulators themselves (at f_in + f_w, not rounded to a format of
+// their own) and the second operand's codes shifted left to that scale are summed and rounded once with rq2.  The
+// accumulator is first clamped to +-(127 * 2^23 + 2^29): |other << sb| <= 2^29 (sb <= 22), so beyond that bound the sum
+// saturates whatever the second operand holds, and inside it the 32-bit sum cannot overflow.  7 instructions per output.
+__device__ __forceinline__ uint4 add_tile_lane_lazy(const v16i &v, const v4i &other, int sb, const Requant &rq2)
+{
+    constexpr int kBound = (127 << 23) + (1 << 29);
+    uint32_t out[4];
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        int t[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++)
+            t[e] = max(-kBound, min(kBound, v[4 * j + e])) + (int)((unsigned)byte_of((uint32_t)other[j], e) << sb);
+        out[j] = rq2.fast_four(t[0], t[1], t[2], t[3]);
+    }
+    return make_uint4(out[0], out[1], out[2], out[3]);
+}
 __device__ __forceinline__ void store_tile_lane_fast(const v16i &v, const ConvArgs &a, const Requant &rq, long long m, int kc)
 {
     *(uint4 *)(a.y + (size_t)m * a.ldy + kc) = requant_tile_lane_fast(v, rq);

@@ -63,11 +63,12 @@ struct MfmaParams {
 // convolution result is rounded to its own format in registers, aligned with the operand at the
 // finer scale and the sum rounded once more.
 template <int BP, int BC, int WAVES_P, int WAVES_C, int NSTAGES, bool UT, bool PW, bool GENERAL, int OCC, bool PC = false,
-          bool FUSE = false>
+          bool FUSE = false, bool LAZY = false>
 __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(MfmaParams prm)
 {
     static_assert(!PC || !GENERAL, "the per-channel form is a lean one");
     static_assert(!FUSE || !GENERAL, "the fused add exists in the lean forms only");
+    static_assert(!LAZY || (FUSE && !PC), "the single-rounding join: fused, one weight format per layer");
     static_assert(NSTAGES >= 2 && NSTAGES <= 6, "ring depth");
     static_assert(UT || !PW, "the pointwise form keeps its position in scalar registers");
     constexpr int NW = WAVES_P * WAVES_C;                 // wavefronts per workgroup
@@ -400,7 +401,8 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
                             if constexpr (FUSE) {
                                 const v4i oth = {(int)other[c * PT + p][0], (int)other[c * PT + p][1], (int)other[c * PT + p][2],
                                                  (int)other[c * PT + p][3]};
-                                store_piece(requant_add_tile_lane(acc[c][p], rq, oth, a.add_sa, a.add_sb, rq2), off, yrsrc);
+                                if constexpr (LAZY) store_piece(add_tile_lane_lazy(acc[c][p], oth, a.add_sb, rq2), off, yrsrc);
+                                else store_piece(requant_add_tile_lane(acc[c][p], rq, oth, a.add_sa, a.add_sb, rq2), off, yrsrc);
                             } else {
                                 store_piece(requant_tile_lane_fast(acc[c][p], rq), off, yrsrc);
                             }
@@ -544,7 +546,7 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     using K = void (*)(MfmaParams);
     const bool ut = a.C % kStepBytes == 0;
     const bool pw = ut && a.R == 1 && a.S == 1 && a.stride == 1 && a.pad == 0;
-    static const K kernels[11] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, false, occ>,
+    static const K kernels[12] = {conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, false, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, true, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, false, occ>,
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, false, true, occ>,
@@ -555,10 +557,12 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
                                  per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, false, false, occ>(),
                                  // unpadded 1x1 stride-1 layers with the add behind them fused into the epilogue
                                  conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, false, occ, false, true>,
-                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, occ, true>()};
-    static const hipError_t attr[11] = {big_lds(kernels[0]), big_lds(kernels[1]), big_lds(kernels[2]), big_lds(kernels[3]),
+                                 per_channel_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, occ, true>(),
+                                 // ... with the single-rounding join
+                                 conv_mfma_kernel<BP, BC, WAVES_P, WAVES_C, NSTAGES, true, true, false, occ, false, true, true>};
+    static const hipError_t attr[12] = {big_lds(kernels[0]), big_lds(kernels[1]), big_lds(kernels[2]), big_lds(kernels[3]),
                                         big_lds(kernels[4]), big_lds(kernels[5]), big_lds(kernels[6]), big_lds(kernels[7]),
-                                        big_lds(kernels[8]), big_lds(kernels[9]), big_lds(kernels[10])};
+                                        big_lds(kernels[8]), big_lds(kernels[9]), big_lds(kernels[10]), big_lds(kernels[11])};
     // shifts the epilogue will meet: one, or with per-channel weight formats the declared range
     const int s_lo = a.shift + (a.frac_w ? a.frac_w_lo : 0), s_hi = a.shift + (a.frac_w ? a.frac_w_hi : 0);
     const bool general = !((!a.frac_w || kernels[6]) && s_lo >= 0 && s_hi <= 23 && !a.acc_out && a.y && (a.ldy & 15) == 0 &&
@@ -567,7 +571,7 @@ hipError_t launch_cfg(const ConvArgs &a, hipStream_t st)
     if (a.add) {
         // conv_mfma_fuses() has vouched for the lean pointwise form
         if (general || !pw || (a.frac_w && !kernels[10])) return hipErrorInvalidValue;
-        which = a.frac_w ? 10 : 9;
+        which = a.frac_w ? 10 : a.add_lazy ? 11 : 9;
     }
     if (attr[which] != hipSuccess) return attr[which];
     K kernel = kernels[which];
@@ -604,6 +608,7 @@ bool conv_mfma_fuses(const ConvArgs &a)
     if (a.frac_w && M <= 1024) return false;      // the tile shape for very few pixels has no per-channel lean form
     if (((uintptr_t)a.add & 15) || (a.ldadd & 15) || a.ldadd < a.K) return false;
     if (!(a.add_shift >= 0 && a.add_shift <= 23) || a.add_sa < 0 || a.add_sa > 22 || a.add_sb < 0 || a.add_sb > 22) return false;
+    if (a.add_lazy && a.frac_w) return false;
     return true;
 }
 

@@ -82,7 +82,7 @@ __device__ __forceinline__ void wait_loads_le(int n)
 // (direct-to-LDS loads, lane order chosen so that the epilogue's 16-byte reads are conflict-free) and awaited one
 // unit later by an exact count of the younger operations - it is in LDS, not in registers, so nothing of it is
 // live in the compiler's view while the load is in flight.
-template <int BP, int BC, int WAVES_P, int WAVES_C, bool FUSE, int OCC, bool PC = false, bool ROWIO = false>
+template <int BP, int BC, int WAVES_P, int WAVES_C, bool FUSE, int OCC, bool PC = false, bool ROWIO = false, bool LAZY = false>
 __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(PwParams prm)
 {
     static_assert(!ROWIO || (WAVES_C == 1 && BC == 128 && BP / WAVES_P == 32), "row-wise epilogue: wavefront tiles of 32 x 128");
@@ -219,6 +219,8 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
     Requant rq, rq2;
     rq.init(a.shift, a.relu);
     rq2.init(FUSE ? a.add_shift : 1, a.add_relu);
+    static_assert(!LAZY || (FUSE && !PC), "the single-rounding join: fused, one weight format per layer");
+    constexpr bool lazy = LAZY;               // single-rounding join: the accumulator itself meets the second operand
     __syncthreads();   // bias_lds complete
 
     // consumer position: unit (c_pt, c_ct) and step of the item being multiplied; reader position:
@@ -355,7 +357,9 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
                 } else {
 #pragma unroll
                     for (int c = 0; c < CT; c++)
-                        out[c] = FUSE ? requant_add_tile_lane(acc[c][0], rq, oth[c], a.add_sa, a.add_sb, rq2) : requant_tile_lane_fast(acc[c][0], rq);
+                        out[c] = !FUSE ? requant_tile_lane_fast(acc[c][0], rq)
+                                 : lazy ? add_tile_lane_lazy(acc[c][0], oth[c], a.add_sb, rq2)
+                                        : requant_add_tile_lane(acc[c][0], rq, oth[c], a.add_sa, a.add_sb, rq2);
                 }
                 // results into the slot, [pixel][16-byte piece ^ (pixel & 7)]; the second operand has been read out of it,
                 // and LDS operations of one wavefront execute in order
@@ -418,8 +422,9 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
 #pragma unroll
                         for (int p = 0; p < PT; p++) {
                             const unsigned off = lane_yoff + tile_off + (unsigned)(p * 32 * a.ldy + c * 32);
-                            if (FUSE) store_piece(requant_add_tile_lane(acc[c][p], rq, other[c * PT + p], a.add_sa, a.add_sb, rq2), off, yrsrc);
-                            else store_piece(requant_tile_lane_fast(acc[c][p], rq), off, yrsrc);
+                            if (!FUSE) store_piece(requant_tile_lane_fast(acc[c][p], rq), off, yrsrc);
+                            else if (lazy) store_piece(add_tile_lane_lazy(acc[c][p], other[c * PT + p], a.add_sb, rq2), off, yrsrc);
+                            else store_piece(requant_add_tile_lane(acc[c][p], rq, other[c * PT + p], a.add_sa, a.add_sb, rq2), off, yrsrc);
                         }
                 }
                 if (FUSE) wait_loads_for<kStoresPerUnit>(other_next[0], other_next[1], other_next[2], other_next[3]);
@@ -550,6 +555,15 @@ hipError_t launch_pw(const ConvArgs &a, hipStream_t st)
     constexpr int occ = PER_CU * WAVES_P * WAVES_C / 4;
     if (a.add) {
         if constexpr (kCanFuse) {
+            if (a.add_lazy) {
+                if constexpr (!PC) {
+                    static const hipError_t attr = big_lds_pw(conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, true, occ, false, ROWIO, true>);
+                    if (attr != hipSuccess) return attr;
+                    conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, true, occ, false, ROWIO, true><<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
+                    return hipGetLastError();
+                }
+                return hipErrorInvalidValue;
+            }
             static const hipError_t attr = big_lds_pw(conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, true, occ, PC, ROWIO>);
             if (attr != hipSuccess) return attr;
             conv_pw_kernel<BP, BC, WAVES_P, WAVES_C, true, occ, PC, ROWIO><<<(unsigned)grid, WAVES_P * WAVES_C * 64, lds_bytes, st>>>(prm);
@@ -597,6 +611,7 @@ bool conv_pw_supports(const ConvArgs &a)
         if (((uintptr_t)a.add & 15) || (a.ldadd & 15) || a.ldadd < a.K) return false;
         if ((long long)a.N * a.P * a.Q * a.ldadd >= (1LL << 31)) return false;
         if (!(a.add_shift >= 0 && a.add_shift <= 23) || a.add_sa < 0 || a.add_sa > 22 || a.add_sb < 0 || a.add_sb > 22) return false;
+        if (a.add_lazy && a.frac_w) return false;        // the single-rounding join exists for one weight format per layer only
     }
     return true;
 }

@@ -308,6 +308,35 @@ dfq_status dfq_conv_q_add(const int8_t *x, const int8_t *w, const int32_t *b, co
     return run_conv_add(c, x, other, y, N, H, W, C, K, ldy, ld_other, fmt_mid, fmt_other, fmt_out, relu_out, stream);
 }
 
+dfq_status dfq_conv_q_add_lazy(const int8_t *x, const int8_t *w, const int32_t *b, const int8_t *other, int8_t *y, int N, int H,
+                               int W, int C, int K, int R, int S, int stride, int pad, int groups, int ldy, int ld_other,
+                               dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_other, dfq_fmt fmt_out, int relu_out, dfq_stream stream)
+{
+    ConvCheck c = check_conv(x, w, b, y, nullptr, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, fmt_w, fmt_out, 0, true);
+    if (c.st != DFQ_OK) return c.st;
+    if (!fmt_ok(fmt_other)) return DFQ_EFMT;
+    if (!y || !other) return DFQ_EINVAL;
+    if (ld_other < K) return DFQ_ESHAPE;
+    // Eq. 12: a code of magnitude <= 2^7 shifted by <= 22 bits stays below 2^29
+    const int sb = fmt_in.frac + fmt_w.frac - fmt_other.frac;
+    if (sb < 0 || sb > 22) return DFQ_EFMT;
+    if (N == 0) return DFQ_OK;
+    const size_t npix = (size_t)N * c.a.P * c.a.Q;
+    if (overlaps(other, npix * (size_t)ld_other, y, npix * (size_t)ldy) ||
+        overlaps(other, npix * (size_t)ld_other, x, (size_t)N * H * W * C))
+        return DFQ_EINVAL;
+    c.a.add = other;
+    c.a.ldadd = ld_other;
+    c.a.add_sa = 0;
+    c.a.add_sb = sb;
+    c.a.add_shift = c.a.shift;                    // f_in + f_w - f_out
+    c.a.add_relu = relu_out ? 1 : 0;
+    c.a.add_lazy = 1;
+    if (conv_pw_supports(c.a)) return from_hip(launch_conv_pw(c.a, (hipStream_t)stream));
+    if (conv_mfma_fuses(c.a)) return from_hip(launch_conv_mfma(c.a, (hipStream_t)stream));
+    return DFQ_EUNSUPPORTED;
+}
+
 dfq_status dfq_conv_q_pc_add(const int8_t *x, const int8_t *w, const int32_t *b, const int8_t *other, int8_t *y, int N,
                              int H, int W, int C, int K, int R, int S, int stride, int pad, int groups, int ldy,
                              int ld_other, dfq_fmt fmt_in, const int32_t *frac_w, int frac_w_lo, int frac_w_hi,

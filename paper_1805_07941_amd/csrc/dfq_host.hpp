@@ -28,6 +28,9 @@ struct ConvArgs {
     int add_sa = 0, add_sb = 0;  // left shifts of the convolution result and of `add`
     int add_shift = 0;           // finer scale's fractional length minus that of y
     int add_relu = 0;
+    // Single-rounding form: the accumulator itself (no format of its own; `shift` and `relu` are not used) plus
+    // `add` << add_sb, rounded once by add_shift = f_in + f_w - f_out; add_sa is 0.
+    int add_lazy = 0;
     // One weight format per output channel (Sec. 3), or frac_w == null: a device array of K
     // fractional lengths; `shift` then holds f_in - f_out and channel k is rescaled by a rounding
     // shift of shift + frac_w[k] (its bias is at f_in + frac_w[k]).  The host cannot read the array:

@@ -185,17 +185,26 @@ class Plan:
     a pass is a fixed sequence of library calls with no allocation and no host
     synchronization."""
 
-    def __init__(self, net, qz: Quantized, batch: int, device="cuda:0", keep_all: bool = True, fuse: bool = False):
+    def __init__(self, net, qz: Quantized, batch: int, device="cuda:0", keep_all: bool = True, fuse: bool = False,
+                 lazy_joins: bool = False):
         """fuse: the joins are merged into the convolutions in front of them (Sec. 3) where that gives the
         same bytes.  A convolution whose only consumer is the element-wise add that follows it directly
         is run together with that add by one dfq_conv_q_add call where a fused kernel covers it (the
         convolution's own int8 tensor is then never produced).  A convolution that feeds only a concat
         and already produces the concat's format writes straight into its channel slice of the joined
         tensor (no rescale is due, so no copy either); only the other branches pass through
-        dfq_concat_q_into."""
+        dfq_concat_q_into.
+        lazy_joins (with fuse): every add of two different tensors one of which is the result of a convolution without
+        activation that nothing else reads - the first such source in the add's own order - is taken with a single
+        rounding by dfq_conv_q_add_lazy (a different arithmetic: the convolution's accumulator meets the other operand
+        at its own scale).  Raises if the library has no kernel for one of them: there is no silent mixture."""
         self.net, self.qz, self.batch, self.device = net, qz, batch, device
         self.order = list(range(len(net.nodes)))                             # node indices in execution order
-        self.fused: Dict[int, int] = self._fusable_pairs() if fuse else {}   # conv node index -> add node index
+        if lazy_joins and not fuse:
+            raise ValueError("lazy_joins needs fuse=True")
+        self.lazy = bool(lazy_joins)
+        # conv node index -> add node index
+        self.fused: Dict[int, int] = (self._lazy_pairs() if lazy_joins else self._fusable_pairs()) if fuse else {}
         self.slice_of: Dict[str, tuple] = self._direct_concat_branches() if fuse else {}   # tensor -> (joined tensor, channel offset)
         self.buf: Dict[str, torch.Tensor] = {}
         H, W, Cc = net.shapes[net.input_name]
@@ -249,6 +258,35 @@ class Plan:
                     continue
             if ok:
                 pairs[j - 1] = j
+        return pairs
+
+    def _lazy_pairs(self) -> Dict[int, int]:
+        """The pairs of the single-rounding mode (see __init__); a pair whose convolution sits two nodes ahead of the add
+        is run behind the node between them, which must not depend on it."""
+        net, qz = self.net, self.qz
+        readers: Dict[str, int] = {}
+        for nd in net.nodes:
+            for s in nd.srcs:
+                readers[s] = readers.get(s, 0) + 1
+        where = {nd.dst: i for i, nd in enumerate(net.nodes)}
+        pairs = {}
+        for j, e in enumerate(net.nodes):
+            if e.op != "eltwise" or e.srcs[0] == e.srcs[1]:
+                continue
+            for s in e.srcs:
+                i = where.get(s)
+                c = net.nodes[i] if i is not None else None
+                if c is None or c.op != "conv" or c.relu or readers[s] != 1 or s == net.output_name:
+                    continue
+                if c.name in qz.w_frac_dev or not self._plain_pointwise(c):
+                    raise NotImplementedError("lazy join behind %s: no single-rounding kernel for this convolution" % c.name)
+                if i == j - 2 and c.dst not in net.nodes[j - 1].srcs:
+                    at = self.order.index(j - 2)
+                    self.order[at], self.order[at + 1] = j - 1, j - 2
+                elif i != j - 1:
+                    raise NotImplementedError("lazy join behind %s: the convolution is not next to its add" % c.name)
+                pairs[i] = j
+                break
         return pairs
 
     def _direct_concat_branches(self) -> Dict[str, tuple]:
@@ -370,6 +408,16 @@ class Plan:
                 head = (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(), t[other].data_ptr(),
                         t[add.dst].data_ptr(), N, H, W, Cc, K, nd.R, nd.R, nd.stride, nd.pad, nd.groups, K, K, f(qz.frac[src]))
                 tail = (f(qz.frac[nd.dst]), int(nd.relu), f(qz.frac[other]), f(qz.frac[add.dst]), int(add.relu))
+                if self.lazy:
+                    fn = L.dfq_conv_q_add_lazy
+                    args = head + (f(qz.w_frac[nd.name]), f(qz.frac[other]), f(qz.frac[add.dst]), int(add.relu))
+                    rc = fn(*args, B._stream(None))
+                    if rc != B.OK:
+                        raise B.DfqError(rc, "dfq_conv_q_add_lazy (%s)" % nd.name)
+                    calls.append((fn, args))
+                    names.append(nd.name)
+                    fused_adds.add(self.fused[idx])
+                    continue
                 if nd.name in qz.w_frac_dev:
                     fn = L.dfq_conv_q_pc_add
                     args = head + (qz.w_frac_dev[nd.name].data_ptr(), int(qz.w_frac[nd.name].min()),

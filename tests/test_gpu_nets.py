@@ -386,3 +386,36 @@ def test_graph_replay_matches_eager(G):
     x2 = dev(net.input_float()[::-1].copy())
     e2 = host(plan.run(x2)).copy()
     assert np.array_equal(host(plan.run_graph(x2)), e2) and not np.array_equal(e2, eager)
+
+
+def test_resnet50_lazy_joins_full_batch(G):
+    """bench.py --lazy-joins: the ResNet-50-shaped network at batch 256 with all sixteen joins taken with a single
+    rounding (dfq_conv_q_add_lazy), pooled buffers, graph replay: logits and every resident tensor of three images
+    against the oracle's inference in the same mode; the formats are those of the ordinary calibration."""
+    B, gnet = G
+    batch = 256
+    net = wl.resnet50(batch=batch)
+    x = net.input_float()
+    calib = x[:2]
+    qz_o, t_o = onet.calibrate(net, calib)
+    qz_g, t_g = gnet.calibrate(net, dev(calib), keep_tensors=False)
+    assert qz_g.frac == qz_o.frac
+    del t_o, t_g
+    xd = dev(x)
+    plan = gnet.Plan(net, qz_g, batch, keep_all=False, fuse=True, lazy_joins=True)
+    for rep in range(2):
+        got = host(plan.run_graph(xd)).copy()
+    assert sum(1 for fn, _ in plan._calls if fn.__name__ == "dfq_conv_q_add_lazy") == 16
+    assert not any(fn.__name__ in ("dfq_conv_q_add", "dfq_eltwise_q") for fn, _ in plan._calls)
+    names = plan.resident()
+    differs = 0
+    for i in (0, batch // 2 + 1, batch - 1):
+        t = onet.infer(net, qz_o, x[i:i + 1], lazy_joins=True)
+        assert np.array_equal(got[i:i + 1], onet.logits(net, qz_o, t)), i
+        for name in names:
+            if name != net.input_name or not net.input_is_int8:
+                assert np.array_equal(host(plan.buf[name][i:i + 1]), t[name]), (i, name)
+        differs += int(not np.array_equal(onet.logits(net, qz_o, onet.infer(net, qz_o, x[i:i + 1])), got[i:i + 1]))
+    assert differs > 0                         # it is a different arithmetic from the two-rounding joins
+    with pytest.raises(ValueError):
+        gnet.Plan(net, qz_g, batch, lazy_joins=True)

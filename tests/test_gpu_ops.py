@@ -539,6 +539,62 @@ def test_conv_q_add_full_size_sampled(B, shape, per_channel):
         assert np.array_equal(got[n:n + 1], ref), n
 
 
+@pytest.mark.parametrize("shape", [(3, 19, 17, 64, 256), (2, 23, 21, 256, 384), (2, 30, 30, 128, 64), (2, 14, 14, 256, 1024),
+                                   (3, 7, 7, 512, 2048), (5, 21, 19, 320, 256), (40, 14, 14, 1024, 512)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_conv_q_add_lazy_small(B, shape):
+    """The single-rounding join (accumulator + second operand at the accumulator's scale, one rescale) against its
+    oracle, on every kernel form that carries it, for alignment shifts from 0 to 22 and final shifts from 0 to 23."""
+    N, H, W, C, K = shape
+    rng = np.random.default_rng(sum(shape) + 1)
+    x, w, b = _rand_conv(rng, N, H, W, C, K, 1, 1, 1)
+    other = rng.integers(-128, 128, (N, H, W, K)).astype(np.int8)
+    xd, wd, bd, od = dev(x), dev(w), dev(b), dev(other)
+    for f_in, f_w, f_other, f_out, relu_out in [(4, 7, 5, 3, True), (4, 9, 4, 0, False), (3, 6, 9, 2, True), (5, 8, 13, -3, False),
+                                                (6, 10, -6, -7, False), (5, 6, 11, 11, True), (7, 16, 3, 0, False)]:
+        ref = orc.conv_q_add_lazy(x, w, b, other, f_in, f_w, f_other, f_out, relu=relu_out)
+        got = B.conv_q_add_lazy(xd, wd, bd, od, f_in, f_w, f_other, f_out, relu_out)
+        assert got is not None
+        assert np.array_equal(host(got), ref), (f_in, f_w, f_other, f_out, relu_out)
+    with pytest.raises(B.DfqError):
+        B.conv_q_add_lazy(xd, wd, bd, od, 2, 2, 5, 0, True)           # second operand finer than the accumulator
+    with pytest.raises(B.DfqError):
+        B.conv_q_add_lazy(xd, wd, bd, od, 16, 16, 4, 8, True)         # 28 bits coarser
+    assert B.conv_q_add_lazy(xd, wd, bd, od, 16, 16, 12, 4, True) is None      # final shift 28: no lean form
+
+
+@pytest.mark.parametrize("shape", [(56, 64, 256), (28, 128, 512), (14, 256, 1024), (7, 512, 2048)], ids=lambda s: "x".join(map(str, s)))
+def test_conv_q_add_lazy_full_size_sampled(B, shape):
+    """dfq_conv_q_add_lazy at batch 256 (many units per workgroup): sampled outputs through the oracle's single-element
+    convolution and exact integer arithmetic, two whole images through the oracle's own call, and a count of where it
+    differs from the two-rounding call (it must, somewhere, and rarely by more than one code)."""
+    H, C, K = shape
+    N = 256
+    rng = np.random.default_rng(6000 + H)
+    x, w, b, other, s = _scaled_pointwise_case(rng, N, H, C, K)
+    f_in, f_other, f_out, relu_out = 4, 4, 3, True
+    f_w = f_out - f_in + s + 1                    # final shift s + 1: the sum of two tensors of similar range
+    sb = f_in + f_w - f_other
+    xd, wd, bd, od = dev(x), dev(w), dev(b), dev(other)
+    got_d = B.conv_q_add_lazy(xd, wd, bd, od, f_in, f_w, f_other, f_out, relu_out)
+    assert got_d is not None
+    got = host(got_d)
+    pts = [(0, 0, 0, 0), (N - 1, H - 1, H - 1, K - 1), (N - 1, 0, H - 1, 0), (0, H - 1, 0, K - 1)]
+    pts += [tuple(int(v) for v in (rng.integers(N), rng.integers(H), rng.integers(H), rng.integers(K))) for _ in range(400)]
+    for pt in pts:
+        n, p, q, k = pt
+        t = orc.conv_acc_at(x, w, b, 1, 0, 1, n, p, q, k) + (int(other[pt]) << sb)
+        assert int(got[pt]) == orc.requant8(max(t, 0), s + 1), pt
+    for n in (0, N - 1):
+        ref = orc.conv_q_add_lazy(x[n:n + 1], w, b, other[n:n + 1], f_in, f_w, f_other, f_out, relu=relu_out)
+        assert np.array_equal(got[n:n + 1], ref), n
+        assert 0.2 < (ref > 0).mean() and (ref == 127).mean() < 0.1
+    two = B.conv_q_add(xd, wd, bd, od, f_in, f_w, f_other, False, f_other, f_out, relu_out)
+    diff = (got_d.to(torch.int16) - two.to(torch.int16)).abs()
+    # (more than one code apart only where the two-rounding form clamps the convolution's own result at +-127 first)
+    assert 0.001 < float((diff != 0).float().mean()) < 0.5 and float((diff > 1).float().mean()) < 0.05
+
+
 def _ties_bias(rng, K, s):
     """Bias values that are exact ties or near-ties of a rounding shift by s, with quotients inside [-127, 127]."""
     t = rng.integers(-120, 121, K).astype(np.int64)

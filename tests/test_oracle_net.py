@@ -202,3 +202,35 @@ def test_scale_layers_are_folded_before_quantizing():
     assert np.array_equal(qz.b[nd.name], orc.quantize_i32(b2, qz.frac["input"] + f_w))
     assert not np.array_equal(qz.w[nd.name], qz0.w[nd.name])
     assert np.isfinite(onet.logits(net, qz, t)).all()
+
+
+def test_lazy_joins_are_single_roundings_of_the_listed_pairs():
+    """Inference with lazy_joins: the sixteen joins of the ResNet-50-shaped graph pair with the third convolution of their
+    block (the first listed source that qualifies, also where a projection qualifies too); the paired convolutions leave
+    no tensor; everything in front of the first join is untouched; the first join is the oracle's single-rounding call
+    on the same operands; the results differ from ordinary inference, by little."""
+    net = wl.resnet50(batch=2, hw=32, classes=10)
+    x = net.input_float()
+    qz, _ = onet.calibrate(net, x)
+    std = onet.infer(net, qz, x)
+    lazy = onet.infer(net, qz, x, lazy_joins=True)
+    pairs = onet.lazy_pairs(net)
+    adds = [nd for nd in net.nodes if nd.op == "eltwise"]
+    assert len(adds) == 16 and set(pairs) == {e.name for e in adds}
+    assert all(c.name.endswith("_c") for c, _ in pairs.values())
+    assert all(c.dst not in lazy for c, _ in pairs.values()) and all(e.dst in lazy for e in adds)
+    first = adds[0]
+    for nd in net.nodes:
+        if nd is first:
+            break
+        if nd.dst in lazy:
+            assert np.array_equal(lazy[nd.dst], std[nd.dst]), nd.name
+    c, other = pairs[first.name]
+    want = orc.conv_q_add_lazy(std[c.srcs[0]], qz.w[c.name], qz.b[c.name], std[other], qz.frac[c.srcs[0]], qz.w_frac[c.name],
+                               qz.frac[other], qz.frac[first.dst], c.stride, c.pad, c.groups, relu=first.relu)
+    assert np.array_equal(lazy[first.dst], want)
+    d = np.abs(lazy[first.dst].astype(np.int16) - std[first.dst].astype(np.int16))
+    assert 0 < (d != 0).mean() < 0.5 and np.percentile(d, 99) <= 1
+    # calibration does not know the mode: same formats either way
+    qz2, _ = onet.calibrate(net, x)
+    assert qz2.frac == qz.frac
