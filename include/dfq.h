@@ -163,8 +163,8 @@ dfq_status dfq_conv_q_add(const int8_t *x, const int8_t *w, const int32_t *b, co
                           int ldy, int ld_other, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_mid, int relu_mid,
                           dfq_fmt fmt_other, dfq_fmt fmt_out, int relu_out, dfq_stream stream);
 
-/* Convolution followed by an element-wise add with ONE rounding (Sec. 3: thresholding is delayed as long as possible
- * so that low bits are not dropped early): the convolution's accumulator (Eq. 6 with bias, at fmt_in.frac + fmt_w.frac;
+/* Convolution followed by an element-wise add with ONE rounding (Sec. 3 wants a value thresholded only when the
+ * datapath can carry it no further): the convolution's accumulator (Eq. 6 with bias, at fmt_in.frac + fmt_w.frac;
  * it gets no format of its own and no ReLU) and the code of `other` brought to that scale by the exact factor
  * 2^(fmt_in.frac + fmt_w.frac - fmt_other.frac) are summed without loss, ReLU acts on the sum if relu_out, and
  *     y = sat8(rne(sum, fmt_in.frac + fmt_w.frac - fmt_out.frac)).

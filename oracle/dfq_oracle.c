@@ -325,8 +325,8 @@ void orc_requant_i32(const int32_t *acc, int8_t *y, size_t n, int shift, int rel
     }
 }
 
-/* Convolution followed by an element-wise add with ONE rounding (Sec. 3: thresholding is delayed as long as
- * possible so that low bits are not dropped early; Eq. 6 and Eq. 10 at the accumulator's scale): the accumulator
+/* Convolution followed by an element-wise add with ONE rounding (Sec. 3 wants a value thresholded only when the
+ * datapath can carry it no further; Eq. 6 and Eq. 10 at the accumulator's scale): the accumulator
  * acc[i] (sum of Eq. 6 plus bias, at f_acc = f_in + f_w) and the code other[i] (at f_other <= f_acc) brought to f_acc by
  * the exact factor 2^(f_acc - f_other) are summed without loss, ReLU acts on the sum if asked, and the sum is rescaled
  * once to f_out: y[i] = sat8(rne(acc[i] + other[i] * 2^sb, shift)).  Returns -1 unless 0 <= sb <= 22. */
