@@ -72,6 +72,28 @@ def conv_np(x_codes, fmt_x, w_codes, fmt_w, bias, shift: int, fmt_y, stride=1, p
     return codes.astype(np.uint8 if fmt_y[0] <= 8 else np.uint16), beta, acc
 
 
+def eltwise_np(a_codes, fmt_a, f_a: int, b_codes, fmt_b, f_b: int, fmt_y, f_y: int, relu=False):
+    """Eq. 10 on (n, p) codes with power-of-two scales: the two values alpha_a * beta_a and alpha_b * beta_b are brought to
+    the finer of their scales by exact factors, summed without loss, ReLU acts on the sum if asked, and the sum is
+    converted once to the output format at 2^-f_y (nearest representable integer, ties to the even significand,
+    saturation).  Returns (codes, beta_y int64, sum int64 at the finer scale before ReLU)."""
+    ba = decode_tensor(a_codes, *fmt_a)
+    bb = decode_tensor(b_codes, *fmt_b)
+    assert ba.shape == bb.shape
+    F_ = max(int(f_a), int(f_b))
+    t = ba * (1 << (F_ - int(f_a))) + bb * (1 << (F_ - int(f_b)))
+    v = np.maximum(t, 0) if relu else t
+    assert np.abs(v).max(initial=0) < (1 << 52)
+    beta = F.round_to_beta(np.ldexp(v.astype(np.float64), -(F_ - int(f_y))), *fmt_y)
+    enc = np.full(F.beta_max(*fmt_y) + 1, -1, np.int64)
+    for c in range(1 << (fmt_y[0] - 1)):
+        enc[F.decode(c, *fmt_y)] = c
+    mag = np.abs(beta)
+    assert (enc[mag] >= 0).all()
+    codes = enc[mag] | np.where(beta < 0, 1 << (fmt_y[0] - 1), 0)
+    return codes.astype(np.uint8 if fmt_y[0] <= 8 else np.uint16), beta, t
+
+
 def conv_sum_at(bx, bw, bias, stride, pad, groups, n, p, q, k) -> int:
     """One output's accumulator (sum + bias) by plain loops over Python integers."""
     N, H, W, C = bx.shape

@@ -127,3 +127,30 @@ def test_deepest_reduction_needs_eq8s_width_and_is_exact():
     assert acc[0, 1, 1, 0] > 2 ** 34
     # 4608 * 1984^2 / 2^25 = 540.56...: between 528 (field 0 of the binade of step 32) and 544: nearest is 544
     assert beta[0, 1, 1, 0] == 544 and beta[0, 1, 1, 1] == -544
+
+
+def test_eltwise_np_against_fractions_enumeration_and_the_int8_add():
+    """Eq. 10 on (n, p) codes: exact rationals and the enumerated code set on random codes of mixed formats and scales;
+    the members that are int8 must give what the int8 path's add (pinned on its own) gives."""
+    rng = np.random.default_rng(21)
+    for fa, f_a, fb, f_b, fy, f_y, relu in [((8, 4), 9, (8, 4), 9, (8, 4), 8, False), ((8, 4), 9, (8, 4), 6, (8, 4), 5, True),
+                                            ((8, 4), 3, (8, 5), 12, (8, 4), 2, False), ((8, 5), 7, (8, 4), 7, (8, 6), 9, False),
+                                            ((8, 4), 5, (8, 4), 5, (8, 4), 12, True), ((8, 4), 10, (8, 4), 0, (8, 4), 0, False)]:
+        a = rng.integers(0, 256, 400).astype(np.uint8)
+        b = rng.integers(0, 256, 400).astype(np.uint8)
+        y, beta, t = NC.eltwise_np(a, fa, f_a, b, fb, f_b, fy, f_y, relu)
+        for i in range(400):
+            val = Fraction(F.decode(int(a[i]), *fa)) / Fraction(2) ** f_a + Fraction(F.decode(int(b[i]), *fb)) / Fraction(2) ** f_b
+            if relu:
+                val = max(val, Fraction(0))
+            want_b, want_c = _nearest_by_enumeration(val * Fraction(2) ** f_y, *fy)
+            assert beta[i] == want_b and y[i] == want_c, (i, a[i], b[i])
+    ai = rng.integers(-127, 128, 2000).astype(np.int8)
+    bi = rng.integers(-127, 128, 2000).astype(np.int8)
+    for fmt in [(8, 7), (8, 6)]:
+        ac = np.array([F.encode(int(v), *fmt) for v in ai], np.uint8)
+        bc = np.array([F.encode(int(v), *fmt) for v in bi], np.uint8)
+        for f_a, f_b, f_y, relu in [(4, 5, 3, True), (6, 2, 2, False), (3, 3, 3, False), (5, 4, 7, False)]:
+            y8, acc8 = oracle.eltwise_q(ai, f_a, bi, f_b, f_y, relu, want_acc=True)
+            _, beta, t = NC.eltwise_np(ac, fmt, f_a, bc, fmt, f_b, fmt, f_y, relu)
+            assert np.array_equal(t, acc8) and np.array_equal(beta, y8)
