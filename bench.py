@@ -173,8 +173,34 @@ def bench_layers_np(args):
                          pct_hbm_peak=round(100 * by / ms / 1e6 / HBM_PEAK_GBS, 1), pct_roofline=round(100 * t_roof / ms, 1),
                          formats=dict(f_x=f_x, f_w=f_w, f_y=f_y), nonzero_outputs=round(nonzero, 3)))
         del xhs, xls, outs, xh, xl
+    # the residual joins of the same network on (8, 4) codes (dfq_eltwise_np: four planes in, two out, 6 B per element)
+    joins = []
+    gen = torch.Generator(device=dev).manual_seed(1)
+    for H, C in ((56, 256), (28, 512), (14, 1024), (7, 2048)):
+        shape = (args.batch, H, H, C)
+        codes = [torch.randint(0, 256, shape, dtype=torch.uint8, device=dev, generator=gen) for _ in range(2)]
+        (ah, al), (bh, bl) = [B.np_digits(c, 4) for c in codes]
+        del codes
+        yh, yl = torch.empty_like(ah), torch.empty_like(ah)
+        L = B.lib()
+        st = torch.cuda.current_stream().cuda_stream
+        run = lambda: L.dfq_eltwise_np(ah.data_ptr(), al.data_ptr(), 9, bh.data_ptr(), bl.data_ptr(), 8, None, yh.data_ptr(), yl.data_ptr(), 8, 4,
+                                       ah.numel(), 1, st)
+        for _ in range(3):
+            assert run() == B.OK
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        by = 6 * ah.numel()
+        joins.append(dict(shape="%dx%dx%d" % (H, H, C), us=round(ms * 1e3, 1), gbs=round(by / ms / 1e6, 1),
+                          pct_hbm_peak=round(100 * by / ms / 1e6 / HBM_PEAK_GBS, 1)))
+        del ah, al, bh, bl, yh, yl
     what = "the four 3x3 shapes of the ResNet-50-shaped network" if args.layer_set == "3x3" else "configs[1]"
-    print(json.dumps({"metric": "(8,4) dynamic floating-point conv TOPS per dense layer of %s, standalone, b=%d" % (what, args.batch),
+    print(json.dumps({"joins": joins, "metric": "(8,4) dynamic floating-point conv TOPS per dense layer of %s, standalone, b=%d" % (what, args.batch),
                       "unit": "TOPS", "n_gpus": 1, "dtype": "(8,4) codes as two int8 digit planes, three int32 accumulators -> exact 64-bit sum",
                       "data": "synthetic", "buffers": "4 rotating sets per layer",
                       "roofline_note": "pct_mfma_peak prices the four int8 matrix products per block against 5 POP/s", "layers": rows}))

@@ -317,6 +317,16 @@ dfq_status dfq_fmt_from_absmax_i32_channels(const uint32_t *m, int K, int32_t fr
  *   N == 0 is a no-op.
  * dfq_conv_np_variant: DFQ_CONV_MFMA (groups == 1, C % 64 == 0, K % 16 == 0, R*S*C <= 13000, all pointers 16-byte
  *   aligned; DFQ_EUNSUPPORTED otherwise) or DFQ_CONV_DIRECT (any geometry); DFQ_CONV_AUTO picks MFMA when it applies. */
+/* Element-wise add on (8, p >= 4) codes held as digit planes (Eq. 10 with power-of-two scales): the two integers are
+ * brought to the finer of the two scales by exact left shifts, summed without loss (Eq. 12: the shifts may be at most 18
+ * bits, DFQ_EFMT otherwise), ReLU acts on the sum if asked, and the sum times 2^-(max(frac_a, frac_b) - frac_y) is
+ * rounded once into the format (8, p_y): nearest representable integer, ties to the even significand field, saturated.
+ * ah, al, bh, bl: input planes, n bytes each; y: output codes or NULL; yh, yl: output planes, both or neither NULL; at
+ * least one output; no output may overlap an input or another output.  All DEVICE.  The final factor's exponent must lie
+ * in [-16, 31] and p_y in [4, 7] (DFQ_EFMT).  n == 0 is a no-op. */
+dfq_status dfq_eltwise_np(const int8_t *ah, const int8_t *al, int frac_a, const int8_t *bh, const int8_t *bl, int frac_b, uint8_t *y,
+                          int8_t *yh, int8_t *yl, int frac_y, int p_y, size_t n, int relu, dfq_stream stream);
+
 /* gamma = alpha * beta_max (Sec. 2.1) solved for a power-of-two alpha in the general family: the largest frac in
  * [-32, 32] with gamma * 2^frac <= beta_max(nbits, p); gamma = 0 gives 32.  Host, pure.  DFQ_EINVAL for a negative,
  * infinite or NaN gamma, DFQ_EFMT for a format dfq_quantize_np does not take. */

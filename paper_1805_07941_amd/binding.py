@@ -27,7 +27,7 @@ EXPORTS = [
     "dfq_conv_q_variant", "dfq_conv_q_select", "dfq_conv_q_add", "dfq_conv_q_pc", "dfq_conv_q_pc_add", "dfq_absmax_i32_channels", "dfq_hist_i32", "dfq_threshold_search", "dfq_absmax_f32_rows", "dfq_quantize_rows", "dfq_quantize_i32_rows", "dfq_fold_scale_f32", "dfq_eltwise_q", "dfq_concat_q", "dfq_concat_q_into", "dfq_pool_q",
     "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_hist_shift", "dfq_fmt_from_absmax_i32_channels",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
-    "dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32", "dfq_conv_q_add_lazy",
+    "dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32", "dfq_conv_q_add_lazy", "dfq_eltwise_np",
 ]
 
 
@@ -94,6 +94,8 @@ def lib():
     L.dfq_np_digits.argtypes = [vp, sz, i32, vp, vp, vp]
     L.dfq_conv_np.argtypes = [vp] * 8 + [i32] * 15 + [vp]
     L.dfq_conv_np_variant.argtypes = [i32] + [vp] * 8 + [i32] * 15 + [vp]
+    L.dfq_eltwise_np.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, sz, i32, vp]
+    L.dfq_eltwise_np.restype = i32
     L.dfq_np_frac_from_absmax_f32.argtypes = [C.c_float, i32, i32, C.POINTER(C.c_int32)]
     for name in ("dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32"):
         getattr(L, name).restype = i32
@@ -214,6 +216,21 @@ def conv_np(xh: torch.Tensor, xl: torch.Tensor, wh: torch.Tensor, wl: torch.Tens
     _check(lib().dfq_conv_np_variant(int(variant), _ptr(xh), _ptr(xl), _ptr(wh), _ptr(wl), _ptr(b), _ptr(y), _ptr(yh), _ptr(yl),
                                      N, H, W, Cc, K, R, S, int(stride), int(pad), int(groups), int(f_x), int(f_w), int(f_y), int(p_y),
                                      int(bool(relu)), _stream(stream)), "dfq_conv_np")
+    return y, yh, yl
+
+
+def eltwise_np(ah: torch.Tensor, al: torch.Tensor, f_a: int, bh: torch.Tensor, bl: torch.Tensor, f_b: int, f_y: int, p_y: int,
+               relu: bool = False, want_codes: bool = True, want_digits: bool = True, stream=None):
+    """Element-wise add of two (8, p >= 4) tensors held as digit planes (Eq. 10).  Returns (codes or None, yh, yl or None, None)."""
+    for t, name in ((ah, "ah"), (al, "al"), (bh, "bh"), (bl, "bl")):
+        _dev(t, torch.int8, name)
+    if not (ah.shape == al.shape == bh.shape == bl.shape):
+        raise ValueError("operand shapes do not match")
+    y = torch.empty(ah.shape, dtype=torch.uint8, device=ah.device) if want_codes else None
+    yh = torch.empty(ah.shape, dtype=torch.int8, device=ah.device) if want_digits else None
+    yl = torch.empty(ah.shape, dtype=torch.int8, device=ah.device) if want_digits else None
+    _check(lib().dfq_eltwise_np(_ptr(ah), _ptr(al), int(f_a), _ptr(bh), _ptr(bl), int(f_b), _ptr(y), _ptr(yh), _ptr(yl), int(f_y), int(p_y),
+                                ah.numel(), int(bool(relu)), _stream(stream)), "dfq_eltwise_np")
     return y, yh, yl
 
 

@@ -194,6 +194,92 @@ __global__ void __launch_bounds__(256) np_digits_kernel(const uint8_t *__restric
     }
 }
 
+// ---- element-wise add (Eq. 10) on digit planes ----------------------------------------------------------------------
+
+// v * 2^-shift for a 32-bit v, rounded to the nearest integer representable with p + 1 significant bits, ties to the even
+// significand, magnitude clamped to bmax (< 2^12); -16 <= shift <= 31.  Binade of the value from the leading bit, step 2^k,
+// r = shift + k bits go with round-half-even (none when r <= 0: the scaled value is exact).  Returns the magnitude.
+__device__ __forceinline__ unsigned np_round_i32(int v, int shift, int p, unsigned bmax, int &sgn)
+{
+    sgn = v >> 31;
+    const unsigned mag = (unsigned)((v ^ sgn) - sgn);
+    if (mag == 0) return 0u;
+    const int L = 31 - __clz((int)mag);
+    const int e = L - shift;                       // floor(log2 of the scaled value)
+    if (e > 11) return bmax;                       // at least 2^12: beyond every format of this path
+    const int k = max(e - p, 0);
+    const int r = shift + k;
+    unsigned q;
+    if (r > 0) {
+        const unsigned odd = (mag >> r) & 1u;      // r <= 31: e >= p + 1 gives r = L - p, else r = shift
+        q = (mag + ((1u << (r - 1)) - 1u) + odd) >> r;   // mag < 2^31 and the addend <= 2^30: no carry out of 32 bits
+    } else {
+        q = mag << (-r);                           // below 2^(p+1): fits
+    }
+    return min(q << k, bmax);
+}
+
+struct NpEltParams {
+    const int8_t *ah, *al, *bh, *bl;
+    uint8_t *y;
+    int8_t *yh, *yl;
+    size_t n16;                  // groups of 16 elements
+    size_t n;                    // elements
+    int sa, sb;                  // left shifts of the two operands to the finer scale
+    int shift;                   // finer scale's fractional length minus that of the result
+    int p_y;
+    int beta_max;
+    int relu;
+};
+
+__device__ __forceinline__ void np_elt_one(int a_h, int a_l, int b_h, int b_l, const NpEltParams &q, unsigned &code, int &h, int &l)
+{
+    int t = ((64 * a_h + a_l) << q.sa) + ((64 * b_h + b_l) << q.sb);
+    if (q.relu) t = max(t, 0);
+    int sgn;
+    const unsigned mag = np_round_i32(t, q.shift, q.p_y, (unsigned)q.beta_max, sgn);
+    const int hu = (int)(mag >> 6), lu = (int)(mag & 63u);
+    h = (hu ^ sgn) - sgn;
+    l = (lu ^ sgn) - sgn;
+    code = np_code_of((int)mag, q.p_y) | (mag ? ((unsigned)sgn & 0x80u) : 0u);
+}
+
+__global__ void __launch_bounds__(256) eltwise_np_kernel(NpEltParams q)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < q.n16; i += (size_t)gridDim.x * 256) {
+        const uint4 ah = ((const uint4 *)q.ah)[i], al = ((const uint4 *)q.al)[i], bh = ((const uint4 *)q.bh)[i], bl = ((const uint4 *)q.bl)[i];
+        const uint32_t wah[4] = {ah.x, ah.y, ah.z, ah.w}, wal[4] = {al.x, al.y, al.z, al.w};
+        const uint32_t wbh[4] = {bh.x, bh.y, bh.z, bh.w}, wbl[4] = {bl.x, bl.y, bl.z, bl.w};
+        uint32_t oc[4], oh[4], ol[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            uint32_t c4 = 0, h4 = 0, l4 = 0;
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                unsigned code;
+                int h, l;
+                np_elt_one(byte_of(wah[j], e), byte_of(wal[j], e), byte_of(wbh[j], e), byte_of(wbl[j], e), q, code, h, l);
+                c4 |= code << (8 * e);
+                h4 |= ((uint32_t)h & 0xffu) << (8 * e);
+                l4 |= ((uint32_t)l & 0xffu) << (8 * e);
+            }
+            oc[j] = c4; oh[j] = h4; ol[j] = l4;
+        }
+        if (q.y) ((uint4 *)q.y)[i] = make_uint4(oc[0], oc[1], oc[2], oc[3]);
+        if (q.yh) ((uint4 *)q.yh)[i] = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+        if (q.yl) ((uint4 *)q.yl)[i] = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+    }
+    // ragged tail, element by element
+    for (size_t i = q.n16 * 16 + (size_t)blockIdx.x * 256 + threadIdx.x; i < q.n; i += (size_t)gridDim.x * 256) {
+        unsigned code;
+        int h, l;
+        np_elt_one(q.ah[i], q.al[i], q.bh[i], q.bl[i], q, code, h, l);
+        if (q.y) q.y[i] = (uint8_t)code;
+        if (q.yh) q.yh[i] = (int8_t)h;
+        if (q.yl) q.yl[i] = (int8_t)l;
+    }
+}
+
 // ---- direct form --------------------------------------------------------------------------------------------------
 
 __global__ void __launch_bounds__(256) conv_np_direct_kernel(NpConvArgs a)
@@ -538,6 +624,19 @@ hipError_t launch_conv_np_direct(const NpConvArgs &a, hipStream_t st)
     size_t blocks = (total + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
     conv_np_direct_kernel<<<(int)blocks, 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_eltwise_np(const int8_t *ah, const int8_t *al, const int8_t *bh, const int8_t *bl, uint8_t *y, int8_t *yh, int8_t *yl,
+                             size_t n, int sa, int sb, int shift, int p_y, int beta_max, int relu, hipStream_t st)
+{
+    const uintptr_t al16 = (uintptr_t)ah | (uintptr_t)al | (uintptr_t)bh | (uintptr_t)bl | (uintptr_t)y | (uintptr_t)yh | (uintptr_t)yl;
+    NpEltParams q{ah, al, bh, bl, y, yh, yl, (al16 & 15) ? 0 : n / 16, n, sa, sb, shift, p_y, beta_max, relu};
+    size_t work = q.n16 > 0 ? q.n16 : n;
+    size_t blocks = (work + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    eltwise_np_kernel<<<(int)blocks, 256, 0, st>>>(q);
     return hipGetLastError();
 }
 

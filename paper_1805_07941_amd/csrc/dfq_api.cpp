@@ -208,6 +208,29 @@ dfq_status dfq_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8
     return from_hip(launch_np_digits(codes, n, p, hi, lo, (hipStream_t)stream));
 }
 
+dfq_status dfq_eltwise_np(const int8_t *ah, const int8_t *al, int frac_a, const int8_t *bh, const int8_t *bl, int frac_b, uint8_t *y,
+                          int8_t *yh, int8_t *yl, int frac_y, int p_y, size_t n, int relu, dfq_stream stream)
+{
+    if (p_y < 4 || p_y > 7) return DFQ_EFMT;
+    if (frac_a < -32 || frac_a > 32 || frac_b < -32 || frac_b > 32 || frac_y < -32 || frac_y > 32) return DFQ_EFMT;
+    const int F = frac_a > frac_b ? frac_a : frac_b;
+    // Eq. 12: two twelve-bit integers shifted by at most 18 bits sum to less than 2^31
+    if (F - frac_a > 18 || F - frac_b > 18) return DFQ_EFMT;
+    if (F - frac_y < -16 || F - frac_y > 31) return DFQ_EFMT;
+    if (n == 0) return DFQ_OK;
+    if (!ah || !al || !bh || !bl || (!y && !yh && !yl) || ((yh == nullptr) != (yl == nullptr))) return DFQ_EINVAL;
+    const void *ins[4] = {ah, al, bh, bl};
+    const void *outs[3] = {y, yh, yl};
+    for (int i = 0; i < 3; i++) {
+        for (int j = 0; j < 4; j++)
+            if (overlaps(outs[i], n, ins[j], n)) return DFQ_EINVAL;
+        for (int j = i + 1; j < 3; j++)
+            if (overlaps(outs[i], n, outs[j], n)) return DFQ_EINVAL;
+    }
+    return from_hip(launch_eltwise_np(ah, al, bh, bl, y, yh, yl, n, F - frac_a, F - frac_b, F - frac_y, p_y, (int)dfq_beta_max(8, p_y),
+                                      relu ? 1 : 0, (hipStream_t)stream));
+}
+
 static dfq_status check_conv_np(NpConvArgs &a, int frac_x, int frac_w, int frac_y)
 {
     if (!a.xh || !a.xl || !a.wh || !a.wl || (!a.y && !a.yh && !a.yl)) return DFQ_EINVAL;

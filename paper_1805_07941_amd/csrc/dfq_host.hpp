@@ -92,6 +92,8 @@ hipError_t launch_conv_grouped(const ConvArgs &a, hipStream_t st);
 bool conv_np_mfma_supports(const NpConvArgs &a);
 hipError_t launch_conv_np_mfma(const NpConvArgs &a, hipStream_t st);
 hipError_t launch_conv_np_direct(const NpConvArgs &a, hipStream_t st);
+hipError_t launch_eltwise_np(const int8_t *ah, const int8_t *al, const int8_t *bh, const int8_t *bl, uint8_t *y, int8_t *yh, int8_t *yl,
+                             size_t n, int sa, int sb, int shift, int p_y, int beta_max, int relu, hipStream_t st);
 hipError_t launch_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, hipStream_t st);
 bool conv_smallc_supports(const ConvArgs &a);
 hipError_t launch_conv_smallc(const ConvArgs &a, hipStream_t st);

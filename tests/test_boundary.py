@@ -162,6 +162,22 @@ def test_conv_np_rejects_bad_arguments_before_launching(B):
     assert L.dfq_np_digits(1 << 20, 0, 4, 2 << 20, 3 << 20, None) == B.OK
 
 
+def test_eltwise_np_rejects_bad_arguments_before_launching(B):
+    L = B.lib()
+
+    def call(ah=1 << 20, al=2 << 20, fa=5, bh=3 << 20, bl=4 << 20, fb=5, y=5 << 20, yh=6 << 20, yl=7 << 20, fy=4, p_y=4, n=1000, relu=0):
+        return L.dfq_eltwise_np(ah, al, fa, bh, bl, fb, y, yh, yl, fy, p_y, n, relu, None)
+
+    assert call(ah=None) == B.EINVAL and call(bl=None) == B.EINVAL
+    assert call(y=None, yh=None, yl=None) == B.EINVAL and call(yh=None) == B.EINVAL
+    assert call(y=1 << 20) == B.EINVAL and call(yh=5 << 20) == B.EINVAL          # output over input, output over output
+    assert call(p_y=3) == B.EFMT and call(p_y=8) == B.EFMT
+    assert call(fa=33) == B.EFMT
+    assert call(fa=20, fb=1) == B.EFMT                                           # a 19-bit alignment: Eq. 12 would need more than 32 bits
+    assert call(fa=0, fb=0, fy=17) == B.EFMT and call(fa=32, fb=32, fy=0) == B.EFMT
+    assert call(n=0) == B.OK and call(n=0, ah=None) == B.OK
+
+
 def test_np_frac_from_absmax_matches_the_oracle(B):
     import oracle.npfmt as F
     rng = np.random.default_rng(9)

@@ -289,3 +289,82 @@ def test_conv_np_full_size_sampled(B, shape):
     beta = torch.from_numpy(NC.decode_tensor(np.arange(256, dtype=np.uint8), 8, 4)).to(DEV)[y.long()]
     assert torch.equal(64 * yh.long() + yl.long(), beta)
     assert bool(((yh.long() * yl.long()) >= 0).all())
+
+
+ELT_CASES = [
+    # p_a, f_a, p_b, f_b, p_y, f_y, relu, n
+    (4, 9, 4, 9, 4, 8, False, 100003),
+    (4, 9, 4, 6, 4, 5, True, 65536),
+    (4, 3, 5, 12, 4, 2, False, 4099),
+    (5, 7, 4, 7, 6, 9, False, 777),            # finer result: exact, saturating where it does not fit
+    (4, 5, 4, 5, 4, 12, True, 5000),           # upscale by 2^7
+    (4, 18, 4, 0, 4, 0, False, 33000),         # the widest alignment allowed
+    (4, 0, 4, 18, 5, 31 - 13, False, 33000),
+    (4, 10, 4, 10, 4, -21, False, 3000),       # final factor 2^-31: everything rounds to zero
+    (4, 4, 4, 4, 4, 20, False, 3000),          # final factor 2^16: saturates unless zero
+    (7, 4, 6, 5, 7, 3, True, 20001),           # the int8 members
+    (4, 6, 4, 6, 7, 0, False, 20001),
+    (4, 8, 4, 8, 4, 7, False, 15),             # shorter than one vector
+    (4, 8, 4, 8, 4, 7, False, 1),
+]
+
+
+@pytest.mark.parametrize("case", ELT_CASES)
+def test_eltwise_np_against_oracle(B, case):
+    p_a, f_a, p_b, f_b, p_y, f_y, relu, n = case
+    rng = np.random.default_rng(zlib.crc32(repr(case).encode()))
+    a = rng.integers(0, 256, n).astype(np.uint8)
+    b = rng.integers(0, 256, n).astype(np.uint8)
+    a[: min(n, 8)] = [0x7f, 0xff, 0x00, 0x80, 0x7f, 0xff, 0x01, 0x81][: min(n, 8)]
+    b[: min(n, 8)] = [0x7f, 0xff, 0x7f, 0x00, 0xff, 0x7f, 0x81, 0x01][: min(n, 8)]
+    ah, al = B.np_digits(dev(a), p_a)
+    bh, bl = B.np_digits(dev(b), p_b)
+    y, yh, yl = B.eltwise_np(ah, al, f_a, bh, bl, f_b, f_y, p_y, relu)
+    torch.cuda.synchronize()
+    ry, rbeta, _ = NC.eltwise_np(a, (8, p_a), f_a, b, (8, p_b), f_b, (8, p_y), f_y, relu)
+    eh, el = digits_of(rbeta)
+    bad = np.flatnonzero(host(y) != ry)
+    assert bad.size == 0, (len(bad), bad[:5], host(y)[bad[:5]], ry[bad[:5]])
+    assert np.array_equal(host(yh), eh) and np.array_equal(host(yl), el)
+    # one kind of output only, and operands that do not start on a 16-byte boundary
+    if n > 40:
+        y2, _, _ = B.eltwise_np(ah[3:], al[3:], f_a, bh[3:], bl[3:], f_b, f_y, p_y, relu, want_digits=False)
+        _, yh3, yl3 = B.eltwise_np(ah, al, f_a, bh, bl, f_b, f_y, p_y, relu, want_codes=False)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(y2), ry[3:]) and np.array_equal(host(yh3), eh) and np.array_equal(host(yl3), el)
+
+
+def test_eltwise_np_every_pair_of_codes(B):
+    """All 256 x 256 pairs of (8, 4) codes, on a few scale settings: every binade boundary and every tie there is."""
+    a = np.repeat(np.arange(256, dtype=np.uint8), 256)
+    b = np.tile(np.arange(256, dtype=np.uint8), 256)
+    ah, al = B.np_digits(dev(a), 4)
+    bh, bl = B.np_digits(dev(b), 4)
+    for f_a, f_b, f_y, p_y, relu in [(5, 5, 4, 4, False), (5, 5, 5, 4, False), (6, 4, 3, 4, True), (4, 7, 2, 5, False), (3, 3, 1, 7, False)]:
+        y, yh, yl = B.eltwise_np(ah, al, f_a, bh, bl, f_b, f_y, p_y, relu)
+        torch.cuda.synchronize()
+        ry, rbeta, _ = NC.eltwise_np(a, (8, 4), f_a, b, (8, 4), f_b, (8, p_y), f_y, relu)
+        assert np.array_equal(host(y), ry)
+        assert np.array_equal(64 * host(yh).astype(np.int64) + host(yl), rbeta)
+
+
+def test_residual_join_through_digit_planes(B):
+    """conv -> add with an identity branch -> conv, every tensor staying in digit planes between the kernels."""
+    rng = np.random.default_rng(5)
+    N, H, W, C = 2, 14, 14, 64
+    x = gaussian_codes(rng, (N, H, W, C), 4, relu=True)
+    w1 = gaussian_codes(rng, (C, 3, 3, C), 4)
+    w2 = gaussian_codes(rng, (C, 1, 1, C), 4)
+    f_x, f_w, f_1, f_j, f_2 = 8, 12, 5, 5, 3
+    xh, xl = B.np_digits(dev(x), 4)
+    w1h, w1l = B.np_digits(dev(w1), 4)
+    w2h, w2l = B.np_digits(dev(w2), 4)
+    _, h1, l1 = B.conv_np(xh, xl, w1h, w1l, None, f_x, f_w, f_1, 4, 1, 1, 1, False, want_codes=False)
+    _, hj, lj = B.eltwise_np(h1, l1, f_1, xh, xl, f_x, f_j, 4, True, want_codes=False)
+    y, _, _ = B.conv_np(hj, lj, w2h, w2l, None, f_j, f_w, f_2, 4, 1, 0, 1, True, want_digits=False)
+    torch.cuda.synchronize()
+    r1, _, _ = NC.conv_np(x, (8, 4), w1, (8, 4), None, f_x + f_w - f_1, (8, 4), 1, 1, 1, False)
+    rj, _, _ = NC.eltwise_np(r1, (8, 4), f_1, x, (8, 4), f_x, (8, 4), f_j, True)
+    ry, _, _ = NC.conv_np(rj, (8, 4), w2, (8, 4), None, f_j + f_w - f_2, (8, 4), 1, 0, 1, True)
+    assert np.array_equal(host(y), ry)
+    assert len(np.unique(ry)) > 20
