@@ -327,6 +327,40 @@ dfq_status dfq_fmt_from_absmax_i32_channels(const uint32_t *m, int K, int32_t fr
 dfq_status dfq_eltwise_np(const int8_t *ah, const int8_t *al, int frac_a, const int8_t *bh, const int8_t *bl, int frac_b, uint8_t *y,
                           int8_t *yh, int8_t *yl, int frac_y, int p_y, size_t n, int relu, dfq_stream stream);
 
+/* Calibration of a layer on (8, p >= 4) codes (Sec. 3: the output threshold is taken on the exact accumulator, after the
+ * ReLU where the layer has one, before anything is rounded): the largest |sum + bias| of Eq. 6 over all outputs of the
+ * layer (negative sums count as 0 when relu is set), as a 64-bit integer at the scale 2^-(frac_x + frac_w), written to
+ * *amax_dev (DEVICE, 8-byte aligned; cleared by the call on the stream, then raised by atomic maxima).  Operands as for
+ * dfq_conv_np; nothing else is written.  One output per lane (a calibration batch is small). */
+dfq_status dfq_conv_np_absmax(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int32_t *b, uint64_t *amax_dev,
+                              int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups, int relu, dfq_stream stream);
+
+/* The same for the add of Eq. 10: the largest magnitude of the exact sum at the finer input scale 2^-max(frac_a, frac_b). */
+dfq_status dfq_eltwise_np_absmax(const int8_t *ah, const int8_t *al, int frac_a, const int8_t *bh, const int8_t *bl, int frac_b,
+                                 uint64_t *amax_dev, size_t n, int relu, dfq_stream stream);
+
+/* HOST.  The scale of a tensor whose largest magnitude is max_abs * 2^-acc_frac: the largest frac <= min(acc_frac, 32) with
+ * max_abs * 2^(frac - acc_frac) <= beta_max(nbits, p), floored at -32 (gamma = alpha * beta_max, Sec. 2.1, towards the
+ * coarser power of two so that nothing clips; the rescale factor stays in (0, 1] as for dfq_fmt_from_absmax_i32). */
+dfq_status dfq_np_frac_from_absmax_u64(uint64_t max_abs, int acc_frac, int nbits, int p, int *frac);
+
+/* Pooling on (8, p_fmt >= 4) digit planes, NHWC, k x k windows, floor-mode output size; the result keeps the input's
+ * scale.  MAX: the largest value among the window's taps inside the image (0 <= pad < k).  AVG: the exact mean of the
+ * k * k integers rounded once to the format (nearest, ties to the even significand); pad must be 0
+ * (DFQ_EUNSUPPORTED otherwise).  Outputs as for dfq_eltwise_np.  k <= 16.  All DEVICE. */
+dfq_status dfq_pool_np(const int8_t *xh, const int8_t *xl, uint8_t *y, int8_t *yh, int8_t *yl, dfq_pool_mode mode, int N, int H, int W, int C,
+                       int k, int stride, int pad, int p_fmt, dfq_stream stream);
+
+/* Layout helpers for a first layer with few channels (data movement only; each acts on one byte tensor, so a tensor held
+ * as two digit planes takes two calls, and int8 codes work the same way).  A stride-2 convolution with an R x S kernel
+ * (R, S <= 8) over C <= 4 channels, padding pad, equals a 4 x 1 convolution with unit stride and no padding over 64
+ * channels of the packed tensor  y[N][P + 3][Q][64],  y[n][i][q][16 s + (2 dy + dx) C + c] = x_padded[n][2 i + dy][2 (q + s) + dx][c]
+ * (s = 0..3, zeros elsewhere), P x Q the layer's output size, with the weights packed alike:
+ * y[K][4][1][64],  y[k][r][0][16 s + (2 dy + dx) C + c] = w[k][2 r + dy][2 s + dx][c] where that tap exists, else 0.
+ * The sums are the same integers term by term (zero taps add nothing).  y 4-byte aligned; no overlap.  All DEVICE. */
+dfq_status dfq_stem_pack_x(const int8_t *x, int8_t *y, int N, int H, int W, int C, int R, int S, int pad, dfq_stream stream);
+dfq_status dfq_stem_pack_w(const int8_t *w, int8_t *y, int K, int R, int S, int C, dfq_stream stream);
+
 /* gamma = alpha * beta_max (Sec. 2.1) solved for a power-of-two alpha in the general family: the largest frac in
  * [-32, 32] with gamma * 2^frac <= beta_max(nbits, p); gamma = 0 gives 32.  Host, pure.  DFQ_EINVAL for a negative,
  * infinite or NaN gamma, DFQ_EFMT for a format dfq_quantize_np does not take. */

@@ -110,9 +110,17 @@ def quantize(x, n: int, p: int, frac: int):
     divide by alpha = 2^-frac (exact in double), round as round_to_beta, encode by Eq. 2."""
     x = np.asarray(x, np.float32)
     beta = round_to_beta(np.ldexp(x.astype(np.float64), int(frac)), n, p)
-    enc = np.frompyfunc(lambda b: encode(int(b), n, p), 1, 1)
-    codes = enc(beta).astype(np.uint16) if beta.size else np.zeros(beta.shape, np.uint16)
-    return codes, beta
+    if beta_max(n, p) >= (1 << 20):
+        enc = np.frompyfunc(lambda b: encode(int(b), n, p), 1, 1)
+        codes = enc(beta).astype(np.uint16) if beta.size else np.zeros(beta.shape, np.uint16)
+        return codes, beta
+    # formats with few integers: Eq. 2 inverted by enumerating the non-negative codes (what encode() computes, one element at a time)
+    table = np.full(beta_max(n, p) + 1, -1, np.int64)
+    for c in range(1 << (n - 1)):
+        table[decode(c, n, p)] = c
+    codes = table[np.abs(beta)] | np.where(beta < 0, 1 << (n - 1), 0)
+    assert (table[np.abs(beta)] >= 0).all()
+    return codes.astype(np.uint16), beta
 
 
 def dequantize(codes, n: int, p: int, frac: int) -> np.ndarray:

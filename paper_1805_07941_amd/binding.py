@@ -28,6 +28,7 @@ EXPORTS = [
     "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_hist_shift", "dfq_fmt_from_absmax_i32_channels",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
     "dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32", "dfq_conv_q_add_lazy", "dfq_eltwise_np",
+    "dfq_conv_np_absmax", "dfq_eltwise_np_absmax", "dfq_np_frac_from_absmax_u64", "dfq_pool_np", "dfq_stem_pack_x", "dfq_stem_pack_w",
 ]
 
 
@@ -96,6 +97,18 @@ def lib():
     L.dfq_conv_np_variant.argtypes = [i32] + [vp] * 8 + [i32] * 15 + [vp]
     L.dfq_eltwise_np.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, sz, i32, vp]
     L.dfq_eltwise_np.restype = i32
+    L.dfq_conv_np_absmax.argtypes = [vp] * 6 + [i32] * 11 + [vp]
+    L.dfq_conv_np_absmax.restype = i32
+    L.dfq_eltwise_np_absmax.argtypes = [vp, vp, i32, vp, vp, i32, vp, sz, i32, vp]
+    L.dfq_eltwise_np_absmax.restype = i32
+    L.dfq_np_frac_from_absmax_u64.argtypes = [C.c_uint64, i32, i32, i32, C.POINTER(i32)]
+    L.dfq_np_frac_from_absmax_u64.restype = i32
+    L.dfq_pool_np.argtypes = [vp] * 5 + [i32] * 9 + [vp]
+    L.dfq_pool_np.restype = i32
+    L.dfq_stem_pack_x.argtypes = [vp, vp] + [i32] * 7 + [vp]
+    L.dfq_stem_pack_x.restype = i32
+    L.dfq_stem_pack_w.argtypes = [vp, vp] + [i32] * 4 + [vp]
+    L.dfq_stem_pack_w.restype = i32
     L.dfq_np_frac_from_absmax_f32.argtypes = [C.c_float, i32, i32, C.POINTER(C.c_int32)]
     for name in ("dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32"):
         getattr(L, name).restype = i32
@@ -232,6 +245,84 @@ def eltwise_np(ah: torch.Tensor, al: torch.Tensor, f_a: int, bh: torch.Tensor, b
     _check(lib().dfq_eltwise_np(_ptr(ah), _ptr(al), int(f_a), _ptr(bh), _ptr(bl), int(f_b), _ptr(y), _ptr(yh), _ptr(yl), int(f_y), int(p_y),
                                 ah.numel(), int(bool(relu)), _stream(stream)), "dfq_eltwise_np")
     return y, yh, yl
+
+
+def _read_u64(t: torch.Tensor) -> int:
+    return int(t.cpu()[0])
+
+
+def conv_np_absmax(xh, xl, wh, wl, b, stride: int = 1, pad: int = 0, groups: int = 1, relu: bool = False, stream=None) -> int:
+    """Largest |sum + bias| of the layer (after ReLU if asked) as a Python integer at the accumulator's scale; synchronizes."""
+    for t, name in ((xh, "xh"), (xl, "xl"), (wh, "wh"), (wl, "wl")):
+        _dev(t, torch.int8, name)
+    if b is not None:
+        _dev(b, torch.int32, "b")
+    N, H, W, Cc = xh.shape
+    K, R, S, Cg = wh.shape
+    if Cg * groups != Cc or xl.shape != xh.shape or wl.shape != wh.shape:
+        raise ValueError("operand shapes do not match")
+    out = torch.empty(1, dtype=torch.int64, device=xh.device)
+    _check(lib().dfq_conv_np_absmax(_ptr(xh), _ptr(xl), _ptr(wh), _ptr(wl), _ptr(b), _ptr(out), N, H, W, Cc, K, R, S, int(stride), int(pad),
+                                    int(groups), int(bool(relu)), _stream(stream)), "dfq_conv_np_absmax")
+    return _read_u64(out)
+
+
+def eltwise_np_absmax(ah, al, f_a: int, bh, bl, f_b: int, relu: bool = False, stream=None) -> int:
+    for t, name in ((ah, "ah"), (al, "al"), (bh, "bh"), (bl, "bl")):
+        _dev(t, torch.int8, name)
+    if not (ah.shape == al.shape == bh.shape == bl.shape):
+        raise ValueError("operand shapes do not match")
+    out = torch.empty(1, dtype=torch.int64, device=ah.device)
+    _check(lib().dfq_eltwise_np_absmax(_ptr(ah), _ptr(al), int(f_a), _ptr(bh), _ptr(bl), int(f_b), _ptr(out), ah.numel(), int(bool(relu)),
+                                       _stream(stream)), "dfq_eltwise_np_absmax")
+    return _read_u64(out)
+
+
+def np_frac_from_absmax_u64(m: int, acc_frac: int, nbits: int, p: int) -> int:
+    f = C.c_int32()
+    _check(lib().dfq_np_frac_from_absmax_u64(int(m), int(acc_frac), int(nbits), int(p), C.byref(f)), "dfq_np_frac_from_absmax_u64")
+    return int(f.value)
+
+
+def pool_np(xh: torch.Tensor, xl: torch.Tensor, mode: str, k: int, stride: int, pad: int, p: int, want_codes: bool = True,
+            want_digits: bool = True, out=None, stream=None):
+    """Pooling on (8, p) digit planes [N,H,W,C]; mode "max" or "avg".  Returns (codes or None, yh, yl or None, None)."""
+    _dev(xh, torch.int8, "xh")
+    _dev(xl, torch.int8, "xl")
+    if xh.shape != xl.shape:
+        raise ValueError("operand shapes do not match")
+    N, H, W, Cc = xh.shape
+    P, Q = conv_out_hw(H, W, k, k, stride, pad)
+    if out is not None:
+        y, yh, yl = out
+    else:
+        y = torch.empty((N, P, Q, Cc), dtype=torch.uint8, device=xh.device) if want_codes else None
+        yh = torch.empty((N, P, Q, Cc), dtype=torch.int8, device=xh.device) if want_digits else None
+        yl = torch.empty((N, P, Q, Cc), dtype=torch.int8, device=xh.device) if want_digits else None
+    _check(lib().dfq_pool_np(_ptr(xh), _ptr(xl), _ptr(y), _ptr(yh), _ptr(yl), {"max": POOL_MAX, "avg": POOL_AVG}[mode], N, H, W, Cc, int(k),
+                             int(stride), int(pad), int(p), _stream(stream)), "dfq_pool_np")
+    return y, yh, yl
+
+
+def stem_pack_x(x: torch.Tensor, R: int, S: int, pad: int, out=None, stream=None) -> torch.Tensor:
+    """One byte tensor [N,H,W,C <= 4] of a stride-2 first layer -> [N, P + 3, Q, 64] (see dfq_stem_pack_x)."""
+    if not x.is_cuda or x.element_size() != 1 or not x.is_contiguous():
+        raise ValueError("x must be a contiguous one-byte device tensor")
+    N, H, W, Cc = x.shape
+    P, Q = conv_out_hw(H, W, R, S, 2, pad)
+    y = out if out is not None else torch.empty((N, P + 3, Q, 64), dtype=x.dtype, device=x.device)
+    _check(lib().dfq_stem_pack_x(_ptr(x), _ptr(y), N, H, W, Cc, int(R), int(S), int(pad), _stream(stream)), "dfq_stem_pack_x")
+    return y
+
+
+def stem_pack_w(w: torch.Tensor, stream=None) -> torch.Tensor:
+    """One byte tensor of weights [K,R,S,C <= 4] -> [K, 4, 1, 64] (see dfq_stem_pack_w)."""
+    if not w.is_cuda or w.element_size() != 1 or not w.is_contiguous():
+        raise ValueError("w must be a contiguous one-byte device tensor")
+    K, R, S, Cc = w.shape
+    y = torch.empty((K, 4, 1, 64), dtype=w.dtype, device=w.device)
+    _check(lib().dfq_stem_pack_w(_ptr(w), _ptr(y), K, R, S, Cc, _stream(stream)), "dfq_stem_pack_w")
+    return y
 
 
 # ---- layers ---------------------------------------------------------------------- #

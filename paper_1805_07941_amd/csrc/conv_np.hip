@@ -194,6 +194,19 @@ __global__ void __launch_bounds__(256) np_digits_kernel(const uint8_t *__restric
     }
 }
 
+// Maximum of m over the wavefront's lanes, then one atomic max per wavefront into *dst (the word starts at zero).
+__device__ __forceinline__ void wave_max_to(unsigned long long *dst, unsigned long long m)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const unsigned long long other = __shfl_xor(m, o, 64);
+        m = other > m ? other : m;
+    }
+    if ((threadIdx.x & 63) == 0 && m) atomicMax(dst, m);
+}
+
+__global__ void clear_u64_kernel(unsigned long long *p) { *p = 0ull; }
+
 // ---- element-wise add (Eq. 10) on digit planes ----------------------------------------------------------------------
 
 // v * 2^-shift for a 32-bit v, rounded to the nearest integer representable with p + 1 significant bits, ties to the even
@@ -280,6 +293,170 @@ __global__ void __launch_bounds__(256) eltwise_np_kernel(NpEltParams q)
     }
 }
 
+// Calibration: the largest magnitude of the exact aligned sum (after ReLU if asked), nothing stored.
+__global__ void __launch_bounds__(256) eltwise_np_absmax_kernel(const int8_t *ah, const int8_t *al, const int8_t *bh, const int8_t *bl, size_t n,
+                                                                 int sa, int sb, int relu, unsigned long long *amax)
+{
+    unsigned mx = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const int t = ((64 * (int)ah[i] + (int)al[i]) << sa) + ((64 * (int)bh[i] + (int)bl[i]) << sb);
+        const unsigned m = t < 0 ? (relu ? 0u : (unsigned)(-t)) : (unsigned)t;
+        mx = max(mx, m);
+    }
+    wave_max_to(amax, (unsigned long long)mx);
+}
+
+// ---- pooling on digit planes ----------------------------------------------------------------------------------------
+
+// The exact mean tot / D (D > 0) to the nearest integer with p + 1 significant bits, ties to the even significand,
+// magnitude clamped to bmax; |tot| < 2^19.  Binade e of the mean from D * 2^e <= |tot| < D * 2^(e+1), step 2^k with
+// k = max(e - p, 0), quotient and remainder of |tot| by D * 2^k decide the rounding exactly.
+__device__ __forceinline__ int np_round_mean(int tot, int D, int p, int bmax)
+{
+    const int sgn = tot >> 31;
+    const unsigned mag = (unsigned)((tot ^ sgn) - sgn);
+    int e = 0;
+    while (e < 12 && ((unsigned)D << (e + 1)) <= mag) e++;
+    const int k = max(e - p, 0);
+    const unsigned den = (unsigned)D << k;
+    unsigned q = mag / den;
+    const unsigned rem2 = 2u * (mag - q * den);
+    if (rem2 > den || (rem2 == den && (q & 1u))) q++;
+    const int r = min((int)(q << k), bmax);
+    return (r ^ sgn) - sgn;
+}
+
+struct NpPoolParams {
+    const int8_t *xh, *xl;
+    uint8_t *y;
+    int8_t *yh, *yl;
+    int N, H, W, C, k, stride, pad, P, Q, p_fmt, beta_max, avg;
+};
+
+// One lane per output element, channels fastest (neighbouring lanes read neighbouring bytes).
+__global__ void __launch_bounds__(256) pool_np_kernel(NpPoolParams a)
+{
+    const size_t total = (size_t)a.N * a.P * a.Q * a.C;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int c = (int)(i % a.C);
+        const size_t pix = i / a.C;
+        const int q = (int)(pix % a.Q);
+        const size_t t = pix / a.Q;
+        const int p = (int)(t % a.P);
+        const int n = (int)(t / a.P);
+        int best = -4096, tot = 0;
+        for (int r = 0; r < a.k; r++) {
+            const int ih = p * a.stride - a.pad + r;
+            if (ih < 0 || ih >= a.H) continue;
+            for (int s = 0; s < a.k; s++) {
+                const int iw = q * a.stride - a.pad + s;
+                if (iw < 0 || iw >= a.W) continue;
+                const size_t o = (((size_t)n * a.H + ih) * a.W + iw) * a.C + c;
+                const int beta = 64 * (int)a.xh[o] + (int)a.xl[o];
+                best = max(best, beta);
+                tot += beta;
+            }
+        }
+        const int beta = a.avg ? np_round_mean(tot, a.k * a.k, a.p_fmt, a.beta_max) : best;
+        if (a.y) a.y[i] = (uint8_t)np_code_of(beta, a.p_fmt);
+        int h, l;
+        np_split(beta, h, l);
+        if (a.yh) a.yh[i] = (int8_t)h;
+        if (a.yl) a.yl[i] = (int8_t)l;
+    }
+}
+
+// 3 x 3 / stride 2 / pad 1 max pooling with C a multiple of 4: one lane per four channels of an output pixel.
+__global__ void __launch_bounds__(256) maxpool3_np_kernel(NpPoolParams a)
+{
+    const int C4 = a.C / 4;
+    const size_t total = (size_t)a.N * a.P * a.Q * C4;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int c4 = (int)(i % C4);
+        const size_t pix = i / C4;
+        const int q = (int)(pix % a.Q);
+        const size_t t = pix / a.Q;
+        const int p = (int)(t % a.P);
+        const int n = (int)(t / a.P);
+        int best[4] = {-4096, -4096, -4096, -4096};
+#pragma unroll
+        for (int r = 0; r < 3; r++) {
+            const int ih = 2 * p - 1 + r;
+            if (ih < 0 || ih >= a.H) continue;
+#pragma unroll
+            for (int s = 0; s < 3; s++) {
+                const int iw = 2 * q - 1 + s;
+                if (iw < 0 || iw >= a.W) continue;
+                const size_t o = ((((size_t)n * a.H + ih) * a.W + iw) * a.C) / 4 + c4;
+                const uint32_t h4 = ((const uint32_t *)a.xh)[o], l4 = ((const uint32_t *)a.xl)[o];
+#pragma unroll
+                for (int e = 0; e < 4; e++) best[e] = max(best[e], 64 * byte_of(h4, e) + byte_of(l4, e));
+            }
+        }
+        uint32_t oc = 0, oh = 0, ol = 0;
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            int h, l;
+            np_split(best[e], h, l);
+            oc |= (uint32_t)np_code_of(best[e], a.p_fmt) << (8 * e);
+            oh |= ((uint32_t)h & 0xffu) << (8 * e);
+            ol |= ((uint32_t)l & 0xffu) << (8 * e);
+        }
+        if (a.y) ((uint32_t *)a.y)[i] = oc;
+        if (a.yh) ((uint32_t *)a.yh)[i] = oh;
+        if (a.yl) ((uint32_t *)a.yl)[i] = ol;
+    }
+}
+
+// ---- space-to-depth packing of a stride-2 first layer with few channels -------------------------------------------------
+// A stride-2 convolution with an R x S kernel (R, S <= 8) over C <= 4 channels is a stride-1 convolution with a
+// ceil(R/2) x ceil(S/2) kernel over the 2 x 2 space-to-depth image with 4 C channels.  With 16 bytes per such pixel
+// (4 C <= 16, the rest zero) four neighbouring pixels are 64 contiguous bytes, i.e. one 64-byte reduction step of the
+// matrix-core kernels holds a whole kernel row.  y[n][i][q][16 s' + (2 dy + dx) C + c] = x_padded[n][2 i + dy][2 (q + s') + dx][c],
+// s' = 0..3, so that the layer becomes a 4 x 1 convolution over 64 channels with unit stride and no padding.
+__global__ void __launch_bounds__(256) stem_pack_x_kernel(const int8_t *x, int8_t *y, int N, int H, int W, int C, int pad, int Hs, int Qs)
+{
+    const size_t total = (size_t)N * Hs * Qs * 16;                  // one lane per 4 bytes: (pixel, s', parity pair)
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int j = (int)(i & 15);                                // dword within the 64-byte row
+        const size_t pix = i >> 4;
+        const int q = (int)(pix % Qs);
+        const size_t t = pix / Qs;
+        const int ii = (int)(t % Hs);
+        const int n = (int)(t / Hs);
+        uint32_t out = 0;
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const int byte = 4 * j + e;                             // 16 s' + (2 dy + dx) C + c
+            const int sp = byte >> 4, rest = byte & 15;
+            if (rest < 4 * C) {
+                const int par = rest / C, c = rest - par * C;
+                const int ih = 2 * ii + (par >> 1) - pad, iw = 2 * (q + sp) + (par & 1) - pad;
+                if (ih >= 0 && ih < H && iw >= 0 && iw < W)
+                    out |= ((uint32_t)(uint8_t)x[(((size_t)n * H + ih) * W + iw) * C + c]) << (8 * e);
+            }
+        }
+        ((uint32_t *)y)[i] = out;
+    }
+}
+
+// y[k][r'][16 s' + (2 dy + dx) C + c] = w[k][2 r' + dy][2 s' + dx][c] where that tap exists, else 0; r' = 0..3.
+__global__ void __launch_bounds__(256) stem_pack_w_kernel(const int8_t *w, int8_t *y, int K, int R, int S, int C)
+{
+    const int total = K * 4 * 64;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+        const int byte = i & 63, rp = (i >> 6) & 3, k = i >> 8;
+        const int sp = byte >> 4, rest = byte & 15;
+        int8_t v = 0;
+        if (rest < 4 * C) {
+            const int par = rest / C, c = rest - par * C;
+            const int r = 2 * rp + (par >> 1), s = 2 * sp + (par & 1);
+            if (r < R && s < S) v = w[((k * R + r) * S + s) * C + c];
+        }
+        y[i] = v;
+    }
+}
+
 // ---- direct form --------------------------------------------------------------------------------------------------
 
 __global__ void __launch_bounds__(256) conv_np_direct_kernel(NpConvArgs a)
@@ -288,6 +465,7 @@ __global__ void __launch_bounds__(256) conv_np_direct_kernel(NpConvArgs a)
     const int Kg = a.K / a.groups;
     const size_t total = (size_t)a.N * a.P * a.Q * a.K;
     NpRound rnd = {a.shift, a.p_y, (float)a.beta_max, a.relu};
+    unsigned long long mx = 0;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
         const int k = (int)(i % a.K);
         const size_t pix = i / a.K;
@@ -309,6 +487,10 @@ __global__ void __launch_bounds__(256) conv_np_direct_kernel(NpConvArgs a)
                     acc += (long long)((64 * (int)a.xh[xo + c] + (int)a.xl[xo + c]) * (64 * (int)a.wh[wo + c] + (int)a.wl[wo + c]));
             }
         }
+        if (a.amax) {
+            const unsigned long long m = acc < 0 ? (a.relu ? 0ull : (unsigned long long)(-acc)) : (unsigned long long)acc;
+            mx = m > mx ? m : mx;
+        }
         const int beta = np_round_acc(acc, rnd);
         if (a.y) a.y[i] = (uint8_t)np_code_of(beta, a.p_y);
         int h, l;
@@ -316,6 +498,7 @@ __global__ void __launch_bounds__(256) conv_np_direct_kernel(NpConvArgs a)
         if (a.yh) a.yh[i] = (int8_t)h;
         if (a.yl) a.yl[i] = (int8_t)l;
     }
+    if (a.amax) wave_max_to(a.amax, mx);
 }
 
 // ---- matrix-core form ---------------------------------------------------------------------------------------------
@@ -624,6 +807,51 @@ hipError_t launch_conv_np_direct(const NpConvArgs &a, hipStream_t st)
     size_t blocks = (total + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
     conv_np_direct_kernel<<<(int)blocks, 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_clear_u64(unsigned long long *p, hipStream_t st)
+{
+    clear_u64_kernel<<<1, 1, 0, st>>>(p);
+    return hipGetLastError();
+}
+
+static int grid_for(size_t work)
+{
+    size_t blocks = (work + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    return blocks < 1 ? 1 : (int)blocks;
+}
+
+hipError_t launch_eltwise_np_absmax(const int8_t *ah, const int8_t *al, const int8_t *bh, const int8_t *bl, size_t n, int sa, int sb, int relu,
+                                    unsigned long long *amax, hipStream_t st)
+{
+    eltwise_np_absmax_kernel<<<grid_for(n), 256, 0, st>>>(ah, al, bh, bl, n, sa, sb, relu, amax);
+    return hipGetLastError();
+}
+
+hipError_t launch_pool_np(const int8_t *xh, const int8_t *xl, uint8_t *y, int8_t *yh, int8_t *yl, int avg, int N, int H, int W, int C, int k,
+                          int stride, int pad, int P, int Q, int p_fmt, int beta_max, hipStream_t st)
+{
+    NpPoolParams a{xh, xl, y, yh, yl, N, H, W, C, k, stride, pad, P, Q, p_fmt, beta_max, avg};
+    const uintptr_t al4 = (uintptr_t)xh | (uintptr_t)xl | (uintptr_t)y | (uintptr_t)yh | (uintptr_t)yl;
+    const size_t total = (size_t)N * P * Q * C;
+    if (!avg && k == 3 && stride == 2 && pad == 1 && C % 4 == 0 && (al4 & 3) == 0)
+        maxpool3_np_kernel<<<grid_for(total / 4), 256, 0, st>>>(a);
+    else
+        pool_np_kernel<<<grid_for(total), 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_stem_pack_x(const int8_t *x, int8_t *y, int N, int H, int W, int C, int pad, int Hs, int Qs, hipStream_t st)
+{
+    stem_pack_x_kernel<<<grid_for((size_t)N * Hs * Qs * 16), 256, 0, st>>>(x, y, N, H, W, C, pad, Hs, Qs);
+    return hipGetLastError();
+}
+
+hipError_t launch_stem_pack_w(const int8_t *w, int8_t *y, int K, int R, int S, int C, hipStream_t st)
+{
+    stem_pack_w_kernel<<<grid_for((size_t)K * 256), 256, 0, st>>>(w, y, K, R, S, C);
     return hipGetLastError();
 }
 

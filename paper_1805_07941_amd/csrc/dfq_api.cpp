@@ -231,9 +231,9 @@ dfq_status dfq_eltwise_np(const int8_t *ah, const int8_t *al, int frac_a, const 
                                       relu ? 1 : 0, (hipStream_t)stream));
 }
 
-static dfq_status check_conv_np(NpConvArgs &a, int frac_x, int frac_w, int frac_y)
+static dfq_status check_conv_np(NpConvArgs &a, int frac_x, int frac_w, int frac_y, bool outputs = true)
 {
-    if (!a.xh || !a.xl || !a.wh || !a.wl || (!a.y && !a.yh && !a.yl)) return DFQ_EINVAL;
+    if (!a.xh || !a.xl || !a.wh || !a.wl || (outputs && !a.y && !a.yh && !a.yl)) return DFQ_EINVAL;
     if ((a.yh == nullptr) != (a.yl == nullptr)) return DFQ_EINVAL;
     if (a.N < 0) return DFQ_EINVAL;
     if (a.H < 1 || a.W < 1 || a.C < 1 || a.K < 1 || a.R < 1 || a.S < 1 || a.stride < 1 || a.pad < 0 || a.groups < 1) return DFQ_ESHAPE;
@@ -264,7 +264,7 @@ dfq_status dfq_conv_np_variant(dfq_conv_variant variant, const int8_t *xh, const
                                int stride, int pad, int groups, int frac_x, int frac_w, int frac_y, int p_y, int relu,
                                dfq_stream stream)
 {
-    NpConvArgs a{xh, xl, wh, wl, b, y, yh, yl, N, H, W, C, K, R, S, stride, pad, groups, 0, 0, 0, p_y, 0, relu ? 1 : 0};
+    NpConvArgs a{xh, xl, wh, wl, b, y, yh, yl, N, H, W, C, K, R, S, stride, pad, groups, 0, 0, 0, p_y, 0, relu ? 1 : 0, nullptr};
     const dfq_status st = check_conv_np(a, frac_x, frac_w, frac_y);
     if (st != DFQ_OK) return st;
     if (N == 0) return DFQ_OK;
@@ -275,6 +275,96 @@ dfq_status dfq_conv_np_variant(dfq_conv_variant variant, const int8_t *xh, const
     }
     if (variant == DFQ_CONV_DIRECT) return from_hip(launch_conv_np_direct(a, (hipStream_t)stream));
     return DFQ_EINVAL;
+}
+
+dfq_status dfq_conv_np_absmax(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int32_t *b, uint64_t *amax_dev,
+                              int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups, int relu, dfq_stream stream)
+{
+    if (!amax_dev || ((uintptr_t)amax_dev & 7)) return DFQ_EINVAL;
+    // (the format arguments of the shared checks are placeholders: nothing is converted or stored)
+    NpConvArgs a{xh, xl, wh, wl, b, nullptr, nullptr, nullptr, N, H, W, C, K, R, S, stride, pad, groups, 0, 0, 0, 4, 0, relu ? 1 : 0, nullptr};
+    const dfq_status st = check_conv_np(a, 0, 0, 0, false);
+    if (st != DFQ_OK) return st;
+    a.amax = reinterpret_cast<unsigned long long *>(amax_dev);
+    hipError_t e = launch_clear_u64(a.amax, (hipStream_t)stream);
+    if (e != hipSuccess || N == 0) return from_hip(e);
+    return from_hip(launch_conv_np_direct(a, (hipStream_t)stream));
+}
+
+dfq_status dfq_eltwise_np_absmax(const int8_t *ah, const int8_t *al, int frac_a, const int8_t *bh, const int8_t *bl, int frac_b,
+                                 uint64_t *amax_dev, size_t n, int relu, dfq_stream stream)
+{
+    if (!amax_dev || ((uintptr_t)amax_dev & 7)) return DFQ_EINVAL;
+    if (frac_a < -32 || frac_a > 32 || frac_b < -32 || frac_b > 32) return DFQ_EFMT;
+    const int F = frac_a > frac_b ? frac_a : frac_b;
+    if (F - frac_a > 18 || F - frac_b > 18) return DFQ_EFMT;
+    if (n && (!ah || !al || !bh || !bl)) return DFQ_EINVAL;
+    hipError_t e = launch_clear_u64(reinterpret_cast<unsigned long long *>(amax_dev), (hipStream_t)stream);
+    if (e != hipSuccess || n == 0) return from_hip(e);
+    return from_hip(launch_eltwise_np_absmax(ah, al, bh, bl, n, F - frac_a, F - frac_b, relu ? 1 : 0,
+                                             reinterpret_cast<unsigned long long *>(amax_dev), (hipStream_t)stream));
+}
+
+dfq_status dfq_np_frac_from_absmax_u64(uint64_t max_abs, int acc_frac, int nbits, int p, int *frac)
+{
+    if (!frac) return DFQ_EINVAL;
+    if (nbits < 2 || nbits > 16 || p < 0 || p > nbits - 1) return DFQ_EFMT;
+    if (acc_frac < -128 || acc_frac > 128) return DFQ_EFMT;
+    const int64_t bm64 = dfq_beta_max(nbits, p);
+    if (bm64 <= 0) return DFQ_EFMT;
+    const uint64_t bm = (uint64_t)bm64;
+    int f = acc_frac > 32 ? 32 : (acc_frac < -32 ? -32 : acc_frac);
+    for (; f > -32; f--) {
+        const int sh = acc_frac - f;          // >= 0: the factor 2^(f - acc_frac) stays in (0, 1]
+        if (sh >= 64) break;                  // max_abs < 2^64 <= beta_max * 2^sh
+        const uint64_t q = max_abs >> sh, r = sh ? (max_abs & ((1ull << sh) - 1ull)) : 0ull;
+        if (q < bm || (q == bm && r == 0)) break;      // max_abs <= beta_max * 2^sh without forming the product
+    }
+    *frac = f;
+    return DFQ_OK;
+}
+
+dfq_status dfq_pool_np(const int8_t *xh, const int8_t *xl, uint8_t *y, int8_t *yh, int8_t *yl, dfq_pool_mode mode, int N, int H, int W, int C,
+                       int k, int stride, int pad, int p_fmt, dfq_stream stream)
+{
+    if (mode != DFQ_POOL_MAX && mode != DFQ_POOL_AVG) return DFQ_EINVAL;
+    if (N < 0) return DFQ_EINVAL;
+    if (H < 1 || W < 1 || C < 1 || k < 1 || k > 16 || stride < 1 || pad < 0 || pad >= k) return DFQ_ESHAPE;
+    if (mode == DFQ_POOL_AVG && pad != 0) return DFQ_EUNSUPPORTED;
+    const int P = out_extent(H, pad, k, stride), Q = out_extent(W, pad, k, stride);
+    if (P < 1 || Q < 1) return DFQ_ESHAPE;
+    if (p_fmt < 4 || p_fmt > 7) return DFQ_EFMT;
+    if (N == 0) return DFQ_OK;
+    if (!xh || !xl || (!y && !yh && !yl) || ((yh == nullptr) != (yl == nullptr))) return DFQ_EINVAL;
+    const size_t nx = (size_t)N * H * W * C, ny = (size_t)N * P * Q * C;
+    const void *outs[3] = {y, yh, yl};
+    for (int i = 0; i < 3; i++) {
+        if (overlaps(outs[i], ny, xh, nx) || overlaps(outs[i], ny, xl, nx)) return DFQ_EINVAL;
+        for (int j = i + 1; j < 3; j++)
+            if (overlaps(outs[i], ny, outs[j], ny)) return DFQ_EINVAL;
+    }
+    return from_hip(launch_pool_np(xh, xl, y, yh, yl, mode == DFQ_POOL_AVG ? 1 : 0, N, H, W, C, k, stride, pad, P, Q, p_fmt,
+                                   (int)dfq_beta_max(8, p_fmt), (hipStream_t)stream));
+}
+
+dfq_status dfq_stem_pack_x(const int8_t *x, int8_t *y, int N, int H, int W, int C, int R, int S, int pad, dfq_stream stream)
+{
+    if (N < 0) return DFQ_EINVAL;
+    if (H < 1 || W < 1 || C < 1 || C > 4 || R < 1 || S < 1 || R > 8 || S > 8 || pad < 0) return DFQ_ESHAPE;
+    const int P = out_extent(H, pad, R, 2), Q = out_extent(W, pad, S, 2);
+    if (P < 1 || Q < 1) return DFQ_ESHAPE;
+    if (N == 0) return DFQ_OK;
+    if (!x || !y || ((uintptr_t)y & 3)) return DFQ_EINVAL;
+    const int Hs = P + 3;                   // rows of the packed tensor: output rows plus the 4-row window minus one
+    if (overlaps(x, (size_t)N * H * W * C, y, (size_t)N * Hs * Q * 64)) return DFQ_EINVAL;
+    return from_hip(launch_stem_pack_x(x, y, N, H, W, C, pad, Hs, Q, (hipStream_t)stream));
+}
+
+dfq_status dfq_stem_pack_w(const int8_t *w, int8_t *y, int K, int R, int S, int C, dfq_stream stream)
+{
+    if (K < 1 || C < 1 || C > 4 || R < 1 || S < 1 || R > 8 || S > 8) return DFQ_ESHAPE;
+    if (!w || !y || overlaps(w, (size_t)K * R * S * C, y, (size_t)K * 256)) return DFQ_EINVAL;
+    return from_hip(launch_stem_pack_w(w, y, K, R, S, C, (hipStream_t)stream));
 }
 
 dfq_status dfq_conv_np(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int32_t *b, uint8_t *y,

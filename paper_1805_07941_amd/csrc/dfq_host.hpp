@@ -53,6 +53,7 @@ struct NpConvArgs {
     int p_y;                       // significand bits of the output format (8, p_y)
     int beta_max;                  // Eq. 5 for the output format
     int relu;
+    unsigned long long *amax;      // calibration: receives max |sum + bias| (after ReLU if relu) by atomic max; direct form only
 };
 
 hipError_t launch_quantize(const float *x, int8_t *q, size_t n, int frac, hipStream_t st);
@@ -92,6 +93,13 @@ hipError_t launch_conv_grouped(const ConvArgs &a, hipStream_t st);
 bool conv_np_mfma_supports(const NpConvArgs &a);
 hipError_t launch_conv_np_mfma(const NpConvArgs &a, hipStream_t st);
 hipError_t launch_conv_np_direct(const NpConvArgs &a, hipStream_t st);
+hipError_t launch_clear_u64(unsigned long long *p, hipStream_t st);
+hipError_t launch_eltwise_np_absmax(const int8_t *ah, const int8_t *al, const int8_t *bh, const int8_t *bl, size_t n, int sa, int sb, int relu,
+                                    unsigned long long *amax, hipStream_t st);
+hipError_t launch_pool_np(const int8_t *xh, const int8_t *xl, uint8_t *y, int8_t *yh, int8_t *yl, int avg, int N, int H, int W, int C, int k,
+                          int stride, int pad, int P, int Q, int p_fmt, int beta_max, hipStream_t st);
+hipError_t launch_stem_pack_x(const int8_t *x, int8_t *y, int N, int H, int W, int C, int pad, int Hs, int Qs, hipStream_t st);
+hipError_t launch_stem_pack_w(const int8_t *w, int8_t *y, int K, int R, int S, int C, hipStream_t st);
 hipError_t launch_eltwise_np(const int8_t *ah, const int8_t *al, const int8_t *bh, const int8_t *bl, uint8_t *y, int8_t *yh, int8_t *yl,
                              size_t n, int sa, int sb, int shift, int p_y, int beta_max, int relu, hipStream_t st);
 hipError_t launch_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, hipStream_t st);

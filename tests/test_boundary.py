@@ -178,6 +178,45 @@ def test_eltwise_np_rejects_bad_arguments_before_launching(B):
     assert call(n=0) == B.OK and call(n=0, ah=None) == B.OK
 
 
+def test_np_network_calls_reject_bad_arguments_before_launching(B):
+    import ctypes as C
+    L = B.lib()
+    a = [1 << 20, 2 << 20, 3 << 20, 4 << 20]
+    assert L.dfq_conv_np_absmax(*a, None, None, 1, 8, 8, 64, 16, 3, 3, 1, 1, 1, 0, None) == B.EINVAL          # no result word
+    assert L.dfq_conv_np_absmax(*a, None, (9 << 20) + 4, 1, 8, 8, 64, 16, 3, 3, 1, 1, 1, 0, None) == B.EINVAL  # misaligned
+    assert L.dfq_conv_np_absmax(None, *a[1:], None, 9 << 20, 1, 8, 8, 64, 16, 3, 3, 1, 1, 1, 0, None) == B.EINVAL
+    assert L.dfq_conv_np_absmax(*a, None, 9 << 20, 1, 8, 8, 64, 16, 3, 3, 0, 1, 1, 0, None) == B.ESHAPE
+    assert L.dfq_eltwise_np_absmax(a[0], a[1], 5, a[2], a[3], 5, None, 100, 0, None) == B.EINVAL
+    assert L.dfq_eltwise_np_absmax(a[0], a[1], 20, a[2], a[3], 1, 9 << 20, 100, 0, None) == B.EFMT
+    assert L.dfq_eltwise_np_absmax(None, a[1], 5, a[2], a[3], 5, 9 << 20, 100, 0, None) == B.EINVAL
+    out = C.c_int32()
+    assert L.dfq_np_frac_from_absmax_u64(5, 0, 8, 4, None) == B.EINVAL
+    assert L.dfq_np_frac_from_absmax_u64(5, 0, 8, 9, C.byref(out)) == B.EFMT
+    assert L.dfq_np_frac_from_absmax_u64(5, 200, 8, 4, C.byref(out)) == B.EFMT
+    import oracle.npnet as NN
+    import oracle.npfmt as F
+    for p in (4, 5, 7):
+        bm = F.beta_max(8, p)
+        for m in [0, 1, bm - 1, bm, bm + 1, 2 * bm, 2 * bm + 1, 12345678, (1 << 36) + 5, bm << 20, (bm << 20) + 1, (1 << 63) + 1, (1 << 64) - 1]:
+            for f_acc in [-40, -3, 0, 7, 20, 40, 100]:
+                assert B.np_frac_from_absmax_u64(m, f_acc, 8, p) == NN.frac_from_absmax_int(m, f_acc, 8, p), (m, f_acc, p)
+
+    def pool(xh=a[0], xl=a[1], y=5 << 20, yh=6 << 20, yl=7 << 20, mode=B.POOL_MAX, N=1, H=8, W=8, Cc=16, k=3, stride=2, pad=1, p=4):
+        return L.dfq_pool_np(xh, xl, y, yh, yl, mode, N, H, W, Cc, k, stride, pad, p, None)
+
+    assert pool(xh=None) == B.EINVAL and pool(y=None, yh=None, yl=None) == B.EINVAL and pool(yl=None) == B.EINVAL
+    assert pool(y=a[0]) == B.EINVAL and pool(mode=7) == B.EINVAL
+    assert pool(k=0) == B.ESHAPE and pool(k=17) == B.ESHAPE and pool(pad=3) == B.ESHAPE and pool(H=1, W=1, pad=0) == B.ESHAPE
+    assert pool(mode=B.POOL_AVG) == B.EUNSUPPORTED and pool(p=3) == B.EFMT and pool(N=0) == B.OK
+    assert L.dfq_stem_pack_x(None, 2 << 20, 1, 32, 32, 3, 7, 7, 3, None) == B.EINVAL
+    assert L.dfq_stem_pack_x(1 << 20, 2 << 20, 1, 32, 32, 5, 7, 7, 3, None) == B.ESHAPE                        # five channels do not fit 16 bytes
+    assert L.dfq_stem_pack_x(1 << 20, 2 << 20, 1, 32, 32, 3, 9, 9, 3, None) == B.ESHAPE
+    assert L.dfq_stem_pack_x(1 << 20, (1 << 20) + 64, 1, 32, 32, 3, 7, 7, 3, None) == B.EINVAL                 # overlap
+    assert L.dfq_stem_pack_x(1 << 20, 2 << 20, 0, 32, 32, 3, 7, 7, 3, None) == B.OK
+    assert L.dfq_stem_pack_w(1 << 20, None, 64, 7, 7, 3, None) == B.EINVAL
+    assert L.dfq_stem_pack_w(1 << 20, 2 << 20, 64, 7, 7, 5, None) == B.ESHAPE
+
+
 def test_np_frac_from_absmax_matches_the_oracle(B):
     import oracle.npfmt as F
     rng = np.random.default_rng(9)
