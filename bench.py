@@ -206,6 +206,98 @@ def bench_layers_np(args):
                       "roofline_note": "pct_mfma_peak prices the four int8 matrix products per block against 5 POP/s", "layers": rows}))
 
 
+def bench_net_np(args):
+    """The ResNet-50-shaped pass with every tensor on (8, 4) dynamic floating-point codes (npnet.NpPlan): single-batch
+    calibration on --calib images, the pass replayed from a HIP graph, then - outside the timed region - the duration of
+    every library call of one pass (event pairs on the launch stream) and the logits of a few images against the
+    network oracle on (8, 4) codes, which calibrates for itself.  One JSON line."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    from paper_1805_07941_amd import binding as B
+    from paper_1805_07941_amd import npnet
+
+    dev = "cuda:0"
+    net = wl.resnet50(batch=args.batch)
+    x_host = net.input_float()
+    x = torch.from_numpy(x_host).to(dev)
+    qz, _ = npnet.calibrate(net, x[:args.calib].contiguous(), p=4)
+    plan = npnet.NpPlan(net, qz, args.batch)
+    step = (lambda: plan.run(x)) if args.no_graph else (lambda: plan.run_graph(x))
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+
+    calls = plan._calls_for(x)
+    st = B._stream(None)
+    reps = max(2, min(args.steps, 5))
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls] for _ in range(reps)]
+    for r in range(reps):
+        torch.cuda._sleep(6_000_000)
+        for (fn, cargs), (e0, e1) in zip(calls, evs[r]):
+            e0.record()
+            rc = fn(*cargs, st)
+            e1.record()
+            if rc != B.OK:
+                raise B.DfqError(rc, fn.__name__)
+    torch.cuda.synchronize()
+    node = {nd.name: nd for nd in net.nodes}
+    by_fn, layers = {}, []
+    for i, ((fn, _), name) in enumerate(zip(calls, plan.call_nodes)):
+        us = sum(evs[r][i][0].elapsed_time(evs[r][i][1]) for r in range(reps)) / reps * 1e3
+        d = by_fn.setdefault(fn.__name__, dict(calls=0, us=0.0))
+        d["calls"] += 1
+        d["us"] = round(d["us"] + us, 1)
+        if fn.__name__ == "dfq_conv_np":
+            nd = node[name]
+            o = 2.0 * node_macs(net, nd) * args.batch
+            layers.append(dict(layer=name, us=round(us, 1), tops=round(o / us / 1e6, 1), int8_matrix_tops=round(4 * o / us / 1e6, 1)))
+    macs_step = net.macs_per_image() * args.batch
+    tops = 2 * macs_step / (ms_per_step * 1e-3) / 1e12
+    conv_us = by_fn["dfq_conv_np"]["us"]
+
+    cpu, parity_checked = None, None
+    if args.cpu_sample > 0:
+        import oracle.npnet as NN
+        n_cpu = min(args.cpu_sample, 4, args.batch)
+        n_cal = min(args.calib, args.batch)
+        oq, _ = NN.calibrate(net, x_host[:n_cal], fmt=(8, 4))
+        t1 = time.perf_counter()
+        ref = NN.logits(net, oq, NN.infer(net, oq, x_host[:n_cpu]))
+        t_cpu = time.perf_counter() - t1
+        got = step().cpu().numpy()[:n_cpu]
+        equal = int(sum(bool(np.array_equal(got[i], ref[i])) for i in range(n_cpu)))
+        parity_checked = dict(images=n_cpu, images_with_identical_logits=equal, tolerance=0,
+                              what="float logits of the timed plan against the (8, 4) network oracle's")
+        cpu = dict(value=round(n_cpu / t_cpu, 3), unit="images/s", cores=os.cpu_count(), kind="oracle",
+                   sample="%d images of the same batch through oracle.npnet.infer (numpy; window sums by the double matrix product)" % n_cpu)
+    line = {
+        "metric": "(8,4) dynamic floating-point conv TOPS (2*MAC/s of Eq. 6's products), whole ResNet-50-shaped pass, b=%d" % args.batch,
+        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "(8,4) codes as two int8 digit planes; four int8 matrix products per block into three int32 accumulators -> exact sum",
+        "data": "synthetic", "launch": "per-call from Python" if args.no_graph else "HIP graph replay of the fixed call sequence",
+        "config": {"workload": "configs[4]'s network on (8, 4) codes: ResNet-50-shaped, 224x224x3, batch %d, scales from a single-batch "
+                               "calibration on %d images" % (args.batch, args.calib), "global_batch": args.batch},
+        "images_per_s": round(args.batch / (ms_per_step * 1e-3), 1),
+        "roofline": {"bound": "mfma", "kernel": "conv_np_mfma_kernel: the %d convolution launches of a pass" % by_fn["dfq_conv_np"]["calls"],
+                     "achieved": round(4 * 2 * macs_step / conv_us / 1e6, 1), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": round(4 * 2 * macs_step / conv_us / 1e6 / INT8_MFMA_PEAK_TOPS, 4),
+                     "note": "int8 matrix operations executed (four per product of Eq. 6) over the summed event intervals of the convolution calls",
+                     "traffic": None},
+        "calls": by_fn, "cpu_baseline": cpu, "parity_checked": parity_checked, "conv_layers": layers,
+    }
+    print(json.dumps(line))
+    if parity_checked is not None and parity_checked["images_with_identical_logits"] != parity_checked["images"]:
+        print("bench.py: the timed plan's logits differ from the oracle's", file=sys.stderr)
+        sys.exit(1)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -227,7 +319,7 @@ def main():
     ap.add_argument("--layer-set", choices=["config1", "3x3"], default="config1",
                     help="with --layers: the five layers of configs[1], or the four 3x3 shapes of the ResNet-50-shaped network")
     ap.add_argument("--np84", action="store_true",
-                    help="with --layers: the same layers on (8, 4) dynamic floating-point codes (dfq_conv_np)")
+                    help="the network pass on (8, 4) dynamic floating-point codes (npnet.NpPlan); with --layers: the dense layers alone (dfq_conv_np)")
     ap.add_argument("--launch-classes", default=None,
                     help="write the per-pass order of the matrix-core launches with their roofline class (JSON) to this file")
     ap.add_argument("--no-mfma-rate", action="store_true", help="skip the register-only matrix-instruction rate probe")
@@ -253,6 +345,9 @@ def main():
     torch.cuda.set_device(0)
     if args.layers:
         (bench_layers_np if args.np84 else bench_layers)(args)
+        return
+    if args.np84:
+        bench_net_np(args)
         return
 
     net = wl.resnet50(batch=args.batch)

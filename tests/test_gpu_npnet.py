@@ -147,3 +147,27 @@ def test_small_resnet_calibration_and_inference(B, p):
         out = plan.run_graph(xd)
         torch.cuda.synchronize()
         assert np.array_equal(host(out), NN.logits(net, oq, oi)), rep
+
+
+def test_resnet50_np84_full_batch(B):
+    """The benchmarked configuration: batch 256 at 224 x 224, scales from 8 images, the pass replayed from a graph; two
+    whole images - every tensor of the first, the logits of both - against the network oracle, which calibrates for itself."""
+    from paper_1805_07941_amd import npnet
+    net = wl.resnet50(batch=256)
+    x = net.input_float()
+    xd = dev(x)
+    qz, _ = npnet.calibrate(net, xd[:8].contiguous(), p=4)
+    oq, _ = NN.calibrate(net, x[:8], fmt=(8, 4))
+    assert qz.frac == oq.frac and qz.w_frac == oq.w_frac
+    plan = npnet.NpPlan(net, qz, batch=256)
+    plan.run_graph(xd)
+    out = plan.run_graph(xd)
+    torch.cuda.synchronize()
+    pick = [0, 255]
+    oi = NN.infer(net, oq, x[pick])
+    assert np.array_equal(host(out)[pick], NN.logits(net, oq, oi))
+    for name, codes in oi.items():
+        K = codes.shape[3]
+        got = 64 * host(plan.buf[name][0][pick]).astype(np.int64) + host(plan.buf[name][1][pick])
+        assert np.array_equal(got[..., :K], NC.decode_tensor(codes, 8, 4)), name
+    assert len(np.unique(host(out)[pick])) > 50
