@@ -66,35 +66,31 @@ __device__ __forceinline__ int np_round_acc(long long v, const NpRound &f)
     return neg ? -beta : beta;
 }
 
-// The same rounding for the matrix-core kernel's epilogue when 7 <= shift <= 36, in 32-bit integers.  The accumulator is
-// 64 * T + c with T and c int32; with hi = c >> 6 (floor) its value is (T + hi + f) * 64 for a fraction f in [0, 1) that
-// is nonzero iff c & 63 is.  The integer a = 2 * (T + hi) + (f != 0) has the sign of the accumulator and |a| is its
-// magnitude in units of 32 with the last bit sticky (odd: strictly between the even neighbours) - all a rounding needs
-// whose kept bits end at least two places above it: the results are integers and one unit of a is 2^(5 - shift) <= 1/4.
-// With L the leading bit of |a| the value lies in binade e = L + 5 - shift, the step is 2^k with k = max(e - p, 0), so
-// r = shift - 5 + k bits of |a| go: q = (|a| + 2^(r-1) - 1 + bit_r(|a|)) >> r is round-half-even, and the result is
-// q * 2^k (q = 2^(p+1) after a carry is the first value of the next binade), clamped at beta_max.  2 <= r <= 31, and
-// |T + hi| < 2^30 by the launcher's bound on the reduction length.  Returns the magnitude; sgn = 0 or -1.
+// The same rounding for the matrix-core kernel's epilogue when 7 <= shift <= 36, through the double-precision adder.  The
+// accumulator is V = 64 * T + c with T and c int32 (|V| < 2^37): a double holds it exactly.  With e the binade of |V| the
+// result's step is 2^(e' - p) in units of V, e' = max(e, p + shift) (below 2^(p+1) output units the step is one unit).
+// Adding M = 1.5 * 2^(e' + 52 - p) puts V into a binade whose unit in the last place is exactly that step, so the adder's
+// own round-to-nearest-even does the rounding (M is an even multiple of the step: the parity of the sum's last bit is the
+// parity of the quotient q = round(V / step), i.e. of the significand field), and q is the low word of the sum's bit
+// pattern (the mantissa field holds 2^51 + q).  The result is q * 2^k, k = e' - p - shift.  Values beyond every format
+// of this path (e' capped at p + shift + 11 - p: at least 2^12 output units) still give a q * 2^k >= 2^12 that fits 31
+// bits because shift >= 7, and the clamp that follows cuts them.  Returns the signed integer before the clamp.
 struct NpFast {
-    int c0;          // 36 - shift - p
-    int sm5;         // shift - 5
-    unsigned bmax;
+    unsigned base_b;     // biased exponent of the smallest e': 1023 + p + shift
+    unsigned top_b;      // base_b + 11 - p
+    unsigned m_const;    // ((52 - p) << 20) | 0x80000: exponent offset and the mantissa bit of the factor 1.5
+    int bmax;
 };
 
-__device__ __forceinline__ unsigned np_round_fast(int T, int c, const NpFast &f, int &sgn)
+__device__ __forceinline__ int np_round_fast(int T, int c, const NpFast &f)
 {
-    const int w = T + (c >> 6);
-    const int a = w + w + ((c & 63) != 0 ? 1 : 0);
-    sgn = a >> 31;
-    const unsigned mag = (unsigned)((a ^ sgn) - sgn);
-    int lz;
-    asm("v_ffbh_u32 %0, %1" : "=v"(lz) : "v"(mag));      // leading zeros; -1 for 0 (then q = 0 whatever r is)
-    const int k = max(f.c0 - lz, 0);
-    const int r = k + f.sm5;
-    const unsigned odd = __builtin_amdgcn_ubfe(mag, (unsigned)r, 1u);
-    const unsigned hm1 = (1u << (r - 1)) - 1u;
-    const unsigned q = (mag + hm1 + odd) >> r;
-    return min(q << k, f.bmax);
+    const double x = __builtin_fma((double)T, 64.0, (double)c);
+    const unsigned e_b = __builtin_amdgcn_ubfe((unsigned)__double2hiint(x), 20u, 11u);
+    unsigned eb;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(eb) : "v"(e_b), "s"(f.base_b), "v"(f.top_b));      // clamp to [base_b, top_b]
+    const double M = __hiloint2double((int)((eb << 20) + f.m_const), 0);
+    const int q = __double2loint(x + M);
+    return q << (eb - f.base_b);
 }
 
 // byte E of w = low byte of (v >> sh), of (v & msk), of (x - y): the operation writes its result's low byte straight
@@ -106,6 +102,14 @@ __device__ __forceinline__ void put_shr(uint32_t &w, unsigned sh, unsigned v)
     if constexpr (E == 1) asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sh), "v"(v));
     if constexpr (E == 2) asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sh), "v"(v));
     if constexpr (E == 3) asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sh), "v"(v));
+}
+template <int E>
+__device__ __forceinline__ void put_ashr(uint32_t &w, unsigned sh, int v)
+{
+    if constexpr (E == 0) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sh), "v"(v));
+    if constexpr (E == 1) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sh), "v"(v));
+    if constexpr (E == 2) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sh), "v"(v));
+    if constexpr (E == 3) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(w) : "v"(sh), "v"(v));
 }
 template <int E>
 __device__ __forceinline__ void put_and(uint32_t &w, unsigned msk, unsigned v)
@@ -155,29 +159,27 @@ __device__ __forceinline__ void np_split(int beta, int &h, int &l)
 // FAST: 7 <= shift <= 36 (32-bit rounding above), else the 64-bit form; RELU and CODES (codes wanted) as template
 // parameters keep the sign handling and the encoding out of the variants that do not need them.
 template <bool FAST, bool RELU, bool CODES, int E>
-__device__ __forceinline__ void np_finish_one(int A, int Cc, int Bm, int bias, const NpRound &rnd, const NpFast &fr, int p_y, uint32_t &wc,
+__device__ __forceinline__ void np_finish_one(int A, int Cc, int Bm, const NpRound &rnd, const NpFast &fr, int p_y, uint32_t &wc,
                                               uint32_t &whi, uint32_t &wlo)
 {
-    const int T = (A << 6) + Bm;                         // 64 A + B
-    unsigned mag;
-    int sgn;
+    const int T = (A << 6) + Bm;                         // 64 A + B (the bias sits in the start values of B and C)
+    int beta;
     if constexpr (FAST) {
-        // (the bias joins both parts: |C| + 63 and |T| + |bias| / 64 stay inside 32 bits)
-        mag = np_round_fast(T + (bias >> 6), Cc + (bias & 63), fr, sgn);
+        beta = np_round_fast(T, Cc, fr);
+        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(beta) : "v"(beta), "s"(RELU ? 0 : -fr.bmax), "v"(fr.bmax));
     } else {
-        const int beta = np_round_acc((long long)T * 64 + (long long)Cc + (long long)bias, rnd);
-        sgn = beta >> 31;
-        mag = (unsigned)((beta ^ sgn) - sgn);
+        beta = np_round_acc((long long)T * 64 + (long long)Cc, rnd);
     }
     if constexpr (RELU) {
-        mag &= ~(unsigned)sgn;
-        put_shr<E>(whi, 6u, mag);
-        put_and<E>(wlo, 63u, mag);
-        if constexpr (CODES) wc |= np_code_of((int)mag, p_y) << (8 * E);
+        put_shr<E>(whi, 6u, (unsigned)beta);
+        put_and<E>(wlo, 63u, (unsigned)beta);
+        if constexpr (CODES) wc |= np_code_of(beta, p_y) << (8 * E);
     } else {
-        put_sub<E>(whi, (mag >> 6) ^ (unsigned)sgn, (unsigned)sgn);
-        put_sub<E>(wlo, (mag & 63u) ^ (unsigned)sgn, (unsigned)sgn);
-        if constexpr (CODES) wc |= (np_code_of((int)mag, p_y) | (mag ? ((unsigned)sgn & 0x80u) : 0u)) << (8 * E);
+        // digits of the sign of beta: h = trunc(beta / 64), l = beta - 64 h
+        const int t = beta + ((beta >> 31) & 63);
+        put_ashr<E>(whi, 6u, t);
+        put_sub<E>(wlo, (unsigned)beta, (unsigned)t & ~63u);
+        if constexpr (CODES) wc |= np_code_of(beta, p_y) << (8 * E);
     }
 }
 
@@ -513,8 +515,8 @@ struct NpConvParams {
     FastDiv div_q, div_p, div_tc;
 };
 
-template <int BP, int BC>
-__global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
+template <int BP, int BC, int OCC>
+__global__ void __launch_bounds__(256, OCC) conv_np_mfma_kernel(NpConvParams prm)
 {
     constexpr int NSTAGES = 3;
     constexpr int ROWS = 2 * BP + 2 * BC;                 // LDS rows of 64 bytes per stage: x_h, x_l, w_h, w_l
@@ -524,7 +526,7 @@ __global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
     static_assert(BP % 64 == 0 && BC % 64 == 0, "whole chunks for four wavefronts");
     constexpr int WP = BP / 2, WC = BC / 2;               // wavefront tile (2 x 2 wavefronts)
     constexpr int PT = WP / 32, CT = WC / 32;
-    static_assert(PT * CT == 4, "twelve accumulator tiles per wavefront");
+    static_assert(PT * CT == 4 || (PT * CT == 2 && OCC == 2), "twelve accumulator tiles per wavefront, or six with two workgroups per compute unit");
 
     extern __shared__ uint4 lds[];
     const NpConvArgs &a = prm.a;
@@ -611,12 +613,28 @@ __global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
     const int l32 = lane & 31, lh = lane >> 5;
     const int swz = (l32 >> 2) & 3;
     v16i accA[CT][PT], accC[CT][PT], accB[CT][PT];
+    // the bias b = 64 * (b >> 6) + (b & 63) starts the accumulators of the middle and the low products
 #pragma unroll
-    for (int c = 0; c < CT; c++)
+    for (int c = 0; c < CT; c++) {
+        const int kc = ct * BC + wc0 + c * 32 + 16 * lh;
+        int bias[16];
+#pragma unroll
+        for (int r4 = 0; r4 < 4; r4++) {
+            const int4 bv = (a.b && kc < a.K) ? *(const int4 *)(a.b + kc + 4 * r4) : make_int4(0, 0, 0, 0);
+            bias[4 * r4 + 0] = bv.x;
+            bias[4 * r4 + 1] = bv.y;
+            bias[4 * r4 + 2] = bv.z;
+            bias[4 * r4 + 3] = bv.w;
+        }
 #pragma unroll
         for (int p = 0; p < PT; p++)
 #pragma unroll
-            for (int r = 0; r < 16; r++) accA[c][p][r] = accC[c][p][r] = accB[c][p][r] = 0;
+            for (int r = 0; r < 16; r++) {
+                accA[c][p][r] = 0;
+                accB[c][p][r] = bias[r] >> 6;
+                accC[c][p][r] = bias[r] & 63;
+            }
+    }
 
     // Operands of one 32-byte half of a step.  Step i multiplies operands that are already in registers and meanwhile
     // reads those of step i+1: after the first half's matrix instructions the wavefront waits for its own loads of step
@@ -696,22 +714,13 @@ __global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
 
     // ---- epilogue: register r of a lane belongs to channel kc + r of pixel m
     const NpRound rnd = {a.shift, a.p_y, (float)a.beta_max, a.relu};
-    const NpFast fr = {36 - a.shift - a.p_y, a.shift - 5, (unsigned)a.beta_max};
+    const NpFast fr = {(unsigned)(1023 + a.p_y + a.shift), (unsigned)(1023 + a.shift + 11), ((unsigned)(52 - a.p_y) << 20) | 0x80000u, a.beta_max};
     auto finish = [&](auto fast, auto relu, auto codes) __attribute__((always_inline)) {
         constexpr bool FAST = decltype(fast)::value, RELU = decltype(relu)::value, CODES = decltype(codes)::value;
 #pragma unroll
         for (int c = 0; c < CT; c++) {
             const int kc = ct * BC + wc0 + c * 32 + 16 * lh;
             if (kc >= a.K) continue;
-            int bias[16];
-#pragma unroll
-            for (int r4 = 0; r4 < 4; r4++) {
-                const int4 bv = a.b ? *(const int4 *)(a.b + kc + 4 * r4) : make_int4(0, 0, 0, 0);
-                bias[4 * r4 + 0] = bv.x;
-                bias[4 * r4 + 1] = bv.y;
-                bias[4 * r4 + 2] = bv.z;
-                bias[4 * r4 + 3] = bv.w;
-            }
 #pragma unroll
             for (int p = 0; p < PT; p++) {
                 const int m = pt * BP + wp0 + p * 32 + l32;
@@ -720,10 +729,10 @@ __global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
                 for (int r4 = 0; r4 < 4; r4++) {
                     uint32_t wc = 0, whi = 0, wlo = 0;
                     const int r = 4 * r4;
-                    np_finish_one<FAST, RELU, CODES, 0>(accA[c][p][r + 0], accC[c][p][r + 0], accB[c][p][r + 0], bias[r + 0], rnd, fr, a.p_y, wc, whi, wlo);
-                    np_finish_one<FAST, RELU, CODES, 1>(accA[c][p][r + 1], accC[c][p][r + 1], accB[c][p][r + 1], bias[r + 1], rnd, fr, a.p_y, wc, whi, wlo);
-                    np_finish_one<FAST, RELU, CODES, 2>(accA[c][p][r + 2], accC[c][p][r + 2], accB[c][p][r + 2], bias[r + 2], rnd, fr, a.p_y, wc, whi, wlo);
-                    np_finish_one<FAST, RELU, CODES, 3>(accA[c][p][r + 3], accC[c][p][r + 3], accB[c][p][r + 3], bias[r + 3], rnd, fr, a.p_y, wc, whi, wlo);
+                    np_finish_one<FAST, RELU, CODES, 0>(accA[c][p][r + 0], accC[c][p][r + 0], accB[c][p][r + 0], rnd, fr, a.p_y, wc, whi, wlo);
+                    np_finish_one<FAST, RELU, CODES, 1>(accA[c][p][r + 1], accC[c][p][r + 1], accB[c][p][r + 1], rnd, fr, a.p_y, wc, whi, wlo);
+                    np_finish_one<FAST, RELU, CODES, 2>(accA[c][p][r + 2], accC[c][p][r + 2], accB[c][p][r + 2], rnd, fr, a.p_y, wc, whi, wlo);
+                    np_finish_one<FAST, RELU, CODES, 3>(accA[c][p][r + 3], accC[c][p][r + 3], accB[c][p][r + 3], rnd, fr, a.p_y, wc, whi, wlo);
                     oc[r4] = wc;
                     oh[r4] = whi;
                     ol[r4] = wlo;
@@ -754,7 +763,7 @@ __global__ void __launch_bounds__(256, 1) conv_np_mfma_kernel(NpConvParams prm)
     }
 }
 
-template <int BP, int BC>
+template <int BP, int BC, int OCC = 1>
 hipError_t launch_np_mfma(const NpConvArgs &a, hipStream_t st)
 {
     NpConvParams prm;
@@ -772,10 +781,10 @@ hipError_t launch_np_mfma(const NpConvArgs &a, hipStream_t st)
     const long long tiles = ((M + BP - 1) / BP) * prm.tiles_c;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     constexpr size_t lds_bytes = (size_t)3 * (2 * BP + 2 * BC) * 64;
-    static_assert(lds_bytes <= (size_t)kLdsBytes, "three stages fit");
-    static const hipError_t attr = hipFuncSetAttribute((const void *)conv_np_mfma_kernel<BP, BC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    static_assert(lds_bytes * OCC <= (size_t)kLdsBytes, "three stages fit");
+    static const hipError_t attr = hipFuncSetAttribute((const void *)conv_np_mfma_kernel<BP, BC, OCC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (attr != hipSuccess) return attr;
-    conv_np_mfma_kernel<BP, BC><<<(unsigned)tiles, 256, lds_bytes, st>>>(prm);
+    conv_np_mfma_kernel<BP, BC, OCC><<<(unsigned)tiles, 256, lds_bytes, st>>>(prm);
     return hipGetLastError();
 }
 
@@ -797,6 +806,10 @@ bool conv_np_mfma_supports(const NpConvArgs &a)
 
 hipError_t launch_conv_np_mfma(const NpConvArgs &a, hipStream_t st)
 {
+    // Short reductions (at most four 64-byte steps: 1 x 1 layers with up to 256 input channels) spend their time on the
+    // latency of the first loads and on the epilogue: half-size wavefront tiles leave room for a second workgroup per
+    // compute unit, which runs its matrix instructions and loads under the other's epilogue.
+    if ((long long)a.R * a.S * a.C <= 4 * kStepBytes) return launch_np_mfma<128, 64, 2>(a, st);
     if (a.K <= 64) return launch_np_mfma<256, 64>(a, st);
     return launch_np_mfma<128, 128>(a, st);
 }
