@@ -357,7 +357,7 @@ dfq_status dfq_pool_np(const int8_t *xh, const int8_t *xl, uint8_t *y, int8_t *y
  * channels of the packed tensor  y[N][P + 3][Q][64],  y[n][i][q][16 s + (2 dy + dx) C + c] = x_padded[n][2 i + dy][2 (q + s) + dx][c]
  * (s = 0..3, zeros elsewhere), P x Q the layer's output size, with the weights packed alike:
  * y[K][4][1][64],  y[k][r][0][16 s + (2 dy + dx) C + c] = w[k][2 r + dy][2 s + dx][c] where that tap exists, else 0.
- * The sums are the same integers term by term (zero taps add nothing).  y 4-byte aligned; no overlap.  All DEVICE. */
+ * The sums are the same integers term by term (zero taps add nothing).  y 16-byte aligned; no overlap.  All DEVICE. */
 dfq_status dfq_stem_pack_x(const int8_t *x, int8_t *y, int N, int H, int W, int C, int R, int S, int pad, dfq_stream stream);
 dfq_status dfq_stem_pack_w(const int8_t *w, int8_t *y, int K, int R, int S, int C, dfq_stream stream);
 

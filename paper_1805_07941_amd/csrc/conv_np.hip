@@ -418,27 +418,33 @@ __global__ void __launch_bounds__(256) maxpool3_np_kernel(NpPoolParams a)
 // s' = 0..3, so that the layer becomes a 4 x 1 convolution over 64 channels with unit stride and no padding.
 __global__ void __launch_bounds__(256) stem_pack_x_kernel(const int8_t *x, int8_t *y, int N, int H, int W, int C, int pad, int Hs, int Qs)
 {
-    const size_t total = (size_t)N * Hs * Qs * 16;                  // one lane per 4 bytes: (pixel, s', parity pair)
+    const size_t total = (size_t)N * Hs * Qs * 4;                   // one lane per 16-byte piece: (pixel, s')
+    const uint8_t *xu = (const uint8_t *)x;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        const int j = (int)(i & 15);                                // dword within the 64-byte row
-        const size_t pix = i >> 4;
+        const int sp = (int)(i & 3);
+        const size_t pix = i >> 2;
         const int q = (int)(pix % Qs);
         const size_t t = pix / Qs;
         const int ii = (int)(t % Hs);
         const int n = (int)(t / Hs);
-        uint32_t out = 0;
+        // the piece holds, for dy = 0, 1, the 2 C bytes of the two neighbouring pixels 2 (q + s') - pad + {0, 1} of row 2 ii + dy - pad
+        unsigned long long lo = 0, hi = 0;                          // bytes 0..7 and 8..15 of the piece
+        const int iw0 = 2 * (q + sp) - pad;
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
-            const int byte = 4 * j + e;                             // 16 s' + (2 dy + dx) C + c
-            const int sp = byte >> 4, rest = byte & 15;
-            if (rest < 4 * C) {
-                const int par = rest / C, c = rest - par * C;
-                const int ih = 2 * ii + (par >> 1) - pad, iw = 2 * (q + sp) + (par & 1) - pad;
-                if (ih >= 0 && ih < H && iw >= 0 && iw < W)
-                    out |= ((uint32_t)(uint8_t)x[(((size_t)n * H + ih) * W + iw) * C + c]) << (8 * e);
+        for (int dy = 0; dy < 2; dy++) {
+            const int ih = 2 * ii + dy - pad;
+            if (ih < 0 || ih >= H) continue;
+            const uint8_t *row = xu + ((size_t)n * H + ih) * W * C;
+            for (int b = 0; b < 2 * C; b++) {
+                const int iw = iw0 + (b >= C ? 1 : 0);
+                if (iw < 0 || iw >= W) continue;
+                const unsigned long long v = row[(size_t)(iw * C + (b >= C ? b - C : b))];
+                const int pos = dy * 2 * C + b;                     // byte position in the piece
+                if (pos < 8) lo |= v << (8 * pos);
+                else hi |= v << (8 * (pos - 8));
             }
         }
-        ((uint32_t *)y)[i] = out;
+        ((uint4 *)y)[i] = make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
     }
 }
 
@@ -515,10 +521,10 @@ struct NpConvParams {
     FastDiv div_q, div_p, div_tc;
 };
 
-template <int BP, int BC, int OCC>
+template <int BP, int BC, int OCC, int NSTAGES>
 __global__ void __launch_bounds__(256, OCC) conv_np_mfma_kernel(NpConvParams prm)
 {
-    constexpr int NSTAGES = 3;
+    static_assert(NSTAGES == 2 || NSTAGES == 3, "ring depth");
     constexpr int ROWS = 2 * BP + 2 * BC;                 // LDS rows of 64 bytes per stage: x_h, x_l, w_h, w_l
     constexpr int XH = 0, XL = BP, WH = 2 * BP, WL = 2 * BP + BC;
     constexpr int XJ = BP / 64, WJ = BC / 64;             // 16-row chunks per wavefront, operand plane and step
@@ -526,7 +532,7 @@ __global__ void __launch_bounds__(256, OCC) conv_np_mfma_kernel(NpConvParams prm
     static_assert(BP % 64 == 0 && BC % 64 == 0, "whole chunks for four wavefronts");
     constexpr int WP = BP / 2, WC = BC / 2;               // wavefront tile (2 x 2 wavefronts)
     constexpr int PT = WP / 32, CT = WC / 32;
-    static_assert(PT * CT == 4 || (PT * CT == 2 && OCC == 2), "twelve accumulator tiles per wavefront, or six with two workgroups per compute unit");
+    static_assert(PT * CT == 4 || (PT * CT == 2 && OCC >= 2), "twelve accumulator tiles per wavefront, or six with two workgroups per compute unit");
 
     extern __shared__ uint4 lds[];
     const NpConvArgs &a = prm.a;
@@ -681,7 +687,7 @@ __global__ void __launch_bounds__(256, OCC) conv_np_mfma_kernel(NpConvParams prm
         if (i < nitems) issue(i);
     if (nitems > 0) {
         // step 0 has landed when at most the loads of steps 1 and 2 are outstanding
-        if (nitems > 2) wait_loads<2 * LPW>();
+        if (NSTAGES > 2 && nitems > 2) wait_loads<(NSTAGES - 1) * LPW>();
         else if (nitems > 1) wait_loads<LPW>();
         else wait_loads<0>();
         ring_barrier();
@@ -696,7 +702,7 @@ __global__ void __launch_bounds__(256, OCC) conv_np_mfma_kernel(NpConvParams prm
         __builtin_amdgcn_sched_barrier(0);
         if (has_next) {
             // loads younger than those of step it+1: those of step it+2 (step it+3 is issued below)
-            if (it + 2 < nitems) wait_loads<LPW>();
+            if (NSTAGES > 2 && it + 2 < nitems) wait_loads<(NSTAGES - 2) * LPW>();
             else wait_loads<0>();
             ring_barrier();
             read_half(f0, 0, next);
@@ -763,7 +769,7 @@ __global__ void __launch_bounds__(256, OCC) conv_np_mfma_kernel(NpConvParams prm
     }
 }
 
-template <int BP, int BC, int OCC = 1>
+template <int BP, int BC, int OCC = 1, int NSTAGES = 3>
 hipError_t launch_np_mfma(const NpConvArgs &a, hipStream_t st)
 {
     NpConvParams prm;
@@ -780,11 +786,11 @@ hipError_t launch_np_mfma(const NpConvArgs &a, hipStream_t st)
     prm.div_tc = make_fastdiv(prm.tiles_c);
     const long long tiles = ((M + BP - 1) / BP) * prm.tiles_c;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    constexpr size_t lds_bytes = (size_t)3 * (2 * BP + 2 * BC) * 64;
+    constexpr size_t lds_bytes = (size_t)NSTAGES * (2 * BP + 2 * BC) * 64;
     static_assert(lds_bytes * OCC <= (size_t)kLdsBytes, "three stages fit");
-    static const hipError_t attr = hipFuncSetAttribute((const void *)conv_np_mfma_kernel<BP, BC, OCC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    static const hipError_t attr = hipFuncSetAttribute((const void *)conv_np_mfma_kernel<BP, BC, OCC, NSTAGES>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (attr != hipSuccess) return attr;
-    conv_np_mfma_kernel<BP, BC, OCC><<<(unsigned)tiles, 256, lds_bytes, st>>>(prm);
+    conv_np_mfma_kernel<BP, BC, OCC, NSTAGES><<<(unsigned)tiles, 256, lds_bytes, st>>>(prm);
     return hipGetLastError();
 }
 
@@ -806,12 +812,13 @@ bool conv_np_mfma_supports(const NpConvArgs &a)
 
 hipError_t launch_conv_np_mfma(const NpConvArgs &a, hipStream_t st)
 {
-    // Short reductions (at most four 64-byte steps: 1 x 1 layers with up to 256 input channels) spend their time on the
-    // latency of the first loads and on the epilogue: half-size wavefront tiles leave room for a second workgroup per
-    // compute unit, which runs its matrix instructions and loads under the other's epilogue.
-    if ((long long)a.R * a.S * a.C <= 4 * kStepBytes) return launch_np_mfma<128, 64, 2>(a, st);
-    if (a.K <= 64) return launch_np_mfma<256, 64>(a, st);
-    return launch_np_mfma<128, 128>(a, st);
+    // Tiles of 128 pixels x 64 channels with 64 x 32 per wavefront (six accumulator tiles, 160 registers) leave room for
+    // several workgroups per compute unit, so that one workgroup's matrix instructions and loads run under another's
+    // epilogue - worth more on every layer shape measured than the larger tiles' fewer LDS reads per matrix
+    // instruction.  Up to 36 steps (all but the 3 x 3 x 512 layers): three workgroups with a two-stage ring; longer
+    // reductions: two workgroups with three stages.
+    if ((long long)a.R * a.S * a.C <= 36 * kStepBytes) return launch_np_mfma<128, 64, 3, 2>(a, st);
+    return launch_np_mfma<128, 64, 2, 3>(a, st);
 }
 
 hipError_t launch_conv_np_direct(const NpConvArgs &a, hipStream_t st)
@@ -858,7 +865,7 @@ hipError_t launch_pool_np(const int8_t *xh, const int8_t *xl, uint8_t *y, int8_t
 
 hipError_t launch_stem_pack_x(const int8_t *x, int8_t *y, int N, int H, int W, int C, int pad, int Hs, int Qs, hipStream_t st)
 {
-    stem_pack_x_kernel<<<grid_for((size_t)N * Hs * Qs * 16), 256, 0, st>>>(x, y, N, H, W, C, pad, Hs, Qs);
+    stem_pack_x_kernel<<<grid_for((size_t)N * Hs * Qs * 4), 256, 0, st>>>(x, y, N, H, W, C, pad, Hs, Qs);
     return hipGetLastError();
 }
 

@@ -354,7 +354,7 @@ dfq_status dfq_stem_pack_x(const int8_t *x, int8_t *y, int N, int H, int W, int 
     const int P = out_extent(H, pad, R, 2), Q = out_extent(W, pad, S, 2);
     if (P < 1 || Q < 1) return DFQ_ESHAPE;
     if (N == 0) return DFQ_OK;
-    if (!x || !y || ((uintptr_t)y & 3)) return DFQ_EINVAL;
+    if (!x || !y || ((uintptr_t)y & 15)) return DFQ_EINVAL;
     const int Hs = P + 3;                   // rows of the packed tensor: output rows plus the 4-row window minus one
     if (overlaps(x, (size_t)N * H * W * C, y, (size_t)N * Hs * Q * 64)) return DFQ_EINVAL;
     return from_hip(launch_stem_pack_x(x, y, N, H, W, C, pad, Hs, Q, (hipStream_t)stream));
