@@ -253,13 +253,14 @@ def bench_net_np(args):
         d = by_fn.setdefault(fn.__name__, dict(calls=0, us=0.0))
         d["calls"] += 1
         d["us"] = round(d["us"] + us, 1)
-        if fn.__name__ == "dfq_conv_np":
+        if fn.__name__ in ("dfq_conv_np", "dfq_conv_np_add"):
             nd = node[name]
             o = 2.0 * node_macs(net, nd) * args.batch
             layers.append(dict(layer=name, us=round(us, 1), tops=round(o / us / 1e6, 1), int8_matrix_tops=round(4 * o / us / 1e6, 1)))
     macs_step = net.macs_per_image() * args.batch
     tops = 2 * macs_step / (ms_per_step * 1e-3) / 1e12
-    conv_us = by_fn["dfq_conv_np"]["us"]
+    conv_us = by_fn["dfq_conv_np"]["us"] + by_fn.get("dfq_conv_np_add", dict(us=0.0))["us"]
+    n_conv = by_fn["dfq_conv_np"]["calls"] + by_fn.get("dfq_conv_np_add", dict(calls=0))["calls"]
 
     cpu, parity_checked = None, None
     if args.cpu_sample > 0:
@@ -285,7 +286,7 @@ def bench_net_np(args):
         "config": {"workload": "configs[4]'s network on (8, 4) codes: ResNet-50-shaped, 224x224x3, batch %d, scales from a single-batch "
                                "calibration on %d images" % (args.batch, args.calib), "global_batch": args.batch},
         "images_per_s": round(args.batch / (ms_per_step * 1e-3), 1),
-        "roofline": {"bound": "mfma", "kernel": "conv_np_mfma_kernel: the %d convolution launches of a pass" % by_fn["dfq_conv_np"]["calls"],
+        "roofline": {"bound": "mfma", "kernel": "conv_np_mfma_kernel: the %d convolution launches of a pass (%d of them with the residual add in the epilogue)" % (n_conv, len(plan.fused)),
                      "achieved": round(4 * 2 * macs_step / conv_us / 1e6, 1), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(4 * 2 * macs_step / conv_us / 1e6 / INT8_MFMA_PEAK_TOPS, 4),
                      "note": "int8 matrix operations executed (four per product of Eq. 6) over the summed event intervals of the convolution calls",

@@ -327,6 +327,18 @@ dfq_status dfq_fmt_from_absmax_i32_channels(const uint32_t *m, int K, int32_t fr
 dfq_status dfq_eltwise_np(const int8_t *ah, const int8_t *al, int frac_a, const int8_t *bh, const int8_t *bl, int frac_b, uint8_t *y,
                           int8_t *yh, int8_t *yl, int frac_y, int p_y, size_t n, int relu, dfq_stream stream);
 
+/* Join fusion on (8, p >= 4) codes (Sec. 3: the add that follows a layer is taken where the layer's result is produced):
+ * the bytes dfq_conv_np (output scale frac_mid, ReLU relu_mid, format (8, p)) followed by dfq_eltwise_np (that result and
+ * the tensor oh/ol at frac_other, output at frac_y in (8, p), ReLU relu_out on the sum) would leave in yh/yl - both
+ * conversions are carried out, the layer's own result is never stored.  oh, ol: [N,P,Q,K] digit planes, 16-byte aligned,
+ * must not overlap the outputs.  Matrix-core form only: DFQ_EUNSUPPORTED where dfq_conv_np_variant(DFQ_CONV_MFMA) is, for
+ * frac_x + frac_w - frac_mid outside [7, 36] and for max(frac_mid, frac_other) - frac_y outside [0, 31]; the caller then
+ * issues the two calls.  All DEVICE. */
+dfq_status dfq_conv_np_add(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int32_t *b, const int8_t *oh,
+                           const int8_t *ol, int8_t *yh, int8_t *yl, int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
+                           int groups, int frac_x, int frac_w, int frac_mid, int relu_mid, int frac_other, int frac_y, int p, int relu_out,
+                           dfq_stream stream);
+
 /* Calibration of a layer on (8, p >= 4) codes (Sec. 3: the output threshold is taken on the exact accumulator, after the
  * ReLU where the layer has one, before anything is rounded): the largest |sum + bias| of Eq. 6 over all outputs of the
  * layer (negative sums count as 0 when relu is set), as a 64-bit integer at the scale 2^-(frac_x + frac_w), written to

@@ -28,7 +28,7 @@ EXPORTS = [
     "dfq_absmax_f32", "dfq_absmax_i32", "dfq_fmt_from_absmax_f32", "dfq_fmt_from_absmax_i32", "dfq_hist_shift", "dfq_fmt_from_absmax_i32_channels",
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
     "dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32", "dfq_conv_q_add_lazy", "dfq_eltwise_np",
-    "dfq_conv_np_absmax", "dfq_eltwise_np_absmax", "dfq_np_frac_from_absmax_u64", "dfq_pool_np", "dfq_stem_pack_x", "dfq_stem_pack_w",
+    "dfq_conv_np_absmax", "dfq_eltwise_np_absmax", "dfq_np_frac_from_absmax_u64", "dfq_pool_np", "dfq_stem_pack_x", "dfq_stem_pack_w", "dfq_conv_np_add",
 ]
 
 
@@ -97,6 +97,8 @@ def lib():
     L.dfq_conv_np_variant.argtypes = [i32] + [vp] * 8 + [i32] * 15 + [vp]
     L.dfq_eltwise_np.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, sz, i32, vp]
     L.dfq_eltwise_np.restype = i32
+    L.dfq_conv_np_add.argtypes = [vp] * 9 + [i32] * 18 + [vp]
+    L.dfq_conv_np_add.restype = i32
     L.dfq_conv_np_absmax.argtypes = [vp] * 6 + [i32] * 11 + [vp]
     L.dfq_conv_np_absmax.restype = i32
     L.dfq_eltwise_np_absmax.argtypes = [vp, vp, i32, vp, vp, i32, vp, sz, i32, vp]
@@ -245,6 +247,26 @@ def eltwise_np(ah: torch.Tensor, al: torch.Tensor, f_a: int, bh: torch.Tensor, b
     _check(lib().dfq_eltwise_np(_ptr(ah), _ptr(al), int(f_a), _ptr(bh), _ptr(bl), int(f_b), _ptr(y), _ptr(yh), _ptr(yl), int(f_y), int(p_y),
                                 ah.numel(), int(bool(relu)), _stream(stream)), "dfq_eltwise_np")
     return y, yh, yl
+
+
+def conv_np_add(xh, xl, wh, wl, b, oh, ol, f_x: int, f_w: int, f_mid: int, relu_mid: bool, f_other: int, f_y: int, p: int, relu_out: bool,
+                stride: int = 1, pad: int = 0, groups: int = 1, out=None, stream=None):
+    """Convolution on (8, p) digit planes with the element-wise add behind it taken in its epilogue (see dfq_conv_np_add).
+    Returns (yh, yl); raises DfqError(EUNSUPPORTED) where the library has no fused kernel for the case."""
+    for t, name in ((xh, "xh"), (xl, "xl"), (wh, "wh"), (wl, "wl"), (oh, "oh"), (ol, "ol")):
+        _dev(t, torch.int8, name)
+    if b is not None:
+        _dev(b, torch.int32, "b")
+    N, H, W, Cc = xh.shape
+    K, R, S, Cg = wh.shape
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    if Cg * groups != Cc or xl.shape != xh.shape or wl.shape != wh.shape or tuple(oh.shape) != (N, P, Q, K) or ol.shape != oh.shape:
+        raise ValueError("operand shapes do not match")
+    yh, yl = out if out is not None else (torch.empty_like(oh), torch.empty_like(oh))
+    _check(lib().dfq_conv_np_add(_ptr(xh), _ptr(xl), _ptr(wh), _ptr(wl), _ptr(b), _ptr(oh), _ptr(ol), _ptr(yh), _ptr(yl), N, H, W, Cc, K, R, S,
+                                 int(stride), int(pad), int(groups), int(f_x), int(f_w), int(f_mid), int(bool(relu_mid)), int(f_other), int(f_y),
+                                 int(p), int(bool(relu_out)), _stream(stream)), "dfq_conv_np_add")
+    return yh, yl
 
 
 def _read_u64(t: torch.Tensor) -> int:

@@ -93,6 +93,18 @@ __device__ __forceinline__ int np_round_fast(int T, int c, const NpFast &f)
     return q << (eb - f.base_b);
 }
 
+// The conversion of a 32-bit sum t (|t| < 2^30) times 2^-shift, 0 <= shift <= 31, by the same device: (double)t is exact.
+__device__ __forceinline__ int np_round_fast_i32(int t, const NpFast &f)
+{
+    const double x = (double)t;
+    const unsigned e_b = __builtin_amdgcn_ubfe((unsigned)__double2hiint(x), 20u, 11u);
+    unsigned eb;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(eb) : "v"(e_b), "s"(f.base_b), "v"(f.top_b));
+    const double M = __hiloint2double((int)((eb << 20) + f.m_const), 0);
+    const int q = __double2loint(x + M);
+    return q << (eb - f.base_b);
+}
+
 // byte E of w = low byte of (v >> sh), of (v & msk), of (x - y): the operation writes its result's low byte straight
 // into the packed word (sub-dword destination select), the other bytes are kept
 template <int E>
@@ -180,6 +192,28 @@ __device__ __forceinline__ void np_finish_one(int A, int Cc, int Bm, const NpRou
         put_ashr<E>(whi, 6u, t);
         put_sub<E>(wlo, (unsigned)beta, (unsigned)t & ~63u);
         if constexpr (CODES) wc |= np_code_of(beta, p_y) << (8 * E);
+    }
+}
+
+// The fused join: the layer's result (32-bit rounding, clamp with the layer's own ReLU as the lower bound), aligned with
+// the other operand's integer 64 h + l, summed, converted a second time and split into digits.
+template <bool RELU_OUT, int E>
+__device__ __forceinline__ void np_finish_add_one(int A, int Cc, int Bm, uint32_t oh4, uint32_t ol4, int lo1, int sa, int sb, const NpFast &fr,
+                                                  const NpFast &fr2, uint32_t &whi, uint32_t &wlo)
+{
+    int beta = np_round_fast((A << 6) + Bm, Cc, fr);
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(beta) : "v"(beta), "s"(lo1), "v"(fr.bmax));
+    const int other = 64 * byte_of(oh4, E) + byte_of(ol4, E);
+    const int t = (beta << sa) + (other << sb);
+    int r = np_round_fast_i32(t, fr2);
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(r), "s"(RELU_OUT ? 0 : -fr2.bmax), "v"(fr2.bmax));
+    if constexpr (RELU_OUT) {
+        put_shr<E>(whi, 6u, (unsigned)r);
+        put_and<E>(wlo, 63u, (unsigned)r);
+    } else {
+        const int u = r + ((r >> 31) & 63);
+        put_ashr<E>(whi, 6u, u);
+        put_sub<E>(wlo, (unsigned)r, (unsigned)u & ~63u);
     }
 }
 
@@ -521,7 +555,7 @@ struct NpConvParams {
     FastDiv div_q, div_p, div_tc;
 };
 
-template <int BP, int BC, int OCC, int NSTAGES>
+template <int BP, int BC, int OCC, int NSTAGES, bool ADD>
 __global__ void __launch_bounds__(256, OCC) conv_np_mfma_kernel(NpConvParams prm)
 {
     static_assert(NSTAGES == 2 || NSTAGES == 3, "ring depth");
@@ -754,6 +788,53 @@ __global__ void __launch_bounds__(256, OCC) conv_np_mfma_kernel(NpConvParams prm
     };
     using T_ = std::true_type;
     using F_ = std::false_type;
+    if constexpr (ADD) {
+        const NpFast fr2 = {(unsigned)(1023 + a.p_y + a.add_shift), (unsigned)(1023 + a.add_shift + 11), ((unsigned)(52 - a.p_y) << 20) | 0x80000u,
+                            a.beta_max};
+        const int lo1 = a.relu ? 0 : -a.beta_max;
+        auto finish_add = [&](auto relu_out) __attribute__((always_inline)) {
+            constexpr bool RELU_OUT = decltype(relu_out)::value;
+#pragma unroll
+            for (int c = 0; c < CT; c++) {
+                const int kc = ct * BC + wc0 + c * 32 + 16 * lh;
+                if (kc >= a.K) continue;
+                // the other operand of all pixel tiles first, so that the loads are in flight together
+                uint4 vh[PT], vl[PT];
+#pragma unroll
+                for (int p = 0; p < PT; p++) {
+                    const int m = min(pt * BP + wp0 + p * 32 + l32, prm.M - 1);
+                    const size_t o = (size_t)m * a.K + kc;
+                    vh[p] = *(const uint4 *)(a.oh + o);
+                    vl[p] = *(const uint4 *)(a.ol + o);
+                }
+#pragma unroll
+                for (int p = 0; p < PT; p++) {
+                    const int m = pt * BP + wp0 + p * 32 + l32;
+                    const uint32_t h4[4] = {vh[p].x, vh[p].y, vh[p].z, vh[p].w}, l4[4] = {vl[p].x, vl[p].y, vl[p].z, vl[p].w};
+                    uint32_t oh[4], ol[4];
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; r4++) {
+                        uint32_t whi = 0, wlo = 0;
+                        const int r = 4 * r4;
+                        np_finish_add_one<RELU_OUT, 0>(accA[c][p][r + 0], accC[c][p][r + 0], accB[c][p][r + 0], h4[r4], l4[r4], lo1, a.add_sa, a.add_sb, fr, fr2, whi, wlo);
+                        np_finish_add_one<RELU_OUT, 1>(accA[c][p][r + 1], accC[c][p][r + 1], accB[c][p][r + 1], h4[r4], l4[r4], lo1, a.add_sa, a.add_sb, fr, fr2, whi, wlo);
+                        np_finish_add_one<RELU_OUT, 2>(accA[c][p][r + 2], accC[c][p][r + 2], accB[c][p][r + 2], h4[r4], l4[r4], lo1, a.add_sa, a.add_sb, fr, fr2, whi, wlo);
+                        np_finish_add_one<RELU_OUT, 3>(accA[c][p][r + 3], accC[c][p][r + 3], accB[c][p][r + 3], h4[r4], l4[r4], lo1, a.add_sa, a.add_sb, fr, fr2, whi, wlo);
+                        oh[r4] = whi;
+                        ol[r4] = wlo;
+                    }
+                    if (m < prm.M) {
+                        const size_t o = (size_t)m * a.K + kc;
+                        *(uint4 *)(a.yh + o) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+                        *(uint4 *)(a.yl + o) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+                    }
+                }
+            }
+        };
+        if (a.add_relu) finish_add(T_{});
+        else finish_add(F_{});
+        return;
+    }
     if (a.shift >= 7 && a.shift <= 36) {
         if (a.y) {
             if (a.relu) finish(T_{}, T_{}, T_{});
@@ -769,7 +850,7 @@ __global__ void __launch_bounds__(256, OCC) conv_np_mfma_kernel(NpConvParams prm
     }
 }
 
-template <int BP, int BC, int OCC = 1, int NSTAGES = 3>
+template <int BP, int BC, int OCC = 1, int NSTAGES = 3, bool ADD = false>
 hipError_t launch_np_mfma(const NpConvArgs &a, hipStream_t st)
 {
     NpConvParams prm;
@@ -788,9 +869,9 @@ hipError_t launch_np_mfma(const NpConvArgs &a, hipStream_t st)
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     constexpr size_t lds_bytes = (size_t)NSTAGES * (2 * BP + 2 * BC) * 64;
     static_assert(lds_bytes * OCC <= (size_t)kLdsBytes, "three stages fit");
-    static const hipError_t attr = hipFuncSetAttribute((const void *)conv_np_mfma_kernel<BP, BC, OCC, NSTAGES>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    static const hipError_t attr = hipFuncSetAttribute((const void *)conv_np_mfma_kernel<BP, BC, OCC, NSTAGES, ADD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (attr != hipSuccess) return attr;
-    conv_np_mfma_kernel<BP, BC, OCC, NSTAGES><<<(unsigned)tiles, 256, lds_bytes, st>>>(prm);
+    conv_np_mfma_kernel<BP, BC, OCC, NSTAGES, ADD><<<(unsigned)tiles, 256, lds_bytes, st>>>(prm);
     return hipGetLastError();
 }
 
@@ -817,6 +898,10 @@ hipError_t launch_conv_np_mfma(const NpConvArgs &a, hipStream_t st)
     // epilogue - worth more on every layer shape measured than the larger tiles' fewer LDS reads per matrix
     // instruction.  Up to 36 steps (all but the 3 x 3 x 512 layers): three workgroups with a two-stage ring; longer
     // reductions: two workgroups with three stages.
+    if (a.oh) {
+        if ((long long)a.R * a.S * a.C <= 36 * kStepBytes) return launch_np_mfma<128, 64, 3, 2, true>(a, st);
+        return launch_np_mfma<128, 64, 2, 3, true>(a, st);
+    }
     if ((long long)a.R * a.S * a.C <= 36 * kStepBytes) return launch_np_mfma<128, 64, 3, 2>(a, st);
     return launch_np_mfma<128, 64, 2, 3>(a, st);
 }

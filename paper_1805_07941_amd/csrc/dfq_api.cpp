@@ -264,7 +264,7 @@ dfq_status dfq_conv_np_variant(dfq_conv_variant variant, const int8_t *xh, const
                                int stride, int pad, int groups, int frac_x, int frac_w, int frac_y, int p_y, int relu,
                                dfq_stream stream)
 {
-    NpConvArgs a{xh, xl, wh, wl, b, y, yh, yl, N, H, W, C, K, R, S, stride, pad, groups, 0, 0, 0, p_y, 0, relu ? 1 : 0, nullptr};
+    NpConvArgs a{xh, xl, wh, wl, b, y, yh, yl, N, H, W, C, K, R, S, stride, pad, groups, 0, 0, 0, p_y, 0, relu ? 1 : 0, nullptr, nullptr, 0, 0, 0, 0, nullptr};
     const dfq_status st = check_conv_np(a, frac_x, frac_w, frac_y);
     if (st != DFQ_OK) return st;
     if (N == 0) return DFQ_OK;
@@ -277,12 +277,38 @@ dfq_status dfq_conv_np_variant(dfq_conv_variant variant, const int8_t *xh, const
     return DFQ_EINVAL;
 }
 
+dfq_status dfq_conv_np_add(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int32_t *b, const int8_t *oh,
+                           const int8_t *ol, int8_t *yh, int8_t *yl, int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
+                           int groups, int frac_x, int frac_w, int frac_mid, int relu_mid, int frac_other, int frac_y, int p, int relu_out,
+                           dfq_stream stream)
+{
+    NpConvArgs a{xh, xl, wh, wl, b, nullptr, yh, yl, N, H, W, C, K, R, S, stride, pad, groups, 0, 0, 0, p, 0, relu_mid ? 1 : 0,
+                 oh, ol, 0, 0, 0, relu_out ? 1 : 0, nullptr};
+    if (!yh || !yl) return DFQ_EINVAL;
+    const dfq_status st = check_conv_np(a, frac_x, frac_w, frac_mid);
+    if (st != DFQ_OK) return st;
+    if (frac_other < -32 || frac_other > 32 || frac_y < -32 || frac_y > 32) return DFQ_EFMT;
+    const int F = frac_mid > frac_other ? frac_mid : frac_other;
+    if (F - frac_mid > 18 || F - frac_other > 18) return DFQ_EFMT;              // Eq. 12, as for dfq_eltwise_np
+    if (N == 0) return DFQ_OK;
+    if (!oh || !ol) return DFQ_EINVAL;
+    const size_t ny = (size_t)N * a.P * a.Q * K;
+    if (overlaps(yh, ny, oh, ny) || overlaps(yh, ny, ol, ny) || overlaps(yl, ny, oh, ny) || overlaps(yl, ny, ol, ny)) return DFQ_EINVAL;
+    a.add_sa = F - frac_mid;
+    a.add_sb = F - frac_other;
+    a.add_shift = F - frac_y;
+    // the fused epilogue covers the 32-bit rounding of the layer's own result and a final factor of at most 1
+    if (!conv_np_mfma_supports(a) || a.shift < 7 || a.shift > 36 || a.add_shift < 0 || a.add_shift > 31 || (((uintptr_t)oh | (uintptr_t)ol) & 15))
+        return DFQ_EUNSUPPORTED;
+    return from_hip(launch_conv_np_mfma(a, (hipStream_t)stream));
+}
+
 dfq_status dfq_conv_np_absmax(const int8_t *xh, const int8_t *xl, const int8_t *wh, const int8_t *wl, const int32_t *b, uint64_t *amax_dev,
                               int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups, int relu, dfq_stream stream)
 {
     if (!amax_dev || ((uintptr_t)amax_dev & 7)) return DFQ_EINVAL;
     // (the format arguments of the shared checks are placeholders: nothing is converted or stored)
-    NpConvArgs a{xh, xl, wh, wl, b, nullptr, nullptr, nullptr, N, H, W, C, K, R, S, stride, pad, groups, 0, 0, 0, 4, 0, relu ? 1 : 0, nullptr};
+    NpConvArgs a{xh, xl, wh, wl, b, nullptr, nullptr, nullptr, N, H, W, C, K, R, S, stride, pad, groups, 0, 0, 0, 4, 0, relu ? 1 : 0, nullptr, nullptr, 0, 0, 0, 0, nullptr};
     const dfq_status st = check_conv_np(a, 0, 0, 0, false);
     if (st != DFQ_OK) return st;
     a.amax = reinterpret_cast<unsigned long long *>(amax_dev);

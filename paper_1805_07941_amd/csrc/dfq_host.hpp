@@ -53,6 +53,12 @@ struct NpConvArgs {
     int p_y;                       // significand bits of the output format (8, p_y)
     int beta_max;                  // Eq. 5 for the output format
     int relu;
+    // fused join (matrix-core form only): the layer's own result, rounded to (8, p_y) at frac_mid, is added to a second
+    // tensor as dfq_eltwise_np would add them, and only the sum is stored
+    const int8_t *oh, *ol;         // the other operand's digit planes [N,P,Q,K], null: no join
+    int add_sa, add_sb;            // left shifts of the layer's result and of the other operand to the finer scale
+    int add_shift;                 // that scale's fractional length minus the output's, 0..31
+    int add_relu;                  // ReLU on the sum
     unsigned long long *amax;      // calibration: receives max |sum + bias| (after ReLU if relu) by atomic max; direct form only
 };
 

@@ -110,8 +110,12 @@ class NpPlan:
     """A calibrated network bound to preallocated device buffers for one batch size: a pass is a fixed sequence of
     library calls with no allocation and no host synchronization (so it can be replayed from a HIP graph)."""
 
-    def __init__(self, net, qz: QuantizedNp, batch: int, device="cuda:0"):
+    def __init__(self, net, qz: QuantizedNp, batch: int, device="cuda:0", fuse: bool = True):
+        """fuse: an element-wise add one of whose sources is the result of a convolution that nothing else reads runs in
+        that convolution's epilogue (dfq_conv_np_add: the same two conversions, the convolution's own tensor is never
+        stored) where the library's fused kernel covers the case; the call then stands at the add's place in the order."""
         self.net, self.qz, self.batch, self.device = net, qz, batch, device
+        self.fused = self._fusable_pairs() if fuse else {}                      # add node name -> (conv node, other source)
         i8 = dict(dtype=torch.int8, device=device)
         H, W, Cc = net.shapes[net.input_name]
         self.codes_in = torch.empty((batch, H, W, Cc), dtype=torch.uint8, device=device)
@@ -133,6 +137,34 @@ class NpPlan:
         self.logits = self._logits_all[:, :P * Q * K] if Kp != K else self._logits_all
         self._calls, self._calls_key, self._graph = None, None, None
 
+    def _fusable_pairs(self):
+        net, qz = self.net, self.qz
+        readers = {}
+        for nd in net.nodes:
+            for s_ in nd.srcs:
+                readers[s_] = readers.get(s_, 0) + 1
+        producer = {nd.dst: nd for nd in net.nodes}
+        pairs = {}
+        for e in net.nodes:
+            if e.op != "eltwise" or e.srcs[0] == e.srcs[1]:
+                continue
+            for i, s_ in enumerate(e.srcs):
+                c = producer.get(s_)
+                if c is None or c.op != "conv" or readers[s_] != 1 or s_ == net.output_name or packs(net, c):
+                    continue
+                other = e.srcs[1 - i]
+                # what dfq_conv_np_add states it covers: the matrix-core form, a downscale of the layer's own result by
+                # 2^7 .. 2^36, a final factor of at most 1
+                Cc = net.shapes[c.srcs[0]][2]
+                K = qz.w[c.name][0].shape[0]
+                mid_shift = qz.frac[c.srcs[0]] + qz.w_frac[c.name] - qz.frac[s_]
+                F = max(qz.frac[s_], qz.frac[other])
+                if (c.groups == 1 and Cc % 64 == 0 and K % 16 == 0 and c.R * c.R * Cc <= 13000 and 7 <= mid_shift <= 36
+                        and 0 <= F - qz.frac[e.dst] <= 31 and F - qz.frac[s_] <= 18 and F - qz.frac[other] <= 18):
+                    pairs[e.name] = (c, other)
+                    break
+        return pairs
+
     def _build_calls(self, x: torch.Tensor):
         L = B.lib()
         net, qz, t, p = self.net, self.qz, self.buf, self.qz.p
@@ -142,9 +174,24 @@ class NpPlan:
         calls.append((L.dfq_quantize_np, (x.data_ptr(), ptr(self.codes_in), x.numel(), 8, p, qz.frac[net.input_name])))
         calls.append((L.dfq_np_digits, (ptr(self.codes_in), x.numel(), p, ptr(xin[0]), ptr(xin[1]))))
         names += [None, None]
+        fused_convs = {c.name for c, _ in self.fused.values()}
         for nd in net.nodes:
             yh, yl = t[nd.dst]
             codes = self.codes_out if nd.dst == net.output_name else None
+            if nd.op == "conv" and nd.name in fused_convs:
+                continue                                            # runs at its add's place
+            if nd.op == "eltwise" and nd.name in self.fused and codes is None:
+                c, other = self.fused[nd.name]
+                src = c.srcs[0]
+                xh, xl = t[src]
+                N, H, W, Cc = xh.shape
+                wh, wl = qz.w[c.name]
+                oh, ol = t[other]
+                calls.append((L.dfq_conv_np_add, (ptr(xh), ptr(xl), ptr(wh), ptr(wl), ptr(qz.b[c.name]), ptr(oh), ptr(ol), ptr(yh), ptr(yl),
+                                                  N, H, W, Cc, wh.shape[0], c.R, c.R, c.stride, c.pad, c.groups, qz.frac[src], qz.w_frac[c.name],
+                                                  qz.frac[c.dst], int(c.relu), qz.frac[other], qz.frac[nd.dst], p, int(nd.relu))))
+                names.append(c.name)
+                continue
             if nd.op == "conv":
                 src = nd.srcs[0]
                 xh, xl = t[src]

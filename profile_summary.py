@@ -6,6 +6,7 @@
     python profile_summary.py counters <out.txt> <counter_collection.csv> ... --cmd "<command>" [--cmd ...]
     python profile_summary.py layers <out.txt> <bench_layers.json> ... --cmd "<command>" [--cmd ...]
     python profile_summary.py variants <out.txt> <bench.log> ... --cmd "<command>" [--cmd ...]
+    python profile_summary.py npnet <out.txt> <bench.log> --cmd "<command>"
 
 `stats`: per-kernel call count and durations of the whole run, and the kernels of the last full
 pass (between the last two launches of the input quantization).
@@ -191,6 +192,22 @@ def cmd_variants(a):
     open(a.out, "w").write("\n".join(out) + "\n")
 
 
+def cmd_npnet(a):
+    import json
+    d = json.loads([x for x in open(a.log) if x.startswith("{")][-1])
+    out = ["bench.py line of the network pass on (8, 4) codes", "command:", "  " + a.cmd[0], "", d["metric"],
+           f"  {d['ms_per_step']:.4f} ms per step, {d['value']:.1f} {d['unit']}, {d.get('images_per_s', 0):.0f} images/s; launch: {d['launch']}",
+           f"  parity_checked: {d.get('parity_checked')}", f"  cpu_baseline: {d.get('cpu_baseline')}",
+           f"  roofline: {d['roofline']['achieved']} {d['roofline']['unit']} = {d['roofline']['frac']} of {d['roofline']['peak']} ({d['roofline']['note']})",
+           "", "library calls of one pass (event intervals on the launch stream, launched call by call):"]
+    for k, v in d["calls"].items():
+        out.append(f"  {k:24s} {v['calls']:3d} calls {v['us']:9.1f} us")
+    out += ["", f"  {'layer':12s} {'us':>7s} {'TOPS':>8s} {'int8 matrix TOPS':>17s}"]
+    for r in d["conv_layers"]:
+        out.append(f"  {r['layer']:12s} {r['us']:7.1f} {r['tops']:8.1f} {r['int8_matrix_tops']:17.1f}")
+    open(a.out, "w").write("\n".join(out) + "\n")
+
+
 def main():
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="what", required=True)
@@ -209,8 +226,10 @@ def main():
     l.add_argument("out"); l.add_argument("jsons", nargs="+"); l.add_argument("--cmd", action="append", required=True)
     v = sub.add_parser("variants")
     v.add_argument("out"); v.add_argument("logs", nargs="+"); v.add_argument("--cmd", action="append", required=True)
+    n = sub.add_parser("npnet")
+    n.add_argument("out"); n.add_argument("log"); n.add_argument("--cmd", action="append", required=True)
     a = ap.parse_args()
-    {"stats": cmd_stats, "traffic": cmd_traffic, "counters": cmd_counters, "layers": cmd_layers, "variants": cmd_variants}[a.what](a)
+    {"npnet": cmd_npnet, "stats": cmd_stats, "traffic": cmd_traffic, "counters": cmd_counters, "layers": cmd_layers, "variants": cmd_variants}[a.what](a)
 
 
 if __name__ == "__main__":

@@ -217,6 +217,23 @@ def test_np_network_calls_reject_bad_arguments_before_launching(B):
     assert L.dfq_stem_pack_w(1 << 20, 2 << 20, 64, 7, 7, 5, None) == B.ESHAPE
 
 
+def test_conv_np_add_rejects_bad_arguments_before_launching(B):
+    L = B.lib()
+
+    def call(xh=1 << 20, xl=2 << 20, wh=3 << 20, wl=4 << 20, b=None, oh=5 << 20, ol=6 << 20, yh=7 << 20, yl=8 << 20, N=1, H=8, W=8, Cc=64, K=64,
+             R=1, S=1, stride=1, pad=0, groups=1, fx=10, fw=12, fm=10, relu_mid=0, fo=10, fy=9, p=4, relu_out=1):
+        return L.dfq_conv_np_add(xh, xl, wh, wl, b, oh, ol, yh, yl, N, H, W, Cc, K, R, S, stride, pad, groups, fx, fw, fm, relu_mid, fo, fy, p,
+                                 relu_out, None)
+
+    assert call(yh=None) == B.EINVAL and call(oh=None) == B.EINVAL and call(xl=None) == B.EINVAL
+    assert call(yh=5 << 20) == B.EINVAL and call(yl=1 << 20) == B.EINVAL                 # output over the other operand / the input
+    assert call(stride=0) == B.ESHAPE and call(p=3) == B.EFMT and call(fo=33) == B.EFMT
+    assert call(fo=29) == B.EFMT                                                         # a 19-bit alignment
+    assert call(fw=2) == B.EUNSUPPORTED and call(fy=11) == B.EUNSUPPORTED and call(Cc=48) == B.EUNSUPPORTED
+    assert call(oh=(5 << 20) + 4) == B.EUNSUPPORTED
+    assert call(N=0) == B.OK
+
+
 def test_np_frac_from_absmax_matches_the_oracle(B):
     import oracle.npfmt as F
     rng = np.random.default_rng(9)

@@ -132,15 +132,20 @@ def test_small_resnet_calibration_and_inference(B, p):
     _compare_all(net, qz, t, oq, ot, p)
     x2 = np.ascontiguousarray(np.roll(x, 1, 0) * np.float32(0.8))
     oi = NN.infer(net, oq, x2)
-    plan = npnet.NpPlan(net, qz, batch=2)
     xd = dev(x2)
-    got = host(plan.run(xd))
-    torch.cuda.synchronize()
-    got = host(plan.logits)
-    for name, codes in oi.items():
-        K = codes.shape[3]
-        assert np.array_equal(beta_of(plan.buf[name])[..., :K], NC.decode_tensor(codes, 8, p)), name
-    assert np.array_equal(got, NN.logits(net, oq, oi))
+    for fuse in (False, True):
+        plan = npnet.NpPlan(net, qz, batch=2, fuse=fuse)
+        assert (len(plan.fused) >= 12) if fuse else (len(plan.fused) == 0)
+        got = host(plan.run(xd))
+        torch.cuda.synchronize()
+        got = host(plan.logits)
+        never_stored = {c.dst for c, _ in plan.fused.values()}
+        for name, codes in oi.items():
+            if name in never_stored:
+                continue
+            K = codes.shape[3]
+            assert np.array_equal(beta_of(plan.buf[name])[..., :K], NC.decode_tensor(codes, 8, p)), (name, fuse)
+        assert np.array_equal(got, NN.logits(net, oq, oi))
     # replayed from a graph, several times with eager work in between
     for rep in range(3):
         plan.logits.zero_()
@@ -166,8 +171,76 @@ def test_resnet50_np84_full_batch(B):
     pick = [0, 255]
     oi = NN.infer(net, oq, x[pick])
     assert np.array_equal(host(out)[pick], NN.logits(net, oq, oi))
+    assert len(plan.fused) == 16
+    never_stored = {c.dst for c, _ in plan.fused.values()}
     for name, codes in oi.items():
+        if name in never_stored:
+            continue
         K = codes.shape[3]
         got = 64 * host(plan.buf[name][0][pick]).astype(np.int64) + host(plan.buf[name][1][pick])
         assert np.array_equal(got[..., :K], NC.decode_tensor(codes, 8, 4)), name
     assert len(np.unique(host(out)[pick])) > 50
+
+
+ADD_CASES = [
+    # N, H, W, C, K, R, stride, pad, mid_shift, relu_mid, d_other (f_other - f_mid), add_shift, relu_out
+    (2, 9, 8, 64, 64, 1, 1, 0, 12, False, 0, 1, True),
+    (2, 9, 8, 64, 80, 1, 1, 0, 12, False, 2, 3, False),          # channel tail (80 = 64 + 16), other operand finer
+    (1, 13, 13, 128, 256, 1, 1, 0, 14, False, -3, 2, True),      # other operand coarser
+    (3, 7, 7, 64, 64, 3, 1, 1, 15, True, 0, 0, False),           # ReLU on the layer, none on the sum, no final downscale
+    (1, 6, 6, 256, 128, 1, 1, 0, 7, False, 0, 1, True),          # smallest downscale of the 32-bit rounding
+    (1, 6, 6, 512, 64, 3, 1, 1, 36, False, 0, 0, True),          # largest
+    (1, 5, 5, 64, 64, 1, 1, 0, 12, False, 18, 20, False),        # widest alignment of the layer's result
+    (1, 5, 5, 64, 64, 1, 1, 0, 12, False, -18, 5, True),         # and of the other operand
+    (1, 5, 5, 64, 64, 1, 1, 0, 12, False, 0, 31, False),         # everything rounds to zero
+    (2, 14, 14, 64, 64, 3, 2, 1, 13, False, 1, 2, True),         # strided
+    (1, 40, 40, 64, 64, 3, 1, 1, 13, False, 0, 1, True),         # 72-step ring variant is taken from C = 512 only; many tiles here
+    (1, 4, 4, 512, 64, 3, 1, 1, 20, False, 0, 1, True),          # three-stage ring (72 steps)
+]
+
+
+@pytest.mark.parametrize("case", ADD_CASES)
+def test_conv_np_add_equals_convolution_then_add(B, case):
+    import zlib
+    N, H, W, C, K, R, stride, pad, mid_shift, relu_mid, d_other, add_shift, relu_out = case
+    rng = np.random.default_rng(zlib.crc32(repr(case).encode()))
+    sigma = 0.25
+    x = gaussian_codes(rng, (N, H, W, C), 4, sigma, relu=True) if mid_shift < 30 else np.full((N, H, W, C), 0x7f, np.uint8)
+    w = gaussian_codes(rng, (K, R, R, C), 4, sigma) if mid_shift < 30 else rng.choice(np.array([0x7f, 0xff], np.uint8), (K, R, R, C), p=[0.7, 0.3])
+    b = rng.integers(-3000, 3000, K).astype(np.int32)
+    P, Q = NC.out_hw(H, W, R, R, stride, pad)
+    other = rng.integers(0, 256, (N, P, Q, K)).astype(np.uint8)
+    f_mid = 4
+    f_x = min(mid_shift, 20)
+    f_w = mid_shift + f_mid - f_x
+    f_other = f_mid + d_other
+    f_y = max(f_mid, f_other) - add_shift
+    mid, mid_beta, _ = NC.conv_np(x, (8, 4), w, (8, 4), b, f_x + f_w - f_mid, (8, 4), stride, pad, 1, relu_mid)
+    ry, rbeta, _ = NC.eltwise_np(mid, (8, 4), f_mid, other, (8, 4), f_other, (8, 4), f_y, relu_out)
+    yh, yl = B.conv_np_add(*planes(B, x, 4), *planes(B, w, 4), dev(b), *planes(B, other, 4), f_x, f_w, f_mid, relu_mid, f_other, f_y, 4, relu_out,
+                           stride, pad)
+    torch.cuda.synchronize()
+    got = beta_of((yh, yl))
+    bad = np.argwhere(got != rbeta)
+    assert bad.size == 0, (len(bad), bad[:4], got[tuple(bad[0])], rbeta[tuple(bad[0])])
+    eh, el = digits_of(rbeta)
+    assert np.array_equal(host(yh), eh) and np.array_equal(host(yl), el)
+    if add_shift < 20 and mid_shift < 30 and abs(d_other) < 10:
+        assert len(np.unique(mid_beta)) > 20 and len(np.unique(rbeta)) > 20
+
+
+def test_conv_np_add_declines_what_it_does_not_cover(B):
+    x = np.zeros((1, 4, 4, 64), np.uint8)
+    w = np.zeros((64, 1, 1, 64), np.uint8)
+    o = np.zeros((1, 4, 4, 64), np.uint8)
+    args = (*planes(B, x, 4), *planes(B, w, 4), None, *planes(B, o, 4))
+    # f_x, f_w, f_mid, f_other, f_y: a downscale of the layer's result by 2^2, by 2^37, and a final upscale
+    for f_x, f_w, f_mid, f_other, f_y in [(10, 2, 10, 10, 10), (10, 32, 5, 5, 5), (10, 12, 10, 10, 11)]:
+        with pytest.raises(B.DfqError) as e:
+            B.conv_np_add(*args, f_x, f_w, f_mid, False, f_other, f_y, 4, True)
+        assert e.value.status == B.EUNSUPPORTED
+    x48 = np.zeros((1, 4, 4, 48), np.uint8)
+    w48 = np.zeros((64, 1, 1, 48), np.uint8)
+    with pytest.raises(B.DfqError) as e:
+        B.conv_np_add(*planes(B, x48, 4), *planes(B, w48, 4), None, *planes(B, o, 4), 10, 12, 10, False, 10, 9, 4, True)
+    assert e.value.status == B.EUNSUPPORTED
