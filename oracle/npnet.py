@@ -15,8 +15,9 @@ every tensor - inputs, weights, activations - held as codes of ONE format (n, p)
 
 Concatenation, grouped layers with per-channel formats and the histogram search are not part of this oracle.
 
-End-to-end results have no pin outside this file except for the members of the family that are int8 ((8, 7)), where the
-whole procedure must reproduce the int8 network oracle tensor for tensor; each ingredient it calls is pinned separately.
+End-to-end results have no pin outside this file ("parity unpinned") except for the members of the family that are int8
+((8, 7)), where the whole procedure must reproduce the int8 network oracle tensor for tensor; each ingredient it calls is
+pinned separately.
 """
 from __future__ import annotations
 
