@@ -22,9 +22,12 @@
 // asked, the codes themselves.
 //
 // conv_np_mfma_kernel: implicit GEMM, one tile of BP pixels x BC channels per workgroup of four wavefronts, the
-// reduction axis in 64-byte steps through a ring of three LDS stages of 2 (BP + BC) rows filled by direct
-// global -> LDS loads three steps ahead; rows are 64 bytes with the 16-byte pieces XOR-swizzled as in the int8 kernels.
-// conv_np_direct_kernel: one output per lane, any geometry (groups, C not a multiple of 64).
+// reduction axis in 64-byte steps through a ring of two or three LDS stages of 2 (BP + BC) rows filled by direct
+// global -> LDS loads that many steps ahead; rows are 64 bytes with the 16-byte pieces XOR-swizzled as in the int8
+// kernels; two or three workgroups share a compute unit.  With ADD the element-wise add that follows the layer
+// (Eq. 10) runs in the epilogue.
+// conv_np_direct_kernel: one output per lane, any geometry (groups, C not a multiple of 64); also the calibration maxima.
+// Further down: the add, pooling and the first layer's space-to-depth packing on digit planes.
 #include <type_traits>
 
 #include "conv_ring.hpp"
