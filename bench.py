@@ -74,44 +74,45 @@ def bench_layers(args):
 
     dev = "cuda:0"
     rows = []
-    layer_set = wl.RESNET_3X3_SET if args.layer_set == "3x3" else wl.RESNET_LAYER_SET
+    layer_set = {"3x3": wl.RESNET_3X3_SET, "grouped": wl.GROUPED_SET}.get(args.layer_set, wl.RESNET_LAYER_SET)
     for i in range(len(layer_set)):
         L = wl.config1_layer(i, batch=args.batch, layer_set=layer_set)
         wf, bf = torch.from_numpy(L["w_float"]).to(dev), torch.from_numpy(L["b_float"]).to(dev)
-        f_in, pad = L["f_in"], L["pad"]
+        f_in, pad, stride, groups = L["f_in"], L["pad"], L["stride"], L["groups"]
         f_w = B.fmt_from_absmax_f32(float(B.absmax_f32(wf).cpu()[0]))
         w, b = B.quantize(wf, f_w), B.quantize_i32(bf, f_in + f_w)
         x0 = torch.from_numpy(L["x"]).to(dev)
-        _, acc = B.conv_q(x0[:8].contiguous(), w, b, f_in, f_w, 0, 1, pad, 1, True, want_y=False, want_acc=True)
+        _, acc = B.conv_q(x0[:8].contiguous(), w, b, f_in, f_w, 0, stride, pad, groups, True, want_y=False, want_acc=True)
         f_out = B.fmt_from_absmax_i32(B.absmax_i32_value(B.absmax_i32(acc, relu=True)), f_in + f_w)
         del acc
         nset = 4
         xs = [x0] + [x0.roll(k + 1, 0).contiguous() for k in range(nset - 1)]
         N, H, W, C = x0.shape
         K, R = w.shape[0], w.shape[1]
-        ys = [torch.empty((N, H, W, K), dtype=torch.int8, device=dev) for _ in range(nset)]
+        P, Q = B.conv_out_hw(H, W, R, R, stride, pad)
+        ys = [torch.empty((N, P, Q, K), dtype=torch.int8, device=dev) for _ in range(nset)]
         for k in range(3):
-            B.conv_q(xs[k % nset], w, b, f_in, f_w, f_out, 1, pad, 1, True, out=ys[k % nset])
+            B.conv_q(xs[k % nset], w, b, f_in, f_w, f_out, stride, pad, groups, True, out=ys[k % nset])
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         iters = args.steps
         e0.record()
         for k in range(iters):
-            B.conv_q(xs[k % nset], w, b, f_in, f_w, f_out, 1, pad, 1, True, out=ys[k % nset])
+            B.conv_q(xs[k % nset], w, b, f_in, f_w, f_out, stride, pad, groups, True, out=ys[k % nset])
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / iters
-        ops = 2.0 * N * H * W * K * R * R * C
+        ops = 2.0 * N * P * Q * K * R * R * (C // groups)
         by = x0.numel() + ys[0].numel() + w.numel() + 4 * K
         t_roof = max(ops / (INT8_MFMA_PEAK_TOPS * 1e12), by / (HBM_PEAK_GBS * 1e9)) * 1e3
-        rows.append(dict(layer=L["name"], shape="%dx%dx%d -> %d, %dx%d" % (H, W, C, K, R, R),
-                         kernel=B.CONV_VARIANT_NAMES[B.conv_q_select(N, H, W, C, K, R, R, 1, pad, 1)], us=round(ms * 1e3, 1),
+        rows.append(dict(layer=L["name"], shape="%dx%dx%d -> %d, %dx%d%s" % (H, W, C, K, R, R, "" if groups == 1 else " /%d g%d" % (stride, groups)),
+                         kernel=B.CONV_VARIANT_NAMES[B.conv_q_select(N, H, W, C, K, R, R, stride, pad, groups)], us=round(ms * 1e3, 1),
                          tops=round(ops / ms / 1e9, 1), gbs=round(by / ms / 1e6, 1),
                          pct_mfma_peak=round(100 * ops / ms / 1e9 / INT8_MFMA_PEAK_TOPS, 1),
                          pct_hbm_peak=round(100 * by / ms / 1e6 / HBM_PEAK_GBS, 1), pct_roofline=round(100 * t_roof / ms, 1)))
         del xs, ys, x0
-    what = "the four 3x3 shapes of the ResNet-50-shaped network" if args.layer_set == "3x3" else "configs[1]"
-    print(json.dumps({"metric": "int8 conv TOPS per dense layer of %s, standalone, b=%d" % (what, args.batch), "unit": "TOPS",
+    what = {"3x3": "the four 3x3 shapes of the ResNet-50-shaped network", "grouped": "grouped and depthwise shapes"}.get(args.layer_set, "configs[1]")
+    print(json.dumps({"metric": "int8 conv TOPS per layer of %s, standalone, b=%d" % (what, args.batch), "unit": "TOPS",
                       "n_gpus": 1, "dtype": "int8", "data": "synthetic", "buffers": "4 rotating sets per layer", "layers": rows}))
 
 
@@ -314,8 +315,8 @@ def main():
                     help="one weight format per output channel (dfq_conv_q_pc) instead of one per layer")
     ap.add_argument("--layers", action="store_true",
                     help="instead of the network pass: time the five dense layers of configs[1] on their own at --batch")
-    ap.add_argument("--layer-set", choices=["config1", "3x3"], default="config1",
-                    help="with --layers: the five layers of configs[1], or the four 3x3 shapes of the ResNet-50-shaped network")
+    ap.add_argument("--layer-set", choices=["config1", "3x3", "grouped"], default="config1",
+                    help="with --layers: the five layers of configs[1], the four 3x3 shapes of the ResNet-50-shaped network, or grouped and depthwise shapes")
     ap.add_argument("--np84", action="store_true",
                     help="the network pass on (8, 4) dynamic floating-point codes (npnet.NpPlan); with --layers: the dense layers alone (dfq_conv_np)")
     ap.add_argument("--no-np84", action="store_true", help="leave the (8, 4) pass out of the default line")

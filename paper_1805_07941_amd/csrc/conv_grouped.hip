@@ -136,6 +136,8 @@ bool conv_grouped_supports(const ConvArgs &a)
 
 hipError_t launch_conv_grouped(const ConvArgs &a, hipStream_t st)
 {
+    // whole groups inside blocks of 64 channels, lean epilogue: the matrix cores take the layer (conv_sg.hip)
+    if (conv_sg_supports(a)) return launch_conv_sg(a, st);
     GroupedParams prm;
     prm.a = a;
     prm.Cg = a.C / a.groups;

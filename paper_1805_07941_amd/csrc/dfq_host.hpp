@@ -96,6 +96,8 @@ bool conv_pw_supports(const ConvArgs &a);
 hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st);
 bool conv_grouped_supports(const ConvArgs &a);
 hipError_t launch_conv_grouped(const ConvArgs &a, hipStream_t st);
+bool conv_sg_supports(const ConvArgs &a);       // grouped layers the matrix-core form (blocks of 64 channels) takes
+hipError_t launch_conv_sg(const ConvArgs &a, hipStream_t st);
 bool conv_np_mfma_supports(const NpConvArgs &a);
 hipError_t launch_conv_np_mfma(const NpConvArgs &a, hipStream_t st);
 hipError_t launch_conv_np_direct(const NpConvArgs &a, hipStream_t st);

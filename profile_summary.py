@@ -168,9 +168,9 @@ def cmd_layers(a):
     for path in a.jsons:
         d = json.loads([x for x in open(path) if x.startswith("{")][-1])
         out += ["", d["metric"]]
-        out.append(f"  {'layer':20s} {'shape':28s} {'kernel':10s} {'us':>7s} {'TOPS':>8s} {'GB/s':>8s} {'%mfma':>6s} {'%hbm':>6s} {'%roof':>6s}")
+        out.append(f"  {'layer':20s} {'shape':34s} {'kernel':10s} {'us':>7s} {'TOPS':>8s} {'GB/s':>8s} {'%mfma':>6s} {'%hbm':>6s} {'%roof':>6s}")
         for r in d["layers"]:
-            out.append(f"  {r['layer']:20s} {r['shape']:28s} {r['kernel']:10s} {r['us']:7.1f} {r['tops']:8.1f} {r['gbs']:8.1f} "
+            out.append(f"  {r['layer']:20s} {r['shape']:34s} {r['kernel']:10s} {r['us']:7.1f} {r['tops']:8.1f} {r['gbs']:8.1f} "
                        f"{r['pct_mfma_peak']:6.1f} {r['pct_hbm_peak']:6.1f} {r['pct_roofline']:6.1f}")
     open(a.out, "w").write("\n".join(out) + "\n")
 

@@ -150,6 +150,12 @@ CONV_SHAPES = [
     (2, 13, 13, 96, 48, 1, 1, 1, 0, 12),         # grouped 1x1
     (1, 12, 10, 24, 36, 7, 7, 2, 3, 3),          # grouped 7x7 stride 2
     (1, 9, 9, 12, 8, 3, 3, 1, 1, 4),             # groups of three channels: direct kernel
+    # grouped layers whose groups fill blocks of 64 channels: the matrix-core form (zero-padded block-diagonal weights)
+    (2, 19, 17, 128, 128, 3, 3, 2, 1, 16),       # groups of 8, stride 2
+    (2, 13, 13, 128, 128, 1, 1, 1, 0, 32),       # 1x1, groups of 4: one step per tile
+    (1, 10, 10, 128, 128, 3, 3, 1, 1, 2),        # groups of 64: no padding zeros at all
+    (1, 9, 9, 64, 64, 2, 3, 1, 1, 4),            # groups of 16, even kernel height
+    (3, 29, 31, 192, 192, 3, 3, 1, 1, 24),       # three channel blocks, ragged last pixel tile
     (1, 33, 31, 16, 16, 3, 3, 1, 0, 1),          # no padding
     (1, 40, 40, 64, 256, 3, 3, 1, 1, 1),         # several tiles in both GEMM dimensions
     # unpadded 1x1 stride 1: the input-resident pointwise kernel (several pixel tiles, ragged last one)

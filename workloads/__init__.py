@@ -77,20 +77,35 @@ RESNET_3X3_SET = [
 ]
 
 
+# grouped and depthwise shapes (ResNeXt- and MobileNet-like), for the kernels that take layers without a dense contraction:
+# (name, H, C, K, R, groups, stride)
+GROUPED_SET = [
+    ("g32_56_128",      56, 128,  128,  3,  32, 1),
+    ("g32_28_256",      28, 256,  256,  3,  32, 1),
+    ("g64_56_256_s2",   56, 256,  256,  3,  64, 2),
+    ("dw_112_32",      112,  32,   32,  3,  32, 1),
+    ("dw_56_128",       56, 128,  128,  3, 128, 1),
+    ("dw_14_512",       14, 512,  512,  3, 512, 1),
+]
+
+
 def config1_layer(i: int, batch: int = 32, layer_set=None) -> dict:
     """Layer i of the set: int8 input at a per-layer f_in in {2..6}, float He-normal
     weights, float N(0, 0.1) bias; stride 1, pad R//2, ReLU.  The weight format,
     the integer bias and f_out are for each implementation to derive.
-    layer_set: RESNET_LAYER_SET (config 1, the default) or RESNET_3X3_SET (tensor indices from 100)."""
-    name, H, C, K, R = (layer_set or RESNET_LAYER_SET)[i]
-    base = 10 * i + (100 if layer_set is RESNET_3X3_SET else 0)
+    layer_set: RESNET_LAYER_SET (config 1, the default), RESNET_3X3_SET (tensor indices from 100) or GROUPED_SET (from 200,
+    with groups and stride per entry)."""
+    entry = (layer_set or RESNET_LAYER_SET)[i]
+    name, H, C, K, R = entry[:5]
+    groups, stride = (entry[5], entry[6]) if len(entry) > 5 else (1, 1)
+    base = 10 * i + (100 if layer_set is RESNET_3X3_SET else 200 if layer_set is GROUPED_SET else 0)
     f_in = int(_rng(1, base + 0).integers(2, 7))
     x = int8_activations(1, base + 1, (batch, H, H, C), f_in)
-    w = (_rng(1, base + 2).standard_normal((K, R, R, C), dtype=np.float32)
-         * np.float32(np.sqrt(2.0 / (R * R * C))))
+    w = (_rng(1, base + 2).standard_normal((K, R, R, C // groups), dtype=np.float32)
+         * np.float32(np.sqrt(2.0 / (R * R * (C // groups)))))
     b = _rng(1, base + 3).standard_normal((K,), dtype=np.float32) * np.float32(0.1)
-    return dict(name=name, x=x, w_float=w, b_float=b, f_in=f_in, stride=1, pad=R // 2,
-                groups=1, relu=1)
+    return dict(name=name, x=x, w_float=w, b_float=b, f_in=f_in, stride=stride, pad=R // 2,
+                groups=groups, relu=1)
 
 
 # --------------------------------------------------------------------------- #
