@@ -178,6 +178,8 @@ bool conv_depthwise_supports(const ConvArgs &a)
 
 hipError_t launch_conv_depthwise(const ConvArgs &a, hipStream_t st)
 {
+    // whole blocks of 64 channels, lean epilogue: the products go to the matrix cores (conv_dwm.hip)
+    if (conv_dwm_supports(a)) return launch_conv_dwm(a, st);
     if (a.stride == 1) return launch_dw<3, 3, 1, 4>(a, st);
     return launch_dw<3, 3, 2, 2>(a, st);
 }

@@ -1,0 +1,192 @@
+// Depthwise 3 x 3 quantized convolution (groups == C == K, C a multiple of 64) with the products on the int8 matrix cores.
+//
+// Every output channel sums nine products of its own input channel (Eq. 6 with nine terms): no contraction over
+// channels, and on the vector ALU the layer costs about 23 instructions per output - index arithmetic, byte transposes,
+// dot products, rounding - which, not memory, bounds it.  v_mfma_i32_16x16x64_i8 multiplies a 16 x 64 by a 64 x 16 matrix;
+// take 16 channels as the rows of the first and 16 neighbouring output pixels of an image row as the columns of the
+// second, and let the 64 entries of the reduction axis be 4 kernel taps x 16 channels: the second operand's lane
+// (pixel q, tap t) then supplies the 16 channel bytes of input pixel q + (offset of tap t) - a plain 16-byte LDS read - and
+// the first operand is diagonal in the channel, row c holding the weight of (channel c, tap t) at position 16 t + c and
+// zeros elsewhere.  Three such instructions (taps 0-3, 4-7, 8) give the nine-tap sums of 16 channels x 16 pixels, each
+// lane ending with four neighbouring channels of one pixel - one packed word of the output.  15 of 16 products are with
+// zeros, which the matrix pipe has to spare; what is left on the vector ALU is the read addresses, the rounding and the
+// stores, about a third of the instructions of the plain form.
+//
+// A workgroup of four wavefronts takes 8 output rows x 16 output columns x 64 channels of one image.  Its input patch
+// (with the kernel's halo; padding and everything outside the image arrive as zeros) is fetched once by direct
+// global -> LDS loads, one 64-byte row per input pixel with the 16-byte pieces XOR-swizzled by (row >> 2) & 3, so that 16
+// neighbouring pixels' reads of the same channel quarter fall into different banks.  The diagonal operands of all taps
+// stay in registers.  Epilogue as in the other kernels: bias as start value, ReLU, rounding shift, clamp (lean form only;
+// the launcher keeps the vector-ALU kernel for everything else).
+#include "conv_ring.hpp"
+
+namespace dfq {
+
+namespace {
+
+constexpr int kDwmTH = 8, kDwmTW = 16;
+
+struct DwmParams {
+    ConvArgs a;
+    int tiles_x, tiles_y, blocks_c;
+    unsigned x_bytes;
+    FastDiv div_bc, div_tx, div_ty;
+};
+
+template <int ST>
+__global__ void __launch_bounds__(256) conv_dwm_kernel(DwmParams prm)
+{
+    constexpr int TH = kDwmTH, TW = kDwmTW;
+    constexpr int IH = (TH - 1) * ST + 3, IW = (TW - 1) * ST + 3;      // input patch
+    constexpr int ROWS = IH * IW;                                      // one LDS row of 64 bytes per input pixel
+    constexpr int CHUNKS = (ROWS + 15) / 16;                           // 16 rows per wavefront-wide load
+    extern __shared__ uint4 lds[];
+    const ConvArgs &a = prm.a;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // workgroup -> (image, tile row, tile column, block of 64 channels), channel blocks fastest: neighbouring workgroups
+    // read neighbouring 64-byte segments of the same pixels
+    // (ids are dealt round-robin to the 8 XCDs; renumbered so that each XCD owns a contiguous range: the channel blocks
+    // of a patch and neighbouring patches then meet in one L2)
+    int t = blockIdx.x;
+    {
+        const int G = gridDim.x, per = G / 8, rem = G % 8, xcd = t % 8, idx = t / 8;
+        t = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+    }
+    int q1 = fastdiv(t, prm.div_bc);
+    const int cb = t - q1 * prm.blocks_c;
+    t = q1;
+    q1 = fastdiv(t, prm.div_tx);
+    const int ox0 = (t - q1 * prm.tiles_x) * TW;
+    t = q1;
+    const int n = fastdiv(t, prm.div_ty);
+    const int oy0 = (t - n * prm.tiles_y) * TH;
+
+    // ---- the input patch: lane l of a load supplies row l/4 of a 16-row chunk, physical piece l%4 = logical piece (l%4) ^ ((row>>2)&3)
+    {
+        const v4i x_rsrc = make_rsrc(a.x, prm.x_bytes);
+        const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char *)(char *)&lds[0];
+        const int lp = (lane & 3) ^ ((lane >> 4) & 3);
+        const int gy0 = oy0 * ST - a.pad, gx0 = ox0 * ST - a.pad;
+        for (int c = wave; c < CHUNKS; c += 4) {
+            const int j = 16 * c + (lane >> 2);
+            const int iy = j / IW, ix = j - iy * IW;
+            const int gy = gy0 + iy, gx = gx0 + ix;
+            const bool ok = j < ROWS && (unsigned)gy < (unsigned)a.H && (unsigned)gx < (unsigned)a.W;
+            const unsigned off = ok ? (unsigned)(((n * a.H + gy) * a.W + gx) * a.C + cb * 64 + lp * 16) : kOutOfRange;
+            load_piece_to_lds(off, x_rsrc, (unsigned)__builtin_amdgcn_readfirstlane((int)(lds_base + (unsigned)c * 1024u)));
+        }
+    }
+
+    // ---- per lane: pixel column l16, tap position lq within a group of four taps
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int wsel = l16 >> 2;         // which word of a first operand holds the lane's weight
+    // diagonal first operands: for tap group g and channel quarter cq the lane holds 16 bytes of row (channel) l16 at
+    // reduction positions 16 lq .. 16 lq + 15, i.e. tap 4 g + lq: the weight at byte l16, zeros elsewhere
+    v4i wd[3][4];
+    int roff[3];                       // row offset of the lane's tap inside the patch
+#pragma unroll
+    for (int g = 0; g < 3; g++) {
+        const int tap = 4 * g + lq;
+        const int tt = min(tap, 8);    // taps 9..11 do not exist: zero weights, any valid row
+        const int r = tt / 3, s = tt - 3 * r;
+        roff[g] = r * IW + s;
+#pragma unroll
+        for (int cq = 0; cq < 4; cq++) {
+            const int ch = cb * 64 + 16 * cq + l16;
+            const int wv = tap < 9 ? (int)(uint8_t)a.w[(size_t)ch * 9 + tap] : 0;
+            const int word = wv << (8 * (l16 & 3));
+#pragma unroll
+            for (int e = 0; e < 4; e++) wd[g][cq][e] = (e == wsel) ? word : 0;
+        }
+    }
+    // the lane's outputs: channels kc .. kc + 3 of every quarter, pixel column ox0 + l16
+    v4i bias[4];
+#pragma unroll
+    for (int cq = 0; cq < 4; cq++) {
+        const int kc = cb * 64 + 16 * cq + 4 * lq;
+        const int4 bv = a.b ? *(const int4 *)(a.b + kc) : make_int4(0, 0, 0, 0);
+        bias[cq][0] = bv.x;
+        bias[cq][1] = bv.y;
+        bias[cq][2] = bv.z;
+        bias[cq][3] = bv.w;
+    }
+    Requant rq;
+    rq.init(a.shift, a.relu);
+
+    wait_loads<0>();
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+
+    const v4i *rows = (const v4i *)lds;
+    for (int oyl = wave; oyl < TH; oyl += 4) {
+        const int oy = oy0 + oyl;
+        if (oy >= a.P) break;          // (uniform: the wavefront's row)
+        const int base = oyl * ST * IW + l16 * ST;
+        v4i acc[4];
+#pragma unroll
+        for (int cq = 0; cq < 4; cq++) acc[cq] = bias[cq];
+#pragma unroll
+        for (int g = 0; g < 3; g++) {
+            const int row = base + roff[g];
+            const int sw = (row >> 2) & 3;
+#pragma unroll
+            for (int cq = 0; cq < 4; cq++) {
+                const v4i xv = rows[row * kPieces + (cq ^ sw)];
+                acc[cq] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wd[g][cq], xv, acc[cq], 0, 0, 0);
+            }
+        }
+        // the lane's four packed words belong to four different 16-byte pieces of its pixel's 64 output bytes: exchanged
+        // through a 1 KB LDS slot of the wavefront, so that every lane stores one whole piece (16 pixels x 64 contiguous bytes)
+        uint32_t *slot = (uint32_t *)(lds + CHUNKS * 64) + wave * 256;
+#pragma unroll
+        for (int cq = 0; cq < 4; cq++) slot[l16 * 16 + 4 * cq + lq] = rq.fast_four(acc[cq][0], acc[cq][1], acc[cq][2], acc[cq][3]);
+        const uint4 piece = ((const uint4 *)slot)[lane];          // pixel lane / 4, piece lane % 4 (same wavefront: program order suffices)
+        const int px = ox0 + (lane >> 2);
+        if (px < a.Q) *(uint4 *)(a.y + ((size_t)(n * a.P + oy) * a.Q + px) * a.ldy + cb * 64 + 16 * (lane & 3)) = piece;
+    }
+}
+
+template <int ST>
+hipError_t launch_dwm(const DwmParams &prm, long long blocks, hipStream_t st)
+{
+    constexpr int IH = (kDwmTH - 1) * ST + 3, IW = (kDwmTW - 1) * ST + 3;
+    constexpr size_t lds_bytes = (size_t)((IH * IW + 15) / 16) * 16 * 64 + 4 * 1024;      // the patch and one exchange slot per wavefront
+    static_assert(lds_bytes <= 64 * 1024, "one patch");
+    conv_dwm_kernel<ST><<<(unsigned)blocks, 256, lds_bytes, st>>>(prm);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool conv_dwm_supports(const ConvArgs &a)
+{
+    if (a.groups != a.C || a.K != a.C || a.C % 64) return false;
+    if (a.R != 3 || a.S != 3 || (a.stride != 1 && a.stride != 2) || a.pad > 2) return false;
+    if (a.frac_w || a.add || a.acc_out || !a.y) return false;
+    if (a.shift < 0 || a.shift > 23) return false;                                   // the lean epilogue
+    if (a.Q <= 8 && a.N > 8) return false;      // rows of at most 8 outputs fill half a patch: the vector-ALU kernel is faster (7 x 7: 15 vs 17 us)
+    if ((a.ldy & 15) || ((uintptr_t)a.y & 15) || ((uintptr_t)a.x & 15) || (a.b && ((uintptr_t)a.b & 15))) return false;
+    if ((long long)a.N * a.H * a.W * a.C >= (1LL << 31) - (1 << 24)) return false;    // 31-bit byte offsets into the input
+    if ((long long)a.N * a.P * a.Q >= (1LL << 31)) return false;
+    const long long blocks = (long long)a.N * ((a.P + kDwmTH - 1) / kDwmTH) * ((a.Q + kDwmTW - 1) / kDwmTW) * (a.C / 64);
+    return blocks <= 0x7fffffffLL;
+}
+
+hipError_t launch_conv_dwm(const ConvArgs &a, hipStream_t st)
+{
+    DwmParams prm;
+    prm.a = a;
+    prm.tiles_x = (a.Q + kDwmTW - 1) / kDwmTW;
+    prm.tiles_y = (a.P + kDwmTH - 1) / kDwmTH;
+    prm.blocks_c = a.C / 64;
+    prm.x_bytes = (unsigned)((long long)a.N * a.H * a.W * a.C);
+    prm.div_bc = make_fastdiv(prm.blocks_c);
+    prm.div_tx = make_fastdiv(prm.tiles_x);
+    prm.div_ty = make_fastdiv(prm.tiles_y);
+    const long long blocks = (long long)a.N * prm.tiles_y * prm.tiles_x * prm.blocks_c;
+    return a.stride == 1 ? launch_dwm<1>(prm, blocks, st) : launch_dwm<2>(prm, blocks, st);
+}
+
+}  // namespace dfq

@@ -91,6 +91,8 @@ bool conv_mfma_fuses(const ConvArgs &a);     // a.add set: the dense kernel has 
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st);
 bool conv_depthwise_supports(const ConvArgs &a);
 hipError_t launch_conv_depthwise(const ConvArgs &a, hipStream_t st);
+bool conv_dwm_supports(const ConvArgs &a);      // depthwise layers the matrix-core form takes
+hipError_t launch_conv_dwm(const ConvArgs &a, hipStream_t st);
 bool conv_pw_geometry_ok(const ConvArgs &a);
 bool conv_pw_supports(const ConvArgs &a);
 hipError_t launch_conv_pw(const ConvArgs &a, hipStream_t st);

@@ -141,6 +141,14 @@ CONV_SHAPES = [
     (2, 10, 10, 32, 32, 3, 3, 1, 1, 32),         # depthwise
     (2, 11, 9, 64, 64, 3, 3, 2, 1, 64),          # depthwise stride 2
     (1, 9, 9, 24, 24, 3, 3, 1, 1, 24),           # depthwise, C % 16 != 0
+    # depthwise with whole blocks of 64 channels: the matrix-core form (patches of 8 x 16 outputs)
+    (2, 19, 37, 64, 64, 3, 3, 1, 1, 64),         # ragged patches in both directions
+    (1, 16, 16, 128, 128, 3, 3, 1, 1, 128),      # exactly two patch rows, one patch column, two channel blocks
+    (2, 21, 35, 128, 128, 3, 3, 2, 1, 128),      # stride 2
+    (3, 7, 7, 192, 192, 3, 3, 1, 1, 192),        # image smaller than a patch
+    (1, 14, 14, 64, 64, 3, 3, 2, 1, 64),         # stride 2, even size
+    (1, 12, 20, 64, 64, 3, 3, 1, 0, 64),         # no padding
+    (1, 1, 1, 64, 64, 3, 3, 1, 1, 64),           # one pixel: eight of nine taps are padding
     (1, 8, 8, 16, 32, 3, 3, 1, 1, 4),            # grouped
     (1, 6, 6, 20, 10, 2, 3, 1, 1, 5),            # grouped, odd kernel
     (2, 19, 17, 128, 128, 3, 3, 1, 1, 32),       # grouped: 32 groups of 4 channels, ragged row blocks
