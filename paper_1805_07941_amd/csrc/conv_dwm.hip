@@ -1,4 +1,4 @@
-// Depthwise 3 x 3 quantized convolution (groups == C == K, C a multiple of 64) with the products on the int8 matrix cores.
+// Depthwise 3 x 3 quantized convolution (groups == C == K, C a multiple of 32) with the products on the int8 matrix cores.
 //
 // Every output channel sums nine products of its own input channel (Eq. 6 with nine terms): no contraction over
 // channels, and on the vector ALU the layer costs about 23 instructions per output - index arithmetic, byte transposes,
@@ -12,10 +12,11 @@
 // zeros, which the matrix pipe has to spare; what is left on the vector ALU is the read addresses, the rounding and the
 // stores, about a third of the instructions of the plain form.
 //
-// A workgroup of four wavefronts takes 8 output rows x 16 output columns x 64 channels of one image.  Its input patch
-// (with the kernel's halo; padding and everything outside the image arrive as zeros) is fetched once by direct
-// global -> LDS loads, one 64-byte row per input pixel with the 16-byte pieces XOR-swizzled by (row >> 2) & 3, so that 16
-// neighbouring pixels' reads of the same channel quarter fall into different banks.  The diagonal operands of all taps
+// A workgroup of four wavefronts takes 8 output rows x 16 output columns x CB = 64 channels of one image (CB = 32 when C is
+// not a multiple of 64).  Its input patch (with the kernel's halo; padding and everything outside the image arrive as
+// zeros) is fetched once by direct global -> LDS loads, CB bytes per input pixel, laid out as 64-byte LDS rows with the
+// 16-byte pieces XOR-swizzled by (row >> 2) & 3, so that 16 neighbouring pixels' reads of the same channel quarter fall
+// into different banks.  The diagonal operands of all taps
 // stay in registers.  Epilogue as in the other kernels: bias as start value, ReLU, rounding shift, clamp (lean form only;
 // the launcher keeps the vector-ALU kernel for everything else).
 #include "conv_ring.hpp"
@@ -33,13 +34,14 @@ struct DwmParams {
     FastDiv div_bc, div_tx, div_ty;
 };
 
-template <int ST>
+template <int ST, int CB>
 __global__ void __launch_bounds__(256) conv_dwm_kernel(DwmParams prm)
 {
+    constexpr int NQ = CB / 16;                                        // 16-channel quarters (16-byte pieces) per pixel
     constexpr int TH = kDwmTH, TW = kDwmTW;
     constexpr int IH = (TH - 1) * ST + 3, IW = (TW - 1) * ST + 3;      // input patch
-    constexpr int ROWS = IH * IW;                                      // one LDS row of 64 bytes per input pixel
-    constexpr int CHUNKS = (ROWS + 15) / 16;                           // 16 rows per wavefront-wide load
+    constexpr int PIX = IH * IW;                                       // input pixels of the patch, CB bytes each
+    constexpr int CHUNKS = (PIX * NQ + 63) / 64;                       // 64 pieces (16 LDS rows) per wavefront-wide load
     extern __shared__ uint4 lds[];
     const ConvArgs &a = prm.a;
     const int tid = threadIdx.x;
@@ -71,11 +73,12 @@ __global__ void __launch_bounds__(256) conv_dwm_kernel(DwmParams prm)
         const int lp = (lane & 3) ^ ((lane >> 4) & 3);
         const int gy0 = oy0 * ST - a.pad, gx0 = ox0 * ST - a.pad;
         for (int c = wave; c < CHUNKS; c += 4) {
-            const int j = 16 * c + (lane >> 2);
+            const int piece = 4 * (16 * c + (lane >> 2)) + lp;          // linear index of the lane's logical piece: pixel * NQ + quarter
+            const int j = piece / NQ, qq = piece - j * NQ;
             const int iy = j / IW, ix = j - iy * IW;
             const int gy = gy0 + iy, gx = gx0 + ix;
-            const bool ok = j < ROWS && (unsigned)gy < (unsigned)a.H && (unsigned)gx < (unsigned)a.W;
-            const unsigned off = ok ? (unsigned)(((n * a.H + gy) * a.W + gx) * a.C + cb * 64 + lp * 16) : kOutOfRange;
+            const bool ok = j < PIX && (unsigned)gy < (unsigned)a.H && (unsigned)gx < (unsigned)a.W;
+            const unsigned off = ok ? (unsigned)(((n * a.H + gy) * a.W + gx) * a.C + cb * CB + qq * 16) : kOutOfRange;
             load_piece_to_lds(off, x_rsrc, (unsigned)__builtin_amdgcn_readfirstlane((int)(lds_base + (unsigned)c * 1024u)));
         }
     }
@@ -85,7 +88,7 @@ __global__ void __launch_bounds__(256) conv_dwm_kernel(DwmParams prm)
     const int wsel = l16 >> 2;         // which word of a first operand holds the lane's weight
     // diagonal first operands: for tap group g and channel quarter cq the lane holds 16 bytes of row (channel) l16 at
     // reduction positions 16 lq .. 16 lq + 15, i.e. tap 4 g + lq: the weight at byte l16, zeros elsewhere
-    v4i wd[3][4];
+    v4i wd[3][NQ];
     int roff[3];                       // row offset of the lane's tap inside the patch
 #pragma unroll
     for (int g = 0; g < 3; g++) {
@@ -94,8 +97,8 @@ __global__ void __launch_bounds__(256) conv_dwm_kernel(DwmParams prm)
         const int r = tt / 3, s = tt - 3 * r;
         roff[g] = r * IW + s;
 #pragma unroll
-        for (int cq = 0; cq < 4; cq++) {
-            const int ch = cb * 64 + 16 * cq + l16;
+        for (int cq = 0; cq < NQ; cq++) {
+            const int ch = cb * CB + 16 * cq + l16;
             const int wv = tap < 9 ? (int)(uint8_t)a.w[(size_t)ch * 9 + tap] : 0;
             const int word = wv << (8 * (l16 & 3));
 #pragma unroll
@@ -103,10 +106,10 @@ __global__ void __launch_bounds__(256) conv_dwm_kernel(DwmParams prm)
         }
     }
     // the lane's outputs: channels kc .. kc + 3 of every quarter, pixel column ox0 + l16
-    v4i bias[4];
+    v4i bias[NQ];
 #pragma unroll
-    for (int cq = 0; cq < 4; cq++) {
-        const int kc = cb * 64 + 16 * cq + 4 * lq;
+    for (int cq = 0; cq < NQ; cq++) {
+        const int kc = cb * CB + 16 * cq + 4 * lq;
         const int4 bv = a.b ? *(const int4 *)(a.b + kc) : make_int4(0, 0, 0, 0);
         bias[cq][0] = bv.x;
         bias[cq][1] = bv.y;
@@ -124,16 +127,16 @@ __global__ void __launch_bounds__(256) conv_dwm_kernel(DwmParams prm)
         const int oy = oy0 + oyl;
         if (oy >= a.P) break;          // (uniform: the wavefront's row)
         const int base = oyl * ST * IW + l16 * ST;
-        v4i acc[4];
+        v4i acc[NQ];
 #pragma unroll
-        for (int cq = 0; cq < 4; cq++) acc[cq] = bias[cq];
+        for (int cq = 0; cq < NQ; cq++) acc[cq] = bias[cq];
 #pragma unroll
         for (int g = 0; g < 3; g++) {
-            const int row = base + roff[g];
-            const int sw = (row >> 2) & 3;
+            const int p0 = (base + roff[g]) * NQ;                    // linear piece index of the pixel's first quarter
 #pragma unroll
-            for (int cq = 0; cq < 4; cq++) {
-                const v4i xv = rows[row * kPieces + (cq ^ sw)];
+            for (int cq = 0; cq < NQ; cq++) {
+                const int L = p0 + cq, row = L >> 2;
+                const v4i xv = rows[row * kPieces + ((L & 3) ^ ((row >> 2) & 3))];
                 acc[cq] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wd[g][cq], xv, acc[cq], 0, 0, 0);
             }
         }
@@ -141,20 +144,22 @@ __global__ void __launch_bounds__(256) conv_dwm_kernel(DwmParams prm)
         // through a 1 KB LDS slot of the wavefront, so that every lane stores one whole piece (16 pixels x 64 contiguous bytes)
         uint32_t *slot = (uint32_t *)(lds + CHUNKS * 64) + wave * 256;
 #pragma unroll
-        for (int cq = 0; cq < 4; cq++) slot[l16 * 16 + 4 * cq + lq] = rq.fast_four(acc[cq][0], acc[cq][1], acc[cq][2], acc[cq][3]);
-        const uint4 piece = ((const uint4 *)slot)[lane];          // pixel lane / 4, piece lane % 4 (same wavefront: program order suffices)
-        const int px = ox0 + (lane >> 2);
-        if (px < a.Q) *(uint4 *)(a.y + ((size_t)(n * a.P + oy) * a.Q + px) * a.ldy + cb * 64 + 16 * (lane & 3)) = piece;
+        for (int cq = 0; cq < NQ; cq++) slot[l16 * (CB / 4) + 4 * cq + lq] = rq.fast_four(acc[cq][0], acc[cq][1], acc[cq][2], acc[cq][3]);
+        if (lane < 16 * NQ) {
+            const uint4 piece = ((const uint4 *)slot)[lane];      // pixel lane / NQ, piece lane % NQ (same wavefront: program order suffices)
+            const int px = ox0 + lane / NQ;
+            if (px < a.Q) *(uint4 *)(a.y + ((size_t)(n * a.P + oy) * a.Q + px) * a.ldy + cb * CB + 16 * (lane % NQ)) = piece;
+        }
     }
 }
 
-template <int ST>
+template <int ST, int CB>
 hipError_t launch_dwm(const DwmParams &prm, long long blocks, hipStream_t st)
 {
     constexpr int IH = (kDwmTH - 1) * ST + 3, IW = (kDwmTW - 1) * ST + 3;
-    constexpr size_t lds_bytes = (size_t)((IH * IW + 15) / 16) * 16 * 64 + 4 * 1024;      // the patch and one exchange slot per wavefront
+    constexpr size_t lds_bytes = (size_t)((IH * IW * (CB / 16) + 63) / 64) * 1024 + 4 * 1024;      // the patch and one exchange slot per wavefront
     static_assert(lds_bytes <= 64 * 1024, "one patch");
-    conv_dwm_kernel<ST><<<(unsigned)blocks, 256, lds_bytes, st>>>(prm);
+    conv_dwm_kernel<ST, CB><<<(unsigned)blocks, 256, lds_bytes, st>>>(prm);
     return hipGetLastError();
 }
 
@@ -162,7 +167,7 @@ hipError_t launch_dwm(const DwmParams &prm, long long blocks, hipStream_t st)
 
 bool conv_dwm_supports(const ConvArgs &a)
 {
-    if (a.groups != a.C || a.K != a.C || a.C % 64) return false;
+    if (a.groups != a.C || a.K != a.C || a.C % 32) return false;
     if (a.R != 3 || a.S != 3 || (a.stride != 1 && a.stride != 2) || a.pad > 2) return false;
     if (a.frac_w || a.add || a.acc_out || !a.y) return false;
     if (a.shift < 0 || a.shift > 23) return false;                                   // the lean epilogue
@@ -170,7 +175,7 @@ bool conv_dwm_supports(const ConvArgs &a)
     if ((a.ldy & 15) || ((uintptr_t)a.y & 15) || ((uintptr_t)a.x & 15) || (a.b && ((uintptr_t)a.b & 15))) return false;
     if ((long long)a.N * a.H * a.W * a.C >= (1LL << 31) - (1 << 24)) return false;    // 31-bit byte offsets into the input
     if ((long long)a.N * a.P * a.Q >= (1LL << 31)) return false;
-    const long long blocks = (long long)a.N * ((a.P + kDwmTH - 1) / kDwmTH) * ((a.Q + kDwmTW - 1) / kDwmTW) * (a.C / 64);
+    const long long blocks = (long long)a.N * ((a.P + kDwmTH - 1) / kDwmTH) * ((a.Q + kDwmTW - 1) / kDwmTW) * (a.C / 32);
     return blocks <= 0x7fffffffLL;
 }
 
@@ -180,13 +185,15 @@ hipError_t launch_conv_dwm(const ConvArgs &a, hipStream_t st)
     prm.a = a;
     prm.tiles_x = (a.Q + kDwmTW - 1) / kDwmTW;
     prm.tiles_y = (a.P + kDwmTH - 1) / kDwmTH;
-    prm.blocks_c = a.C / 64;
+    const int CB = a.C % 64 ? 32 : 64;
+    prm.blocks_c = a.C / CB;
     prm.x_bytes = (unsigned)((long long)a.N * a.H * a.W * a.C);
     prm.div_bc = make_fastdiv(prm.blocks_c);
     prm.div_tx = make_fastdiv(prm.tiles_x);
     prm.div_ty = make_fastdiv(prm.tiles_y);
     const long long blocks = (long long)a.N * prm.tiles_y * prm.tiles_x * prm.blocks_c;
-    return a.stride == 1 ? launch_dwm<1>(prm, blocks, st) : launch_dwm<2>(prm, blocks, st);
+    if (CB == 64) return a.stride == 1 ? launch_dwm<1, 64>(prm, blocks, st) : launch_dwm<2, 64>(prm, blocks, st);
+    return a.stride == 1 ? launch_dwm<1, 32>(prm, blocks, st) : launch_dwm<2, 32>(prm, blocks, st);
 }
 
 }  // namespace dfq

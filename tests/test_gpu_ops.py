@@ -149,6 +149,8 @@ CONV_SHAPES = [
     (1, 14, 14, 64, 64, 3, 3, 2, 1, 64),         # stride 2, even size
     (1, 12, 20, 64, 64, 3, 3, 1, 0, 64),         # no padding
     (1, 1, 1, 64, 64, 3, 3, 1, 1, 64),           # one pixel: eight of nine taps are padding
+    (1, 40, 33, 32, 32, 3, 3, 1, 1, 32),         # 32 channels: two pixels per LDS row
+    (2, 21, 35, 96, 96, 3, 3, 2, 1, 96),         # three blocks of 32 channels, stride 2
     (1, 8, 8, 16, 32, 3, 3, 1, 1, 4),            # grouped
     (1, 6, 6, 20, 10, 2, 3, 1, 1, 5),            # grouped, odd kernel
     (2, 19, 17, 128, 128, 3, 3, 1, 1, 32),       # grouped: 32 groups of 4 channels, ragged row blocks
