@@ -163,6 +163,23 @@ dfq_status dfq_conv_q_add(const int8_t *x, const int8_t *w, const int32_t *b, co
                           int ldy, int ld_other, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_mid, int relu_mid,
                           dfq_fmt fmt_other, dfq_fmt fmt_out, int relu_out, dfq_stream stream);
 
+/* Convolution followed by max-pooling, in one kernel (Sec. 3: adjacent operations are merged; the paper
+ * names max-pool among the layers of the path).  The result is exactly that of
+ *     dfq_conv_q(x, w, b, t, NULL, ..., ldy = K, fmt_in, fmt_w, fmt_out, relu)   followed by
+ *     dfq_pool_q(t, y, DFQ_POOL_MAX, N, P, Q, K, pool_k, pool_stride, pool_pad, fmt_out, fmt_out)
+ * without the int8 tensor t ever being stored (the pooling keeps the convolution's format, so it
+ * rounds nothing).  y: device, int8 [N, PP, PQ, K] with ldy bytes between pixels (>= K, a multiple of
+ * 16, y 16-byte aligned), PP = floor((P + 2*pool_pad - pool_k)/pool_stride) + 1, PQ likewise; must not
+ * overlap x.  All other arguments as for dfq_conv_q.  Returns DFQ_EUNSUPPORTED - and does nothing -
+ * when no fused kernel covers the call (the caller then issues the two calls above).  A fused kernel
+ * exists for first layers: C == 3, stride 2, groups == 1, R in {3, 7}, S + (pad & 1) <= 8, pad <= 4,
+ * K in {32, 64}, W % 4 == 0, W <= 256, P and Q even, Q <= 122, x 4-byte aligned, a rescale shift in
+ * [0, 23], followed by a 3x3 / stride 2 / pad 1 pooling. */
+dfq_status dfq_conv_q_maxpool(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y,
+                              int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                              int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu,
+                              int pool_k, int pool_stride, int pool_pad, dfq_stream stream);
+
 /* Convolution followed by an element-wise add with ONE rounding (Sec. 3 wants a value thresholded only when the
  * datapath can carry it no further): the convolution's accumulator (Eq. 6 with bias, at fmt_in.frac + fmt_w.frac;
  * it gets no format of its own and no ReLU) and the code of `other` brought to that scale by the exact factor

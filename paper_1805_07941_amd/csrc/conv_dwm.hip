@@ -143,6 +143,7 @@ __global__ void __launch_bounds__(256) conv_dwm_kernel(DwmParams prm)
         // the lane's four packed words belong to four different 16-byte pieces of its pixel's 64 output bytes: exchanged
         // through a 1 KB LDS slot of the wavefront, so that every lane stores one whole piece (16 pixels x 64 contiguous bytes)
         uint32_t *slot = (uint32_t *)(lds + CHUNKS * 64) + wave * 256;
+        settle_accumulators<NQ>(&acc[0]);
 #pragma unroll
         for (int cq = 0; cq < NQ; cq++) slot[l16 * (CB / 4) + 4 * cq + lq] = rq.fast_four(acc[cq][0], acc[cq][1], acc[cq][2], acc[cq][3]);
         if (lane < 16 * NQ) {

@@ -10,6 +10,21 @@ namespace dfq {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
+// The epilogue forms below read the accumulators with instructions inside inline assembly.  The compiler's hazard
+// pass inserts the wait states a vector instruction needs behind a matrix instruction that writes its operand (up to
+// 19 for the 16-pass int8 forms) only for instructions it can see, so a kernel calls this once between the last
+// matrix instruction of a tile and the tile's epilogue: every accumulator passes through a statement that is ordered
+// behind the wait, and the wait behind the statements that follow the matrix instructions.
+template <int N, typename Acc>
+__device__ __forceinline__ void settle_accumulators(Acc *acc)
+{
+#pragma unroll
+    for (int i = 1; i < N; i++) asm volatile("" : "+v"(acc[i]));
+    asm volatile("s_nop 15\n\ts_nop 3" : "+v"(acc[0]));
+#pragma unroll
+    for (int i = 1; i < N; i++) asm volatile("" : "+v"(acc[i]));
+}
+
 // Per-launch constants of the requantization.  For 0 <= shift <= 23 the fast form is used:
 // the sum is first clamped to +-127 * 2^shift (anything beyond saturates to +-127 anyway; with
 // ReLU the lower bound is 0), which makes  (v + 2^(shift-1) - 1 + bit_shift(v)) >> shift

@@ -342,6 +342,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_mfma_kernel(
         if (++c_step == nsteps) {
             // ---- epilogue of this tile: lane holds, per (c, p), channels kc..kc+15 of pixel m
             const int m0 = fastdiv(c_tile, prm.div_tc) * BP;
+            settle_accumulators<CT * PT>(&acc[0][0]);
             if (!GENERAL) {
                 const unsigned tile_off = (unsigned)(m0 * a.ldy);
                 v4u other[FUSE ? CT * PT : 1];

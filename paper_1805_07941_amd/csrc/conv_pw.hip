@@ -319,6 +319,7 @@ __global__ void __launch_bounds__(WAVES_P * WAVES_C * 64, OCC) conv_pw_kernel(Pw
     auto finish_item = [&]() __attribute__((always_inline)) {
         ep_hist = (ep_hist << 1) & kHistMask;
         if (++c_step == nsteps) {
+            settle_accumulators<CT * PT>(&acc[0][0]);
             const unsigned tile_off = (unsigned)(c_pt * BP * a.ldy + c_ct * BC);
             if constexpr (ROWIO) {
                 v4i *slot = (v4i *)(io_lds + (FUSE ? io_par * kIoSlotBytes : 0));

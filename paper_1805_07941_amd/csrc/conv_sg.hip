@@ -184,6 +184,7 @@ __global__ void __launch_bounds__(256, OCC) conv_sg_kernel(SgParams prm)
     // ---- epilogue: register r of a lane belongs to channel kc + r of pixel m
     Requant rq;
     rq.init(a.shift, a.relu);
+    settle_accumulators<PT>(&acc[0]);
 #pragma unroll
     for (int p = 0; p < PT; p++) {
         const int m = pt * BP + wp0 + p * 32 + l32;

@@ -153,6 +153,7 @@ __global__ void __launch_bounds__(kThreads, 2) conv_smallc_kernel(SmallCParams p
             }
         }
 
+        settle_accumulators<CT * 2>(&acc[0][0]);
 #pragma unroll
         for (int c = 0; c < CT; c++) {
             const int kc = k0 + c * 32 + 16 * lh;
@@ -364,6 +365,7 @@ __global__ void __launch_bounds__(kThreads, 2) conv_smallc_rows_kernel(SmallCRow
         }
 
         const int mbase = tile * kTilePixels + wave * 64;
+        settle_accumulators<CT * 2>(&acc[0][0]);
 #pragma unroll
         for (int c = 0; c < CT; c++) {
             const int kc = k0 + c * 32 + 16 * lh;

@@ -205,6 +205,8 @@ class Plan:
         self.lazy = bool(lazy_joins)
         # conv node index -> add node index
         self.fused: Dict[int, int] = (self._lazy_pairs() if lazy_joins else self._fusable_pairs()) if fuse else {}
+        if fuse:
+            self.fused.update(self._pool_pairs())                            # conv node index -> max-pool node index
         self.slice_of: Dict[str, tuple] = self._direct_concat_branches() if fuse else {}   # tensor -> (joined tensor, channel offset)
         self.buf: Dict[str, torch.Tensor] = {}
         H, W, Cc = net.shapes[net.input_name]
@@ -257,6 +259,23 @@ class Plan:
                     pairs[j - 2] = j
                     continue
             if ok:
+                pairs[j - 1] = j
+        return pairs
+
+    def _pool_pairs(self) -> Dict[int, int]:
+        """Convolution nodes directly followed by a 3x3 / 2 / pad 1 max-pooling that is the only reader of their
+        result and keeps its format (one weight format per layer): candidates for dfq_conv_q_maxpool."""
+        net, qz = self.net, self.qz
+        readers: Dict[str, int] = {}
+        for nd in net.nodes:
+            for s in nd.srcs:
+                readers[s] = readers.get(s, 0) + 1
+        pairs = {}
+        for j in range(1, len(net.nodes)):
+            e, c = net.nodes[j], net.nodes[j - 1]
+            if (e.op == "maxpool" and (e.R, e.stride, e.pad) == (3, 2, 1) and c.op == "conv" and e.srcs[0] == c.dst
+                    and readers.get(c.dst, 0) == 1 and c.dst != net.output_name and c.groups == 1
+                    and c.name not in qz.w_frac_dev and qz.frac[c.dst] == qz.frac[e.dst]):
                 pairs[j - 1] = j
         return pairs
 
@@ -397,10 +416,31 @@ class Plan:
             nd = net.nodes[idx]
             if idx in fused_adds:
                 continue
-            if nd.op == "conv" and idx in self.fused:
+            partner = net.nodes[self.fused[idx]] if idx in self.fused else None
+            if nd.op == "conv" and partner is not None and partner.op == "maxpool":
+                # one call for the convolution and the max-pooling behind it, probed like the fused add below
+                src = nd.srcs[0]
+                N, H, W, Cc = t[src].shape
+                K = nd.K
+                fn = L.dfq_conv_q_maxpool
+                args = (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(), t[partner.dst].data_ptr(), N, H, W, Cc,
+                        K, nd.R, nd.R, nd.stride, nd.pad, nd.groups, K, f(qz.frac[src]), f(qz.w_frac[nd.name]), f(qz.frac[nd.dst]),
+                        int(nd.relu), partner.R, partner.stride, partner.pad)
+                rc = fn(*args, B._stream(None))
+                if rc == B.OK:
+                    calls.append((fn, args))
+                    names.append(nd.name)
+                    fused_adds.add(self.fused[idx])
+                    continue
+                if rc != B.EUNSUPPORTED:
+                    raise B.DfqError(rc, "dfq_conv_q_maxpool")
+                if nd.dst not in t:
+                    P, Q, Kd = net.shapes[nd.dst]
+                    t[nd.dst] = torch.empty((self.batch, P, Q, Kd), dtype=torch.int8, device=self.device)
+            elif nd.op == "conv" and partner is not None:
                 # one call for the convolution and the add behind it; probed once here, outside any
                 # capture: where no fused kernel covers the call, the two calls are issued instead
-                add = net.nodes[self.fused[idx]]
+                add = partner
                 other = add.srcs[0] if add.srcs[1] == nd.dst else add.srcs[1]
                 src = nd.srcs[0]
                 N, H, W, Cc = t[src].shape

@@ -684,3 +684,55 @@ def test_fused_add_alignment_and_shift_edges(B, sa, sb, add_shift):
         got = B.conv_q_pc_add(xd, wd, bd, od, f_in, dev(f_wk), (int(f_wk.min()), int(f_wk.max())), f_mid, relu_mid, f_other,
                               f_out, relu_out)
         assert got is not None and np.array_equal(host(got), ref), (sa, sb, add_shift, relu_mid, relu_out, "per channel")
+
+
+# ---------------------------------------------------------------------------------------- #
+# first layers (3 channels, stride 2) on the strip kernel, alone and with the max-pooling fused
+STEM_SHAPES = [
+    # N  H    W    K   R  S  pad
+    (2, 64, 64, 64, 7, 7, 3),        # two column blocks of the plain kernel, one of the pooling kernel; two strips per image
+    (3, 224, 224, 64, 7, 7, 3),      # seven column blocks (plain), four pooled column blocks
+    (2, 58, 96, 64, 7, 7, 3),        # 29 output rows: the last step is ragged; no fused pooling for an odd row count
+    (2, 60, 96, 64, 7, 7, 3),        # 30 output rows = 15 pooled rows: the last step holds one; two pooled column blocks
+    (2, 224, 224, 32, 3, 3, 1),      # 3x3 first layer, 32 channels
+    (1, 66, 64, 32, 3, 3, 1),        # 33 output rows
+    (1, 68, 72, 32, 3, 3, 1),        # 36 output columns: 18 pooled columns, the second block mostly empty
+    (2, 64, 64, 64, 7, 5, 2),        # even padding: taps start at an even input column; 31 output rows
+    (5, 32, 32, 64, 3, 7, 3),        # one column block, strips of one or two steps
+    (1, 40, 244, 64, 7, 7, 3),       # 61 pooled columns: the widest image the pooling kernel takes
+]
+
+
+@pytest.mark.parametrize("shape", STEM_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_stem_kernel_alone_and_with_max_pool(B, shape):
+    N, H, W, K, R, S, pad = shape
+    rng = np.random.default_rng(abs(hash(shape)) % (2 ** 31))
+    x = rng.integers(-128, 128, (N, H, W, 3)).astype(np.int8)
+    w = rng.integers(-128, 128, (K, R, S, 3)).astype(np.int8)
+    b = rng.integers(-2 ** 16, 2 ** 16, (K,)).astype(np.int32)
+    xd, bd = dev(x), dev(b)
+    P, Q = (H + 2 * pad - R) // 2 + 1, (W + 2 * pad - S) // 2 + 1
+    fused_expected = P % 2 == 0 and Q % 2 == 0 and Q // 2 <= 61
+    # shifts 13, 9, 0 (small weights), 23; with and without ReLU (without it the pooling sees negative values)
+    cases = [(4, 7, -2, 1, w, True), (4, 7, 2, 0, w, True), (3, 3, 6, 1, np.sign(w).astype(np.int8), False), (12, 12, 1, 0, w, True)]
+    for f_in, f_w, f_out, relu, wv, bias in cases:
+        wdv = dev(wv)
+        y_ref, _ = orc.conv_q(x, wv, b if bias else None, f_in, f_w, f_out, 2, pad, 1, relu)
+        for v in (B.CONV_AUTO, B.CONV_SMALLC):
+            y, _ = B.conv_q(xd, wdv, bd if bias else None, f_in, f_w, f_out, 2, pad, 1, relu, variant=v)
+            assert np.array_equal(host(y), y_ref), (f_in, f_w, f_out, relu, v)
+        p_ref = orc.pool_q(y_ref, "max", 3, 2, 1, f_out, f_out)
+        p = B.conv_q_maxpool(xd, wdv, bd if bias else None, f_in, f_w, f_out, 2, pad, relu)
+        assert (p is not None) == fused_expected
+        if p is not None:
+            assert np.array_equal(host(p), p_ref), (f_in, f_w, f_out, relu)
+
+
+def test_conv_q_maxpool_declines_what_it_does_not_cover(B):
+    rng = np.random.default_rng(77)
+    x = dev(rng.integers(-128, 128, (1, 70, 72, 3)).astype(np.int8))        # 35 output rows: the last window would hang over
+    w = dev(rng.integers(-128, 128, (64, 7, 7, 3)).astype(np.int8))
+    assert B.conv_q_maxpool(x, w, None, 4, 7, 4, 2, 3, True) is None
+    x = dev(rng.integers(-128, 128, (1, 64, 64, 3)).astype(np.int8))
+    assert B.conv_q_maxpool(x, w, None, 4, 7, 4, 2, 3, True, pool_k=2, pool_stride=2, pool_pad=0) is None   # another pooling
+    assert B.conv_q_maxpool(x, w, None, 4, 7, 12, 2, 3, True) is None                                        # shift < 0
