@@ -130,6 +130,33 @@ def test_conv_q_rejects_bad_arguments_before_launching(B):
     assert _conv(B, N=0) == B.OK                              # empty batch: nothing to do
 
 
+def test_conv_q_maxpool_rejects_bad_arguments_before_launching(B):
+    L = B.lib()
+    f = B.fmt
+
+    def call(x=1 << 20, w=2 << 20, y=3 << 20, N=1, H=64, W=64, C=3, K=64, R=7, S=7, stride=2, pad=3, groups=1, ldy=64, fi=4, fw=7,
+             fo=4, k=3, ps=2, pp=1):
+        return L.dfq_conv_q_maxpool(x, w, None, y, N, H, W, C, K, R, S, stride, pad, groups, ldy, f(fi), f(fw), f(fo), 1, k, ps, pp, None)
+
+    assert call(x=None) == B.EINVAL
+    assert call(y=None) == B.EINVAL
+    assert call(N=-1) == B.EINVAL
+    assert call(C=0) == B.ESHAPE
+    assert call(k=0) == B.ESHAPE
+    assert call(pp=3) == B.ESHAPE                             # pooling pad >= window
+    assert call(ldy=32) == B.ESHAPE                           # ldy < K
+    assert call(fo=40) == B.EFMT
+    assert call(y=1 << 20) == B.EINVAL                        # output aliases the input
+    assert call(N=0) == B.OK                                  # empty batch: nothing to do
+    # valid requests no fused kernel covers: nothing is launched
+    assert call(k=2, ps=2, pp=0) == B.EUNSUPPORTED            # another pooling
+    assert call(C=4) == B.EUNSUPPORTED                        # not a 3-channel first layer
+    assert call(H=66) == B.EUNSUPPORTED                       # 33 output rows: the last window would hang over the image
+    assert call(W=252) == B.EUNSUPPORTED                      # 63 pooled columns
+    assert call(fo=12) == B.EUNSUPPORTED                      # rescale shift below 0
+    assert call(ldy=72) == B.EUNSUPPORTED                     # output pixels not 16-byte aligned
+
+
 def test_conv_np_rejects_bad_arguments_before_launching(B):
     """(fake non-null addresses, 16-byte aligned and far apart: every case below must fail in validation)"""
     L = B.lib()
