@@ -193,7 +193,8 @@ class Plan:
         convolution's own int8 tensor is then never produced).  A convolution that feeds only a concat
         and already produces the concat's format writes straight into its channel slice of the joined
         tensor (no rescale is due, so no copy either); only the other branches pass through
-        dfq_concat_q_into.
+        dfq_concat_q_into.  A convolution whose only reader is a 3x3 / 2 / pad 1 max-pooling of the same format runs
+        together with it by one dfq_conv_q_maxpool call where a fused kernel covers it.
         lazy_joins (with fuse): every add of two different tensors one of which is the result of a convolution without
         activation that nothing else reads - the first such source in the add's own order - is taken with a single
         rounding by dfq_conv_q_add_lazy (a different arithmetic: the convolution's accumulator meets the other operand
