@@ -74,7 +74,7 @@ def bench_layers(args):
 
     dev = "cuda:0"
     rows = []
-    layer_set = {"3x3": wl.RESNET_3X3_SET, "grouped": wl.GROUPED_SET}.get(args.layer_set, wl.RESNET_LAYER_SET)
+    layer_set = {"3x3": wl.RESNET_3X3_SET, "grouped": wl.GROUPED_SET, "first": wl.FIRST_LAYER_SET}.get(args.layer_set, wl.RESNET_LAYER_SET)
     for i in range(len(layer_set)):
         L = wl.config1_layer(i, batch=args.batch, layer_set=layer_set)
         wf, bf = torch.from_numpy(L["w_float"]).to(dev), torch.from_numpy(L["b_float"]).to(dev)
@@ -110,8 +110,39 @@ def bench_layers(args):
                          tops=round(ops / ms / 1e9, 1), gbs=round(by / ms / 1e6, 1),
                          pct_mfma_peak=round(100 * ops / ms / 1e9 / INT8_MFMA_PEAK_TOPS, 1),
                          pct_hbm_peak=round(100 * by / ms / 1e6 / HBM_PEAK_GBS, 1), pct_roofline=round(100 * t_roof / ms, 1)))
+        if args.layer_set == "first":
+            # the 3x3 / 2 / pad 1 max-pooling behind the layer: as a second call, and inside the convolution's kernel
+            PP, PQ = B.conv_out_hw(P, Q, 3, 3, 2, 1)
+            ps = [torch.empty((N, PP, PQ, K), dtype=torch.int8, device=dev) for _ in range(nset)]
+
+            def timed(fn):
+                for k in range(3):
+                    fn(k)
+                torch.cuda.synchronize()
+                e0.record()
+                for k in range(iters):
+                    fn(k)
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / iters
+
+            ms_pool = timed(lambda k: B.pool_q(ys[k % nset], "max", 3, 2, 1, f_out, f_out, out=ps[k % nset]))
+            fused_ok = B.conv_q_maxpool(xs[0], w, b, f_in, f_w, f_out, stride, pad, True, out=ps[0]) is not None
+            by_pool = ys[0].numel() + ps[0].numel()
+            rows.append(dict(layer=L["name"] + " max-pool alone", shape="%dx%dx%d -> %dx%d, 3x3 /2" % (P, Q, K, PP, PQ), kernel="dfq_pool_q",
+                             us=round(ms_pool * 1e3, 1), gbs=round(by_pool / ms_pool / 1e6, 1), pct_hbm_peak=round(100 * by_pool / ms_pool / 1e6 / HBM_PEAK_GBS, 1)))
+            if fused_ok:
+                ms_f = timed(lambda k: B.conv_q_maxpool(xs[k % nset], w, b, f_in, f_w, f_out, stride, pad, True, out=ps[k % nset]))
+                by_f = x0.numel() + ps[0].numel() + w.numel() + 4 * K
+                rows.append(dict(layer=L["name"] + " + max-pool in one kernel", shape="%dx%dx%d -> %dx%dx%d" % (H, W, C, PP, PQ, K), kernel="dfq_conv_q_maxpool",
+                                 us=round(ms_f * 1e3, 1), tops=round(ops / ms_f / 1e9, 1), gbs=round(by_f / ms_f / 1e6, 1),
+                                 pct_mfma_peak=round(100 * ops / ms_f / 1e9 / INT8_MFMA_PEAK_TOPS, 1),
+                                 pct_hbm_peak=round(100 * by_f / ms_f / 1e6 / HBM_PEAK_GBS, 1),
+                                 two_calls_us=round((ms + ms_pool) * 1e3, 1)))
+            del ps
         del xs, ys, x0
-    what = {"3x3": "the four 3x3 shapes of the ResNet-50-shaped network", "grouped": "grouped and depthwise shapes"}.get(args.layer_set, "configs[1]")
+    what = {"3x3": "the four 3x3 shapes of the ResNet-50-shaped network", "grouped": "grouped and depthwise shapes",
+            "first": "first layers (3 channels, stride 2) with the max-pooling behind them"}.get(args.layer_set, "configs[1]")
     print(json.dumps({"metric": "int8 conv TOPS per layer of %s, standalone, b=%d" % (what, args.batch), "unit": "TOPS",
                       "n_gpus": 1, "dtype": "int8", "data": "synthetic", "buffers": "4 rotating sets per layer", "layers": rows}))
 
@@ -315,7 +346,7 @@ def main():
                     help="one weight format per output channel (dfq_conv_q_pc) instead of one per layer")
     ap.add_argument("--layers", action="store_true",
                     help="instead of the network pass: time the five dense layers of configs[1] on their own at --batch")
-    ap.add_argument("--layer-set", choices=["config1", "3x3", "grouped"], default="config1",
+    ap.add_argument("--layer-set", choices=["config1", "3x3", "grouped", "first"], default="config1",
                     help="with --layers: the five layers of configs[1], the four 3x3 shapes of the ResNet-50-shaped network, or grouped and depthwise shapes")
     ap.add_argument("--np84", action="store_true",
                     help="the network pass on (8, 4) dynamic floating-point codes (npnet.NpPlan); with --layers: the dense layers alone (dfq_conv_np)")

@@ -170,8 +170,10 @@ def cmd_layers(a):
         out += ["", d["metric"]]
         out.append(f"  {'layer':20s} {'shape':34s} {'kernel':10s} {'us':>7s} {'TOPS':>8s} {'GB/s':>8s} {'%mfma':>6s} {'%hbm':>6s} {'%roof':>6s}")
         for r in d["layers"]:
-            out.append(f"  {r['layer']:20s} {r['shape']:34s} {r['kernel']:10s} {r['us']:7.1f} {r['tops']:8.1f} {r['gbs']:8.1f} "
-                       f"{r['pct_mfma_peak']:6.1f} {r['pct_hbm_peak']:6.1f} {r['pct_roofline']:6.1f}")
+            num = lambda k, w: (f"{r[k]:{w}.1f}" if k in r else " " * (w - 1) + "-")
+            out.append(f"  {r['layer']:20s} {r['shape']:34s} {r['kernel']:10s} {r['us']:7.1f} {num('tops', 8)} {num('gbs', 8)} "
+                       f"{num('pct_mfma_peak', 6)} {num('pct_hbm_peak', 6)} {num('pct_roofline', 6)}"
+                       + (f"   (the two calls: {r['two_calls_us']:.1f} us)" if "two_calls_us" in r else ""))
     open(a.out, "w").write("\n".join(out) + "\n")
 
 

@@ -89,16 +89,23 @@ GROUPED_SET = [
 ]
 
 
+# first layers of image networks (3 input channels, stride 2), same entry layout as GROUPED_SET
+FIRST_LAYER_SET = [
+    ("first_7x7_3_64",  224,   3,   64,  7,   1, 2),
+    ("first_3x3_3_32",  224,   3,   32,  3,   1, 2),
+]
+
+
 def config1_layer(i: int, batch: int = 32, layer_set=None) -> dict:
     """Layer i of the set: int8 input at a per-layer f_in in {2..6}, float He-normal
     weights, float N(0, 0.1) bias; stride 1, pad R//2, ReLU.  The weight format,
     the integer bias and f_out are for each implementation to derive.
-    layer_set: RESNET_LAYER_SET (config 1, the default), RESNET_3X3_SET (tensor indices from 100) or GROUPED_SET (from 200,
-    with groups and stride per entry)."""
+    layer_set: RESNET_LAYER_SET (config 1, the default), RESNET_3X3_SET (tensor indices from 100), GROUPED_SET (from 200,
+    with groups and stride per entry) or FIRST_LAYER_SET (from 300)."""
     entry = (layer_set or RESNET_LAYER_SET)[i]
     name, H, C, K, R = entry[:5]
     groups, stride = (entry[5], entry[6]) if len(entry) > 5 else (1, 1)
-    base = 10 * i + (100 if layer_set is RESNET_3X3_SET else 200 if layer_set is GROUPED_SET else 0)
+    base = 10 * i + (100 if layer_set is RESNET_3X3_SET else 200 if layer_set is GROUPED_SET else 300 if layer_set is FIRST_LAYER_SET else 0)
     f_in = int(_rng(1, base + 0).integers(2, 7))
     x = int8_activations(1, base + 1, (batch, H, H, C), f_in)
     w = (_rng(1, base + 2).standard_normal((K, R, R, C // groups), dtype=np.float32)
