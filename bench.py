@@ -581,7 +581,7 @@ def main():
                                                                                               "dfq_conv_q_add_lazy: ONE rounding per join, a different arithmetic from the default" if args.lazy_joins
                                                                                               else "dfq_conv_q_add"),
         "first_layer": "convolution and the max-pooling behind it in one kernel (dfq_conv_q_maxpool)"
-                       if any(fn.__name__ == "dfq_conv_q_maxpool" for fn, _ in plan._calls_for(x)) else "convolution, then dfq_pool_q",
+                       if any(fn.__name__ == "dfq_conv_q_maxpool" for fn, _ in plan._calls_for(x)) else "input conversion, convolution and max-pooling in one kernel (dfq_quantize_conv_q_maxpool)" if any(fn.__name__ == "dfq_quantize_conv_q_maxpool" for fn, _ in plan._calls_for(x)) else "convolution, then dfq_pool_q",
         "weight_formats": "one per output channel (dfq_conv_q_pc)" if args.per_channel else "one per layer",
         "config": {"workload": "configs[4]: ResNet-50-shaped int8 network, 224x224x3, batch %d, formats from a "
                                "single-batch calibrate() on %d images" % (args.batch, args.calib),

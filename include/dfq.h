@@ -180,6 +180,16 @@ dfq_status dfq_conv_q_maxpool(const int8_t *x, const int8_t *w, const int32_t *b
                               int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu,
                               int pool_k, int pool_stride, int pool_pad, dfq_stream stream);
 
+/* dfq_conv_q_maxpool on float images: the conversion of the network's input (Sec. 3, conversion paragraph)
+ * merged into the first layer as well.  The result is exactly that of
+ *     dfq_quantize(x, t, N*H*W*C, fmt_in)   followed by   dfq_conv_q_maxpool(t, w, b, y, ...)
+ * without the int8 image t ever being stored.  x: device, float32 [N][H][W][C], 16-byte aligned, must not overlap y.
+ * Everything else, the DFQ_EUNSUPPORTED rule and the shapes covered as for dfq_conv_q_maxpool. */
+dfq_status dfq_quantize_conv_q_maxpool(const float *x, const int8_t *w, const int32_t *b, int8_t *y,
+                                       int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                                       int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu,
+                                       int pool_k, int pool_stride, int pool_pad, dfq_stream stream);
+
 /* Convolution followed by an element-wise add with ONE rounding (Sec. 3 wants a value thresholded only when the
  * datapath can carry it no further): the convolution's accumulator (Eq. 6 with bias, at fmt_in.frac + fmt_w.frac;
  * it gets no format of its own and no ReLU) and the code of `other` brought to that scale by the exact factor

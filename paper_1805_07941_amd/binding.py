@@ -29,7 +29,7 @@ EXPORTS = [
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
     "dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32", "dfq_conv_q_add_lazy", "dfq_eltwise_np",
     "dfq_conv_np_absmax", "dfq_eltwise_np_absmax", "dfq_np_frac_from_absmax_u64", "dfq_pool_np", "dfq_stem_pack_x", "dfq_stem_pack_w", "dfq_conv_np_add",
-    "dfq_conv_q_maxpool",
+    "dfq_conv_q_maxpool", "dfq_quantize_conv_q_maxpool",
 ]
 
 
@@ -86,6 +86,8 @@ def lib():
     L.dfq_conv_q_add_lazy.restype = i32
     L.dfq_conv_q_maxpool.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [Fmt, Fmt, Fmt, i32, i32, i32, i32, vp]
     L.dfq_conv_q_maxpool.restype = i32
+    L.dfq_quantize_conv_q_maxpool.argtypes = L.dfq_conv_q_maxpool.argtypes
+    L.dfq_quantize_conv_q_maxpool.restype = i32
     L.dfq_eltwise_q.argtypes = [vp, Fmt, vp, Fmt, vp, Fmt, vp, sz, i32, vp]
     L.dfq_concat_q.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, Fmt, sz, vp]
     L.dfq_concat_q_into.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, i32, Fmt, sz, vp]
@@ -471,9 +473,11 @@ def conv_q_add_lazy(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor],
 def conv_q_maxpool(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], f_in: int, f_w: int, f_out: int, stride: int,
                    pad: int, relu: bool, pool_k: int = 3, pool_stride: int = 2, pool_pad: int = 1,
                    out: Optional[torch.Tensor] = None, stream=None):
-    """Convolution + max-pooling in one kernel.  Returns the pooled int8 tensor, or None when no fused kernel
-    covers the call (nothing was launched)."""
-    _dev(x, torch.int8, "x"); _dev(w, torch.int8, "w")
+    """Convolution + max-pooling in one kernel; x int8 codes, or float32 images that are converted at f_in on the way in
+    (dfq_quantize_conv_q_maxpool).  Returns the pooled int8 tensor, or None when no fused kernel covers the call (nothing
+    was launched)."""
+    from_float = x.dtype == torch.float32
+    _dev(x, torch.float32 if from_float else torch.int8, "x"); _dev(w, torch.int8, "w")
     if b is not None:
         _dev(b, torch.int32, "b")
     N, H, W, Cc = x.shape
@@ -483,8 +487,9 @@ def conv_q_maxpool(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], 
     P, Q = conv_out_hw(H, W, R, S, stride, pad)
     PP, PQ = conv_out_hw(P, Q, pool_k, pool_k, pool_stride, pool_pad)
     y = out if out is not None else torch.empty((N, PP, PQ, K), dtype=torch.int8, device=x.device)
-    st = lib().dfq_conv_q_maxpool(_ptr(x), _ptr(w), _ptr(b), _ptr(y), N, H, W, Cc, K, R, S, stride, pad, 1, K, fmt(f_in), fmt(f_w),
-                                  fmt(f_out), int(bool(relu)), pool_k, pool_stride, pool_pad, _stream(stream))
+    fn = lib().dfq_quantize_conv_q_maxpool if from_float else lib().dfq_conv_q_maxpool
+    st = fn(_ptr(x), _ptr(w), _ptr(b), _ptr(y), N, H, W, Cc, K, R, S, stride, pad, 1, K, fmt(f_in), fmt(f_w),
+            fmt(f_out), int(bool(relu)), pool_k, pool_stride, pool_pad, _stream(stream))
     if st == EUNSUPPORTED:
         return None
     _check(st, "dfq_conv_q_maxpool")

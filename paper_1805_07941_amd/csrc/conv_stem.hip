@@ -27,6 +27,9 @@
 // convolution's own tensor exists nowhere.  Column blocks overlap by one pooled column (the left neighbour of a
 // block's first column is recomputed in the block, its result discarded); a strip that does not start at the top
 // of the image recomputes the step above it for the row its first windows need.
+#include <cmath>
+#include <type_traits>
+
 #include "conv_ring.hpp"
 
 namespace dfq {
@@ -48,6 +51,8 @@ struct StemParams {
     int strips;          // strips per image
     int steps_per_strip;
     int triples;         // W / 4: 12-byte pieces of an input row
+    const float *xf;     // float images [N, H, W, 3] to be converted to codes on the way in (pooling form only), or null
+    float scale;         // 2^f_in of that conversion
 };
 
 struct Row12 {
@@ -114,6 +119,63 @@ __device__ __forceinline__ void stem_stage_rows(int8_t *xin, int pitch, int trip
             uint2 *dst = (uint2 *)(xin + slot * pitch + (SKEW ? 2 * (slot & 4) : 0) + kLeftPad + 16 * lane);
             dst[0] = make_uint2(d0, __builtin_amdgcn_alignbit(d1, d0, 24));
             dst[1] = make_uint2(__builtin_amdgcn_alignbit(d2, d1, 16), d2 >> 8);
+        }
+    }
+}
+
+// The same two steps for float images that are converted on the way in (Sec. 3, conversion paragraph; the
+// arithmetic of dfq_quantize: x * 2^f is exact, round to nearest even, NaN -> 0, clamp to +-127): 12 floats per lane.
+struct Row12f {
+    float4 v[3];
+};
+
+template <int NW, int MAXR>
+__device__ __forceinline__ void stem_fetch_rows(const ConvArgs &a, const float *ximg, int triples, int wave, int lane, int first,
+                                                int count, Row12f (&pf)[MAXR])
+{
+#pragma unroll
+    for (int j = 0; j < MAXR; j++) {
+        const int k = wave + j * NW;
+        const int row = first + k;
+        pf[j].v[0] = pf[j].v[1] = pf[j].v[2] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k < count && (unsigned)row < (unsigned)a.H && lane < triples) {
+            const float4 *src = (const float4 *)(ximg + (size_t)row * (a.W * 3) + 12 * lane);
+            pf[j].v[0] = src[0];
+            pf[j].v[1] = src[1];
+            pf[j].v[2] = src[2];
+        }
+    }
+}
+
+__device__ __forceinline__ int stem_code(float x, float scale)
+{
+    // v_cvt_i32_f32 gives 0 for NaN and saturates beyond the 32-bit range (the instruction, not a C cast, whose result
+    // is undefined there), so the clamp can follow the conversion; the rounded value is integral, the conversion exact
+    const float t = __builtin_rintf(x * scale);
+    int c;
+    asm("v_cvt_i32_f32 %0, %1" : "=v"(c) : "v"(t));
+    return max(-127, min(127, c));
+}
+
+template <int NW, int MAXR, bool SKEW>
+__device__ __forceinline__ void stem_stage_rows(int8_t *xin, int pitch, int triples, int wave, int lane, int first, int count,
+                                                const Row12f (&pf)[MAXR], float scale)
+{
+#pragma unroll
+    for (int j = 0; j < MAXR; j++) {
+        const int k = wave + j * NW;
+        const int row = first + k;
+        if (k < count && lane < triples) {
+            const float4 a0 = pf[j].v[0], a1 = pf[j].v[1], a2 = pf[j].v[2];
+            const float f[12] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w, a2.x, a2.y, a2.z, a2.w};
+            uint32_t w[4];
+#pragma unroll
+            for (int px = 0; px < 4; px++)
+                w[px] = pack4_clamped(stem_code(f[3 * px], scale), stem_code(f[3 * px + 1], scale), stem_code(f[3 * px + 2], scale), 0);
+            const int slot = (row + 32) & (kRowSlots - 1);
+            uint2 *dst = (uint2 *)(xin + slot * pitch + (SKEW ? 2 * (slot & 4) : 0) + kLeftPad + 16 * lane);
+            dst[0] = make_uint2(w[0], w[1]);
+            dst[1] = make_uint2(w[2], w[3]);
         }
     }
 }
@@ -222,14 +284,14 @@ __device__ __forceinline__ int from_left_lane(int v)
 // 15 w + (lane & 15), pooled row 2t + ((lane >> 4) & 1), half of the reduction block lane >> 5).  Ring rows whose
 // slot has bit 2 set are staged 8 bytes later: the two pooled rows of a lane group lie four input rows apart, and
 // with the 16-byte lane stride this puts their 8-byte reads on disjoint LDS banks.
-template <int CT, int R>
+template <int CT, int R, bool XF>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) conv_stem_pool_kernel(StemParams prm)
 {
     constexpr int BC = CT * 32;
     constexpr int NW = 4;
     constexpr int kThreads = NW * 64;
     constexpr int kRowsFirst = R + 6;
-    constexpr int MAXR = (kRowsFirst + NW - 1) / NW;
+    constexpr int MAXR = 2;                                 // 8 staged rows at a time over four wavefronts
     constexpr int kWeightBytes = R * BC * 32;
     extern __shared__ uint4 lds4[];
     const ConvArgs &a = prm.a;
@@ -252,7 +314,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int t_emit = strip * prm.steps_per_strip;                 // first step whose pooled rows this strip stores
     const int t1 = min(t_emit + prm.steps_per_strip, prm.steps);
     const int t0 = strip > 0 ? t_emit - 1 : t_emit;                 // the strip's first windows reach into the step above
-    const int8_t *const ximg = a.x + (size_t)n * a.H * a.W * 3;
+    typedef typename std::conditional<XF, float, int8_t>::type In;
+    typedef typename std::conditional<XF, Row12f, Row12>::type Rows;
+    const In *const ximg = (XF ? (const In *)prm.xf : (const In *)a.x) + (size_t)n * a.H * a.W * 3;
+    auto stage = [&](int first, int count, const Rows (&rows)[MAXR]) __attribute__((always_inline)) {
+        if constexpr (XF) stem_stage_rows<NW, MAXR, true>(xin, prm.pitch, prm.triples, wave, lane, first, count, rows, prm.scale);
+        else stem_stage_rows<NW, MAXR, true>(xin, prm.pitch, prm.triples, wave, lane, first, count, rows);
+    };
 
     const int j = l32 & 15, rsel = l32 >> 4;
     const int pw = 15 * wave + j;
@@ -268,9 +336,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
         for (int i = 0; i < 16; i++) above[c][i] = kIntMin;
 
-    Row12 pf[MAXR];
-    stem_fetch_rows<NW, MAXR>(a, ximg, prm.triples, wave, lane, 8 * t0 - a.pad, kRowsFirst, pf);
-    stem_stage_rows<NW, MAXR, true>(xin, prm.pitch, prm.triples, wave, lane, 8 * t0 - a.pad, kRowsFirst, pf);
+    Rows pf[MAXR];
+    stem_fetch_rows<NW, MAXR>(a, ximg, prm.triples, wave, lane, 8 * t0 - a.pad, 8, pf);
+    stage(8 * t0 - a.pad, 8, pf);
+    stem_fetch_rows<NW, MAXR>(a, ximg, prm.triples, wave, lane, 8 * t0 - a.pad + 8, kRowsFirst - 8, pf);
+    stage(8 * t0 - a.pad + 8, kRowsFirst - 8, pf);
     __syncthreads();
 
     for (int t = t0; t < t1; t++) {
@@ -345,7 +415,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
         }
         __syncthreads();          // the step's reads of the input ring are done
-        if (has_next) stem_stage_rows<NW, MAXR, true>(xin, prm.pitch, prm.triples, wave, lane, next_first, 8, pf);
+        if (has_next) stage(next_first, 8, pf);
         __syncthreads();          // the next step's input rows are staged
     }
 }
@@ -388,8 +458,12 @@ hipError_t launch_plain(const StemParams &prm, size_t lds, hipStream_t st)
 template <int CT>
 hipError_t launch_pool(const StemParams &prm, size_t lds, hipStream_t st)
 {
-    if (prm.a.R == 7) return launch_kernel(conv_stem_pool_kernel<CT, 7>, prm, 256, lds, st);
-    return launch_kernel(conv_stem_pool_kernel<CT, 3>, prm, 256, lds, st);
+    if (prm.xf) {
+        if (prm.a.R == 7) return launch_kernel(conv_stem_pool_kernel<CT, 7, true>, prm, 256, lds, st);
+        return launch_kernel(conv_stem_pool_kernel<CT, 3, true>, prm, 256, lds, st);
+    }
+    if (prm.a.R == 7) return launch_kernel(conv_stem_pool_kernel<CT, 7, false>, prm, 256, lds, st);
+    return launch_kernel(conv_stem_pool_kernel<CT, 3, false>, prm, 256, lds, st);
 }
 
 }  // namespace
@@ -419,12 +493,15 @@ bool conv_stem_supports(const ConvArgs &a, bool pool)
 }
 
 // yp == null: the layer itself into a.y.  Otherwise a.y is not used and yp receives the pooled tensor
-// [N, (P - 1) / 2 + 1, (Q - 1) / 2 + 1, K] with ldyp bytes between pixels.
-hipError_t launch_conv_stem(const ConvArgs &a, int8_t *yp, int ldyp, hipStream_t st)
+// [N, (P - 1) / 2 + 1, (Q - 1) / 2 + 1, K] with ldyp bytes between pixels.  x_float (pooling form only; 16-byte
+// aligned): the input as float images, converted to codes at frac_in inside the kernel; a.x is then not read.
+hipError_t launch_conv_stem(const ConvArgs &a, int8_t *yp, int ldyp, hipStream_t st, const float *x_float, int frac_in)
 {
     const bool pool = yp != nullptr;
     StemParams prm;
     prm.a = a;
+    prm.xf = x_float;
+    prm.scale = ldexpf(1.0f, frac_in);
     prm.yp = yp;
     prm.ldyp = ldyp;
     prm.PP = (a.P - 1) / 2 + 1;

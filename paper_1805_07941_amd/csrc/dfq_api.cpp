@@ -448,12 +448,13 @@ dfq_status dfq_conv_q_add(const int8_t *x, const int8_t *w, const int32_t *b, co
     return run_conv_add(c, x, other, y, N, H, W, C, K, ldy, ld_other, fmt_mid, fmt_other, fmt_out, relu_out, stream);
 }
 
-dfq_status dfq_conv_q_maxpool(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int N, int H, int W, int C, int K,
-                              int R, int S, int stride, int pad, int groups, int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out,
-                              int relu, int pool_k, int pool_stride, int pool_pad, dfq_stream stream)
+// x: int8 codes (x_is_float == false) or float images to be converted at fmt_in on the way in
+static dfq_status conv_maxpool(const void *x, bool x_is_float, const int8_t *w, const int32_t *b, int8_t *y, int N, int H, int W, int C,
+                               int K, int R, int S, int stride, int pad, int groups, int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w,
+                               dfq_fmt fmt_out, int relu, int pool_k, int pool_stride, int pool_pad, dfq_stream stream)
 {
     // the convolution's own checks, with a placeholder where its tensor would be (never written)
-    ConvCheck c = check_conv(x, w, b, nullptr, nullptr, N, H, W, C, K, R, S, stride, pad, groups, K, fmt_in, fmt_w, fmt_out, relu,
+    ConvCheck c = check_conv((const int8_t *)x, w, b, nullptr, nullptr, N, H, W, C, K, R, S, stride, pad, groups, K, fmt_in, fmt_w, fmt_out, relu,
                              false);
     if (c.st != DFQ_OK) return c.st;
     if (!x || !w || !y) return DFQ_EINVAL;
@@ -461,11 +462,33 @@ dfq_status dfq_conv_q_maxpool(const int8_t *x, const int8_t *w, const int32_t *b
     const int PP = out_extent(c.a.P, pool_pad, pool_k, pool_stride), PQ = out_extent(c.a.Q, pool_pad, pool_k, pool_stride);
     if (PP < 1 || PQ < 1 || ldy < K) return DFQ_ESHAPE;
     if (N == 0) return DFQ_OK;
-    if (overlaps(x, (size_t)N * H * W * C, y, (size_t)N * PP * PQ * (size_t)ldy)) return DFQ_EINVAL;
+    if (overlaps(x, (size_t)N * H * W * C * (x_is_float ? 4 : 1), y, (size_t)N * PP * PQ * (size_t)ldy)) return DFQ_EINVAL;
     if (pool_k != 3 || pool_stride != 2 || pool_pad != 1) return DFQ_EUNSUPPORTED;
     if (((uintptr_t)y & 15) || (ldy & 15)) return DFQ_EUNSUPPORTED;
+    if (x_is_float) {
+        if ((uintptr_t)x & 15) return DFQ_EUNSUPPORTED;
+        c.a.x = nullptr;
+    } else {
+        c.a.x = (const int8_t *)x;
+    }
     if (!conv_stem_supports(c.a, true)) return DFQ_EUNSUPPORTED;
-    return from_hip(launch_conv_stem(c.a, y, ldy, (hipStream_t)stream));
+    return from_hip(launch_conv_stem(c.a, y, ldy, (hipStream_t)stream, x_is_float ? (const float *)x : nullptr, fmt_in.frac));
+}
+
+dfq_status dfq_conv_q_maxpool(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int N, int H, int W, int C, int K,
+                              int R, int S, int stride, int pad, int groups, int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out,
+                              int relu, int pool_k, int pool_stride, int pool_pad, dfq_stream stream)
+{
+    return conv_maxpool(x, false, w, b, y, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, fmt_w, fmt_out, relu, pool_k,
+                        pool_stride, pool_pad, stream);
+}
+
+dfq_status dfq_quantize_conv_q_maxpool(const float *x, const int8_t *w, const int32_t *b, int8_t *y, int N, int H, int W, int C,
+                                       int K, int R, int S, int stride, int pad, int groups, int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w,
+                                       dfq_fmt fmt_out, int relu, int pool_k, int pool_stride, int pool_pad, dfq_stream stream)
+{
+    return conv_maxpool(x, true, w, b, y, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, fmt_w, fmt_out, relu, pool_k,
+                        pool_stride, pool_pad, stream);
 }
 
 dfq_status dfq_conv_q_add_lazy(const int8_t *x, const int8_t *w, const int32_t *b, const int8_t *other, int8_t *y, int N, int H,

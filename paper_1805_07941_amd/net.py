@@ -225,6 +225,7 @@ class Plan:
         self.logits = torch.empty((batch, P * Q * K), dtype=torch.float32, device=device)
         self._calls, self._calls_key, self._graph, self._keep = None, None, None, None
         self._fused_ran = None                   # after the call list is built: results of convolutions that ran fused
+        self._input_in_kernel = False            # the input's conversion ran inside the first layer's kernel
 
     @staticmethod
     def _plain_pointwise(nd) -> bool:
@@ -384,7 +385,9 @@ class Plan:
     def resident(self):
         """Names of the tensors whose buffer still holds them after a pass (with pooled buffers a dead
         tensor's storage is handed to a later one; a fused convolution's own result is never stored)."""
-        skip = {self.net.nodes[i].dst for i in self.fused} if self._fused_ran is None else self._fused_ran
+        skip = set({self.net.nodes[i].dst for i in self.fused} if self._fused_ran is None else self._fused_ran)
+        if self._input_in_kernel:
+            skip.add(self.net.input_name)        # converted inside the first layer's kernel, never stored
         last_at: Dict[int, str] = {}
         for name, tns in self.buf.items():          # insertion order = execution order
             if name not in skip and name not in self.slice_of:
@@ -408,6 +411,8 @@ class Plan:
             calls.append((L.dfq_quantize, (x.data_ptr(), t[net.input_name].data_ptr(), x.numel(), f(qz.frac[net.input_name]))))
             names.append(None)
         fused_adds = set()
+        self._input_in_kernel = False
+        input_readers = sum(1 for nd in net.nodes for sname in nd.srcs if sname == net.input_name)
 
         def ldy_of(name, K):
             # bytes between pixels of a convolution's output: its own channels, or the joined tensor's
@@ -424,11 +429,25 @@ class Plan:
                 N, H, W, Cc = t[src].shape
                 K = nd.K
                 fn = L.dfq_conv_q_maxpool
-                args = (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(), t[partner.dst].data_ptr(), N, H, W, Cc,
+                src_ptr = t[src].data_ptr()
+                from_float = (src == net.input_name and not net.input_is_int8 and input_readers == 1 and calls
+                              and calls[-1][0] is L.dfq_quantize)
+                if from_float:
+                    # the input's conversion goes into the same kernel: the float images are read directly
+                    fn, src_ptr = L.dfq_quantize_conv_q_maxpool, x.data_ptr()
+                args = (src_ptr, qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(), t[partner.dst].data_ptr(), N, H, W, Cc,
                         K, nd.R, nd.R, nd.stride, nd.pad, nd.groups, K, f(qz.frac[src]), f(qz.w_frac[nd.name]), f(qz.frac[nd.dst]),
                         int(nd.relu), partner.R, partner.stride, partner.pad)
                 rc = fn(*args, B._stream(None))
+                if rc == B.EUNSUPPORTED and from_float:
+                    fn, args = L.dfq_conv_q_maxpool, (t[src].data_ptr(),) + args[1:]
+                    from_float = False
+                    rc = fn(*args, B._stream(None))
                 if rc == B.OK:
+                    if from_float:
+                        calls.pop()              # the separate conversion of the input
+                        names.pop()
+                        self._input_in_kernel = True
                     calls.append((fn, args))
                     names.append(nd.name)
                     fused_adds.add(self.fused[idx])

@@ -59,7 +59,10 @@ def cmd_stats(a):
     out.append("The totals include the untimed calibration pass, plan set-up and warm-up of the same command.")
     tr = list(csv.DictReader(open(a.trace_csv)))
     tr.sort(key=lambda r: int(r["Start_Timestamp"]))
-    starts = [i for i, r in enumerate(tr) if "quantize_vec4" in r["Kernel_Name"]]
+    # a pass begins with the conversion of the input images: a kernel of its own, or the first layer's kernel where that
+    # takes the float images itself (the launches with the largest grid are the full-batch ones)
+    first = "conv_stem_pool_kernel" if any("conv_stem_pool_kernel" in r["Kernel_Name"] and ", true>" in r["Kernel_Name"] for r in tr) else "quantize_vec4"
+    starts = [i for i, r in enumerate(tr) if first in r["Kernel_Name"]]
     big = max(int(tr[i]["Grid_Size_X"]) for i in starts)
     starts = [i for i in starts if int(tr[i]["Grid_Size_X"]) == big]
     if len(starts) >= 2:
@@ -72,7 +75,7 @@ def cmd_stats(a):
             e = per.setdefault(k, [0, 0])
             e[0] += 1; e[1] += int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
         out.append("")
-        out.append(f"One pass (the launches between the last two input quantizations): {len(seg)} kernels, GPU busy {busy / 1e3:.1f} us")
+        out.append(f"One pass (from one full-batch launch of {first} to the next): {len(seg)} kernels, GPU busy {busy / 1e3:.1f} us")
         for k, e in sorted(per.items(), key=lambda kv: -kv[1][1]):
             out.append(f"  {e[1] / 1e3:9.1f} us {e[0]:4d} launches  avg {e[1] / 1e3 / e[0]:8.2f} us  {k}")
         conv = [(n, e) for n, e in per.items() if is_conv(n)]

@@ -351,7 +351,10 @@ def test_fused_joins_give_the_same_logits(G):
     assert sum(1 for j in fused.fused.values() if net.nodes[j].op == "eltwise") == 16
     # the first layer and the max-pooling behind it run as one call too
     assert sum(1 for j in fused.fused.values() if net.nodes[j].op == "maxpool") == 1
-    assert sum(1 for fn, _ in fused._calls if fn.__name__ == "dfq_conv_q_maxpool") == 1
+    # ... and, the images being float, so does their conversion: no dfq_quantize call is left
+    assert sum(1 for fn, _ in fused._calls if fn.__name__ == "dfq_quantize_conv_q_maxpool") == 1
+    assert not any(fn.__name__ == "dfq_quantize" for fn, _ in fused._calls)
+    assert net.input_name not in fused.resident()
     # first blocks of the later stages list (c, projection, add): only c fits the fused kernel, so the plan
     # runs the projection first and c together with the add
     assert fused.order != sorted(fused.order) and sorted(fused.order) == list(range(len(net.nodes)))

@@ -728,6 +728,28 @@ def test_stem_kernel_alone_and_with_max_pool(B, shape):
             assert np.array_equal(host(p), p_ref), (f_in, f_w, f_out, relu)
 
 
+def test_quantize_conv_q_maxpool_equals_the_three_calls(B):
+    """Float images in: the conversion of Sec. 3 inside the first layer's kernel, against the oracle's quantize, convolution
+    and pooling one after the other; values on ties, beyond the clamp, infinities and NaN included."""
+    rng = np.random.default_rng(4321)
+    for (N, H, W, K, R, pad), f_in in itertools.product([(3, 224, 224, 64, 7, 3), (2, 60, 96, 64, 7, 3), (2, 64, 64, 32, 3, 1)], [5, 0, -2]):
+        x = (rng.standard_normal((N, H, W, 3)) * 2.0 ** (2 - f_in)).astype(np.float32)
+        x.reshape(-1)[::7] = np.rint(x.reshape(-1)[::7] * 2.0 ** f_in) * 2.0 ** -f_in + 0.5 * 2.0 ** -f_in      # exact ties
+        x.reshape(-1)[5::1001] = np.float32(np.inf)
+        x.reshape(-1)[6::1003] = np.float32(-np.inf)
+        x.reshape(-1)[7::1009] = np.float32(np.nan)
+        x.reshape(-1)[8::1013] = np.float32(1e30)
+        w = rng.integers(-128, 128, (K, R, R, 3)).astype(np.int8)
+        b = rng.integers(-2 ** 14, 2 ** 14, (K,)).astype(np.int32)
+        xq = orc.quantize(x, f_in)
+        f_w, f_out = 7, f_in + 7 - 12
+        y_ref, _ = orc.conv_q(xq, w, b, f_in, f_w, f_out, 2, pad, 1, True)
+        p_ref = orc.pool_q(y_ref, "max", 3, 2, 1, f_out, f_out)
+        p = B.conv_q_maxpool(dev(x), dev(w), dev(b), f_in, f_w, f_out, 2, pad, True)
+        assert p is not None
+        assert np.array_equal(host(p), p_ref), (N, H, W, K, R, f_in)
+
+
 def test_conv_q_maxpool_declines_what_it_does_not_cover(B):
     rng = np.random.default_rng(77)
     x = dev(rng.integers(-128, 128, (1, 70, 72, 3)).astype(np.int8))        # 35 output rows: the last window would hang over
