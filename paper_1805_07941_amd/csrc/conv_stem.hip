@@ -68,17 +68,21 @@ __device__ __forceinline__ void stem_setup(const ConvArgs &a, int8_t *lds, int *
 {
     const int tid = threadIdx.x;
     const int odd = a.pad & 1;
-    for (int i = tid; i < R * BC * 32; i += THREADS) {
-        const int j = i & 31;
-        const int kl = (i >> 5) % BC;
-        const int r = (i >> 5) / BC;
-        const int s = (j >> 2) - odd, c = j & 3;
-        int8_t v = 0;
-        if (c < 3 && s >= 0 && s < a.S && kl < a.K) v = a.w[(((size_t)kl * R + r) * a.S + s) * 3 + c];
+    // one dword (input pixel i of the run of kernel row r, channel k) per iteration
+    for (int t = tid; t < R * BC * 8; t += THREADS) {
+        const int i = t & 7;
+        const int kl = (t >> 3) % BC;
+        const int r = (t >> 3) / BC;
+        const int s = i - odd;
+        uint32_t v = 0;
+        if (s >= 0 && s < a.S && kl < a.K) {
+            const uint8_t *src = (const uint8_t *)a.w + (((size_t)kl * R + r) * a.S + s) * 3;
+            v = (uint32_t)src[0] | ((uint32_t)src[1] << 8) | ((uint32_t)src[2] << 16);
+        }
         const int c32 = kl & 31;
         const int row = (kl & ~31) + 8 * ((c32 & 15) >> 2) + 4 * (c32 >> 4) + (c32 & 3);
-        const int piece = (j >> 4) ^ ((row >> 3) & 1);
-        lds[((r * BC + row) * 2 + piece) * 16 + (j & 15)] = v;
+        const int piece = (i >> 2) ^ ((row >> 3) & 1);
+        *(uint32_t *)(lds + ((r * BC + row) * 2 + piece) * 16 + 4 * (i & 3)) = v;
     }
     for (int i = tid; i < BC; i += THREADS) biasl[i] = (a.b && i < a.K) ? a.b[i] : 0;
     for (int i = tid; i < ring_bytes / 8; i += THREADS) ((uint2 *)xin)[i] = make_uint2(0, 0);
