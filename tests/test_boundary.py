@@ -156,6 +156,17 @@ def test_conv_q_maxpool_rejects_bad_arguments_before_launching(B):
     assert call(fo=12) == B.EUNSUPPORTED                      # rescale shift below 0
     assert call(ldy=72) == B.EUNSUPPORTED                     # output pixels not 16-byte aligned
 
+    # the same call on float images
+    def callf(x=1 << 20, y=3 << 20, N=1, H=64, W=64, fi=4):
+        return L.dfq_quantize_conv_q_maxpool(x, 2 << 20, None, y, N, H, W, 3, 64, 7, 7, 2, 3, 1, 64, f(fi), f(7), f(4), 1, 3, 2, 1, None)
+
+    assert callf(x=None) == B.EINVAL
+    assert callf(fi=-40) == B.EFMT
+    assert callf(y=(1 << 20) + 4 * 64 * 64 * 3 - 16) == B.EINVAL   # the output begins inside the float images (4 bytes per element)
+    assert callf(N=0) == B.OK
+    assert callf(x=(1 << 20) + 4) == B.EUNSUPPORTED           # images not 16-byte aligned
+    assert callf(H=66) == B.EUNSUPPORTED
+
 
 def test_conv_np_rejects_bad_arguments_before_launching(B):
     """(fake non-null addresses, 16-byte aligned and far apart: every case below must fail in validation)"""
