@@ -139,6 +139,22 @@ def bench_layers(args):
                                  pct_mfma_peak=round(100 * ops / ms_f / 1e9 / INT8_MFMA_PEAK_TOPS, 1),
                                  pct_hbm_peak=round(100 * by_f / ms_f / 1e6 / HBM_PEAK_GBS, 1),
                                  two_calls_us=round((ms + ms_pool) * 1e3, 1)))
+                # ... and with the conversion of the float images in front taken into the kernel as well
+                xf = [(t.float() * 2.0 ** -f_in).contiguous() for t in xs]           # exact: converts back to the same codes
+                qs = [torch.empty_like(t) for t in xs]
+                ms_q = timed(lambda k: B.quantize(xf[k % nset], f_in, out=qs[k % nset]))
+                rows.append(dict(layer=L["name"] + " input conversion alone", shape="%dx%dx%d float -> int8" % (H, W, C), kernel="dfq_quantize",
+                                 us=round(ms_q * 1e3, 1), gbs=round(5 * x0.numel() / ms_q / 1e6, 1),
+                                 pct_hbm_peak=round(100 * 5 * x0.numel() / ms_q / 1e6 / HBM_PEAK_GBS, 1)))
+                if B.conv_q_maxpool(xf[0], w, b, f_in, f_w, f_out, stride, pad, True, out=ps[0]) is not None:
+                    ms_qf = timed(lambda k: B.conv_q_maxpool(xf[k % nset], w, b, f_in, f_w, f_out, stride, pad, True, out=ps[k % nset]))
+                    by_qf = 4 * x0.numel() + ps[0].numel() + w.numel() + 4 * K
+                    rows.append(dict(layer=L["name"] + " conversion + layer + max-pool in one kernel", shape="%dx%dx%d float -> %dx%dx%d" % (H, W, C, PP, PQ, K),
+                                     kernel="dfq_quantize_conv_q_maxpool", us=round(ms_qf * 1e3, 1), tops=round(ops / ms_qf / 1e9, 1),
+                                     gbs=round(by_qf / ms_qf / 1e6, 1), pct_mfma_peak=round(100 * ops / ms_qf / 1e9 / INT8_MFMA_PEAK_TOPS, 1),
+                                     pct_hbm_peak=round(100 * by_qf / ms_qf / 1e6 / HBM_PEAK_GBS, 1),
+                                     two_calls_us=round((ms_q + ms + ms_pool) * 1e3, 1)))
+                del xf, qs
             del ps
         del xs, ys, x0
     what = {"3x3": "the four 3x3 shapes of the ResNet-50-shaped network", "grouped": "grouped and depthwise shapes",

@@ -176,7 +176,7 @@ def cmd_layers(a):
             num = lambda k, w: (f"{r[k]:{w}.1f}" if k in r else " " * (w - 1) + "-")
             out.append(f"  {r['layer']:20s} {r['shape']:34s} {r['kernel']:10s} {r['us']:7.1f} {num('tops', 8)} {num('gbs', 8)} "
                        f"{num('pct_mfma_peak', 6)} {num('pct_hbm_peak', 6)} {num('pct_roofline', 6)}"
-                       + (f"   (the two calls: {r['two_calls_us']:.1f} us)" if "two_calls_us" in r else ""))
+                       + (f"   (as separate calls: {r['two_calls_us']:.1f} us)" if "two_calls_us" in r else ""))
     open(a.out, "w").write("\n".join(out) + "\n")
 
 
