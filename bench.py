@@ -596,8 +596,11 @@ def main():
                  "%d of %d residual adds run inside the convolution in front of them (%s)" % (n_fused, n_joins, "dfq_conv_q_pc_add" if args.per_channel else
                                                                                               "dfq_conv_q_add_lazy: ONE rounding per join, a different arithmetic from the default" if args.lazy_joins
                                                                                               else "dfq_conv_q_add"),
-        "first_layer": "convolution and the max-pooling behind it in one kernel (dfq_conv_q_maxpool)"
-                       if any(fn.__name__ == "dfq_conv_q_maxpool" for fn, _ in plan._calls_for(x)) else "input conversion, convolution and max-pooling in one kernel (dfq_quantize_conv_q_maxpool)" if any(fn.__name__ == "dfq_quantize_conv_q_maxpool" for fn, _ in plan._calls_for(x)) else "convolution, then dfq_pool_q",
+        "first_layer": {"dfq_conv_q_maxpool": "convolution and the max-pooling behind it in one kernel (dfq_conv_q_maxpool)",
+                        "dfq_conv_q_pc_maxpool": "convolution and the max-pooling behind it in one kernel (dfq_conv_q_pc_maxpool)",
+                        "dfq_quantize_conv_q_maxpool": "input conversion, convolution and max-pooling in one kernel (dfq_quantize_conv_q_maxpool)",
+                        "dfq_quantize_conv_q_pc_maxpool": "input conversion, convolution and max-pooling in one kernel (dfq_quantize_conv_q_pc_maxpool)",
+                        }.get(next((fn.__name__ for fn, _ in plan._calls_for(x) if "maxpool" in fn.__name__), None), "convolution, then dfq_pool_q"),
         "weight_formats": "one per output channel (dfq_conv_q_pc)" if args.per_channel else "one per layer",
         "config": {"workload": "configs[4]: ResNet-50-shaped int8 network, 224x224x3, batch %d, formats from a "
                                "single-batch calibrate() on %d images" % (args.batch, args.calib),

@@ -190,6 +190,19 @@ dfq_status dfq_quantize_conv_q_maxpool(const float *x, const int8_t *w, const in
                                        int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu,
                                        int pool_k, int pool_stride, int pool_pad, dfq_stream stream);
 
+/* dfq_conv_q_maxpool and dfq_quantize_conv_q_maxpool with one weight format per output channel: the result of
+ * dfq_conv_q_pc(..., fmt_out, relu) followed by dfq_pool_q(., DFQ_POOL_MAX, ..., fmt_out, fmt_out) (with dfq_quantize in
+ * front for the second).  frac_w, frac_w_lo, frac_w_hi as in dfq_conv_q_pc; the fused kernel needs every rounding shift
+ * fmt_in.frac + frac_w[k] - fmt_out.frac in [0, 23] (judged from the declared bounds); everything else as above. */
+dfq_status dfq_conv_q_pc_maxpool(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y,
+                                 int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                                 int ldy, dfq_fmt fmt_in, const int32_t *frac_w, int frac_w_lo, int frac_w_hi, dfq_fmt fmt_out,
+                                 int relu, int pool_k, int pool_stride, int pool_pad, dfq_stream stream);
+dfq_status dfq_quantize_conv_q_pc_maxpool(const float *x, const int8_t *w, const int32_t *b, int8_t *y,
+                                          int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                                          int ldy, dfq_fmt fmt_in, const int32_t *frac_w, int frac_w_lo, int frac_w_hi,
+                                          dfq_fmt fmt_out, int relu, int pool_k, int pool_stride, int pool_pad, dfq_stream stream);
+
 /* Convolution followed by an element-wise add with ONE rounding (Sec. 3 wants a value thresholded only when the
  * datapath can carry it no further): the convolution's accumulator (Eq. 6 with bias, at fmt_in.frac + fmt_w.frac;
  * it gets no format of its own and no ReLU) and the code of `other` brought to that scale by the exact factor

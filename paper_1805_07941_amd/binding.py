@@ -29,7 +29,7 @@ EXPORTS = [
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
     "dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32", "dfq_conv_q_add_lazy", "dfq_eltwise_np",
     "dfq_conv_np_absmax", "dfq_eltwise_np_absmax", "dfq_np_frac_from_absmax_u64", "dfq_pool_np", "dfq_stem_pack_x", "dfq_stem_pack_w", "dfq_conv_np_add",
-    "dfq_conv_q_maxpool", "dfq_quantize_conv_q_maxpool",
+    "dfq_conv_q_maxpool", "dfq_quantize_conv_q_maxpool", "dfq_conv_q_pc_maxpool", "dfq_quantize_conv_q_pc_maxpool",
 ]
 
 
@@ -88,6 +88,10 @@ def lib():
     L.dfq_conv_q_maxpool.restype = i32
     L.dfq_quantize_conv_q_maxpool.argtypes = L.dfq_conv_q_maxpool.argtypes
     L.dfq_quantize_conv_q_maxpool.restype = i32
+    L.dfq_conv_q_pc_maxpool.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [Fmt, vp, i32, i32, Fmt, i32, i32, i32, i32, vp]
+    L.dfq_conv_q_pc_maxpool.restype = i32
+    L.dfq_quantize_conv_q_pc_maxpool.argtypes = L.dfq_conv_q_pc_maxpool.argtypes
+    L.dfq_quantize_conv_q_pc_maxpool.restype = i32
     L.dfq_eltwise_q.argtypes = [vp, Fmt, vp, Fmt, vp, Fmt, vp, sz, i32, vp]
     L.dfq_concat_q.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, Fmt, sz, vp]
     L.dfq_concat_q_into.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, i32, Fmt, sz, vp]
@@ -470,9 +474,9 @@ def conv_q_add_lazy(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor],
     return y
 
 
-def conv_q_maxpool(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], f_in: int, f_w: int, f_out: int, stride: int,
+def conv_q_maxpool(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], f_in: int, f_w, f_out: int, stride: int,
                    pad: int, relu: bool, pool_k: int = 3, pool_stride: int = 2, pool_pad: int = 1,
-                   out: Optional[torch.Tensor] = None, stream=None):
+                   out: Optional[torch.Tensor] = None, stream=None, frac_w_range=None):
     """Convolution + max-pooling in one kernel; x int8 codes, or float32 images that are converted at f_in on the way in
     (dfq_quantize_conv_q_maxpool).  Returns the pooled int8 tensor, or None when no fused kernel covers the call (nothing
     was launched)."""
@@ -487,9 +491,17 @@ def conv_q_maxpool(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], 
     P, Q = conv_out_hw(H, W, R, S, stride, pad)
     PP, PQ = conv_out_hw(P, Q, pool_k, pool_k, pool_stride, pool_pad)
     y = out if out is not None else torch.empty((N, PP, PQ, K), dtype=torch.int8, device=x.device)
-    fn = lib().dfq_quantize_conv_q_maxpool if from_float else lib().dfq_conv_q_maxpool
-    st = fn(_ptr(x), _ptr(w), _ptr(b), _ptr(y), N, H, W, Cc, K, R, S, stride, pad, 1, K, fmt(f_in), fmt(f_w),
-            fmt(f_out), int(bool(relu)), pool_k, pool_stride, pool_pad, _stream(stream))
+    if isinstance(f_w, torch.Tensor):
+        # one weight format per output channel: f_w a device int32 array of K entries, frac_w_range the bounds of its entries
+        _dev(f_w, torch.int32, "frac_w")
+        lo, hi = frac_w_range
+        fn = lib().dfq_quantize_conv_q_pc_maxpool if from_float else lib().dfq_conv_q_pc_maxpool
+        st = fn(_ptr(x), _ptr(w), _ptr(b), _ptr(y), N, H, W, Cc, K, R, S, stride, pad, 1, K, fmt(f_in), _ptr(f_w), int(lo), int(hi),
+                fmt(f_out), int(bool(relu)), pool_k, pool_stride, pool_pad, _stream(stream))
+    else:
+        fn = lib().dfq_quantize_conv_q_maxpool if from_float else lib().dfq_conv_q_maxpool
+        st = fn(_ptr(x), _ptr(w), _ptr(b), _ptr(y), N, H, W, Cc, K, R, S, stride, pad, 1, K, fmt(f_in), fmt(f_w),
+                fmt(f_out), int(bool(relu)), pool_k, pool_stride, pool_pad, _stream(stream))
     if st == EUNSUPPORTED:
         return None
     _check(st, "dfq_conv_q_maxpool")

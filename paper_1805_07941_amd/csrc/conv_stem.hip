@@ -288,7 +288,9 @@ __device__ __forceinline__ int from_left_lane(int v)
 // 15 w + (lane & 15), pooled row 2t + ((lane >> 4) & 1), half of the reduction block lane >> 5).  Ring rows whose
 // slot has bit 2 set are staged 8 bytes later: the two pooled rows of a lane group lie four input rows apart, and
 // with the 16-byte lane stride this puts their 8-byte reads on disjoint LDS banks.
-template <int CT, int R, bool XF>
+// PC: one weight format per output channel (a.frac_w, every rounding shift a.shift + frac_w[k] in [0, 23]): shift, clamp bound
+// and rounding constant of each channel come from LDS tables behind the bias.
+template <int CT, int R, bool XF, bool PC>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) conv_stem_pool_kernel(StemParams prm)
 {
     constexpr int BC = CT * 32;
@@ -301,12 +303,21 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     const ConvArgs &a = prm.a;
     int8_t *const lds = (int8_t *)lds4;
     int *const biasl = (int *)(lds + kWeightBytes);
-    int8_t *const xin = lds + kWeightBytes + BC * 4;
+    int *const pc_shift = biasl + BC, *const pc_hi = biasl + 2 * BC, *const pc_badd = biasl + 3 * BC;   // PC only
+    int8_t *const xin = lds + kWeightBytes + BC * 4 * (PC ? 4 : 1);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lh = lane >> 5;
 
     stem_setup<BC, R, kThreads>(a, lds, biasl, xin, kRowSlots * prm.pitch + 16);
+    if constexpr (PC) {
+        for (int i = tid; i < BC; i += kThreads) {
+            const int sh = a.shift + a.frac_w[i];
+            pc_shift[i] = sh;
+            pc_hi[i] = 127 << sh;
+            pc_badd[i] = sh > 0 ? (1 << (sh - 1)) - 1 : 0;
+        }
+    }
     __syncthreads();
 
     Requant rq;
@@ -413,8 +424,20 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 above[c][i] = below;
             }
             if (emit) {
-                const uint4 o = make_uint4(rq.fast_four(m[0], m[1], m[2], m[3]), rq.fast_four(m[4], m[5], m[6], m[7]),
-                                           rq.fast_four(m[8], m[9], m[10], m[11]), rq.fast_four(m[12], m[13], m[14], m[15]));
+                uint4 o;
+                if constexpr (PC) {
+                    uint32_t q[4];
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; r4++) {
+                        const int kr = c * 32 + 16 * lh + 4 * r4;
+                        q[r4] = requant_four_per_channel(m[4 * r4], m[4 * r4 + 1], m[4 * r4 + 2], m[4 * r4 + 3], *(const int4 *)(pc_shift + kr),
+                                                         *(const int4 *)(pc_hi + kr), *(const int4 *)(pc_badd + kr), a.relu);
+                    }
+                    o = make_uint4(q[0], q[1], q[2], q[3]);
+                } else {
+                    o = make_uint4(rq.fast_four(m[0], m[1], m[2], m[3]), rq.fast_four(m[4], m[5], m[6], m[7]),
+                                   rq.fast_four(m[8], m[9], m[10], m[11]), rq.fast_four(m[12], m[13], m[14], m[15]));
+                }
                 *(uint4 *)(prm.yp + (((size_t)n * prm.PP + ph) * prm.PQ + pw) * prm.ldyp + c * 32 + 16 * lh) = o;
             }
         }
@@ -438,7 +461,7 @@ int stem_pitch(const ConvArgs &a, bool pool)
 
 size_t stem_lds_bytes(const ConvArgs &a, bool pool)
 {
-    return (size_t)a.R * a.K * 32 + (size_t)a.K * 4 + (size_t)kRowSlots * stem_pitch(a, pool) + (pool ? 16 : 0);
+    return (size_t)a.R * a.K * 32 + (size_t)a.K * 4 * (a.frac_w ? 4 : 1) + (size_t)kRowSlots * stem_pitch(a, pool) + (pool ? 16 : 0);
 }
 
 template <typename Kernel>
@@ -459,22 +482,25 @@ hipError_t launch_plain(const StemParams &prm, size_t lds, hipStream_t st)
     return launch_kernel(conv_stem_kernel<CT, NW, 3>, prm, NW * 64, lds, st);
 }
 
+template <int CT, bool XF, bool PC>
+hipError_t launch_pool_r(const StemParams &prm, size_t lds, hipStream_t st)
+{
+    if (prm.a.R == 7) return launch_kernel(conv_stem_pool_kernel<CT, 7, XF, PC>, prm, 256, lds, st);
+    return launch_kernel(conv_stem_pool_kernel<CT, 3, XF, PC>, prm, 256, lds, st);
+}
+
 template <int CT>
 hipError_t launch_pool(const StemParams &prm, size_t lds, hipStream_t st)
 {
-    if (prm.xf) {
-        if (prm.a.R == 7) return launch_kernel(conv_stem_pool_kernel<CT, 7, true>, prm, 256, lds, st);
-        return launch_kernel(conv_stem_pool_kernel<CT, 3, true>, prm, 256, lds, st);
-    }
-    if (prm.a.R == 7) return launch_kernel(conv_stem_pool_kernel<CT, 7, false>, prm, 256, lds, st);
-    return launch_kernel(conv_stem_pool_kernel<CT, 3, false>, prm, 256, lds, st);
+    if (prm.xf) return prm.a.frac_w ? launch_pool_r<CT, true, true>(prm, lds, st) : launch_pool_r<CT, true, false>(prm, lds, st);
+    return prm.a.frac_w ? launch_pool_r<CT, false, true>(prm, lds, st) : launch_pool_r<CT, false, false>(prm, lds, st);
 }
 
 }  // namespace
 
 // What the kernels take: 3 input channels, stride 2, 3 or 7 kernel rows, 32 or 64 output channels, input rows of
-// at most 256 pixels and a multiple of 4, the lean epilogue (one rounding shift in [0, 23] for the whole layer, no
-// accumulator dump).  Alone: output rows a multiple of 16 wide, aligned output.  pool (the output is the 3x3 / 2 /
+// at most 256 pixels and a multiple of 4, the lean epilogue (rounding shifts in [0, 23]: one for the whole layer, or - pooling
+// form only - one per output channel; no accumulator dump).  Alone: output rows a multiple of 16 wide, aligned output.  pool (the output is the 3x3 / 2 /
 // pad 1 max-pooled tensor): an even number of output rows and columns, at most 61 pooled columns.
 bool conv_stem_supports(const ConvArgs &a, bool pool)
 {
@@ -484,7 +510,13 @@ bool conv_stem_supports(const ConvArgs &a, bool pool)
     if (a.K != 32 && a.K != 64) return false;
     if (a.W % 4 || a.W > 256) return false;
     if ((uintptr_t)a.x & 3) return false;
-    if (a.frac_w || a.acc_out || a.add || a.shift < 0 || a.shift > 23) return false;
+    if (a.acc_out || a.add) return false;
+    if (a.frac_w) {
+        // one weight format per output channel: the pooling kernel only, every channel's shift in the lean range
+        if (!pool || a.shift + a.frac_w_lo < 0 || a.shift + a.frac_w_hi > 23) return false;
+    } else if (a.shift < 0 || a.shift > 23) {
+        return false;
+    }
     if (pool) {
         if ((a.P & 1) || (a.Q & 1) || a.Q / 2 > 61) return false;
     } else {

@@ -449,9 +449,11 @@ dfq_status dfq_conv_q_add(const int8_t *x, const int8_t *w, const int32_t *b, co
 }
 
 // x: int8 codes (x_is_float == false) or float images to be converted at fmt_in on the way in
+// frac_w != null: one weight format per output channel (fmt_w is then a placeholder with frac 0)
 static dfq_status conv_maxpool(const void *x, bool x_is_float, const int8_t *w, const int32_t *b, int8_t *y, int N, int H, int W, int C,
                                int K, int R, int S, int stride, int pad, int groups, int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w,
-                               dfq_fmt fmt_out, int relu, int pool_k, int pool_stride, int pool_pad, dfq_stream stream)
+                               dfq_fmt fmt_out, int relu, int pool_k, int pool_stride, int pool_pad, dfq_stream stream,
+                               const int32_t *frac_w = nullptr, int frac_w_lo = 0, int frac_w_hi = 0)
 {
     // the convolution's own checks, with a placeholder where its tensor would be (never written)
     ConvCheck c = check_conv((const int8_t *)x, w, b, nullptr, nullptr, N, H, W, C, K, R, S, stride, pad, groups, K, fmt_in, fmt_w, fmt_out, relu,
@@ -465,6 +467,9 @@ static dfq_status conv_maxpool(const void *x, bool x_is_float, const int8_t *w, 
     if (overlaps(x, (size_t)N * H * W * C * (x_is_float ? 4 : 1), y, (size_t)N * PP * PQ * (size_t)ldy)) return DFQ_EINVAL;
     if (pool_k != 3 || pool_stride != 2 || pool_pad != 1) return DFQ_EUNSUPPORTED;
     if (((uintptr_t)y & 15) || (ldy & 15)) return DFQ_EUNSUPPORTED;
+    c.a.frac_w = frac_w;
+    c.a.frac_w_lo = frac_w_lo;
+    c.a.frac_w_hi = frac_w_hi;
     if (x_is_float) {
         if ((uintptr_t)x & 15) return DFQ_EUNSUPPORTED;
         c.a.x = nullptr;
@@ -489,6 +494,28 @@ dfq_status dfq_quantize_conv_q_maxpool(const float *x, const int8_t *w, const in
 {
     return conv_maxpool(x, true, w, b, y, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, fmt_w, fmt_out, relu, pool_k,
                         pool_stride, pool_pad, stream);
+}
+
+dfq_status dfq_conv_q_pc_maxpool(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int N, int H, int W, int C, int K,
+                                 int R, int S, int stride, int pad, int groups, int ldy, dfq_fmt fmt_in, const int32_t *frac_w,
+                                 int frac_w_lo, int frac_w_hi, dfq_fmt fmt_out, int relu, int pool_k, int pool_stride, int pool_pad,
+                                 dfq_stream stream)
+{
+    if (frac_w_lo > frac_w_hi || frac_w_lo < -32 || frac_w_hi > 32) return DFQ_EFMT;
+    if (!frac_w || ((uintptr_t)frac_w & 3)) return DFQ_EINVAL;
+    return conv_maxpool(x, false, w, b, y, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, dfq_fmt{8, 0}, fmt_out, relu, pool_k,
+                        pool_stride, pool_pad, stream, frac_w, frac_w_lo, frac_w_hi);
+}
+
+dfq_status dfq_quantize_conv_q_pc_maxpool(const float *x, const int8_t *w, const int32_t *b, int8_t *y, int N, int H, int W, int C,
+                                          int K, int R, int S, int stride, int pad, int groups, int ldy, dfq_fmt fmt_in,
+                                          const int32_t *frac_w, int frac_w_lo, int frac_w_hi, dfq_fmt fmt_out, int relu, int pool_k,
+                                          int pool_stride, int pool_pad, dfq_stream stream)
+{
+    if (frac_w_lo > frac_w_hi || frac_w_lo < -32 || frac_w_hi > 32) return DFQ_EFMT;
+    if (!frac_w || ((uintptr_t)frac_w & 3)) return DFQ_EINVAL;
+    return conv_maxpool(x, true, w, b, y, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, dfq_fmt{8, 0}, fmt_out, relu, pool_k,
+                        pool_stride, pool_pad, stream, frac_w, frac_w_lo, frac_w_hi);
 }
 
 dfq_status dfq_conv_q_add_lazy(const int8_t *x, const int8_t *w, const int32_t *b, const int8_t *other, int8_t *y, int N, int H,

@@ -266,7 +266,7 @@ class Plan:
 
     def _pool_pairs(self) -> Dict[int, int]:
         """Convolution nodes directly followed by a 3x3 / 2 / pad 1 max-pooling that is the only reader of their
-        result and keeps its format (one weight format per layer): candidates for dfq_conv_q_maxpool."""
+        result and keeps its format: candidates for dfq_conv_q_maxpool / dfq_conv_q_pc_maxpool."""
         net, qz = self.net, self.qz
         readers: Dict[str, int] = {}
         for nd in net.nodes:
@@ -277,7 +277,7 @@ class Plan:
             e, c = net.nodes[j], net.nodes[j - 1]
             if (e.op == "maxpool" and (e.R, e.stride, e.pad) == (3, 2, 1) and c.op == "conv" and e.srcs[0] == c.dst
                     and readers.get(c.dst, 0) == 1 and c.dst != net.output_name and c.groups == 1
-                    and c.name not in qz.w_frac_dev and qz.frac[c.dst] == qz.frac[e.dst]):
+                    and qz.frac[c.dst] == qz.frac[e.dst]):
                 pairs[j - 1] = j
         return pairs
 
@@ -428,19 +428,22 @@ class Plan:
                 src = nd.srcs[0]
                 N, H, W, Cc = t[src].shape
                 K = nd.K
-                fn = L.dfq_conv_q_maxpool
-                src_ptr = t[src].data_ptr()
+                pc = nd.name in qz.w_frac_dev                      # one weight format per output channel
+                fn_codes = L.dfq_conv_q_pc_maxpool if pc else L.dfq_conv_q_maxpool
+                fn, src_ptr = fn_codes, t[src].data_ptr()
                 from_float = (src == net.input_name and not net.input_is_int8 and input_readers == 1 and calls
                               and calls[-1][0] is L.dfq_quantize)
                 if from_float:
                     # the input's conversion goes into the same kernel: the float images are read directly
-                    fn, src_ptr = L.dfq_quantize_conv_q_maxpool, x.data_ptr()
+                    fn, src_ptr = (L.dfq_quantize_conv_q_pc_maxpool if pc else L.dfq_quantize_conv_q_maxpool), x.data_ptr()
+                wfmt = ((qz.w_frac_dev[nd.name].data_ptr(), int(qz.w_frac[nd.name].min()), int(qz.w_frac[nd.name].max())) if pc
+                        else (f(qz.w_frac[nd.name]),))
                 args = (src_ptr, qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(), t[partner.dst].data_ptr(), N, H, W, Cc,
-                        K, nd.R, nd.R, nd.stride, nd.pad, nd.groups, K, f(qz.frac[src]), f(qz.w_frac[nd.name]), f(qz.frac[nd.dst]),
+                        K, nd.R, nd.R, nd.stride, nd.pad, nd.groups, K, f(qz.frac[src])) + wfmt + (f(qz.frac[nd.dst]),
                         int(nd.relu), partner.R, partner.stride, partner.pad)
                 rc = fn(*args, B._stream(None))
                 if rc == B.EUNSUPPORTED and from_float:
-                    fn, args = L.dfq_conv_q_maxpool, (t[src].data_ptr(),) + args[1:]
+                    fn, args = fn_codes, (t[src].data_ptr(),) + args[1:]
                     from_float = False
                     rc = fn(*args, B._stream(None))
                 if rc == B.OK:

@@ -167,6 +167,18 @@ def test_conv_q_maxpool_rejects_bad_arguments_before_launching(B):
     assert callf(x=(1 << 20) + 4) == B.EUNSUPPORTED           # images not 16-byte aligned
     assert callf(H=66) == B.EUNSUPPORTED
 
+    # one weight format per output channel
+    def callpc(fw=4 << 20, lo=3, hi=9, fo=4, fn=L.dfq_conv_q_pc_maxpool):
+        return fn(1 << 20, 2 << 20, None, 3 << 20, 1, 64, 64, 3, 64, 7, 7, 2, 3, 1, 64, f(4), fw, lo, hi, f(fo), 1, 3, 2, 1, None)
+
+    for fn in (L.dfq_conv_q_pc_maxpool, L.dfq_quantize_conv_q_pc_maxpool):
+        assert callpc(fw=None, fn=fn) == B.EINVAL
+        assert callpc(fw=(4 << 20) + 2, fn=fn) == B.EINVAL        # format array not 4-byte aligned
+        assert callpc(lo=9, hi=3, fn=fn) == B.EFMT
+        assert callpc(hi=40, fn=fn) == B.EFMT
+        assert callpc(lo=3, hi=24, fn=fn) == B.EUNSUPPORTED       # shifts 4 + 24 - 4 > 23
+        assert callpc(lo=-1, hi=5, fn=fn) == B.EUNSUPPORTED       # a shift below 0
+
 
 def test_conv_np_rejects_bad_arguments_before_launching(B):
     """(fake non-null addresses, 16-byte aligned and far apart: every case below must fail in validation)"""

@@ -748,6 +748,18 @@ def test_quantize_conv_q_maxpool_equals_the_three_calls(B):
         p = B.conv_q_maxpool(dev(x), dev(w), dev(b), f_in, f_w, f_out, 2, pad, True)
         assert p is not None
         assert np.array_equal(host(p), p_ref), (N, H, W, K, R, f_in)
+        # one weight format per output channel (shifts 0 .. 23 over the channels), from codes and from float images
+        fw = rng.integers(f_out - f_in, f_out - f_in + 24, K).astype(np.int32)
+        fw[:2] = (f_out - f_in, f_out - f_in + 23)
+        y_pc, _ = orc.conv_q(xq, w, b, f_in, fw, f_out, 2, pad, 1, True)
+        p_pc_ref = orc.pool_q(y_pc, "max", 3, 2, 1, f_out, f_out)
+        for xin in (dev(xq), dev(x)):
+            p = B.conv_q_maxpool(xin, dev(w), dev(b), f_in, dev(fw), f_out, 2, pad, True, frac_w_range=(int(fw.min()), int(fw.max())))
+            assert p is not None
+            assert np.array_equal(host(p), p_pc_ref), (N, H, W, K, R, f_in, str(xin.dtype))
+        # a channel whose shift leaves the lean range: no fused kernel
+        assert B.conv_q_maxpool(dev(xq), dev(w), dev(b), f_in, dev(fw), f_out, 2, pad, True,
+                                frac_w_range=(int(fw.min()), int(fw.max()) + 1)) is None
 
 
 def test_conv_q_maxpool_declines_what_it_does_not_cover(B):
