@@ -190,6 +190,16 @@ dfq_status dfq_quantize_conv_q_maxpool(const float *x, const int8_t *w, const in
                                        int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu,
                                        int pool_k, int pool_stride, int pool_pad, dfq_stream stream);
 
+/* The conversion of float images merged into a first layer that no pooling follows: exactly
+ *     dfq_quantize(x, t, N*H*W*C, fmt_in)   followed by   dfq_conv_q(t, w, b, y, NULL, ...)
+ * without the int8 image t being stored.  x: device, float32 [N][H][W][C], 16-byte aligned, must not overlap y; no accumulator
+ * dump.  DFQ_EUNSUPPORTED - nothing done - when no fused kernel covers the call: one exists for C == 3, stride 2, groups == 1,
+ * R in {3, 7}, S + (pad & 1) <= 8, pad <= 4, K == 32, W % 4 == 0, W <= 256, Q % 16 == 0, y 16-byte aligned with ldy % 16 == 0,
+ * a rescale shift in [0, 23]. */
+dfq_status dfq_quantize_conv_q(const float *x, const int8_t *w, const int32_t *b, int8_t *y,
+                               int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int groups,
+                               int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu, dfq_stream stream);
+
 /* dfq_conv_q_maxpool and dfq_quantize_conv_q_maxpool with one weight format per output channel: the result of
  * dfq_conv_q_pc(..., fmt_out, relu) followed by dfq_pool_q(., DFQ_POOL_MAX, ..., fmt_out, fmt_out) (with dfq_quantize in
  * front for the second).  frac_w, frac_w_lo, frac_w_hi as in dfq_conv_q_pc; the fused kernel needs every rounding shift

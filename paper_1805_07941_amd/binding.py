@@ -29,7 +29,7 @@ EXPORTS = [
     "dfq_beta_max", "dfq_mac_acc_bits", "dfq_mac_max_len", "dfq_add_acc_bits", "dfq_add_max_len",
     "dfq_np_digits", "dfq_conv_np", "dfq_conv_np_variant", "dfq_np_frac_from_absmax_f32", "dfq_conv_q_add_lazy", "dfq_eltwise_np",
     "dfq_conv_np_absmax", "dfq_eltwise_np_absmax", "dfq_np_frac_from_absmax_u64", "dfq_pool_np", "dfq_stem_pack_x", "dfq_stem_pack_w", "dfq_conv_np_add",
-    "dfq_conv_q_maxpool", "dfq_quantize_conv_q_maxpool", "dfq_conv_q_pc_maxpool", "dfq_quantize_conv_q_pc_maxpool",
+    "dfq_conv_q_maxpool", "dfq_quantize_conv_q_maxpool", "dfq_conv_q_pc_maxpool", "dfq_quantize_conv_q_pc_maxpool", "dfq_quantize_conv_q",
 ]
 
 
@@ -92,6 +92,8 @@ def lib():
     L.dfq_conv_q_pc_maxpool.restype = i32
     L.dfq_quantize_conv_q_pc_maxpool.argtypes = L.dfq_conv_q_pc_maxpool.argtypes
     L.dfq_quantize_conv_q_pc_maxpool.restype = i32
+    L.dfq_quantize_conv_q.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [Fmt, Fmt, Fmt, i32, vp]
+    L.dfq_quantize_conv_q.restype = i32
     L.dfq_eltwise_q.argtypes = [vp, Fmt, vp, Fmt, vp, Fmt, vp, sz, i32, vp]
     L.dfq_concat_q.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, Fmt, sz, vp]
     L.dfq_concat_q_into.argtypes = [i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(Fmt), vp, i32, Fmt, sz, vp]
@@ -471,6 +473,27 @@ def conv_q_add_lazy(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor],
     if st == EUNSUPPORTED:
         return None
     _check(st, "dfq_conv_q_add_lazy")
+    return y
+
+
+def quantize_conv_q(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], f_in: int, f_w: int, f_out: int, stride: int,
+                    pad: int, relu: bool, out: Optional[torch.Tensor] = None, stream=None):
+    """Float images converted at f_in inside the first layer's kernel.  Returns the int8 result, or None when no fused
+    kernel covers the call (nothing was launched)."""
+    _dev(x, torch.float32, "x"); _dev(w, torch.int8, "w")
+    if b is not None:
+        _dev(b, torch.int32, "b")
+    N, H, W, Cc = x.shape
+    K, R, S, Cg = w.shape
+    if Cg != Cc:
+        raise DfqError(ESHAPE, "quantize_conv_q (weight shape does not match C)")
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    y = out if out is not None else torch.empty((N, P, Q, K), dtype=torch.int8, device=x.device)
+    st = lib().dfq_quantize_conv_q(_ptr(x), _ptr(w), _ptr(b), _ptr(y), N, H, W, Cc, K, R, S, stride, pad, 1, K, fmt(f_in), fmt(f_w),
+                                   fmt(f_out), int(bool(relu)), _stream(stream))
+    if st == EUNSUPPORTED:
+        return None
+    _check(st, "dfq_quantize_conv_q")
     return y
 
 

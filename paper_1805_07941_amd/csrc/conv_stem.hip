@@ -51,7 +51,7 @@ struct StemParams {
     int strips;          // strips per image
     int steps_per_strip;
     int triples;         // W / 4: 12-byte pieces of an input row
-    const float *xf;     // float images [N, H, W, 3] to be converted to codes on the way in (pooling form only), or null
+    const float *xf;     // float images [N, H, W, 3] to be converted to codes on the way in, or null
     float scale;         // 2^f_in of that conversion
 };
 
@@ -184,13 +184,14 @@ __device__ __forceinline__ void stem_stage_rows(int8_t *xin, int pitch, int trip
     }
 }
 
-template <int CT, int NW, int R>
+// XF: float images, converted to codes while they are staged (prm.xf, prm.scale; a.x is not read)
+template <int CT, int NW, int R, bool XF>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) conv_stem_kernel(StemParams prm)
 {
     constexpr int BC = CT * 32;
     constexpr int kThreads = NW * 64;
     constexpr int kRowsFirst = R + 6;                       // input rows of one step
-    constexpr int MAXR = (kRowsFirst + NW - 1) / NW;        // staged rows one wavefront carries at a time
+    constexpr int MAXR = (8 + NW - 1) / NW;                 // staged rows one wavefront carries at a time (8 rows per round)
     constexpr int kWeightBytes = R * BC * 32;
     extern __shared__ uint4 lds4[];
     const ConvArgs &a = prm.a;
@@ -212,11 +213,19 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4,
     const int strip = blockIdx.x - n * prm.strips;
     const int t0 = strip * prm.steps_per_strip;
     const int t1 = min(t0 + prm.steps_per_strip, prm.steps);
-    const int8_t *const ximg = a.x + (size_t)n * a.H * a.W * 3;
+    typedef typename std::conditional<XF, float, int8_t>::type In;
+    typedef typename std::conditional<XF, Row12f, Row12>::type Rows;
+    const In *const ximg = (XF ? (const In *)prm.xf : (const In *)a.x) + (size_t)n * a.H * a.W * 3;
+    auto stage = [&](int first, int count, const Rows (&rows)[MAXR]) __attribute__((always_inline)) {
+        if constexpr (XF) stem_stage_rows<NW, MAXR, false>(xin, prm.pitch, prm.triples, wave, lane, first, count, rows, prm.scale);
+        else stem_stage_rows<NW, MAXR, false>(xin, prm.pitch, prm.triples, wave, lane, first, count, rows);
+    };
 
-    Row12 pf[MAXR];
-    stem_fetch_rows<NW, MAXR>(a, ximg, prm.triples, wave, lane, 8 * t0 - a.pad, kRowsFirst, pf);
-    stem_stage_rows<NW, MAXR, false>(xin, prm.pitch, prm.triples, wave, lane, 8 * t0 - a.pad, kRowsFirst, pf);
+    Rows pf[MAXR];
+    stem_fetch_rows<NW, MAXR>(a, ximg, prm.triples, wave, lane, 8 * t0 - a.pad, 8, pf);
+    stage(8 * t0 - a.pad, 8, pf);
+    stem_fetch_rows<NW, MAXR>(a, ximg, prm.triples, wave, lane, 8 * t0 - a.pad + 8, kRowsFirst - 8, pf);
+    stage(8 * t0 - a.pad + 8, kRowsFirst - 8, pf);
     __syncthreads();
 
     const int ncb = a.Q >> 4;
@@ -272,7 +281,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4,
             }
         }
         __syncthreads();          // the step's reads of the input ring are done
-        if (has_next) stem_stage_rows<NW, MAXR, false>(xin, prm.pitch, prm.triples, wave, lane, next_first, 8, pf);
+        if (has_next) stage(next_first, 8, pf);
         __syncthreads();          // the next step's input rows are staged
     }
 }
@@ -478,8 +487,12 @@ hipError_t launch_kernel(Kernel k, const StemParams &prm, int threads, size_t ld
 template <int CT, int NW>
 hipError_t launch_plain(const StemParams &prm, size_t lds, hipStream_t st)
 {
-    if (prm.a.R == 7) return launch_kernel(conv_stem_kernel<CT, NW, 7>, prm, NW * 64, lds, st);
-    return launch_kernel(conv_stem_kernel<CT, NW, 3>, prm, NW * 64, lds, st);
+    if (prm.xf) {
+        if (prm.a.R == 7) return launch_kernel(conv_stem_kernel<CT, NW, 7, true>, prm, NW * 64, lds, st);
+        return launch_kernel(conv_stem_kernel<CT, NW, 3, true>, prm, NW * 64, lds, st);
+    }
+    if (prm.a.R == 7) return launch_kernel(conv_stem_kernel<CT, NW, 7, false>, prm, NW * 64, lds, st);
+    return launch_kernel(conv_stem_kernel<CT, NW, 3, false>, prm, NW * 64, lds, st);
 }
 
 template <int CT, bool XF, bool PC>
@@ -502,8 +515,9 @@ hipError_t launch_pool(const StemParams &prm, size_t lds, hipStream_t st)
 // at most 256 pixels and a multiple of 4, the lean epilogue (rounding shifts in [0, 23]: one for the whole layer, or - pooling
 // form only - one per output channel; no accumulator dump).  Alone: output rows a multiple of 16 wide, aligned output.  pool (the output is the 3x3 / 2 /
 // pad 1 max-pooled tensor): an even number of output rows and columns, at most 61 pooled columns.
-bool conv_stem_supports(const ConvArgs &a, bool pool)
+bool conv_stem_supports(const ConvArgs &a, bool pool, bool from_float)
 {
+    if (from_float && !pool && a.K != 32) return false;   // the plain kernel has the registers for float rows at 32 channels only
     if (a.groups != 1 || a.C != 3 || a.stride != 2) return false;
     if (a.R != 3 && a.R != 7) return false;
     if (a.S + (a.pad & 1) > 8 || a.pad > 4) return false;
@@ -529,7 +543,7 @@ bool conv_stem_supports(const ConvArgs &a, bool pool)
 }
 
 // yp == null: the layer itself into a.y.  Otherwise a.y is not used and yp receives the pooled tensor
-// [N, (P - 1) / 2 + 1, (Q - 1) / 2 + 1, K] with ldyp bytes between pixels.  x_float (pooling form only; 16-byte
+// [N, (P - 1) / 2 + 1, (Q - 1) / 2 + 1, K] with ldyp bytes between pixels.  x_float (16-byte
 // aligned): the input as float images, converted to codes at frac_in inside the kernel; a.x is then not read.
 hipError_t launch_conv_stem(const ConvArgs &a, int8_t *yp, int ldyp, hipStream_t st, const float *x_float, int frac_in)
 {

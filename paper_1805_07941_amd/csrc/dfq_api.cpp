@@ -476,7 +476,7 @@ static dfq_status conv_maxpool(const void *x, bool x_is_float, const int8_t *w, 
     } else {
         c.a.x = (const int8_t *)x;
     }
-    if (!conv_stem_supports(c.a, true)) return DFQ_EUNSUPPORTED;
+    if (!conv_stem_supports(c.a, true, x_is_float)) return DFQ_EUNSUPPORTED;
     return from_hip(launch_conv_stem(c.a, y, ldy, (hipStream_t)stream, x_is_float ? (const float *)x : nullptr, fmt_in.frac));
 }
 
@@ -494,6 +494,20 @@ dfq_status dfq_quantize_conv_q_maxpool(const float *x, const int8_t *w, const in
 {
     return conv_maxpool(x, true, w, b, y, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, fmt_w, fmt_out, relu, pool_k,
                         pool_stride, pool_pad, stream);
+}
+
+dfq_status dfq_quantize_conv_q(const float *x, const int8_t *w, const int32_t *b, int8_t *y, int N, int H, int W, int C, int K, int R,
+                               int S, int stride, int pad, int groups, int ldy, dfq_fmt fmt_in, dfq_fmt fmt_w, dfq_fmt fmt_out, int relu,
+                               dfq_stream stream)
+{
+    ConvCheck c = check_conv(nullptr, w, b, y, nullptr, N, H, W, C, K, R, S, stride, pad, groups, ldy, fmt_in, fmt_w, fmt_out, relu, false);
+    if (c.st != DFQ_OK) return c.st;
+    if (!x || !w || !y) return DFQ_EINVAL;
+    if (ldy < K) return DFQ_ESHAPE;
+    if (N == 0) return DFQ_OK;
+    if (overlaps(x, (size_t)N * H * W * C * 4, y, (size_t)N * c.a.P * c.a.Q * (size_t)ldy)) return DFQ_EINVAL;
+    if (((uintptr_t)x & 15) || !conv_stem_supports(c.a, false, true)) return DFQ_EUNSUPPORTED;
+    return from_hip(launch_conv_stem(c.a, nullptr, 0, (hipStream_t)stream, x, fmt_in.frac));
 }
 
 dfq_status dfq_conv_q_pc_maxpool(const int8_t *x, const int8_t *w, const int32_t *b, int8_t *y, int N, int H, int W, int C, int K,

@@ -115,7 +115,7 @@ hipError_t launch_eltwise_np(const int8_t *ah, const int8_t *al, const int8_t *b
 hipError_t launch_np_digits(const uint8_t *codes, size_t n, int p, int8_t *hi, int8_t *lo, hipStream_t st);
 bool conv_smallc_supports(const ConvArgs &a);
 hipError_t launch_conv_smallc(const ConvArgs &a, hipStream_t st);
-bool conv_stem_supports(const ConvArgs &a, bool pool);   // first layers (3 channels, stride 2) the strip kernel takes; pool: with the 3x3/2 max-pool behind it
+bool conv_stem_supports(const ConvArgs &a, bool pool, bool from_float = false);   // first layers (3 channels, stride 2) the strip kernel takes; pool: with the 3x3/2 max-pool behind it
 // y_pooled == null: the layer alone, into a.y.  x_float != null (with y_pooled): float images converted to codes at frac_in on the way in.
 hipError_t launch_conv_stem(const ConvArgs &a, int8_t *y_pooled, int ld_pooled, hipStream_t st, const float *x_float = nullptr,
                             int frac_in = 0);

@@ -204,6 +204,7 @@ class Plan:
         if lazy_joins and not fuse:
             raise ValueError("lazy_joins needs fuse=True")
         self.lazy = bool(lazy_joins)
+        self.fuse_input = bool(fuse)             # the input's conversion may run inside the first layer's kernel
         # conv node index -> add node index
         self.fused: Dict[int, int] = (self._lazy_pairs() if lazy_joins else self._fusable_pairs()) if fuse else {}
         if fuse:
@@ -512,6 +513,22 @@ class Plan:
                 src = nd.srcs[0]
                 N, H, W, Cc = t[src].shape
                 K = nd.K
+                if (self.fuse_input and src == net.input_name and not net.input_is_int8 and input_readers == 1 and calls
+                        and calls[-1][0] is L.dfq_quantize and nd.dst not in self.slice_of):
+                    # the input's conversion inside the first layer's kernel, where the library has one for the call
+                    args = (x.data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(), t[nd.dst].data_ptr(), N, H, W, Cc, K,
+                            nd.R, nd.R, nd.stride, nd.pad, nd.groups, K, f(qz.frac[src]), f(qz.w_frac[nd.name]), f(qz.frac[nd.dst]),
+                            int(nd.relu))
+                    rc = L.dfq_quantize_conv_q(*args, B._stream(None))
+                    if rc == B.OK:
+                        calls.pop()
+                        names.pop()
+                        self._input_in_kernel = True
+                        calls.append((L.dfq_quantize_conv_q, args))
+                        names.append(nd.name)
+                        continue
+                    if rc != B.EUNSUPPORTED:
+                        raise B.DfqError(rc, "dfq_quantize_conv_q")
                 calls.append((L.dfq_conv_q, (t[src].data_ptr(), qz.w[nd.name].data_ptr(), qz.b[nd.name].data_ptr(),
                                              t[nd.dst].data_ptr(), None, N, H, W, Cc, K, nd.R, nd.R, nd.stride, nd.pad,
                                              nd.groups, ldy_of(nd.dst, K), f(qz.frac[src]), f(qz.w_frac[nd.name]), f(qz.frac[nd.dst]),

@@ -167,6 +167,20 @@ def test_conv_q_maxpool_rejects_bad_arguments_before_launching(B):
     assert callf(x=(1 << 20) + 4) == B.EUNSUPPORTED           # images not 16-byte aligned
     assert callf(H=66) == B.EUNSUPPORTED
 
+    # float images into a first layer without pooling
+    def callq(x=1 << 20, y=3 << 20, N=1, K=32, W=64, ldy=None, fo=4):
+        return L.dfq_quantize_conv_q(x, 2 << 20, None, y, N, 64, W, 3, K, 3, 3, 2, 1, 1, K if ldy is None else ldy, f(4), f(7), f(fo), 1, None)
+
+    assert callq(x=None) == B.EINVAL
+    assert callq(y=None) == B.EINVAL
+    assert callq(ldy=16) == B.ESHAPE
+    assert callq(fo=40) == B.EFMT
+    assert callq(y=(1 << 20) + 64) == B.EINVAL                # output inside the images
+    assert callq(N=0) == B.OK
+    assert callq(K=64) == B.EUNSUPPORTED                      # float images: 32 output channels only
+    assert callq(W=72) == B.EUNSUPPORTED                      # 36 output columns
+    assert callq(x=(1 << 20) + 8) == B.EUNSUPPORTED
+
     # one weight format per output channel
     def callpc(fw=4 << 20, lo=3, hi=9, fo=4, fn=L.dfq_conv_q_pc_maxpool):
         return fn(1 << 20, 2 << 20, None, 3 << 20, 1, 64, 64, 3, 64, 7, 7, 2, 3, 1, 64, f(4), fw, lo, hi, f(fo), 1, 3, 2, 1, None)

@@ -732,7 +732,7 @@ def test_quantize_conv_q_maxpool_equals_the_three_calls(B):
     """Float images in: the conversion of Sec. 3 inside the first layer's kernel, against the oracle's quantize, convolution
     and pooling one after the other; values on ties, beyond the clamp, infinities and NaN included."""
     rng = np.random.default_rng(4321)
-    for (N, H, W, K, R, pad), f_in in itertools.product([(3, 224, 224, 64, 7, 3), (2, 60, 96, 64, 7, 3), (2, 64, 64, 32, 3, 1)], [5, 0, -2]):
+    for (N, H, W, K, R, pad), f_in in itertools.product([(3, 224, 224, 64, 7, 3), (2, 60, 96, 64, 7, 3), (2, 64, 64, 32, 3, 1), (2, 224, 224, 32, 3, 1), (1, 60, 96, 32, 7, 3)], [5, 0, -2]):
         x = (rng.standard_normal((N, H, W, 3)) * 2.0 ** (2 - f_in)).astype(np.float32)
         x.reshape(-1)[::7] = np.rint(x.reshape(-1)[::7] * 2.0 ** f_in) * 2.0 ** -f_in + 0.5 * 2.0 ** -f_in      # exact ties
         x.reshape(-1)[5::1001] = np.float32(np.inf)
@@ -757,6 +757,11 @@ def test_quantize_conv_q_maxpool_equals_the_three_calls(B):
             p = B.conv_q_maxpool(xin, dev(w), dev(b), f_in, dev(fw), f_out, 2, pad, True, frac_w_range=(int(fw.min()), int(fw.max())))
             assert p is not None
             assert np.array_equal(host(p), p_pc_ref), (N, H, W, K, R, f_in, str(xin.dtype))
+        # without the pooling: the library has a kernel for float images at 32 output channels
+        y = B.quantize_conv_q(dev(x), dev(w), dev(b), f_in, f_w, f_out, 2, pad, True)
+        assert (y is not None) == (K == 32 and (W // 2) % 16 == 0)
+        if y is not None:
+            assert np.array_equal(host(y), y_ref), (N, H, W, K, R, f_in)
         # a channel whose shift leaves the lean range: no fused kernel
         assert B.conv_q_maxpool(dev(xq), dev(w), dev(b), f_in, dev(fw), f_out, 2, pad, True,
                                 frac_w_range=(int(fw.min()), int(fw.max()) + 1)) is None
