@@ -61,7 +61,7 @@ def cmd_stats(a):
     tr.sort(key=lambda r: int(r["Start_Timestamp"]))
     # a pass begins with the conversion of the input images: a kernel of its own, or the first layer's kernel where that
     # takes the float images itself (the launches with the largest grid are the full-batch ones)
-    first = "conv_stem_pool_kernel" if any("conv_stem_pool_kernel" in r["Kernel_Name"] and ", true>" in r["Kernel_Name"] for r in tr) else "quantize_vec4"
+    first = "conv_stem_pool_kernel" if any(re.search(r"conv_stem_pool_kernel<\d+, \d+, true", r["Kernel_Name"]) for r in tr) else "quantize_vec4"
     starts = [i for i, r in enumerate(tr) if first in r["Kernel_Name"]]
     big = max(int(tr[i]["Grid_Size_X"]) for i in starts)
     starts = [i for i in starts if int(tr[i]["Grid_Size_X"]) == big]
