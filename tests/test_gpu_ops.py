@@ -660,7 +660,8 @@ def test_lean_epilogue_shift_edges(B, s):
         assert np.array_equal(host(y), ref), (N, H, W, C, K, R, s, "per channel")
 
 
-@pytest.mark.parametrize("sa,sb,add_shift", [(22, 0, 23), (0, 22, 23), (21, 0, 22), (0, 21, 23), (0, 0, 23), (1, 0, 0), (0, 1, 1)])
+@pytest.mark.parametrize("sa,sb,add_shift", [(22, 0, 23), (0, 22, 23), (21, 0, 22), (0, 21, 23), (0, 0, 23), (1, 0, 0), (0, 1, 1),
+                                             (0, 0, 0), (0, 0, 1), (0, 0, 2)])
 def test_fused_add_alignment_and_shift_edges(B, sa, sb, add_shift):
     """dfq_conv_q_add / dfq_conv_q_pc_add with the alignment shifts of Eq. 10 at their largest (21, 22) and the final
     rounding shift at the end of the lean range (23): against the oracle's convolution followed by its add."""
@@ -668,6 +669,11 @@ def test_fused_add_alignment_and_shift_edges(B, sa, sb, add_shift):
     N, H, W, C, K = 2, 21, 19, 128, 256
     x, w, b, other, s = _scaled_pointwise_case(rng, N, H, C, K)
     x = x[:, :, :W].copy(); other = other[:, :, :W].copy()
+    # channels 0 and 1 saturate at both ends whatever the input, and meet the extreme codes of the other operand:
+    # sums of -255 and 254 in the join's accumulator
+    b[0], b[1] = -2 ** 30, 2 ** 30
+    other[:, ::2, :, 0], other[:, 1::2, :, 0] = -128, 127
+    other[:, ::2, :, 1], other[:, 1::2, :, 1] = 127, -128
     F = 22                                   # the finer of the two scales
     f_mid, f_other, f_out = F - sa, F - sb, F - add_shift
     f_in = 4
