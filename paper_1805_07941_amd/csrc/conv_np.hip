@@ -447,6 +447,64 @@ __global__ void __launch_bounds__(256) maxpool3_np_kernel(NpPoolParams a)
     }
 }
 
+// The same for C a multiple of 16 when only the digit planes are wanted: one lane per 16 channels of an output pixel,
+// 16-byte loads.  beta = 64 h + l with both digits of beta's sign orders like the pair (h, l), so the maximum is taken
+// on 16-bit keys (h in the high byte, l with its sign bit flipped in the low byte: signed order of the key = order of
+// beta), two keys per packed instruction - no value is decoded.  Window positions outside the image are replaced by
+// the nearest one inside, which lies in the same window.
+struct NpMaxPool3Params {
+    NpPoolParams a;
+    int total;              // N * P * Q * C / 16
+    FastDiv div_cv, div_q, div_p;
+};
+
+__global__ void __launch_bounds__(256) maxpool3_np16_kernel(NpMaxPool3Params prm)
+{
+    typedef short v2s __attribute__((ext_vector_type(2)));
+    const NpPoolParams &a = prm.a;
+    const int cv = a.C / 16;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < prm.total; i += gridDim.x * 256) {
+        const int px = fastdiv(i, prm.div_cv);
+        const int c = (i - px * cv) * 16;
+        const int t = fastdiv(px, prm.div_q);
+        const int q = px - t * a.Q;
+        const int n = fastdiv(t, prm.div_p);
+        const int p = t - n * a.P;
+        v2s best[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) best[e] = v2s{(short)-32768, (short)-32768};
+#pragma unroll
+        for (int r = 0; r < 3; r++) {
+            const int ih = min(max(2 * p - 1 + r, 0), a.H - 1);
+#pragma unroll
+            for (int s2 = 0; s2 < 3; s2++) {
+                const int iw = min(max(2 * q - 1 + s2, 0), a.W - 1);
+                const size_t o = (((size_t)n * a.H + ih) * a.W + iw) * a.C + c;
+                const uint4 h4 = *(const uint4 *)(a.xh + o), l4 = *(const uint4 *)(a.xl + o);
+                const uint32_t hw[4] = {h4.x, h4.y, h4.z, h4.w}, lw[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const uint32_t lx = lw[e] ^ 0x80808080u;
+                    const uint32_t k01 = __builtin_amdgcn_perm(hw[e], lx, 0x05010400u);     // {l0, h0, l1, h1}
+                    const uint32_t k23 = __builtin_amdgcn_perm(hw[e], lx, 0x07030602u);     // {l2, h2, l3, h3}
+                    best[2 * e] = __builtin_elementwise_max(best[2 * e], __builtin_bit_cast(v2s, k01));
+                    best[2 * e + 1] = __builtin_elementwise_max(best[2 * e + 1], __builtin_bit_cast(v2s, k23));
+                }
+            }
+        }
+        uint32_t oh[4], ol[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const uint32_t k01 = __builtin_bit_cast(uint32_t, best[2 * e]), k23 = __builtin_bit_cast(uint32_t, best[2 * e + 1]);
+            oh[e] = __builtin_amdgcn_perm(k23, k01, 0x07050301u);                           // {h0, h1, h2, h3}
+            ol[e] = __builtin_amdgcn_perm(k23, k01, 0x06040200u) ^ 0x80808080u;             // {l0, l1, l2, l3}
+        }
+        const size_t oo = (size_t)px * a.C + c;
+        if (a.yh) *(uint4 *)(a.yh + oo) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+        if (a.yl) *(uint4 *)(a.yl + oo) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+    }
+}
+
 // ---- space-to-depth packing of a stride-2 first layer with few channels -------------------------------------------------
 // A stride-2 convolution with an R x S kernel (R, S <= 8) over C <= 4 channels is a stride-1 convolution with a
 // ceil(R/2) x ceil(S/2) kernel over the 2 x 2 space-to-depth image with 4 C channels.  With 16 bytes per such pixel
@@ -944,7 +1002,15 @@ hipError_t launch_pool_np(const int8_t *xh, const int8_t *xl, uint8_t *y, int8_t
     NpPoolParams a{xh, xl, y, yh, yl, N, H, W, C, k, stride, pad, P, Q, p_fmt, beta_max, avg};
     const uintptr_t al4 = (uintptr_t)xh | (uintptr_t)xl | (uintptr_t)y | (uintptr_t)yh | (uintptr_t)yl;
     const size_t total = (size_t)N * P * Q * C;
-    if (!avg && k == 3 && stride == 2 && pad == 1 && C % 4 == 0 && (al4 & 3) == 0)
+    if (!avg && k == 3 && stride == 2 && pad == 1 && !y && C % 16 == 0 && (al4 & 15) == 0 && total / 16 < (1u << 31)) {
+        NpMaxPool3Params prm;
+        prm.a = a;
+        prm.total = (int)(total / 16);
+        prm.div_cv = make_fastdiv(C / 16);
+        prm.div_q = make_fastdiv(Q);
+        prm.div_p = make_fastdiv(P);
+        maxpool3_np16_kernel<<<grid_for(total / 16), 256, 0, st>>>(prm);
+    } else if (!avg && k == 3 && stride == 2 && pad == 1 && C % 4 == 0 && (al4 & 3) == 0)
         maxpool3_np_kernel<<<grid_for(total / 4), 256, 0, st>>>(a);
     else
         pool_np_kernel<<<grid_for(total), 256, 0, st>>>(a);

@@ -81,6 +81,12 @@ def test_pool_np_against_oracle(B, p):
         torch.cuda.synchronize()
         assert np.array_equal(host(y), ry), (shape, mode)
         assert np.array_equal(beta_of((yh, yl)), rbeta)
+    # digit planes only, channels a multiple of 16: the kernel that takes the maximum on (h, l) keys without decoding
+    for shape in [(2, 13, 11, 64), (3, 57, 58, 32), (1, 8, 8, 16), (2, 112, 112, 64)]:
+        x = rng.integers(0, 256, shape).astype(np.uint8)
+        _, rbeta = NC.pool_np(x, (8, p), "max", 3, 2, 1)
+        _, yh, yl = B.pool_np(*planes(B, x, p), "max", 3, 2, 1, p, want_codes=False)
+        assert np.array_equal(beta_of((yh, yl)), rbeta), shape
     # exact ties of the mean (oracle pin: test_average_pool_ties)
     enc = lambda v: F.encode(v, 8, 4)
     if p == 4:
