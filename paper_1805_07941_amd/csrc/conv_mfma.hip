@@ -627,11 +627,13 @@ hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st)
     // else:    256 x 128 tiles (eight wavefronts), two workgroups per CU, for kernels larger than 1x1;
     //          for 1x1 kernels (few items per tile) 128 x 128 tiles (four wavefronts), three per CU.
     const bool pointwise = a.R == 1 && a.S == 1;
-    // very few pixels (fully connected layers): 64 x 64 tiles, wavefronts of 32 x 32, so that the channel
-    // tiles alone spread over more compute units; every workgroup walks the whole reduction alone, one short step
-    // at a time, so the ring is six stages deep (2048 -> 1000 at batch 256: 20 -> 10.6 us against three with the
-    // weights in L2, 20.6 -> 18.7 us inside the network pass where they come from HBM)
-    if ((long long)a.N * a.P * a.Q <= 1024 && a.K > 64) return launch_cfg<64, 64, 2, 2, 6, 2>(a, st);
+    // very few pixels (fully connected layers): one wavefront per 32 x 32 tile, each with its own deep ring and no
+    // barrier, where that kernel applies (unpadded 1x1, whole 64-byte steps); else 64 x 64 tiles, wavefronts of 32 x 32,
+    // so that the channel tiles alone spread over more compute units, with a ring six stages deep
+    if ((long long)a.N * a.P * a.Q <= 1024 && a.K > 64) {
+        if (conv_fc_supports(a)) return launch_conv_fc(a, st);
+        return launch_cfg<64, 64, 2, 2, 6, 2>(a, st);
+    }
     // one weight format per output channel: the tile shapes for which that epilogue is built
     if (a.frac_w && a.K > 64) return launch_cfg<128, 128, 2, 2, 3, 3>(a, st);
     if (a.K <= 64) return pointwise ? launch_cfg<256, 64, 4, 1, 3, 2>(a, st) : launch_cfg<256, 64, 4, 1, 2, 3>(a, st);

@@ -89,6 +89,8 @@ hipError_t launch_conv_direct(const ConvArgs &a, hipStream_t st);
 bool conv_mfma_supports(const ConvArgs &a);
 bool conv_mfma_fuses(const ConvArgs &a);     // a.add set: the dense kernel has a fused form for this call
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st);
+bool conv_fc_supports(const ConvArgs &a);       // unpadded 1x1 layers over at most 1024 pixels: one wavefront per 32 x 32 tile
+hipError_t launch_conv_fc(const ConvArgs &a, hipStream_t st);
 bool conv_depthwise_supports(const ConvArgs &a);
 hipError_t launch_conv_depthwise(const ConvArgs &a, hipStream_t st);
 bool conv_dwm_supports(const ConvArgs &a);      // depthwise layers the matrix-core form takes

@@ -133,6 +133,7 @@ CONV_SHAPES = [
     (2, 8, 8, 128, 96, 3, 3, 2, 1, 1),
     (1, 7, 7, 512, 200, 1, 1, 1, 0, 1),
     (5, 1, 1, 256, 100, 1, 1, 1, 0, 1),          # fully connected
+    (40, 1, 1, 1024, 1000, 1, 1, 1, 0, 1),       # fully connected: the one-wavefront-per-tile kernel
     (1, 20, 20, 3, 32, 3, 3, 2, 1, 1),           # stem-like
     (1, 23, 23, 3, 64, 7, 7, 2, 3, 1),           # stem-like 7x7
     (2, 72, 72, 3, 64, 7, 7, 2, 3, 1),           # stem-like, rows long enough for the row-staging kernel
@@ -177,6 +178,12 @@ CONV_SHAPES = [
     (1, 3, 3, 64, 256, 1, 1, 1, 0, 1),           # fewer pixels than one tile
     (1, 10, 10, 128, 1088, 1, 1, 1, 0, 1),       # K a multiple of 64 only and large: one workgroup per CU for LDS
     (1, 9, 9, 512, 128, 1, 1, 1, 0, 1),          # C too large for it: general dense kernel
+    # at most 1024 pixels, unpadded 1x1, whole 64-byte steps: one wavefront per 32 x 32 tile, a ring of twelve steps
+    (256, 1, 1, 2048, 1000, 1, 1, 1, 0, 1),      # the classifier at full batch: 8 x 32 tiles, channel tail of eight
+    (33, 1, 1, 832, 1000, 1, 1, 1, 0, 1),        # a pixel tile with one row; thirteen steps: one refill of the ring
+    (5, 1, 1, 64, 72, 1, 1, 1, 0, 1),            # a single step
+    (7, 3, 3, 192, 130, 1, 1, 1, 0, 1),          # 63 pixels, channel tail of two
+    (2, 16, 32, 768, 96, 1, 1, 1, 0, 1),         # 1024 pixels: 32 x 3 tiles, twelve steps: the ring exactly
     # 3x3 stride 1 pad 1 with whole channel chunks on degenerate images
     (2, 9, 7, 128, 128, 3, 3, 1, 1, 1),          # image rows much shorter than a tile
     (5, 3, 1, 64, 64, 3, 3, 1, 1, 1),            # one column: every pixel is at both borders
@@ -255,6 +262,22 @@ def test_conv_q_writes_into_a_channel_slice(B):
         got = host(wide)
         assert np.array_equal(got[..., 20:68], y_ref)
         assert np.all(got[..., :20] == 99) and np.all(got[..., 68:] == 99)
+
+
+def test_fully_connected_into_a_row_slice_of_odd_pitch(B):
+    """The kernel for very few pixels writing rows of 1000 channels at a pitch that is not a multiple of 16, from an
+    offset that is not one either: whole and partial 16-channel groups, aligned and not."""
+    rng = np.random.default_rng(104)
+    x, w, b = _rand_conv(rng, 37, 1, 1, 512, 1000, 1, 1, 1)
+    wide = torch.full((37, 1, 1, 1012), 99, dtype=torch.int8, device=DEV)
+    y_ref, _ = orc.conv_q(x, w, b, 4, 7, -3, 1, 0, 1, False)
+    assert (np.abs(y_ref) == 127).mean() < 0.1
+    for v in (B.CONV_AUTO, B.CONV_MFMA):
+        wide.fill_(99)
+        B.conv_q(dev(x), dev(w), dev(b), 4, 7, -3, 1, 0, 1, False, out=wide.view(-1)[7:], ldy=1012, variant=v)
+        got = host(wide)
+        assert np.array_equal(got[..., 7:1007], y_ref)
+        assert np.all(got[..., :7] == 99) and np.all(got[..., 1007:] == 99)
 
 
 def test_conv_q_shift_extremes(B):
@@ -383,6 +406,7 @@ PC_SHAPES = [
     (1, 8, 8, 16, 32, 3, 3, 1, 1, 4),            # grouped
     (2, 19, 17, 128, 256, 3, 3, 2, 1, 16),       # grouped, stride 2
     (5, 1, 1, 256, 100, 1, 1, 1, 0, 1),          # fully connected
+    (40, 1, 1, 1024, 1000, 1, 1, 1, 0, 1),       # fully connected: the one-wavefront-per-tile kernel
     (4, 223, 224, 64, 256, 1, 1, 2, 0, 1),       # enough tiles for the dense kernel's largest tile shape
 ]
 
