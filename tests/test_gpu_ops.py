@@ -150,6 +150,11 @@ CONV_SHAPES = [
     (1, 14, 14, 64, 64, 3, 3, 2, 1, 64),         # stride 2, even size
     (1, 12, 20, 64, 64, 3, 3, 1, 0, 64),         # no padding
     (1, 1, 1, 64, 64, 3, 3, 1, 1, 64),           # one pixel: eight of nine taps are padding
+    # stride 1 with at least four patches per workgroup of a full grid: every workgroup streams its patches through two buffers
+    (128, 45, 52, 96, 96, 3, 3, 1, 1, 96),       # blocks of 32 channels: 9216 units on 1791 workgroups
+    (100, 41, 50, 128, 128, 3, 3, 1, 1, 128),    # two blocks of 64 channels, ragged last patch row and column: 4800 units on 1024
+    (400, 30, 40, 64, 64, 3, 3, 1, 0, 64),       # no padding
+    (800, 20, 30, 64, 64, 3, 3, 1, 2, 64),       # padding of two: outputs outnumber inputs
     (1, 40, 33, 32, 32, 3, 3, 1, 1, 32),         # 32 channels: two pixels per LDS row
     (2, 21, 35, 96, 96, 3, 3, 2, 1, 96),         # three blocks of 32 channels, stride 2
     (1, 8, 8, 16, 32, 3, 3, 1, 1, 4),            # grouped
