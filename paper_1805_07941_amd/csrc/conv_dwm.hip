@@ -207,9 +207,14 @@ __global__ void __launch_bounds__(256) conv_dwm_stream_kernel(DwmParams prm)
         const int per = G / 8, rem = G % 8, xcd = lb % 8, idx = lb / 8;
         lb = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
     }
-    const int sp0 = fastdiv(lb, prm.div_bc);
-    const int cb = lb - sp0 * prm.blocks_c;
-    const int sp_step = fastdiv(G, prm.div_bc);
+    const int wg = fastdiv(lb, prm.div_bc);
+    const int cb = lb - wg * prm.blocks_c;
+    const int nwg = fastdiv(G, prm.div_bc);
+    // contiguous, equally long runs of patches: an XCD then owns one contiguous part of the layer, as in the kernels
+    // before and behind it (with every nwg-th patch instead, the pointwise layer behind a 14 x 14 layer was 3 us slower)
+    const int sp0 = (int)((long long)wg * prm.patches / nwg);
+    const int sp_end = (int)((long long)(wg + 1) * prm.patches / nwg);
+    constexpr int sp_step = 1;
 
     const v4i x_rsrc = make_rsrc(a.x, prm.x_bytes);
     const __amdgpu_buffer_rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, (int)prm.y_bytes, 0x00020000);
@@ -255,7 +260,7 @@ __global__ void __launch_bounds__(256) conv_dwm_stream_kernel(DwmParams prm)
 
     int sp = sp0;
     Pos cur = locate(min(sp, prm.patches - 1));
-    if (sp < prm.patches) issue(cur, 0);
+    if (sp < sp_end) issue(cur, 0);
     DwmLane<ST, CB> ln;
     ln.init(a, cb, lane);
     Requant rq;
@@ -264,7 +269,7 @@ __global__ void __launch_bounds__(256) conv_dwm_stream_kernel(DwmParams prm)
     const unsigned lane_yoff = lane < 16 * NQ ? (unsigned)((lane / NQ) * a.ldy + cb * CB + 16 * (lane % NQ)) : kOutOfRange;
 
     int nst = 0;                       // stores this wavefront issued in the previous iteration
-    for (int k = 0; sp < prm.patches; k++, sp += sp_step) {
+    for (int k = 0; sp < sp_end; k++, sp += sp_step) {
         // this patch's loads are older than those stores, and nothing else is younger
         switch (nst) {
             case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
@@ -274,7 +279,7 @@ __global__ void __launch_bounds__(256) conv_dwm_stream_kernel(DwmParams prm)
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         const int buf = k & 1;
         Pos next = cur;
-        if (sp + sp_step < prm.patches) {
+        if (sp + sp_step < sp_end) {
             next = locate(sp + sp_step);
             issue(next, buf ^ 1);
         }
@@ -353,12 +358,12 @@ hipError_t launch_conv_dwm(const ConvArgs &a, hipStream_t st)
     prm.div_tx = make_fastdiv(prm.tiles_x);
     prm.div_ty = make_fastdiv(prm.tiles_y);
     const long long blocks = (long long)a.N * prm.tiles_y * prm.tiles_x * prm.blocks_c;
-    // stride 1, 31-bit output offsets and at least four patches for every workgroup of a full grid: the streaming form.
+    // stride 1, 31-bit output offsets and at least two patches for every workgroup of a full grid: the streaming form.
     // (MobileNet-shaped pass at batch 128, same box: 112 x 112 x 32 37.9 -> 31.4 us, 56 x 56 x 128 38 -> 32.5,
-    // 28 x 28 x 256 24.4 -> 22.4; with two patches per workgroup - 14 x 14 x 512 - it was slower, 15 -> 20 us.)
+    // 28 x 28 x 256 24.4 -> 22.4, 14 x 14 x 512 - two patches per workgroup - 15.2 -> 14.3.)
     const long long y_bytes = (long long)a.N * a.P * a.Q * a.ldy;
-    const long long min_units = 4LL * (CB == 64 ? kDwmStreamPerCU<64> : kDwmStreamPerCU<32>) * kNumCU;
-    if (a.stride == 1 && y_bytes < (1LL << 31) && blocks >= min_units && min_units >= 4LL * prm.blocks_c) {
+    const long long min_units = 2LL * (CB == 64 ? kDwmStreamPerCU<64> : kDwmStreamPerCU<32>) * kNumCU;
+    if (a.stride == 1 && y_bytes < (1LL << 31) && blocks >= min_units && min_units >= 2LL * prm.blocks_c) {
         prm.patches = a.N * prm.tiles_y * prm.tiles_x;
         prm.y_bytes = (unsigned)y_bytes;
         return CB == 64 ? launch_dwm_stream<64>(prm, st) : launch_dwm_stream<32>(prm, st);
