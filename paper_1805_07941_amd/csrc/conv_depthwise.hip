@@ -31,7 +31,11 @@ struct DwParams {
     FastDiv div_cw, div_qb, div_p;
 };
 
-template <int R, int S, int ST, int TW>
+// OWN: the grid's stride over the items is a multiple of C / 4, so a lane meets the same four channels in every item:
+// it fetches their 36 weight bytes itself (nine words) and keeps the row words in registers - no gather of all
+// channels' weights into LDS in front of a block's first item, which for layers of few pixels and many channels
+// (7 x 7 x 1024) took as long as the items.
+template <int R, int S, int ST, int TW, bool OWN>
 __global__ void __launch_bounds__(kThreads) conv_depthwise_kernel(DwParams prm)
 {
     static_assert(S == 3 && (ST == 1 || ST == 2), "windows of three taps inside eight columns");
@@ -40,7 +44,24 @@ __global__ void __launch_bounds__(kThreads) conv_depthwise_kernel(DwParams prm)
     extern __shared__ uint32_t wt[];        // [R][C] words: (w[c][r][0], w[c][r][1], w[c][r][2], 0)
 
     const ConvArgs &a = prm.a;
-    for (int c = threadIdx.x; c < a.C; c += kThreads) {
+    uint32_t wown[R][4];                    // OWN: (w[c+e][r][0], w[c+e][r][1], w[c+e][r][2], 0) of the lane's channels c .. c+3
+    if constexpr (OWN) {
+        static_assert(R == 3 && S == 3, "36 weight bytes per lane");
+        const int cwi = (int)((blockIdx.x * (unsigned)kThreads + threadIdx.x) % (unsigned)prm.cw);
+        const uint32_t *wp = (const uint32_t *)(a.w + (size_t)cwi * 36);
+        uint32_t d[10];
+#pragma unroll
+        for (int i = 0; i < 9; i++) d[i] = wp[i];
+        d[9] = 0;
+#pragma unroll
+        for (int r = 0; r < R; r++)
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const int k = 9 * e + 3 * r;    // first of the three bytes
+                wown[r][e] = __builtin_amdgcn_alignbyte(d[(k >> 2) + 1], d[k >> 2], k & 3) & 0x00ffffffu;
+            }
+    }
+    for (int c = threadIdx.x; !OWN && c < a.C; c += kThreads) {
         // the channel's R*S weight bytes, all loads in flight together
         uint32_t wb[R * S];
 #pragma unroll
@@ -91,8 +112,14 @@ __global__ void __launch_bounds__(kThreads) conv_depthwise_kernel(DwParams prm)
         }
 #pragma unroll
         for (int r = 0; r < R; r++) {
-            const uint4 wq = *(const uint4 *)(wt + r * a.C + c);
-            const uint32_t wrow[4] = {wq.x, wq.y, wq.z, wq.w};
+            uint32_t wrow[4];
+            if constexpr (OWN) {
+#pragma unroll
+                for (int e = 0; e < 4; e++) wrow[e] = wown[r][e];
+            } else {
+                const uint4 wq = *(const uint4 *)(wt + r * a.C + c);
+                wrow[0] = wq.x; wrow[1] = wq.y; wrow[2] = wq.z; wrow[3] = wq.w;
+            }
             // columns 0-3 transposed: lo[e] = (x0.e, x1.e, x2.e, x3.e); columns 4-5: hi[e] = (x4.e, x5.e, 0, 0)
             const uint32_t ab_l = __builtin_amdgcn_perm(xw[r][1], xw[r][0], 0x05010400u), ab_h = __builtin_amdgcn_perm(xw[r][1], xw[r][0], 0x07030602u);
             const uint32_t cd_l = __builtin_amdgcn_perm(xw[r][3], xw[r][2], 0x05010400u), cd_h = __builtin_amdgcn_perm(xw[r][3], xw[r][2], 0x07030602u);
@@ -152,10 +179,24 @@ hipError_t launch_dw(const ConvArgs &a, hipStream_t st)
     prm.div_qb = make_fastdiv(prm.qblocks);
     prm.div_p = make_fastdiv(a.P);
     long long blocks = (items + kThreads - 1) / kThreads;
-    if (blocks > 256 * 8) blocks = 256 * 8;   // every block first gathers the weights of all channels: few, long-lived blocks
+    if (blocks > 256 * 8) blocks = 256 * 8;
     if (blocks < 1) blocks = 1;
+    // a lane keeps its channels when blocks * kThreads is a multiple of C / 4: C / 4 a divisor of the block size, or a
+    // multiple of it with the grid rounded down to whole sets of channels
+    if (((uintptr_t)a.w & 3) == 0) {
+        if (kThreads % prm.cw == 0) {
+            conv_depthwise_kernel<R, S, ST, TW, true><<<(unsigned)blocks, kThreads, 0, st>>>(prm);
+            return hipGetLastError();
+        }
+        if (prm.cw % kThreads == 0 && blocks >= prm.cw / kThreads) {
+            blocks -= blocks % (prm.cw / kThreads);
+            conv_depthwise_kernel<R, S, ST, TW, true><<<(unsigned)blocks, kThreads, 0, st>>>(prm);
+            return hipGetLastError();
+        }
+    }
+    // otherwise every block first gathers the weights of all channels: few, long-lived blocks
     size_t lds = (size_t)R * a.C * 4;
-    conv_depthwise_kernel<R, S, ST, TW><<<(unsigned)blocks, kThreads, lds, st>>>(prm);
+    conv_depthwise_kernel<R, S, ST, TW, false><<<(unsigned)blocks, kThreads, lds, st>>>(prm);
     return hipGetLastError();
 }
 

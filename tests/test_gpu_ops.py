@@ -142,6 +142,8 @@ CONV_SHAPES = [
     (2, 10, 10, 32, 32, 3, 3, 1, 1, 32),         # depthwise
     (2, 11, 9, 64, 64, 3, 3, 2, 1, 64),          # depthwise stride 2
     (1, 9, 9, 24, 24, 3, 3, 1, 1, 24),           # depthwise, C % 16 != 0
+    (9, 7, 7, 1024, 1024, 3, 3, 1, 1, 1024),     # depthwise, few pixels and C / 4 = the block size: every lane keeps its own weights
+    (9, 7, 7, 2048, 2048, 3, 3, 2, 1, 2048),     # C / 4 twice the block size: the grid in whole sets of channels
     # depthwise with whole blocks of 64 channels: the matrix-core form (patches of 8 x 16 outputs)
     (2, 19, 37, 64, 64, 3, 3, 1, 1, 64),         # ragged patches in both directions
     (1, 16, 16, 128, 128, 3, 3, 1, 1, 128),      # exactly two patch rows, one patch column, two channel blocks
