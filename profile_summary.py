@@ -35,7 +35,7 @@ def short(name: str) -> str:
 
 
 def is_conv(name: str) -> bool:
-    return "conv_mfma_kernel" in name or "conv_pw_kernel" in name
+    return "conv_mfma_kernel" in name or "conv_pw_kernel" in name or "conv_fc_kernel" in name
 
 
 def cmd_stats(a):
