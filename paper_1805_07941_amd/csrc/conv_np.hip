@@ -543,6 +543,52 @@ __global__ void __launch_bounds__(256) stem_pack_x_kernel(const int8_t *x, int8_
     }
 }
 
+// The same packing with word loads, for inputs below 2^31 bytes: the 2 C bytes a piece takes from one image row - the
+// pixels 2 (q + s') - pad and the next one - are contiguous there, so each row's share is cut out of three aligned words
+// (range-checked buffer loads: words past the end read as zero) and masked by which of the two pixels exist.
+__global__ void __launch_bounds__(256) stem_pack_x_words_kernel(const int8_t *x, int8_t *y, int N, int H, int W, int C, int pad, int Hs, int Qs)
+{
+    const size_t total = (size_t)N * Hs * Qs * 4;                   // one lane per 16-byte piece: (pixel, s')
+    // (the range rounded up to whole words: x is word-aligned, so the word that holds the last byte lies in the same page)
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(x), 0, (N * H * W * C + 3) & ~3, 0x00020000);
+    const unsigned long long pixel_mask = (1ULL << (8 * C)) - 1ULL;  // C <= 4
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int sp = (int)(i & 3);
+        const size_t pix = i >> 2;
+        const int q = (int)(pix % Qs);
+        const size_t t = pix / Qs;
+        const int ii = (int)(t % Hs);
+        const int n = (int)(t / Hs);
+        const int iw0 = 2 * (q + sp) - pad;
+        const bool first = iw0 >= 0 && iw0 < W, second = iw0 + 1 >= 0 && iw0 + 1 < W;
+        unsigned long long part[2];                                 // the 2 C bytes of rows dy = 0, 1
+#pragma unroll
+        for (int dy = 0; dy < 2; dy++) {
+            const int ih = 2 * ii + dy - pad;
+            part[dy] = 0;
+            if (ih < 0 || ih >= H || !(first || second)) continue;
+            // eight bytes from the first existing pixel on
+            const int o = ((n * H + ih) * W + (first ? iw0 : iw0 + 1)) * C;
+            const int a = o & ~3, sh = o & 3;
+            const uint32_t d0 = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(xr, a, 0, 0);
+            const uint32_t d1 = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(xr, a + 4, 0, 0);
+            const uint32_t d2 = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(xr, a + 8, 0, 0);
+            const unsigned long long v = (unsigned long long)__builtin_amdgcn_alignbyte(d1, d0, sh) |
+                                         ((unsigned long long)__builtin_amdgcn_alignbyte(d2, d1, sh) << 32);
+            if (first) part[dy] = (v & pixel_mask) | (second ? v & (pixel_mask << (8 * C)) : 0ULL);
+            else part[dy] = (v & pixel_mask) << (8 * C);            // only the second pixel exists: it is the one loaded
+        }
+        // bytes 0 .. 2C-1 from row 0, 2C .. 4C-1 from row 1, zeros behind
+        unsigned long long lo = part[0], hi = 0;
+        if (C == 4) hi = part[1];
+        else {
+            lo |= part[1] << (16 * C);
+            hi = part[1] >> (64 - 16 * C);
+        }
+        ((uint4 *)y)[i] = make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
+    }
+}
+
 // y[k][r'][16 s' + (2 dy + dx) C + c] = w[k][2 r' + dy][2 s' + dx][c] where that tap exists, else 0; r' = 0..3.
 __global__ void __launch_bounds__(256) stem_pack_w_kernel(const int8_t *w, int8_t *y, int K, int R, int S, int C)
 {
@@ -1019,7 +1065,10 @@ hipError_t launch_pool_np(const int8_t *xh, const int8_t *xl, uint8_t *y, int8_t
 
 hipError_t launch_stem_pack_x(const int8_t *x, int8_t *y, int N, int H, int W, int C, int pad, int Hs, int Qs, hipStream_t st)
 {
-    stem_pack_x_kernel<<<grid_for((size_t)N * Hs * Qs * 4), 256, 0, st>>>(x, y, N, H, W, C, pad, Hs, Qs);
+    if ((long long)N * H * W * C < (1LL << 31) - 16 && ((uintptr_t)x & 3) == 0)
+        stem_pack_x_words_kernel<<<grid_for((size_t)N * Hs * Qs * 4), 256, 0, st>>>(x, y, N, H, W, C, pad, Hs, Qs);
+    else
+        stem_pack_x_kernel<<<grid_for((size_t)N * Hs * Qs * 4), 256, 0, st>>>(x, y, N, H, W, C, pad, Hs, Qs);
     return hipGetLastError();
 }
 
