@@ -624,7 +624,7 @@ hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st)
     //          traffic per matrix instruction and half the re-reads of the input (4-12 % faster on
     //          the 14x14 layers and the strided 1x1 shortcuts; with fewer tiles too many CUs stay
     //          idle, and strided 3x3 layers were 8 % slower);
-    // else:    256 x 128 tiles (eight wavefronts), two workgroups per CU, for kernels larger than 1x1;
+    // else:    256 x 128 tiles (eight wavefronts), two workgroups per CU, for kernels larger than 1x1 with enough of them;
     //          for 1x1 kernels (few items per tile) 128 x 128 tiles (four wavefronts), three per CU.
     const bool pointwise = a.R == 1 && a.S == 1;
     // very few pixels (fully connected layers): one wavefront per 32 x 32 tile, each with its own deep ring and no
@@ -641,6 +641,11 @@ hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st)
         const long long M = (long long)a.N * a.P * a.Q;
         if ((M + 255) / 256 * (a.K / 256) >= 192) return launch_cfg<256, 256, 4, 2, 3, 1>(a, st);
     }
+    // kernels larger than 1x1 whose 256 x 128 tiles would occupy at most half of the compute units: 128 x 128 tiles, twice as
+    // many workgroups (7 x 7 x 512 -> 512, 3x3, at batch 128: 34.0 -> 28.5 us; at batch 256, with 196 such tiles, the
+    // smaller tiles were slower, 39.7 -> 45.8 us)
+    if (!pointwise && ((long long)a.N * a.P * a.Q + 255) / 256 * ((a.K + 127) / 128) <= kNumCU / 2)
+        return launch_cfg<128, 128, 2, 2, 3, 3>(a, st);
     return pointwise ? launch_cfg<128, 128, 2, 2, 3, 3>(a, st) : launch_cfg<256, 128, 4, 2, 3, 2>(a, st);
 }
 

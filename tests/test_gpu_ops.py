@@ -176,6 +176,7 @@ CONV_SHAPES = [
     (3, 29, 31, 192, 192, 3, 3, 1, 1, 24),       # three channel blocks, ragged last pixel tile
     (1, 33, 31, 16, 16, 3, 3, 1, 0, 1),          # no padding
     (1, 40, 40, 64, 256, 3, 3, 1, 1, 1),         # several tiles in both GEMM dimensions
+    (9, 64, 64, 64, 128, 3, 3, 1, 1, 1),         # 144 tiles of 256 x 128: more than half the compute units, so that tile shape
     # unpadded 1x1 stride 1: the input-resident pointwise kernel (several pixel tiles, ragged last one)
     (3, 19, 17, 64, 256, 1, 1, 1, 0, 1),
     (2, 23, 21, 256, 384, 1, 1, 1, 0, 1),
