@@ -405,6 +405,39 @@ __global__ void __launch_bounds__(256) pool_np_kernel(NpPoolParams a)
     }
 }
 
+// Average over the whole unpadded image (k = H = W) with C a multiple of 4: one lane per four channels of an image, word
+// loads, the pixels in turn (neighbouring lanes read neighbouring words).
+__global__ void __launch_bounds__(256) avgpool_global_np4_kernel(NpPoolParams a)
+{
+    const int C4 = a.C / 4;
+    const int total = a.N * C4;
+    const int pixels = a.H * a.W;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+        const int n = i / C4, c4 = i - n * C4;
+        const uint32_t *ph = (const uint32_t *)a.xh + (size_t)n * pixels * C4 + c4;
+        const uint32_t *pl = (const uint32_t *)a.xl + (size_t)n * pixels * C4 + c4;
+        int tot[4] = {0, 0, 0, 0};
+        for (int j = 0; j < pixels; j++) {
+            const uint32_t h4 = ph[(size_t)j * C4], l4 = pl[(size_t)j * C4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) tot[e] += 64 * byte_of(h4, e) + byte_of(l4, e);
+        }
+        uint32_t oc = 0, oh = 0, ol = 0;
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const int beta = np_round_mean(tot[e], pixels, a.p_fmt, a.beta_max);
+            int h, l;
+            np_split(beta, h, l);
+            oc |= (uint32_t)np_code_of(beta, a.p_fmt) << (8 * e);
+            oh |= (uint32_t)(uint8_t)h << (8 * e);
+            ol |= (uint32_t)(uint8_t)l << (8 * e);
+        }
+        if (a.y) ((uint32_t *)a.y)[i] = oc;
+        if (a.yh) ((uint32_t *)a.yh)[i] = oh;
+        if (a.yl) ((uint32_t *)a.yl)[i] = ol;
+    }
+}
+
 // 3 x 3 / stride 2 / pad 1 max pooling with C a multiple of 4: one lane per four channels of an output pixel.
 __global__ void __launch_bounds__(256) maxpool3_np_kernel(NpPoolParams a)
 {
@@ -1058,6 +1091,9 @@ hipError_t launch_pool_np(const int8_t *xh, const int8_t *xl, uint8_t *y, int8_t
         maxpool3_np16_kernel<<<grid_for(total / 16), 256, 0, st>>>(prm);
     } else if (!avg && k == 3 && stride == 2 && pad == 1 && C % 4 == 0 && (al4 & 3) == 0)
         maxpool3_np_kernel<<<grid_for(total / 4), 256, 0, st>>>(a);
+    else if (avg && k == H && k == W && pad == 0 && P == 1 && Q == 1 && C % 4 == 0 && (al4 & 3) == 0 && total / 4 < (1u << 31) &&
+             (long long)k * k <= (1 << 18))
+        avgpool_global_np4_kernel<<<grid_for(total / 4), 256, 0, st>>>(a);
     else
         pool_np_kernel<<<grid_for(total), 256, 0, st>>>(a);
     return hipGetLastError();

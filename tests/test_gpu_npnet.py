@@ -70,7 +70,7 @@ def test_eltwise_np_absmax_and_scale_rule(B):
 def test_pool_np_against_oracle(B, p):
     rng = np.random.default_rng(p)
     for shape, mode, k, stride, pad in [((2, 13, 11, 64), "max", 3, 2, 1), ((2, 12, 12, 8), "max", 3, 2, 1), ((1, 9, 9, 5), "max", 3, 2, 1),
-                                        ((2, 8, 8, 16), "max", 2, 2, 0), ((1, 7, 7, 6), "max", 3, 1, 1), ((3, 7, 7, 64), "avg", 7, 1, 0),
+                                        ((2, 8, 8, 16), "max", 2, 2, 0), ((1, 7, 7, 6), "max", 3, 1, 1), ((3, 7, 7, 64), "avg", 7, 1, 0), ((5, 7, 7, 2048), "avg", 7, 1, 0), ((2, 5, 5, 12), "avg", 5, 1, 0),
                                         ((1, 8, 8, 10), "avg", 2, 2, 0), ((2, 9, 9, 4), "avg", 3, 3, 0), ((1, 16, 16, 3), "avg", 16, 1, 0)]:
         x = rng.integers(0, 256, shape).astype(np.uint8)
         if mode == "avg":
